@@ -1,0 +1,188 @@
+/*
+ * vdnn.h - C ABI of the MI355X-native vDNN library (arxiv 1602.08124).
+ *
+ * The library runs the layer-wise CNN training step (Section 2.2 of the paper) with hand-written
+ * HIP kernels for gfx950 and manages GPU memory the way Section 3 describes: layer-wise allocation
+ * from a pool of fixed size, offload of a layer's input feature map X to pinned host memory during
+ * forward propagation, prefetch during backward propagation, release as soon as data is dead,
+ * under one of the transfer policies of Section 3.3.
+ *
+ * Conventions
+ *   - every entry point returns a vdnn_status_t and never throws or aborts across the ABI;
+ *     output parameters are untouched on error; vdnn_last_error() gives a message.
+ *   - tensors are fp32, NCHW, dense.  Pointers are marked (host) or (device) below.
+ *   - the caller owns descriptors and host arrays (consumed before the call returns); the library
+ *     owns the net, its pinned host arena and its events.  The device pool and the two streams are
+ *     borrowed from the caller when vdnn_attach_device() is used, otherwise created by the library.
+ *   - a net is not thread safe; calls on one net must be serialised by the caller.
+ *   - all sizes are bytes unless a name says "count" (elements).
+ */
+#ifndef VDNN_H
+#define VDNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vdnn_net vdnn_net_t; /* opaque, library-owned */
+
+typedef enum {
+    VDNN_OK = 0,
+    VDNN_ERR_INVALID_ARG = 1,
+    VDNN_ERR_OOM_DEVICE = 2, /* the step does not fit the GPU byte budget: the paper's "fails to train" */
+    VDNN_ERR_OOM_HOST = 3,   /* pinned host arena could not be allocated */
+    VDNN_ERR_HIP = 4,        /* a HIP runtime call failed */
+    VDNN_ERR_STATE = 5,      /* call sequence error, e.g. backward without forward */
+    VDNN_ERR_UNSUPPORTED = 6
+} vdnn_status_t;
+
+/* Section 3.3: static policies all / conv, the dynamic policy, and no offloading at all. */
+typedef enum { VDNN_POLICY_NONE = 0, VDNN_POLICY_ALL = 1, VDNN_POLICY_CONV = 2, VDNN_POLICY_DYN = 3 } vdnn_policy_t;
+
+typedef enum {
+    VDNN_CONV = 0,       /* cross-correlation, zero padding, no bias */
+    VDNN_RELU = 1,       /* in place: shares its input's feature map and gradient map */
+    VDNN_MAXPOOL = 2,
+    VDNN_AVGPOOL = 3,    /* divisor kernel*kernel, padded cells count as zeros */
+    VDNN_FC = 4,         /* on the flattened NCHW vector, weight [out][in] */
+    VDNN_CONCAT = 5,     /* along channels, in input order */
+    VDNN_SOFTMAX_CE = 6  /* mean softmax cross-entropy over the batch; must be the last layer */
+} vdnn_layer_type_t;
+
+#define VDNN_MAX_INPUTS 8
+
+typedef struct {
+    int32_t type;                    /* vdnn_layer_type_t */
+    int32_t n_inputs;                /* 1, except CONCAT (2..VDNN_MAX_INPUTS) */
+    int32_t inputs[VDNN_MAX_INPUTS]; /* producer layer ids (< own id), -1 = the network input */
+    int32_t out_channels;            /* CONV: output channels, FC: output features */
+    int32_t kernel, stride, pad;     /* CONV and pools: square window */
+} vdnn_layer_desc_t;
+
+typedef struct {
+    int32_t batch, in_c, in_h, in_w;
+    int32_t n_layers;
+    const vdnn_layer_desc_t* layers; /* (host) */
+} vdnn_net_desc_t;
+
+typedef struct {
+    uint64_t budget_bytes;        /* 0 = unlimited */
+    uint64_t cur_bytes;           /* live pool bytes now (after a step: W, dW, labels, loss) */
+    uint64_t peak_bytes;          /* largest live total during the last planned step */
+    uint64_t pool_extent_bytes;   /* address range the placement of that step needs (>= peak_bytes) */
+    uint64_t baseline_bytes;      /* network-wide allocation of the baseline (Fig. 2 of the paper) */
+    uint64_t persistent_bytes;    /* W + dW + labels + loss */
+    double avg_bytes_layerstep;   /* mean of live bytes sampled at the start of every layer's fwd and bwd */
+    uint64_t offloaded_bytes, prefetched_bytes; /* per step, device->host and host->device */
+    uint64_t pinned_host_bytes;
+    uint64_t workspace_bytes;     /* largest transient workspace of the step */
+    int32_t n_offload, n_prefetch, n_ondemand_fetch;
+    int32_t effective_policy;     /* what DYN resolved to; otherwise the policy set */
+    /* measured on the last executed step (0 until one has run) */
+    double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
+} vdnn_mem_stats_t;
+
+/* ---- the five calls of the paper's problem statement -------------------------------------- */
+
+/* Builds the layer list, the dataflow graph with its consumer counts (Fig. nonlinear_dfg) and
+ * the memory plan for policy NONE.  gpu_mem_budget covers everything on the device: feature
+ * maps, gradient maps, W, dW, workspace (Section 3.2, "Memory Allocation/Release": one pool).
+ * 0 means unlimited.  Host-only: does not touch the GPU. */
+vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_budget, vdnn_net_t** out);
+
+/* Section 3.3.  ALL: offload the X of every CONV and POOL layer; CONV: only X that feed a CONV
+ * layer; DYN: the profiling-pass sequence with out-of-memory as the signal (with one convolution
+ * algorithm: all must fit, then none, conv, all - first that fits).  Re-plans the step.
+ * Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net stays usable). */
+vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
+
+/* Forward propagation, layers 0..L-1 (Section 2.2; offload per Section 3.2 "Memory Offload").
+ * input: (device) batch*in_c*in_h*in_w floats; labels: (device) batch int32 in [0, classes).
+ * Both are copied into the pool before use.  loss_out: (host) mean softmax-CE loss.
+ * Returns after the forward pass has completed on the GPU. */
+vdnn_status_t vdnn_forward(vdnn_net_t*, const float* input, const int32_t* labels, float* loss_out);
+
+/* Backward propagation, layers L-1..0 (Eq. chain_rule; prefetch per Section 3.2 "Memory Prefetch").
+ * Leaves every dW in the pool.  Returns after completion on the GPU. */
+vdnn_status_t vdnn_backward(vdnn_net_t*);
+
+/* Figures 11/12 of the paper: maximum and average memory, offloaded bytes; plus measured times. */
+vdnn_status_t vdnn_mem_stats(const vdnn_net_t*, vdnn_mem_stats_t* out /*host*/);
+
+/* ---- what the five need in order to be usable and testable ------------------------------- */
+
+/* Borrow device memory and streams (e.g. torch-owned).  pool_bytes must be >= pool_extent_bytes
+ * of the current plan.  stream_* are hipStream_t.  Without this call the library allocates its
+ * own pool (hipMalloc) and streams on first use. */
+vdnn_status_t vdnn_attach_device(vdnn_net_t*, void* pool_base /*device*/, size_t pool_bytes, void* stream_compute,
+                                 void* stream_memory);
+
+/* Weights: CONV [K][C][R][S], FC [out][in], fp32 (host).  count must match. */
+vdnn_status_t vdnn_set_weights(vdnn_net_t*, int layer, const float* w /*host*/, size_t count);
+vdnn_status_t vdnn_get_weight_grad(vdnn_net_t*, int layer, float* dw /*host*/, size_t count);
+size_t vdnn_weight_count(const vdnn_net_t*, int layer); /* 0 for layers without weights */
+size_t vdnn_output_count(const vdnn_net_t*, int layer); /* elements of the layer's output */
+
+/* Test hooks: copy layer's output Y (right after its forward computation) / the gradient w.r.t.
+ * its output dY (right before its backward computation) to a host array during the next
+ * passes.  dst = NULL removes the hook.  The copies synchronise the compute stream. */
+vdnn_status_t vdnn_capture_output(vdnn_net_t*, int layer, float* dst /*host*/);
+vdnn_status_t vdnn_capture_grad(vdnn_net_t*, int layer, float* dst /*host*/);
+
+/* The planned step as text, one op per line: "<where> <op> <tag> <bytes> [<offset>]" with
+ * where = create | F<layer> | B<layer>, op = alloc | free | offload | prefetch | ondemand | compute.
+ * Writes at most cap bytes (NUL-terminated) and stores the full length in *needed. */
+vdnn_status_t vdnn_trace(const vdnn_net_t*, char* buf /*host*/, size_t cap, size_t* needed);
+
+const char* vdnn_last_error(const vdnn_net_t*);
+void vdnn_destroy(vdnn_net_t*);
+
+/* ---- single-layer entry points (the kernels behind the step; all pointers are device) ----- */
+/* stream: hipStream_t or NULL.  Shapes: X [N][C][H][W], W [K][C][R][S], Y [N][K][P][Q] with
+ * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream. */
+
+/* Y = conv(X, W); relu != 0 applies max(.,0) to the result in the same kernel. */
+vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                               int stride, int pad, int relu, void* stream);
+/* dX = sum over the forward terms that touched it (Eq. chain_rule). */
+vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R,
+                                    int S, int stride, int pad, void* stream);
+/* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
+ * order (deterministic, no atomics).  workspace may be NULL iff the required size is 0. */
+size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
+                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
+
+/* FC: Y[N][O] = X[N][I] W[O][I]^T ; dX = dY W ; dW = dY^T X.  Same workspace rule. */
+size_t vdnn_op_fc_workspace(int N, int I, int O, int which /*0 fwd, 1 bwd-data, 2 bwd-filter*/);
+vdnn_status_t vdnn_op_fc_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int I,
+                             int O, void* stream);
+vdnn_status_t vdnn_op_fc_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
+                                  int I, int O, void* stream);
+vdnn_status_t vdnn_op_fc_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes, int N,
+                                    int I, int O, void* stream);
+
+vdnn_status_t vdnn_op_relu_fwd(float* y, size_t count, void* stream);                  /* in place */
+vdnn_status_t vdnn_op_relu_bwd(const float* y, float* dy, size_t count, void* stream); /* in place on dy, mask y > 0 */
+vdnn_status_t vdnn_op_maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
+/* first maximum in row-major window order takes the gradient; overlapping windows add up */
+vdnn_status_t vdnn_op_maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride,
+                                  int pad, void* stream);
+vdnn_status_t vdnn_op_avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
+vdnn_status_t vdnn_op_avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
+/* loss: (device) one float, mean over the batch.  dz = (softmax(z) - onehot)/N. */
+vdnn_status_t vdnn_op_softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, void* stream);
+vdnn_status_t vdnn_op_softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, void* stream);
+/* to_big != 0 (concat forward):  big[n][c_off + c][hw] = small[n][c][hw], src = small, dst = big.
+ * to_big == 0 (concat backward): small[n][c][hw] = big[n][c_off + c][hw], src = big,   dst = small. */
+vdnn_status_t vdnn_op_concat_copy(const float* src, float* dst, int N, int c_small, int c_big, int c_off, int hw, int to_big,
+                                  void* stream);
+vdnn_status_t vdnn_op_add(float* acc, const float* src, size_t count, void* stream); /* acc += src */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VDNN_H */

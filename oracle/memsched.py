@@ -295,7 +295,7 @@ def simulate(net, policy, budget):
                 free("T", blk)
             if t not in IN_PLACE and t != "softmax_ce":
                 free("dB%d" % m, grad.pop(m))
-            for b in list(res):
+            for b in sorted(res):
                 users = bwd_users(net, info, b)
                 if users and users[0] == m:
                     free("B%d" % b, res.pop(b))

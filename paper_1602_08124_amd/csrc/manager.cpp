@@ -1,0 +1,918 @@
+// vDNN memory manager: graph construction, step planning (policy -> ops + block placement) and
+// execution on two HIP streams.  See manager.h for the overall shape.
+#include "manager.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <cstring>
+#include <map>
+#include <set>
+
+#include "ops.h"
+
+using namespace vdnn;
+
+namespace {
+
+bool in_place(int type) { return type == VDNN_RELU; }
+bool needs_x_in_bwd(int type) { return type == VDNN_CONV || type == VDNN_MAXPOOL || type == VDNN_FC || type == VDNN_SOFTMAX_CE; }
+const char* type_name(int t) {
+    static const char* n[] = {"conv", "relu", "maxpool", "avgpool", "fc", "concat", "softmax_ce"};
+    return (t >= 0 && t <= 6) ? n[t] : "?";
+}
+
+std::string fmt(const char* f, ...) {
+    char b[512];
+    va_list ap;
+    va_start(ap, f);
+    vsnprintf(b, sizeof b, f, ap);
+    va_end(ap);
+    return b;
+}
+
+int buf_of(const vdnn_net& n, int layer) { return layer < 0 ? -1 : n.layers[layer].buf; }
+
+void shape_of(const vdnn_net& n, int layer, int* C, int* H, int* W) {
+    if (layer < 0) { *C = n.in_c; *H = n.in_h; *W = n.in_w; }
+    else { *C = n.layers[layer].C; *H = n.layers[layer].H; *W = n.layers[layer].W; }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// graph
+// ---------------------------------------------------------------------------------------------
+static vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::string& err) {
+    if (d->batch <= 0 || d->in_c <= 0 || d->in_h <= 0 || d->in_w <= 0 || d->n_layers <= 0 || !d->layers) {
+        err = "bad network dimensions";
+        return VDNN_ERR_INVALID_ARG;
+    }
+    n.batch = d->batch; n.in_c = d->in_c; n.in_h = d->in_h; n.in_w = d->in_w;
+    const int L = d->n_layers;
+    n.layers.resize(L);
+    std::vector<int> n_consumers(L + 1, 0);
+    for (int i = 0; i < L; ++i) {
+        const vdnn_layer_desc_t& s = d->layers[i];
+        Layer& l = n.layers[i];
+        l.type = s.type; l.out = s.out_channels; l.k = s.kernel; l.stride = s.stride; l.pad = s.pad;
+        if (s.type < 0 || s.type > VDNN_SOFTMAX_CE) { err = fmt("layer %d: unknown type %d", i, s.type); return VDNN_ERR_INVALID_ARG; }
+        const int want_min = s.type == VDNN_CONCAT ? 2 : 1, want_max = s.type == VDNN_CONCAT ? VDNN_MAX_INPUTS : 1;
+        if (s.n_inputs < want_min || s.n_inputs > want_max) { err = fmt("layer %d: bad number of inputs %d", i, s.n_inputs); return VDNN_ERR_INVALID_ARG; }
+        for (int j = 0; j < s.n_inputs; ++j) {
+            const int src = s.inputs[j];
+            if (src < -1 || src >= i) { err = fmt("layer %d: input %d is not an earlier layer", i, src); return VDNN_ERR_INVALID_ARG; }
+            if (src >= 0 && n.layers[src].type == VDNN_SOFTMAX_CE) { err = fmt("layer %d consumes the loss", i); return VDNN_ERR_INVALID_ARG; }
+            if (std::find(l.inputs.begin(), l.inputs.end(), src) != l.inputs.end()) { err = fmt("layer %d: duplicate input %d", i, src); return VDNN_ERR_INVALID_ARG; }
+            l.inputs.push_back(src);
+            n_consumers[src + 1]++;
+        }
+        int C, H, W;
+        shape_of(n, l.inputs[0], &C, &H, &W);
+        switch (l.type) {
+            case VDNN_CONV:
+                if (l.out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0) { err = fmt("layer %d: bad conv geometry", i); return VDNN_ERR_INVALID_ARG; }
+                l.C = l.out; l.H = (H + 2 * l.pad - l.k) / l.stride + 1; l.W = (W + 2 * l.pad - l.k) / l.stride + 1;
+                if (H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) { err = fmt("layer %d: window larger than image", i); return VDNN_ERR_INVALID_ARG; }
+                l.wcount = (size_t)l.out * C * l.k * l.k;
+                break;
+            case VDNN_MAXPOOL:
+            case VDNN_AVGPOOL:
+                if (l.k <= 0 || l.stride <= 0 || l.pad < 0 || l.pad >= l.k || H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) { err = fmt("layer %d: bad pool geometry", i); return VDNN_ERR_INVALID_ARG; }
+                l.C = C; l.H = (H + 2 * l.pad - l.k) / l.stride + 1; l.W = (W + 2 * l.pad - l.k) / l.stride + 1;
+                break;
+            case VDNN_FC:
+                if (l.out <= 0) { err = fmt("layer %d: bad fc size", i); return VDNN_ERR_INVALID_ARG; }
+                l.C = l.out; l.H = 1; l.W = 1;
+                l.wcount = (size_t)l.out * C * H * W;
+                break;
+            case VDNN_CONCAT: {
+                int csum = 0;
+                for (int src : l.inputs) {
+                    int c2, h2, w2;
+                    shape_of(n, src, &c2, &h2, &w2);
+                    if (h2 != H || w2 != W) { err = fmt("layer %d: concat inputs differ in size", i); return VDNN_ERR_INVALID_ARG; }
+                    csum += c2;
+                }
+                l.C = csum; l.H = H; l.W = W;
+                break;
+            }
+            case VDNN_RELU:
+                l.C = C; l.H = H; l.W = W;
+                break;
+            case VDNN_SOFTMAX_CE:
+                if (i != L - 1) { err = "softmax_ce must be the last layer"; return VDNN_ERR_INVALID_ARG; }
+                l.C = l.H = l.W = 0;
+                break;
+        }
+        if (l.type != VDNN_SOFTMAX_CE && (l.H <= 0 || l.W <= 0)) { err = fmt("layer %d: empty output", i); return VDNN_ERR_INVALID_ARG; }
+        l.buf = in_place(l.type) ? buf_of(n, l.inputs[0]) : i;
+    }
+    if (n.layers[L - 1].type != VDNN_SOFTMAX_CE) { err = "the last layer must be softmax_ce"; return VDNN_ERR_INVALID_ARG; }
+    for (int i = 0; i < L; ++i) {
+        if (in_place(n.layers[i].type) && n_consumers[n.layers[i].inputs[0] + 1] != 1) {
+            err = fmt("layer %d: an in-place layer must be the only consumer of its input", i);
+            return VDNN_ERR_INVALID_ARG;
+        }
+        if (n.layers[i].type != VDNN_SOFTMAX_CE && n_consumers[i + 1] == 0) { err = fmt("layer %d: output is never consumed", i); return VDNN_ERR_INVALID_ARG; }
+    }
+    if (n_consumers[0] == 0) { err = "the network input is never consumed"; return VDNN_ERR_INVALID_ARG; }
+    n.bufs.assign(L + 1, Buffer());
+    for (int b = -1; b < L; ++b) {
+        if (b >= 0 && (n.layers[b].buf != b || n.layers[b].type == VDNN_SOFTMAX_CE)) continue;
+        Buffer& B = n.B(b);
+        shape_of(n, b, &B.C, &B.H, &B.W);
+        B.count = (size_t)n.batch * B.C * B.H * B.W;
+        if (B.count >= 0x7fffffffULL) { err = fmt("feature map %d has 2^31 or more elements", b); return VDNN_ERR_UNSUPPORTED; }
+    }
+    for (int i = 0; i < L; ++i) {
+        const Layer& l = n.layers[i];
+        if (in_place(l.type)) {
+            if (l.buf < 0) { err = "an in-place layer cannot overwrite the network input"; return VDNN_ERR_INVALID_ARG; }
+            n.B(l.buf).inplace.push_back(i);
+        } else {
+            for (int src : l.inputs) n.B(buf_of(n, src)).readers.push_back(i);
+        }
+    }
+    for (int b = -1; b < L; ++b) {
+        Buffer& B = n.B(b);
+        if (!B.count) continue;
+        for (int r : B.readers)
+            if (needs_x_in_bwd(n.layers[r].type)) B.bwd_users.push_back(r);
+        for (int r : B.inplace) B.bwd_users.push_back(r);
+        std::sort(B.bwd_users.begin(), B.bwd_users.end());
+    }
+    n.cap_out.assign(L, nullptr);
+    n.cap_grad.assign(L, nullptr);
+    return VDNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// workspace of a layer (partial sums of reduction-split GEMMs)
+// ---------------------------------------------------------------------------------------------
+static size_t layer_workspace(const vdnn_net& n, int i, bool bwd) {
+    const Layer& l = n.layers[i];
+    int C, H, W;
+    shape_of(n, l.inputs[0], &C, &H, &W);
+    if (l.type == VDNN_CONV && bwd) return conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+    if (l.type == VDNN_FC) {
+        const int I = C * H * W;
+        if (!bwd) return fc_workspace(n.batch, I, l.out, 0);
+        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
+        return std::max(fc_workspace(n.batch, I, l.out, 2), need_dx ? fc_workspace(n.batch, I, l.out, 1) : (size_t)0);
+    }
+    return 0;
+}
+
+static bool selected(const vdnn_net& n, int b, int policy) {
+    const Buffer& B = n.B(b);
+    if (B.bwd_users.empty()) return false;
+    bool conv = false, pool = false;
+    for (int r : B.readers) {
+        const int t = n.layers[r].type;
+        conv |= t == VDNN_CONV;
+        pool |= t == VDNN_MAXPOOL || t == VDNN_AVGPOOL;
+    }
+    if (policy == VDNN_POLICY_ALL) return conv || pool;
+    if (policy == VDNN_POLICY_CONV) return conv;
+    return false;
+}
+
+// ---------------------------------------------------------------------------------------------
+// planning
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct Compiler {
+    const vdnn_net& n;
+    Plan& p;
+    size_t budget;  // aligned; SIZE_MAX/4 when unlimited
+    size_t live = 0;
+    int phase = 0, layer = -1;
+    std::vector<size_t> samples;
+    bool failed = false;
+
+    Compiler(const vdnn_net& net, Plan& plan, size_t b) : n(net), p(plan), budget(b) {}
+
+    std::string where() const {
+        if (phase == 0) return "create";
+        return fmt("%c%d", phase == 1 ? 'F' : 'B', layer);
+    }
+
+    Op& emit(OpKind k) {
+        Op o;
+        o.kind = k; o.phase = phase; o.layer = layer;
+        p.ops.push_back(o);
+        return p.ops.back();
+    }
+
+    int alloc(const std::string& tag, size_t raw, bool persistent = false) {
+        Block b;
+        b.tag = tag; b.raw = raw; b.bytes = align_up(std::max<size_t>(raw, 1));
+        b.persistent = persistent;
+        b.t0 = (int)p.ops.size(); b.t1 = -1;
+        if (live + b.bytes > budget) {
+            failed = true;
+            p.fail_where = where();
+            p.fail_why = fmt("%s: allocating %zu bytes for %s with %zu live exceeds the budget of %zu", where().c_str(), b.bytes,
+                             tag.c_str(), live, budget);
+            return -1;
+        }
+        live += b.bytes;
+        p.peak = std::max(p.peak, live);
+        p.blocks.push_back(b);
+        const int id = (int)p.blocks.size() - 1;
+        emit(OP_ALLOC).block = id;
+        return id;
+    }
+
+    void release(int id) {
+        live -= p.blocks[id].bytes;
+        emit(OP_FREE).block = id;
+        p.blocks[id].t1 = (int)p.ops.size();
+    }
+};
+
+}  // namespace
+
+// Greedy-by-size placement of the transient blocks above the persistent region: each block takes
+// the lowest offset at which it overlaps no already placed block whose lifetime intersects its own.
+static size_t place_blocks(Plan& p, size_t base) {
+    std::vector<int> order;
+    for (int i = 0; i < (int)p.blocks.size(); ++i)
+        if (!p.blocks[i].persistent) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        if (p.blocks[a].bytes != p.blocks[b].bytes) return p.blocks[a].bytes > p.blocks[b].bytes;
+        return p.blocks[a].t0 < p.blocks[b].t0;
+    });
+    std::vector<int> placed;
+    size_t extent = base;
+    for (int id : order) {
+        Block& b = p.blocks[id];
+        std::vector<std::pair<size_t, size_t>> conf;
+        for (int o : placed) {
+            const Block& q = p.blocks[o];
+            if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({q.offset, q.bytes});
+        }
+        std::sort(conf.begin(), conf.end());
+        size_t off = base;
+        for (auto& c : conf) {
+            if (off + b.bytes <= c.first) break;
+            off = std::max(off, c.first + c.second);
+        }
+        b.offset = off;
+        extent = std::max(extent, off + b.bytes);
+        placed.push_back(id);
+    }
+    return extent;
+}
+
+// Compiles one training step under a static policy (NONE / ALL / CONV).
+static void compile_plan(const vdnn_net& n, int policy, Plan& p) {
+    p = Plan();
+    p.policy = policy;
+    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
+    Compiler c(n, p, budget);
+    const int L = (int)n.layers.size();
+    std::vector<int> res(L + 1, -1), grad(L + 1, -1);        // buffer id + 1 -> block
+    std::vector<char> on_host(L + 1, 0);
+    std::vector<std::vector<int>> offloaded_at(L);            // layer -> buffers it offloaded
+    std::vector<int> host_block(L + 1, -1);                   // buffer -> block it was offloaded from (for host_off)
+    std::vector<int> w_block(L, -1), dw_block(L, -1);
+    size_t pinned = 0;
+    std::vector<size_t> host_off(L + 1, 0);
+
+#define CHECK_FAIL() do { if (c.failed) return; } while (0)
+
+    // ---- create: persistent blocks --------------------------------------------------------
+    c.phase = 0;
+    for (int i = 0; i < L; ++i) {
+        if (!n.layers[i].wcount) continue;
+        w_block[i] = c.alloc(fmt("W%d", i), n.layers[i].wcount * 4, true); CHECK_FAIL();
+        dw_block[i] = c.alloc(fmt("dW%d", i), n.layers[i].wcount * 4, true); CHECK_FAIL();
+    }
+    p.labels_block = c.alloc("labels", (size_t)n.batch * 4, true); CHECK_FAIL();
+    p.loss_block = c.alloc("loss", 4, true); CHECK_FAIL();
+    p.persistent = c.live;
+    {   // persistent blocks are packed from offset 0 in creation order: their place never depends on the policy
+        size_t off = 0;
+        for (Block& b : p.blocks) { b.offset = off; off += b.bytes; b.t0 = 0; b.t1 = 1 << 30; }
+    }
+
+    // ---- forward --------------------------------------------------------------------------
+    c.phase = 1; c.layer = -1;
+    p.first_fwd_op = (int)p.ops.size();
+    res[0] = c.alloc("B-1", n.B(-1).count * 4); CHECK_FAIL();
+    {
+        Op& o = c.emit(OP_LOAD_INPUT);
+        o.out_block = res[0];
+    }
+    for (int i = 0; i < L; ++i) {
+        const Layer& l = n.layers[i];
+        c.layer = i;
+        c.emit(OP_SAMPLE);
+        c.samples.push_back(c.live);
+        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); }
+        const size_t ws = layer_workspace(n, i, false);
+        int wsb = -1;
+        if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
+        std::vector<int> in_bufs;
+        for (int src : l.inputs) in_bufs.push_back(buf_of(n, src));
+        if (!in_place(l.type)) {
+            for (int b : in_bufs) {
+                if (n.B(b).readers.back() == i && selected(n, b, policy)) {
+                    Op& o = c.emit(OP_OFFLOAD);
+                    o.block = res[b + 1]; o.buf = b;
+                    host_off[b + 1] = pinned;
+                    p.blocks[res[b + 1]].host_off = pinned;
+                    pinned += align_up(n.B(b).count * 4);
+                    p.offloaded += n.B(b).count * 4;
+                    p.n_offload++;
+                    offloaded_at[i].push_back(b);
+                }
+            }
+        }
+        {
+            Op& o = c.emit(OP_FWD);
+            for (int b : in_bufs) o.in_blocks.push_back(res[b + 1]);
+            o.out_block = res[l.buf + 1];
+            o.ws_block = wsb;
+        }
+        if (wsb >= 0) c.release(wsb);
+        for (int b : offloaded_at[i]) {
+            Op& o = c.emit(OP_WAIT_COPY);
+            o.block = res[b + 1]; o.buf = b;
+            c.release(res[b + 1]);
+            res[b + 1] = -1;
+            on_host[b + 1] = 1;
+        }
+        if (!in_place(l.type))
+            for (int b : in_bufs)
+                if (res[b + 1] >= 0 && n.B(b).readers.back() == i && n.B(b).bwd_users.empty()) { c.release(res[b + 1]); res[b + 1] = -1; }
+    }
+
+    // ---- backward -------------------------------------------------------------------------
+    c.phase = 2;
+    p.first_bwd_op = (int)p.ops.size();
+    auto fetch = [&](int b, OpKind kind) -> bool {
+        res[b + 1] = c.alloc(fmt("B%d", b), n.B(b).count * 4);
+        if (c.failed) return false;
+        p.blocks[res[b + 1]].host_off = host_off[b + 1];
+        on_host[b + 1] = 0;
+        Op& o = c.emit(kind);
+        o.block = res[b + 1]; o.buf = b;
+        p.prefetched += n.B(b).count * 4;
+        return true;
+    };
+    for (int m = L - 1; m >= 0; --m) {
+        const Layer& l = n.layers[m];
+        c.layer = m;
+        c.emit(OP_SAMPLE);
+        c.samples.push_back(c.live);
+        // findPrefetchLayer (Fig. code_prefetch): nearest preceding layer whose offloaded X is still on the host;
+        // the search window ends at the first CONV layer that has nothing to prefetch.
+        std::vector<int> issued;
+        for (int j = m - 1; j >= 0; --j) {
+            std::vector<int> pending;
+            for (int b : offloaded_at[j]) if (on_host[b + 1]) pending.push_back(b);
+            if (!pending.empty()) {
+                for (int b : pending) { if (!fetch(b, OP_PREFETCH)) return; p.n_prefetch++; issued.push_back(b); }
+                break;
+            }
+            if (n.layers[j].type == VDNN_CONV) break;
+        }
+        std::vector<int> in_bufs;
+        for (int src : l.inputs) in_bufs.push_back(buf_of(n, src));
+        std::vector<int> needed;
+        if (in_place(l.type)) needed.push_back(l.buf);
+        else if (needs_x_in_bwd(l.type)) needed = in_bufs;
+        for (int b : needed)
+            if (on_host[b + 1]) { if (!fetch(b, OP_ONDEMAND)) return; p.n_ondemand++; }
+        std::vector<int> gout(in_bufs.size(), -1), gacc(in_bufs.size(), -1), temps;
+        if (!in_place(l.type)) {
+            for (size_t k = 0; k < in_bufs.size(); ++k) {
+                const int b = in_bufs[k];
+                if (b < 0) continue;
+                if (grad[b + 1] < 0) { grad[b + 1] = c.alloc(fmt("dB%d", b), n.B(b).count * 4); CHECK_FAIL(); gout[k] = grad[b + 1]; }
+                else { const int t = c.alloc(fmt("T%d", b), n.B(b).count * 4); CHECK_FAIL(); temps.push_back(t); gout[k] = t; gacc[k] = grad[b + 1]; }
+            }
+        }
+        const size_t ws = layer_workspace(n, m, true);
+        int wsb = -1;
+        if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
+        {
+            Op& o = c.emit(OP_BWD);
+            for (int b : in_bufs) o.in_blocks.push_back(res[b + 1]);
+            o.out_block = l.type == VDNN_SOFTMAX_CE ? -1 : res[l.buf + 1];
+            o.gin_block = l.type == VDNN_SOFTMAX_CE ? -1 : grad[l.buf + 1];
+            o.gout_blocks = gout; o.gacc_blocks = gacc; o.ws_block = wsb;
+        }
+        if (wsb >= 0) c.release(wsb);
+        for (int t : temps) c.release(t);
+        for (int b : issued) {  // end-of-layer synchronisation with the prefetch issued for this layer
+            Op& o = c.emit(OP_WAIT_COPY);
+            o.block = res[b + 1]; o.buf = b;
+        }
+        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { c.release(grad[m + 1]); grad[m + 1] = -1; }
+        for (int b = -1; b < L; ++b)
+            if (res[b + 1] >= 0 && !n.B(b).bwd_users.empty() && n.B(b).bwd_users.front() == m) { c.release(res[b + 1]); res[b + 1] = -1; }
+    }
+#undef CHECK_FAIL
+    for (Block& b : p.blocks)
+        if (b.t1 < 0) b.t1 = (int)p.ops.size() + 1;  // still live at the end of the step (nothing should be)
+    p.avg = 0.0;
+    for (size_t s : c.samples) p.avg += (double)s;
+    if (!c.samples.empty()) p.avg /= (double)c.samples.size();
+    p.pinned = pinned;
+    p.extent = place_blocks(p, p.persistent);
+    if (p.extent > budget) {
+        p.fail_where = "placement";
+        p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
+        return;
+    }
+    for (int i = 0; i < L; ++i) { const_cast<Layer&>(n.layers[i]).w_block = w_block[i]; const_cast<Layer&>(n.layers[i]).dw_block = dw_block[i]; }
+    p.ok = true;
+}
+
+static size_t baseline_bytes(const vdnn_net& n) {
+    const int L = (int)n.layers.size();
+    size_t fm = 0, wb = 0, gmax = 0, wmax = 0;
+    for (int b = -1; b < L; ++b) {
+        const size_t s = n.B(b).count ? align_up(n.B(b).count * 4) : 0;
+        fm += s;
+        if (b >= 0) gmax = std::max(gmax, s);
+    }
+    for (int i = 0; i < L; ++i) {
+        if (n.layers[i].wcount) wb += 2 * align_up(n.layers[i].wcount * 4);
+        wmax = std::max(wmax, std::max(layer_workspace(n, i, false), layer_workspace(n, i, true)));
+    }
+    return fm + wb + 2 * gmax + align_up(wmax);
+}
+
+// Section 3.3, "Dynamic vDNN", with one convolution algorithm: (1) all must be trainable;
+// (2) adopt the first of none, conv, all that fits.  The greedy per-layer downgrade of the third
+// phase has nothing to choose from.  Trainability of a pass is decided by the planner, which
+// performs exactly the allocations a real pass would.
+static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
+    Plan p;
+    if (policy == VDNN_POLICY_DYN) {
+        compile_plan(n, VDNN_POLICY_ALL, p);
+        if (!p.ok) { n.err = "vDNN_dyn: even vDNN_all does not fit: " + p.fail_why; return VDNN_ERR_OOM_DEVICE; }
+        const int order[3] = {VDNN_POLICY_NONE, VDNN_POLICY_CONV, VDNN_POLICY_ALL};
+        for (int pol : order) {
+            compile_plan(n, pol, p);
+            if (p.ok) { n.plan = p; n.policy = policy; n.effective = pol; return VDNN_OK; }
+        }
+        n.err = "vDNN_dyn: internal error";
+        return VDNN_ERR_STATE;
+    }
+    compile_plan(n, policy, p);
+    if (!p.ok) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
+    n.plan = p; n.policy = policy; n.effective = policy;
+    return VDNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// device plumbing
+// ---------------------------------------------------------------------------------------------
+#define HIPCHK(call)                                                                             \
+    do {                                                                                         \
+        hipError_t e__ = (call);                                                                 \
+        if (e__ != hipSuccess) {                                                                 \
+            n.err = fmt("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+            return VDNN_ERR_HIP;                                                                 \
+        }                                                                                        \
+    } while (0)
+
+static vdnn_status_t ensure_device(vdnn_net& n) {
+    if (!n.plan.ok) { n.err = "no valid plan (the current policy does not fit the budget)"; return VDNN_ERR_STATE; }
+    if (!n.have_streams) {
+        HIPCHK(hipStreamCreateWithFlags(&n.sc, hipStreamNonBlocking));
+        HIPCHK(hipStreamCreateWithFlags(&n.sm, hipStreamNonBlocking));
+        n.have_streams = n.own_streams = true;
+    }
+    if (!n.pool || n.pool_bytes < n.plan.extent) {
+        if (n.pool && !n.own_pool) {
+            n.err = fmt("attached pool of %zu bytes is smaller than the plan's extent %zu", n.pool_bytes, n.plan.extent);
+            return VDNN_ERR_INVALID_ARG;
+        }
+        const size_t want = n.budget ? n.budget / kAlign * kAlign : n.plan.extent;
+        char* fresh = nullptr;
+        HIPCHK(hipMalloc((void**)&fresh, want));
+        if (n.pool) {  // keep W (persistent region sits at the bottom of the pool)
+            HIPCHK(hipMemcpy(fresh, n.pool, n.plan.persistent, hipMemcpyDeviceToDevice));
+            HIPCHK(hipFree(n.pool));
+        }
+        n.pool = fresh; n.pool_bytes = want; n.own_pool = true;
+    }
+    if (n.plan.pinned > n.pinned_bytes) {
+        if (n.pinned) { HIPCHK(hipHostFree(n.pinned)); n.pinned = nullptr; n.pinned_bytes = 0; }
+        hipError_t e = hipHostMalloc((void**)&n.pinned, n.plan.pinned, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            n.err = fmt("pinned host arena of %zu bytes: %s", n.plan.pinned, hipGetErrorString(e));
+            (void)hipGetLastError();
+            n.pinned = nullptr;
+            return VDNN_ERR_OOM_HOST;
+        }
+        n.pinned_bytes = n.plan.pinned;
+    }
+    return VDNN_OK;
+}
+
+static int new_event(vdnn_net& n, hipError_t* err) {
+    if (n.events_used == (int)n.events.size()) {
+        hipEvent_t e;
+        *err = hipEventCreate(&e);
+        if (*err != hipSuccess) return -1;
+        n.events.push_back(e);
+    }
+    *err = hipSuccess;
+    return n.events_used++;
+}
+
+#define NEWEV(var)                                   \
+    int var;                                         \
+    {                                                \
+        hipError_t ee__;                             \
+        var = new_event(n, &ee__);                   \
+        if (var < 0) HIPCHK(ee__);                   \
+    }
+
+static inline float* blk(vdnn_net& n, int id) { return id < 0 ? nullptr : (float*)(n.pool + n.plan.blocks[id].offset); }
+
+static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
+    const Layer& l = n.layers[o.layer];
+    int C, H, W;
+    shape_of(n, l.inputs[0], &C, &H, &W);
+    const int N = n.batch;
+    float* x = blk(n, o.in_blocks[0]);
+    float* y = blk(n, o.out_block);
+    switch (l.type) {
+        case VDNN_CONV: HIPCHK(conv_fwd(x, blk(n, l.w_block), y, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, 0, n.sc)); break;
+        case VDNN_RELU: HIPCHK(relu_fwd(y, n.B(l.buf).count, n.sc)); break;
+        case VDNN_MAXPOOL: HIPCHK(maxpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
+        case VDNN_AVGPOOL: HIPCHK(avgpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
+        case VDNN_FC: {
+            const size_t wsb = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
+            HIPCHK(fc_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            break;
+        }
+        case VDNN_CONCAT: {
+            int coff = 0;
+            for (size_t k = 0; k < l.inputs.size(); ++k) {
+                int c2, h2, w2;
+                shape_of(n, l.inputs[k], &c2, &h2, &w2);
+                HIPCHK(concat_copy(blk(n, o.in_blocks[k]), y, N, c2, l.C, coff, H * W, 1, n.sc));
+                coff += c2;
+            }
+            break;
+        }
+        case VDNN_SOFTMAX_CE:
+            HIPCHK(softmax_ce_fwd(x, (const int32_t*)blk(n, n.plan.labels_block), blk(n, n.plan.loss_block), N, C * H * W, n.sc));
+            break;
+    }
+    return VDNN_OK;
+}
+
+static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
+    const Layer& l = n.layers[o.layer];
+    int C, H, W;
+    shape_of(n, l.inputs[0], &C, &H, &W);
+    const int N = n.batch;
+    float* x = blk(n, o.in_blocks[0]);
+    float* dy = blk(n, o.gin_block);
+    float* dx = o.gout_blocks.empty() ? nullptr : blk(n, o.gout_blocks[0]);
+    const size_t wsb = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
+    switch (l.type) {
+        case VDNN_CONV:
+            HIPCHK(conv_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            break;
+        case VDNN_RELU: HIPCHK(relu_bwd(blk(n, o.out_block), dy, n.B(l.buf).count, n.sc)); break;
+        case VDNN_MAXPOOL: if (dx) HIPCHK(maxpool_bwd(x, dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
+        case VDNN_AVGPOOL: if (dx) HIPCHK(avgpool_bwd(dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
+        case VDNN_FC:
+            HIPCHK(fc_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            if (dx) HIPCHK(fc_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            break;
+        case VDNN_CONCAT: {
+            int coff = 0;
+            for (size_t k = 0; k < l.inputs.size(); ++k) {
+                int c2, h2, w2;
+                shape_of(n, l.inputs[k], &c2, &h2, &w2);
+                if (o.gout_blocks[k] >= 0) HIPCHK(concat_copy(dy, blk(n, o.gout_blocks[k]), N, c2, l.C, coff, H * W, 0, n.sc));
+                coff += c2;
+            }
+            break;
+        }
+        case VDNN_SOFTMAX_CE:
+            if (dx) HIPCHK(softmax_ce_bwd(x, (const int32_t*)blk(n, n.plan.labels_block), dx, N, C * H * W, n.sc));
+            break;
+    }
+    for (size_t k = 0; k < o.gacc_blocks.size(); ++k)
+        if (o.gacc_blocks[k] >= 0) HIPCHK(add_inplace(blk(n, o.gacc_blocks[k]), blk(n, o.gout_blocks[k]), n.B(buf_of(n, l.inputs[k])).count, n.sc));
+    return VDNN_OK;
+}
+
+// Replays ops [first, last) of the plan.
+static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* input, const int32_t* labels) {
+    Plan& p = n.plan;
+    if ((int)n.copy_done_event.size() != (int)p.blocks.size()) n.copy_done_event.assign(p.blocks.size(), -1);
+    for (int t = first; t < last; ++t) {
+        const Op& o = p.ops[t];
+        switch (o.kind) {
+            case OP_SAMPLE:
+            case OP_ALLOC:
+            case OP_FREE:
+                break;  // placement is static: nothing to do at run time
+            case OP_LOAD_INPUT:
+                HIPCHK(hipMemcpyAsync(blk(n, o.out_block), input, n.B(-1).count * 4, hipMemcpyDeviceToDevice, n.sc));
+                HIPCHK(hipMemcpyAsync(blk(n, p.labels_block), labels, (size_t)n.batch * 4, hipMemcpyDeviceToDevice, n.sc));
+                break;
+            case OP_OFFLOAD:
+            case OP_PREFETCH:
+            case OP_ONDEMAND: {
+                // The copy may start once everything enqueued so far on the compute stream has finished:
+                // for an offload that is the producer of X; for a fetch it covers the last users of whatever
+                // occupied the destination's address range before.
+                NEWEV(e_ready);
+                HIPCHK(hipEventRecord(n.events[e_ready], n.sc));
+                HIPCHK(hipStreamWaitEvent(n.sm, n.events[e_ready], 0));
+                NEWEV(e0);
+                NEWEV(e1);
+                HIPCHK(hipEventRecord(n.events[e0], n.sm));
+                const size_t bytes = n.B(o.buf).count * 4;
+                char* host = n.pinned + p.blocks[o.block].host_off;
+                if (o.kind == OP_OFFLOAD) HIPCHK(hipMemcpyAsync(host, blk(n, o.block), bytes, hipMemcpyDeviceToHost, n.sm));
+                else HIPCHK(hipMemcpyAsync(blk(n, o.block), host, bytes, hipMemcpyHostToDevice, n.sm));
+                HIPCHK(hipEventRecord(n.events[e1], n.sm));
+                n.copies.push_back({e0, e1, bytes, o.kind == OP_OFFLOAD ? 0 : 1});
+                n.copy_done_event[o.block] = e1;
+                if (o.kind == OP_ONDEMAND) {
+                    n.stalls.push_back({e_ready, e1});
+                    HIPCHK(hipStreamWaitEvent(n.sc, n.events[e1], 0));
+                }
+                break;
+            }
+            case OP_WAIT_COPY: {
+                const int e1 = n.copy_done_event[o.block];
+                if (e1 < 0) { n.err = "internal: wait for a copy that was never issued"; return VDNN_ERR_STATE; }
+                NEWEV(e_here);
+                HIPCHK(hipEventRecord(n.events[e_here], n.sc));
+                n.stalls.push_back({e_here, e1});
+                HIPCHK(hipStreamWaitEvent(n.sc, n.events[e1], 0));
+                break;
+            }
+            case OP_FWD: {
+                vdnn_status_t s = run_fwd(n, o);
+                if (s != VDNN_OK) return s;
+                if (n.cap_out[o.layer]) {
+                    const Layer& l = n.layers[o.layer];
+                    HIPCHK(hipStreamSynchronize(n.sc));
+                    if (l.type == VDNN_SOFTMAX_CE) HIPCHK(hipMemcpy(n.cap_out[o.layer], blk(n, p.loss_block), 4, hipMemcpyDeviceToHost));
+                    else HIPCHK(hipMemcpy(n.cap_out[o.layer], blk(n, o.out_block), n.B(l.buf).count * 4, hipMemcpyDeviceToHost));
+                }
+                break;
+            }
+            case OP_BWD: {
+                if (n.cap_grad[o.layer] && o.gin_block >= 0) {
+                    HIPCHK(hipStreamSynchronize(n.sc));
+                    HIPCHK(hipMemcpy(n.cap_grad[o.layer], blk(n, o.gin_block), n.B(n.layers[o.layer].buf).count * 4, hipMemcpyDeviceToHost));
+                }
+                vdnn_status_t s = run_bwd(n, o);
+                if (s != VDNN_OK) return s;
+                break;
+            }
+        }
+    }
+    return VDNN_OK;
+}
+
+static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
+    float ms = 0.f;
+    if (!bwd) {
+        HIPCHK(hipEventElapsedTime(&ms, n.events[n.ev_f0], n.events[n.ev_f1]));
+        n.fwd_ms = ms;
+        n.stall_ms = n.d2h_ms = n.h2d_ms = 0;
+    } else {
+        HIPCHK(hipEventElapsedTime(&ms, n.events[n.ev_b0], n.events[n.ev_b1]));
+        n.bwd_ms = ms;
+    }
+    for (auto& c : n.copies) {
+        HIPCHK(hipEventElapsedTime(&ms, n.events[c.e0], n.events[c.e1]));
+        (c.dir == 0 ? n.d2h_ms : n.h2d_ms) += ms;
+    }
+    for (auto& s : n.stalls) {
+        hipError_t e = hipEventElapsedTime(&ms, n.events[s.e_compute], n.events[s.e_copy]);
+        if (e == hipSuccess && ms > 0.f) n.stall_ms += ms;
+        else (void)hipGetLastError();
+    }
+    n.copies.clear();
+    n.stalls.clear();
+    return VDNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc, size_t gpu_mem_budget, vdnn_net_t** out) {
+    if (!desc || !out) return VDNN_ERR_INVALID_ARG;
+    vdnn_net* n = new (std::nothrow) vdnn_net();
+    if (!n) return VDNN_ERR_OOM_HOST;
+    std::string err;
+    vdnn_status_t s = build_graph(*n, desc, err);
+    if (s != VDNN_OK) { delete n; return s; }
+    n->budget = gpu_mem_budget;
+    n->baseline = baseline_bytes(*n);
+    s = plan_policy(*n, VDNN_POLICY_NONE);
+    // A network that does not fit without offloading is still a valid object: the caller is
+    // expected to pick a policy next.  The plan stays invalid until one fits.
+    (void)s;
+    *out = n;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_policy(vdnn_net_t* n, vdnn_policy_t policy) {
+    if (!n || policy < VDNN_POLICY_NONE || policy > VDNN_POLICY_DYN) return VDNN_ERR_INVALID_ARG;
+    n->fwd_done = false;
+    return plan_policy(*n, policy);
+}
+
+vdnn_status_t vdnn_attach_device(vdnn_net_t* np, void* pool_base, size_t pool_bytes, void* stream_compute, void* stream_memory) {
+    if (!np || !pool_base || !stream_compute || !stream_memory || stream_compute == stream_memory) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (((uintptr_t)pool_base) % kAlign) { n.err = "pool base must be 256-byte aligned"; return VDNN_ERR_INVALID_ARG; }
+    if (n.weights_set) { n.err = "attach the device pool before setting weights"; return VDNN_ERR_STATE; }
+    if (n.own_pool && n.pool) { HIPCHK(hipFree(n.pool)); }
+    n.pool = (char*)pool_base; n.pool_bytes = pool_bytes; n.own_pool = false;
+    if (n.own_streams) { HIPCHK(hipStreamDestroy(n.sc)); HIPCHK(hipStreamDestroy(n.sm)); }
+    n.sc = (hipStream_t)stream_compute; n.sm = (hipStream_t)stream_memory;
+    n.have_streams = true; n.own_streams = false;
+    return VDNN_OK;
+}
+
+size_t vdnn_weight_count(const vdnn_net_t* n, int layer) {
+    if (!n || layer < 0 || layer >= (int)n->layers.size()) return 0;
+    return n->layers[layer].wcount;
+}
+
+size_t vdnn_output_count(const vdnn_net_t* n, int layer) {
+    if (!n || layer < 0 || layer >= (int)n->layers.size()) return 0;
+    const Layer& l = n->layers[layer];
+    return l.type == VDNN_SOFTMAX_CE ? 1 : (size_t)n->batch * l.C * l.H * l.W;
+}
+
+vdnn_status_t vdnn_set_weights(vdnn_net_t* np, int layer, const float* w, size_t count) {
+    if (!np || !w) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (layer < 0 || layer >= (int)n.layers.size() || !n.layers[layer].wcount || n.layers[layer].wcount != count) {
+        n.err = "set_weights: wrong layer or count";
+        return VDNN_ERR_INVALID_ARG;
+    }
+    vdnn_status_t s = ensure_device(n);
+    if (s != VDNN_OK) return s;
+    HIPCHK(hipMemcpy(blk(n, n.layers[layer].w_block), w, count * 4, hipMemcpyHostToDevice));
+    n.weights_set = true;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_get_weight_grad(vdnn_net_t* np, int layer, float* dw, size_t count) {
+    if (!np || !dw) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (layer < 0 || layer >= (int)n.layers.size() || !n.layers[layer].wcount || n.layers[layer].wcount != count) {
+        n.err = "get_weight_grad: wrong layer or count";
+        return VDNN_ERR_INVALID_ARG;
+    }
+    if (!n.pool) { n.err = "no step has run"; return VDNN_ERR_STATE; }
+    HIPCHK(hipStreamSynchronize(n.sc));
+    HIPCHK(hipMemcpy(dw, blk(n, n.layers[layer].dw_block), count * 4, hipMemcpyDeviceToHost));
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_capture_output(vdnn_net_t* n, int layer, float* dst) {
+    if (!n || layer < 0 || layer >= (int)n->layers.size()) return VDNN_ERR_INVALID_ARG;
+    n->cap_out[layer] = dst;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_capture_grad(vdnn_net_t* n, int layer, float* dst) {
+    if (!n || layer < 0 || layer >= (int)n->layers.size()) return VDNN_ERR_INVALID_ARG;
+    n->cap_grad[layer] = dst;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_forward(vdnn_net_t* np, const float* input, const int32_t* labels, float* loss_out) {
+    if (!np || !input || !labels) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    vdnn_status_t s = ensure_device(n);
+    if (s != VDNN_OK) return s;
+    n.fwd_done = false;
+    n.events_used = 0;
+    n.copies.clear();
+    n.stalls.clear();
+    { NEWEV(e); n.ev_f0 = e; }
+    { NEWEV(e); n.ev_f1 = e; }
+    HIPCHK(hipEventRecord(n.events[n.ev_f0], n.sc));
+    s = run_ops(n, n.plan.first_fwd_op, n.plan.first_bwd_op, input, labels);
+    if (s != VDNN_OK) { (void)hipDeviceSynchronize(); return s; }
+    HIPCHK(hipEventRecord(n.events[n.ev_f1], n.sc));
+    HIPCHK(hipStreamSynchronize(n.sc));
+    HIPCHK(hipStreamSynchronize(n.sm));
+    float loss = 0.f;
+    HIPCHK(hipMemcpy(&loss, blk(n, n.plan.loss_block), 4, hipMemcpyDeviceToHost));
+    s = finish_timing(n, false);
+    if (s != VDNN_OK) return s;
+    if (loss_out) *loss_out = loss;
+    n.fwd_done = true;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_backward(vdnn_net_t* np) {
+    if (!np) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (!n.fwd_done) { n.err = "backward without a completed forward"; return VDNN_ERR_STATE; }
+    n.fwd_done = false;
+    { NEWEV(e); n.ev_b0 = e; }
+    { NEWEV(e); n.ev_b1 = e; }
+    HIPCHK(hipEventRecord(n.events[n.ev_b0], n.sc));
+    vdnn_status_t s = run_ops(n, n.plan.first_bwd_op, (int)n.plan.ops.size(), nullptr, nullptr);
+    if (s != VDNN_OK) { (void)hipDeviceSynchronize(); return s; }
+    HIPCHK(hipEventRecord(n.events[n.ev_b1], n.sc));
+    HIPCHK(hipStreamSynchronize(n.sc));
+    HIPCHK(hipStreamSynchronize(n.sm));
+    return finish_timing(n, true);
+}
+
+vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
+    if (!n || !out) return VDNN_ERR_INVALID_ARG;
+    vdnn_mem_stats_t s;
+    memset(&s, 0, sizeof s);
+    const Plan& p = n->plan;
+    s.budget_bytes = n->budget;
+    s.baseline_bytes = n->baseline;
+    s.effective_policy = n->effective;
+    if (p.ok) {
+        s.cur_bytes = p.persistent;
+        s.peak_bytes = p.peak;
+        s.pool_extent_bytes = p.extent;
+        s.persistent_bytes = p.persistent;
+        s.avg_bytes_layerstep = p.avg;
+        s.offloaded_bytes = p.offloaded;
+        s.prefetched_bytes = p.prefetched;
+        s.pinned_host_bytes = p.pinned;
+        s.workspace_bytes = p.max_ws;
+        s.n_offload = p.n_offload;
+        s.n_prefetch = p.n_prefetch;
+        s.n_ondemand_fetch = p.n_ondemand;
+    }
+    s.fwd_ms = n->fwd_ms; s.bwd_ms = n->bwd_ms; s.stall_ms = n->stall_ms;
+    s.d2h_ms = n->d2h_ms; s.h2d_ms = n->h2d_ms;
+    s.d2h_gbps = n->d2h_ms > 0 ? (double)p.offloaded / (n->d2h_ms * 1e6) : 0.0;
+    s.h2d_gbps = n->h2d_ms > 0 ? (double)p.prefetched / (n->h2d_ms * 1e6) : 0.0;
+    *out = s;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_trace(const vdnn_net_t* n, char* buf, size_t cap, size_t* needed) {
+    if (!n || !needed) return VDNN_ERR_INVALID_ARG;
+    std::string s;
+    const Plan& p = n->plan;
+    for (const Op& o : p.ops) {
+        std::string where = o.phase == 0 ? "create" : fmt("%c%d", o.phase == 1 ? 'F' : 'B', o.layer);
+        switch (o.kind) {
+            case OP_ALLOC: s += fmt("%s alloc %s %zu %zu\n", where.c_str(), p.blocks[o.block].tag.c_str(), p.blocks[o.block].bytes, p.blocks[o.block].offset); break;
+            case OP_FREE: s += fmt("%s free %s %zu %zu\n", where.c_str(), p.blocks[o.block].tag.c_str(), p.blocks[o.block].bytes, p.blocks[o.block].offset); break;
+            case OP_OFFLOAD: s += fmt("%s offload B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
+            case OP_PREFETCH: s += fmt("%s prefetch B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
+            case OP_ONDEMAND: s += fmt("%s ondemand B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
+            case OP_FWD:
+            case OP_BWD: s += fmt("%s compute %s\n", where.c_str(), type_name(n->layers[o.layer].type)); break;
+            default: break;
+        }
+    }
+    if (!p.ok && !p.fail_where.empty()) s += "fail " + p.fail_where + "\n";
+    *needed = s.size() + 1;
+    if (buf && cap) {
+        const size_t k = std::min(cap - 1, s.size());
+        memcpy(buf, s.data(), k);
+        buf[k] = 0;
+    }
+    return VDNN_OK;
+}
+
+const char* vdnn_last_error(const vdnn_net_t* n) { return n ? n->err.c_str() : "null net"; }
+
+void vdnn_destroy(vdnn_net_t* n) {
+    if (!n) return;
+    if (n->have_streams) { (void)hipStreamSynchronize(n->sc); (void)hipStreamSynchronize(n->sm); }
+    for (hipEvent_t e : n->events) (void)hipEventDestroy(e);
+    if (n->own_streams) { (void)hipStreamDestroy(n->sc); (void)hipStreamDestroy(n->sm); }
+    if (n->own_pool && n->pool) (void)hipFree(n->pool);
+    if (n->pinned) (void)hipHostFree(n->pinned);
+    delete n;
+}
+
+}  // extern "C"

@@ -1,0 +1,131 @@
+// Host-side vDNN memory manager: dataflow graph, transfer policy, step planner and executor.
+//
+// The training step of a fixed network is a fixed sequence of operations, so the manager compiles
+// it once per (network, policy, budget) into a "plan": an ordered list of ops (allocate, release,
+// offload, prefetch, compute ...) together with the byte offset of every block inside the pool.
+// Executing a step replays the plan on two HIP streams.  Nothing on the step path calls
+// hipMalloc/hipFree (Section 3.2, "Memory Allocation/Release").  Planning is pure host code and
+// needs no GPU, which is also how vDNN_dyn tests trainability (Section 3.3).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/vdnn.h"
+
+namespace vdnn {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+struct Layer {
+    int type = 0;
+    std::vector<int> inputs;
+    int out = 0, k = 0, stride = 1, pad = 0;
+    int C = 0, H = 0, W = 0;  // output shape (per image)
+    int buf = 0;              // feature-map buffer holding the output (-1 = network input)
+    size_t wcount = 0;        // weight elements
+    int w_block = -1, dw_block = -1;
+};
+
+// A feature-map buffer: produced by one non-in-place layer (or the network input), possibly
+// overwritten in place by activation layers, read by `readers`.
+struct Buffer {
+    size_t count = 0;          // elements
+    int C = 0, H = 0, W = 0;
+    std::vector<int> readers;  // non-in-place layers that read it, ascending
+    std::vector<int> inplace;  // in-place layers living in it
+    std::vector<int> bwd_users;  // layers whose backward computation reads its contents, ascending
+};
+
+enum OpKind {
+    OP_SAMPLE,       // start of a layer's fwd/bwd: sample live bytes
+    OP_ALLOC,
+    OP_FREE,
+    OP_LOAD_INPUT,   // copy the caller's batch and labels into the pool
+    OP_OFFLOAD,      // issue device->host copy of a buffer on the memory stream
+    OP_WAIT_COPY,    // compute stream waits for a copy issued earlier (end-of-layer synchronisation)
+    OP_PREFETCH,     // issue host->device copy on the memory stream
+    OP_ONDEMAND,     // host->device copy the compute stream waits for immediately
+    OP_FWD,
+    OP_BWD,
+};
+
+struct Op {
+    OpKind kind;
+    int phase;       // 0 create, 1 forward, 2 backward
+    int layer;       // -1 for the input load
+    int block = -1;  // ALLOC/FREE/OFFLOAD/PREFETCH/ONDEMAND: the block; WAIT_COPY: block whose copy is awaited
+    int buf = -2;    // buffer id for transfers
+    // compute ops
+    std::vector<int> in_blocks;    // blocks holding the layer's inputs
+    int out_block = -1;            // Y (fwd) / the buffer itself for in-place layers
+    int gin_block = -1;            // dY
+    std::vector<int> gout_blocks;  // dX per input (-1 = not needed); a temp block when accumulate is set
+    std::vector<int> gacc_blocks;  // when >= 0: add gout_blocks[i] into this block afterwards
+    int ws_block = -1;
+};
+
+struct Block {
+    std::string tag;
+    size_t bytes = 0;  // aligned
+    size_t raw = 0;
+    int t0 = 0, t1 = 0;  // op indices [t0, t1)
+    size_t offset = 0;
+    bool persistent = false;
+    size_t host_off = 0;  // offset in the pinned arena (buffers that are offloaded)
+};
+
+struct Plan {
+    bool ok = false;
+    std::string fail_where, fail_why;
+    int policy = 0;
+    std::vector<Op> ops;
+    std::vector<Block> blocks;
+    int first_fwd_op = 0, first_bwd_op = 0;
+    size_t peak = 0, extent = 0, persistent = 0, pinned = 0, max_ws = 0;
+    double avg = 0.0;
+    size_t offloaded = 0, prefetched = 0;
+    int n_offload = 0, n_prefetch = 0, n_ondemand = 0;
+    int labels_block = -1, loss_block = -1;
+};
+
+}  // namespace vdnn
+
+struct vdnn_net {
+    int batch = 0, in_c = 0, in_h = 0, in_w = 0;
+    std::vector<vdnn::Layer> layers;
+    std::vector<vdnn::Buffer> bufs;  // index = buffer id + 1
+    size_t budget = 0;               // 0 = unlimited
+    int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
+    vdnn::Plan plan;
+    size_t baseline = 0;
+
+    // device side
+    char* pool = nullptr;
+    size_t pool_bytes = 0;
+    bool own_pool = false, weights_set = false;
+    hipStream_t sc = nullptr, sm = nullptr;
+    bool have_streams = false, own_streams = false;
+    char* pinned = nullptr;
+    size_t pinned_bytes = 0;
+    std::vector<hipEvent_t> events;
+    int events_used = 0;
+
+    bool fwd_done = false;
+    std::vector<float*> cap_out, cap_grad;
+    std::string err;
+
+    // measured on the last step
+    double fwd_ms = 0, bwd_ms = 0, stall_ms = 0, d2h_ms = 0, h2d_ms = 0;
+    struct Timed { int e0, e1; size_t bytes; int dir; };
+    std::vector<Timed> copies;
+    struct Stall { int e_compute, e_copy; };
+    std::vector<Stall> stalls;
+    int ev_f0 = -1, ev_f1 = -1, ev_b0 = -1, ev_b1 = -1;
+    std::vector<int> copy_done_event;  // per block: event recorded after its last copy
+
+    vdnn::Buffer& B(int id) { return bufs[id + 1]; }
+    const vdnn::Buffer& B(int id) const { return bufs[id + 1]; }
+};

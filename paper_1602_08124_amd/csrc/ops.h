@@ -1,0 +1,38 @@
+// Internal declarations of the layer kernels' host launchers (all pointers are device pointers,
+// all launches are asynchronous on the given stream).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <algorithm>
+
+namespace vdnn {
+
+int gemm_splits(long long m, long long n, long long kred);
+size_t gemm_workspace_bytes(long long m, long long n, long long kred);
+
+hipError_t conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S, int stride,
+                    int pad, int relu, hipStream_t st);
+hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R, int S, int stride,
+                         int pad, hipStream_t st);
+size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
+                           int K, int R, int S, int stride, int pad, hipStream_t st);
+
+size_t fc_workspace(int N, int I, int O, int which);
+hipError_t fc_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st);
+hipError_t fc_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st);
+hipError_t fc_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st);
+
+hipError_t relu_fwd(float* y, size_t count, hipStream_t st);
+hipError_t relu_bwd(const float* y, float* dy, size_t count, hipStream_t st);
+hipError_t maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
+hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
+hipError_t avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
+hipError_t avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
+hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, hipStream_t st);
+hipError_t softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, hipStream_t st);
+hipError_t concat_copy(const float* src, float* dst, int N, int c_src, int c_dst, int c_off, int hw, int to_dst, hipStream_t st);
+hipError_t add_inplace(float* acc, const float* src, size_t count, hipStream_t st);
+
+}  // namespace vdnn

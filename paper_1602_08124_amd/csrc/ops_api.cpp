@@ -1,0 +1,121 @@
+// extern "C" wrappers of the single-layer entry points: argument checks and status mapping only.
+#include "../../include/vdnn.h"
+#include "ops.h"
+
+using namespace vdnn;
+
+static vdnn_status_t st(hipError_t e) {
+    if (e == hipSuccess) return VDNN_OK;
+    (void)hipGetLastError();
+    return e == hipErrorInvalidValue ? VDNN_ERR_INVALID_ARG : VDNN_ERR_HIP;
+}
+
+static bool conv_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    return N > 0 && C > 0 && H > 0 && W > 0 && K > 0 && R > 0 && S > 0 && R == S && stride > 0 && pad >= 0 && H + 2 * pad >= R && W + 2 * pad >= S;
+}
+
+extern "C" {
+
+vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                               int stride, int pad, int relu, void* stream) {
+    if (!x || !w || !y || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_fwd(x, w, y, N, C, H, W, K, R, S, stride, pad, relu, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R,
+                                    int S, int stride, int pad, void* stream) {
+    if (!dy || !w || !dx || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_bwd_data(dy, w, dx, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
+}
+
+size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (!conv_ok(N, C, H, W, K, R, S, stride, pad)) return 0;
+    return conv_bwd_filter_workspace(N, C, H, W, K, R, S, stride, pad);
+}
+
+vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
+                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream) {
+    if (!x || !dy || !dw || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_bwd_filter(x, dy, dw, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
+}
+
+size_t vdnn_op_fc_workspace(int N, int I, int O, int which) {
+    if (N <= 0 || I <= 0 || O <= 0 || which < 0 || which > 2) return 0;
+    return fc_workspace(N, I, O, which);
+}
+
+vdnn_status_t vdnn_op_fc_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int I,
+                             int O, void* stream) {
+    if (!x || !w || !y || N <= 0 || I <= 0 || O <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(fc_fwd(x, w, y, workspace, workspace_bytes, N, I, O, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_fc_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
+                                  int I, int O, void* stream) {
+    if (!dy || !w || !dx || N <= 0 || I <= 0 || O <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(fc_bwd_data(dy, w, dx, workspace, workspace_bytes, N, I, O, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_fc_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes, int N,
+                                    int I, int O, void* stream) {
+    if (!x || !dy || !dw || N <= 0 || I <= 0 || O <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(fc_bwd_filter(x, dy, dw, workspace, workspace_bytes, N, I, O, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_relu_fwd(float* y, size_t count, void* stream) {
+    if (!y && count) return VDNN_ERR_INVALID_ARG;
+    return st(relu_fwd(y, count, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_relu_bwd(const float* y, float* dy, size_t count, void* stream) {
+    if ((!y || !dy) && count) return VDNN_ERR_INVALID_ARG;
+    return st(relu_bwd(y, dy, count, (hipStream_t)stream));
+}
+
+static bool pool_ok(const void* a, const void* b, int N, int C, int H, int W, int k, int stride, int pad) {
+    return a && b && N > 0 && C > 0 && H > 0 && W > 0 && k > 0 && stride > 0 && pad >= 0 && pad < k && H + 2 * pad >= k && W + 2 * pad >= k;
+}
+
+vdnn_status_t vdnn_op_maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream) {
+    if (!pool_ok(x, y, N, C, H, W, k, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(maxpool_fwd(x, y, N, C, H, W, k, stride, pad, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride,
+                                  int pad, void* stream) {
+    if (!dy || !pool_ok(x, dx, N, C, H, W, k, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(maxpool_bwd(x, dy, dx, N, C, H, W, k, stride, pad, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream) {
+    if (!pool_ok(x, y, N, C, H, W, k, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(avgpool_fwd(x, y, N, C, H, W, k, stride, pad, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, void* stream) {
+    if (!pool_ok(dy, dx, N, C, H, W, k, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(avgpool_bwd(dy, dx, N, C, H, W, k, stride, pad, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, void* stream) {
+    if (!z || !labels || !loss || N <= 0 || classes <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(softmax_ce_fwd(z, labels, loss, N, classes, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, void* stream) {
+    if (!z || !labels || !dz || N <= 0 || classes <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(softmax_ce_bwd(z, labels, dz, N, classes, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_concat_copy(const float* src, float* dst, int N, int c_small, int c_big, int c_off, int hw, int to_big,
+                                  void* stream) {
+    if (!src || !dst || N <= 0 || c_small <= 0 || c_big <= 0 || hw <= 0) return VDNN_ERR_INVALID_ARG;
+    return st(concat_copy(src, dst, N, c_small, c_big, c_off, hw, to_big, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_add(float* acc, const float* src, size_t count, void* stream) {
+    if ((!acc || !src) && count) return VDNN_ERR_INVALID_ARG;
+    return st(add_inplace(acc, src, count, (hipStream_t)stream));
+}
+
+}  // extern "C"

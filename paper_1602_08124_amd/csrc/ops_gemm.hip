@@ -1,0 +1,261 @@
+// Launchers for the GEMM-shaped layers: convolution forward / backward-data / backward-filter
+// (implicit GEMM on fp32 MFMA, Section 2.2's "memory-optimal" algorithm: X, Y, W only) and the
+// three FC products.  Reductions that would leave the chip idle are split across workgroups;
+// partial sums go to a caller-provided workspace and are added in a fixed order.
+#include "gemm_tile.h"
+#include "ops.h"
+
+namespace vdnn {
+
+// -------------------------------------------------------------------------------------------
+// split heuristic (shared by the workspace query and the launch)
+// -------------------------------------------------------------------------------------------
+static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+int gemm_splits(long long m, long long n, long long kred) {
+    const int bm = m <= 64 ? 64 : 128;
+    const long long tiles = (long long)cdiv(m, bm) * cdiv(n, 128);
+    long long s = std::min<long long>(1024 / tiles, cdiv(kred, 2048));
+    return (int)std::max<long long>(1, s);
+}
+
+size_t gemm_workspace_bytes(long long m, long long n, long long kred) {
+    const int s = gemm_splits(m, n, kred);
+    return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
+}
+
+// out[i] = sum_s ws[s * slice + i], s ascending (deterministic)
+__global__ void reduce_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, size_t count, int splits) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        float acc = ws[i];
+        for (int s = 1; s < splits; ++s) acc += ws[(size_t)s * count + i];
+        out[i] = acc;
+    }
+}
+
+static hipError_t launch_reduce(const float* ws, float* out, size_t count, int splits, hipStream_t st) {
+    const int threads = 256;
+    const int blocks = (int)std::min<size_t>((count + threads - 1) / threads, 4096);
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks), dim3(threads), 0, st, ws, out, count, splits);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int PADA, int PADB, class LA, class LB, class EP>
+static hipError_t launch_tile(const typename LA::Params& pa, const typename LB::Params& pb, const EP& ep, int rows, int cols,
+                              int ktot, int splits, hipStream_t st) {
+    auto kern = gemm_tile_kernel<BM, BN, BK, WM, WN, PADA, PADB, LA, LB, EP>;
+    constexpr size_t smem = gemm_smem_bytes<BM, BN, BK, PADA, PADB>();
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    GridInfo gi;
+    gi.tiles_m = cdiv(rows, BM);
+    gi.tiles_n = cdiv(cols, BN);
+    gi.splits = splits;
+    gi.ktot = ktot;
+    gi.ksplit = cdiv(cdiv(ktot, splits), BK) * BK;
+    const long long nb = (long long)gi.tiles_m * gi.tiles_n * splits;
+    if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, pa, pb, ep, gi);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------
+// convolution forward and (stride 1) backward-data
+// -------------------------------------------------------------------------------------------
+static ConvGeom make_geom(const float* src, int N, int C, int H, int W, int R, int S, int stride, int pad, int P, int Q) {
+    ConvGeom g;
+    g.src = src;
+    g.C = C; g.H = H; g.W = W;
+    g.R = R; g.S = S; g.stride = stride; g.pad = pad;
+    g.P = P; g.Q = Q;
+    g.M = N * P * Q;
+    g.Ktot = C * R * S;
+    g.fd_pq = make_fastdiv((uint32_t)(P * Q));
+    g.fd_q = make_fastdiv((uint32_t)Q);
+    g.fd_rs = make_fastdiv((uint32_t)(R * S));
+    g.fd_s = make_fastdiv((uint32_t)S);
+    return g;
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t conv_gemm_cfg(const GatherKParams& wa, const ConvGeom& g, const ConvOut& eo, hipStream_t st) {
+    constexpr int BK = 16, PADA = 2, PADB = 32;
+    return launch_tile<BM, BN, BK, WM, WN, PADA, PADB, GatherK<BM, BK, PADA>, Im2colR<BN, BK, PADB>, ConvOut>(
+        wa, g, eo, eo.rows, g.M, g.Ktot, 1, st);
+}
+
+static hipError_t conv_gemm(const GatherKParams& wa, const ConvGeom& g, const ConvOut& eo, hipStream_t st) {
+    if (eo.rows <= 32) return conv_gemm_cfg<32, 256, 1, 4>(wa, g, eo, st);
+    if (eo.rows <= 64) return conv_gemm_cfg<64, 256, 1, 4>(wa, g, eo, st);
+    return conv_gemm_cfg<128, 128, 2, 2>(wa, g, eo, st);
+}
+
+static bool fits_i32(long long v) { return v >= 0 && v < 0x7fffffffLL; }
+
+hipError_t conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S, int stride,
+                    int pad, int relu, hipStream_t st) {
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
+    if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
+    ConvGeom g = make_geom(x, N, C, H, W, R, S, stride, pad, P, Q);
+    GatherKParams wa;
+    wa.base = w; wa.rows = K; wa.rstride = C * R * S; wa.kstride = 1; wa.rs = 1; wa.flip = 0;
+    wa.fd_rs = make_fastdiv(1);
+    ConvOut eo;
+    eo.out = y; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
+    return conv_gemm(wa, g, eo, st);
+}
+
+// General backward-data for strided convolutions: one thread per dX element, gathers every forward
+// term that touched it.  Only first layers are strided in the paper's networks and those need no
+// dX, so this path is for completeness, not speed.
+__global__ void conv_bwd_data_direct_kernel(const float* __restrict__ dy, const float* __restrict__ w, float* __restrict__ dx,
+                                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int P, int Q) {
+    const size_t total = (size_t)N * C * H * W;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int wi = (int)(i % W), hi = (int)((i / W) % H), c = (int)((i / ((size_t)W * H)) % C), n = (int)(i / ((size_t)W * H * C));
+        float acc = 0.f;
+        for (int k = 0; k < K; ++k)
+            for (int r = 0; r < R; ++r) {
+                const int hn = hi + pad - r;
+                if (hn < 0 || hn % stride) continue;
+                const int p = hn / stride;
+                if (p >= P) continue;
+                for (int s = 0; s < S; ++s) {
+                    const int wn = wi + pad - s;
+                    if (wn < 0 || wn % stride) continue;
+                    const int q = wn / stride;
+                    if (q >= Q) continue;
+                    acc += dy[(((size_t)n * K + k) * P + p) * Q + q] * w[(((size_t)k * C + c) * R + r) * S + s];
+                }
+            }
+        dx[i] = acc;
+    }
+}
+
+hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R, int S, int stride,
+                         int pad, hipStream_t st) {
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
+    if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
+    if (stride != 1 || pad > R - 1 || pad > S - 1) {
+        const size_t total = (size_t)N * C * H * W;
+        const int blocks = (int)std::min<size_t>((total + 255) / 256, 65535 * 4);
+        hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3(blocks), dim3(256), 0, st, dy, w, dx, N, C, H, W, K, R, S, stride, pad, P, Q);
+        return hipGetLastError();
+    }
+    // dX[n][c][h][w] = sum_{k,r',s'} dY[n][k][h - (R-1-pad) + r'][w - (S-1-pad) + s'] * W[k][c][R-1-r'][S-1-s']:
+    // a stride-1 convolution of dY (K channels, P x Q image) producing the H x W grid.
+    ConvGeom g = make_geom(dy, N, K, P, Q, R, S, 1, R - 1 - pad, H, W);
+    if (S - 1 - pad != R - 1 - pad) return hipErrorInvalidValue;  // square windows only
+    GatherKParams wa;
+    wa.base = w; wa.rows = C; wa.rstride = R * S; wa.kstride = C * R * S; wa.rs = R * S; wa.flip = 1;
+    wa.fd_rs = make_fastdiv((uint32_t)(R * S));
+    ConvOut eo;
+    eo.out = dx; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
+    return conv_gemm(wa, g, eo, st);
+}
+
+// -------------------------------------------------------------------------------------------
+// convolution backward-filter
+// -------------------------------------------------------------------------------------------
+size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t bwdf_cfg(const PixKParams& pa, const ConvGeom& g, const RowMajorOut& eo, int splits, hipStream_t st) {
+    constexpr int BK = 32, PAD = 1;
+    return launch_tile<BM, BN, BK, WM, WN, PAD, PAD, PixK<BM, BK, PAD>, Im2colK<BN, BK, PAD>, RowMajorOut>(
+        pa, g, eo, eo.rows, eo.cols, g.M, splits, st);
+}
+
+hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
+                           int K, int R, int S, int stride, int pad, hipStream_t st) {
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
+    if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
+    const int CRS = C * R * S;
+    const int splits = gemm_splits(K, CRS, (long long)N * P * Q);
+    const size_t need = splits > 1 ? (size_t)splits * K * CRS * sizeof(float) : 0;
+    if (ws_bytes < need || (need && !ws)) return hipErrorInvalidValue;
+    ConvGeom g = make_geom(x, N, C, H, W, R, S, stride, pad, P, Q);
+    PixKParams pa;
+    pa.base = dy; pa.rows = K; pa.PQ = P * Q; pa.fd_pq = g.fd_pq;
+    RowMajorOut eo;
+    eo.out = splits > 1 ? (float*)ws : dw;
+    eo.rows = K; eo.cols = CRS; eo.ld = CRS; eo.slice = (size_t)K * CRS;
+    hipError_t e = K <= 64 ? bwdf_cfg<64, 128, 1, 4>(pa, g, eo, splits, st) : bwdf_cfg<128, 128, 2, 2>(pa, g, eo, splits, st);
+    if (e != hipSuccess) return e;
+    if (splits > 1) return launch_reduce((const float*)ws, dw, (size_t)K * CRS, splits, st);
+    return hipSuccess;
+}
+
+// -------------------------------------------------------------------------------------------
+// FC
+// -------------------------------------------------------------------------------------------
+size_t fc_workspace(int N, int I, int O, int which) {
+    if (which == 0) return gemm_workspace_bytes(N, O, I);
+    if (which == 1) return gemm_workspace_bytes(N, I, O);
+    return gemm_workspace_bytes(O, I, N);
+}
+
+static GatherKParams dense_k(const float* base, int rows, int ld) {
+    GatherKParams p;
+    p.base = base; p.rows = rows; p.rstride = ld; p.kstride = 1; p.rs = 1; p.flip = 0;
+    p.fd_rs = make_fastdiv(1);
+    return p;
+}
+
+static RowMajorOut fc_out(float* out, void* ws, int rows, int cols, int splits) {
+    RowMajorOut eo;
+    eo.out = splits > 1 ? (float*)ws : out;
+    eo.rows = rows; eo.cols = cols; eo.ld = cols; eo.slice = (size_t)rows * cols;
+    return eo;
+}
+
+hipError_t fc_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
+    constexpr int BK = 16, PAD = 2;
+    const int splits = gemm_splits(N, O, I);
+    if (ws_bytes < gemm_workspace_bytes(N, O, I) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    RowMajorOut eo = fc_out(y, ws, N, O, splits);
+    hipError_t e = launch_tile<128, 128, BK, 2, 2, PAD, PAD, GatherK<128, BK, PAD>, GatherK<128, BK, PAD>, RowMajorOut>(
+        dense_k(x, N, I), dense_k(w, O, I), eo, N, O, I, splits, st);
+    if (e != hipSuccess) return e;
+    return splits > 1 ? launch_reduce((const float*)ws, y, (size_t)N * O, splits, st) : hipSuccess;
+}
+
+hipError_t fc_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
+    constexpr int BK = 16, PADA = 2, PADB = 32;
+    const int splits = gemm_splits(N, I, O);
+    if (ws_bytes < gemm_workspace_bytes(N, I, O) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    RowMajorOut eo = fc_out(dx, ws, N, I, splits);
+    DenseRParams pb;
+    pb.base = w; pb.rows = I; pb.ld = I;
+    hipError_t e = launch_tile<128, 128, BK, 2, 2, PADA, PADB, GatherK<128, BK, PADA>, DenseR<128, BK, PADB>, RowMajorOut>(
+        dense_k(dy, N, O), pb, eo, N, I, O, splits, st);
+    if (e != hipSuccess) return e;
+    return splits > 1 ? launch_reduce((const float*)ws, dx, (size_t)N * I, splits, st) : hipSuccess;
+}
+
+hipError_t fc_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
+    constexpr int BK = 16, PAD = 32;
+    const int splits = gemm_splits(O, I, N);
+    if (ws_bytes < gemm_workspace_bytes(O, I, N) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    RowMajorOut eo = fc_out(dw, ws, O, I, splits);
+    DenseRParams pa, pb;
+    pa.base = dy; pa.rows = O; pa.ld = O;
+    pb.base = x; pb.rows = I; pb.ld = I;
+    hipError_t e = launch_tile<128, 128, BK, 2, 2, PAD, PAD, DenseR<128, BK, PAD>, DenseR<128, BK, PAD>, RowMajorOut>(
+        pa, pb, eo, O, I, N, splits, st);
+    if (e != hipSuccess) return e;
+    return splits > 1 ? launch_reduce((const float*)ws, dw, (size_t)O * I, splits, st) : hipSuccess;
+}
+
+}  // namespace vdnn

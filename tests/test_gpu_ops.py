@@ -1,0 +1,235 @@
+"""GPU parity, single layers: every kernel behind the C ABI against the CPU oracle, element by
+element, on seeded inputs whose sizes span several tiles and leave ragged tails."""
+import numpy as np
+import pytest
+
+from oracle import layers as L
+from tests.gpu_util import TOL, dev, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1602_08124_amd import binding
+    return binding
+
+
+def _t(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+
+
+CONV_SHAPES = [
+    # N, C, H, W, K, R, stride, pad
+    (2, 3, 32, 32, 16, 3, 1, 1),      # 32-row tile, K-tail (27)
+    (3, 16, 17, 19, 40, 3, 1, 1),     # 64-row tile, ragged pixel count (969)
+    (2, 24, 20, 20, 136, 3, 1, 1),    # 128-row tile + ragged rows, reduction 216 (not a multiple of 16)
+    (2, 3, 35, 35, 96, 11, 4, 0),     # AlexNet-style first layer
+    (2, 8, 14, 14, 20, 5, 1, 2),      # 5x5
+    (1, 16, 9, 9, 8, 1, 1, 0),        # 1x1
+    (2, 3, 30, 30, 64, 7, 2, 3),      # GoogLeNet-style stem
+    (1, 130, 7, 7, 260, 3, 1, 1),     # more rows than pixels, 3 row tiles
+    (5, 4, 3, 3, 4, 3, 1, 1),         # tiny image
+    (2, 6, 12, 12, 10, 3, 1, 0),      # no padding
+    (2, 6, 12, 12, 10, 3, 1, 2),      # padding larger than usual (output grows)
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_conv_fwd(B, shape, relu):
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    x, wt = _t((n, c, h, w), 1), _t((k, c, r, r), 2)
+    ref = L.conv_fwd(x, wt, st, pd)
+    if relu:
+        ref = L.relu_fwd(ref)
+    y = torch.full(ref.shape, float("nan"), device="cuda")
+    B.op_conv_fwd(dev(x), dev(wt), y, st, pd, relu)
+    assert rel_err(host(y), ref) < TOL
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_bwd_data(B, shape):
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    wt = _t((k, c, r, r), 3)
+    p, q = L.out_dim(h, r, st, pd), L.out_dim(w, r, st, pd)
+    dy = _t((n, k, p, q), 4)
+    ref = L.conv_bwd_data(dy, wt, (n, c, h, w), st, pd)
+    dx = torch.full((n, c, h, w), float("nan"), device="cuda")
+    B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd)
+    assert rel_err(host(dx), ref) < TOL
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES + [(8, 8, 64, 64, 16, 3, 1, 1), (4, 20, 40, 40, 72, 3, 1, 1)])
+def test_conv_bwd_filter(B, shape):
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    x = _t((n, c, h, w), 5)
+    p, q = L.out_dim(h, r, st, pd), L.out_dim(w, r, st, pd)
+    dy = _t((n, k, p, q), 6)
+    ref = L.conv_bwd_filter(x, dy, (k, c, r, r), st, pd)
+    nbytes = B.op_conv_bwd_filter_workspace(x.shape, (k, c, r, r), st, pd)
+    ws = torch.empty(max(nbytes, 4) // 4, device="cuda") if nbytes else None
+    dw = torch.full((k, c, r, r), float("nan"), device="cuda")
+    B.op_conv_bwd_filter(dev(x), dev(dy), dw, ws, st, pd)
+    assert rel_err(host(dw), ref) < TOL
+
+
+def test_conv_bwd_filter_is_split_and_deterministic(B):
+    import torch
+    shape = (8, 8, 64, 64, 16, 3, 1, 1)
+    n, c, h, w, k, r, st, pd = shape
+    nbytes = B.op_conv_bwd_filter_workspace((n, c, h, w), (k, c, r, r), st, pd)
+    assert nbytes == 16 * k * c * r * r * 4  # reduction of 32768 split 16 ways
+    x, dy = dev(_t((n, c, h, w), 7)), dev(_t((n, k, h, w), 8))
+    outs = []
+    for _ in range(3):
+        ws = torch.empty(nbytes // 4, device="cuda")
+        dw = torch.empty((k, c, r, r), device="cuda")
+        B.op_conv_bwd_filter(x, dy, dw, ws, st, pd)
+        outs.append(host(dw).copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_conv_adjoint_identities_on_gpu(B):
+    """<conv(X,W),dY> = <X,bwd_data(dY,W)> = <W,bwd_filter(X,dY)> with the GPU's own tensors (fp64 inner products)."""
+    import torch
+    n, c, h, w, k, r, st, pd = 4, 32, 28, 28, 48, 3, 1, 1
+    x, wt, dy = dev(_t((n, c, h, w), 9)), dev(_t((k, c, r, r), 10)), dev(_t((n, k, h, w), 11))
+    y = torch.empty((n, k, h, w), device="cuda")
+    dx = torch.empty((n, c, h, w), device="cuda")
+    dw = torch.empty((k, c, r, r), device="cuda")
+    nbytes = B.op_conv_bwd_filter_workspace((n, c, h, w), (k, c, r, r), st, pd)
+    ws = torch.empty(max(nbytes, 4) // 4, device="cuda")
+    B.op_conv_fwd(x, wt, y, st, pd)
+    B.op_conv_bwd_data(dy, wt, dx, st, pd)
+    B.op_conv_bwd_filter(x, dy, dw, ws, st, pd)
+    a = np.vdot(host(y).astype(np.float64), host(dy).astype(np.float64))
+    b = np.vdot(host(x).astype(np.float64), host(dx).astype(np.float64))
+    cc = np.vdot(host(wt).astype(np.float64), host(dw).astype(np.float64))
+    assert abs(a - b) < 1e-5 * abs(a) and abs(a - cc) < 1e-5 * abs(a)
+
+
+@pytest.mark.parametrize("nio", [(8, 2048, 10), (5, 300, 130), (64, 4096, 256), (256, 1000, 384), (130, 520, 260)])
+def test_fc(B, nio):
+    import torch
+    n, i, o = nio
+    x, w, dy = _t((n, i), 12), _t((o, i), 13), _t((n, o), 14)
+
+    def ws(which):
+        nb = B.op_fc_workspace(n, i, o, which)
+        return torch.empty(nb // 4, device="cuda") if nb else None
+    y = torch.full((n, o), float("nan"), device="cuda")
+    B.op_fc_fwd(dev(x), dev(w), y, ws(0))
+    assert rel_err(host(y), L.fc_fwd(x, w)) < TOL
+    dx = torch.full((n, i), float("nan"), device="cuda")
+    B.op_fc_bwd_data(dev(dy), dev(w), dx, ws(1))
+    assert rel_err(host(dx), L.fc_bwd_data(dy, w, (n, i))) < TOL
+    dw = torch.full((o, i), float("nan"), device="cuda")
+    B.op_fc_bwd_filter(dev(x), dev(dy), dw, ws(2))
+    assert rel_err(host(dw), L.fc_bwd_filter(x, dy)) < TOL
+
+
+@pytest.mark.parametrize("count", [1, 3, 4, 1023, 4096 * 33 + 2])
+def test_relu(B, count):
+    x = _t((count,), 15)
+    x[::7] = 0.0
+    y = dev(x.copy())
+    B.op_relu_fwd(y)
+    ref = L.relu_fwd(x)
+    assert np.array_equal(host(y), ref.astype(np.float32))
+    g = _t((count,), 16)
+    dy = dev(g.copy())
+    B.op_relu_bwd(y, dy)
+    assert np.array_equal(host(dy), L.relu_bwd(ref, g).astype(np.float32))
+
+
+POOLS = [(2, 3, 8, 8, 2, 2, 0), (2, 5, 13, 13, 3, 2, 0), (3, 4, 14, 14, 3, 2, 1), (2, 6, 7, 9, 3, 1, 1), (1, 2, 7, 7, 7, 1, 0),
+         (2, 3, 55, 55, 3, 2, 0), (1, 3, 6, 6, 2, 2, 0)]
+
+
+@pytest.mark.parametrize("cfg", POOLS)
+def test_maxpool(B, cfg):
+    import torch
+    n, c, h, w, k, st, pd = cfg
+    x = _t((n, c, h, w), 17)
+    x = np.maximum(x, 0)  # post-ReLU style input: plenty of ties at 0, the case the tie rule is for
+    ref = L.maxpool_fwd(x, k, st, pd)
+    y = torch.full(ref.shape, float("nan"), device="cuda")
+    B.op_maxpool_fwd(dev(x), y, k, st, pd)
+    assert np.array_equal(host(y), ref.astype(np.float32))
+    dy = _t(ref.shape, 18)
+    dx = torch.full(x.shape, float("nan"), device="cuda")
+    B.op_maxpool_bwd(dev(x), dev(dy), dx, k, st, pd)
+    assert rel_err(host(dx), L.maxpool_bwd(x, dy, k, st, pd)) < 1e-6
+
+
+@pytest.mark.parametrize("cfg", POOLS)
+def test_avgpool(B, cfg):
+    import torch
+    n, c, h, w, k, st, pd = cfg
+    x = _t((n, c, h, w), 19)
+    ref = L.avgpool_fwd(x, k, st, pd)
+    y = torch.full(ref.shape, float("nan"), device="cuda")
+    B.op_avgpool_fwd(dev(x), y, k, st, pd)
+    assert rel_err(host(y), ref) < 1e-6
+    dy = _t(ref.shape, 20)
+    dx = torch.full(x.shape, float("nan"), device="cuda")
+    B.op_avgpool_bwd(dev(dy), dx, k, st, pd)
+    assert rel_err(host(dx), L.avgpool_bwd(dy, x.shape, k, st, pd)) < 1e-6
+
+
+@pytest.mark.parametrize("nc", [(8, 10), (256, 1000), (3, 1000), (17, 65), (1, 2)])
+def test_softmax_ce(B, nc):
+    import torch
+    n, classes = nc
+    z = _t((n, classes), 21) * 3
+    lab = np.random.default_rng(22).integers(0, classes, n).astype(np.int32)
+    loss_ref, dz_ref = L.softmax_ce(z, lab)
+    loss = torch.full((1,), float("nan"), device="cuda")
+    B.op_softmax_ce_fwd(dev(z), dev(lab), loss)
+    assert abs(host(loss)[0] - loss_ref) < TOL * abs(loss_ref)
+    dz = torch.full((n, classes), float("nan"), device="cuda")
+    B.op_softmax_ce_bwd(dev(z), dev(lab), dz)
+    assert rel_err(host(dz), dz_ref) < TOL
+    # zero logits: the loss is ln(classes)
+    B.op_softmax_ce_fwd(dev(np.zeros((n, classes), np.float32)), dev(lab), loss)
+    assert abs(host(loss)[0] - np.log(classes)) < 1e-6 * np.log(classes) + 1e-7
+
+
+def test_concat_and_add(B):
+    import torch
+    n, hw = 3, 35
+    parts = [_t((n, c, 5, 7), 30 + c) for c in (3, 8, 1)]
+    big = torch.full((n, 12, 5, 7), float("nan"), device="cuda")
+    off = 0
+    for p in parts:
+        B.op_concat_copy(dev(p), big, n, p.shape[1], 12, off, hw, True)
+        off += p.shape[1]
+    ref = np.concatenate(parts, axis=1)
+    assert np.array_equal(host(big), ref)
+    off = 0
+    for p in parts:
+        small = torch.full(p.shape, float("nan"), device="cuda")
+        B.op_concat_copy(big, small, n, p.shape[1], 12, off, hw, False)
+        assert np.array_equal(host(small), p)
+        off += p.shape[1]
+    a, b = _t((1000,), 40), _t((1000,), 41)
+    acc = dev(a.copy())
+    B.op_add(acc, dev(b))
+    assert np.array_equal(host(acc), a + b)
+
+
+def test_invalid_arguments_are_rejected(B):
+    import torch
+    x = torch.zeros(16, device="cuda")
+    lib = B.lib
+    assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
+    # workspace too small for a split reduction
+    assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG

@@ -1,0 +1,135 @@
+"""CPU tests of the library's host logic: the C ABI loads and exports every declared symbol, the
+planner's op sequence and byte statistics equal the memory-schedule oracle's, its placement never
+overlaps live blocks, and error paths return statuses."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import memsched as ms
+from synth import nets
+
+binding = pytest.importorskip("paper_1602_08124_amd.binding")
+G = 2 ** 30
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "vdnn.h")).read()
+    declared = set(re.findall(r"\b(vdnn_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 30
+    for name in declared:
+        assert hasattr(binding.lib, name), name
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+
+
+def _check_placement(trace, budget):
+    live = {}
+    for t in trace:
+        if t[1] == "alloc":
+            off, size = t[4], t[3]
+            assert off % 256 == 0 and off + size <= budget
+            for tag, (o2, s2) in live.items():
+                assert off + size <= o2 or o2 + s2 <= off, (t, tag)
+            assert t[2] not in live
+            live[t[2]] = (off, size)
+        elif t[1] == "free":
+            assert live.pop(t[2]) == (t[4], t[3])
+    return live
+
+
+CASES = [(nets.tiny, 8), (nets.alexnet, 128), (nets.overfeat, 128), (nets.googlenet, 128), (nets.vgg16, 256),
+         (nets.fork_join, 4), (lambda b: nets.vgg(b, extra_per_group=20), 32)]
+
+
+@pytest.mark.parametrize("mk,batch", CASES)
+@pytest.mark.parametrize("policy", ["none", "conv", "all"])
+def test_plan_equals_memory_schedule_oracle(mk, batch, policy):
+    net = mk(batch)
+    n = binding.Net(net, 0)
+    n.set_policy(policy)
+    ref = ms.simulate(net, policy, 1 << 50)
+    tr = n.trace()
+    assert [t[:4] for t in tr] == [tuple(t) for t in ref["trace"]]
+    st = n.stats()
+    for k in ("peak_bytes", "offloaded_bytes", "prefetched_bytes", "n_offload", "n_prefetch", "n_ondemand_fetch"):
+        assert st[k] == ref[k], k
+    assert st["cur_bytes"] == ref["cur_bytes"] == st["persistent_bytes"]
+    assert abs(st["avg_bytes_layerstep"] - ref["avg_bytes_layerstep"]) < 1e-6 * ref["avg_bytes_layerstep"]
+    assert st["baseline_bytes"] == ms.baseline_bytes(net)
+    assert st["pool_extent_bytes"] >= st["peak_bytes"]
+    left = _check_placement(tr, st["pool_extent_bytes"])
+    assert sum(s for _, s in left.values()) == st["persistent_bytes"]
+    n.close()
+
+
+@pytest.mark.parametrize("mk,batch,budget", [(nets.tiny, 8, 4 << 20), (nets.alexnet, 128, G), (nets.overfeat, 128, 2 * G),
+                                             (nets.googlenet, 128, 3 * G), (nets.vgg16, 256, 12 * G), (nets.vgg16, 256, 2 * G),
+                                             (nets.vgg16, 128, 12 * G)])
+def test_trainability_and_dyn_match_oracle(mk, batch, budget):
+    net = mk(batch)
+    n = binding.Net(net, budget)
+    for policy in ("none", "conv", "all"):
+        ref = ms.simulate(net, policy, budget)
+        s = n.try_policy(policy)
+        assert (s == binding.OK) == (ref["status"] == "ok"), (policy, n.last_error())
+        if s != binding.OK:
+            assert s == binding.ERR_OOM_DEVICE
+            assert n.last_error().startswith(ref["oom_at"] + ":")
+        else:
+            assert n.stats()["pool_extent_bytes"] <= budget
+    pol, _ = ms.dynamic(net, budget)
+    s = n.try_policy("dyn")
+    if pol is None:
+        assert s == binding.ERR_OOM_DEVICE
+    else:
+        assert s == binding.OK and n.stats()["effective_policy"] == pol
+    n.close()
+
+
+def test_vgg16_b256_fits_12_gib_with_all_and_conv():
+    net = nets.vgg16(256)
+    n = binding.Net(net, 12 * G)
+    assert n.try_policy("none") == binding.ERR_OOM_DEVICE
+    for p in ("all", "conv"):
+        n.set_policy(p)
+        st = n.stats()
+        assert st["pool_extent_bytes"] <= 12 * G
+    n.set_policy("dyn")
+    assert n.stats()["effective_policy"] == "conv"
+    n.close()
+
+
+def test_invalid_descriptions_are_rejected():
+    def status(net):
+        desc, keep = binding.make_desc(net)
+        h = C.c_void_p()
+        s = binding.lib.vdnn_create(C.byref(desc), 0, C.byref(h))
+        if s == binding.OK:
+            binding.lib.vdnn_destroy(h)
+        return s
+    good = nets.tiny(2)
+    assert status(good) == binding.OK
+    bad = nets.tiny(2)
+    bad["layers"][-1]["type"] = "relu"          # no loss at the end
+    assert status(bad) == binding.ERR_INVALID_ARG
+    bad = nets.tiny(2)
+    bad["layers"][2]["inputs"] = [5]            # consumes a later layer
+    assert status(bad) == binding.ERR_INVALID_ARG
+    bad = nets.tiny(2)
+    bad["layers"][0]["k"] = 99                  # window larger than the image
+    assert status(bad) == binding.ERR_INVALID_ARG
+    bad = nets.tiny(2)
+    bad["batch"] = 0
+    assert status(bad) == binding.ERR_INVALID_ARG
+    bad = nets.tiny(2)
+    bad["layers"][2]["inputs"] = [0]            # pool reads conv output that an in-place relu overwrites
+    assert status(bad) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_create(None, 0, None) == binding.ERR_INVALID_ARG
+
+
+def test_backward_without_forward_is_a_state_error():
+    n = binding.Net(nets.tiny(2), 0)
+    assert binding.lib.vdnn_backward(n.h) == binding.ERR_STATE
+    n.close()
