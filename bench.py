@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark: one training step (forward + backward) of VGG-16, batch 256, fp32, on one MI355X,
+with the vDNN memory manager under a 12 GiB device budget.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints ONE JSON line.  `value` is images/s with vDNN_all under 12 GiB (inputs resident in HBM);
+the `policies` object gives the same measurement for none (unlimited budget), conv, dyn and all,
+with peak pool bytes and achieved host-link GB/s.  `roofline` times the dominant kernel (the
+implicit-GEMM convolution) with HIP events on its own stream; `cpu_baseline` times the CPU oracle
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+GIB = 1 << 30
+FP32_MFMA_PEAK_TFLOPS = 157.3
+# HBM bytes per launch of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured.
+ROOFLINE_TRAFFIC_BYTES = None
+
+
+def conv_layers_vgg16(batch):
+    """(name, N, C, H, W, K) of the 13 convolutions, 3x3 stride 1 pad 1."""
+    cfg = [("c1_1", 3, 224, 64), ("c1_2", 64, 224, 64), ("c2_1", 64, 112, 128), ("c2_2", 128, 112, 128),
+           ("c3_1", 128, 56, 256), ("c3_2", 256, 56, 256), ("c3_3", 256, 56, 256), ("c4_1", 256, 28, 512),
+           ("c4_2", 512, 28, 512), ("c4_3", 512, 28, 512), ("c5_1", 512, 14, 512), ("c5_2", 512, 14, 512),
+           ("c5_3", 512, 14, 512)]
+    return [(n, batch, c, h, h, k) for n, c, h, k in cfg]
+
+
+def time_kernel(fn, stream, warmup=2, iters=8):
+    """Average duration (ms) of fn() launches, from HIP events recorded on the launch stream."""
+    import torch
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+_STREAMS = None
+
+
+def streams():
+    """One (compute, memory) stream pair for the whole process."""
+    global _STREAMS
+    if _STREAMS is None:
+        import torch
+        _STREAMS = (torch.cuda.Stream(), torch.cuda.Stream())
+    return _STREAMS
+
+
+def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=None, iters=5):
+    import torch
+    stream = streams()[0]
+    rows = []
+    for name, n, c, h, w, k in conv_layers_vgg16(batch):
+        if layers and name not in layers:
+            continue
+        x = torch.randn((n, c, h, w), device="cuda")
+        wt = torch.randn((k, c, 3, 3), device="cuda") * 0.05
+        y = torch.empty((n, k, h, w), device="cuda")
+        flop = 2.0 * n * h * w * k * c * 9
+        row = dict(layer=name, gflop=flop / 1e9)
+        torch.cuda.synchronize()
+        if "fwd" in which:
+            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream), stream, iters=iters)
+            row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9
+        if "bwd_data" in which and c > 3:
+            dx = torch.empty_like(x)
+            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream), stream, iters=iters)
+            row["bwd_data_ms"], row["bwd_data_tflops"] = ms, flop / ms / 1e9
+            del dx
+        if "bwd_filter" in which:
+            nb = B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)
+            ws = torch.empty(max(nb, 4) // 4, device="cuda")
+            dw = torch.empty_like(wt)
+            ms = time_kernel(lambda: B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream), stream, iters=iters)
+            row["bwd_filter_ms"], row["bwd_filter_tflops"] = ms, flop / ms / 1e9
+            del ws, dw
+        rows.append(row)
+        del x, wt, y
+    return rows
+
+
+def roofline(B, batch):
+    """Dominant kernel: the 128x128 implicit-GEMM convolution tile kernel, on the most common VGG-16
+    shape (c4_2 / c4_3 forward: 256 x 512 x 28 x 28 -> 512 channels, 947 GFLOP per launch)."""
+    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c4_2",), iters=10)[0]
+    ach = row["fwd_tflops"]
+    return dict(bound="mfma", kernel="gemm_tile_kernel<128,128,16> conv fwd, VGG-16 c4_2 b%d" % batch, achieved=ach,
+                peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=ROOFLINE_TRAFFIC_BYTES,
+                flop_per_launch=row["gflop"] * 1e9, ms_per_launch=row["fwd_ms"])
+
+
+def cpu_baseline(sample_batch):
+    """The CPU oracle, as it stands, on one training step of VGG-16 at a small batch."""
+    from oracle import net as onet
+    from synth import gen, nets
+    net = nets.vgg16(sample_batch)
+    x, labels, weights = gen.make(net, seed=gen.seed_for("vgg16"))
+    t0 = time.perf_counter()
+    onet.step(net, x, labels, weights)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+    return dict(value=sample_batch / dt, unit="img/s", cores=cores, kind="oracle",
+                sample="one fwd+bwd step of VGG-16 at batch %d (%.1f s); per-image cost of the direct loops does not depend on the batch" % (sample_batch, dt))
+
+
+def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
+    import torch
+    n = B.Net(net, budget)
+    status = n.try_policy(policy)
+    if status != B.OK:
+        msg = n.last_error()
+        n.close()
+        return dict(status="oom" if status == B.ERR_OOM_DEVICE else "error %d" % status, detail=msg)
+    n.attach_torch(streams=streams())
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    loss = None
+    for _ in range(warmup):
+        loss = n.forward(x_dev, lab_dev)
+        n.backward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    fwd_ms = bwd_ms = stall = d2h = h2d = 0.0
+    for _ in range(steps):
+        loss = n.forward(x_dev, lab_dev)
+        n.backward()
+        st = n.stats()
+        fwd_ms += st["fwd_ms"]; bwd_ms += st["bwd_ms"]; stall += st["stall_ms"]; d2h += st["d2h_gbps"]; h2d += st["h2d_gbps"]
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    st = n.stats()
+    out = dict(status="ok", img_per_s=net["batch"] / dt, ms_per_step=dt * 1e3, fwd_ms=fwd_ms / steps, bwd_ms=bwd_ms / steps,
+               stall_ms=stall / steps, loss=loss, effective_policy=st["effective_policy"], budget_bytes=budget,
+               peak_bytes=st["peak_bytes"], pool_extent_bytes=st["pool_extent_bytes"], avg_bytes=st["avg_bytes_layerstep"],
+               baseline_bytes=st["baseline_bytes"], offloaded_bytes=st["offloaded_bytes"], pinned_host_bytes=st["pinned_host_bytes"],
+               n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
+               d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=64.0)
+    n.close()
+    del n
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--budget-gib", type=float, default=12.0)
+    ap.add_argument("--policies", default="none,conv,dyn,all")
+    ap.add_argument("--kernel-only", action="store_true", help="only the roofline kernel (for rocprofv3 runs)")
+    ap.add_argument("--calibrate-copy", action="store_true", help="with --kernel-only: also run a 1 GiB plain copy kernel")
+    ap.add_argument("--kernel-table", action="store_true", help="also time every VGG-16 convolution, three passes each")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the vDNN step is a single-GPU method); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1602_08124_amd import binding as B
+    from synth import gen, nets
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.kernel_only:
+        out = dict(roofline=roofline(B, args.batch))
+        if args.calibrate_copy:
+            # a plain copy of known size, so that FETCH_SIZE / WRITE_SIZE readings can be scaled
+            nfl = (1 << 30) // 4
+            src = torch.ones(nfl, device="cuda")
+            dst = torch.empty(nfl, device="cuda")
+            st = streams()[0]
+            for _ in range(3):
+                B.op_concat_copy(src, dst, 1, 1, 1, 0, nfl, True, st)
+            st.synchronize()
+            out["copy_calibration"] = dict(kernel="concat_copy_kernel", read_bytes=nfl * 4, write_bytes=nfl * 4)
+        print(json.dumps(out))
+        return
+
+    net = nets.vgg16(args.batch)
+    x, labels, weights = gen.make(net)
+    x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
+    budget = int(args.budget_gib * GIB)
+    policies = {}
+    for pol in args.policies.split(","):
+        policies[pol] = run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else budget, args.steps, args.warmup)
+        print("[bench] %s: %s" % (pol, json.dumps(policies[pol])), file=sys.stderr, flush=True)
+    head = policies.get("all") or next(iter(policies.values()))
+    none = policies.get("none")
+    if none and none.get("status") == "ok":
+        for p in policies.values():
+            if p.get("status") == "ok":
+                p["vs_no_offload"] = p["img_per_s"] / none["img_per_s"]
+    rf = roofline(B, args.batch)
+    out = {
+        "metric": "img/s VGG-16 b%d fp32 under %g GiB budget (vDNN_all)" % (args.batch, args.budget_gib),
+        "value": head.get("img_per_s"), "unit": "img/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head.get("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "vgg16_b%d_fp32_fwd+bwd_vdnn_all_%ggib" % (args.batch, args.budget_gib), "batch": args.batch,
+                   "budget_bytes": budget, "policy": "all", "step_tflop": 23.718 * args.batch / 256},
+        "step_tflops_achieved": 23.718 * args.batch / 256 / (head["ms_per_step"] / 1e3) if head.get("ms_per_step") else None,
+        "peak_gpu_bytes": head.get("peak_bytes"),
+        "policies": policies,
+        "roofline": rf,
+    }
+    if args.kernel_table:
+        out["conv_kernels"] = conv_kernel_table(B, args.batch)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_batch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

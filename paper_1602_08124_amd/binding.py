@@ -163,13 +163,16 @@ class Net:
             out.append(tuple(t[:3]) + tuple(int(v) for v in t[3:]))
         return out
 
-    def attach_torch(self, pool_bytes=None):
-        """Allocates the pool as a torch uint8 tensor and two torch streams, and lends them to the library."""
+    def attach_torch(self, pool_bytes=None, streams=None):
+        """Allocates the pool as a torch uint8 tensor and lends it to the library together with two
+        torch streams (compute, memory).  Pass `streams` to reuse a pair: a process that keeps
+        creating streams ends up with several of them on one hardware queue, where a copy and
+        a kernel from different streams no longer overlap."""
         import torch
         st = self.stats()
         nbytes = int(pool_bytes if pool_bytes is not None else (st["budget_bytes"] or st["pool_extent_bytes"]))
         self._pool = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        self._streams = (torch.cuda.Stream(), torch.cuda.Stream())
+        self._streams = tuple(streams) if streams is not None else (torch.cuda.Stream(), torch.cuda.Stream())
         self._chk(lib.vdnn_attach_device(self.h, self._pool.data_ptr(), nbytes, self._streams[0].cuda_stream,
                                          self._streams[1].cuda_stream))
 
