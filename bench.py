@@ -76,12 +76,13 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
         flop = 2.0 * n * h * w * k * c * 9
         row = dict(layer=name, gflop=flop / 1e9)
         torch.cuda.synchronize()
+        wsp = torch.empty_like(wt)  # packed-weight workspace of the faster algorithm (ignored when it does not apply)
         if "fwd" in which:
-            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp), stream, iters=iters)
             row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9
         if "bwd_data" in which and c > 3:
             dx = torch.empty_like(x)
-            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream, wsp), stream, iters=iters)
             row["bwd_data_ms"], row["bwd_data_tflops"] = ms, flop / ms / 1e9
             del dx
         if "bwd_filter" in which:

@@ -144,12 +144,20 @@ void vdnn_destroy(vdnn_net_t*);
 /* stream: hipStream_t or NULL.  Shapes: X [N][C][H][W], W [K][C][R][S], Y [N][K][P][Q] with
  * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream. */
 
+/* Two implicit-GEMM algorithms, in the sense of Section 2.2's memory-optimal / performance-optimal
+ * pair: without workspace the gather works directly on W as stored; with a workspace of
+ * vdnn_op_conv_*_workspace() bytes (one packed copy of W, 0 when the faster kernel does not apply:
+ * reduction channels not a multiple of 16, strided backward-data, tensors of 4 GiB or more) the faster
+ * kernel runs.  workspace may be NULL: then the no-workspace algorithm runs.  Same results to rounding
+ * order; each algorithm is deterministic. */
+size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 /* Y = conv(X, W); relu != 0 applies max(.,0) to the result in the same kernel. */
-vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
-                               int stride, int pad, int relu, void* stream);
+vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
+                               int H, int W, int K, int R, int S, int stride, int pad, int relu, void* stream);
 /* dX = sum over the forward terms that touched it (Eq. chain_rule). */
-vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R,
-                                    int S, int stride, int pad, void* stream);
+vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
+                                    int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
 /* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
  * order (deterministic, no atomics).  workspace may be NULL iff the required size is 0. */
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);

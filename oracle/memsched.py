@@ -157,9 +157,16 @@ def workspace_bytes(net, info, i, phase):
     l = net["layers"][i]
     n = net["batch"]
     c, h, w = info["shp"](l["inputs"][0])
-    if l["type"] == "conv" and phase == "bwd":
+    if l["type"] == "conv":
         k, p, q = info["shape"][i]
-        return _ws(k, c * l["k"] * l["k"], n * p * q)
+        wbytes = 4 * k * c * l["k"] * l["k"]
+        # packed copy of W for the faster kernel: reduction channels a multiple of 16, tensors below 4 GiB
+        if phase == "fwd":
+            return wbytes if c % 16 == 0 and 4 * n * c * h * w < 0xfffffff0 else 0
+        need_dx = info["bufof"](l["inputs"][0]) >= 0
+        packed = wbytes if (need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0
+                            and 4 * n * k * p * q < 0xfffffff0) else 0
+        return max(_ws(k, c * l["k"] * l["k"], n * p * q), packed)
     if l["type"] == "fc":
         i_feat, o = c * h * w, l["out"]
         if phase == "fwd":

@@ -61,8 +61,10 @@ EXPORTS = {
     "vdnn_trace": ([_vp, C.c_char_p, _sz, C.POINTER(_sz)], _i),
     "vdnn_last_error": ([_vp], C.c_char_p),
     "vdnn_destroy": ([_vp], None),
-    "vdnn_op_conv_fwd": ([_vp] * 3 + [_i] * 10 + [_vp], _i),
-    "vdnn_op_conv_bwd_data": ([_vp] * 3 + [_i] * 9 + [_vp], _i),
+    "vdnn_op_conv_fwd_workspace": ([_i] * 9, _sz),
+    "vdnn_op_conv_bwd_data_workspace": ([_i] * 9, _sz),
+    "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
+    "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp], _i),
     "vdnn_op_conv_bwd_filter_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_filter": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp], _i),
     "vdnn_op_fc_workspace": ([_i] * 4, _sz),
@@ -226,18 +228,34 @@ def _ck(s, what):
 
 
 # ---- single-layer entry points on torch CUDA tensors (marshalling only) -------------------------
-def op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None):
+def _ws_args(ws):
+    return (ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0)
+
+
+def op_conv_fwd_workspace(x_shape, w_shape, stride, pad):
+    n, c, h, wd = x_shape
+    k, _, r, s = w_shape
+    return lib.vdnn_op_conv_fwd_workspace(n, c, h, wd, k, r, s, stride, pad)
+
+
+def op_conv_bwd_data_workspace(x_shape, w_shape, stride, pad):
+    n, c, h, wd = x_shape
+    k, _, r, s = w_shape
+    return lib.vdnn_op_conv_bwd_data_workspace(n, c, h, wd, k, r, s, stride, pad)
+
+
+def op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None, ws=None):
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
-    _ck(lib.vdnn_op_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), n, c, h, wd, k, r, s, stride, pad, int(relu),
-                             _stream_ptr(stream)), "conv_fwd")
+    _ck(lib.vdnn_op_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride, pad,
+                             int(relu), _stream_ptr(stream)), "conv_fwd")
 
 
-def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None):
+def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None):
     n, c, h, wd = dx.shape
     k, _, r, s = w.shape
-    _ck(lib.vdnn_op_conv_bwd_data(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), n, c, h, wd, k, r, s, stride, pad,
-                                  _stream_ptr(stream)), "conv_bwd_data")
+    _ck(lib.vdnn_op_conv_bwd_data(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride,
+                                  pad, _stream_ptr(stream)), "conv_bwd_data")
 
 
 def op_conv_bwd_filter_workspace(x_shape, w_shape, stride, pad):
@@ -256,10 +274,6 @@ def op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None):
 
 def op_fc_workspace(n, i, o, which):
     return lib.vdnn_op_fc_workspace(n, i, o, which)
-
-
-def _ws_args(ws):
-    return (ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0)
 
 
 def op_fc_fwd(x, w, y, ws, stream=None):

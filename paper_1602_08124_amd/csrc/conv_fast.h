@@ -1,0 +1,193 @@
+// Fast path of the implicit-GEMM convolution (forward and stride-1 backward-data) for channel
+// counts that are a multiple of 16.
+//
+// The reduction index is ordered (channel block of 16, filter tap, channel in block), so that one
+// K-step of 16 lies inside a single filter tap: the tap decomposition and the image-border test
+// happen once per K-step per thread instead of once per element, and the 9 taps of a 3x3 filter
+// re-read the same 16 channels back to back (L1 hits).  Loads are raw buffer loads: the per-thread
+// part of the address sits in a VGPR that never changes within a K-step, the per-element part in
+// an SGPR, and elements outside the image (padding) or outside the matrix are redirected to an
+// out-of-range offset for which the hardware returns 0 - no branches, no per-element vector ALU work.
+// The weight operand is read from a packed copy Wp[k_ordered][row] (row = output channel for
+// forward, input channel for backward-data) written by pack_weights_kernel just before, so
+// that its tile loads are contiguous along rows.
+#pragma once
+#include "gemm_tile.h"
+
+namespace vdnn {
+
+typedef int int32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+
+constexpr uint32_t kOobOffset = 0xfffffff0u;  // >= num_records of any buffer: the load returns 0
+
+struct ConvFastParams {
+    const float* src;   // X (forward) or dY (backward-data): [N][Cred][H][W]
+    const float* wp;    // packed weights [Cred*R*S][rows]
+    uint32_t src_bytes, wp_bytes;
+    int rows;           // output channels of this GEMM
+    int Cred, H, W;     // reduction channels and source image
+    int R, S, stride, pad;
+    int P, Q, M;        // output pixel grid, M = N*P*Q
+    FastDiv fd_pq, fd_q;
+    int tiles_m, tiles_n;
+    ConvOut out;
+};
+
+// Wp[((cb*RS + rs)*16 + ci)][row]:
+//   forward:       row = k, value W[k][cb*16+ci][rs]                       (W is [K][C][R][S])
+//   backward-data: row = c, value W[cb*16+ci][c][RS-1-rs]  (taps flipped, reduction over output channels)
+__global__ void pack_weights_kernel(const float* __restrict__ w, float* __restrict__ wp, int K, int C, int RS, int bwd) {
+    const int rows = bwd ? C : K, red = bwd ? K : C;
+    const size_t total = (size_t)K * C * RS;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int row = (int)(i % rows);
+        const int kred = (int)(i / rows);
+        const int ci = kred & 15, t = kred >> 4;
+        const int rs = t % RS, cb = t / RS;
+        const int ch = cb * 16 + ci;
+        (void)red;
+        wp[i] = bwd ? w[((size_t)ch * C + row) * RS + (RS - 1 - rs)] : w[((size_t)row * C + ch) * RS + rs];
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
+    constexpr int BK = 16;
+    constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
+    constexpr int PADA = 32, PADB = 32;
+    constexpr int LDA = BM + PADA, LDB = BN + PADB;
+    constexpr int EA = BM * BK / kThreads, EB = BN * BK / kThreads;
+    constexpr int KSA = kThreads / BM > 0 ? kThreads / BM : 1;  // k distance between a thread's A elements
+    constexpr int KSB = kThreads / BN > 0 ? kThreads / BN : 1;
+    static_assert(EA >= 1 && EB >= 1, "tile too small");
+    extern __shared__ float smem[];
+    float* As = smem;
+    float* Bs = smem + 2 * BK * LDA;
+
+    const int tid = threadIdx.x;
+    const int nb = p.tiles_m * p.tiles_n;
+    const int logical = xcd_remap(blockIdx.x, nb);
+    const int tile_n = logical / p.tiles_m, tile_m = logical - tile_n * p.tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+    const __amdgpu_buffer_rsrc_t rs_src = make_rsrc(p.src, p.src_bytes);
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.wp, p.wp_bytes);
+
+    // ---- A (weights): thread owns row a_row and k = a_k0 + j*KSA ----
+    const int a_row = tid % BM, a_k0 = tid / BM;
+    const uint32_t a_voff = (row0 + a_row < p.rows) ? (uint32_t)((a_k0 * p.rows + row0 + a_row) * 4) : kOobOffset;
+    // ---- B (gathered feature map): thread owns pixel b_row and k = b_k0 + j*KSB ----
+    const int b_row = tid % BN, b_k0 = tid / BN;
+    const int HW = p.H * p.W;
+    int ih0, iw0, pix_base;
+    bool vm;
+    {
+        const int m = col0 + b_row;
+        vm = m < p.M;
+        const uint32_t mm = vm ? (uint32_t)m : 0u;
+        const uint32_t n = fd_div(mm, p.fd_pq);
+        const uint32_t pq = mm - n * (uint32_t)(p.P * p.Q);
+        const uint32_t pp = fd_div(pq, p.fd_q);
+        const uint32_t qq = pq - pp * (uint32_t)p.Q;
+        ih0 = (int)pp * p.stride - p.pad;
+        iw0 = (int)qq * p.stride - p.pad;
+        pix_base = (int)n * p.Cred * HW + b_k0 * HW;  // + (ih*W + iw) of the tap
+    }
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int l32 = lane & 31, khalf = lane >> 5;
+    const int a_off = khalf * LDA + wm * (TM * 32) + l32;
+    const int b_off = khalf * LDB + wn * (TN * 32) + l32;
+    float* a_st = As + a_k0 * LDA + a_row;
+    float* b_st = Bs + b_k0 * LDB + b_row;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int RS = p.R * p.S;
+    const int nsteps = (p.Cred / 16) * RS;
+    // scalar state of the K-step being LOADED: channel block cb, tap (r, s)
+    int cb = 0, r = 0, s = 0;
+    float ra[EA], rb[EB];
+
+    auto load_step = [&](int step) {
+        const int ih = ih0 + r, iw = iw0 + s;
+        const bool ok = vm && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+        const uint32_t b_voff = ok ? (uint32_t)(pix_base + ih * p.W + iw) * 4u : kOobOffset;
+        const uint32_t a_s = (uint32_t)step * (uint32_t)(16 * p.rows * 4);
+        const uint32_t b_s = (uint32_t)cb * (uint32_t)(16 * HW * 4);
+#pragma unroll
+        for (int j = 0; j < EA; ++j) ra[j] = buf_load(rs_w, a_voff, a_s + (uint32_t)(j * KSA) * (uint32_t)(p.rows * 4));
+#pragma unroll
+        for (int j = 0; j < EB; ++j) rb[j] = buf_load(rs_src, b_voff, b_s + (uint32_t)(j * KSB) * (uint32_t)(HW * 4));
+        // advance (cb, r, s): taps fastest, then channel block
+        if (++s == p.S) {
+            s = 0;
+            if (++r == p.R) {
+                r = 0;
+                ++cb;
+            }
+        }
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < EA; ++j) a_st[buf * BK * LDA + j * KSA * LDA] = ra[j];
+#pragma unroll
+        for (int j = 0; j < EB; ++j) b_st[buf * BK * LDB + j * KSB * LDB] = rb[j];
+    };
+
+    load_step(0);
+    store_step(0);
+    __syncthreads();
+    for (int kt = 0; kt < nsteps; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nsteps;
+        if (more) load_step(kt + 1);
+        const float* at = As + cur * BK * LDA + a_off;
+        const float* bt = Bs + cur * BK * LDB + b_off;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = at[kk * LDA + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = bt[kk * LDB + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) store_step(cur ^ 1);
+        __syncthreads();
+    }
+
+    float* obase = p.out.base(0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const ConvOut::Col c = p.out.col(col0 + wn * (TN * 32) + j * 32 + l32);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rbase = row0 + wm * (TM * 32) + i * 32 + 4 * khalf;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) p.out.put(obase, rbase + 8 * (v / 4) + (v % 4), c, acc[i][j][v]);
+        }
+    }
+}
+
+}  // namespace vdnn

@@ -155,7 +155,12 @@ static size_t layer_workspace(const vdnn_net& n, int i, bool bwd) {
     const Layer& l = n.layers[i];
     int C, H, W;
     shape_of(n, l.inputs[0], &C, &H, &W);
-    if (l.type == VDNN_CONV && bwd) return conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+    if (l.type == VDNN_CONV && !bwd) return conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+    if (l.type == VDNN_CONV && bwd) {
+        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
+        return std::max(conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad),
+                        need_dx ? conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad) : (size_t)0);
+    }
     if (l.type == VDNN_FC) {
         const int I = C * H * W;
         if (!bwd) return fc_workspace(n.batch, I, l.out, 0);
@@ -548,8 +553,9 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
     const int N = n.batch;
     float* x = blk(n, o.in_blocks[0]);
     float* y = blk(n, o.out_block);
+    const size_t wsb0 = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
     switch (l.type) {
-        case VDNN_CONV: HIPCHK(conv_fwd(x, blk(n, l.w_block), y, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, 0, n.sc)); break;
+        case VDNN_CONV: HIPCHK(conv_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, 0, n.sc)); break;
         case VDNN_RELU: HIPCHK(relu_fwd(y, n.B(l.buf).count, n.sc)); break;
         case VDNN_MAXPOOL: HIPCHK(maxpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_AVGPOOL: HIPCHK(avgpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
@@ -587,7 +593,7 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
     switch (l.type) {
         case VDNN_CONV:
             HIPCHK(conv_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
-            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
             break;
         case VDNN_RELU: HIPCHK(relu_bwd(blk(n, o.out_block), dy, n.B(l.buf).count, n.sc)); break;
         case VDNN_MAXPOOL: if (dx) HIPCHK(maxpool_bwd(x, dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;

@@ -11,10 +11,13 @@ namespace vdnn {
 int gemm_splits(long long m, long long n, long long kred);
 size_t gemm_workspace_bytes(long long m, long long n, long long kred);
 
-hipError_t conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S, int stride,
-                    int pad, int relu, hipStream_t st);
-hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R, int S, int stride,
-                         int pad, hipStream_t st);
+// ws: room for a packed copy of W (conv_*_workspace bytes); with less the slower no-workspace kernel runs.
+size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R,
+                    int S, int stride, int pad, int relu, hipStream_t st);
+hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K,
+                         int R, int S, int stride, int pad, hipStream_t st);
 size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
                            int K, int R, int S, int stride, int pad, hipStream_t st);

@@ -16,16 +16,26 @@ static bool conv_ok(int N, int C, int H, int W, int K, int R, int S, int stride,
 
 extern "C" {
 
-vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
-                               int stride, int pad, int relu, void* stream) {
-    if (!x || !w || !y || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_fwd(x, w, y, N, C, H, W, K, R, S, stride, pad, relu, (hipStream_t)stream));
+size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (!conv_ok(N, C, H, W, K, R, S, stride, pad)) return 0;
+    return conv_fwd_workspace(N, C, H, W, K, R, S, stride, pad);
 }
 
-vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R,
-                                    int S, int stride, int pad, void* stream) {
+size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (!conv_ok(N, C, H, W, K, R, S, stride, pad)) return 0;
+    return conv_bwd_data_workspace(N, C, H, W, K, R, S, stride, pad);
+}
+
+vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
+                               int H, int W, int K, int R, int S, int stride, int pad, int relu, void* stream) {
+    if (!x || !w || !y || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_fwd(x, w, y, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu, (hipStream_t)stream));
+}
+
+vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
+                                    int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream) {
     if (!dy || !w || !dx || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_bwd_data(dy, w, dx, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
+    return st(conv_bwd_data(dy, w, dx, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
 }
 
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {

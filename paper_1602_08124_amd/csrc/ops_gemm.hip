@@ -2,6 +2,7 @@
 // (implicit GEMM on fp32 MFMA, Section 2.2's "memory-optimal" algorithm: X, Y, W only) and the
 // three FC products.  Reductions that would leave the chip idle are split across workgroups;
 // partial sums go to a caller-provided workspace and are added in a fixed order.
+#include "conv_fast.h"
 #include "gemm_tile.h"
 #include "ops.h"
 
@@ -97,7 +98,66 @@ static hipError_t conv_gemm(const GatherKParams& wa, const ConvGeom& g, const Co
 
 static bool fits_i32(long long v) { return v >= 0 && v < 0x7fffffffLL; }
 
-hipError_t conv_fwd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S, int stride,
+
+// ---- fast path: reduction channels a multiple of 16, tensors below 4 GiB (32-bit buffer offsets) ----
+static bool fast_ok(long long src_elems, long long w_elems, int cred, int R, int S) {
+    return cred % 16 == 0 && src_elems * 4 < 0xfffffff0LL && w_elems * 4 < 0x7fffffffLL && R == S;
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t conv_fast_cfg(ConvFastParams& p, hipStream_t st) {
+    auto kern = conv_fast_kernel<BM, BN, WM, WN>;
+    constexpr size_t smem = sizeof(float) * 2 * 16 * ((BM + 32) + (BN + 32));
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = cdiv(p.rows, BM);
+    p.tiles_n = cdiv(p.M, BN);
+    const long long nb = (long long)p.tiles_m * p.tiles_n;
+    if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
+    return hipGetLastError();
+}
+
+// src: the gathered tensor [N][cred][H][W]; w: original KCRS weights; ws: room for the packed copy.
+static hipError_t conv_fast(const float* src, const float* w, float* ws, const ConvOut& eo, int N, int cred, int H, int W, int K,
+                            int C, int R, int S, int stride, int pad, int P, int Q, int bwd, hipStream_t st) {
+    const size_t wcount = (size_t)K * C * R * S;
+    const int pblocks = (int)std::min<size_t>((wcount + 255) / 256, 4096);
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(pblocks), dim3(256), 0, st, w, ws, K, C, R * S, bwd);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    ConvFastParams p;
+    p.src = src; p.wp = ws;
+    p.src_bytes = (uint32_t)((size_t)N * cred * H * W * 4);
+    p.wp_bytes = (uint32_t)(wcount * 4);
+    p.rows = eo.rows;
+    p.Cred = cred; p.H = H; p.W = W;
+    p.R = R; p.S = S; p.stride = stride; p.pad = pad;
+    p.P = P; p.Q = Q; p.M = N * P * Q;
+    p.fd_pq = make_fastdiv((uint32_t)(P * Q));
+    p.fd_q = make_fastdiv((uint32_t)Q);
+    p.out = eo;
+    if (eo.rows <= 32) return conv_fast_cfg<32, 256, 1, 4>(p, st);
+    if (eo.rows <= 64) return conv_fast_cfg<64, 256, 1, 4>(p, st);
+    return conv_fast_cfg<128, 128, 2, 2>(p, st);
+}
+
+size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    (void)stride; (void)pad;
+    return fast_ok((long long)N * C * H * W, (long long)K * C * R * S, C, R, S) ? (size_t)K * C * R * S * 4 : 0;
+}
+
+size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (stride != 1 || pad > R - 1) return 0;
+    return fast_ok((long long)N * K * P * Q, (long long)K * C * R * S, K, R, S) ? (size_t)K * C * R * S * 4 : 0;
+}
+
+hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
                     int pad, int relu, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
@@ -108,6 +168,8 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, int N, int C, int 
     wa.fd_rs = make_fastdiv(1);
     ConvOut eo;
     eo.out = y; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
+    const size_t need = conv_fwd_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (need && ws && ws_bytes >= need) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
 }
 
@@ -138,7 +200,7 @@ __global__ void conv_bwd_data_direct_kernel(const float* __restrict__ dy, const 
     }
 }
 
-hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, int N, int C, int H, int W, int K, int R, int S, int stride,
+hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
                          int pad, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
@@ -158,6 +220,9 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, int N, int 
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
     eo.out = dx; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
+    const size_t need = conv_bwd_data_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (need && ws && ws_bytes >= need)
+        return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
     return conv_gemm(wa, g, eo, st);
 }
 

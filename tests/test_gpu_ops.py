@@ -34,33 +34,50 @@ CONV_SHAPES = [
     (5, 4, 3, 3, 4, 3, 1, 1),         # tiny image
     (2, 6, 12, 12, 10, 3, 1, 0),      # no padding
     (2, 6, 12, 12, 10, 3, 1, 2),      # padding larger than usual (output grows)
+    (2, 32, 20, 20, 136, 3, 1, 1),    # channels a multiple of 16: the packed-weight kernel, ragged row tile
+    (3, 64, 14, 14, 80, 5, 1, 2),     # 5x5, packed-weight kernel both ways (C and K multiples of 16)
+    (1, 48, 9, 9, 32, 1, 1, 0),       # 1x1
+    (2, 16, 30, 30, 64, 7, 2, 3),     # strided forward on the packed-weight kernel
+    (2, 16, 33, 31, 48, 3, 1, 1),     # 64-row tile, ragged pixels
+    (1, 16, 3, 3, 16, 3, 1, 1),       # tiny image: every tap but the centre hits padding somewhere
 ]
 
 
+def _ws(nbytes):
+    import torch
+    return torch.empty(max(nbytes, 4) // 4, device="cuda") if nbytes else None
+
+
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-@pytest.mark.parametrize("relu", [False, True])
-def test_conv_fwd(B, shape, relu):
+@pytest.mark.parametrize("relu,use_ws", [(False, False), (True, False), (False, True), (True, True)])
+def test_conv_fwd(B, shape, relu, use_ws):
+    """use_ws=False: the no-workspace algorithm; True: the packed-weight algorithm where it applies."""
     import torch
     n, c, h, w, k, r, st, pd = shape
     x, wt = _t((n, c, h, w), 1), _t((k, c, r, r), 2)
     ref = L.conv_fwd(x, wt, st, pd)
     if relu:
         ref = L.relu_fwd(ref)
+    nbytes = B.op_conv_fwd_workspace(x.shape, wt.shape, st, pd)
+    assert nbytes == (wt.size * 4 if c % 16 == 0 else 0)
     y = torch.full(ref.shape, float("nan"), device="cuda")
-    B.op_conv_fwd(dev(x), dev(wt), y, st, pd, relu)
+    B.op_conv_fwd(dev(x), dev(wt), y, st, pd, relu, ws=_ws(nbytes) if use_ws else None)
     assert rel_err(host(y), ref) < TOL
 
 
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-def test_conv_bwd_data(B, shape):
+@pytest.mark.parametrize("use_ws", [False, True])
+def test_conv_bwd_data(B, shape, use_ws):
     import torch
     n, c, h, w, k, r, st, pd = shape
     wt = _t((k, c, r, r), 3)
     p, q = L.out_dim(h, r, st, pd), L.out_dim(w, r, st, pd)
     dy = _t((n, k, p, q), 4)
     ref = L.conv_bwd_data(dy, wt, (n, c, h, w), st, pd)
+    nbytes = B.op_conv_bwd_data_workspace((n, c, h, w), wt.shape, st, pd)
+    assert nbytes == (wt.size * 4 if (k % 16 == 0 and st == 1 and pd <= r - 1) else 0)
     dx = torch.full((n, c, h, w), float("nan"), device="cuda")
-    B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd)
+    B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd, ws=_ws(nbytes) if use_ws else None)
     assert rel_err(host(dx), ref) < TOL
 
 
@@ -105,8 +122,9 @@ def test_conv_adjoint_identities_on_gpu(B):
     dw = torch.empty((k, c, r, r), device="cuda")
     nbytes = B.op_conv_bwd_filter_workspace((n, c, h, w), (k, c, r, r), st, pd)
     ws = torch.empty(max(nbytes, 4) // 4, device="cuda")
-    B.op_conv_fwd(x, wt, y, st, pd)
-    B.op_conv_bwd_data(dy, wt, dx, st, pd)
+    wsp = torch.empty(k * c * r * r, device="cuda")
+    B.op_conv_fwd(x, wt, y, st, pd, ws=wsp)
+    B.op_conv_bwd_data(dy, wt, dx, st, pd, ws=wsp)
     B.op_conv_bwd_filter(x, dy, dw, ws, st, pd)
     a = np.vdot(host(y).astype(np.float64), host(dy).astype(np.float64))
     b = np.vdot(host(x).astype(np.float64), host(dx).astype(np.float64))
@@ -228,8 +246,8 @@ def test_invalid_arguments_are_rejected(B):
     import torch
     x = torch.zeros(16, device="cuda")
     lib = B.lib
-    assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
     # workspace too small for a split reduction
     assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
