@@ -166,7 +166,13 @@ def workspace_bytes(net, info, i, phase):
         need_dx = info["bufof"](l["inputs"][0]) >= 0
         packed = wbytes if (need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0
                             and 4 * n * k * p * q < 0xfffffff0) else 0
-        return max(_ws(k, c * l["k"] * l["k"], n * p * q), packed)
+        # backward-filter: partial sums of the split reduction; with input channels a multiple of 64
+        # the faster kernel always stages dW through the workspace (at least one copy)
+        if c % 64 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
+            filt = gemm_splits(k, c * l["k"] * l["k"], n * p * q) * wbytes
+        else:
+            filt = _ws(k, c * l["k"] * l["k"], n * p * q)
+        return max(filt, packed)
     if l["type"] == "fc":
         i_feat, o = c * h * w, l["out"]
         if phase == "fwd":

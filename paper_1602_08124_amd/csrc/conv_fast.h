@@ -191,3 +191,165 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
 }
 
 }  // namespace vdnn
+
+namespace vdnn {
+
+// ---------------------------------------------------------------------------------------------
+// Backward-filter fast path: dW[k][(tap, c)] = sum over pixels m = (n, p, q) of
+// dY[n][k][p][q] * X[n][c][p*stride - pad + r][q*stride - pad + s].
+// Columns are ordered tap-major and a column tile never straddles two taps (C is a multiple of the
+// tile width), so the tap and the image-border test are the same for the whole workgroup and are
+// evaluated once per K-step per thread.  Lanes walk along pixels (contiguous in NCHW).
+// Partial sums of reduction split s go to ws[s][k][tap*C + c]; reduce_permute_kernel adds the splits
+// in order and writes dW in [K][C][R][S] order.
+// ---------------------------------------------------------------------------------------------
+struct BwdFilterFastParams {
+    const float* x;   // [N][C][H][W]
+    const float* dy;  // [N][K][P][Q]
+    float* ws;        // [splits][K][RS*C]
+    uint32_t x_bytes, dy_bytes;
+    int K, C, H, W, R, S, stride, pad, P, Q;
+    int M;            // N*P*Q (reduction length)
+    FastDiv fd_pq, fd_q;
+    int tiles_m, tiles_n, splits, ksplit;
+};
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastParams p) {
+    constexpr int BK = 32;
+    constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
+    constexpr int LDA = BM + 1, LDB = BN + 1;
+    constexpr int EA = BM * BK / kThreads, EB = BN * BK / kThreads;
+    constexpr int RSTEP = kThreads / BK;  // 8 rows between a thread's elements
+    extern __shared__ float smem[];
+    float* As = smem;
+    float* Bs = smem + 2 * BK * LDA;
+
+    const int tid = threadIdx.x;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int logical = xcd_remap(blockIdx.x, tiles * p.splits);
+    const int split = logical / tiles;
+    const int t2 = logical - split * tiles;
+    const int tile_n = t2 / p.tiles_m, tile_m = t2 - tile_n * p.tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const int tap = col0 / p.C, c0 = col0 - tap * p.C;  // uniform: the tile lies inside one tap
+    const int tr = tap / p.S, ts = tap - tr * p.S;
+    const int kbeg = split * p.ksplit;
+    const int kend = min(p.M, kbeg + p.ksplit);
+    const int nk = (kend - kbeg + BK - 1) / BK;
+
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rs_dy = make_rsrc(p.dy, p.dy_bytes);
+
+    const int kk = tid % BK, r_first = tid / BK;
+    const int PQ = p.P * p.Q, HW = p.H * p.W;
+    const uint32_t a_rowpart = (uint32_t)(row0 + r_first) * (uint32_t)PQ;          // elements
+    const uint32_t b_chpart = (uint32_t)(c0 + r_first) * (uint32_t)HW;
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int l32 = lane & 31, khalf = lane >> 5;
+    const int a_off = khalf * LDA + wm * (TM * 32) + l32;
+    const int b_off = khalf * LDB + wn * (TN * 32) + l32;
+    float* a_st = As + kk * LDA + r_first;
+    float* b_st = Bs + kk * LDB + r_first;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float ra[EA], rb[EB];
+    auto load_step = [&](int k0) {
+        const int m = k0 + kk;
+        const bool vm = m < kend;
+        const uint32_t mm = vm ? (uint32_t)m : 0u;
+        const uint32_t n = fd_div(mm, p.fd_pq);
+        const uint32_t pq = mm - n * (uint32_t)PQ;
+        const uint32_t pp = fd_div(pq, p.fd_q);
+        const uint32_t qq = pq - pp * (uint32_t)p.Q;
+        const int ih = (int)pp * p.stride - p.pad + tr, iw = (int)qq * p.stride - p.pad + ts;
+        const bool okb = vm && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+        // A: everything in the vector offset, so that rows past K (ragged last row tile) are either
+        // another image's data (never stored) or out of range (0).
+        const uint32_t a_base = vm ? (n * (uint32_t)p.K * (uint32_t)PQ + pq + a_rowpart) * 4u : kOobOffset;
+        const uint32_t b_voff = okb ? (n * (uint32_t)p.C * (uint32_t)HW + (uint32_t)(ih * p.W + iw) + b_chpart) * 4u : kOobOffset;
+#pragma unroll
+        for (int j = 0; j < EA; ++j) {
+            const uint32_t v = vm ? a_base + (uint32_t)(j * RSTEP) * (uint32_t)(PQ * 4) : kOobOffset;
+            ra[j] = buf_load(rs_dy, v, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < EB; ++j) rb[j] = buf_load(rs_x, b_voff, (uint32_t)(j * RSTEP) * (uint32_t)(HW * 4));
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < EA; ++j) a_st[buf * BK * LDA + j * RSTEP] = ra[j];
+#pragma unroll
+        for (int j = 0; j < EB; ++j) b_st[buf * BK * LDB + j * RSTEP] = rb[j];
+    };
+
+    if (nk > 0) {
+        load_step(kbeg);
+        store_step(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) load_step(kbeg + (kt + 1) * BK);
+        const float* at = As + cur * BK * LDA + a_off;
+        const float* bt = Bs + cur * BK * LDB + b_off;
+#pragma unroll
+        for (int k2 = 0; k2 < BK; k2 += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = at[k2 * LDA + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = bt[k2 * LDB + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) store_step(cur ^ 1);
+        __syncthreads();
+    }
+
+    const int CRS = p.C * p.R * p.S;
+    float* obase = p.ws + (size_t)split * p.K * CRS;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = col0 + wn * (TN * 32) + j * 32 + l32;  // < CRS: column tiles are never ragged here
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rbase = row0 + wm * (TM * 32) + i * 32 + 4 * khalf;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + 8 * (v / 4) + (v % 4);
+                if (row < p.K) obase[(size_t)row * CRS + col] = acc[i][j][v];
+            }
+        }
+    }
+}
+
+// dW[k][c][rs] = sum_s ws[s][k][rs*C + c], s ascending
+__global__ void reduce_permute_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int RS, int splits) {
+    const size_t total = (size_t)K * C * RS;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int rs = (int)(i % RS);
+        const int c = (int)((i / RS) % C);
+        const size_t k = i / ((size_t)RS * C);
+        const size_t src = k * (size_t)C * RS + (size_t)rs * C + c;
+        float acc = ws[src];
+        for (int s = 1; s < splits; ++s) acc += ws[(size_t)s * total + src];
+        dw[i] = acc;
+    }
+}
+
+}  // namespace vdnn

@@ -229,9 +229,37 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
 // -------------------------------------------------------------------------------------------
 // convolution backward-filter
 // -------------------------------------------------------------------------------------------
+// Fast path: input channels a multiple of 64 (a column tile of 64 or 128 never straddles two filter
+// taps), both tensors below 4 GiB.  It always goes through the workspace (the column order there is
+// tap-major and the final pass permutes it back), so the workspace is max(splits, 1) copies of dW.
+static bool bwdf_fast_ok(int N, int C, int H, int W, int K, int P, int Q) {
+    return C % 64 == 0 && (long long)N * C * H * W * 4 < 0xfffffff0LL && (long long)N * K * P * Q * 4 < 0xfffffff0LL;
+}
+
 size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (bwdf_fast_ok(N, C, H, W, K, P, Q))
+        return (size_t)gemm_splits(K, (long long)C * R * S, (long long)N * P * Q) * K * C * R * S * sizeof(float);
     return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
+    auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN>;
+    constexpr size_t smem = sizeof(float) * 2 * 32 * ((BM + 1) + (BN + 1));
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = cdiv(p.K, BM);
+    p.tiles_n = p.C * p.R * p.S / BN;
+    p.ksplit = cdiv(cdiv(p.M, p.splits), 32) * 32;
+    const long long nb = (long long)p.tiles_m * p.tiles_n * p.splits;
+    if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
+    return hipGetLastError();
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -248,6 +276,27 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     const int CRS = C * R * S;
     const int splits = gemm_splits(K, CRS, (long long)N * P * Q);
+    if (bwdf_fast_ok(N, C, H, W, K, P, Q)) {
+        const size_t need_fast = (size_t)splits * K * CRS * sizeof(float);
+        if (ws_bytes < need_fast || !ws) return hipErrorInvalidValue;
+        BwdFilterFastParams fp;
+        fp.x = x; fp.dy = dy; fp.ws = (float*)ws;
+        fp.x_bytes = (uint32_t)((size_t)N * C * H * W * 4);
+        fp.dy_bytes = (uint32_t)((size_t)N * K * P * Q * 4);
+        fp.K = K; fp.C = C; fp.H = H; fp.W = W; fp.R = R; fp.S = S; fp.stride = stride; fp.pad = pad; fp.P = P; fp.Q = Q;
+        fp.M = N * P * Q;
+        fp.fd_pq = make_fastdiv((uint32_t)(P * Q));
+        fp.fd_q = make_fastdiv((uint32_t)Q);
+        fp.splits = splits;
+        hipError_t e;
+        if (C % 128 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 128, 1, 4>(fp, st) : bwdf_fast_cfg<128, 128, 2, 2>(fp, st);
+        else e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1>(fp, st);
+        if (e != hipSuccess) return e;
+        const size_t total = (size_t)K * CRS;
+        const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+        hipLaunchKernelGGL(reduce_permute_kernel, dim3(blocks), dim3(256), 0, st, (const float*)ws, dw, K, C, R * S, splits);
+        return hipGetLastError();
+    }
     const size_t need = splits > 1 ? (size_t)splits * K * CRS * sizeof(float) : 0;
     if (ws_bytes < need || (need && !ws)) return hipErrorInvalidValue;
     ConvGeom g = make_geom(x, N, C, H, W, R, S, stride, pad, P, Q);

@@ -81,7 +81,21 @@ def test_conv_bwd_data(B, shape, use_ws):
     assert rel_err(host(dx), ref) < TOL
 
 
-@pytest.mark.parametrize("shape", CONV_SHAPES + [(8, 8, 64, 64, 16, 3, 1, 1), (4, 20, 40, 40, 72, 3, 1, 1)])
+BWDF_EXTRA = [
+    (8, 8, 64, 64, 16, 3, 1, 1),      # long reduction, split 16 ways
+    (4, 20, 40, 40, 72, 3, 1, 1),
+    # input channels a multiple of 64: the tap-uniform kernel, all four tile shapes
+    (2, 128, 10, 10, 72, 3, 1, 1),    # 128x128 tiles, ragged rows
+    (2, 128, 9, 9, 48, 3, 1, 1),      # 64x128
+    (2, 64, 12, 12, 32, 3, 1, 1),     # 64x64
+    (2, 64, 14, 14, 80, 3, 1, 1),     # 128x64, ragged rows
+    (1, 192, 8, 8, 130, 1, 1, 0),     # 1x1, 128x64, two row tiles
+    (2, 64, 15, 15, 64, 3, 2, 1),     # strided
+    (6, 64, 40, 40, 64, 3, 1, 1),     # reduction 9600: split, ragged last chunk
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES + BWDF_EXTRA)
 def test_conv_bwd_filter(B, shape):
     import torch
     n, c, h, w, k, r, st, pd = shape
