@@ -155,9 +155,12 @@ size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R,
 /* Y = conv(X, W); relu != 0 applies max(.,0) to the result in the same kernel. */
 vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
                                int H, int W, int K, int R, int S, int stride, int pad, int relu, void* stream);
-/* dX = sum over the forward terms that touched it (Eq. chain_rule). */
+/* dX = sum over the forward terms that touched it (Eq. chain_rule).  relu_mask (may be NULL): a tensor of
+ * dX's shape, the output of an in-place ReLU that produced X; dX is zeroed where it is not positive,
+ * which is that ReLU's backward computation folded into this kernel's store. */
 vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
-                                    int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
+                                    int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
+                                    void* stream);
 /* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
  * order (deterministic, no atomics).  workspace may be NULL iff the required size is 0. */
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
@@ -176,9 +179,10 @@ vdnn_status_t vdnn_op_fc_bwd_filter(const float* x, const float* dy, float* dw, 
 vdnn_status_t vdnn_op_relu_fwd(float* y, size_t count, void* stream);                  /* in place */
 vdnn_status_t vdnn_op_relu_bwd(const float* y, float* dy, size_t count, void* stream); /* in place on dy, mask y > 0 */
 vdnn_status_t vdnn_op_maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
-/* first maximum in row-major window order takes the gradient; overlapping windows add up */
+/* first maximum in row-major window order takes the gradient; overlapping windows add up.
+ * relu_mask != 0: X is the output of an in-place ReLU whose backward is folded in (dX = 0 where X <= 0). */
 vdnn_status_t vdnn_op_maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride,
-                                  int pad, void* stream);
+                                  int pad, int relu_mask, void* stream);
 vdnn_status_t vdnn_op_avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
 vdnn_status_t vdnn_op_avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
 /* loss: (device) one float, mean over the batch.  dz = (softmax(z) - onehot)/N. */

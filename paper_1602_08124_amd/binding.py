@@ -64,7 +64,7 @@ EXPORTS = {
     "vdnn_op_conv_fwd_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_data_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
-    "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp], _i),
+    "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp, _vp], _i),
     "vdnn_op_conv_bwd_filter_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_filter": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp], _i),
     "vdnn_op_fc_workspace": ([_i] * 4, _sz),
@@ -74,7 +74,7 @@ EXPORTS = {
     "vdnn_op_relu_fwd": ([_vp, _sz, _vp], _i),
     "vdnn_op_relu_bwd": ([_vp, _vp, _sz, _vp], _i),
     "vdnn_op_maxpool_fwd": ([_vp] * 2 + [_i] * 7 + [_vp], _i),
-    "vdnn_op_maxpool_bwd": ([_vp] * 3 + [_i] * 7 + [_vp], _i),
+    "vdnn_op_maxpool_bwd": ([_vp] * 3 + [_i] * 8 + [_vp], _i),
     "vdnn_op_avgpool_fwd": ([_vp] * 2 + [_i] * 7 + [_vp], _i),
     "vdnn_op_avgpool_bwd": ([_vp] * 2 + [_i] * 7 + [_vp], _i),
     "vdnn_op_softmax_ce_fwd": ([_vp] * 3 + [_i] * 2 + [_vp], _i),
@@ -251,11 +251,12 @@ def op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None, ws=None):
                              int(relu), _stream_ptr(stream)), "conv_fwd")
 
 
-def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None):
+def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None, relu_mask=None):
     n, c, h, wd = dx.shape
     k, _, r, s = w.shape
     _ck(lib.vdnn_op_conv_bwd_data(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride,
-                                  pad, _stream_ptr(stream)), "conv_bwd_data")
+                                  pad, relu_mask.data_ptr() if relu_mask is not None else None, _stream_ptr(stream)),
+        "conv_bwd_data")
 
 
 def op_conv_bwd_filter_workspace(x_shape, w_shape, stride, pad):
@@ -303,8 +304,9 @@ def op_maxpool_fwd(x, y, k, stride, pad, stream=None):
     _ck(lib.vdnn_op_maxpool_fwd(x.data_ptr(), y.data_ptr(), *x.shape, k, stride, pad, _stream_ptr(stream)), "maxpool_fwd")
 
 
-def op_maxpool_bwd(x, dy, dx, k, stride, pad, stream=None):
-    _ck(lib.vdnn_op_maxpool_bwd(x.data_ptr(), dy.data_ptr(), dx.data_ptr(), *x.shape, k, stride, pad, _stream_ptr(stream)), "maxpool_bwd")
+def op_maxpool_bwd(x, dy, dx, k, stride, pad, stream=None, relu_mask=False):
+    _ck(lib.vdnn_op_maxpool_bwd(x.data_ptr(), dy.data_ptr(), dx.data_ptr(), *x.shape, k, stride, pad, int(relu_mask),
+                                _stream_ptr(stream)), "maxpool_bwd")
 
 
 def op_avgpool_fwd(x, y, k, stride, pad, stream=None):

@@ -312,9 +312,12 @@ struct RowMajorOut {
     __device__ float* base(int split) const { return out + (size_t)split * slice; }
 };
 
-// NCHW feature map: row = channel k, col = pixel m = (n, pq) -> Y[(n*K + k)*PQ + pq]; optional ReLU.
+// NCHW feature map: row = channel k, col = pixel m = (n, pq) -> Y[(n*K + k)*PQ + pq]; optional ReLU
+// on the value (forward), or optional zeroing where a same-shaped tensor is not positive (backward-data
+// with the backward of the preceding in-place ReLU folded in: mask = that ReLU's output).
 struct ConvOut {
     float* out;
+    const float* mask;
     int rows;  // K
     int M, PQ;
     int relu;
@@ -332,7 +335,11 @@ struct ConvOut {
     }
     __device__ void put(float* base, int row, const Col& c, float v) const {
         if (relu) v = v > 0.f ? v : 0.f;
-        if (c.ok && row < rows) base[c.off + (size_t)row * PQ] = v;
+        if (c.ok && row < rows) {
+            const size_t idx = c.off + (size_t)row * PQ;
+            if (mask && !(mask[idx] > 0.f)) v = 0.f;
+            base[idx] = v;
+        }
     }
     __device__ float* base(int) const { return out; }
 };

@@ -143,9 +143,34 @@ static vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::str
         for (int r : B.inplace) B.bwd_users.push_back(r);
         std::sort(B.bwd_users.begin(), B.bwd_users.end());
     }
+    // ReLU folding.  Forward: a CONV whose output holds exactly one in-place ReLU applies it in its
+    // epilogue.  Backward: when a feature map holds exactly one in-place ReLU and has a single reader
+    // that is a CONV or max-POOL layer, that reader masks its dX store with (X > 0), which is the
+    // ReLU's backward computation.  Values are identical to running the ReLU kernels separately.
+    for (int b = 0; b < L; ++b) {
+        Buffer& B = n.B(b);
+        if (!B.count || B.inplace.size() != 1) continue;
+        const int r = B.inplace[0];
+        if (n.layers[b].type == VDNN_CONV) { n.layers[b].relu_after = r; n.layers[r].fwd_folded_into = b; }
+        if (B.readers.size() == 1) {
+            const int m = B.readers[0];
+            if (n.layers[m].type == VDNN_CONV || n.layers[m].type == VDNN_MAXPOOL) { n.layers[m].relu_before = r; n.layers[r].bwd_folded_into = m; }
+        }
+    }
     n.cap_out.assign(L, nullptr);
     n.cap_grad.assign(L, nullptr);
     return VDNN_OK;
+}
+
+// A test hook on the tensors in between switches the folding off for that pair, so that the hook
+// still sees the unfused intermediate value.
+static bool fold_fwd(const vdnn_net& n, int conv) {
+    const int r = n.layers[conv].relu_after;
+    return r >= 0 && !n.cap_out[conv];
+}
+static bool fold_bwd(const vdnn_net& n, int reader) {
+    const int r = n.layers[reader].relu_before;
+    return r >= 0 && !n.cap_grad[r];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -555,8 +580,14 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
     float* y = blk(n, o.out_block);
     const size_t wsb0 = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
     switch (l.type) {
-        case VDNN_CONV: HIPCHK(conv_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, 0, n.sc)); break;
-        case VDNN_RELU: HIPCHK(relu_fwd(y, n.B(l.buf).count, n.sc)); break;
+        case VDNN_CONV:
+            HIPCHK(conv_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
+                            fold_fwd(n, o.layer) ? 1 : 0, n.sc));
+            break;
+        case VDNN_RELU:
+            if (l.fwd_folded_into >= 0 && fold_fwd(n, l.fwd_folded_into)) break;  // done in the conv's epilogue
+            HIPCHK(relu_fwd(y, n.B(l.buf).count, n.sc));
+            break;
         case VDNN_MAXPOOL: HIPCHK(maxpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_AVGPOOL: HIPCHK(avgpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_FC: {
@@ -593,10 +624,14 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
     switch (l.type) {
         case VDNN_CONV:
             HIPCHK(conv_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
-            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
+                                         fold_bwd(n, o.layer) ? x : nullptr, n.sc));
             break;
-        case VDNN_RELU: HIPCHK(relu_bwd(blk(n, o.out_block), dy, n.B(l.buf).count, n.sc)); break;
-        case VDNN_MAXPOOL: if (dx) HIPCHK(maxpool_bwd(x, dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
+        case VDNN_RELU:
+            if (l.bwd_folded_into >= 0 && fold_bwd(n, l.bwd_folded_into)) break;  // done in the reader's dX store
+            HIPCHK(relu_bwd(blk(n, o.out_block), dy, n.B(l.buf).count, n.sc));
+            break;
+        case VDNN_MAXPOOL: if (dx) HIPCHK(maxpool_bwd(x, dy, dx, N, C, H, W, l.k, l.stride, l.pad, fold_bwd(n, o.layer) ? 1 : 0, n.sc)); break;
         case VDNN_AVGPOOL: if (dx) HIPCHK(avgpool_bwd(dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_FC:
             HIPCHK(fc_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));

@@ -27,6 +27,10 @@ struct Layer {
     int buf = 0;              // feature-map buffer holding the output (-1 = network input)
     size_t wcount = 0;        // weight elements
     int w_block = -1, dw_block = -1;
+    // Kernel fusion of in-place ReLU layers (same values, fewer passes over HBM):
+    int relu_after = -1;      // CONV: the ReLU living in its output whose forward runs in the conv's epilogue
+    int relu_before = -1;     // CONV / MAXPOOL: the ReLU living in its input whose backward runs in this layer's dX store
+    int fwd_folded_into = -1, bwd_folded_into = -1;  // RELU: the layer that does its work (or -1)
 };
 
 // A feature-map buffer: produced by one non-in-place layer (or the network input), possibly

@@ -16,8 +16,9 @@ size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int s
 size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R,
                     int S, int stride, int pad, int relu, hipStream_t st);
+// relu_mask (may be null): tensor of dX's shape; dX is zeroed where it is not positive.
 hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K,
-                         int R, int S, int stride, int pad, hipStream_t st);
+                         int R, int S, int stride, int pad, const float* relu_mask, hipStream_t st);
 size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
                            int K, int R, int S, int stride, int pad, hipStream_t st);
@@ -30,7 +31,8 @@ hipError_t fc_bwd_filter(const float* x, const float* dy, float* dw, void* ws, s
 hipError_t relu_fwd(float* y, size_t count, hipStream_t st);
 hipError_t relu_bwd(const float* y, float* dy, size_t count, hipStream_t st);
 hipError_t maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
-hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
+hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, int relu_mask,
+                       hipStream_t st);
 hipError_t avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
 hipError_t avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st);
 hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, hipStream_t st);

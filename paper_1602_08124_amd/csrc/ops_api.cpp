@@ -33,9 +33,10 @@ vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* w
 }
 
 vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
-                                    int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream) {
+                                    int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
+                                    void* stream) {
     if (!dy || !w || !dx || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_bwd_data(dy, w, dx, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
+    return st(conv_bwd_data(dy, w, dx, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu_mask, (hipStream_t)stream));
 }
 
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
@@ -92,9 +93,9 @@ vdnn_status_t vdnn_op_maxpool_fwd(const float* x, float* y, int N, int C, int H,
 }
 
 vdnn_status_t vdnn_op_maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride,
-                                  int pad, void* stream) {
+                                  int pad, int relu_mask, void* stream) {
     if (!dy || !pool_ok(x, dx, N, C, H, W, k, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(maxpool_bwd(x, dy, dx, N, C, H, W, k, stride, pad, (hipStream_t)stream));
+    return st(maxpool_bwd(x, dy, dx, N, C, H, W, k, stride, pad, relu_mask, (hipStream_t)stream));
 }
 
 vdnn_status_t vdnn_op_avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream) {

@@ -56,18 +56,29 @@ hipError_t relu_bwd(const float* y, float* dy, size_t count, hipStream_t st) {
 }
 
 // ---- pooling ---------------------------------------------------------------------------------
+// 32-bit index arithmetic with precomputed reciprocals (tensors have fewer than 2^31 elements).
+struct FD { uint32_t m, s; };
+static FD make_fd(uint32_t d) {
+    FD f; uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    f.s = s;
+    f.m = (uint32_t)((((1ull << 32) * ((1ull << s) - d)) / d) + 1);
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FD f) { return (__umulhi(n, f.m) + n) >> f.s; }
+
 __global__ void maxpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H, int W, int P, int Q, int k, int stride,
-                                   int pad, size_t total) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int q = (int)(i % Q), p = (int)((i / Q) % P);
-        const size_t nc = i / ((size_t)P * Q);
-        const float* xp = x + nc * (size_t)H * W;
+                                   int pad, uint32_t total, FD fq, FD fp) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fq), q = i - t * Q;
+        const uint32_t nc = fdiv(t, fp), p = t - nc * P;
+        const float* xp = x + (size_t)nc * H * W;
         float best = -INFINITY;
         for (int r = 0; r < k; ++r) {
-            const int h = p * stride + r - pad;
+            const int h = (int)p * stride + r - pad;
             if ((unsigned)h >= (unsigned)H) continue;
             for (int s = 0; s < k; ++s) {
-                const int w = q * stride + s - pad;
+                const int w = (int)q * stride + s - pad;
                 if ((unsigned)w >= (unsigned)W) continue;
                 const float v = xp[h * W + w];
                 if (v > best) best = v;
@@ -79,14 +90,17 @@ __global__ void maxpool_fwd_kernel(const float* __restrict__ x, float* __restric
 
 // One thread per dX element: visit every window that contains it, recompute that window's first
 // maximum (row-major scan, strict >) and take the window's dY if this element is it.  Windows are
-// visited in ascending (p, q), so overlapping windows add up in a fixed order.
+// visited in ascending (p, q), so overlapping windows add up in a fixed order.  relu_mask: the
+// pooled tensor is the output of an in-place ReLU whose backward is folded in (dX = 0 where X <= 0).
 __global__ void maxpool_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, int H, int W,
-                                   int P, int Q, int k, int stride, int pad, size_t total) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int w = (int)(i % W), h = (int)((i / W) % H);
-        const size_t nc = i / ((size_t)H * W);
-        const float* xp = x + nc * (size_t)H * W;
-        const float* gp = dy + nc * (size_t)P * Q;
+                                   int P, int Q, int k, int stride, int pad, uint32_t total, FD fw, FD fh, int relu_mask) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fw);
+        const int w = (int)(i - t * W);
+        const uint32_t nc = fdiv(t, fh);
+        const int h = (int)(t - nc * H);
+        const float* xp = x + (size_t)nc * H * W;
+        const float* gp = dy + (size_t)nc * P * Q;
         const int p_lo = max(0, (h + pad - k + stride) / stride), p_hi = min(P - 1, (h + pad) / stride);
         const int q_lo = max(0, (w + pad - k + stride) / stride), q_hi = min(Q - 1, (w + pad) / stride);
         float acc = 0.f;
@@ -106,23 +120,67 @@ __global__ void maxpool_bwd_kernel(const float* __restrict__ x, const float* __r
                 }
                 if (bh == h && bw == w) acc += gp[p * Q + q];
             }
+        if (relu_mask && !(xp[h * W + w] > 0.f)) acc = 0.f;
         dx[i] = acc;
     }
 }
 
+// 2x2 stride 2, no padding, H even, W a multiple of 4: one thread per two adjacent windows, float4
+// rows in, float2 out (forward) / float4 rows out (backward).  Same tie rule as the general kernel.
+__global__ void maxpool2x2_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int W, int Q2, uint32_t total, FD fq2) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t row = fdiv(i, fq2), j = i - row * Q2;  // row = (nc*P + p), j = pair index in the row
+        const float4 a = *reinterpret_cast<const float4*>(x + (size_t)row * 2 * W + 4 * j);
+        const float4 b = *reinterpret_cast<const float4*>(x + (size_t)row * 2 * W + W + 4 * j);
+        float m0 = a.x; if (a.y > m0) m0 = a.y; if (b.x > m0) m0 = b.x; if (b.y > m0) m0 = b.y;
+        float m1 = a.z; if (a.w > m1) m1 = a.w; if (b.z > m1) m1 = b.z; if (b.w > m1) m1 = b.w;
+        *reinterpret_cast<float2*>(y + (size_t)row * (2 * Q2) + 2 * j) = make_float2(m0, m1);
+    }
+}
+
+__global__ void maxpool2x2_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, int W, int Q2,
+                                      uint32_t total, FD fq2, int relu_mask) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t row = fdiv(i, fq2), j = i - row * Q2;
+        const size_t o0 = (size_t)row * 2 * W + 4 * j, o1 = o0 + W;
+        const float4 a = *reinterpret_cast<const float4*>(x + o0);
+        const float4 b = *reinterpret_cast<const float4*>(x + o1);
+        const float2 g = *reinterpret_cast<const float2*>(dy + (size_t)row * (2 * Q2) + 2 * j);
+        float4 da = make_float4(0.f, 0.f, 0.f, 0.f), db = da;
+        {   // window 0: a.x a.y / b.x b.y, first maximum in that order
+            float m = a.x; int w = 0;
+            if (a.y > m) { m = a.y; w = 1; }
+            if (b.x > m) { m = b.x; w = 2; }
+            if (b.y > m) { m = b.y; w = 3; }
+            const float v = (relu_mask && !(m > 0.f)) ? 0.f : g.x;
+            if (w == 0) da.x = v; else if (w == 1) da.y = v; else if (w == 2) db.x = v; else db.y = v;
+        }
+        {
+            float m = a.z; int w = 0;
+            if (a.w > m) { m = a.w; w = 1; }
+            if (b.z > m) { m = b.z; w = 2; }
+            if (b.w > m) { m = b.w; w = 3; }
+            const float v = (relu_mask && !(m > 0.f)) ? 0.f : g.y;
+            if (w == 0) da.z = v; else if (w == 1) da.w = v; else if (w == 2) db.z = v; else db.w = v;
+        }
+        *reinterpret_cast<float4*>(dx + o0) = da;
+        *reinterpret_cast<float4*>(dx + o1) = db;
+    }
+}
+
 __global__ void avgpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H, int W, int P, int Q, int k, int stride,
-                                   int pad, size_t total) {
+                                   int pad, uint32_t total, FD fq, FD fp) {
     const float inv = 1.f / (float)(k * k);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int q = (int)(i % Q), p = (int)((i / Q) % P);
-        const size_t nc = i / ((size_t)P * Q);
-        const float* xp = x + nc * (size_t)H * W;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fq), q = i - t * Q;
+        const uint32_t nc = fdiv(t, fp), p = t - nc * P;
+        const float* xp = x + (size_t)nc * H * W;
         float acc = 0.f;
         for (int r = 0; r < k; ++r) {
-            const int h = p * stride + r - pad;
+            const int h = (int)p * stride + r - pad;
             if ((unsigned)h >= (unsigned)H) continue;
             for (int s = 0; s < k; ++s) {
-                const int w = q * stride + s - pad;
+                const int w = (int)q * stride + s - pad;
                 if ((unsigned)w >= (unsigned)W) continue;
                 acc += xp[h * W + w];
             }
@@ -132,12 +190,14 @@ __global__ void avgpool_fwd_kernel(const float* __restrict__ x, float* __restric
 }
 
 __global__ void avgpool_bwd_kernel(const float* __restrict__ dy, float* __restrict__ dx, int H, int W, int P, int Q, int k, int stride,
-                                   int pad, size_t total) {
+                                   int pad, uint32_t total, FD fw, FD fh) {
     const float inv = 1.f / (float)(k * k);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int w = (int)(i % W), h = (int)((i / W) % H);
-        const size_t nc = i / ((size_t)H * W);
-        const float* gp = dy + nc * (size_t)P * Q;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fw);
+        const int w = (int)(i - t * W);
+        const uint32_t nc = fdiv(t, fh);
+        const int h = (int)(t - nc * H);
+        const float* gp = dy + (size_t)nc * P * Q;
         const int p_lo = max(0, (h + pad - k + stride) / stride), p_hi = min(P - 1, (h + pad) / stride);
         const int q_lo = max(0, (w + pad - k + stride) / stride), q_hi = min(Q - 1, (w + pad) / stride);
         float acc = 0.f;
@@ -154,19 +214,36 @@ static bool pool_dims(int H, int W, int k, int stride, int pad, int* P, int* Q) 
     return *P > 0 && *Q > 0;
 }
 
+static bool small_enough(size_t a, size_t b) { return a < 0x7fffffffULL && b < 0x7fffffffULL; }
+
 hipError_t maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st) {
     int P, Q;
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * P * Q;
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad, total);
+    if (!small_enough(total, (size_t)N * C * H * W)) return hipErrorInvalidValue;
+    if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
+        const uint32_t t2 = (uint32_t)(total / 2);
+        hipLaunchKernelGGL(maxpool2x2_fwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, y, W, Q / 2, t2, make_fd(Q / 2));
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
+                       (uint32_t)total, make_fd(Q), make_fd(P));
     return hipGetLastError();
 }
 
-hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, hipStream_t st) {
+hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad,
+                       int relu_mask, hipStream_t st) {
     int P, Q;
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * H * W;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad, total);
+    if (!small_enough(total, total)) return hipErrorInvalidValue;
+    if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
+        const uint32_t t2 = (uint32_t)((size_t)N * C * P * Q / 2);
+        hipLaunchKernelGGL(maxpool2x2_bwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, dy, dx, W, Q / 2, t2, make_fd(Q / 2), relu_mask);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad,
+                       (uint32_t)total, make_fd(W), make_fd(H), relu_mask);
     return hipGetLastError();
 }
 
@@ -174,7 +251,9 @@ hipError_t avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int
     int P, Q;
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * P * Q;
-    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad, total);
+    if (!small_enough(total, (size_t)N * C * H * W)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
+                       (uint32_t)total, make_fd(Q), make_fd(P));
     return hipGetLastError();
 }
 
@@ -182,7 +261,9 @@ hipError_t avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, i
     int P, Q;
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * H * W;
-    hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, dx, H, W, P, Q, k, stride, pad, total);
+    if (!small_enough(total, total)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, dx, H, W, P, Q, k, stride, pad,
+                       (uint32_t)total, make_fd(W), make_fd(H));
     return hipGetLastError();
 }
 

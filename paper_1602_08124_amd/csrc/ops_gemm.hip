@@ -167,7 +167,7 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
     wa.base = w; wa.rows = K; wa.rstride = C * R * S; wa.kstride = 1; wa.rs = 1; wa.flip = 0;
     wa.fd_rs = make_fastdiv(1);
     ConvOut eo;
-    eo.out = y; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
+    eo.out = y; eo.mask = nullptr; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
     const size_t need = conv_fwd_workspace(N, C, H, W, K, R, S, stride, pad);
     if (need && ws && ws_bytes >= need) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
@@ -177,7 +177,8 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
 // term that touched it.  Only first layers are strided in the paper's networks and those need no
 // dX, so this path is for completeness, not speed.
 __global__ void conv_bwd_data_direct_kernel(const float* __restrict__ dy, const float* __restrict__ w, float* __restrict__ dx,
-                                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int P, int Q) {
+                                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int P, int Q,
+                                            const float* __restrict__ relu_mask) {
     const size_t total = (size_t)N * C * H * W;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int wi = (int)(i % W), hi = (int)((i / W) % H), c = (int)((i / ((size_t)W * H)) % C), n = (int)(i / ((size_t)W * H * C));
@@ -196,19 +197,20 @@ __global__ void conv_bwd_data_direct_kernel(const float* __restrict__ dy, const 
                     acc += dy[(((size_t)n * K + k) * P + p) * Q + q] * w[(((size_t)k * C + c) * R + r) * S + s];
                 }
             }
+        if (relu_mask && !(relu_mask[i] > 0.f)) acc = 0.f;
         dx[i] = acc;
     }
 }
 
 hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
-                         int pad, hipStream_t st) {
+                         int pad, const float* relu_mask, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     if (stride != 1 || pad > R - 1 || pad > S - 1) {
         const size_t total = (size_t)N * C * H * W;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 65535 * 4);
-        hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3(blocks), dim3(256), 0, st, dy, w, dx, N, C, H, W, K, R, S, stride, pad, P, Q);
+        hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3(blocks), dim3(256), 0, st, dy, w, dx, N, C, H, W, K, R, S, stride, pad, P, Q, relu_mask);
         return hipGetLastError();
     }
     // dX[n][c][h][w] = sum_{k,r',s'} dY[n][k][h - (R-1-pad) + r'][w - (S-1-pad) + s'] * W[k][c][R-1-r'][S-1-s']:
@@ -219,7 +221,7 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     wa.base = w; wa.rows = C; wa.rstride = R * S; wa.kstride = C * R * S; wa.rs = R * S; wa.flip = 1;
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
-    eo.out = dx; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
+    eo.out = dx; eo.mask = relu_mask; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
     const size_t need = conv_bwd_data_workspace(N, C, H, W, K, R, S, stride, pad);
     if (need && ws && ws_bytes >= need)
         return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);

@@ -78,6 +78,12 @@ def test_step_matches_oracle(B, name, mk):
         assert rel_err(got["outs"][i], ref["outs"][i]) < TOL, (i, l["type"])
     for i in weights:
         assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+    # without the output hooks the ReLU forward passes run inside the convolution epilogues
+    # (the hooks switch that folding off): same values, checked through the loss and every dW
+    fused = run_gpu(B, net, x, labels, weights, "none", capture=False)
+    assert fused["loss"] == got["loss"]
+    for i in weights:
+        assert np.array_equal(fused["dw"][i], got["dw"][i]), i
 
 
 @pytest.mark.parametrize("name,mk", NETS)
@@ -85,7 +91,12 @@ def test_offload_is_bit_identical(B, name, mk):
     net = mk()
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 18)
     base = run_gpu(B, net, x, labels, weights, "none")
+    base_nohook = run_gpu(B, net, x, labels, weights, "none", capture=False)
     for pol in ("all", "conv", "dyn"):
+        nohook = run_gpu(B, net, x, labels, weights, pol, capture=False)
+        assert nohook["loss"] == base_nohook["loss"]
+        for i in weights:
+            assert np.array_equal(nohook["dw"][i], base_nohook["dw"][i]), (pol, i)
         got = run_gpu(B, net, x, labels, weights, pol)
         assert got["loss"] == base["loss"]
         for i in weights:

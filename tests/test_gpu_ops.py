@@ -79,6 +79,11 @@ def test_conv_bwd_data(B, shape, use_ws):
     dx = torch.full((n, c, h, w), float("nan"), device="cuda")
     B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd, ws=_ws(nbytes) if use_ws else None)
     assert rel_err(host(dx), ref) < TOL
+    # with the backward of a preceding in-place ReLU folded into the store
+    xr = np.maximum(_t((n, c, h, w), 44), 0)
+    dx.fill_(float("nan"))
+    B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd, ws=_ws(nbytes) if use_ws else None, relu_mask=dev(xr))
+    assert rel_err(host(dx), L.relu_bwd(xr, ref)) < TOL
 
 
 BWDF_EXTRA = [
@@ -180,7 +185,7 @@ def test_relu(B, count):
     assert np.array_equal(host(dy), L.relu_bwd(ref, g).astype(np.float32))
 
 
-POOLS = [(2, 3, 8, 8, 2, 2, 0), (2, 5, 13, 13, 3, 2, 0), (3, 4, 14, 14, 3, 2, 1), (2, 6, 7, 9, 3, 1, 1), (1, 2, 7, 7, 7, 1, 0),
+POOLS = [(2, 3, 8, 8, 2, 2, 0), (3, 5, 12, 20, 2, 2, 0), (2, 2, 6, 10, 2, 2, 0), (1, 2, 7, 8, 2, 2, 0), (2, 5, 13, 13, 3, 2, 0), (3, 4, 14, 14, 3, 2, 1), (2, 6, 7, 9, 3, 1, 1), (1, 2, 7, 7, 7, 1, 0),
          (2, 3, 55, 55, 3, 2, 0), (1, 3, 6, 6, 2, 2, 0)]
 
 
@@ -198,6 +203,9 @@ def test_maxpool(B, cfg):
     dx = torch.full(x.shape, float("nan"), device="cuda")
     B.op_maxpool_bwd(dev(x), dev(dy), dx, k, st, pd)
     assert rel_err(host(dx), L.maxpool_bwd(x, dy, k, st, pd)) < 1e-6
+    dx.fill_(float("nan"))
+    B.op_maxpool_bwd(dev(x), dev(dy), dx, k, st, pd, relu_mask=True)
+    assert rel_err(host(dx), L.relu_bwd(x, L.maxpool_bwd(x, dy, k, st, pd))) < 1e-6
 
 
 @pytest.mark.parametrize("cfg", POOLS)
