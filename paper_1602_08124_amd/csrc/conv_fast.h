@@ -160,18 +160,28 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
         if (more) load_step(kt + 1);
         const float* at = As + cur * BK * LDA + a_off;
         const float* bt = Bs + cur * BK * LDB + b_off;
+        // operand fragments are read from LDS one k-pair ahead of the MFMAs that consume them
+        float a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][i] = at[i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][j] = bt[j * 32];
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float a[TM], b[TN];
+            const int c = (kk >> 1) & 1, nx = c ^ 1;
+            if (kk + 2 < BK) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = at[kk * LDA + i * 32];
+                for (int i = 0; i < TM; ++i) a[nx][i] = at[(kk + 2) * LDA + i * 32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bt[kk * LDB + j * 32];
+                for (int j = 0; j < TN; ++j) b[nx][j] = bt[(kk + 2) * LDB + j * 32];
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of the MFMAs below
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (more) store_step(cur ^ 1);
         __syncthreads();
@@ -304,18 +314,27 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
         if (more) load_step(kbeg + (kt + 1) * BK);
         const float* at = As + cur * BK * LDA + a_off;
         const float* bt = Bs + cur * BK * LDB + b_off;
+        float a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][i] = at[i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][j] = bt[j * 32];
 #pragma unroll
         for (int k2 = 0; k2 < BK; k2 += 2) {
-            float a[TM], b[TN];
+            const int c = (k2 >> 1) & 1, nx = c ^ 1;
+            if (k2 + 2 < BK) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = at[k2 * LDA + i * 32];
+                for (int i = 0; i < TM; ++i) a[nx][i] = at[(k2 + 2) * LDA + i * 32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bt[k2 * LDB + j * 32];
+                for (int j = 0; j < TN; ++j) b[nx][j] = bt[(k2 + 2) * LDB + j * 32];
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of the MFMAs below
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (more) store_step(cur ^ 1);
         __syncthreads();
