@@ -123,7 +123,11 @@ vdnn_status_t vdnn_attach_device(vdnn_net_t*, void* pool_base /*device*/, size_t
 /* Weights: CONV [K][C][R][S], FC [out][in], fp32 (host).  count must match. */
 vdnn_status_t vdnn_set_weights(vdnn_net_t*, int layer, const float* w /*host*/, size_t count);
 vdnn_status_t vdnn_get_weight_grad(vdnn_net_t*, int layer, float* dw /*host*/, size_t count);
+vdnn_status_t vdnn_get_weights(vdnn_net_t*, int layer, float* w /*host*/, size_t count);
 size_t vdnn_weight_count(const vdnn_net_t*, int layer); /* 0 for layers without weights */
+/* Section 2.2: once backward propagation reaches the first layer the weights are adjusted with the
+ * weight gradients.  Plain SGD on every layer: W <- W - learning_rate * dW.  Call after vdnn_backward. */
+vdnn_status_t vdnn_sgd_step(vdnn_net_t*, float learning_rate);
 size_t vdnn_output_count(const vdnn_net_t*, int layer); /* elements of the layer's output */
 
 /* Test hooks: copy layer's output Y (right after its forward computation) / the gradient w.r.t.

@@ -102,3 +102,9 @@ def step(net, x, labels, weights, want_dx_input=False):
         else:
             raise ValueError(t)
     return dict(outs=outs, loss=loss, dw=dw, dx=grads)
+
+
+def sgd_update(weights, dw, lr):
+    """Section 2.2: after backward propagation reaches the first layer, the weights are adjusted with the
+    weight gradients.  Plain SGD: W <- W - lr * dW."""
+    return {i: np.asarray(w, np.float64) - lr * dw[i] for i, w in weights.items()}

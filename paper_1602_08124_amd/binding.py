@@ -54,6 +54,8 @@ EXPORTS = {
     "vdnn_attach_device": ([_vp, _vp, _sz, _vp, _vp], _i),
     "vdnn_set_weights": ([_vp, _i, _vp, _sz], _i),
     "vdnn_get_weight_grad": ([_vp, _i, _vp, _sz], _i),
+    "vdnn_get_weights": ([_vp, _i, _vp, _sz], _i),
+    "vdnn_sgd_step": ([_vp, C.c_float], _i),
     "vdnn_weight_count": ([_vp, _i], _sz),
     "vdnn_output_count": ([_vp, _i], _sz),
     "vdnn_capture_output": ([_vp, _i, _vp], _i),
@@ -194,6 +196,15 @@ class Net:
         out = np.empty(self.weight_count(layer), np.float32)
         self._chk(lib.vdnn_get_weight_grad(self.h, layer, out.ctypes.data, out.size))
         return out.reshape(shape) if shape is not None else out
+
+    def get_weights(self, layer, shape=None):
+        import numpy as np
+        out = np.empty(self.weight_count(layer), np.float32)
+        self._chk(lib.vdnn_get_weights(self.h, layer, out.ctypes.data, out.size))
+        return out.reshape(shape) if shape is not None else out
+
+    def sgd_step(self, lr):
+        self._chk(lib.vdnn_sgd_step(self.h, lr))
 
     def capture_output(self, layer, arr):
         self._chk(lib.vdnn_capture_output(self.h, layer, arr.ctypes.data if arr is not None else None))

@@ -833,6 +833,29 @@ vdnn_status_t vdnn_get_weight_grad(vdnn_net_t* np, int layer, float* dw, size_t 
     return VDNN_OK;
 }
 
+vdnn_status_t vdnn_get_weights(vdnn_net_t* np, int layer, float* w, size_t count) {
+    if (!np || !w) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (layer < 0 || layer >= (int)n.layers.size() || !n.layers[layer].wcount || n.layers[layer].wcount != count) {
+        n.err = "get_weights: wrong layer or count";
+        return VDNN_ERR_INVALID_ARG;
+    }
+    if (!n.pool) { n.err = "weights were never set"; return VDNN_ERR_STATE; }
+    HIPCHK(hipStreamSynchronize(n.sc));
+    HIPCHK(hipMemcpy(w, blk(n, n.layers[layer].w_block), count * 4, hipMemcpyDeviceToHost));
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_sgd_step(vdnn_net_t* np, float learning_rate) {
+    if (!np) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (!n.pool || !n.have_streams || !n.plan.ok) { n.err = "sgd_step before any backward pass"; return VDNN_ERR_STATE; }
+    for (const Layer& l : n.layers)
+        if (l.wcount) HIPCHK(sgd_update(blk(n, l.w_block), blk(n, l.dw_block), learning_rate, l.wcount, n.sc));
+    HIPCHK(hipStreamSynchronize(n.sc));
+    return VDNN_OK;
+}
+
 vdnn_status_t vdnn_capture_output(vdnn_net_t* n, int layer, float* dst) {
     if (!n || layer < 0 || layer >= (int)n->layers.size()) return VDNN_ERR_INVALID_ARG;
     n->cap_out[layer] = dst;

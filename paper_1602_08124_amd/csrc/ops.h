@@ -39,5 +39,6 @@ hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, in
 hipError_t softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, hipStream_t st);
 hipError_t concat_copy(const float* src, float* dst, int N, int c_src, int c_dst, int c_off, int hw, int to_dst, hipStream_t st);
 hipError_t add_inplace(float* acc, const float* src, size_t count, hipStream_t st);
+hipError_t sgd_update(float* w, const float* dw, float lr, size_t count, hipStream_t st);
 
 }  // namespace vdnn

@@ -363,6 +363,16 @@ __global__ void add_kernel(float* __restrict__ acc, const float* __restrict__ sr
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) acc[i] += src[i];
 }
 
+__global__ void sgd_kernel(float* __restrict__ w, const float* __restrict__ dw, float lr, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) w[i] -= lr * dw[i];
+}
+
+hipError_t sgd_update(float* w, const float* dw, float lr, size_t count, hipStream_t st) {
+    if (!count) return hipSuccess;
+    hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, w, dw, lr, count);
+    return hipGetLastError();
+}
+
 hipError_t add_inplace(float* acc, const float* src, size_t count, hipStream_t st) {
     if (!count) return hipSuccess;
     hipLaunchKernelGGL(add_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, acc, src, count);

@@ -144,3 +144,35 @@ def test_two_steps_in_a_row_and_policy_switch(B):
     for i in weights:
         assert np.array_equal(d1[i], n.get_weight_grad(i))
     n.close()
+
+
+@pytest.mark.parametrize("policy", ["none", "all"])
+def test_training_iterations_follow_the_oracle(B, policy):
+    """Five SGD iterations (forward, backward, update) on the Tiny net: the loss trajectory and the final weights
+    follow the fp64 oracle, and the loss goes down."""
+    net = nets.tiny(8)
+    x, labels, weights = gen.make(net)
+    lr = 0.05
+    ow = {i: w.astype(np.float64) for i, w in weights.items()}
+    ref_losses = []
+    for _ in range(5):
+        r = onet.step(net, x, labels, ow)
+        ref_losses.append(r["loss"])
+        ow = onet.sgd_update(ow, r["dw"], lr)
+    n = B.Net(net, 4 << 20)
+    n.set_policy(policy)
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    xd, ld = dev(x), dev(labels)
+    losses = []
+    for _ in range(5):
+        losses.append(n.forward(xd, ld))
+        n.backward()
+        n.sgd_step(lr)
+    assert ref_losses[-1] < ref_losses[0]
+    for a, b in zip(losses, ref_losses):
+        assert abs(a - b) < 5 * TOL * abs(b)
+    for i, w in weights.items():
+        assert rel_err(n.get_weights(i, w.shape), ow[i]) < 5 * TOL
+    n.close()
