@@ -42,6 +42,11 @@ typedef enum {
 /* Section 3.3: static policies all / conv, the dynamic policy, and no offloading at all. */
 typedef enum { VDNN_POLICY_NONE = 0, VDNN_POLICY_ALL = 1, VDNN_POLICY_CONV = 2, VDNN_POLICY_DYN = 3 } vdnn_policy_t;
 
+/* Section 2.2 / 3.3: per CONV layer, the performance-optimal algorithm (needs workspace) or the
+ * memory-optimal one (none).  GREEDY is what phase 3 of vDNN_dyn produces: performance-optimal except
+ * where its workspace would overflow the budget. */
+typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdnn_conv_algo_t;
+
 typedef enum {
     VDNN_CONV = 0,       /* cross-correlation, zero padding, no bias */
     VDNN_RELU = 1,       /* in place: shares its input's feature map and gradient map */
@@ -81,6 +86,9 @@ typedef struct {
     uint64_t workspace_bytes;     /* largest transient workspace of the step */
     int32_t n_offload, n_prefetch, n_ondemand_fetch;
     int32_t effective_policy;     /* what DYN resolved to; otherwise the policy set */
+    int32_t conv_algo;            /* vdnn_conv_algo_t of the current plan */
+    int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
+    int32_t reserved_;
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
@@ -94,10 +102,17 @@ typedef struct {
 vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_budget, vdnn_net_t** out);
 
 /* Section 3.3.  ALL: offload the X of every CONV and POOL layer; CONV: only X that feed a CONV
- * layer; DYN: the profiling-pass sequence with out-of-memory as the signal (with one convolution
- * algorithm: all must fit, then none, conv, all - first that fits).  Re-plans the step.
- * Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net stays usable). */
+ * layer; DYN: the profiling-pass sequence with out-of-memory as the signal:
+ *   1. all with the memory-optimal algorithm must fit (else VDNN_ERR_OOM_DEVICE);
+ *   2. performance-optimal algorithms with none, then conv, then all: adopt the first that fits;
+ *   3. greedy: conv, then all, with each CONV layer downgraded to the memory-optimal algorithm
+ *      where its workspace would overflow the budget; else fall back to 1.
+ * Static policies use the algorithm set by vdnn_set_conv_algo (default performance-optimal).
+ * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
+ * stays usable with its previous plan). */
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
+/* Algorithm for the static policies; takes effect at the next vdnn_set_policy. */
+vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);
 
 /* Forward propagation, layers 0..L-1 (Section 2.2; offload per Section 3.2 "Memory Offload").
  * input: (device) batch*in_c*in_h*in_w floats; labels: (device) batch int32 in [0, classes).
@@ -145,6 +160,8 @@ const char* vdnn_last_error(const vdnn_net_t*);
 void vdnn_destroy(vdnn_net_t*);
 
 /* ---- single-layer entry points (the kernels behind the step; all pointers are device) ----- */
+/* Message of the last failing vdnn_op_* call of this thread. */
+const char* vdnn_op_last_error(void);
 /* stream: hipStream_t or NULL.  Shapes: X [N][C][H][W], W [K][C][R][S], Y [N][K][P][Q] with
  * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream. */
 
@@ -166,12 +183,13 @@ vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, 
                                     int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
                                     void* stream);
 /* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
- * order (deterministic, no atomics).  workspace may be NULL iff the required size is 0. */
+ * order (deterministic, no atomics).  With workspace NULL or smaller than required the memory-optimal
+ * algorithm runs instead: no split, one workgroup per output tile (much slower on long reductions). */
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
                                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
 
-/* FC: Y[N][O] = X[N][I] W[O][I]^T ; dX = dY W ; dW = dY^T X.  Same workspace rule. */
+/* FC: Y[N][O] = X[N][I] W[O][I]^T ; dX = dY W ; dW = dY^T X.  Same workspace rule (too little: no split). */
 size_t vdnn_op_fc_workspace(int N, int I, int O, int which /*0 fwd, 1 bwd-data, 2 bwd-filter*/);
 vdnn_status_t vdnn_op_fc_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int I,
                              int O, void* stream);

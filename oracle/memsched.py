@@ -152,11 +152,14 @@ def selected(net, info, b, policy):
     return False
 
 
-def workspace_bytes(net, info, i, phase):
-    """Transient workspace of layer i: partial sums of reduction-split GEMMs."""
+def workspace_bytes(net, info, i, phase, memopt=False):
+    """Transient workspace of layer i: partial sums of reduction-split GEMMs and packed weights.
+    memopt: the CONV layer runs the memory-optimal algorithm, which needs X, Y and W only (Section 2.2)."""
     l = net["layers"][i]
     n = net["batch"]
     c, h, w = info["shp"](l["inputs"][0])
+    if l["type"] == "conv" and memopt:
+        return 0
     if l["type"] == "conv":
         k, p, q = info["shape"][i]
         wbytes = 4 * k * c * l["k"] * l["k"]
@@ -195,10 +198,12 @@ def baseline_bytes(net):
     return fm + wb + 2 * gmax + _al(wmax)
 
 
-def simulate(net, policy, budget):
-    """One training step under a static policy ("none" | "all" | "conv").  Returns a dict with
-    status ("ok" | "oom"), where it failed, peak / average / final pool bytes, transfer counts
-    and the ordered op trace."""
+def simulate(net, policy, budget, algo="p"):
+    """One training step under a static policy ("none" | "all" | "conv") and a convolution algorithm
+    mode: "p" performance-optimal (workspace), "m" memory-optimal (none), "greedy" = performance-optimal
+    except where that layer's workspace would overflow the budget (Section 3.3, phase 3 of vDNN_dyn).
+    Returns a dict with status ("ok" | "oom"), where it failed, peak / average / final pool bytes,
+    transfer counts, the number of CONV layers on the memory-optimal algorithm and the ordered op trace."""
     info = analyse(net)
     layers = net["layers"]
     nl = len(layers)
@@ -206,6 +211,19 @@ def simulate(net, policy, budget):
     trace = []
     samples = []
     st = dict(offloaded_bytes=0, prefetched_bytes=0, n_offload=0, n_prefetch=0, n_ondemand_fetch=0)
+    memopt = set()  # CONV layers downgraded (or set) to the memory-optimal algorithm in either pass
+
+    def layer_ws(i, phase):
+        conv = layers[i]["type"] == "conv"
+        if conv and algo == "m":
+            memopt.add(i)
+            return 0
+        ws = workspace_bytes(net, info, i, phase)
+        if conv and algo == "greedy" and ws and pool.live + _al(ws) > pool.budget:
+            memopt.add(i)
+            return 0
+        return ws
+
     res = {}        # buffer -> (tag, size) while resident
     grad = {}       # buffer -> (tag, size) of its gradient map
     on_host = set()
@@ -240,7 +258,7 @@ def simulate(net, policy, budget):
             t = l["type"]
             if t not in IN_PLACE and t != "softmax_ce":
                 res[i] = alloc("B%d" % i, info["nbytes"][i])
-            ws = workspace_bytes(net, info, i, "fwd")
+            ws = layer_ws(i, "fwd")
             wsb = alloc("WS", ws) if ws else None
             if t not in IN_PLACE:
                 for b in dict.fromkeys(info["bufof"](j) for j in l["inputs"]):
@@ -299,7 +317,7 @@ def simulate(net, policy, budget):
                         grad[b] = alloc("dB%d" % b, info["nbytes"][b])
                     else:
                         temps.append(alloc("T%d" % b, info["nbytes"][b]))
-            ws = workspace_bytes(net, info, m, "bwd")
+            ws = layer_ws(m, "bwd")
             wsb = alloc("WS", ws) if ws else None
             trace.append((where, "compute", t))
             if wsb:
@@ -321,19 +339,24 @@ def simulate(net, policy, budget):
     if status == "ok":
         out["persistent_bytes"] = persistent
     out.update(st)
+    out["n_memopt_convs"] = len(memopt)
     return out
 
 
 def dynamic(net, budget):
-    """vDNN_dyn with a single convolution algorithm (Section 3.3, "Dynamic vDNN"): pass 1 tests
-    all; if it fits, pass 2 tests none, then conv, then all and adopts the first that fits.
-    The greedy per-layer algorithm downgrade of pass 3 has nothing to choose from while one
-    algorithm exists.  Returns (effective policy or None, result of the adopted pass)."""
-    first = simulate(net, "all", budget)
+    """vDNN_dyn (Section 3.3, "Dynamic vDNN").  Pass 1: all with the memory-optimal algorithm must fit.
+    Pass 2: performance-optimal algorithms with no offloading, else conv, else all - adopt the first
+    that fits.  Pass 3: greedy per-layer downgrade under conv, then all; else the configuration of pass 1.
+    Returns (policy or None, algorithm mode, result of the adopted pass)."""
+    first = simulate(net, "all", budget, "m")
     if first["status"] != "ok":
-        return None, first
+        return None, None, first
     for pol in ("none", "conv", "all"):
-        r = simulate(net, pol, budget)
+        r = simulate(net, pol, budget, "p")
         if r["status"] == "ok":
-            return pol, r
-    return "all", first
+            return pol, "p", r
+    for pol in ("conv", "all"):
+        r = simulate(net, pol, budget, "greedy")
+        if r["status"] == "ok":
+            return pol, "greedy", r
+    return "all", "m", first

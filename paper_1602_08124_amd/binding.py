@@ -7,6 +7,15 @@ if libvdnn.so is missing, importing this module raises.
 import ctypes as C
 import os
 
+# PyTorch ships its own copy of the HIP runtime (same SONAME as the system one).  It has to be in the
+# process BEFORE libvdnn.so is loaded, so that the library binds to that same runtime instance; in the
+# other order the process ends up with two runtimes and the pool and streams borrowed from torch
+# would belong to a different one than the library's kernels are launched with.
+try:
+    import torch  # noqa: F401
+except ImportError:  # a pure C / ctypes user without torch: the system runtime is the only one
+    torch = None
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libvdnn.so")
 if not os.path.exists(LIB_PATH):
@@ -16,6 +25,8 @@ lib = C.CDLL(LIB_PATH)
 OK, ERR_INVALID_ARG, ERR_OOM_DEVICE, ERR_OOM_HOST, ERR_HIP, ERR_STATE, ERR_UNSUPPORTED = range(7)
 POLICY = {"none": 0, "all": 1, "conv": 2, "dyn": 3}
 POLICY_NAME = {v: k for k, v in POLICY.items()}
+ALGO = {"p": 0, "m": 1, "greedy": 2}
+ALGO_NAME = {v: k for k, v in ALGO.items()}
 LAYER_TYPE = {"conv": 0, "relu": 1, "maxpool": 2, "avgpool": 3, "fc": 4, "concat": 5, "softmax_ce": 6}
 MAX_INPUTS = 8
 
@@ -36,7 +47,8 @@ class MemStats(C.Structure):
                 ("avg_bytes_layerstep", C.c_double), ("offloaded_bytes", C.c_uint64), ("prefetched_bytes", C.c_uint64),
                 ("pinned_host_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64),
                 ("n_offload", C.c_int32), ("n_prefetch", C.c_int32), ("n_ondemand_fetch", C.c_int32),
-                ("effective_policy", C.c_int32),
+                ("effective_policy", C.c_int32), ("conv_algo", C.c_int32), ("n_memopt_convs", C.c_int32),
+                ("reserved_", C.c_int32),
                 ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("stall_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double)]
 
@@ -48,6 +60,7 @@ _sz = C.c_size_t
 EXPORTS = {
     "vdnn_create": ([C.POINTER(NetDesc), _sz, C.POINTER(_vp)], _i),
     "vdnn_set_policy": ([_vp, _i], _i),
+    "vdnn_set_conv_algo": ([_vp, _i], _i),
     "vdnn_forward": ([_vp, _vp, _vp, C.POINTER(C.c_float)], _i),
     "vdnn_backward": ([_vp], _i),
     "vdnn_mem_stats": ([_vp, C.POINTER(MemStats)], _i),
@@ -63,6 +76,7 @@ EXPORTS = {
     "vdnn_trace": ([_vp, C.c_char_p, _sz, C.POINTER(_sz)], _i),
     "vdnn_last_error": ([_vp], C.c_char_p),
     "vdnn_destroy": ([_vp], None),
+    "vdnn_op_last_error": ([], C.c_char_p),
     "vdnn_op_conv_fwd_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_data_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
@@ -142,6 +156,10 @@ class Net:
     def set_policy(self, policy):
         self._chk(lib.vdnn_set_policy(self.h, POLICY[policy]))
 
+    def set_conv_algo(self, algo):
+        """"p" (performance-optimal, workspace), "m" (memory-optimal) or "greedy"; applies at the next set_policy."""
+        self._chk(lib.vdnn_set_conv_algo(self.h, ALGO[algo]))
+
     def try_policy(self, policy):
         """Returns the status instead of raising (OOM is an expected outcome)."""
         return lib.vdnn_set_policy(self.h, POLICY[policy])
@@ -154,6 +172,7 @@ class Net:
         self._chk(lib.vdnn_mem_stats(self.h, C.byref(st)))
         d = {k: getattr(st, k) for k, _ in MemStats._fields_}
         d["effective_policy"] = POLICY_NAME[d["effective_policy"]]
+        d["conv_algo"] = ALGO_NAME[d["conv_algo"]]
         return d
 
     def trace(self):
@@ -235,7 +254,7 @@ def _stream_ptr(stream):
 
 def _ck(s, what):
     if s != OK:
-        raise VdnnError(s, what)
+        raise VdnnError(s, what + ": " + lib.vdnn_op_last_error().decode())
 
 
 # ---- single-layer entry points on torch CUDA tensors (marshalling only) -------------------------

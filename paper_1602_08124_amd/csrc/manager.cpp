@@ -176,10 +176,11 @@ static bool fold_bwd(const vdnn_net& n, int reader) {
 // ---------------------------------------------------------------------------------------------
 // workspace of a layer (partial sums of reduction-split GEMMs)
 // ---------------------------------------------------------------------------------------------
-static size_t layer_workspace(const vdnn_net& n, int i, bool bwd) {
+static size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false) {
     const Layer& l = n.layers[i];
     int C, H, W;
     shape_of(n, l.inputs[0], &C, &H, &W);
+    if (l.type == VDNN_CONV && memopt) return 0;  // the memory-optimal algorithm needs X, Y, W only
     if (l.type == VDNN_CONV && !bwd) return conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
     if (l.type == VDNN_CONV && bwd) {
         const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
@@ -266,24 +267,28 @@ struct Compiler {
 
 }  // namespace
 
-// Greedy-by-size placement of the transient blocks above the persistent region: each block takes
-// the lowest offset at which it overlaps no already placed block whose lifetime intersects its own.
-static size_t place_blocks(Plan& p, size_t base) {
-    std::vector<int> order;
-    for (int i = 0; i < (int)p.blocks.size(); ++i)
-        if (!p.blocks[i].persistent) order.push_back(i);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        if (p.blocks[a].bytes != p.blocks[b].bytes) return p.blocks[a].bytes > p.blocks[b].bytes;
-        return p.blocks[a].t0 < p.blocks[b].t0;
-    });
+// Placement of the transient blocks above the persistent region.  Blocks are taken in a priority
+// order and each takes the lowest offset at which it overlaps no already placed block whose lifetime
+// intersects its own.  The live-byte peak is the lower bound of the address range.  Three orders are
+// tried first (by size; by lifetime; by size x lifetime); if none reaches the bound, the same three
+// priorities are perturbed with seeded noise for a bounded number of rounds and the best placement
+// wins.  On the paper's workloads this reaches the bound (no fragmentation) within a few rounds.
+static size_t place_with_keys(Plan& p, size_t base, const std::vector<int>& ids, const std::vector<double>& key,
+                              std::vector<size_t>& offsets) {
+    std::vector<int> order(ids.size());
+    for (size_t i = 0; i < ids.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key[a] > key[b]; });
     std::vector<int> placed;
+    offsets.assign(p.blocks.size(), 0);
     size_t extent = base;
-    for (int id : order) {
-        Block& b = p.blocks[id];
-        std::vector<std::pair<size_t, size_t>> conf;
+    std::vector<std::pair<size_t, size_t>> conf;
+    for (int oi : order) {
+        const int id = ids[oi];
+        const Block& b = p.blocks[id];
+        conf.clear();
         for (int o : placed) {
             const Block& q = p.blocks[o];
-            if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({q.offset, q.bytes});
+            if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({offsets[o], q.bytes});
         }
         std::sort(conf.begin(), conf.end());
         size_t off = base;
@@ -291,17 +296,57 @@ static size_t place_blocks(Plan& p, size_t base) {
             if (off + b.bytes <= c.first) break;
             off = std::max(off, c.first + c.second);
         }
-        b.offset = off;
+        offsets[id] = off;
         extent = std::max(extent, off + b.bytes);
         placed.push_back(id);
     }
     return extent;
 }
 
-// Compiles one training step under a static policy (NONE / ALL / CONV).
-static void compile_plan(const vdnn_net& n, int policy, Plan& p) {
+static size_t place_blocks(Plan& p, size_t base) {
+    std::vector<int> ids;
+    for (int i = 0; i < (int)p.blocks.size(); ++i)
+        if (!p.blocks[i].persistent) ids.push_back(i);
+    if (ids.empty()) return base;
+    const size_t n = ids.size();
+    std::vector<double> size(n), life(n), area(n), key(n);
+    for (size_t i = 0; i < n; ++i) {
+        const Block& b = p.blocks[ids[i]];
+        // ties: earlier blocks first (the tiny bias keeps the order deterministic and stable)
+        size[i] = (double)b.bytes;
+        life[i] = (double)(b.t1 - b.t0);
+        area[i] = size[i] * life[i];
+    }
+    std::vector<size_t> best, cur;
+    size_t best_extent = (size_t)-1;
+    const std::vector<double>* base_keys[3] = {&size, &life, &area};
+    for (int kind = 0; kind < 3; ++kind) {
+        const size_t e = place_with_keys(p, base, ids, *base_keys[kind], cur);
+        if (e < best_extent) { best_extent = e; best = cur; }
+    }
+    uint64_t rng = 0x9E3779B97F4A7C15ull;  // fixed seed: the plan is a pure function of (net, policy, budget)
+    auto next = [&]() { rng = rng * 6364136223846793005ull + 1442695040888963407ull; return (double)(rng >> 11) / 9007199254740992.0; };
+    const double noises[4] = {0.1, 0.3, 0.6, 1.0};
+    for (int round = 0; round < 300 && best_extent > p.peak; ++round) {
+        const std::vector<double>& k0 = *base_keys[(int)(next() * 3) % 3];
+        const double noise = noises[(int)(next() * 4) % 4];
+        for (size_t i = 0; i < n; ++i) key[i] = k0[i] * (1.0 + noise * (next() - 0.5));
+        const size_t e = place_with_keys(p, base, ids, key, cur);
+        if (e < best_extent) { best_extent = e; best = cur; }
+    }
+    for (int id : ids) p.blocks[id].offset = best[id];
+    return best_extent;
+}
+
+// Compiles one training step under a static policy (NONE / ALL / CONV) and a convolution algorithm
+// mode: performance-optimal everywhere, memory-optimal everywhere, or greedy (performance-optimal
+// unless that layer's workspace would overflow the budget: Section 3.3, phase 3 of vDNN_dyn).
+static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p) {
     p = Plan();
     p.policy = policy;
+    p.algo = algo;
+    p.memopt_fwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
+    p.memopt_bwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     Compiler c(n, p, budget);
     const int L = (int)n.layers.size();
@@ -344,7 +389,8 @@ static void compile_plan(const vdnn_net& n, int policy, Plan& p) {
         c.emit(OP_SAMPLE);
         c.samples.push_back(c.live);
         if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); }
-        const size_t ws = layer_workspace(n, i, false);
+        size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
+        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
         std::vector<int> in_bufs;
@@ -428,7 +474,8 @@ static void compile_plan(const vdnn_net& n, int policy, Plan& p) {
                 else { const int t = c.alloc(fmt("T%d", b), n.B(b).count * 4); CHECK_FAIL(); temps.push_back(t); gout[k] = t; gacc[k] = grad[b + 1]; }
             }
         }
-        const size_t ws = layer_workspace(n, m, true);
+        size_t ws = layer_workspace(n, m, true, p.memopt_bwd[m]);
+        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_bwd[m] = 1; ws = 0; }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
         {
@@ -462,6 +509,8 @@ static void compile_plan(const vdnn_net& n, int policy, Plan& p) {
         return;
     }
     for (int i = 0; i < L; ++i) { const_cast<Layer&>(n.layers[i]).w_block = w_block[i]; const_cast<Layer&>(n.layers[i]).dw_block = dw_block[i]; }
+    for (int i = 0; i < L; ++i)
+        if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
     p.ok = true;
 }
 
@@ -480,24 +529,30 @@ static size_t baseline_bytes(const vdnn_net& n) {
     return fm + wb + 2 * gmax + align_up(wmax);
 }
 
-// Section 3.3, "Dynamic vDNN", with one convolution algorithm: (1) all must be trainable;
-// (2) adopt the first of none, conv, all that fits.  The greedy per-layer downgrade of the third
-// phase has nothing to choose from.  Trainability of a pass is decided by the planner, which
-// performs exactly the allocations a real pass would.
+// Section 3.3, "Dynamic vDNN".  Trainability of a pass is decided by the planner, which performs
+// exactly the allocations a real pass would (the paper's profiling passes only use pass/fail).
+//   1. all with the memory-optimal algorithm: can the network be trained at all;
+//   2. performance-optimal algorithms without offloading, else with conv, else with all;
+//   3. greedy per-layer algorithm downgrade under conv, then under all; else back to 1.
 static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
     Plan p;
     if (policy == VDNN_POLICY_DYN) {
-        compile_plan(n, VDNN_POLICY_ALL, p);
-        if (!p.ok) { n.err = "vDNN_dyn: even vDNN_all does not fit: " + p.fail_why; return VDNN_ERR_OOM_DEVICE; }
+        Plan first;
+        compile_plan(n, VDNN_POLICY_ALL, VDNN_ALGO_MEM, first);
+        if (!first.ok) { n.err = "vDNN_dyn: even vDNN_all with the memory-optimal algorithm does not fit: " + first.fail_why; return VDNN_ERR_OOM_DEVICE; }
         const int order[3] = {VDNN_POLICY_NONE, VDNN_POLICY_CONV, VDNN_POLICY_ALL};
         for (int pol : order) {
-            compile_plan(n, pol, p);
+            compile_plan(n, pol, VDNN_ALGO_PERF, p);
             if (p.ok) { n.plan = p; n.policy = policy; n.effective = pol; return VDNN_OK; }
         }
-        n.err = "vDNN_dyn: internal error";
-        return VDNN_ERR_STATE;
+        for (int pol : {VDNN_POLICY_CONV, VDNN_POLICY_ALL}) {
+            compile_plan(n, pol, VDNN_ALGO_GREEDY, p);
+            if (p.ok) { n.plan = p; n.policy = policy; n.effective = pol; return VDNN_OK; }
+        }
+        n.plan = first; n.policy = policy; n.effective = VDNN_POLICY_ALL;
+        return VDNN_OK;
     }
-    compile_plan(n, policy, p);
+    compile_plan(n, policy, n.static_algo, p);
     if (!p.ok) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
     n.plan = p; n.policy = policy; n.effective = policy;
     return VDNN_OK;
@@ -578,7 +633,7 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
     const int N = n.batch;
     float* x = blk(n, o.in_blocks[0]);
     float* y = blk(n, o.out_block);
-    const size_t wsb0 = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
+    const size_t wsb0 = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;  // no block: the memory-optimal algorithm runs
     switch (l.type) {
         case VDNN_CONV:
             HIPCHK(conv_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
@@ -776,6 +831,12 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc, size_t gpu_mem_budget, vd
     return VDNN_OK;
 }
 
+vdnn_status_t vdnn_set_conv_algo(vdnn_net_t* n, vdnn_conv_algo_t algo) {
+    if (!n || algo < VDNN_ALGO_PERF || algo > VDNN_ALGO_GREEDY) return VDNN_ERR_INVALID_ARG;
+    n->static_algo = algo;
+    return VDNN_OK;
+}
+
 vdnn_status_t vdnn_set_policy(vdnn_net_t* n, vdnn_policy_t policy) {
     if (!n || policy < VDNN_POLICY_NONE || policy > VDNN_POLICY_DYN) return VDNN_ERR_INVALID_ARG;
     n->fwd_done = false;
@@ -931,6 +992,8 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
         s.n_offload = p.n_offload;
         s.n_prefetch = p.n_prefetch;
         s.n_ondemand_fetch = p.n_ondemand;
+        s.conv_algo = p.algo;
+        s.n_memopt_convs = p.n_memopt;
     }
     s.fwd_ms = n->fwd_ms; s.bwd_ms = n->bwd_ms; s.stall_ms = n->stall_ms;
     s.d2h_ms = n->d2h_ms; s.h2d_ms = n->h2d_ms;

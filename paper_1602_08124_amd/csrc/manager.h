@@ -93,6 +93,9 @@ struct Plan {
     size_t offloaded = 0, prefetched = 0;
     int n_offload = 0, n_prefetch = 0, n_ondemand = 0;
     int labels_block = -1, loss_block = -1;
+    int algo = 0;                        // vdnn_conv_algo_t the plan was compiled with
+    std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
+    int n_memopt = 0;
 };
 
 }  // namespace vdnn
@@ -103,6 +106,7 @@ struct vdnn_net {
     std::vector<vdnn::Buffer> bufs;  // index = buffer id + 1
     size_t budget = 0;               // 0 = unlimited
     int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
+    int static_algo = VDNN_ALGO_PERF;
     vdnn::Plan plan;
     size_t baseline = 0;
 

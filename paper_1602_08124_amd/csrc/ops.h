@@ -6,6 +6,15 @@
 #include <stdint.h>
 #include <algorithm>
 
+// hipGetLastError() after a launch reports the last error of ANY earlier runtime call of this thread,
+// including calls made by other libraries in the process; clear that state first so that the value
+// read after the launch belongs to the launch.
+#define VDNN_LAUNCH(...)            \
+    do {                            \
+        (void)hipGetLastError();    \
+        hipLaunchKernelGGL(__VA_ARGS__); \
+    } while (0)
+
 namespace vdnn {
 
 int gemm_splits(long long m, long long n, long long kred);

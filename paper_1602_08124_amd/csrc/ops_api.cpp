@@ -1,14 +1,21 @@
 // extern "C" wrappers of the single-layer entry points: argument checks and status mapping only.
 #include "../../include/vdnn.h"
+#include <cstdio>
+
 #include "ops.h"
 
 using namespace vdnn;
 
+static thread_local char g_op_error[256] = "";
+
 static vdnn_status_t st(hipError_t e) {
     if (e == hipSuccess) return VDNN_OK;
+    snprintf(g_op_error, sizeof g_op_error, "%s (%s)", hipGetErrorString(e), hipGetErrorName(e));
     (void)hipGetLastError();
     return e == hipErrorInvalidValue ? VDNN_ERR_INVALID_ARG : VDNN_ERR_HIP;
 }
+
+extern "C" const char* vdnn_op_last_error(void) { return g_op_error; }
 
 static bool conv_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     return N > 0 && C > 0 && H > 0 && W > 0 && K > 0 && R > 0 && S > 0 && R == S && stride > 0 && pad >= 0 && H + 2 * pad >= R && W + 2 * pad >= S;

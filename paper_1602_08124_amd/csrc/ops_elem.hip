@@ -45,13 +45,13 @@ __global__ void relu_bwd_kernel(const float* __restrict__ y, float* __restrict__
 
 hipError_t relu_fwd(float* y, size_t count, hipStream_t st) {
     if (!count) return hipSuccess;
-    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid_for(count / 4 + 1, 256)), dim3(256), 0, st, y, count);
+    VDNN_LAUNCH(relu_fwd_kernel, dim3(grid_for(count / 4 + 1, 256)), dim3(256), 0, st, y, count);
     return hipGetLastError();
 }
 
 hipError_t relu_bwd(const float* y, float* dy, size_t count, hipStream_t st) {
     if (!count) return hipSuccess;
-    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid_for(count / 4 + 1, 256)), dim3(256), 0, st, y, dy, count);
+    VDNN_LAUNCH(relu_bwd_kernel, dim3(grid_for(count / 4 + 1, 256)), dim3(256), 0, st, y, dy, count);
     return hipGetLastError();
 }
 
@@ -223,10 +223,10 @@ hipError_t maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int
     if (!small_enough(total, (size_t)N * C * H * W)) return hipErrorInvalidValue;
     if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
         const uint32_t t2 = (uint32_t)(total / 2);
-        hipLaunchKernelGGL(maxpool2x2_fwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, y, W, Q / 2, t2, make_fd(Q / 2));
+        VDNN_LAUNCH(maxpool2x2_fwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, y, W, Q / 2, t2, make_fd(Q / 2));
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
+    VDNN_LAUNCH(maxpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
                        (uint32_t)total, make_fd(Q), make_fd(P));
     return hipGetLastError();
 }
@@ -239,10 +239,10 @@ hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C,
     if (!small_enough(total, total)) return hipErrorInvalidValue;
     if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
         const uint32_t t2 = (uint32_t)((size_t)N * C * P * Q / 2);
-        hipLaunchKernelGGL(maxpool2x2_bwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, dy, dx, W, Q / 2, t2, make_fd(Q / 2), relu_mask);
+        VDNN_LAUNCH(maxpool2x2_bwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, dy, dx, W, Q / 2, t2, make_fd(Q / 2), relu_mask);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad,
+    VDNN_LAUNCH(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad,
                        (uint32_t)total, make_fd(W), make_fd(H), relu_mask);
     return hipGetLastError();
 }
@@ -252,7 +252,7 @@ hipError_t avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * P * Q;
     if (!small_enough(total, (size_t)N * C * H * W)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
+    VDNN_LAUNCH(avgpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
                        (uint32_t)total, make_fd(Q), make_fd(P));
     return hipGetLastError();
 }
@@ -262,7 +262,7 @@ hipError_t avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, i
     if (!pool_dims(H, W, k, stride, pad, &P, &Q)) return hipErrorInvalidValue;
     const size_t total = (size_t)N * C * H * W;
     if (!small_enough(total, total)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, dx, H, W, P, Q, k, stride, pad,
+    VDNN_LAUNCH(avgpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, dx, H, W, P, Q, k, stride, pad,
                        (uint32_t)total, make_fd(W), make_fd(H));
     return hipGetLastError();
 }
@@ -327,13 +327,13 @@ __global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const float* __rest
 
 hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, hipStream_t st) {
     if (N <= 0 || classes <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(softmax_ce_fwd_kernel, dim3(1), dim3(1024), 0, st, z, labels, loss, N, classes);
+    VDNN_LAUNCH(softmax_ce_fwd_kernel, dim3(1), dim3(1024), 0, st, z, labels, loss, N, classes);
     return hipGetLastError();
 }
 
 hipError_t softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, hipStream_t st) {
     if (N <= 0 || classes <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(softmax_ce_bwd_kernel, dim3((N + 3) / 4), dim3(256), 0, st, z, labels, dz, N, classes);
+    VDNN_LAUNCH(softmax_ce_bwd_kernel, dim3((N + 3) / 4), dim3(256), 0, st, z, labels, dz, N, classes);
     return hipGetLastError();
 }
 
@@ -354,7 +354,7 @@ hipError_t concat_copy(const float* src, float* dst, int N, int c_small, int c_b
     if (c_off < 0 || c_off + c_small > c_big) return hipErrorInvalidValue;
     const size_t total = (size_t)N * c_small * hw;
     if (!total) return hipSuccess;
-    hipLaunchKernelGGL(concat_copy_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, (size_t)c_small * hw,
+    VDNN_LAUNCH(concat_copy_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, (size_t)c_small * hw,
                        (size_t)c_big * hw, (size_t)c_off * hw, to_dst, total);
     return hipGetLastError();
 }
@@ -369,13 +369,13 @@ __global__ void sgd_kernel(float* __restrict__ w, const float* __restrict__ dw, 
 
 hipError_t sgd_update(float* w, const float* dw, float lr, size_t count, hipStream_t st) {
     if (!count) return hipSuccess;
-    hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, w, dw, lr, count);
+    VDNN_LAUNCH(sgd_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, w, dw, lr, count);
     return hipGetLastError();
 }
 
 hipError_t add_inplace(float* acc, const float* src, size_t count, hipStream_t st) {
     if (!count) return hipSuccess;
-    hipLaunchKernelGGL(add_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, acc, src, count);
+    VDNN_LAUNCH(add_kernel, dim3(grid_for(count, 256)), dim3(256), 0, st, acc, src, count);
     return hipGetLastError();
 }
 

@@ -38,7 +38,7 @@ __global__ void reduce_splits_kernel(const float* __restrict__ ws, float* __rest
 static hipError_t launch_reduce(const float* ws, float* out, size_t count, int splits, hipStream_t st) {
     const int threads = 256;
     const int blocks = (int)std::min<size_t>((count + threads - 1) / threads, 4096);
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks), dim3(threads), 0, st, ws, out, count, splits);
+    VDNN_LAUNCH(reduce_splits_kernel, dim3(blocks), dim3(threads), 0, st, ws, out, count, splits);
     return hipGetLastError();
 }
 
@@ -61,7 +61,7 @@ static hipError_t launch_tile(const typename LA::Params& pa, const typename LB::
     gi.ksplit = cdiv(cdiv(ktot, splits), BK) * BK;
     const long long nb = (long long)gi.tiles_m * gi.tiles_n * splits;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, pa, pb, ep, gi);
+    VDNN_LAUNCH(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, pa, pb, ep, gi);
     return hipGetLastError();
 }
 
@@ -118,7 +118,7 @@ static hipError_t conv_fast_cfg(ConvFastParams& p, hipStream_t st) {
     p.tiles_n = cdiv(p.M, BN);
     const long long nb = (long long)p.tiles_m * p.tiles_n;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
+    VDNN_LAUNCH(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
     return hipGetLastError();
 }
 
@@ -127,7 +127,7 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
                             int C, int R, int S, int stride, int pad, int P, int Q, int bwd, hipStream_t st) {
     const size_t wcount = (size_t)K * C * R * S;
     const int pblocks = (int)std::min<size_t>((wcount + 255) / 256, 4096);
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(pblocks), dim3(256), 0, st, w, ws, K, C, R * S, bwd);
+    VDNN_LAUNCH(pack_weights_kernel, dim3(pblocks), dim3(256), 0, st, w, ws, K, C, R * S, bwd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     ConvFastParams p;
@@ -210,7 +210,7 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     if (stride != 1 || pad > R - 1 || pad > S - 1) {
         const size_t total = (size_t)N * C * H * W;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 65535 * 4);
-        hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3(blocks), dim3(256), 0, st, dy, w, dx, N, C, H, W, K, R, S, stride, pad, P, Q, relu_mask);
+        VDNN_LAUNCH(conv_bwd_data_direct_kernel, dim3(blocks), dim3(256), 0, st, dy, w, dx, N, C, H, W, K, R, S, stride, pad, P, Q, relu_mask);
         return hipGetLastError();
     }
     // dX[n][c][h][w] = sum_{k,r',s'} dY[n][k][h - (R-1-pad) + r'][w - (S-1-pad) + s'] * W[k][c][R-1-r'][S-1-s']:
@@ -260,7 +260,7 @@ static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
     p.ksplit = cdiv(cdiv(p.M, p.splits), 32) * 32;
     const long long nb = (long long)p.tiles_m * p.tiles_n * p.splits;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
+    VDNN_LAUNCH(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
     return hipGetLastError();
 }
 
@@ -277,10 +277,11 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     const int CRS = C * R * S;
-    const int splits = gemm_splits(K, CRS, (long long)N * P * Q);
-    if (bwdf_fast_ok(N, C, H, W, K, P, Q)) {
-        const size_t need_fast = (size_t)splits * K * CRS * sizeof(float);
-        if (ws_bytes < need_fast || !ws) return hipErrorInvalidValue;
+    int splits = gemm_splits(K, CRS, (long long)N * P * Q);
+    const size_t need_ws = conv_bwd_filter_workspace(N, C, H, W, K, R, S, stride, pad);
+    const bool have_ws = ws && ws_bytes >= need_ws;
+    if (!have_ws) splits = 1;  // memory-optimal algorithm: no workspace, the whole reduction in one workgroup per tile
+    if (have_ws && bwdf_fast_ok(N, C, H, W, K, P, Q)) {
         BwdFilterFastParams fp;
         fp.x = x; fp.dy = dy; fp.ws = (float*)ws;
         fp.x_bytes = (uint32_t)((size_t)N * C * H * W * 4);
@@ -296,11 +297,9 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
         if (e != hipSuccess) return e;
         const size_t total = (size_t)K * CRS;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-        hipLaunchKernelGGL(reduce_permute_kernel, dim3(blocks), dim3(256), 0, st, (const float*)ws, dw, K, C, R * S, splits);
+        VDNN_LAUNCH(reduce_permute_kernel, dim3(blocks), dim3(256), 0, st, (const float*)ws, dw, K, C, R * S, splits);
         return hipGetLastError();
     }
-    const size_t need = splits > 1 ? (size_t)splits * K * CRS * sizeof(float) : 0;
-    if (ws_bytes < need || (need && !ws)) return hipErrorInvalidValue;
     ConvGeom g = make_geom(x, N, C, H, W, R, S, stride, pad, P, Q);
     PixKParams pa;
     pa.base = dy; pa.rows = K; pa.PQ = P * Q; pa.fd_pq = g.fd_pq;
@@ -338,8 +337,7 @@ static RowMajorOut fc_out(float* out, void* ws, int rows, int cols, int splits) 
 
 hipError_t fc_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
     constexpr int BK = 16, PAD = 2;
-    const int splits = gemm_splits(N, O, I);
-    if (ws_bytes < gemm_workspace_bytes(N, O, I) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    const int splits = (ws && ws_bytes >= gemm_workspace_bytes(N, O, I)) ? gemm_splits(N, O, I) : 1;
     RowMajorOut eo = fc_out(y, ws, N, O, splits);
     hipError_t e = launch_tile<128, 128, BK, 2, 2, PAD, PAD, GatherK<128, BK, PAD>, GatherK<128, BK, PAD>, RowMajorOut>(
         dense_k(x, N, I), dense_k(w, O, I), eo, N, O, I, splits, st);
@@ -349,8 +347,7 @@ hipError_t fc_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_
 
 hipError_t fc_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
     constexpr int BK = 16, PADA = 2, PADB = 32;
-    const int splits = gemm_splits(N, I, O);
-    if (ws_bytes < gemm_workspace_bytes(N, I, O) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    const int splits = (ws && ws_bytes >= gemm_workspace_bytes(N, I, O)) ? gemm_splits(N, I, O) : 1;
     RowMajorOut eo = fc_out(dx, ws, N, I, splits);
     DenseRParams pb;
     pb.base = w; pb.rows = I; pb.ld = I;
@@ -362,8 +359,7 @@ hipError_t fc_bwd_data(const float* dy, const float* w, float* dx, void* ws, siz
 
 hipError_t fc_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st) {
     constexpr int BK = 16, PAD = 32;
-    const int splits = gemm_splits(O, I, N);
-    if (ws_bytes < gemm_workspace_bytes(O, I, N) || (splits > 1 && !ws)) return hipErrorInvalidValue;
+    const int splits = (ws && ws_bytes >= gemm_workspace_bytes(O, I, N)) ? gemm_splits(O, I, N) : 1;
     RowMajorOut eo = fc_out(dw, ws, O, I, splits);
     DenseRParams pa, pb;
     pa.base = dy; pa.rows = O; pa.ld = O;

@@ -42,8 +42,10 @@ def small_googlenet(batch=2):
     return nets.googlenet(batch, in_hw=64, modules=mods)
 
 
-def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True):
+def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=None):
     n = B.Net(net, budget)
+    if algo:
+        n.set_conv_algo(algo)
     n.set_policy(policy)
     n.attach_torch()
     for i, w in weights.items():
@@ -176,3 +178,37 @@ def test_training_iterations_follow_the_oracle(B, policy):
     for i, w in weights.items():
         assert rel_err(n.get_weights(i, w.shape), ow[i]) < 5 * TOL
     n.close()
+
+
+@pytest.mark.parametrize("name,mk", [("tiny", lambda: nets.tiny(8)), ("small_vgg", small_vgg), ("small_googlenet", small_googlenet)])
+def test_memory_optimal_algorithm_matches_oracle(B, name, mk):
+    """Section 2.2: the memory-optimal convolution algorithm (X, Y, W only, no workspace) computes the same
+    step as the performance-optimal one, to rounding order."""
+    net = mk()
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 19)
+    ref = onet.step(net, x, labels, weights)
+    got = run_gpu(B, net, x, labels, weights, "all", capture=False, algo="m")
+    assert got["stats"]["conv_algo"] == "m" and got["stats"]["workspace_bytes"] <= max(
+        (w.size * 4 for i, w in weights.items() if net["layers"][i]["type"] == "fc"), default=0) * 64
+    assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
+    for i in weights:
+        assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+
+
+def test_dyn_greedy_downgrade_runs(B):
+    """A budget between vDNN_all's peak with and without convolution workspace: vDNN_dyn reaches its greedy phase
+    and the step still matches the oracle."""
+    from oracle import memsched as ms
+    net = nets.alexnet(8)
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 20)
+    budget = ms.simulate(net, "all", 1 << 50, "p")["peak_bytes"] - 256
+    pol, algo, sim = ms.dynamic(net, budget)
+    assert algo == "greedy"
+    got = run_gpu(B, net, x, labels, weights, "dyn", budget=budget, capture=False)
+    st = got["stats"]
+    assert (st["effective_policy"], st["conv_algo"]) == (pol, "greedy") and st["n_memopt_convs"] == sim["n_memopt_convs"] >= 1
+    assert st["peak_bytes"] <= budget
+    base = run_gpu(B, net, x, labels, weights, "none", capture=False)
+    assert abs(got["loss"] - base["loss"]) < TOL * abs(base["loss"])
+    for i in weights:
+        assert rel_err(got["dw"][i], base["dw"][i].astype(np.float64)) < TOL, i

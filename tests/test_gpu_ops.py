@@ -113,6 +113,10 @@ def test_conv_bwd_filter(B, shape):
     dw = torch.full((k, c, r, r), float("nan"), device="cuda")
     B.op_conv_bwd_filter(dev(x), dev(dy), dw, ws, st, pd)
     assert rel_err(host(dw), ref) < TOL
+    # memory-optimal algorithm: no workspace, the reduction is not split
+    dw.fill_(float("nan"))
+    B.op_conv_bwd_filter(dev(x), dev(dy), dw, None, st, pd)
+    assert rel_err(host(dw), ref) < TOL
 
 
 def test_conv_bwd_filter_is_split_and_deterministic(B):
@@ -160,6 +164,10 @@ def test_fc(B, nio):
     def ws(which):
         nb = B.op_fc_workspace(n, i, o, which)
         return torch.empty(nb // 4, device="cuda") if nb else None
+    # without workspace the reduction is not split: same result to rounding order
+    y0 = torch.full((n, o), float("nan"), device="cuda")
+    B.op_fc_fwd(dev(x), dev(w), y0, None)
+    assert rel_err(host(y0), L.fc_fwd(x, w)) < TOL
     y = torch.full((n, o), float("nan"), device="cuda")
     B.op_fc_fwd(dev(x), dev(w), y, ws(0))
     assert rel_err(host(y), L.fc_fwd(x, w)) < TOL
@@ -271,5 +279,4 @@ def test_invalid_arguments_are_rejected(B):
     assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
-    # workspace too small for a split reduction
-    assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), None, x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG

@@ -79,13 +79,52 @@ def test_trainability_and_dyn_match_oracle(mk, batch, budget):
             assert n.last_error().startswith(ref["oom_at"] + ":")
         else:
             assert n.stats()["pool_extent_bytes"] <= budget
-    pol, _ = ms.dynamic(net, budget)
+    pol, algo, ref = ms.dynamic(net, budget)
     s = n.try_policy("dyn")
     if pol is None:
         assert s == binding.ERR_OOM_DEVICE
     else:
-        assert s == binding.OK and n.stats()["effective_policy"] == pol
+        st = n.stats()
+        assert s == binding.OK and st["effective_policy"] == pol and st["conv_algo"] == algo
+        assert st["peak_bytes"] == ref["peak_bytes"]
     n.close()
+
+
+def test_dyn_phases_and_algorithm_modes_match_oracle():
+    """Budgets placed so that each phase of vDNN_dyn decides; static policies under each algorithm mode."""
+    net = nets.alexnet(8)
+    n_conv = sum(l["type"] == "conv" for l in net["layers"])
+    peaks = {}
+    for pol in ("none", "conv", "all"):
+        for algo in ("p", "m"):
+            n = binding.Net(net, 0)
+            n.set_conv_algo(algo)
+            n.set_policy(pol)
+            ref = ms.simulate(net, pol, 1 << 50, algo)
+            st = n.stats()
+            assert [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+            assert st["peak_bytes"] == ref["peak_bytes"] and st["conv_algo"] == algo
+            assert st["n_memopt_convs"] == ref["n_memopt_convs"] == (n_conv if algo == "m" else 0)
+            peaks[pol, algo] = st["peak_bytes"]
+            n.close()
+    assert peaks["all", "m"] < peaks["all", "p"] < peaks["conv", "p"] < peaks["none", "p"]
+    seen = set()
+    for budget in (peaks["none", "p"], peaks["none", "p"] - 256, peaks["conv", "p"] - 256, peaks["all", "p"] - 256,
+                   peaks["all", "m"], peaks["all", "m"] - 256):
+        pol, algo, ref = ms.dynamic(net, budget)
+        seen.add((pol, algo))
+        n = binding.Net(net, budget)
+        s = n.try_policy("dyn")
+        if pol is None:
+            assert s == binding.ERR_OOM_DEVICE
+        else:
+            st = n.stats()
+            assert (st["effective_policy"], st["conv_algo"]) == (pol, algo), budget
+            assert st["peak_bytes"] == ref["peak_bytes"] and st["n_memopt_convs"] == ref["n_memopt_convs"]
+            assert [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+            assert st["pool_extent_bytes"] <= budget
+        n.close()
+    assert seen == {("none", "p"), ("conv", "p"), ("all", "p"), ("conv", "greedy"), (None, None)}
 
 
 def test_vgg16_b256_fits_12_gib_with_all_and_conv():
@@ -97,7 +136,7 @@ def test_vgg16_b256_fits_12_gib_with_all_and_conv():
         st = n.stats()
         assert st["pool_extent_bytes"] <= 12 * G
     n.set_policy("dyn")
-    assert n.stats()["effective_policy"] == "conv"
+    assert n.stats()["effective_policy"] == "conv" and n.stats()["conv_algo"] == "p"
     n.close()
 
 

@@ -44,8 +44,8 @@ def test_vgg16_trainability_under_12_gib():
     assert ms.simulate(net, "conv", 12 * G)["status"] == "ok"
     assert ms.baseline_bytes(net) > 12 * G
     assert ms.baseline_bytes(nets.vgg16(64)) < 12 * G
-    assert ms.dynamic(net, 12 * G)[0] == "conv"
-    assert ms.dynamic(nets.vgg16(64), 12 * G)[0] == "none"
+    assert ms.dynamic(net, 12 * G)[:2] == ("conv", "p")
+    assert ms.dynamic(nets.vgg16(64), 12 * G)[:2] == ("none", "p")
     assert ms.dynamic(net, 2 * G)[0] is None
 
 
@@ -160,3 +160,22 @@ def test_very_deep_vgg_host_fraction():
         total = sum(info["nbytes"].values())
         fracs.append(r["offloaded_bytes"] / total)
     assert all(f > 0.8 for f in fracs)
+
+
+def test_dynamic_policy_phases():
+    """Section 3.3: budgets chosen so that each phase of vDNN_dyn decides."""
+    net = nets.alexnet(8)
+    none_p = ms.simulate(net, "none", 1 << 50, "p")["peak_bytes"]
+    conv_p = ms.simulate(net, "conv", 1 << 50, "p")["peak_bytes"]
+    all_p = ms.simulate(net, "all", 1 << 50, "p")["peak_bytes"]
+    all_m = ms.simulate(net, "all", 1 << 50, "m")["peak_bytes"]
+    assert all_m < all_p <= conv_p <= none_p
+    assert ms.dynamic(net, none_p)[:2] == ("none", "p")                 # phase 2, first try
+    assert ms.dynamic(net, none_p - 256)[:2] == ("conv", "p")           # phase 2, second try
+    pol, algo, r = ms.dynamic(net, all_p - 256)                           # phase 3: greedy downgrade
+    assert algo == "greedy" and r["status"] == "ok" and r["n_memopt_convs"] >= 1 and r["peak_bytes"] <= all_p - 256
+    assert ms.dynamic(net, all_m - 256)[0] is None                        # phase 1 fails: not trainable
+    # the memory-optimal algorithm allocates no convolution workspace at all
+    tr = ms.simulate(net, "all", 1 << 50, "m")["trace"]
+    conv_layers = {i for i, l in enumerate(net["layers"]) if l["type"] == "conv"}
+    assert not [t for t in tr if t[1] == "alloc" and t[2] == "WS" and int(t[0][1:]) in conv_layers]
