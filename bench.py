@@ -22,9 +22,11 @@ if ROOT not in sys.path:
 
 GIB = 1 << 30
 FP32_MFMA_PEAK_TFLOPS = 157.3
-# HBM bytes per launch of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured.
-ROOFLINE_TRAFFIC_BYTES = None
+# HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# runs summarised in profiles/conv_fwd_vgg16_c4_2_b256.txt, each scaled by what the same counter reads
+# for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 0.832e9.
+ROOFLINE_TRAFFIC_BYTES = 2.519e9
+LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 
 
 def conv_layers_vgg16(batch):
@@ -102,7 +104,7 @@ def roofline(B, batch):
     shape (c4_2 / c4_3 forward: 256 x 512 x 28 x 28 -> 512 channels, 947 GFLOP per launch)."""
     row = conv_kernel_table(B, batch, which=("fwd",), layers=("c4_2",), iters=10)[0]
     ach = row["fwd_tflops"]
-    return dict(bound="mfma", kernel="gemm_tile_kernel<128,128,16> conv fwd, VGG-16 c4_2 b%d" % batch, achieved=ach,
+    return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 c4_2 b%d" % batch, achieved=ach,
                 peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=ROOFLINE_TRAFFIC_BYTES,
                 flop_per_launch=row["gflop"] * 1e9, ms_per_launch=row["fwd_ms"])
 
@@ -152,7 +154,13 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
                peak_bytes=st["peak_bytes"], pool_extent_bytes=st["pool_extent_bytes"], avg_bytes=st["avg_bytes_layerstep"],
                baseline_bytes=st["baseline_bytes"], offloaded_bytes=st["offloaded_bytes"], pinned_host_bytes=st["pinned_host_bytes"],
                n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
-               d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=64.0)
+               d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
+               conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"])
+    if st["offloaded_bytes"]:
+        # the step cannot be shorter than the time the host link needs for the bytes of each pass
+        link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
+        out["link_bound_img_per_s"] = net["batch"] / link_s
+        out["link_frac_of_peak"] = (st["offloaded_bytes"] + st["prefetched_bytes"]) / dt / (LINK_PEAK_GBPS * 1e9)
     n.close()
     del n
     torch.cuda.empty_cache()
