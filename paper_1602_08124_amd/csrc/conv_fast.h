@@ -224,9 +224,8 @@ struct BwdFilterFastParams {
     int tiles_m, tiles_n, splits, ksplit;
 };
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK>
 __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastParams p) {
-    constexpr int BK = 32;
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
     constexpr int LDA = BM + 1, LDB = BN + 1;

@@ -245,10 +245,10 @@ size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S
     return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK = 32>
 static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
-    auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN>;
-    constexpr size_t smem = sizeof(float) * 2 * 32 * ((BM + 1) + (BN + 1));
+    auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN, BK>;
+    constexpr size_t smem = sizeof(float) * 2 * BK * ((BM + 1) + (BN + 1));
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -257,7 +257,7 @@ static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
     }
     p.tiles_m = cdiv(p.K, BM);
     p.tiles_n = p.C * p.R * p.S / BN;
-    p.ksplit = cdiv(cdiv(p.M, p.splits), 32) * 32;
+    p.ksplit = cdiv(cdiv(p.M, p.splits), BK) * BK;
     const long long nb = (long long)p.tiles_m * p.tiles_n * p.splits;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
     VDNN_LAUNCH(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
@@ -292,8 +292,10 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
         fp.fd_q = make_fastdiv((uint32_t)Q);
         fp.splits = splits;
         hipError_t e;
-        if (C % 128 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 128, 1, 4>(fp, st) : bwdf_fast_cfg<128, 128, 2, 2>(fp, st);
-        else e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1>(fp, st);
+        // K-step 16 (33 KB of LDS, 4 workgroups per CU) for the 128-row tiles, 32 for the 64-row ones: measured
+        // 127 against 121 TFLOP/s on VGG-16's 128..512-channel layers, 105 against 94 on the 64-channel one
+        if (C % 128 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 128, 1, 4, 32>(fp, st) : bwdf_fast_cfg<128, 128, 2, 2, 16>(fp, st);
+        else e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2, 32>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1, 16>(fp, st);
         if (e != hipSuccess) return e;
         const size_t total = (size_t)K * CRS;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
