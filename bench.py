@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--budget-gib", type=float, default=12.0)
     ap.add_argument("--policies", default="none,conv,dyn,all")
+    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "overfeat", "googlenet", "vgg16"],
+                    help="vgg16 is the benchmark; the others are the paper's remaining workloads (side measurements)")
     ap.add_argument("--kernel-only", action="store_true", help="only the roofline kernel (for rocprofv3 runs)")
     ap.add_argument("--calibrate-copy", action="store_true", help="with --kernel-only: also run a 1 GiB plain copy kernel")
     ap.add_argument("--kernel-table", action="store_true", help="also time every VGG-16 convolution, three passes each")
@@ -205,6 +207,17 @@ def main():
         print(json.dumps(out))
         return
 
+    if args.workload != "vgg16":
+        # side measurement of another workload: its own batch and budget, policies as asked; one JSON line, no roofline
+        defaults = {"tiny": (8, 4 / 1024), "alexnet": (128, 1.0), "overfeat": (128, 2.0), "googlenet": (128, 3.0)}
+        batch, gib = defaults[args.workload]
+        net = nets.CONFIGS[args.workload](batch)
+        x, labels, weights = gen.make(net)
+        x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
+        res = {pol: run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else int(gib * GIB), args.steps, args.warmup)
+               for pol in args.policies.split(",")}
+        print(json.dumps({"workload": args.workload, "batch": batch, "budget_gib": gib, "policies": res}))
+        return
     net = nets.vgg16(args.batch)
     x, labels, weights = gen.make(net)
     x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()

@@ -125,6 +125,62 @@ __global__ void maxpool_bwd_kernel(const float* __restrict__ x, const float* __r
     }
 }
 
+// 3x3 windows (stride 1 or 2, any padding below 3): same rule, but the 5x5 neighbourhood that all windows
+// containing the element lie in is loaded into registers once (cells outside the image read as -inf, which
+// never wins), and the candidate windows are evaluated from registers with compile-time indices.
+template <int STRIDE>
+__global__ void maxpool3_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, int H, int W,
+                                    int P, int Q, int pad, uint32_t total, FD fw, FD fh, int relu_mask) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fw);
+        const int w = (int)(i - t * W);
+        const uint32_t nc = fdiv(t, fh);
+        const int h = (int)(t - nc * H);
+        const float* xp = x + (size_t)nc * H * W;
+        const float* gp = dy + (size_t)nc * P * Q;
+        float nb[5][5];
+#pragma unroll
+        for (int a = 0; a < 5; ++a) {
+            const int hh = h + a - 2;
+            const bool okh = (unsigned)hh < (unsigned)H;
+            const int hc = min(max(hh, 0), H - 1);
+#pragma unroll
+            for (int b = 0; b < 5; ++b) {
+                const int ww = w + b - 2;
+                const bool ok = okh && (unsigned)ww < (unsigned)W;
+                const float v = xp[hc * W + min(max(ww, 0), W - 1)];
+                nb[a][b] = ok ? v : -INFINITY;
+            }
+        }
+        float acc = 0.f;
+        // window starts (h0, w0) = (h - 2 + a, w - 2 + b), a, b in 0..2, ascending = ascending (p, q)
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+            const int hn = h - 2 + a + pad;  // = p * STRIDE
+            const int p = hn / STRIDE;
+            const bool okp = hn >= 0 && (hn % STRIDE) == 0 && p < P;
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const int wn = w - 2 + b + pad;
+                const int q = wn / STRIDE;
+                const bool okq = wn >= 0 && (wn % STRIDE) == 0 && q < Q;
+                float best = -INFINITY;
+                int br = -1, bs = -1;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s2 = 0; s2 < 3; ++s2) {
+                        const float v = nb[a + r][b + s2];
+                        if (v > best) { best = v; br = a + r; bs = b + s2; }
+                    }
+                if (okp && okq && br == 2 && bs == 2) acc += gp[p * Q + q];
+            }
+        }
+        if (relu_mask && !(nb[2][2] > 0.f)) acc = 0.f;
+        dx[i] = acc;
+    }
+}
+
 // 2x2 stride 2, no padding, H even, W a multiple of 4: one thread per two adjacent windows, float4
 // rows in, float2 out (forward) / float4 rows out (backward).  Same tie rule as the general kernel.
 __global__ void maxpool2x2_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int W, int Q2, uint32_t total, FD fq2) {
@@ -240,6 +296,15 @@ hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C,
     if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
         const uint32_t t2 = (uint32_t)((size_t)N * C * P * Q / 2);
         VDNN_LAUNCH(maxpool2x2_bwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, dy, dx, W, Q / 2, t2, make_fd(Q / 2), relu_mask);
+        return hipGetLastError();
+    }
+    if (k == 3 && (stride == 1 || stride == 2)) {
+        if (stride == 1)
+            VDNN_LAUNCH(maxpool3_bwd_kernel<1>, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)total,
+                        make_fd(W), make_fd(H), relu_mask);
+        else
+            VDNN_LAUNCH(maxpool3_bwd_kernel<2>, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)total,
+                        make_fd(W), make_fd(H), relu_mask);
         return hipGetLastError();
     }
     VDNN_LAUNCH(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad,
