@@ -78,7 +78,9 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
         flop = 2.0 * n * h * w * k * c * 9
         row = dict(layer=name, gflop=flop / 1e9)
         torch.cuda.synchronize()
-        wsp = torch.empty_like(wt)  # packed-weight workspace of the faster algorithm (ignored when it does not apply)
+        # workspace of the faster algorithm (packed W + partial sums of split tiles; ignored when it does not apply)
+        nws = max(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1), B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1), 4)
+        wsp = torch.empty(nws // 4, device="cuda")
         if "fwd" in which:
             ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp), stream, iters=iters)
             row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9

@@ -47,6 +47,27 @@ def gemm_splits(m, n, kred):
     return max(1, min(TARGET_BLOCKS // tiles, _cdiv(kred, MIN_SPLIT_LEN)))
 
 
+CONV_SLOTS = 768  # resident workgroups of the packed-weight convolution kernel (3 per CU x 256 CUs)
+
+
+def conv_packed_workspace(wcount, rows, m, cred, rs):
+    """Workspace of the packed-weight convolution kernel: a packed copy of W (rounded up to 256 bytes), plus
+    partial sums for the tiles whose reduction is split because the last round of workgroups would be
+    mostly idle (fewer than 70 % of the resident workgroups) and the job is short (under 4 full rounds)."""
+    bm = 32 if rows <= 32 else (64 if rows <= 64 else 128)
+    bn = 256 if rows <= 64 else 128
+    tiles = _cdiv(rows, bm) * _cdiv(m, bn)
+    steps = cred // 16 * rs
+    tail = tiles - tiles // CONV_SLOTS * CONV_SLOTS
+    extra = 0
+    if tail > 0 and tail * 10 < CONV_SLOTS * 7 and tiles - tail < 4 * CONV_SLOTS:
+        s = min(CONV_SLOTS // tail, 8, steps // 8)
+        if s > 1:
+            per = _cdiv(steps, s)
+            extra = tail * _cdiv(steps, per) * bm * bn * 4
+    return _cdiv(wcount, 64) * 64 * 4 + extra
+
+
 def _ws(m, n, kred):
     s = gemm_splits(m, n, kred)
     return s * m * n * 4 if s > 1 else 0
@@ -164,11 +185,15 @@ def workspace_bytes(net, info, i, phase, memopt=False):
         k, p, q = info["shape"][i]
         wbytes = 4 * k * c * l["k"] * l["k"]
         # packed copy of W for the faster kernel: reduction channels a multiple of 16, tensors below 4 GiB
+        rs = l["k"] * l["k"]
         if phase == "fwd":
-            return wbytes if c % 16 == 0 and 4 * n * c * h * w < 0xfffffff0 else 0
+            if c % 16 == 0 and 4 * n * c * h * w < 0xfffffff0:
+                return conv_packed_workspace(wbytes // 4, k, n * p * q, c, rs)
+            return 0
         need_dx = info["bufof"](l["inputs"][0]) >= 0
-        packed = wbytes if (need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0
-                            and 4 * n * k * p * q < 0xfffffff0) else 0
+        packed = 0
+        if need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0 and 4 * n * k * p * q < 0xfffffff0:
+            packed = conv_packed_workspace(wbytes // 4, c, n * h * w, k, rs)
         # backward-filter: partial sums of the split reduction; with input channels a multiple of 64
         # the faster kernel always stages dW through the workspace (at least one copy)
         if c % 64 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:

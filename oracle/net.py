@@ -51,10 +51,23 @@ def forward(net, x, labels, weights):
     return outs, loss
 
 
-def step(net, x, labels, weights, want_dx_input=False):
-    """One forward + backward pass.  Returns dict(outs, loss, dw {layer: array}, dx {tensor id: array})."""
+def step(net, x, labels, weights, want_dx_input=False, outs_override=None):
+    """One forward + backward pass.  Returns dict(outs, loss, dw {layer: array}, dx {tensor id: array}).
+
+    outs_override: {layer id: array} - layer outputs to run the BACKWARD pass from instead of this
+    function's own forward values (which are still returned in `outs`).  Backward propagation takes
+    discrete decisions from forward values (which window element is the maximum, whether an activation
+    is positive); an fp32 forward pass that differs from the fp64 one in the last bit can decide one of
+    them differently, which moves a whole gradient term.  A comparison that hands the other side's
+    forward values in here makes both sides decide on the same numbers."""
     x = np.asarray(x, np.float64)
     outs, loss = forward(net, x, labels, weights)
+    own_outs = outs
+    if outs_override:
+        outs = list(outs)
+        for i, a in outs_override.items():
+            if net["layers"][i]["type"] != "softmax_ce":
+                outs[i] = np.asarray(a, np.float64).reshape(own_outs[i].shape)
     nl = len(net["layers"])
 
     def val(i):
@@ -101,7 +114,7 @@ def step(net, x, labels, weights, want_dx_input=False):
                 c0 += cj
         else:
             raise ValueError(t)
-    return dict(outs=outs, loss=loss, dw=dw, dx=grads)
+    return dict(outs=own_outs, loss=loss, dw=dw, dx=grads)
 
 
 def sgd_update(weights, dw, lr):

@@ -38,6 +38,11 @@ struct ConvFastParams {
     int P, Q, M;        // output pixel grid, M = N*P*Q
     FastDiv fd_pq, fd_q;
     int tiles_m, tiles_n;
+    // One launch covers the logical tiles [tile_begin, tile_begin + n_tiles).  With splits > 1 each tile's
+    // reduction is cut into `splits` runs of `steps_per_split` K-steps, one workgroup each, and the raw
+    // accumulators go to partial[(tile - tile_begin) * splits + split][BM][BN] instead of the output.
+    int tile_begin, n_tiles, splits, steps_per_split;
+    float* partial;
     ConvOut out;
 };
 
@@ -58,7 +63,9 @@ __global__ void pack_weights_kernel(const float* __restrict__ w, float* __restri
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+// SPLIT = false: one workgroup per tile, whole reduction, result through the epilogue.
+// SPLIT = true : one workgroup per (tile, split), partial sums to p.partial.
+template <int BM, int BN, int WM, int WN, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
     constexpr int BK = 16;
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
@@ -74,9 +81,11 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
     float* Bs = smem + 2 * BK * LDA;
 
     const int tid = threadIdx.x;
-    const int nb = p.tiles_m * p.tiles_n;
-    const int logical = xcd_remap(blockIdx.x, nb);
-    const int tile_n = logical / p.tiles_m, tile_m = logical - tile_n * p.tiles_m;
+    const int nsplit = SPLIT ? p.splits : 1;
+    const int logical = xcd_remap(blockIdx.x, p.n_tiles * nsplit);
+    const int tile_local = logical / nsplit, split = logical - tile_local * nsplit;
+    const int tile = (SPLIT ? p.tile_begin : 0) + tile_local;
+    const int tile_n = tile / p.tiles_m, tile_m = tile - tile_n * p.tiles_m;
     const int row0 = tile_m * BM, col0 = tile_n * BN;
 
     const __amdgpu_buffer_rsrc_t rs_src = make_rsrc(p.src, p.src_bytes);
@@ -120,9 +129,13 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int RS = p.R * p.S;
-    const int nsteps = (p.Cred / 16) * RS;
+    const int total_steps = (p.Cred / 16) * RS;
+    const int step_begin = SPLIT ? split * p.steps_per_split : 0;
+    const int nsteps = SPLIT ? max(0, min(total_steps, step_begin + p.steps_per_split) - step_begin) : total_steps;
     // scalar state of the K-step being LOADED: channel block cb, tap (r, s)
-    int cb = 0, r = 0, s = 0;
+    int cb = step_begin / RS;
+    int r = (step_begin - cb * RS) / p.S;
+    int s = step_begin - cb * RS - r * p.S;
     float ra[EA], rb[EB];
 
     auto load_step = [&](int step) {
@@ -151,13 +164,15 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
         for (int j = 0; j < EB; ++j) b_st[buf * BK * LDB + j * KSB * LDB] = rb[j];
     };
 
-    load_step(0);
-    store_step(0);
+    if (nsteps > 0) {
+        load_step(step_begin);
+        store_step(0);
+    }
     __syncthreads();
     for (int kt = 0; kt < nsteps; ++kt) {
         const int cur = kt & 1;
         const bool more = kt + 1 < nsteps;
-        if (more) load_step(kt + 1);
+        if (more) load_step(step_begin + kt + 1);
         const float* at = As + cur * BK * LDA + a_off;
         const float* bt = Bs + cur * BK * LDB + b_off;
         // operand fragments are read from LDS one k-pair ahead of the MFMAs that consume them
@@ -187,6 +202,21 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
         __syncthreads();
     }
 
+    if constexpr (SPLIT) {  // raw partial sums, tile-local [BM][BN]; conv_split_fixup_kernel finishes the tile
+        float* pb = p.partial + (size_t)(tile_local * p.splits + split) * (BM * BN);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = wn * (TN * 32) + j * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int rbase = wm * (TM * 32) + i * 32 + 4 * khalf;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) pb[(rbase + 8 * (v / 4) + (v % 4)) * BN + col] = acc[i][j][v];
+            }
+        }
+        return;
+    }
+    if constexpr (SPLIT) return;
     float* obase = p.out.base(0);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -197,6 +227,26 @@ __global__ __launch_bounds__(kThreads) void conv_fast_kernel(ConvFastParams p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) p.out.put(obase, rbase + 8 * (v / 4) + (v % 4), c, acc[i][j][v]);
         }
+    }
+}
+
+// Finishes the tiles whose reduction was split: adds the partial sums of a tile in split order (fixed:
+// results do not depend on scheduling) and stores through the same epilogue as the unsplit kernel.
+// One workgroup per tile; lanes walk along pixels.
+template <int BM, int BN>
+__global__ __launch_bounds__(kThreads) void conv_split_fixup_kernel(ConvFastParams p) {
+    const int tile_local = blockIdx.x;
+    const int tile = p.tile_begin + tile_local;
+    const int tile_n = tile / p.tiles_m, tile_m = tile - tile_n * p.tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const float* pb = p.partial + (size_t)tile_local * p.splits * (BM * BN);
+    float* obase = p.out.base(0);
+    const int col = threadIdx.x % BN;
+    const ConvOut::Col c = p.out.col(col0 + col);
+    for (int row = threadIdx.x / BN; row < BM; row += kThreads / BN) {
+        float acc = pb[row * BN + col];
+        for (int s = 1; s < p.splits; ++s) acc += pb[(size_t)s * (BM * BN) + row * BN + col];
+        p.out.put(obase, row0 + row, c, acc);
     }
 }
 

@@ -59,7 +59,7 @@ def test_conv_fwd(B, shape, relu, use_ws):
     if relu:
         ref = L.relu_fwd(ref)
     nbytes = B.op_conv_fwd_workspace(x.shape, wt.shape, st, pd)
-    assert nbytes == (wt.size * 4 if c % 16 == 0 else 0)
+    assert (nbytes >= wt.size * 4) if c % 16 == 0 else (nbytes == 0)
     y = torch.full(ref.shape, float("nan"), device="cuda")
     B.op_conv_fwd(dev(x), dev(wt), y, st, pd, relu, ws=_ws(nbytes) if use_ws else None)
     assert rel_err(host(y), ref) < TOL
@@ -75,7 +75,7 @@ def test_conv_bwd_data(B, shape, use_ws):
     dy = _t((n, k, p, q), 4)
     ref = L.conv_bwd_data(dy, wt, (n, c, h, w), st, pd)
     nbytes = B.op_conv_bwd_data_workspace((n, c, h, w), wt.shape, st, pd)
-    assert nbytes == (wt.size * 4 if (k % 16 == 0 and st == 1 and pd <= r - 1) else 0)
+    assert (nbytes >= wt.size * 4) if (k % 16 == 0 and st == 1 and pd <= r - 1) else (nbytes == 0)
     dx = torch.full((n, c, h, w), float("nan"), device="cuda")
     B.op_conv_bwd_data(dev(dy), dev(wt), dx, st, pd, ws=_ws(nbytes) if use_ws else None)
     assert rel_err(host(dx), ref) < TOL
@@ -145,7 +145,7 @@ def test_conv_adjoint_identities_on_gpu(B):
     dw = torch.empty((k, c, r, r), device="cuda")
     nbytes = B.op_conv_bwd_filter_workspace((n, c, h, w), (k, c, r, r), st, pd)
     ws = torch.empty(max(nbytes, 4) // 4, device="cuda")
-    wsp = torch.empty(k * c * r * r, device="cuda")
+    wsp = _ws(max(B.op_conv_fwd_workspace(x.shape, wt.shape, st, pd), B.op_conv_bwd_data_workspace(x.shape, wt.shape, st, pd)))
     B.op_conv_fwd(x, wt, y, st, pd, ws=wsp)
     B.op_conv_bwd_data(dy, wt, dx, st, pd, ws=wsp)
     B.op_conv_bwd_filter(x, dy, dw, ws, st, pd)

@@ -278,3 +278,18 @@ def test_planted_mistakes_are_caught():
     lab = np.array([1, 2, 3, 4])
     loss, _ = L.softmax_ce(z, lab)
     assert abs(loss * 4 - np.mean(special.logsumexp(z, axis=1) - z[np.arange(4), lab])) > 1e-3  # sum vs mean
+
+
+def test_backward_from_given_forward_values():
+    """step(outs_override=...) with the oracle's own outputs is the plain step; with perturbed outputs the
+    decisions (here: which element of a pooling window wins) follow the given values."""
+    net = nets.tiny(batch=2)
+    x, labels, weights = gen.make(net, seed=3)
+    a = onet.step(net, x, labels, weights)
+    b = onet.step(net, x, labels, weights, outs_override={i: o for i, o in enumerate(a["outs"])})
+    for i in a["dw"]:
+        assert np.array_equal(a["dw"][i], b["dw"][i])
+    flipped = {1: -np.asarray(a["outs"][1])}          # ReLU output negated: every mask and arg-max changes
+    c = onet.step(net, x, labels, weights, outs_override=flipped)
+    assert np.abs(c["dw"][0] - a["dw"][0]).max() > 1e-6
+    assert all(np.array_equal(p, q) for p, q in zip(a["outs"], c["outs"]))  # reported outputs stay the oracle's own
