@@ -16,8 +16,6 @@
 
 namespace vdnn {
 
-typedef int int32x4_t __attribute__((ext_vector_type(4)));
-
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
@@ -50,7 +48,7 @@ struct ConvFastParams {
 //   forward:       row = k, value W[k][cb*16+ci][rs]                       (W is [K][C][R][S])
 //   backward-data: row = c, value W[cb*16+ci][c][RS-1-rs]  (taps flipped, reduction over output channels)
 __global__ void pack_weights_kernel(const float* __restrict__ w, float* __restrict__ wp, int K, int C, int RS, int bwd) {
-    const int rows = bwd ? C : K, red = bwd ? K : C;
+    const int rows = bwd ? C : K;
     const size_t total = (size_t)K * C * RS;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int row = (int)(i % rows);
@@ -58,7 +56,6 @@ __global__ void pack_weights_kernel(const float* __restrict__ w, float* __restri
         const int ci = kred & 15, t = kred >> 4;
         const int rs = t % RS, cb = t / RS;
         const int ch = cb * 16 + ci;
-        (void)red;
         wp[i] = bwd ? w[((size_t)ch * C + row) * RS + (RS - 1 - rs)] : w[((size_t)row * C + ch) * RS + rs];
     }
 }

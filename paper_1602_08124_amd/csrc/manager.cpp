@@ -508,7 +508,8 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p) {
         p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
         return;
     }
-    for (int i = 0; i < L; ++i) { const_cast<Layer&>(n.layers[i]).w_block = w_block[i]; const_cast<Layer&>(n.layers[i]).dw_block = dw_block[i]; }
+    p.w_block = w_block;
+    p.dw_block = dw_block;
     for (int i = 0; i < L; ++i)
         if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
     p.ok = true;
@@ -636,7 +637,7 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
     const size_t wsb0 = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;  // no block: the memory-optimal algorithm runs
     switch (l.type) {
         case VDNN_CONV:
-            HIPCHK(conv_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
+            HIPCHK(conv_fwd(x, blk(n, n.plan.w_block[o.layer]), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
                             fold_fwd(n, o.layer) ? 1 : 0, n.sc));
             break;
         case VDNN_RELU:
@@ -647,7 +648,7 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
         case VDNN_AVGPOOL: HIPCHK(avgpool_fwd(x, y, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_FC: {
             const size_t wsb = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
-            HIPCHK(fc_fwd(x, blk(n, l.w_block), y, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            HIPCHK(fc_fwd(x, blk(n, n.plan.w_block[o.layer]), y, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
             break;
         }
         case VDNN_CONCAT: {
@@ -678,8 +679,8 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
     const size_t wsb = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
     switch (l.type) {
         case VDNN_CONV:
-            HIPCHK(conv_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
-            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
+            HIPCHK(conv_bwd_filter(x, dy, blk(n, n.plan.dw_block[o.layer]), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            if (dx) HIPCHK(conv_bwd_data(dy, blk(n, n.plan.w_block[o.layer]), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
                                          fold_bwd(n, o.layer) ? x : nullptr, n.sc));
             break;
         case VDNN_RELU:
@@ -689,8 +690,8 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
         case VDNN_MAXPOOL: if (dx) HIPCHK(maxpool_bwd(x, dy, dx, N, C, H, W, l.k, l.stride, l.pad, fold_bwd(n, o.layer) ? 1 : 0, n.sc)); break;
         case VDNN_AVGPOOL: if (dx) HIPCHK(avgpool_bwd(dy, dx, N, C, H, W, l.k, l.stride, l.pad, n.sc)); break;
         case VDNN_FC:
-            HIPCHK(fc_bwd_filter(x, dy, blk(n, l.dw_block), blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
-            if (dx) HIPCHK(fc_bwd_data(dy, blk(n, l.w_block), dx, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            HIPCHK(fc_bwd_filter(x, dy, blk(n, n.plan.dw_block[o.layer]), blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
+            if (dx) HIPCHK(fc_bwd_data(dy, blk(n, n.plan.w_block[o.layer]), dx, blk(n, o.ws_block), wsb, N, C * H * W, l.out, n.sc));
             break;
         case VDNN_CONCAT: {
             int coff = 0;
@@ -876,7 +877,7 @@ vdnn_status_t vdnn_set_weights(vdnn_net_t* np, int layer, const float* w, size_t
     }
     vdnn_status_t s = ensure_device(n);
     if (s != VDNN_OK) return s;
-    HIPCHK(hipMemcpy(blk(n, n.layers[layer].w_block), w, count * 4, hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(blk(n, n.plan.w_block[layer]), w, count * 4, hipMemcpyHostToDevice));
     n.weights_set = true;
     return VDNN_OK;
 }
@@ -890,7 +891,7 @@ vdnn_status_t vdnn_get_weight_grad(vdnn_net_t* np, int layer, float* dw, size_t 
     }
     if (!n.pool) { n.err = "no step has run"; return VDNN_ERR_STATE; }
     HIPCHK(hipStreamSynchronize(n.sc));
-    HIPCHK(hipMemcpy(dw, blk(n, n.layers[layer].dw_block), count * 4, hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(dw, blk(n, n.plan.dw_block[layer]), count * 4, hipMemcpyDeviceToHost));
     return VDNN_OK;
 }
 
@@ -903,7 +904,7 @@ vdnn_status_t vdnn_get_weights(vdnn_net_t* np, int layer, float* w, size_t count
     }
     if (!n.pool) { n.err = "weights were never set"; return VDNN_ERR_STATE; }
     HIPCHK(hipStreamSynchronize(n.sc));
-    HIPCHK(hipMemcpy(w, blk(n, n.layers[layer].w_block), count * 4, hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(w, blk(n, n.plan.w_block[layer]), count * 4, hipMemcpyDeviceToHost));
     return VDNN_OK;
 }
 
@@ -911,8 +912,8 @@ vdnn_status_t vdnn_sgd_step(vdnn_net_t* np, float learning_rate) {
     if (!np) return VDNN_ERR_INVALID_ARG;
     vdnn_net& n = *np;
     if (!n.pool || !n.have_streams || !n.plan.ok) { n.err = "sgd_step before any backward pass"; return VDNN_ERR_STATE; }
-    for (const Layer& l : n.layers)
-        if (l.wcount) HIPCHK(sgd_update(blk(n, l.w_block), blk(n, l.dw_block), learning_rate, l.wcount, n.sc));
+    for (size_t i = 0; i < n.layers.size(); ++i)
+        if (n.layers[i].wcount) HIPCHK(sgd_update(blk(n, n.plan.w_block[i]), blk(n, n.plan.dw_block[i]), learning_rate, n.layers[i].wcount, n.sc));
     HIPCHK(hipStreamSynchronize(n.sc));
     return VDNN_OK;
 }

@@ -26,7 +26,6 @@ struct Layer {
     int C = 0, H = 0, W = 0;  // output shape (per image)
     int buf = 0;              // feature-map buffer holding the output (-1 = network input)
     size_t wcount = 0;        // weight elements
-    int w_block = -1, dw_block = -1;
     // Kernel fusion of in-place ReLU layers (same values, fewer passes over HBM):
     int relu_after = -1;      // CONV: the ReLU living in its output whose forward runs in the conv's epilogue
     int relu_before = -1;     // CONV / MAXPOOL: the ReLU living in its input whose backward runs in this layer's dX store
@@ -93,6 +92,7 @@ struct Plan {
     size_t offloaded = 0, prefetched = 0;
     int n_offload = 0, n_prefetch = 0, n_ondemand = 0;
     int labels_block = -1, loss_block = -1;
+    std::vector<int> w_block, dw_block;  // per layer: persistent blocks of W and dW (-1 for layers without weights)
     int algo = 0;                        // vdnn_conv_algo_t the plan was compiled with
     std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
     int n_memopt = 0;
