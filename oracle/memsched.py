@@ -47,7 +47,10 @@ def gemm_splits(m, n, kred):
     return max(1, min(TARGET_BLOCKS // tiles, _cdiv(kred, MIN_SPLIT_LEN)))
 
 
-CONV_SLOTS = 768  # resident workgroups of the packed-weight convolution kernel (3 per CU x 256 CUs)
+def conv_slots(rows):
+    """Resident workgroups of the packed-weight convolution kernel on 256 CUs: 4 per CU for the
+    128 x 128 tile (more than 64 output rows), 3 per CU for the 256-pixel tiles."""
+    return 768 if rows <= 64 else 1024
 
 
 def conv_packed_workspace(wcount, rows, m, cred, rs):
@@ -58,6 +61,7 @@ def conv_packed_workspace(wcount, rows, m, cred, rs):
     bn = 256 if rows <= 64 else 128
     tiles = _cdiv(rows, bm) * _cdiv(m, bn)
     steps = cred // 16 * rs
+    CONV_SLOTS = conv_slots(rows)
     tail = tiles - tiles // CONV_SLOTS * CONV_SLOTS
     extra = 0
     if tail > 0 and tail * 10 < CONV_SLOTS * 7 and tiles - tail < 4 * CONV_SLOTS:

@@ -104,10 +104,11 @@ static bool fast_ok(long long src_elems, long long w_elems, int cred, int R, int
     return cred % 16 == 0 && src_elems * 4 < 0xfffffff0LL && w_elems * 4 < 0x7fffffffLL && R == S;
 }
 
-// Resident workgroups of the packed-weight kernel: 3 per CU (140 registers per lane, 40-48 KB of LDS) x 256 CUs.
-// Workgroups are dispatched in rounds of this many; when the last round would be mostly empty, or when there
-// are fewer tiles than this altogether, the reduction of those tiles is split across the idle workgroups.
-constexpr int kConvSlots = 768;
+// Resident workgroups of the packed-weight kernel on 256 CUs: 4 per CU for the 128x128 tile (40 KB of LDS,
+// 128 registers per lane), 3 per CU for the 256-pixel tiles (45-48 KB of LDS).  Workgroups are dispatched in
+// rounds of this many; when the last round would be mostly empty, or when there are fewer tiles than this
+// altogether, the reduction of those tiles is split across the idle workgroups.
+static int conv_slots(int rows) { return rows <= 64 ? 768 : 1024; }
 
 struct TailSplit {
     int full_tiles, tail_tiles, splits, steps_per_split;
@@ -118,6 +119,7 @@ static TailSplit conv_tail_split(int rows, long long M, int cred, int RS) {
     const int bm = rows <= 32 ? 32 : (rows <= 64 ? 64 : 128), bn = rows <= 64 ? 256 : 128;
     const long long tiles = (long long)cdiv(rows, bm) * cdiv(M, bn);
     const int steps = cred / 16 * RS;
+    const int kConvSlots = conv_slots(rows);
     TailSplit t;
     t.full_tiles = (int)(tiles / kConvSlots * kConvSlots);
     t.tail_tiles = (int)(tiles - t.full_tiles);
