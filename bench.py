@@ -126,8 +126,12 @@ def cpu_baseline(sample_batch):
 
 
 def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
+    """policy: none | conv | all | dyn, optionally with ":m" for the memory-optimal convolution algorithm."""
     import torch
     n = B.Net(net, budget)
+    if ":" in policy:
+        policy, algo = policy.split(":")
+        n.set_conv_algo(algo)
     status = n.try_policy(policy)
     if status != B.OK:
         msg = n.last_error()

@@ -63,7 +63,35 @@ def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=Non
     return dict(loss=loss, outs=outs, dw=dw, stats=st)
 
 
-NETS = [("tiny", lambda: nets.tiny(8)), ("forkjoin", lambda: nets.fork_join(4)), ("small_vgg", small_vgg),
+def fc_only():
+    b = nets._Builder("fconly", 1, 5, 1, 1)
+    b.fc(3, relu=False)
+    return b.done()
+
+
+def one_pixel():
+    b = nets._Builder("onepx", 1, 2, 1, 1)
+    b.conv(3, 3, pad=1)
+    b.maxpool(1, 1)
+    b.fc(2, relu=False)
+    return b.done()
+
+
+def odd_sizes(batch=3):
+    """Every size off the tile grid: odd batch, odd channels, odd images, strided conv, overlapping pools, an
+    average pool with padding, two FC layers."""
+    b = nets._Builder("odd", batch, 5, 23, 19)
+    b.conv(7, 5, stride=2, pad=2)
+    b.maxpool(3, 2, pad=1)
+    b.conv(18, 3, pad=1)
+    b.conv(33, 1)
+    b.avgpool(3, 2, pad=1)
+    b.fc(21)
+    b.fc(4, relu=False)
+    return b.done()
+
+
+NETS = [("fc_only", fc_only), ("one_pixel", one_pixel), ("odd_sizes", odd_sizes), ("tiny", lambda: nets.tiny(8)), ("forkjoin", lambda: nets.fork_join(4)), ("small_vgg", small_vgg),
         ("small_alex", small_alex), ("small_googlenet", small_googlenet)]
 
 
@@ -107,7 +135,7 @@ def test_offload_is_bit_identical(B, name, mk):
             assert np.array_equal(got["dw"][i], base["dw"][i]), (pol, i)
         for i in got["outs"]:
             assert np.array_equal(got["outs"][i], base["outs"][i], equal_nan=True), (pol, i)
-        if pol != "dyn":
+        if pol != "dyn" and name != "fc_only":
             assert got["stats"]["offloaded_bytes"] > 0
             assert got["stats"]["prefetched_bytes"] == got["stats"]["offloaded_bytes"]
 
@@ -214,3 +242,39 @@ def test_dyn_greedy_downgrade_runs(B):
     assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
     for i in weights:
         assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+
+
+def test_error_paths_on_the_device(B):
+    import torch
+    net = nets.tiny(8)
+    x, labels, weights = gen.make(net)
+    n = B.Net(net, 0)
+    n.set_policy("all")
+    # a borrowed pool smaller than the plan's extent is refused at first use, with a message
+    n.attach_torch(pool_bytes=64 * 1024)
+    assert B.lib.vdnn_set_weights(n.h, 0, weights[0].ctypes.data, weights[0].size) == B.ERR_INVALID_ARG
+    assert "smaller than the plan" in n.last_error()
+    n.close()
+    n = B.Net(net, 0)
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    assert B.lib.vdnn_forward(n.h, None, None, None) == B.ERR_INVALID_ARG
+    assert B.lib.vdnn_backward(n.h) == B.ERR_STATE            # no forward yet
+    loss = n.forward(dev(x), dev(labels))
+    n.backward()
+    assert B.lib.vdnn_backward(n.h) == B.ERR_STATE            # a second backward needs a new forward
+    # a policy that cannot fit leaves the net usable with its previous plan
+    tight = B.Net(net, 1850000)   # between the peaks of "all" (1796096) and "none" (1894400)
+    assert tight.try_policy("none") == B.ERR_OOM_DEVICE
+    tight.set_policy("all")
+    assert tight.try_policy("none") == B.ERR_OOM_DEVICE and tight.stats()["effective_policy"] == "all"
+    tight.attach_torch()
+    for i, w in weights.items():
+        tight.set_weights(i, w)
+    assert tight.forward(dev(x), dev(labels)) == loss
+    tight.backward()
+    for i, w in weights.items():
+        assert np.array_equal(tight.get_weight_grad(i), n.get_weight_grad(i))
+    tight.close()
+    n.close()

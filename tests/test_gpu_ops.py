@@ -280,3 +280,45 @@ def test_invalid_arguments_are_rejected(B):
     assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), None, x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
+
+
+def _random_conv_shapes(count, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k_sz = int(r.choice([1, 2, 3, 3, 3, 5, 7]))
+        st = int(r.choice([1, 1, 1, 2, 3]))
+        pd = int(r.integers(0, k_sz))
+        c = int(r.choice([1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
+        k = int(r.choice([1, 7, 16, 33, 64, 96, 130]))
+        h, w = int(r.integers(1, 25)), int(r.integers(1, 25))
+        n = int(r.integers(1, 5))
+        if h + 2 * pd < k_sz or w + 2 * pd < k_sz:
+            continue
+        out.append((n, c, h, w, k, k_sz, st, pd))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_conv_shapes(48, 20260101), ids=lambda s: "x".join(map(str, s)))
+def test_conv_random_shapes(B, shape):
+    """Seeded random geometry (odd sizes, one-pixel images, even windows, stride 3, channel counts on both sides of
+    every tile and algorithm boundary): all three convolution passes, with and without workspace."""
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    x, wt = _t((n, c, h, w), 51), _t((k, c, r, r), 52)
+    p, q = L.out_dim(h, r, st, pd), L.out_dim(w, r, st, pd)
+    dy = _t((n, k, p, q), 53)
+    ref_y = L.conv_fwd(x, wt, st, pd)
+    ref_dx = L.conv_bwd_data(dy, wt, x.shape, st, pd)
+    ref_dw = L.conv_bwd_filter(x, dy, wt.shape, st, pd)
+    xd, wd, dyd = dev(x), dev(wt), dev(dy)
+    for use_ws in (False, True):
+        y = torch.full(ref_y.shape, float("nan"), device="cuda")
+        B.op_conv_fwd(xd, wd, y, st, pd, False, ws=_ws(B.op_conv_fwd_workspace(x.shape, wt.shape, st, pd)) if use_ws else None)
+        assert rel_err(host(y), ref_y) < TOL
+        dx = torch.full(x.shape, float("nan"), device="cuda")
+        B.op_conv_bwd_data(dyd, wd, dx, st, pd, ws=_ws(B.op_conv_bwd_data_workspace(x.shape, wt.shape, st, pd)) if use_ws else None)
+        assert rel_err(host(dx), ref_dx) < TOL
+        dw = torch.full(wt.shape, float("nan"), device="cuda")
+        B.op_conv_bwd_filter(xd, dyd, dw, _ws(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, st, pd)) if use_ws else None, st, pd)
+        assert rel_err(host(dw), ref_dw) < TOL

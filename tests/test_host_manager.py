@@ -172,3 +172,53 @@ def test_backward_without_forward_is_a_state_error():
     n = binding.Net(nets.tiny(2), 0)
     assert binding.lib.vdnn_backward(n.h) == binding.ERR_STATE
     n.close()
+
+
+def test_oversized_tensors_and_degenerate_nets():
+    # a feature map with 2^31 or more elements is rejected at create (32-bit element offsets inside kernels)
+    big = nets._Builder("big", 4096, 64, 224, 224)
+    big.conv(64, 3, pad=1)
+    big.fc(10, relu=False)
+    desc, keep = binding.make_desc(big.done())
+    h = C.c_void_p()
+    assert binding.lib.vdnn_create(C.byref(desc), 0, C.byref(h)) == binding.ERR_UNSUPPORTED
+    # smallest possible nets plan and agree with the oracle: FC only, batch 1, one-pixel images
+    for mk in (lambda: _fc_only(), lambda: _one_pixel()):
+        net = mk()
+        n = binding.Net(net, 0)
+        for pol in ("none", "conv", "all", "dyn"):
+            n.set_policy(pol)
+            ref = ms.simulate(net, n.stats()["effective_policy"], 1 << 50)
+            assert [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+        n.close()
+
+
+def _fc_only():
+    b = nets._Builder("fconly", 1, 5, 1, 1)
+    b.fc(3, relu=False)
+    return b.done()
+
+
+def _one_pixel():
+    b = nets._Builder("onepx", 1, 2, 1, 1)
+    b.conv(3, 3, pad=1)
+    b.maxpool(1, 1)
+    b.fc(2, relu=False)
+    return b.done()
+
+
+def test_trace_buffer_truncation_and_null_arguments():
+    n = binding.Net(nets.tiny(2), 0)
+    need = C.c_size_t()
+    assert binding.lib.vdnn_trace(n.h, None, 0, C.byref(need)) == binding.OK and need.value > 100
+    buf = C.create_string_buffer(16)
+    assert binding.lib.vdnn_trace(n.h, buf, 16, C.byref(need)) == binding.OK
+    assert len(buf.value) == 15  # truncated, NUL-terminated
+    assert binding.lib.vdnn_trace(n.h, None, 0, None) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_mem_stats(n.h, None) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_set_policy(n.h, 7) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_set_conv_algo(n.h, 9) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_set_weights(n.h, 1, None, 0) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_weight_count(n.h, 99) == 0 and binding.lib.vdnn_weight_count(n.h, 0) == 16 * 3 * 9
+    assert binding.lib.vdnn_output_count(n.h, 0) == 2 * 16 * 32 * 32
+    n.close()
