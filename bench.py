@@ -5,8 +5,9 @@ with the vDNN memory manager under a 12 GiB device budget.
   python bench.py [--gpus 1] [--steps K] [--warmup W]
 
 Prints ONE JSON line.  `value` is images/s with vDNN_all under 12 GiB (inputs resident in HBM);
-the `policies` object gives the same measurement for none (unlimited budget), conv, dyn and all,
-with peak pool bytes and achieved host-link GB/s.  `roofline` times the dominant kernel (the
+the `policies` object gives the same measurement for none (unlimited budget), conv, dyn, all and for
+fit (beyond the paper: per-feature-map offload set with budget-aware transfer windows), with peak pool
+bytes and achieved host-link GB/s.  `roofline` times the dominant kernel (the
 implicit-GEMM convolution) with HIP events on its own stream; `cpu_baseline` times the CPU oracle
 on a bounded sample of the same workload.
 """
@@ -126,13 +127,18 @@ def cpu_baseline(sample_batch):
 
 
 def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
-    """policy: none | conv | all | dyn, optionally with ":m" for the memory-optimal convolution algorithm."""
+    """policy: none | conv | all | dyn | fit, optionally with ":m" for the memory-optimal convolution algorithm;
+    or "set:<id>+<id>...:<fill>" for an explicit offload set with transfer windows filling <fill> per mille."""
     import torch
     n = B.Net(net, budget)
-    if ":" in policy:
-        policy, algo = policy.split(":")
-        n.set_conv_algo(algo)
-    status = n.try_policy(policy)
+    if policy.startswith("set:"):
+        _, ids, fill = policy.split(":")
+        status = n.try_offload_set({int(v) for v in ids.split("+") if v}, int(fill))
+    else:
+        if ":" in policy:
+            policy, algo = policy.split(":")
+            n.set_conv_algo(algo)
+        status = n.try_policy(policy)
     if status != B.OK:
         msg = n.last_error()
         n.close()
@@ -161,7 +167,8 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
                baseline_bytes=st["baseline_bytes"], offloaded_bytes=st["offloaded_bytes"], pinned_host_bytes=st["pinned_host_bytes"],
                n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
                d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
-               conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"])
+               conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"],
+               offload_set=sorted(n.offload_set()))
     if st["offloaded_bytes"]:
         # the step cannot be shorter than the time the host link needs for the bytes of each pass
         link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
@@ -180,7 +187,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--budget-gib", type=float, default=12.0)
-    ap.add_argument("--policies", default="none,conv,dyn,all")
+    ap.add_argument("--policies", default="none,conv,dyn,all,fit")
     ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "overfeat", "googlenet", "vgg16"],
                     help="vgg16 is the benchmark; the others are the paper's remaining workloads (side measurements)")
     ap.add_argument("--kernel-only", action="store_true", help="only the roofline kernel (for rocprofv3 runs)")

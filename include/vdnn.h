@@ -40,7 +40,11 @@ typedef enum {
 } vdnn_status_t;
 
 /* Section 3.3: static policies all / conv, the dynamic policy, and no offloading at all. */
-typedef enum { VDNN_POLICY_NONE = 0, VDNN_POLICY_ALL = 1, VDNN_POLICY_CONV = 2, VDNN_POLICY_DYN = 3 } vdnn_policy_t;
+typedef enum {
+    VDNN_POLICY_NONE = 0, VDNN_POLICY_ALL = 1, VDNN_POLICY_CONV = 2, VDNN_POLICY_DYN = 3, /* Section 3.3 */
+    VDNN_POLICY_FIT = 4,    /* not in the paper: see vdnn_set_policy */
+    VDNN_POLICY_CUSTOM = 5  /* reported after vdnn_set_offload_set; not accepted by vdnn_set_policy */
+} vdnn_policy_t;
 
 /* Section 2.2 / 3.3: per CONV layer, the performance-optimal algorithm (needs workspace) or the
  * memory-optimal one (none).  GREEDY is what phase 3 of vDNN_dyn produces: performance-optimal except
@@ -88,7 +92,7 @@ typedef struct {
     int32_t effective_policy;     /* what DYN resolved to; otherwise the policy set */
     int32_t conv_algo;            /* vdnn_conv_algo_t of the current plan */
     int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
-    int32_t reserved_;
+    int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the transfer windows fill; 0 = static schedule */
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
@@ -111,6 +115,30 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
  * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
  * stays usable with its previous plan). */
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
+/* VDNN_POLICY_FIT goes beyond the paper.  Section 3.3 motivates vDNN_dyn by the cost of offloading more
+ * than the budget asks for, and Section 3.1 by the distance between the two uses of X that a transfer can
+ * hide behind; where arithmetic is fast relative to the host link, step time is simply bytes moved over
+ * link rate.  FIT therefore
+ *   (a) picks single feature maps (candidates: what ALL would offload): starting from none, while the step
+ *       does not fit, it adds the smallest candidate whose addition makes it fit, else the largest remaining
+ *       one; performance-optimal algorithms first, then the greedy downgrade, then memory-optimal;
+ *   (b) keeps the paper's transfers (offload with the last forward consumer, fetches in findPrefetchLayer
+ *       order) but not its end-of-layer synchronisation: an offloaded X is released only when a later
+ *       allocation needs the bytes (oldest copy first), a fetch is issued as early as its destination fits,
+ *       and the compute stream waits for a fetch just before the first computation that reads it.  The
+ *       windows may fill 100 % of the budget; if the blocks then cannot be placed, 97, 94, 88, 75 % are
+ *       tried, then the static schedule (window_fill_pm in the stats says which).
+ * Values computed are bit-identical to every other policy.
+ *
+ * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
+ * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
+ * input's id); each must be one that ALL would offload, else VDNN_ERR_INVALID_ARG.  window_fill_pm: 0 = the
+ * paper's synchronisation, 1..1000 = transfer windows filling at most that share of the budget.  Uses the
+ * algorithm set by vdnn_set_conv_algo.  VDNN_ERR_OOM_DEVICE if it does not fit (previous plan kept).
+ * vdnn_get_offload_set: the feature maps the current plan offloads (ascending); count receives how many,
+ * at most cap are written. */
+vdnn_status_t vdnn_set_offload_set(vdnn_net_t*, const int32_t* buffers /*host*/, size_t count, int32_t window_fill_pm);
+vdnn_status_t vdnn_get_offload_set(const vdnn_net_t*, int32_t* buffers /*host, may be NULL*/, size_t cap, size_t* count);
 /* Algorithm for the static policies; takes effect at the next vdnn_set_policy. */
 vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);
 

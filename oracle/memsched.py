@@ -227,10 +227,11 @@ def baseline_bytes(net):
     return fm + wb + 2 * gmax + _al(wmax)
 
 
-def simulate(net, policy, budget, algo="p"):
+def simulate(net, policy, budget, algo="p", offload_set=None):
     """One training step under a static policy ("none" | "all" | "conv") and a convolution algorithm
     mode: "p" performance-optimal (workspace), "m" memory-optimal (none), "greedy" = performance-optimal
     except where that layer's workspace would overflow the budget (Section 3.3, phase 3 of vDNN_dyn).
+    offload_set: when given, exactly these buffers are offloaded (the policy argument is then unused).
     Returns a dict with status ("ok" | "oom"), where it failed, peak / average / final pool bytes,
     transfer counts, the number of CONV layers on the memory-optimal algorithm and the ordered op trace."""
     info = analyse(net)
@@ -291,7 +292,8 @@ def simulate(net, policy, budget, algo="p"):
             wsb = alloc("WS", ws) if ws else None
             if t not in IN_PLACE:
                 for b in dict.fromkeys(info["bufof"](j) for j in l["inputs"]):
-                    if info["readers"][b][-1] == i and selected(net, info, b, policy):
+                    if info["readers"][b][-1] == i and (b in offload_set if offload_set is not None
+                                                         else selected(net, info, b, policy)):
                         trace.append((where, "offload", "B%d" % b, info["nbytes"][b]))
                         st["offloaded_bytes"] += info["nbytes"][b]
                         st["n_offload"] += 1
@@ -389,3 +391,173 @@ def dynamic(net, budget):
         if r["status"] == "ok":
             return pol, "greedy", r
     return "all", "m", first
+
+
+# ---------------------------------------------------------------------------------------------------
+# Beyond the paper's three policies: "fit".
+#
+# Section 3.3 motivates vDNN_dyn with the observation that offloading more than needed costs
+# performance, and Section 3.1 (reuse distance) with the observation that a transfer can hide behind
+# whatever computation lies between the two uses of X.  On a machine whose arithmetic is fast relative
+# to its host link both become the whole story: the step time is the bytes moved divided by the link
+# rate.  "fit" therefore (a) offloads a set of feature maps chosen to move few bytes, and (b) keeps the
+# paper's transfers but drops the layer-by-layer synchronisation wherever the budget has room: an
+# offloaded X is released only when a later allocation needs its bytes, and a prefetch is issued as
+# early as its destination fits.
+# ---------------------------------------------------------------------------------------------------
+
+FILLS_PM = (1000, 970, 940, 880, 750)  # share of the budget (per mille) the windows may fill, tried in turn
+
+
+def fit_candidates(net):
+    """Buffers vDNN_all would offload, ascending id."""
+    info = analyse(net)
+    return [b for b in sorted(info["nbytes"]) if selected(net, info, b, "all")]
+
+
+def fit_select(net, budget, algo="p"):
+    """Offload set for "fit": start empty; while the step does not fit, add the SMALLEST remaining candidate
+    whose addition makes it fit, and if there is none add the LARGEST remaining one (ties: lower id) and
+    repeat.  Returns the set, or None when even every candidate together does not fit."""
+    info = analyse(net)
+    cands = fit_candidates(net)
+    chosen = set()
+
+    def fits(s):
+        return simulate(net, "none", budget, algo, offload_set=s)["status"] == "ok"
+
+    while not fits(chosen):
+        rest = [b for b in cands if b not in chosen]
+        if not rest:
+            return None
+        by_size = sorted(rest, key=lambda b: (info["nbytes"][b], b))
+        done = next((b for b in by_size if fits(chosen | {b})), None)
+        if done is not None:
+            chosen.add(done)
+            break
+        chosen.add(max(rest, key=lambda b: (info["nbytes"][b], -b)))
+    return chosen
+
+
+def _phase(where):
+    return 0 if where == "create" else (1 if where[0] == "F" else 2)
+
+
+def retime(trace, budget, fill_pm):
+    """Budget-aware transfer windows on the op trace of a static schedule.
+
+    Forward: the release of an offloaded X no longer follows its last consumer; released blocks queue up in
+    copy order and the oldest are released just before the first allocation that would otherwise pass
+    `soft` = budget * fill_pm / 1000 (whatever is left is released at the end of forward propagation).
+    Backward: fetches are taken in the order of the static schedule; each (allocation + copy) moves to the
+    earliest point, not before the previous fetch, from which the live total plus its size stays within
+    `soft` up to its original place.  A moved op is reported under the layer it now sits in."""
+    budget_al = budget // ALIGN * ALIGN
+    soft = budget_al * fill_pm // 1000 // ALIGN * ALIGN
+    create = [t for t in trace if _phase(t[0]) == 0]
+    fwd = [t for t in trace if _phase(t[0]) == 1]
+    bwd = [t for t in trace if _phase(t[0]) == 2]
+    live = sum(t[3] for t in create if t[1] == "alloc")
+
+    # ---- forward: lazy release of offloaded blocks ----
+    out = list(create)
+    pending = []           # (tag, size), oldest first
+    copying = set()
+    for t in fwd:
+        kind = t[1]
+        if kind == "offload":
+            copying.add(t[2])
+        if kind == "free" and t[2] in copying:
+            copying.discard(t[2])
+            pending.append((t[2], t[3]))
+            continue
+        if kind == "alloc":
+            while pending and live + t[3] > soft:
+                tag, size = pending.pop(0)
+                out.append((t[0], "free", tag, size))
+                live -= size
+            live += t[3]
+        elif kind == "free":
+            live -= t[3]
+        out.append(t)
+    last_fwd = fwd[-1][0] if fwd else "F0"
+    for tag, size in pending:
+        out.append((last_fwd, "free", tag, size))
+        live -= size
+
+    # ---- backward: early issue of fetches ----
+    before = []            # live total before each entry
+    for t in bwd:
+        before.append(live)
+        if t[1] == "alloc":
+            live += t[3]
+        elif t[1] == "free":
+            live -= t[3]
+    fetches = [q for q in range(len(bwd) - 1) if bwd[q][1] == "alloc" and bwd[q + 1][1] in ("prefetch", "ondemand")
+               and bwd[q + 1][2] == bwd[q][2]]
+    moved = {}             # landing index -> [original index of the allocation]
+    skip = set()
+    lo = 0
+    for q in fetches:
+        size = bwd[q][3]
+        j = q
+        while j > lo and before[j - 1] + size <= soft:   # landing before entry j - 1 keeps every state up to q within soft
+            j -= 1
+        if j < q:
+            for t in range(j, q + 1):
+                before[t] += size
+            moved.setdefault(j, []).append(q)
+            skip.update((q, q + 1))
+            lo = j
+        else:
+            lo = q + 2
+    for t, entry in enumerate(bwd):
+        for q in moved.get(t, []):
+            out.append((entry[0], "alloc", bwd[q][2], bwd[q][3]))
+            out.append((entry[0], "prefetch", bwd[q + 1][2], bwd[q + 1][3]))
+        if t not in skip:
+            out.append(entry)
+    return out
+
+
+def trace_stats(trace):
+    """Peak, final and layer-step average of the live bytes of a trace (sampled before the first entry of
+    each layer of each pass), and its transfer counts."""
+    live = peak = 0
+    samples = []
+    seen = set()
+    st = dict(offloaded_bytes=0, prefetched_bytes=0, n_offload=0, n_prefetch=0, n_ondemand_fetch=0)
+    for t in trace:
+        if t[0] != "create" and t[0] != "F-1" and t[0] not in seen:
+            seen.add(t[0])
+            samples.append(live)
+        if t[1] == "alloc":
+            live += t[3]
+            peak = max(peak, live)
+        elif t[1] == "free":
+            live -= t[3]
+        elif t[1] == "offload":
+            st["offloaded_bytes"] += t[3]
+            st["n_offload"] += 1
+        elif t[1] in ("prefetch", "ondemand"):
+            st["prefetched_bytes"] += t[3]
+            st["n_prefetch" if t[1] == "prefetch" else "n_ondemand_fetch"] += 1
+    st.update(peak_bytes=peak, cur_bytes=live, avg_bytes_layerstep=sum(samples) / len(samples) if samples else 0.0)
+    return st
+
+
+def fit(net, budget, fill_pm=1000):
+    """The "fit" policy: offload set from fit_select (performance-optimal algorithms first, then the greedy
+    downgrade, then memory-optimal everywhere), transfer windows from retime.  fill_pm = 0 keeps the static
+    schedule of the chosen set.  Returns (offload set, algorithm mode, result dict) or (None, None, None)."""
+    for algo in ("p", "greedy", "m"):
+        chosen = fit_select(net, budget, algo)
+        if chosen is not None:
+            break
+    else:
+        return None, None, None
+    r = simulate(net, "none", budget, algo, offload_set=chosen)
+    if fill_pm and budget:
+        r["trace"] = retime(r["trace"], budget, fill_pm)
+        r.update(trace_stats(r["trace"]))
+    return chosen, algo, r

@@ -23,8 +23,9 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 OK, ERR_INVALID_ARG, ERR_OOM_DEVICE, ERR_OOM_HOST, ERR_HIP, ERR_STATE, ERR_UNSUPPORTED = range(7)
-POLICY = {"none": 0, "all": 1, "conv": 2, "dyn": 3}
+POLICY = {"none": 0, "all": 1, "conv": 2, "dyn": 3, "fit": 4}
 POLICY_NAME = {v: k for k, v in POLICY.items()}
+POLICY_NAME[5] = "custom"
 ALGO = {"p": 0, "m": 1, "greedy": 2}
 ALGO_NAME = {v: k for k, v in ALGO.items()}
 LAYER_TYPE = {"conv": 0, "relu": 1, "maxpool": 2, "avgpool": 3, "fc": 4, "concat": 5, "softmax_ce": 6}
@@ -48,7 +49,7 @@ class MemStats(C.Structure):
                 ("pinned_host_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64),
                 ("n_offload", C.c_int32), ("n_prefetch", C.c_int32), ("n_ondemand_fetch", C.c_int32),
                 ("effective_policy", C.c_int32), ("conv_algo", C.c_int32), ("n_memopt_convs", C.c_int32),
-                ("reserved_", C.c_int32),
+                ("window_fill_pm", C.c_int32),
                 ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("stall_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double)]
 
@@ -61,6 +62,8 @@ EXPORTS = {
     "vdnn_create": ([C.POINTER(NetDesc), _sz, C.POINTER(_vp)], _i),
     "vdnn_set_policy": ([_vp, _i], _i),
     "vdnn_set_conv_algo": ([_vp, _i], _i),
+    "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32], _i),
+    "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
     "vdnn_forward": ([_vp, _vp, _vp, C.POINTER(C.c_float)], _i),
     "vdnn_backward": ([_vp], _i),
     "vdnn_mem_stats": ([_vp, C.POINTER(MemStats)], _i),
@@ -163,6 +166,22 @@ class Net:
     def try_policy(self, policy):
         """Returns the status instead of raising (OOM is an expected outcome)."""
         return lib.vdnn_set_policy(self.h, POLICY[policy])
+
+    def set_offload_set(self, buffers, window_fill_pm=0):
+        """Offload exactly these feature maps (-1 = network input, else producing layer id)."""
+        self._chk(self.try_offload_set(buffers, window_fill_pm))
+
+    def try_offload_set(self, buffers, window_fill_pm=0):
+        ids = sorted(buffers)
+        arr = (C.c_int32 * max(len(ids), 1))(*ids)
+        return lib.vdnn_set_offload_set(self.h, arr, len(ids), window_fill_pm)
+
+    def offload_set(self):
+        k = _sz(0)
+        self._chk(lib.vdnn_get_offload_set(self.h, None, 0, C.byref(k)))
+        arr = (C.c_int32 * max(k.value, 1))()
+        self._chk(lib.vdnn_get_offload_set(self.h, arr, k.value, C.byref(k)))
+        return set(arr[:k.value])
 
     def last_error(self):
         return lib.vdnn_last_error(self.h).decode()

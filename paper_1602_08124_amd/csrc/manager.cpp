@@ -341,7 +341,12 @@ static size_t place_blocks(Plan& p, size_t base) {
 // Compiles one training step under a static policy (NONE / ALL / CONV) and a convolution algorithm
 // mode: performance-optimal everywhere, memory-optimal everywhere, or greedy (performance-optimal
 // unless that layer's workspace would overflow the budget: Section 3.3, phase 3 of vDNN_dyn).
-static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p) {
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm);
+
+// offload_set (indexed by buffer id + 1), when given, replaces the policy's choice of feature maps;
+// place = false stops after the byte accounting (p.ok then only says that the live total fits).
+static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set = nullptr,
+                         bool place = true, int fill_pm = 0) {
     p = Plan();
     p.policy = policy;
     p.algo = algo;
@@ -397,7 +402,7 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p) {
         for (int src : l.inputs) in_bufs.push_back(buf_of(n, src));
         if (!in_place(l.type)) {
             for (int b : in_bufs) {
-                if (n.B(b).readers.back() == i && selected(n, b, policy)) {
+                if (n.B(b).readers.back() == i && (offload_set ? (bool)(*offload_set)[b + 1] : selected(n, b, policy))) {
                     Op& o = c.emit(OP_OFFLOAD);
                     o.block = res[b + 1]; o.buf = b;
                     host_off[b + 1] = pinned;
@@ -496,22 +501,156 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p) {
             if (res[b + 1] >= 0 && !n.B(b).bwd_users.empty() && n.B(b).bwd_users.front() == m) { c.release(res[b + 1]); res[b + 1] = -1; }
     }
 #undef CHECK_FAIL
-    for (Block& b : p.blocks)
-        if (b.t1 < 0) b.t1 = (int)p.ops.size() + 1;  // still live at the end of the step (nothing should be)
-    p.avg = 0.0;
-    for (size_t s : c.samples) p.avg += (double)s;
-    if (!c.samples.empty()) p.avg /= (double)c.samples.size();
     p.pinned = pinned;
+    p.w_block = w_block;
+    p.dw_block = dw_block;
+    p.offload_set.assign(L + 1, 0);
+    for (int i = 0; i < L; ++i)
+        for (int b : offloaded_at[i]) p.offload_set[b + 1] = 1;
+    for (int i = 0; i < L; ++i)
+        if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
+    if (place) finish_plan(n, p, fill_pm);
+    else p.ok = true;
+}
+
+// Budget-aware transfer windows (not in the paper, which synchronises the two streams at the end of every
+// layer: Section 3.2).  The transfers of the static schedule stay; what moves is when the pool gives up or
+// takes the memory.
+//   forward:  the release of an offloaded X (and the wait for its copy) is held back; held blocks queue in
+//             copy order and the oldest go just before the first allocation that would otherwise pass `soft`;
+//             the rest go at the end of forward propagation;
+//   backward: every fetch (allocation + copy), in the order of the static schedule, moves to the earliest
+//             point, not before the previous fetch, from which live bytes plus its size stay within `soft`
+//             up to its original place; the wait for a fetch moves to just before the first computation
+//             that reads it.
+static void retime(const vdnn_net& n, Plan& p, size_t soft) {
+    const int L = (int)n.layers.size();
+    std::vector<Op> out;
+    out.reserve(p.ops.size() + 16);
+    for (int t = 0; t < p.first_fwd_op; ++t) out.push_back(p.ops[t]);
+    size_t live = p.persistent;
+    struct Held { Op wait, free; size_t bytes; };
+    std::vector<Held> held;
+    size_t held_head = 0;
+    auto let_go = [&](int layer) {
+        Held& h = held[held_head++];
+        h.wait.layer = h.free.layer = layer;
+        out.push_back(h.wait);
+        out.push_back(h.free);
+        live -= h.bytes;
+    };
+    for (int t = p.first_fwd_op; t < p.first_bwd_op; ++t) {
+        const Op& o = p.ops[t];
+        if (o.kind == OP_WAIT_COPY && t + 1 < p.first_bwd_op && p.ops[t + 1].kind == OP_FREE && p.ops[t + 1].block == o.block) {
+            held.push_back({o, p.ops[t + 1], p.blocks[o.block].bytes});
+            ++t;
+            continue;
+        }
+        if (o.kind == OP_ALLOC) {
+            const size_t s = p.blocks[o.block].bytes;
+            while (held_head < held.size() && live + s > soft) let_go(o.layer);
+            live += s;
+        } else if (o.kind == OP_FREE) {
+            live -= p.blocks[o.block].bytes;
+        }
+        out.push_back(o);
+    }
+    while (held_head < held.size()) let_go(L - 1);
+    const int new_first_bwd = (int)out.size();
+
+    const std::vector<Op> bw(p.ops.begin() + p.first_bwd_op, p.ops.end());
+    const int nb = (int)bw.size();
+    std::vector<size_t> before(nb + 1);
+    for (int t = 0; t < nb; ++t) {
+        before[t] = live;
+        if (bw[t].kind == OP_ALLOC) live += p.blocks[bw[t].block].bytes;
+        else if (bw[t].kind == OP_FREE) live -= p.blocks[bw[t].block].bytes;
+    }
+    std::vector<std::vector<int>> landing(nb + 1);
+    std::vector<char> skip(nb + 1, 0), wait_moved(p.blocks.size(), 0);
+    int lo = 0;
+    for (int q = 0; q + 1 < nb; ++q) {
+        if (bw[q].kind != OP_ALLOC || (bw[q + 1].kind != OP_PREFETCH && bw[q + 1].kind != OP_ONDEMAND) || bw[q + 1].block != bw[q].block) continue;
+        const size_t s = p.blocks[bw[q].block].bytes;
+        int j = q;
+        while (j > lo && before[j - 1] + s <= soft) --j;
+        wait_moved[bw[q].block] = 1;
+        if (j < q) {
+            for (int t = j; t <= q; ++t) before[t] += s;
+            landing[j].push_back(q);
+            skip[q] = skip[q + 1] = 1;
+            lo = j;
+        } else {
+            lo = q + 2;
+            if (bw[q + 1].kind == OP_ONDEMAND) wait_moved[bw[q].block] = 0;  // stays an on-demand fetch, which waits by itself
+        }
+    }
+    std::vector<char> waited(p.blocks.size(), 0);
+    auto emit_landing = [&](int t) {
+        for (int q : landing[t]) {
+            Op a = bw[q], c = bw[q + 1];
+            a.layer = c.layer = bw[t].layer;
+            c.kind = OP_PREFETCH;
+            out.push_back(a);
+            out.push_back(c);
+        }
+    };
+    for (int t = 0; t < nb; ++t) {
+        const Op& o = bw[t];
+        if (o.kind != OP_SAMPLE) emit_landing(t);
+        if (!skip[t] && !(o.kind == OP_WAIT_COPY && wait_moved[o.block])) {
+            if (o.kind == OP_BWD) {  // the waits that were taken out of the static schedule: just before the first reader
+                std::vector<int> reads = o.in_blocks;
+                reads.push_back(o.out_block);
+                for (int b : reads)
+                    if (b >= 0 && wait_moved[b] && !waited[b]) {
+                        Op w;
+                        w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b;
+                        out.push_back(w);
+                        waited[b] = 1;
+                    }
+            }
+            out.push_back(o);
+        }
+        if (o.kind == OP_SAMPLE) emit_landing(t);
+    }
+    p.ops.swap(out);
+    p.first_bwd_op = new_first_bwd;
+}
+
+// Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm) {
+    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
+    p.ok = false;
+    p.fill_pm = 0;
+    if (fill_pm > 0 && n.budget) {
+        // budget * fill_pm / 1000 rounded down to a block boundary, in integers
+        retime(n, p, (size_t)((unsigned __int128)budget * (unsigned)fill_pm / 1000u) / kAlign * kAlign);
+        p.fill_pm = fill_pm;
+    }
+    size_t live = 0;
+    double sum = 0.0;
+    size_t n_samples = 0;
+    p.peak = 0; p.n_prefetch = p.n_ondemand = 0;
+    for (int t = 0; t < (int)p.ops.size(); ++t) {
+        const Op& o = p.ops[t];
+        if (o.kind == OP_ALLOC) { p.blocks[o.block].t0 = t; p.blocks[o.block].t1 = -1; live += p.blocks[o.block].bytes; p.peak = std::max(p.peak, live); }
+        else if (o.kind == OP_FREE) { p.blocks[o.block].t1 = t + 1; live -= p.blocks[o.block].bytes; }
+        else if (o.kind == OP_SAMPLE) { sum += (double)live; ++n_samples; }
+        else if (o.kind == OP_PREFETCH) p.n_prefetch++;
+        else if (o.kind == OP_ONDEMAND) p.n_ondemand++;
+    }
+    for (Block& b : p.blocks) {
+        if (b.persistent) { b.t0 = 0; b.t1 = 1 << 30; }
+        else if (b.t1 < 0) b.t1 = (int)p.ops.size() + 1;  // still live at the end of the step (nothing should be)
+    }
+    p.avg = n_samples ? sum / (double)n_samples : 0.0;
     p.extent = place_blocks(p, p.persistent);
     if (p.extent > budget) {
         p.fail_where = "placement";
         p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
         return;
     }
-    p.w_block = w_block;
-    p.dw_block = dw_block;
-    for (int i = 0; i < L; ++i)
-        if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
     p.ok = true;
 }
 
@@ -535,8 +674,62 @@ static size_t baseline_bytes(const vdnn_net& n) {
 //   1. all with the memory-optimal algorithm: can the network be trained at all;
 //   2. performance-optimal algorithms without offloading, else with conv, else with all;
 //   3. greedy per-layer algorithm downgrade under conv, then under all; else back to 1.
+//
+// VDNN_POLICY_FIT is not one of the paper's policies.  It takes the observation behind vDNN_dyn (offload no
+// more than the budget asks for) one step further: the offload set is built from single feature maps, and the
+// transfers get budget-aware windows (see retime).
+static bool fits_with(const vdnn_net& n, const std::vector<char>& set, int algo) {
+    Plan q;
+    compile_plan(n, VDNN_POLICY_FIT, algo, q, &set, false);
+    return q.ok;
+}
+
+// Start with nothing offloaded.  While the step does not fit: add the smallest remaining candidate whose
+// addition makes it fit; if there is none, add the largest remaining one (ties: lower id) and repeat.
+static bool fit_select(const vdnn_net& n, int algo, std::vector<char>& set) {
+    const int L = (int)n.layers.size();
+    std::vector<int> cands;
+    for (int b = -1; b < L; ++b)
+        if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL)) cands.push_back(b);
+    set.assign(L + 1, 0);
+    while (!fits_with(n, set, algo)) {
+        std::vector<int> rest;
+        for (int b : cands)
+            if (!set[b + 1]) rest.push_back(b);
+        if (rest.empty()) return false;
+        std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return n.B(a).count < n.B(b).count; });
+        bool done = false;
+        for (int b : rest) {
+            set[b + 1] = 1;
+            if (fits_with(n, set, algo)) { done = true; break; }
+            set[b + 1] = 0;
+        }
+        if (done) break;
+        int pick = rest[0];
+        for (int b : rest)
+            if (n.B(b).count > n.B(pick).count) pick = b;  // rest is ascending by (size, id): the first of the largest wins
+        set[pick + 1] = 1;
+    }
+    return true;
+}
+
+static const int kFills[] = {1000, 970, 940, 880, 750, 0};
+
 static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
     Plan p;
+    if (policy == VDNN_POLICY_FIT) {
+        std::vector<char> set;
+        int algo = -1;
+        for (int a : {VDNN_ALGO_PERF, VDNN_ALGO_GREEDY, VDNN_ALGO_MEM})
+            if (fit_select(n, a, set)) { algo = a; break; }
+        if (algo < 0) { n.err = "fit: the step does not fit even with every CONV/POOL input offloaded and no workspace"; return VDNN_ERR_OOM_DEVICE; }
+        for (int fill : kFills) {
+            compile_plan(n, policy, algo, p, &set, true, fill);
+            if (p.ok) { n.plan = p; n.policy = policy; n.effective = policy; return VDNN_OK; }
+        }
+        n.err = p.fail_why;
+        return VDNN_ERR_OOM_DEVICE;
+    }
     if (policy == VDNN_POLICY_DYN) {
         Plan first;
         compile_plan(n, VDNN_POLICY_ALL, VDNN_ALGO_MEM, first);
@@ -839,9 +1032,42 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t* n, vdnn_conv_algo_t algo) {
 }
 
 vdnn_status_t vdnn_set_policy(vdnn_net_t* n, vdnn_policy_t policy) {
-    if (!n || policy < VDNN_POLICY_NONE || policy > VDNN_POLICY_DYN) return VDNN_ERR_INVALID_ARG;
+    if (!n || policy < VDNN_POLICY_NONE || policy > VDNN_POLICY_FIT) return VDNN_ERR_INVALID_ARG;
     n->fwd_done = false;
     return plan_policy(*n, policy);
+}
+
+vdnn_status_t vdnn_set_offload_set(vdnn_net_t* np, const int32_t* buffers, size_t count, int32_t window_fill_pm) {
+    if (!np || (count && !buffers) || window_fill_pm < 0 || window_fill_pm > 1000) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    const int L = (int)n.layers.size();
+    std::vector<char> set(L + 1, 0);
+    for (size_t i = 0; i < count; ++i) {
+        const int b = buffers[i];
+        if (b < -1 || b >= L || !n.B(b).count || !selected(n, b, VDNN_POLICY_ALL)) {
+            n.err = fmt("set_offload_set: %d is not a feature map that a CONV or POOL layer reads and backward propagation needs", b);
+            return VDNN_ERR_INVALID_ARG;
+        }
+        set[b + 1] = 1;
+    }
+    n.fwd_done = false;
+    Plan p;
+    compile_plan(n, VDNN_POLICY_CUSTOM, n.static_algo, p, &set, true, window_fill_pm);
+    if (!p.ok) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
+    n.plan = p; n.policy = n.effective = VDNN_POLICY_CUSTOM;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_get_offload_set(const vdnn_net_t* n, int32_t* buffers, size_t cap, size_t* count) {
+    if (!n || !count) return VDNN_ERR_INVALID_ARG;
+    size_t k = 0;
+    for (size_t i = 0; i < n->plan.offload_set.size(); ++i) {
+        if (!n->plan.ok || !n->plan.offload_set[i]) continue;
+        if (buffers && k < cap) buffers[k] = (int32_t)i - 1;
+        ++k;
+    }
+    *count = k;
+    return VDNN_OK;
 }
 
 vdnn_status_t vdnn_attach_device(vdnn_net_t* np, void* pool_base, size_t pool_bytes, void* stream_compute, void* stream_memory) {
@@ -995,6 +1221,7 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
         s.n_ondemand_fetch = p.n_ondemand;
         s.conv_algo = p.algo;
         s.n_memopt_convs = p.n_memopt;
+        s.window_fill_pm = p.fill_pm;
     }
     s.fwd_ms = n->fwd_ms; s.bwd_ms = n->bwd_ms; s.stall_ms = n->stall_ms;
     s.d2h_ms = n->d2h_ms; s.h2d_ms = n->h2d_ms;

@@ -96,6 +96,8 @@ struct Plan {
     int algo = 0;                        // vdnn_conv_algo_t the plan was compiled with
     std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
     int n_memopt = 0;
+    std::vector<char> offload_set;  // buffer id + 1 -> this step offloads it
+    int fill_pm = 0;                // share of the budget (per mille) the transfer windows were allowed to fill; 0 = static schedule
 };
 
 }  // namespace vdnn

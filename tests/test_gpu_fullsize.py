@@ -121,9 +121,13 @@ def test_vgg16_b256_step_under_12_gib(B):
     # invariants: every dW finite, and identical bits under every offloading policy
     for i, d in base_dw.items():
         assert np.isfinite(d).all(), i
-    for pol in ("all", "conv", "dyn"):
+    for pol in ("all", "conv", "dyn", "fit"):
         loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G)
-        ref = ms.simulate(net, st["effective_policy"], 12 * G)
+        if pol == "fit":
+            ref = ms.fit(net, 12 * G, st["window_fill_pm"])[2]
+            assert st["offloaded_bytes"] == 3288334336 + 822083584  # c1_1's output and pool1's output
+        else:
+            ref = ms.simulate(net, st["effective_policy"], 12 * G)
         assert st["peak_bytes"] == ref["peak_bytes"] <= 12 * G
         assert st["offloaded_bytes"] == ref["offloaded_bytes"] == st["prefetched_bytes"]
         assert st["pool_extent_bytes"] <= 12 * G

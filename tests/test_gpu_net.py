@@ -4,6 +4,7 @@ invariant that offloading changes where bytes live but not a single bit of the r
 import numpy as np
 import pytest
 
+from oracle import memsched as ms
 from oracle import net as onet
 from synth import gen, nets
 from tests.gpu_util import TOL, dev, rel_err
@@ -138,6 +139,52 @@ def test_offload_is_bit_identical(B, name, mk):
         if pol != "dyn" and name != "fc_only":
             assert got["stats"]["offloaded_bytes"] > 0
             assert got["stats"]["prefetched_bytes"] == got["stats"]["offloaded_bytes"]
+
+
+@pytest.mark.parametrize("name,mk", [(a, b) for a, b in NETS if a != "fc_only"])
+def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
+    """The per-feature-map offload set with budget-aware transfer windows: budgets between the peaks of the
+    static policies, so that the windows really are partly filled; values must equal the no-offload run's bit
+    for bit, and the planned step must equal the memory-schedule oracle's."""
+    net = mk()
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 19)
+    base = run_gpu(B, net, x, labels, weights, "none", capture=False)
+    lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
+    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+    seen_offload = False
+    for budget in (lo, lo + (hi - lo) // 3, lo + 2 * (hi - lo) // 3, hi - 256):
+        n = B.Net(net, budget)
+        if n.try_policy("fit") != B.OK:   # placement may need more than the live peak right at the lower end
+            n.close()
+            continue
+        st = n.stats()
+        chosen, algo, ref = ms.fit(net, budget, st["window_fill_pm"])
+        assert n.offload_set() == chosen and [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+        n.close()
+        got = run_gpu(B, net, x, labels, weights, "fit", budget=budget, capture=False)
+        assert got["loss"] == base["loss"], budget
+        for i in weights:
+            assert np.array_equal(got["dw"][i], base["dw"][i]), (budget, i)
+        assert got["stats"]["prefetched_bytes"] == got["stats"]["offloaded_bytes"]
+        assert got["stats"]["pool_extent_bytes"] <= budget
+        seen_offload |= got["stats"]["offloaded_bytes"] > 0
+    assert seen_offload or hi - lo <= 256
+    # every candidate offloaded, windows of several sizes under a budget with room to spare
+    cands = set(ms.fit_candidates(net))
+    for fill in (1000, 800, 500):
+        n = B.Net(net, hi)
+        n.set_offload_set(cands, fill)
+        n.attach_torch()
+        for i, w in weights.items():
+            n.set_weights(i, w)
+        for _ in range(2):
+            loss = n.forward(dev(x), dev(labels))
+            n.backward()
+            assert loss == base["loss"], fill
+            for i, w in weights.items():
+                assert np.array_equal(n.get_weight_grad(i, w.shape), base["dw"][i]), (fill, i)
+        assert n.stats()["offloaded_bytes"] == ms.simulate(net, "all", 1 << 50)["offloaded_bytes"]
+        n.close()
 
 
 def test_tiny_config_under_4_mib_budget(B):

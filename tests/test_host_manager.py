@@ -222,3 +222,122 @@ def test_trace_buffer_truncation_and_null_arguments():
     assert binding.lib.vdnn_weight_count(n.h, 99) == 0 and binding.lib.vdnn_weight_count(n.h, 0) == 16 * 3 * 9
     assert binding.lib.vdnn_output_count(n.h, 0) == 2 * 16 * 32 * 32
     n.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# "fit": offload set chosen per feature map + budget-aware transfer windows
+# ---------------------------------------------------------------------------------------------------
+def _assert_plan_is(n, ref, budget):
+    st = n.stats()
+    tr = n.trace()
+    assert [t[:4] for t in tr] == [tuple(t) for t in ref["trace"]]
+    for k in ("peak_bytes", "offloaded_bytes", "prefetched_bytes", "n_offload", "n_prefetch", "n_ondemand_fetch"):
+        assert st[k] == ref[k], k
+    assert abs(st["avg_bytes_layerstep"] - ref["avg_bytes_layerstep"]) <= 1e-9 * ref["avg_bytes_layerstep"]
+    assert st["peak_bytes"] <= st["pool_extent_bytes"] <= budget
+    assert st["offloaded_bytes"] == st["prefetched_bytes"]
+    left = _check_placement(tr, st["pool_extent_bytes"])
+    assert sum(s for _, s in left.values()) == st["persistent_bytes"]
+
+
+FIT_CASES = [(nets.tiny, 8, 1850000), (nets.tiny, 8, 1400000), (nets.alexnet, 128, G), (nets.overfeat, 128, 2 * G),
+             (nets.googlenet, 128, 3 * G), (nets.vgg16, 256, 12 * G), (nets.vgg16, 256, 14 * G), (nets.vgg16, 64, 4 * G),
+             (nets.fork_join, 4, 0), (lambda b: nets.vgg(b, extra_per_group=20), 32, 4 * G), (nets.vgg16, 256, 0),
+             (nets.vgg16, 256, 60 * G)]
+
+
+@pytest.mark.parametrize("mk,batch,budget", FIT_CASES)
+def test_fit_policy_matches_oracle(mk, batch, budget):
+    net = mk(batch)
+    if mk is nets.fork_join:
+        budget = ms.simulate(net, "conv", 1 << 50)["peak_bytes"]
+    n = binding.Net(net, budget)
+    chosen, algo, _ = ms.fit(net, budget or 1 << 50, 0)
+    s = n.try_policy("fit")
+    if chosen is None:
+        assert s == binding.ERR_OOM_DEVICE
+        n.close()
+        return
+    assert s == binding.OK, n.last_error()
+    st = n.stats()
+    assert st["effective_policy"] == "fit" and st["conv_algo"] == algo
+    assert n.offload_set() == chosen
+    fill = st["window_fill_pm"]
+    assert fill in ms.FILLS_PM + (0,) and (budget or fill == 0)
+    _, _, ref = ms.fit(net, budget or 1 << 50, fill)
+    _assert_plan_is(n, ref, budget or 1 << 60)
+    # no more bytes than the paper's static policies move, whenever those fit
+    for pol in ("conv", "all"):
+        r = ms.simulate(net, pol, budget or 1 << 50)
+        if r["status"] == "ok":
+            assert st["offloaded_bytes"] <= r["offloaded_bytes"]
+    if ms.simulate(net, "none", budget or 1 << 50)["status"] == "ok":
+        assert chosen == set() and st["offloaded_bytes"] == 0
+    n.close()
+
+
+def test_explicit_offload_sets_and_window_fills_match_oracle():
+    import random
+    rnd = random.Random(7)
+    for mk, batch in ((nets.alexnet, 8), (nets.fork_join, 4), (lambda b: nets.googlenet(b, in_hw=64, modules=nets._INCEPTION[:4]), 4),
+                      (lambda b: nets.vgg(b, in_hw=32), 8)):
+        net = mk(batch)
+        cands = ms.fit_candidates(net)
+        peak_all = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
+        peak_none = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+        for trial in range(12):
+            chosen = set(b for b in cands if rnd.random() < (0.3, 0.6, 1.0)[trial % 3])
+            base = ms.simulate(net, "none", 1 << 50, offload_set=chosen)
+            budget = base["peak_bytes"] + rnd.choice((0, 256, (peak_none - peak_all) // 3, peak_none))
+            for fill in (0, 1000, 900, 600):
+                n = binding.Net(net, budget)
+                s = n.try_offload_set(chosen, fill)
+                assert s in (binding.OK, binding.ERR_OOM_DEVICE)
+                if s == binding.OK:
+                    ref = dict(base)
+                    if fill:
+                        ref["trace"] = ms.retime(base["trace"], budget, fill)
+                        ref.update(ms.trace_stats(ref["trace"]))
+                    st = n.stats()
+                    assert st["effective_policy"] == "custom" and st["window_fill_pm"] == fill and n.offload_set() == chosen
+                    _assert_plan_is(n, ref, budget)
+                else:
+                    assert "placement" in n.last_error() or fill == 0
+                n.close()
+    # what is not a CONV/POOL input that backward needs is refused
+    net = nets.tiny(8)
+    n = binding.Net(net, 0)
+    fc_in = [i for i, l in enumerate(net["layers"]) if l["type"] == "fc"][0] - 1
+    assert n.try_offload_set({net["layers"][fc_in]["inputs"][0] if net["layers"][fc_in]["type"] == "relu" else fc_in}) == binding.ERR_INVALID_ARG
+    assert n.try_offload_set({len(net["layers"])}) == binding.ERR_INVALID_ARG
+    assert n.try_offload_set({-2}) == binding.ERR_INVALID_ARG
+    assert n.try_offload_set(set(), 1001) == binding.ERR_INVALID_ARG
+    assert n.try_policy("fit") == binding.OK and n.offload_set() == set()
+    n.close()
+
+
+def test_window_invariants_on_oracle_traces():
+    """Properties of retime that hold whatever the implementation: same multiset of ops, every block released
+    once, peak within max(static peak, soft), forward releases in copy order, a fetch never later than in the
+    static schedule."""
+    for mk, batch, budget in ((nets.vgg16, 256, 12 * G), (nets.alexnet, 128, G), (nets.googlenet, 128, 3 * G)):
+        net = mk(batch)
+        chosen, algo, base = ms.fit(net, budget, 0)
+        for fill in ms.FILLS_PM:
+            tr = ms.retime(base["trace"], budget, fill)
+            assert sorted(t[1:] for t in tr if t[1] != "prefetch" and t[1] != "ondemand") == \
+                sorted(t[1:] for t in base["trace"] if t[1] != "prefetch" and t[1] != "ondemand")
+            assert sorted(t[2:] for t in tr if t[1] in ("prefetch", "ondemand")) == \
+                sorted(t[2:] for t in base["trace"] if t[1] in ("prefetch", "ondemand"))
+            st = ms.trace_stats(tr)
+            soft = budget * fill // 1000
+            assert st["peak_bytes"] <= max(base["peak_bytes"], soft) and st["cur_bytes"] == base["cur_bytes"]
+            offl = [t[2] for t in tr if t[1] == "offload"]
+            frees = [t[2] for t in tr if t[1] == "free" and t[0][0] == "F" and t[2] in offl]
+            assert frees == offl
+            pos = {(t[1], t[2]): i for i, t in enumerate(tr) if t[1] in ("prefetch", "ondemand")}
+            layer_of = lambda w: int(w[1:])
+            for t in base["trace"]:
+                if t[1] in ("prefetch", "ondemand"):
+                    new = [x for x in tr if x[1] in ("prefetch", "ondemand") and x[2] == t[2]][0]
+                    assert layer_of(new[0]) >= layer_of(t[0])      # backward runs from high layer ids to low
