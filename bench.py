@@ -128,12 +128,12 @@ def cpu_baseline(sample_batch):
 
 def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
     """policy: none | conv | all | dyn | fit, optionally with ":m" for the memory-optimal convolution algorithm;
-    or "set:<id>+<id>...:<fill>" for an explicit offload set with transfer windows filling <fill> per mille."""
+    or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille."""
     import torch
     n = B.Net(net, budget)
     if policy.startswith("set:"):
-        _, ids, fill = policy.split(":")
-        status = n.try_offload_set({int(v) for v in ids.split("+") if v}, int(fill))
+        _, ids, *fills = policy.split(":")
+        status = n.try_offload_set({int(v) for v in ids.split("+") if v}, *[int(f) for f in fills])
     else:
         if ":" in policy:
             policy, algo = policy.split(":")
@@ -167,7 +167,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
                baseline_bytes=st["baseline_bytes"], offloaded_bytes=st["offloaded_bytes"], pinned_host_bytes=st["pinned_host_bytes"],
                n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
                d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
-               conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"],
+               conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"], window_fill_bwd_pm=st["window_fill_bwd_pm"],
                offload_set=sorted(n.offload_set()))
     if st["offloaded_bytes"]:
         # the step cannot be shorter than the time the host link needs for the bytes of each pass

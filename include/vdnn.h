@@ -92,7 +92,8 @@ typedef struct {
     int32_t effective_policy;     /* what DYN resolved to; otherwise the policy set */
     int32_t conv_algo;            /* vdnn_conv_algo_t of the current plan */
     int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
-    int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the transfer windows fill; 0 = static schedule */
+    int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the forward transfer windows fill; 0 = static schedule */
+    int32_t window_fill_bwd_pm;   /* the same for backward propagation */
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
@@ -126,18 +127,29 @@ vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
  *       order) but not its end-of-layer synchronisation: an offloaded X is released only when a later
  *       allocation needs the bytes (oldest copy first), a fetch is issued as early as its destination fits,
  *       and the compute stream waits for a fetch just before the first computation that reads it.  The
- *       windows may fill 100 % of the budget; if the blocks then cannot be placed, 97, 94, 88, 75 % are
- *       tried, then the static schedule (window_fill_pm in the stats says which).
+ *       windows may fill 100 % of the budget; if the blocks then cannot be placed inside it, smaller shares
+ *       are tried (100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 %; 0 = the static schedule): first the
+ *       largest share for forward propagation, then under it the largest for backward propagation
+ *       (window_fill_pm and window_fill_bwd_pm in the stats say which pair was adopted).
  * Values computed are bit-identical to every other policy.
  *
  * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
  * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
- * input's id); each must be one that ALL would offload, else VDNN_ERR_INVALID_ARG.  window_fill_pm: 0 = the
- * paper's synchronisation, 1..1000 = transfer windows filling at most that share of the budget.  Uses the
+ * input's id); each must be one that ALL would offload, else VDNN_ERR_INVALID_ARG.  window_fill_pm,
+ * window_fill_bwd_pm (forward, backward): 0 = the paper's synchronisation, 1..1000 = transfer windows filling
+ * at most that share of the budget.  Uses the
  * algorithm set by vdnn_set_conv_algo.  VDNN_ERR_OOM_DEVICE if it does not fit (previous plan kept).
  * vdnn_get_offload_set: the feature maps the current plan offloads (ascending); count receives how many,
- * at most cap are written. */
-vdnn_status_t vdnn_set_offload_set(vdnn_net_t*, const int32_t* buffers /*host*/, size_t count, int32_t window_fill_pm);
+ * at most cap are written.
+ *
+ * With transfer windows, a block larger than the part size (default 128 MiB) is copied, released and fetched
+ * in at most 32 equal pieces, each following rule (b) on its own, so that one long copy does not hold up
+ * every allocation behind it.  vdnn_set_window_part changes the part size (0 = whole blocks only); it takes
+ * effect at the next vdnn_set_policy / vdnn_set_offload_set.  In the statistics n_offload, n_prefetch and
+ * n_ondemand_fetch count copies, so a block that moves in pieces counts once per piece. */
+vdnn_status_t vdnn_set_offload_set(vdnn_net_t*, const int32_t* buffers /*host*/, size_t count, int32_t window_fill_pm,
+                                   int32_t window_fill_bwd_pm);
+vdnn_status_t vdnn_set_window_part(vdnn_net_t*, size_t part_bytes);
 vdnn_status_t vdnn_get_offload_set(const vdnn_net_t*, int32_t* buffers /*host, may be NULL*/, size_t cap, size_t* count);
 /* Algorithm for the static policies; takes effect at the next vdnn_set_policy. */
 vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);

@@ -406,7 +406,9 @@ def dynamic(net, budget):
 # early as its destination fits.
 # ---------------------------------------------------------------------------------------------------
 
-FILLS_PM = (1000, 970, 940, 880, 750)  # share of the budget (per mille) the windows may fill, tried in turn
+# Share of the budget (per mille) the windows may fill: the library takes the largest forward share for which the
+# blocks can be placed inside the budget (backward on the static schedule), then the largest backward share.
+FILLS_PM = (1000, 990, 980, 970, 960, 950, 940, 930, 920, 910, 900, 880, 860, 840, 820, 800, 750, 700, 600, 500, 0)
 
 
 def fit_candidates(net):
@@ -443,40 +445,76 @@ def _phase(where):
     return 0 if where == "create" else (1 if where[0] == "F" else 2)
 
 
-def retime(trace, budget, fill_pm):
+PART_BYTES = 128 << 20   # transfers of larger blocks are cut into at most MAX_PARTS pieces of about this size
+MAX_PARTS = 32
+
+
+def parts_of(size, raw, part_bytes):
+    """[(block bytes, bytes to copy)] of the pieces of a block of `size` (aligned) bytes holding `raw` bytes."""
+    if not part_bytes or size <= part_bytes:
+        return [(size, raw)]
+    k = min(MAX_PARTS, _cdiv(size, part_bytes))
+    step = _al(_cdiv(size, k))
+    out = []
+    for i in range(k):
+        lo = i * step
+        if lo >= size:
+            break
+        out.append((min(step, size - lo), max(0, min(step, raw - lo))))
+    return out
+
+
+def retime(trace, budget, fill_pm, part_bytes=PART_BYTES, fill_bwd_pm=None):
     """Budget-aware transfer windows on the op trace of a static schedule.
 
     Forward: the release of an offloaded X no longer follows its last consumer; released blocks queue up in
-    copy order and the oldest are released just before the first allocation that would otherwise pass
-    `soft` = budget * fill_pm / 1000 (whatever is left is released at the end of forward propagation).
+    copy order; an allocation that would pass `soft` = budget * fill_pm / 1000 first releases the oldest of
+    them, until the live total fits AND at least as many bytes were released as it asks for (pieces of one
+    block leave from its low end upwards, so the request finds one contiguous range); whatever is left is
+    released at the end of forward propagation.
     Backward: fetches are taken in the order of the static schedule; each (allocation + copy) moves to the
     earliest point, not before the previous fetch, from which the live total plus its size stays within
-    `soft` up to its original place.  A moved op is reported under the layer it now sits in."""
+    `soft` (with fill_bwd_pm, default fill_pm) up to its original place.  A moved op is reported under the
+    layer it now sits in.
+    Blocks larger than part_bytes are copied, released and fetched in pieces ("B7#2" = third piece of B7),
+    each piece following the same two rules on its own; backward fetches the pieces from the top one down
+    (the mirror image of the order in which forward gave them up)."""
     budget_al = budget // ALIGN * ALIGN
     soft = budget_al * fill_pm // 1000 // ALIGN * ALIGN
+    soft_bwd = soft if fill_bwd_pm is None else budget_al * fill_bwd_pm // 1000 // ALIGN * ALIGN
     create = [t for t in trace if _phase(t[0]) == 0]
     fwd = [t for t in trace if _phase(t[0]) == 1]
     bwd = [t for t in trace if _phase(t[0]) == 2]
     live = sum(t[3] for t in create if t[1] == "alloc")
+    size_of = {}           # tag -> aligned size of the block while it is live
 
-    # ---- forward: lazy release of offloaded blocks ----
+    def pieces(tag, raw):
+        ps = parts_of(size_of[tag], raw, part_bytes)
+        return [(tag if len(ps) == 1 else "%s#%d" % (tag, i), sz, rw) for i, (sz, rw) in enumerate(ps)]
+
+    # ---- forward: copies in pieces, lazy release of offloaded blocks ----
     out = list(create)
     pending = []           # (tag, size), oldest first
-    copying = set()
+    copying = {}           # tag -> raw bytes being offloaded
     for t in fwd:
         kind = t[1]
         if kind == "offload":
-            copying.add(t[2])
+            copying[t[2]] = t[3]
+            out.extend((t[0], "offload", tag, rw) for tag, _, rw in pieces(t[2], t[3]))
+            continue
         if kind == "free" and t[2] in copying:
-            copying.discard(t[2])
-            pending.append((t[2], t[3]))
+            pending.extend((tag, sz) for tag, sz, _ in pieces(t[2], copying.pop(t[2])))
             continue
         if kind == "alloc":
-            while pending and live + t[3] > soft:
-                tag, size = pending.pop(0)
-                out.append((t[0], "free", tag, size))
-                live -= size
+            if live + t[3] > soft:
+                released = 0
+                while pending and (live + t[3] > soft or released < t[3]):
+                    tag, size = pending.pop(0)
+                    out.append((t[0], "free", tag, size))
+                    live -= size
+                    released += size
             live += t[3]
+            size_of[t[2]] = t[3]
         elif kind == "free":
             live -= t[3]
         out.append(t)
@@ -485,36 +523,43 @@ def retime(trace, budget, fill_pm):
         out.append((last_fwd, "free", tag, size))
         live -= size
 
-    # ---- backward: early issue of fetches ----
+    # ---- backward: early issue of fetches, piece by piece ----
     before = []            # live total before each entry
     for t in bwd:
         before.append(live)
         if t[1] == "alloc":
             live += t[3]
+            size_of[t[2]] = t[3]
         elif t[1] == "free":
             live -= t[3]
     fetches = [q for q in range(len(bwd) - 1) if bwd[q][1] == "alloc" and bwd[q + 1][1] in ("prefetch", "ondemand")
                and bwd[q + 1][2] == bwd[q][2]]
-    moved = {}             # landing index -> [original index of the allocation]
-    skip = set()
+    moved = {}             # landing index -> [(tag, size, raw)] in issue order
+    stay = {}              # original index -> pieces that stay there
     lo = 0
     for q in fetches:
-        size = bwd[q][3]
-        j = q
-        while j > lo and before[j - 1] + size <= soft:   # landing before entry j - 1 keeps every state up to q within soft
-            j -= 1
-        if j < q:
-            for t in range(j, q + 1):
-                before[t] += size
-            moved.setdefault(j, []).append(q)
-            skip.update((q, q + 1))
-            lo = j
-        else:
-            lo = q + 2
+        for tag, size, raw in reversed(pieces(bwd[q][2], bwd[q + 1][3])):
+            j = q
+            while j > lo and before[j - 1] + size <= soft_bwd:   # landing before entry j - 1 keeps every state up to q within soft
+                j -= 1
+            if j < q:
+                for t in range(j, q + 1):
+                    before[t] += size
+                moved.setdefault(j, []).append((tag, size, raw))
+                lo = j
+            else:
+                stay.setdefault(q, []).append((tag, size, raw))
+                lo = q + 2
+    skip = set()
+    for q in fetches:
+        skip.update((q, q + 1))
     for t, entry in enumerate(bwd):
-        for q in moved.get(t, []):
-            out.append((entry[0], "alloc", bwd[q][2], bwd[q][3]))
-            out.append((entry[0], "prefetch", bwd[q + 1][2], bwd[q + 1][3]))
+        for tag, size, raw in moved.get(t, []):
+            out.append((entry[0], "alloc", tag, size))
+            out.append((entry[0], "prefetch", tag, raw))
+        for tag, size, raw in stay.get(t, []):
+            out.append((entry[0], "alloc", tag, size))
+            out.append((entry[0], bwd[t + 1][1], tag, raw))
         if t not in skip:
             out.append(entry)
     return out
@@ -546,18 +591,24 @@ def trace_stats(trace):
     return st
 
 
-def fit(net, budget, fill_pm=1000):
+def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, fill_bwd_pm=None):
     """The "fit" policy: offload set from fit_select (performance-optimal algorithms first, then the greedy
     downgrade, then memory-optimal everywhere), transfer windows from retime.  fill_pm = 0 keeps the static
-    schedule of the chosen set.  Returns (offload set, algorithm mode, result dict) or (None, None, None)."""
+    schedule of the chosen set.  extra: that many more candidates, largest first (ties: lower id), join the
+    set (what the library does when it finds no placement of the blocks inside the budget).
+    Returns (offload set, algorithm mode, result dict) or (None, None, None)."""
     for algo in ("p", "greedy", "m"):
         chosen = fit_select(net, budget, algo)
         if chosen is not None:
             break
     else:
         return None, None, None
+    info = analyse(net)
+    for _ in range(extra):
+        rest = [b for b in fit_candidates(net) if b not in chosen]
+        chosen.add(max(rest, key=lambda b: (info["nbytes"][b], -b)))
     r = simulate(net, "none", budget, algo, offload_set=chosen)
-    if fill_pm and budget:
-        r["trace"] = retime(r["trace"], budget, fill_pm)
+    if (fill_pm or fill_bwd_pm) and budget:
+        r["trace"] = retime(r["trace"], budget, fill_pm, part_bytes, fill_bwd_pm)
         r.update(trace_stats(r["trace"]))
     return chosen, algo, r

@@ -49,7 +49,7 @@ class MemStats(C.Structure):
                 ("pinned_host_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64),
                 ("n_offload", C.c_int32), ("n_prefetch", C.c_int32), ("n_ondemand_fetch", C.c_int32),
                 ("effective_policy", C.c_int32), ("conv_algo", C.c_int32), ("n_memopt_convs", C.c_int32),
-                ("window_fill_pm", C.c_int32),
+                ("window_fill_pm", C.c_int32), ("window_fill_bwd_pm", C.c_int32),
                 ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("stall_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double)]
 
@@ -62,8 +62,9 @@ EXPORTS = {
     "vdnn_create": ([C.POINTER(NetDesc), _sz, C.POINTER(_vp)], _i),
     "vdnn_set_policy": ([_vp, _i], _i),
     "vdnn_set_conv_algo": ([_vp, _i], _i),
-    "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32], _i),
+    "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32, C.c_int32], _i),
     "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
+    "vdnn_set_window_part": ([_vp, _sz], _i),
     "vdnn_forward": ([_vp, _vp, _vp, C.POINTER(C.c_float)], _i),
     "vdnn_backward": ([_vp], _i),
     "vdnn_mem_stats": ([_vp, C.POINTER(MemStats)], _i),
@@ -167,14 +168,18 @@ class Net:
         """Returns the status instead of raising (OOM is an expected outcome)."""
         return lib.vdnn_set_policy(self.h, POLICY[policy])
 
-    def set_offload_set(self, buffers, window_fill_pm=0):
+    def set_offload_set(self, buffers, window_fill_pm=0, window_fill_bwd_pm=None):
         """Offload exactly these feature maps (-1 = network input, else producing layer id)."""
-        self._chk(self.try_offload_set(buffers, window_fill_pm))
+        self._chk(self.try_offload_set(buffers, window_fill_pm, window_fill_bwd_pm))
 
-    def try_offload_set(self, buffers, window_fill_pm=0):
+    def try_offload_set(self, buffers, window_fill_pm=0, window_fill_bwd_pm=None):
         ids = sorted(buffers)
         arr = (C.c_int32 * max(len(ids), 1))(*ids)
-        return lib.vdnn_set_offload_set(self.h, arr, len(ids), window_fill_pm)
+        fb = window_fill_pm if window_fill_bwd_pm is None else window_fill_bwd_pm
+        return lib.vdnn_set_offload_set(self.h, arr, len(ids), window_fill_pm, fb)
+
+    def set_window_part(self, part_bytes):
+        self._chk(lib.vdnn_set_window_part(self.h, part_bytes))
 
     def offload_set(self):
         k = _sz(0)

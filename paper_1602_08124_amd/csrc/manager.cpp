@@ -269,36 +269,66 @@ struct Compiler {
 
 // Placement of the transient blocks above the persistent region.  Blocks are taken in a priority
 // order and each takes the lowest offset at which it overlaps no already placed block whose lifetime
-// intersects its own.  The live-byte peak is the lower bound of the address range.  Three orders are
-// tried first (by size; by lifetime; by size x lifetime); if none reaches the bound, the same three
-// priorities are perturbed with seeded noise for a bounded number of rounds and the best placement
+// intersects its own.  The live-byte peak is the lower bound of the address range.  Four orders are
+// tried first (by size; by lifetime; by size x lifetime; by allocation time); if none reaches the bound, the
+// same priorities are perturbed with seeded noise for a bounded number of rounds and the best placement
 // wins.  On the paper's workloads this reaches the bound (no fragmentation) within a few rounds.
+//
+// A block that moves in pieces occupies a staircase in (time x address): one rectangle per piece, at fixed
+// distances from the block's offset.  It takes the lowest offset at which none of its rectangles meets a
+// placed one; later blocks see its rectangles one by one and can move into the part of the range a piece
+// has left (or not yet taken).
+namespace {
+struct Rect { size_t off, bytes; int t0, t1; };
+}
+
 static size_t place_with_keys(Plan& p, size_t base, const std::vector<int>& ids, const std::vector<double>& key,
                               std::vector<size_t>& offsets) {
     std::vector<int> order(ids.size());
     for (size_t i = 0; i < ids.size(); ++i) order[i] = (int)i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key[a] > key[b]; });
-    std::vector<int> placed;
+    std::vector<Rect> placed;  // absolute offsets
     offsets.assign(p.blocks.size(), 0);
     size_t extent = base;
     std::vector<std::pair<size_t, size_t>> conf;
+    std::vector<Rect> own, near;
     for (int oi : order) {
         const int id = ids[oi];
         const Block& b = p.blocks[id];
-        conf.clear();
-        for (int o : placed) {
-            const Block& q = p.blocks[o];
-            if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({offsets[o], q.bytes});
-        }
-        std::sort(conf.begin(), conf.end());
         size_t off = base;
-        for (auto& c : conf) {
-            if (off + b.bytes <= c.first) break;
-            off = std::max(off, c.first + c.second);
+        if (b.parts == 1) {
+            conf.clear();
+            for (const Rect& q : placed)
+                if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({q.off, q.bytes});
+            std::sort(conf.begin(), conf.end());
+            for (auto& c : conf) {
+                if (off + b.bytes <= c.first) break;
+                off = std::max(off, c.first + c.second);
+            }
+            placed.push_back({off, b.bytes, b.t0, b.t1});
+        } else {
+            own.clear();
+            for (int i = 0; i < b.parts; ++i) own.push_back({(size_t)i * b.part_bytes, b.piece_bytes(i), b.part_t0[i], b.part_t1[i]});
+            near.clear();
+            for (const Rect& q : placed)
+                if (q.t0 < b.t1 && b.t0 < q.t1) near.push_back(q);
+            auto fits = [&](size_t o) {
+                for (const Rect& r : own)
+                    for (const Rect& q : near)
+                        if (q.t0 < r.t1 && r.t0 < q.t1 && o + r.off < q.off + q.bytes && q.off < o + r.off + r.bytes) return false;
+                return true;
+            };
+            std::vector<size_t> cands{base};
+            for (const Rect& r : own)
+                for (const Rect& q : near)
+                    if (q.t0 < r.t1 && r.t0 < q.t1 && q.off + q.bytes >= base + r.off) cands.push_back(q.off + q.bytes - r.off);
+            std::sort(cands.begin(), cands.end());
+            for (size_t o : cands)
+                if (fits(o)) { off = o; break; }   // the candidate above every neighbour always fits
+            for (const Rect& r : own) placed.push_back({off + r.off, r.bytes, r.t0, r.t1});
         }
         offsets[id] = off;
         extent = std::max(extent, off + b.bytes);
-        placed.push_back(id);
     }
     return extent;
 }
@@ -309,18 +339,20 @@ static size_t place_blocks(Plan& p, size_t base) {
         if (!p.blocks[i].persistent) ids.push_back(i);
     if (ids.empty()) return base;
     const size_t n = ids.size();
-    std::vector<double> size(n), life(n), area(n), key(n);
+    std::vector<double> size(n), life(n), area(n), start(n), key(n);
     for (size_t i = 0; i < n; ++i) {
         const Block& b = p.blocks[ids[i]];
-        // ties: earlier blocks first (the tiny bias keeps the order deterministic and stable)
+        // ties: earlier blocks first (the sort is stable)
         size[i] = (double)b.bytes;
         life[i] = (double)(b.t1 - b.t0);
         area[i] = size[i] * life[i];
+        start[i] = (double)(p.ops.size() + 2 - b.t0);  // allocation order: what a run-time first-fit allocator would do
     }
     std::vector<size_t> best, cur;
     size_t best_extent = (size_t)-1;
-    const std::vector<double>* base_keys[3] = {&size, &life, &area};
-    for (int kind = 0; kind < 3; ++kind) {
+    constexpr int kKinds = 4;
+    const std::vector<double>* base_keys[kKinds] = {&size, &life, &area, &start};
+    for (int kind = 0; kind < kKinds; ++kind) {
         const size_t e = place_with_keys(p, base, ids, *base_keys[kind], cur);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
@@ -328,7 +360,7 @@ static size_t place_blocks(Plan& p, size_t base) {
     auto next = [&]() { rng = rng * 6364136223846793005ull + 1442695040888963407ull; return (double)(rng >> 11) / 9007199254740992.0; };
     const double noises[4] = {0.1, 0.3, 0.6, 1.0};
     for (int round = 0; round < 300 && best_extent > p.peak; ++round) {
-        const std::vector<double>& k0 = *base_keys[(int)(next() * 3) % 3];
+        const std::vector<double>& k0 = *base_keys[(int)(next() * kKinds) % kKinds];
         const double noise = noises[(int)(next() * 4) % 4];
         for (size_t i = 0; i < n; ++i) key[i] = k0[i] * (1.0 + noise * (next() - 0.5));
         const size_t e = place_with_keys(p, base, ids, key, cur);
@@ -341,12 +373,12 @@ static size_t place_blocks(Plan& p, size_t base) {
 // Compiles one training step under a static policy (NONE / ALL / CONV) and a convolution algorithm
 // mode: performance-optimal everywhere, memory-optimal everywhere, or greedy (performance-optimal
 // unless that layer's workspace would overflow the budget: Section 3.3, phase 3 of vDNN_dyn).
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm);
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm);
 
 // offload_set (indexed by buffer id + 1), when given, replaces the policy's choice of feature maps;
 // place = false stops after the byte accounting (p.ok then only says that the live total fits).
 static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set = nullptr,
-                         bool place = true, int fill_pm = 0) {
+                         bool place = true, int fill_pm = 0, int fill_bwd_pm = 0) {
     p = Plan();
     p.policy = policy;
     p.algo = algo;
@@ -509,7 +541,7 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
         for (int b : offloaded_at[i]) p.offload_set[b + 1] = 1;
     for (int i = 0; i < L; ++i)
         if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
-    if (place) finish_plan(n, p, fill_pm);
+    if (place) finish_plan(n, p, fill_pm, fill_bwd_pm);
     else p.ok = true;
 }
 
@@ -517,16 +549,29 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
 // layer: Section 3.2).  The transfers of the static schedule stay; what moves is when the pool gives up or
 // takes the memory.
 //   forward:  the release of an offloaded X (and the wait for its copy) is held back; held blocks queue in
-//             copy order and the oldest go just before the first allocation that would otherwise pass `soft`;
-//             the rest go at the end of forward propagation;
+//             copy order; an allocation that would pass `soft` first lets the oldest go, until the live total
+//             fits and at least as many bytes went as it asks for (pieces of one block go from its low end
+//             upwards, so the request finds one contiguous range); the rest go at the end of forward
+//             propagation;
 //   backward: every fetch (allocation + copy), in the order of the static schedule, moves to the earliest
-//             point, not before the previous fetch, from which live bytes plus its size stay within `soft`
-//             up to its original place; the wait for a fetch moves to just before the first computation
-//             that reads it.
-static void retime(const vdnn_net& n, Plan& p, size_t soft) {
+//             point, not before the previous fetch, from which live bytes plus its size stay within
+//             `soft_bwd` up to its original place; a block that moves in pieces is fetched from its top piece
+//             down, the mirror image of forward; the wait for a fetch moves to just before the first
+//             computation that reads it.
+static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
     const int L = (int)n.layers.size();
+    constexpr int kMaxParts = 32;
+    // Blocks larger than the part size move in at most kMaxParts pieces of equal (aligned) size.
+    auto split = [&](int block) {
+        Block& b = p.blocks[block];
+        if (!n.part_bytes || b.bytes <= n.part_bytes) return 1;
+        const size_t k = std::min<size_t>(kMaxParts, (b.bytes + n.part_bytes - 1) / n.part_bytes);
+        b.part_bytes = align_up((b.bytes + k - 1) / k);
+        b.parts = (int)((b.bytes + b.part_bytes - 1) / b.part_bytes);
+        return b.parts;
+    };
     std::vector<Op> out;
-    out.reserve(p.ops.size() + 16);
+    out.reserve(p.ops.size() + 64);
     for (int t = 0; t < p.first_fwd_op; ++t) out.push_back(p.ops[t]);
     size_t live = p.persistent;
     struct Held { Op wait, free; size_t bytes; };
@@ -541,14 +586,31 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
     };
     for (int t = p.first_fwd_op; t < p.first_bwd_op; ++t) {
         const Op& o = p.ops[t];
+        if (o.kind == OP_OFFLOAD) {
+            const int k = split(o.block);
+            for (int i = 0; i < k; ++i) {
+                Op c = o;
+                c.part = k == 1 ? -1 : i;
+                out.push_back(c);
+            }
+            continue;
+        }
         if (o.kind == OP_WAIT_COPY && t + 1 < p.first_bwd_op && p.ops[t + 1].kind == OP_FREE && p.ops[t + 1].block == o.block) {
-            held.push_back({o, p.ops[t + 1], p.blocks[o.block].bytes});
+            const Block& b = p.blocks[o.block];
+            for (int i = 0; i < b.parts; ++i) {
+                Held h{o, p.ops[t + 1], b.piece_bytes(i)};
+                h.wait.part = h.free.part = b.parts == 1 ? -1 : i;
+                held.push_back(h);
+            }
             ++t;
             continue;
         }
         if (o.kind == OP_ALLOC) {
             const size_t s = p.blocks[o.block].bytes;
-            while (held_head < held.size() && live + s > soft) let_go(o.layer);
+            if (live + s > soft) {
+                const size_t live0 = live;
+                while (held_head < held.size() && (live + s > soft || live0 - live < s)) let_go(o.layer);
+            }
             live += s;
         } else if (o.kind == OP_FREE) {
             live -= p.blocks[o.block].bytes;
@@ -560,89 +622,123 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
 
     const std::vector<Op> bw(p.ops.begin() + p.first_bwd_op, p.ops.end());
     const int nb = (int)bw.size();
-    std::vector<size_t> before(nb + 1);
+    std::vector<size_t> before(nb + 1);  // live bytes before each backward op of the static schedule
     for (int t = 0; t < nb; ++t) {
         before[t] = live;
         if (bw[t].kind == OP_ALLOC) live += p.blocks[bw[t].block].bytes;
         else if (bw[t].kind == OP_FREE) live -= p.blocks[bw[t].block].bytes;
     }
-    std::vector<std::vector<int>> landing(nb + 1);
-    std::vector<char> skip(nb + 1, 0), wait_moved(p.blocks.size(), 0);
+    struct Piece { int q, part; };
+    std::vector<std::vector<Piece>> landing(nb + 1), stay(nb + 1);
+    std::vector<char> skip(nb + 1, 0);
+    std::vector<std::vector<int>> await(p.blocks.size());  // block -> pieces whose copy the first reader has to wait for
     int lo = 0;
     for (int q = 0; q + 1 < nb; ++q) {
         if (bw[q].kind != OP_ALLOC || (bw[q + 1].kind != OP_PREFETCH && bw[q + 1].kind != OP_ONDEMAND) || bw[q + 1].block != bw[q].block) continue;
-        const size_t s = p.blocks[bw[q].block].bytes;
-        int j = q;
-        while (j > lo && before[j - 1] + s <= soft) --j;
-        wait_moved[bw[q].block] = 1;
-        if (j < q) {
-            for (int t = j; t <= q; ++t) before[t] += s;
-            landing[j].push_back(q);
-            skip[q] = skip[q + 1] = 1;
-            lo = j;
-        } else {
-            lo = q + 2;
-            if (bw[q + 1].kind == OP_ONDEMAND) wait_moved[bw[q].block] = 0;  // stays an on-demand fetch, which waits by itself
+        const int block = bw[q].block;
+        const int k = split(block);
+        skip[q] = skip[q + 1] = 1;
+        for (int i = k - 1; i >= 0; --i) {
+            const size_t s = p.blocks[block].piece_bytes(i);
+            const int part = k == 1 ? -1 : i;
+            int j = q;
+            while (j > lo && before[j - 1] + s <= soft_bwd) --j;
+            if (j < q) {
+                for (int t = j; t <= q; ++t) before[t] += s;
+                landing[j].push_back({q, part});
+                await[block].push_back(part);
+                lo = j;
+            } else {
+                stay[q].push_back({q, part});
+                if (bw[q + 1].kind == OP_PREFETCH) await[block].push_back(part);  // an on-demand fetch waits by itself
+                lo = q + 2;
+            }
         }
     }
     std::vector<char> waited(p.blocks.size(), 0);
-    auto emit_landing = [&](int t) {
-        for (int q : landing[t]) {
-            Op a = bw[q], c = bw[q + 1];
-            a.layer = c.layer = bw[t].layer;
-            c.kind = OP_PREFETCH;
+    auto emit_pieces = [&](const std::vector<Piece>& list, int layer, bool moved) {
+        for (const Piece& pc : list) {
+            Op a = bw[pc.q], c = bw[pc.q + 1];
+            a.layer = c.layer = layer;
+            a.part = c.part = pc.part;
+            if (moved) c.kind = OP_PREFETCH;
             out.push_back(a);
             out.push_back(c);
         }
     };
     for (int t = 0; t < nb; ++t) {
         const Op& o = bw[t];
-        if (o.kind != OP_SAMPLE) emit_landing(t);
-        if (!skip[t] && !(o.kind == OP_WAIT_COPY && wait_moved[o.block])) {
-            if (o.kind == OP_BWD) {  // the waits that were taken out of the static schedule: just before the first reader
+        if (o.kind != OP_SAMPLE) emit_pieces(landing[t], o.layer, true);
+        emit_pieces(stay[t], o.layer, false);
+        // the waits of the static schedule for fetches are dropped: each fetch is awaited just before its first reader
+        if (!skip[t] && !(o.kind == OP_WAIT_COPY && !await[o.block].empty())) {
+            if (o.kind == OP_BWD) {
                 std::vector<int> reads = o.in_blocks;
                 reads.push_back(o.out_block);
                 for (int b : reads)
-                    if (b >= 0 && wait_moved[b] && !waited[b]) {
-                        Op w;
-                        w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b;
-                        out.push_back(w);
+                    if (b >= 0 && !await[b].empty() && !waited[b]) {
+                        for (int part : await[b]) {
+                            Op w;
+                            w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b; w.part = part;
+                            out.push_back(w);
+                        }
                         waited[b] = 1;
                     }
             }
             out.push_back(o);
         }
-        if (o.kind == OP_SAMPLE) emit_landing(t);
+        if (o.kind == OP_SAMPLE) emit_pieces(landing[t], o.layer, true);
     }
     p.ops.swap(out);
     p.first_bwd_op = new_first_bwd;
 }
 
 // Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm) {
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     p.ok = false;
-    p.fill_pm = 0;
-    if (fill_pm > 0 && n.budget) {
-        // budget * fill_pm / 1000 rounded down to a block boundary, in integers
-        retime(n, p, (size_t)((unsigned __int128)budget * (unsigned)fill_pm / 1000u) / kAlign * kAlign);
+    p.fill_pm = p.fill_bwd_pm = 0;
+    if ((fill_pm > 0 || fill_bwd_pm > 0) && n.budget) {
+        // budget * fill / 1000 rounded down to a block boundary, in integers
+        auto soft = [&](int pm) { return (size_t)((unsigned __int128)budget * (unsigned)pm / 1000u) / kAlign * kAlign; };
+        retime(n, p, soft(fill_pm), soft(fill_bwd_pm));
         p.fill_pm = fill_pm;
+        p.fill_bwd_pm = fill_bwd_pm;
     }
     size_t live = 0;
     double sum = 0.0;
     size_t n_samples = 0;
-    p.peak = 0; p.n_prefetch = p.n_ondemand = 0;
+    p.peak = 0; p.n_offload = p.n_prefetch = p.n_ondemand = 0;
+    for (Block& b : p.blocks) {
+        b.t0 = b.t1 = -1;
+        b.part_t0.assign(b.parts, -1);
+        b.part_t1.assign(b.parts, -1);
+    }
     for (int t = 0; t < (int)p.ops.size(); ++t) {
         const Op& o = p.ops[t];
-        if (o.kind == OP_ALLOC) { p.blocks[o.block].t0 = t; p.blocks[o.block].t1 = -1; live += p.blocks[o.block].bytes; p.peak = std::max(p.peak, live); }
-        else if (o.kind == OP_FREE) { p.blocks[o.block].t1 = t + 1; live -= p.blocks[o.block].bytes; }
+        if (o.kind == OP_ALLOC || o.kind == OP_FREE) {
+            Block& b = p.blocks[o.block];
+            const size_t bytes = o.part < 0 ? b.bytes : b.piece_bytes(o.part);
+            for (int i = 0; i < b.parts; ++i) {
+                if (o.part >= 0 && i != o.part) continue;
+                if (o.kind == OP_ALLOC) b.part_t0[i] = t; else b.part_t1[i] = t + 1;
+            }
+            if (o.kind == OP_ALLOC) { if (b.t0 < 0) b.t0 = t; live += bytes; p.peak = std::max(p.peak, live); }
+            else { b.t1 = t + 1; live -= bytes; }
+        }
         else if (o.kind == OP_SAMPLE) { sum += (double)live; ++n_samples; }
+        else if (o.kind == OP_OFFLOAD) p.n_offload++;   // copies issued: a block that moves in pieces counts once per piece
         else if (o.kind == OP_PREFETCH) p.n_prefetch++;
         else if (o.kind == OP_ONDEMAND) p.n_ondemand++;
     }
+    const int t_end = (int)p.ops.size() + 1;
     for (Block& b : p.blocks) {
         if (b.persistent) { b.t0 = 0; b.t1 = 1 << 30; }
-        else if (b.t1 < 0) b.t1 = (int)p.ops.size() + 1;  // still live at the end of the step (nothing should be)
+        else if (b.t1 < 0) b.t1 = t_end;  // still live at the end of the step (nothing should be)
+        for (int i = 0; i < b.parts; ++i) {
+            if (b.persistent) { b.part_t0[i] = 0; b.part_t1[i] = 1 << 30; }
+            else if (b.part_t1[i] < 0) b.part_t1[i] = t_end;
+        }
     }
     p.avg = n_samples ? sum / (double)n_samples : 0.0;
     p.extent = place_blocks(p, p.persistent);
@@ -713,7 +809,7 @@ static bool fit_select(const vdnn_net& n, int algo, std::vector<char>& set) {
     return true;
 }
 
-static const int kFills[] = {1000, 970, 940, 880, 750, 0};
+static const int kFills[] = {1000, 990, 980, 970, 960, 950, 940, 930, 920, 910, 900, 880, 860, 840, 820, 800, 750, 700, 600, 500, 0};
 
 static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
     Plan p;
@@ -723,9 +819,31 @@ static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
         for (int a : {VDNN_ALGO_PERF, VDNN_ALGO_GREEDY, VDNN_ALGO_MEM})
             if (fit_select(n, a, set)) { algo = a; break; }
         if (algo < 0) { n.err = "fit: the step does not fit even with every CONV/POOL input offloaded and no workspace"; return VDNN_ERR_OOM_DEVICE; }
-        for (int fill : kFills) {
-            compile_plan(n, policy, algo, p, &set, true, fill);
-            if (p.ok) { n.plan = p; n.policy = policy; n.effective = policy; return VDNN_OK; }
+        // The set was chosen by live bytes; when no placement of the blocks fits the budget either (the live
+        // peak then sits within a fraction of a percent of it), the largest remaining candidate is added.
+        for (;;) {
+            // the largest forward share that can be placed with backward on the static schedule, then the largest
+            // backward share under it
+            int ff = -1;
+            for (int f : kFills) {
+                compile_plan(n, policy, algo, p, &set, true, f, 0);
+                if (p.ok) { ff = f; break; }
+            }
+            if (ff >= 0) {
+                Plan q;
+                for (int fb : kFills) {
+                    if (fb == 0) break;  // p already holds (ff, 0)
+                    compile_plan(n, policy, algo, q, &set, true, ff, fb);
+                    if (q.ok) { p = q; break; }
+                }
+                n.plan = p; n.policy = policy; n.effective = policy;
+                return VDNN_OK;
+            }
+            int pick = -2;
+            for (int b = -1; b < (int)n.layers.size(); ++b)
+                if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL) && !set[b + 1] && (pick == -2 || n.B(b).count > n.B(pick).count)) pick = b;
+            if (pick == -2) break;
+            set[pick + 1] = 1;
         }
         n.err = p.fail_why;
         return VDNN_ERR_OOM_DEVICE;
@@ -908,7 +1026,8 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
 // Replays ops [first, last) of the plan.
 static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* input, const int32_t* labels) {
     Plan& p = n.plan;
-    if ((int)n.copy_done_event.size() != (int)p.blocks.size()) n.copy_done_event.assign(p.blocks.size(), -1);
+    constexpr int kSlots = 33;  // per block: the whole block, or up to 32 pieces
+    if (n.copy_done_event.size() != p.blocks.size() * kSlots) n.copy_done_event.assign(p.blocks.size() * kSlots, -1);
     for (int t = first; t < last; ++t) {
         const Op& o = p.ops[t];
         switch (o.kind) {
@@ -932,13 +1051,18 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
                 NEWEV(e0);
                 NEWEV(e1);
                 HIPCHK(hipEventRecord(n.events[e0], n.sm));
-                const size_t bytes = n.B(o.buf).count * 4;
-                char* host = n.pinned + p.blocks[o.block].host_off;
-                if (o.kind == OP_OFFLOAD) HIPCHK(hipMemcpyAsync(host, blk(n, o.block), bytes, hipMemcpyDeviceToHost, n.sm));
-                else HIPCHK(hipMemcpyAsync(blk(n, o.block), host, bytes, hipMemcpyHostToDevice, n.sm));
+                const Block& b = p.blocks[o.block];
+                const size_t bytes = o.part < 0 ? b.raw : b.piece_raw(o.part);
+                const size_t shift = o.part < 0 ? 0 : (size_t)o.part * b.part_bytes;
+                char* host = n.pinned + b.host_off + shift;
+                char* dev = (char*)blk(n, o.block) + shift;
+                if (bytes) {
+                    if (o.kind == OP_OFFLOAD) HIPCHK(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, n.sm));
+                    else HIPCHK(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, n.sm));
+                }
                 HIPCHK(hipEventRecord(n.events[e1], n.sm));
                 n.copies.push_back({e0, e1, bytes, o.kind == OP_OFFLOAD ? 0 : 1});
-                n.copy_done_event[o.block] = e1;
+                n.copy_done_event[(size_t)o.block * kSlots + o.part + 1] = e1;
                 if (o.kind == OP_ONDEMAND) {
                     n.stalls.push_back({e_ready, e1});
                     HIPCHK(hipStreamWaitEvent(n.sc, n.events[e1], 0));
@@ -946,7 +1070,7 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
                 break;
             }
             case OP_WAIT_COPY: {
-                const int e1 = n.copy_done_event[o.block];
+                const int e1 = n.copy_done_event[(size_t)o.block * kSlots + o.part + 1];
                 if (e1 < 0) { n.err = "internal: wait for a copy that was never issued"; return VDNN_ERR_STATE; }
                 NEWEV(e_here);
                 HIPCHK(hipEventRecord(n.events[e_here], n.sc));
@@ -1037,8 +1161,9 @@ vdnn_status_t vdnn_set_policy(vdnn_net_t* n, vdnn_policy_t policy) {
     return plan_policy(*n, policy);
 }
 
-vdnn_status_t vdnn_set_offload_set(vdnn_net_t* np, const int32_t* buffers, size_t count, int32_t window_fill_pm) {
-    if (!np || (count && !buffers) || window_fill_pm < 0 || window_fill_pm > 1000) return VDNN_ERR_INVALID_ARG;
+vdnn_status_t vdnn_set_offload_set(vdnn_net_t* np, const int32_t* buffers, size_t count, int32_t window_fill_pm, int32_t window_fill_bwd_pm) {
+    if (!np || (count && !buffers) || window_fill_pm < 0 || window_fill_pm > 1000 || window_fill_bwd_pm < 0 || window_fill_bwd_pm > 1000)
+        return VDNN_ERR_INVALID_ARG;
     vdnn_net& n = *np;
     const int L = (int)n.layers.size();
     std::vector<char> set(L + 1, 0);
@@ -1052,9 +1177,15 @@ vdnn_status_t vdnn_set_offload_set(vdnn_net_t* np, const int32_t* buffers, size_
     }
     n.fwd_done = false;
     Plan p;
-    compile_plan(n, VDNN_POLICY_CUSTOM, n.static_algo, p, &set, true, window_fill_pm);
+    compile_plan(n, VDNN_POLICY_CUSTOM, n.static_algo, p, &set, true, window_fill_pm, window_fill_bwd_pm);
     if (!p.ok) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
     n.plan = p; n.policy = n.effective = VDNN_POLICY_CUSTOM;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_window_part(vdnn_net_t* n, size_t part_bytes) {
+    if (!n) return VDNN_ERR_INVALID_ARG;
+    n->part_bytes = part_bytes;
     return VDNN_OK;
 }
 
@@ -1222,6 +1353,7 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
         s.conv_algo = p.algo;
         s.n_memopt_convs = p.n_memopt;
         s.window_fill_pm = p.fill_pm;
+        s.window_fill_bwd_pm = p.fill_bwd_pm;
     }
     s.fwd_ms = n->fwd_ms; s.bwd_ms = n->bwd_ms; s.stall_ms = n->stall_ms;
     s.d2h_ms = n->d2h_ms; s.h2d_ms = n->h2d_ms;
@@ -1238,11 +1370,23 @@ vdnn_status_t vdnn_trace(const vdnn_net_t* n, char* buf, size_t cap, size_t* nee
     for (const Op& o : p.ops) {
         std::string where = o.phase == 0 ? "create" : fmt("%c%d", o.phase == 1 ? 'F' : 'B', o.layer);
         switch (o.kind) {
-            case OP_ALLOC: s += fmt("%s alloc %s %zu %zu\n", where.c_str(), p.blocks[o.block].tag.c_str(), p.blocks[o.block].bytes, p.blocks[o.block].offset); break;
-            case OP_FREE: s += fmt("%s free %s %zu %zu\n", where.c_str(), p.blocks[o.block].tag.c_str(), p.blocks[o.block].bytes, p.blocks[o.block].offset); break;
-            case OP_OFFLOAD: s += fmt("%s offload B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
-            case OP_PREFETCH: s += fmt("%s prefetch B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
-            case OP_ONDEMAND: s += fmt("%s ondemand B%d %zu\n", where.c_str(), o.buf, n->B(o.buf).count * 4); break;
+            case OP_ALLOC:
+            case OP_FREE: {
+                const Block& b = p.blocks[o.block];
+                const char* what = o.kind == OP_ALLOC ? "alloc" : "free";
+                if (o.part < 0) s += fmt("%s %s %s %zu %zu\n", where.c_str(), what, b.tag.c_str(), b.bytes, b.offset);
+                else s += fmt("%s %s %s#%d %zu %zu\n", where.c_str(), what, b.tag.c_str(), o.part, b.piece_bytes(o.part), b.offset + (size_t)o.part * b.part_bytes);
+                break;
+            }
+            case OP_OFFLOAD:
+            case OP_PREFETCH:
+            case OP_ONDEMAND: {
+                const Block& b = p.blocks[o.block];
+                const char* what = o.kind == OP_OFFLOAD ? "offload" : (o.kind == OP_PREFETCH ? "prefetch" : "ondemand");
+                if (o.part < 0) s += fmt("%s %s B%d %zu\n", where.c_str(), what, o.buf, b.raw);
+                else s += fmt("%s %s B%d#%d %zu\n", where.c_str(), what, o.buf, o.part, b.piece_raw(o.part));
+                break;
+            }
             case OP_FWD:
             case OP_BWD: s += fmt("%s compute %s\n", where.c_str(), type_name(n->layers[o.layer].type)); break;
             default: break;

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -60,6 +61,7 @@ struct Op {
     int phase;       // 0 create, 1 forward, 2 backward
     int layer;       // -1 for the input load
     int block = -1;  // ALLOC/FREE/OFFLOAD/PREFETCH/ONDEMAND: the block; WAIT_COPY: block whose copy is awaited
+    int part = -1;   // the same ops on one piece of a block that moves in pieces (-1 = the whole block)
     int buf = -2;    // buffer id for transfers
     // compute ops
     std::vector<int> in_blocks;    // blocks holding the layer's inputs
@@ -78,6 +80,17 @@ struct Block {
     size_t offset = 0;
     bool persistent = false;
     size_t host_off = 0;  // offset in the pinned arena (buffers that are offloaded)
+    // A block that is copied in pieces: `parts` pieces of part_bytes (the last one shorter), which share the
+    // block's address range but are released (forward) or allocated (backward) one by one.
+    int parts = 1;
+    size_t part_bytes = 0;
+    std::vector<int> part_t0, part_t1;  // lifetime of each piece, op indices [t0, t1)
+    size_t piece_bytes(int i) const { return parts == 1 ? bytes : std::min(part_bytes, bytes - (size_t)i * part_bytes); }
+    size_t piece_raw(int i) const {
+        if (parts == 1) return raw;
+        const size_t lo = (size_t)i * part_bytes;
+        return raw > lo ? std::min(part_bytes, raw - lo) : 0;
+    }
 };
 
 struct Plan {
@@ -97,7 +110,7 @@ struct Plan {
     std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
     int n_memopt = 0;
     std::vector<char> offload_set;  // buffer id + 1 -> this step offloads it
-    int fill_pm = 0;                // share of the budget (per mille) the transfer windows were allowed to fill; 0 = static schedule
+    int fill_pm = 0, fill_bwd_pm = 0;  // share of the budget (per mille) the transfer windows may fill in forward / backward; 0 = static schedule
 };
 
 }  // namespace vdnn
@@ -107,6 +120,7 @@ struct vdnn_net {
     std::vector<vdnn::Layer> layers;
     std::vector<vdnn::Buffer> bufs;  // index = buffer id + 1
     size_t budget = 0;               // 0 = unlimited
+    size_t part_bytes = (size_t)128 << 20;  // transfer windows move larger blocks in pieces of about this size (0 = whole blocks)
     int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
     int static_algo = VDNN_ALGO_PERF;
     vdnn::Plan plan;

@@ -125,6 +125,7 @@ def test_vgg16_b256_step_under_12_gib(B):
         loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G)
         if pol == "fit":
             ref = ms.fit(net, 12 * G, st["window_fill_pm"])[2]
+            assert st["n_offload"] == ref["n_offload"] > 2   # the two feature maps move in pieces
             assert st["offloaded_bytes"] == 3288334336 + 822083584  # c1_1's output and pool1's output
         else:
             ref = ms.simulate(net, st["effective_policy"], 12 * G)

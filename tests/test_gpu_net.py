@@ -8,6 +8,7 @@ from oracle import memsched as ms
 from oracle import net as onet
 from synth import gen, nets
 from tests.gpu_util import TOL, dev, rel_err
+from tests.sched_util import fit_reference
 
 pytestmark = pytest.mark.gpu
 
@@ -43,10 +44,12 @@ def small_googlenet(batch=2):
     return nets.googlenet(batch, in_hw=64, modules=mods)
 
 
-def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=None):
+def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=None, part=None):
     n = B.Net(net, budget)
     if algo:
         n.set_conv_algo(algo)
+    if part is not None:
+        n.set_window_part(part)
     n.set_policy(policy)
     n.attach_torch()
     for i, w in weights.items():
@@ -152,16 +155,17 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
     lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
     hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
     seen_offload = False
+    part = 8192   # the feature maps of these nets are small: cut them into pieces all the same
     for budget in (lo, lo + (hi - lo) // 3, lo + 2 * (hi - lo) // 3, hi - 256):
         n = B.Net(net, budget)
+        n.set_window_part(part)
         if n.try_policy("fit") != B.OK:   # placement may need more than the live peak right at the lower end
             n.close()
             continue
-        st = n.stats()
-        chosen, algo, ref = ms.fit(net, budget, st["window_fill_pm"])
+        chosen, algo, ref = fit_reference(n, net, budget, part)
         assert n.offload_set() == chosen and [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
         n.close()
-        got = run_gpu(B, net, x, labels, weights, "fit", budget=budget, capture=False)
+        got = run_gpu(B, net, x, labels, weights, "fit", budget=budget, capture=False, part=part)
         assert got["loss"] == base["loss"], budget
         for i in weights:
             assert np.array_equal(got["dw"][i], base["dw"][i]), (budget, i)
@@ -173,6 +177,7 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
     cands = set(ms.fit_candidates(net))
     for fill in (1000, 800, 500):
         n = B.Net(net, hi)
+        n.set_window_part((4096, 65536, 0)[fill % 3])
         n.set_offload_set(cands, fill)
         n.attach_torch()
         for i, w in weights.items():
