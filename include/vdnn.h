@@ -124,20 +124,25 @@ vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
  *       does not fit, it adds the smallest candidate whose addition makes it fit, else the largest remaining
  *       one; performance-optimal algorithms first, then the greedy downgrade, then memory-optimal;
  *   (b) keeps the paper's transfers (offload with the last forward consumer, fetches in findPrefetchLayer
- *       order) but not its end-of-layer synchronisation: an offloaded X is released only when a later
- *       allocation needs the bytes (oldest copy first), a fetch is issued as early as its destination fits,
- *       and the compute stream waits for a fetch just before the first computation that reads it.  The
- *       windows may fill 100 % of the budget; if the blocks then cannot be placed inside it, smaller shares
- *       are tried (100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 %; 0 = the static schedule): first the
- *       largest share for forward propagation, then under it the largest for backward propagation
- *       (window_fill_pm and window_fill_bwd_pm in the stats say which pair was adopted).
+ *       order) but not its end-of-layer synchronisation:
+ *       forward: an offloaded X is released only when a later allocation would otherwise pass a share of the
+ *       budget (oldest copy first).  While X is away its address range is lent out: a feature map that is not
+ *       offloaded itself and had to release something becomes a tenant of the block released last, lined up
+ *       from the low end of that range;
+ *       backward: the fetch of X returns to the range X had (once its tenants are gone), and every fetch is
+ *       issued as early as its own address range is free in the placement of the blocks; the compute stream
+ *       waits for a fetch just before the first computation that reads it.
+ *       The forward share is the largest of 100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 % for which the
+ *       blocks can be placed inside the budget (window_fill_pm in the stats; window_fill_bwd_pm = 1000 when
+ *       fetches are issued early).
  * Values computed are bit-identical to every other policy.
  *
  * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
  * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
  * input's id); each must be one that ALL would offload, else VDNN_ERR_INVALID_ARG.  window_fill_pm,
- * window_fill_bwd_pm (forward, backward): 0 = the paper's synchronisation, 1..1000 = transfer windows filling
- * at most that share of the budget.  Uses the
+ * window_fill_bwd_pm (forward, backward): 0 = the paper's synchronisation, 1..1000 = transfer windows; forward
+ * releases are postponed while live bytes stay within that share of the budget, backward fetches are issued
+ * early while live bytes stay within that share of the budget and the address range is free.  Uses the
  * algorithm set by vdnn_set_conv_algo.  VDNN_ERR_OOM_DEVICE if it does not fit (previous plan kept).
  * vdnn_get_offload_set: the feature maps the current plan offloads (ascending); count receives how many,
  * at most cap are written.

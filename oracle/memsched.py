@@ -406,8 +406,8 @@ def dynamic(net, budget):
 # early as its destination fits.
 # ---------------------------------------------------------------------------------------------------
 
-# Share of the budget (per mille) the windows may fill: the library takes the largest forward share for which the
-# blocks can be placed inside the budget (backward on the static schedule), then the largest backward share.
+# Share of the budget (per mille) the forward windows may fill: the library takes the largest for which the blocks
+# can be placed inside the budget.
 FILLS_PM = (1000, 990, 980, 970, 960, 950, 940, 930, 920, 910, 900, 880, 860, 840, 820, 800, 750, 700, 600, 500, 0)
 
 
@@ -464,38 +464,48 @@ def parts_of(size, raw, part_bytes):
     return out
 
 
-def retime(trace, budget, fill_pm, part_bytes=PART_BYTES, fill_bwd_pm=None):
+def retime(trace, budget, fill_pm, part_bytes=PART_BYTES, lent=None, twins=None):
     """Budget-aware transfer windows on the op trace of a static schedule.
 
     Forward: the release of an offloaded X no longer follows its last consumer; released blocks queue up in
-    copy order; an allocation that would pass `soft` = budget * fill_pm / 1000 first releases the oldest of
-    them, until the live total fits AND at least as many bytes were released as it asks for (pieces of one
-    block leave from its low end upwards, so the request finds one contiguous range); whatever is left is
-    released at the end of forward propagation.
-    Backward: fetches are taken in the order of the static schedule; each (allocation + copy) moves to the
-    earliest point, not before the previous fetch, from which the live total plus its size stays within
-    `soft` (with fill_bwd_pm, default fill_pm) up to its original place.  A moved op is reported under the
-    layer it now sits in.
-    Blocks larger than part_bytes are copied, released and fetched in pieces ("B7#2" = third piece of B7),
-    each piece following the same two rules on its own; backward fetches the pieces from the top one down
-    (the mirror image of the order in which forward gave them up)."""
+    copy order, and an allocation that would pass `soft` = budget * fill_pm / 1000 first releases the oldest
+    of them until the live total fits.  The address range of X is lent out while X is away: a feature map that
+    is not offloaded itself and whose allocation had to release something becomes a TENANT of the block
+    released last; tenants line up from the low end of the host's range (pieces leave from the low end
+    upwards), and the allocation keeps releasing until the host has room for it.  When the host runs out of
+    pieces, the next block in the queue becomes the host.  Whatever is still queued at the end of forward
+    propagation is released there.
+    Backward: fetches keep their place in the static schedule here.  (The library issues them earlier, as soon
+    as the address range a fetch will occupy is free in its placement of the blocks; that needs addresses,
+    which this byte-counting model does not have: see settle_fetches.)  A fetch returns to the range its block
+    had in forward propagation (it is the host's TWIN) when every tenant has left by then.
+    Blocks larger than part_bytes are copied, released and fetched in pieces ("B7#2" = third piece of B7);
+    forward gives the pieces up from the low end upwards, backward fetches them from the top one down.
+
+    lent: optional dict, filled with {tenant tag: (host tag, byte offset inside the host's range)};
+    twins: optional set, filled with the tags whose fetch returns to the forward range."""
     budget_al = budget // ALIGN * ALIGN
     soft = budget_al * fill_pm // 1000 // ALIGN * ALIGN
-    soft_bwd = soft if fill_bwd_pm is None else budget_al * fill_bwd_pm // 1000 // ALIGN * ALIGN
     create = [t for t in trace if _phase(t[0]) == 0]
     fwd = [t for t in trace if _phase(t[0]) == 1]
     bwd = [t for t in trace if _phase(t[0]) == 2]
     live = sum(t[3] for t in create if t[1] == "alloc")
     size_of = {}           # tag -> aligned size of the block while it is live
+    offloaded = {t[2] for t in fwd if t[1] == "offload"}
+    lent = {} if lent is None else lent
+    twins = set() if twins is None else twins
 
     def pieces(tag, raw):
         ps = parts_of(size_of[tag], raw, part_bytes)
         return [(tag if len(ps) == 1 else "%s#%d" % (tag, i), sz, rw) for i, (sz, rw) in enumerate(ps)]
 
-    # ---- forward: copies in pieces, lazy release of offloaded blocks ----
+    # ---- forward: copies in pieces, lazy release of offloaded blocks, tenants ----
     out = list(create)
-    pending = []           # (tag, size), oldest first
+    pending = []           # (piece tag, size, block tag), oldest first
     copying = {}           # tag -> raw bytes being offloaded
+    released = {}          # host tag -> bytes released so far (from the low end of its range)
+    taken = {}             # host tag -> bytes lent so far
+    host = None            # block released last
     for t in fwd:
         kind = t[1]
         if kind == "offload":
@@ -503,66 +513,73 @@ def retime(trace, budget, fill_pm, part_bytes=PART_BYTES, fill_bwd_pm=None):
             out.extend((t[0], "offload", tag, rw) for tag, _, rw in pieces(t[2], t[3]))
             continue
         if kind == "free" and t[2] in copying:
-            pending.extend((tag, sz) for tag, sz, _ in pieces(t[2], copying.pop(t[2])))
+            pending.extend((tag, sz, t[2]) for tag, sz, _ in pieces(t[2], copying.pop(t[2])))
             continue
         if kind == "alloc":
             if live + t[3] > soft:
-                released = 0
-                while pending and (live + t[3] > soft or released < t[3]):
-                    tag, size = pending.pop(0)
+                rents = t[2][0] == "B" and t[2] not in offloaded
+
+                def room():
+                    return released[host] - taken[host] if host is not None else 0
+
+                while pending and (live + t[3] > soft or (rents and room() < t[3])):
+                    tag, size, host = pending.pop(0)
                     out.append((t[0], "free", tag, size))
                     live -= size
-                    released += size
+                    released[host] = released.get(host, 0) + size
+                    taken.setdefault(host, 0)
+                if rents and room() >= t[3]:
+                    lent[t[2]] = (host, taken[host])
+                    taken[host] += t[3]
             live += t[3]
             size_of[t[2]] = t[3]
         elif kind == "free":
             live -= t[3]
         out.append(t)
     last_fwd = fwd[-1][0] if fwd else "F0"
-    for tag, size in pending:
+    for tag, size, _ in pending:
         out.append((last_fwd, "free", tag, size))
         live -= size
 
-    # ---- backward: early issue of fetches, piece by piece ----
-    before = []            # live total before each entry
-    for t in bwd:
-        before.append(live)
-        if t[1] == "alloc":
-            live += t[3]
+    # ---- backward: fetches in pieces, top piece first, at their place in the static schedule ----
+    freed_at = {t[2]: i for i, t in enumerate(bwd) if t[1] == "free"}
+    i = 0
+    while i < len(bwd):
+        t = bwd[i]
+        if t[1] == "alloc" and i + 1 < len(bwd) and bwd[i + 1][1] in ("prefetch", "ondemand") and bwd[i + 1][2] == t[2]:
             size_of[t[2]] = t[3]
-        elif t[1] == "free":
-            live -= t[3]
-    fetches = [q for q in range(len(bwd) - 1) if bwd[q][1] == "alloc" and bwd[q + 1][1] in ("prefetch", "ondemand")
-               and bwd[q + 1][2] == bwd[q][2]]
-    moved = {}             # landing index -> [(tag, size, raw)] in issue order
-    stay = {}              # original index -> pieces that stay there
-    lo = 0
-    for q in fetches:
-        for tag, size, raw in reversed(pieces(bwd[q][2], bwd[q + 1][3])):
-            j = q
-            while j > lo and before[j - 1] + size <= soft_bwd:   # landing before entry j - 1 keeps every state up to q within soft
-                j -= 1
-            if j < q:
-                for t in range(j, q + 1):
-                    before[t] += size
-                moved.setdefault(j, []).append((tag, size, raw))
-                lo = j
-            else:
-                stay.setdefault(q, []).append((tag, size, raw))
-                lo = q + 2
-    skip = set()
-    for q in fetches:
-        skip.update((q, q + 1))
-    for t, entry in enumerate(bwd):
-        for tag, size, raw in moved.get(t, []):
-            out.append((entry[0], "alloc", tag, size))
-            out.append((entry[0], "prefetch", tag, raw))
-        for tag, size, raw in stay.get(t, []):
-            out.append((entry[0], "alloc", tag, size))
-            out.append((entry[0], bwd[t + 1][1], tag, raw))
-        if t not in skip:
-            out.append(entry)
+            tenants = [tn for tn, (h, _) in lent.items() if h == t[2]]
+            if tenants and all(freed_at[tn] < i for tn in tenants):
+                twins.add(t[2])
+            for tag, size, raw in reversed(pieces(t[2], bwd[i + 1][3])):
+                out.append((t[0], "alloc", tag, size))
+                out.append((t[0], bwd[i + 1][1], tag, raw))
+            i += 2
+            continue
+        out.append(t)
+        i += 1
     return out
+
+
+def settle_fetches(trace):
+    """Canonical form of a backward schedule whose fetches may have been issued early: every (alloc, prefetch |
+    ondemand) pair of a fetched block or piece is taken out.  Returns (trace without them, [(tag, number of
+    compute entries that precede the pair)]).  Two schedules that differ only in how early fetches are issued
+    have the same first part; the second part says how early."""
+    rest, fetches = [], []
+    computes = 0
+    i = 0
+    while i < len(trace):
+        t = trace[i]
+        if (_phase(t[0]) == 2 and t[1] == "alloc" and i + 1 < len(trace) and trace[i + 1][1] in ("prefetch", "ondemand")
+                and trace[i + 1][2] == t[2]):
+            fetches.append((t[2], computes))
+            i += 2
+            continue
+        computes += t[1] == "compute"
+        rest.append(t)
+        i += 1
+    return rest, fetches
 
 
 def trace_stats(trace):
@@ -591,10 +608,10 @@ def trace_stats(trace):
     return st
 
 
-def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, fill_bwd_pm=None):
+def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, windows=None):
     """The "fit" policy: offload set from fit_select (performance-optimal algorithms first, then the greedy
-    downgrade, then memory-optimal everywhere), transfer windows from retime.  fill_pm = 0 keeps the static
-    schedule of the chosen set.  extra: that many more candidates, largest first (ties: lower id), join the
+    downgrade, then memory-optimal everywhere), transfer windows from retime.  windows (default: fill_pm > 0)
+    = False keeps the static schedule of the chosen set.  extra: that many more candidates, largest first (ties: lower id), join the
     set (what the library does when it finds no placement of the blocks inside the budget).
     Returns (offload set, algorithm mode, result dict) or (None, None, None)."""
     for algo in ("p", "greedy", "m"):
@@ -608,7 +625,7 @@ def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, fill_bwd_pm=N
         rest = [b for b in fit_candidates(net) if b not in chosen]
         chosen.add(max(rest, key=lambda b: (info["nbytes"][b], -b)))
     r = simulate(net, "none", budget, algo, offload_set=chosen)
-    if (fill_pm or fill_bwd_pm) and budget:
-        r["trace"] = retime(r["trace"], budget, fill_pm, part_bytes, fill_bwd_pm)
+    if (fill_pm > 0 if windows is None else windows) and budget:
+        r["trace"] = retime(r["trace"], budget, fill_pm, part_bytes)
         r.update(trace_stats(r["trace"]))
     return chosen, algo, r

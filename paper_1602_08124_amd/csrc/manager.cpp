@@ -278,82 +278,110 @@ struct Compiler {
 // distances from the block's offset.  It takes the lowest offset at which none of its rectangles meets a
 // placed one; later blocks see its rectangles one by one and can move into the part of the range a piece
 // has left (or not yet taken).
+//
+// A host, its tenants and its twin (see retime) form one such object too: the tenants' rectangles and the
+// twin's staircase lie inside the host's range by construction, so the group is placed as a whole.
 namespace {
 struct Rect { size_t off, bytes; int t0, t1; };
+struct Unit {
+    std::vector<Rect> rects;                         // offsets relative to the unit's offset
+    std::vector<std::pair<int, size_t>> members;     // (block, distance from the unit's offset)
+    size_t bytes = 0;                                // address range the unit spans
+    int t0 = 1 << 30, t1 = 0;
+};
 }
 
-static size_t place_with_keys(Plan& p, size_t base, const std::vector<int>& ids, const std::vector<double>& key,
+static std::vector<Unit> make_units(const Plan& p) {
+    std::vector<Unit> units;
+    std::vector<int> unit_of(p.blocks.size(), -1);
+    auto add = [&](Unit& u, int id, size_t rel) {
+        const Block& b = p.blocks[id];
+        u.members.push_back({id, rel});
+        for (int i = 0; i < b.parts; ++i) {
+            const Rect r{rel + (b.parts == 1 ? 0 : (size_t)i * b.part_bytes), b.piece_bytes(i), b.parts == 1 ? b.t0 : b.part_t0[i],
+                         b.parts == 1 ? b.t1 : b.part_t1[i]};
+            u.rects.push_back(r);
+            u.bytes = std::max(u.bytes, r.off + r.bytes);
+            u.t0 = std::min(u.t0, r.t0);
+            u.t1 = std::max(u.t1, r.t1);
+        }
+    };
+    for (int id = 0; id < (int)p.blocks.size(); ++id) {
+        if (p.blocks[id].persistent || p.blocks[id].host >= 0) continue;
+        unit_of[id] = (int)units.size();
+        units.emplace_back();
+        add(units.back(), id, 0);
+    }
+    for (int id = 0; id < (int)p.blocks.size(); ++id)
+        if (!p.blocks[id].persistent && p.blocks[id].host >= 0) add(units[unit_of[p.blocks[id].host]], id, p.blocks[id].host_rel);
+    return units;
+}
+
+static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, size_t base, const std::vector<double>& key,
                               std::vector<size_t>& offsets) {
-    std::vector<int> order(ids.size());
-    for (size_t i = 0; i < ids.size(); ++i) order[i] = (int)i;
+    std::vector<int> order(units.size());
+    for (size_t i = 0; i < units.size(); ++i) order[i] = (int)i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key[a] > key[b]; });
     std::vector<Rect> placed;  // absolute offsets
-    offsets.assign(p.blocks.size(), 0);
+    offsets.assign(n_blocks, 0);
     size_t extent = base;
     std::vector<std::pair<size_t, size_t>> conf;
-    std::vector<Rect> own, near;
-    for (int oi : order) {
-        const int id = ids[oi];
-        const Block& b = p.blocks[id];
+    std::vector<Rect> near;
+    for (int ui : order) {
+        const Unit& u = units[ui];
         size_t off = base;
-        if (b.parts == 1) {
+        if (u.rects.size() == 1) {
             conf.clear();
             for (const Rect& q : placed)
-                if (q.t0 < b.t1 && b.t0 < q.t1) conf.push_back({q.off, q.bytes});
+                if (q.t0 < u.t1 && u.t0 < q.t1) conf.push_back({q.off, q.bytes});
             std::sort(conf.begin(), conf.end());
             for (auto& c : conf) {
-                if (off + b.bytes <= c.first) break;
+                if (off + u.bytes <= c.first) break;
                 off = std::max(off, c.first + c.second);
             }
-            placed.push_back({off, b.bytes, b.t0, b.t1});
         } else {
-            own.clear();
-            for (int i = 0; i < b.parts; ++i) own.push_back({(size_t)i * b.part_bytes, b.piece_bytes(i), b.part_t0[i], b.part_t1[i]});
             near.clear();
             for (const Rect& q : placed)
-                if (q.t0 < b.t1 && b.t0 < q.t1) near.push_back(q);
+                if (q.t0 < u.t1 && u.t0 < q.t1) near.push_back(q);
             auto fits = [&](size_t o) {
-                for (const Rect& r : own)
+                for (const Rect& r : u.rects)
                     for (const Rect& q : near)
                         if (q.t0 < r.t1 && r.t0 < q.t1 && o + r.off < q.off + q.bytes && q.off < o + r.off + r.bytes) return false;
                 return true;
             };
             std::vector<size_t> cands{base};
-            for (const Rect& r : own)
+            for (const Rect& r : u.rects)
                 for (const Rect& q : near)
                     if (q.t0 < r.t1 && r.t0 < q.t1 && q.off + q.bytes >= base + r.off) cands.push_back(q.off + q.bytes - r.off);
             std::sort(cands.begin(), cands.end());
             for (size_t o : cands)
-                if (fits(o)) { off = o; break; }   // the candidate above every neighbour always fits
-            for (const Rect& r : own) placed.push_back({off + r.off, r.bytes, r.t0, r.t1});
+                if (fits(o)) { off = o; break; }   // sliding down from above every neighbour stops at one of the candidates
         }
-        offsets[id] = off;
-        extent = std::max(extent, off + b.bytes);
+        for (const Rect& r : u.rects) placed.push_back({off + r.off, r.bytes, r.t0, r.t1});
+        for (auto& m : u.members) offsets[m.first] = off + m.second;
+        extent = std::max(extent, off + u.bytes);
     }
     return extent;
 }
 
 static size_t place_blocks(Plan& p, size_t base) {
-    std::vector<int> ids;
-    for (int i = 0; i < (int)p.blocks.size(); ++i)
-        if (!p.blocks[i].persistent) ids.push_back(i);
-    if (ids.empty()) return base;
-    const size_t n = ids.size();
+    const std::vector<Unit> units = make_units(p);
+    if (units.empty()) return base;
+    const size_t n = units.size();
     std::vector<double> size(n), life(n), area(n), start(n), key(n);
     for (size_t i = 0; i < n; ++i) {
-        const Block& b = p.blocks[ids[i]];
         // ties: earlier blocks first (the sort is stable)
-        size[i] = (double)b.bytes;
-        life[i] = (double)(b.t1 - b.t0);
+        size[i] = (double)units[i].bytes;
+        life[i] = (double)(units[i].t1 - units[i].t0);
         area[i] = size[i] * life[i];
-        start[i] = (double)(p.ops.size() + 2 - b.t0);  // allocation order: what a run-time first-fit allocator would do
+        start[i] = (double)(p.ops.size() + 2 - units[i].t0);  // allocation order: what a run-time first-fit allocator would do
     }
     std::vector<size_t> best, cur;
     size_t best_extent = (size_t)-1;
     constexpr int kKinds = 4;
     const std::vector<double>* base_keys[kKinds] = {&size, &life, &area, &start};
     for (int kind = 0; kind < kKinds; ++kind) {
-        const size_t e = place_with_keys(p, base, ids, *base_keys[kind], cur);
+        const size_t e = place_with_keys(units, p.blocks.size(), base, *base_keys[kind], cur);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
     uint64_t rng = 0x9E3779B97F4A7C15ull;  // fixed seed: the plan is a pure function of (net, policy, budget)
@@ -363,10 +391,11 @@ static size_t place_blocks(Plan& p, size_t base) {
         const std::vector<double>& k0 = *base_keys[(int)(next() * kKinds) % kKinds];
         const double noise = noises[(int)(next() * 4) % 4];
         for (size_t i = 0; i < n; ++i) key[i] = k0[i] * (1.0 + noise * (next() - 0.5));
-        const size_t e = place_with_keys(p, base, ids, key, cur);
+        const size_t e = place_with_keys(units, p.blocks.size(), base, key, cur);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
-    for (int id : ids) p.blocks[id].offset = best[id];
+    for (const Unit& u : units)
+        for (auto& m : u.members) p.blocks[m.first].offset = best[m.first];
     return best_extent;
 }
 
@@ -416,6 +445,7 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
     c.phase = 1; c.layer = -1;
     p.first_fwd_op = (int)p.ops.size();
     res[0] = c.alloc("B-1", n.B(-1).count * 4); CHECK_FAIL();
+    p.blocks[res[0]].buf = -1;
     {
         Op& o = c.emit(OP_LOAD_INPUT);
         o.out_block = res[0];
@@ -425,7 +455,7 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
         c.layer = i;
         c.emit(OP_SAMPLE);
         c.samples.push_back(c.live);
-        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); }
+        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); p.blocks[res[i + 1]].buf = i; }
         size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
         if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
         int wsb = -1;
@@ -471,6 +501,7 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
     auto fetch = [&](int b, OpKind kind) -> bool {
         res[b + 1] = c.alloc(fmt("B%d", b), n.B(b).count * 4);
         if (c.failed) return false;
+        p.blocks[res[b + 1]].buf = b;
         p.blocks[res[b + 1]].host_off = host_off[b + 1];
         on_host[b + 1] = 0;
         Op& o = c.emit(kind);
@@ -550,15 +581,19 @@ static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const
 // takes the memory.
 //   forward:  the release of an offloaded X (and the wait for its copy) is held back; held blocks queue in
 //             copy order; an allocation that would pass `soft` first lets the oldest go, until the live total
-//             fits and at least as many bytes went as it asks for (pieces of one block go from its low end
-//             upwards, so the request finds one contiguous range); the rest go at the end of forward
-//             propagation;
-//   backward: every fetch (allocation + copy), in the order of the static schedule, moves to the earliest
-//             point, not before the previous fetch, from which live bytes plus its size stay within
-//             `soft_bwd` up to its original place; a block that moves in pieces is fetched from its top piece
-//             down, the mirror image of forward; the wait for a fetch moves to just before the first
-//             computation that reads it.
-static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
+//             fits.  The range of X is lent out while X is away: a feature map that is not offloaded itself
+//             and had to let something go becomes a tenant of the block released last, lined up from the low
+//             end of its range (pieces go from the low end upwards), and keeps letting pieces go until that
+//             host has room for it; when a host runs out of pieces the next held block takes over.  The rest
+//             go at the end of forward propagation;
+//   backward: a block that moves in pieces is fetched from its top piece down, the mirror image of forward;
+//             a fetch returns to the range its buffer had in forward propagation (as the host's twin) when
+//             every tenant has left by then; the wait for a fetch moves to just before the first computation
+//             that reads it.  Once the blocks have addresses, hoist_fetches moves every fetch (allocation +
+//             copy), in the order of the static schedule, to the earliest point, not before the previous
+//             fetch, from which its own address range is free and live bytes plus its size stay within
+//             `soft_bwd`, up to its original place.
+static void retime(const vdnn_net& n, Plan& p, size_t soft) {
     const int L = (int)n.layers.size();
     constexpr int kMaxParts = 32;
     // Blocks larger than the part size move in at most kMaxParts pieces of equal (aligned) size.
@@ -577,16 +612,22 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
     struct Held { Op wait, free; size_t bytes; };
     std::vector<Held> held;
     size_t held_head = 0;
+    std::vector<size_t> released(p.blocks.size(), 0), taken(p.blocks.size(), 0);  // per host: bytes given up / lent so far
+    std::vector<int> fwd_block_of(L + 1, -1);  // buffer id + 1 -> the block that was offloaded
+    int host = -1;                             // block released last
     auto let_go = [&](int layer) {
         Held& h = held[held_head++];
         h.wait.layer = h.free.layer = layer;
         out.push_back(h.wait);
         out.push_back(h.free);
         live -= h.bytes;
+        host = h.free.block;
+        released[host] += h.bytes;
     };
     for (int t = p.first_fwd_op; t < p.first_bwd_op; ++t) {
         const Op& o = p.ops[t];
         if (o.kind == OP_OFFLOAD) {
+            fwd_block_of[o.buf + 1] = o.block;
             const int k = split(o.block);
             for (int i = 0; i < k; ++i) {
                 Op c = o;
@@ -608,8 +649,16 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
         if (o.kind == OP_ALLOC) {
             const size_t s = p.blocks[o.block].bytes;
             if (live + s > soft) {
-                const size_t live0 = live;
-                while (held_head < held.size() && (live + s > soft || live0 - live < s)) let_go(o.layer);
+                // a feature map that is not offloaded itself moves into the range of the block released last
+                Block& me = p.blocks[o.block];
+                const bool rents = me.buf >= -1 && !p.offload_set[me.buf + 1];
+                auto room = [&]() { return host >= 0 ? released[host] - taken[host] : (size_t)0; };
+                while (held_head < held.size() && (live + s > soft || (rents && room() < s))) let_go(o.layer);
+                if (rents && room() >= s) {
+                    me.host = host;
+                    me.host_rel = taken[host];
+                    taken[host] += s;
+                }
             }
             live += s;
         } else if (o.kind == OP_FREE) {
@@ -620,91 +669,60 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
     while (held_head < held.size()) let_go(L - 1);
     const int new_first_bwd = (int)out.size();
 
+    // backward: fetches stay where the static schedule has them (hoist_fetches moves them once the blocks have
+    // addresses), but are cut into pieces, top piece first, and awaited just before their first reader
     const std::vector<Op> bw(p.ops.begin() + p.first_bwd_op, p.ops.end());
     const int nb = (int)bw.size();
-    std::vector<size_t> before(nb + 1);  // live bytes before each backward op of the static schedule
-    for (int t = 0; t < nb; ++t) {
-        before[t] = live;
-        if (bw[t].kind == OP_ALLOC) live += p.blocks[bw[t].block].bytes;
-        else if (bw[t].kind == OP_FREE) live -= p.blocks[bw[t].block].bytes;
-    }
-    struct Piece { int q, part; };
-    std::vector<std::vector<Piece>> landing(nb + 1), stay(nb + 1);
-    std::vector<char> skip(nb + 1, 0);
+    std::vector<int> freed_at(p.blocks.size(), -1);  // block -> backward op that releases it
+    for (int t = 0; t < nb; ++t)
+        if (bw[t].kind == OP_FREE) freed_at[bw[t].block] = t;
     std::vector<std::vector<int>> await(p.blocks.size());  // block -> pieces whose copy the first reader has to wait for
-    int lo = 0;
-    for (int q = 0; q + 1 < nb; ++q) {
-        if (bw[q].kind != OP_ALLOC || (bw[q + 1].kind != OP_PREFETCH && bw[q + 1].kind != OP_ONDEMAND) || bw[q + 1].block != bw[q].block) continue;
-        const int block = bw[q].block;
-        const int k = split(block);
-        skip[q] = skip[q + 1] = 1;
-        for (int i = k - 1; i >= 0; --i) {
-            const size_t s = p.blocks[block].piece_bytes(i);
-            const int part = k == 1 ? -1 : i;
-            int j = q;
-            while (j > lo && before[j - 1] + s <= soft_bwd) --j;
-            if (j < q) {
-                for (int t = j; t <= q; ++t) before[t] += s;
-                landing[j].push_back({q, part});
-                await[block].push_back(part);
-                lo = j;
-            } else {
-                stay[q].push_back({q, part});
-                if (bw[q + 1].kind == OP_PREFETCH) await[block].push_back(part);  // an on-demand fetch waits by itself
-                lo = q + 2;
-            }
-        }
-    }
     std::vector<char> waited(p.blocks.size(), 0);
-    auto emit_pieces = [&](const std::vector<Piece>& list, int layer, bool moved) {
-        for (const Piece& pc : list) {
-            Op a = bw[pc.q], c = bw[pc.q + 1];
-            a.layer = c.layer = layer;
-            a.part = c.part = pc.part;
-            if (moved) c.kind = OP_PREFETCH;
-            out.push_back(a);
-            out.push_back(c);
-        }
-    };
     for (int t = 0; t < nb; ++t) {
         const Op& o = bw[t];
-        if (o.kind != OP_SAMPLE) emit_pieces(landing[t], o.layer, true);
-        emit_pieces(stay[t], o.layer, false);
-        // the waits of the static schedule for fetches are dropped: each fetch is awaited just before its first reader
-        if (!skip[t] && !(o.kind == OP_WAIT_COPY && !await[o.block].empty())) {
-            if (o.kind == OP_BWD) {
-                std::vector<int> reads = o.in_blocks;
-                reads.push_back(o.out_block);
-                for (int b : reads)
-                    if (b >= 0 && !await[b].empty() && !waited[b]) {
-                        for (int part : await[b]) {
-                            Op w;
-                            w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b; w.part = part;
-                            out.push_back(w);
-                        }
-                        waited[b] = 1;
-                    }
+        if (o.kind == OP_ALLOC && t + 1 < nb && (bw[t + 1].kind == OP_PREFETCH || bw[t + 1].kind == OP_ONDEMAND) && bw[t + 1].block == o.block) {
+            const int block = o.block;
+            const int k = split(block);
+            // the fetch returns to the range its buffer had in forward propagation when every tenant has left by then
+            const int fwd_block = fwd_block_of[p.blocks[block].buf + 1];
+            if (fwd_block >= 0) {
+                bool any = false, gone = true;
+                for (size_t b = 0; b < p.blocks.size(); ++b)
+                    if (p.blocks[b].host == fwd_block) { any = true; gone = gone && freed_at[b] >= 0 && freed_at[b] < t; }
+                if (any && gone) { p.blocks[block].host = fwd_block; p.blocks[block].host_rel = 0; }
             }
-            out.push_back(o);
+            for (int i = k - 1; i >= 0; --i) {
+                Op a = o, c = bw[t + 1];
+                a.part = c.part = k == 1 ? -1 : i;
+                out.push_back(a);
+                out.push_back(c);
+                if (c.kind == OP_PREFETCH) await[block].push_back(c.part);  // an on-demand fetch waits by itself
+            }
+            ++t;
+            continue;
         }
-        if (o.kind == OP_SAMPLE) emit_pieces(landing[t], o.layer, true);
+        if (o.kind == OP_WAIT_COPY && !await[o.block].empty()) continue;  // re-issued below, before the first reader
+        if (o.kind == OP_BWD) {
+            std::vector<int> reads = o.in_blocks;
+            reads.push_back(o.out_block);
+            for (int b : reads)
+                if (b >= 0 && !await[b].empty() && !waited[b]) {
+                    for (int part : await[b]) {
+                        Op w;
+                        w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b; w.part = part;
+                        out.push_back(w);
+                    }
+                    waited[b] = 1;
+                }
+        }
+        out.push_back(o);
     }
     p.ops.swap(out);
     p.first_bwd_op = new_first_bwd;
 }
 
-// Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
-    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
-    p.ok = false;
-    p.fill_pm = p.fill_bwd_pm = 0;
-    if ((fill_pm > 0 || fill_bwd_pm > 0) && n.budget) {
-        // budget * fill / 1000 rounded down to a block boundary, in integers
-        auto soft = [&](int pm) { return (size_t)((unsigned __int128)budget * (unsigned)pm / 1000u) / kAlign * kAlign; };
-        retime(n, p, soft(fill_pm), soft(fill_bwd_pm));
-        p.fill_pm = fill_pm;
-        p.fill_bwd_pm = fill_bwd_pm;
-    }
+// Lifetimes of blocks and pieces in op indices, live-byte statistics and copy counts of the op list.
+static void measure_plan(Plan& p) {
     size_t live = 0;
     double sum = 0.0;
     size_t n_samples = 0;
@@ -741,11 +759,125 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
         }
     }
     p.avg = n_samples ? sum / (double)n_samples : 0.0;
+}
+
+namespace {
+struct Span { size_t off, bytes; int t0, t1, block; };
+}
+static std::vector<Span> spans_of(const Plan& p) {
+    std::vector<Span> v;
+    for (int id = 0; id < (int)p.blocks.size(); ++id) {
+        const Block& b = p.blocks[id];
+        if (b.persistent) continue;
+        for (int i = 0; i < b.parts; ++i)
+            v.push_back({b.offset + (b.parts == 1 ? 0 : (size_t)i * b.part_bytes), b.piece_bytes(i), b.parts == 1 ? b.t0 : b.part_t0[i],
+                         b.parts == 1 ? b.t1 : b.part_t1[i], id});
+    }
+    return v;
+}
+
+// True when two pieces of memory that are live at the same time share an address.
+static bool plan_overlaps(const Plan& p) {
+    const std::vector<Span> v = spans_of(p);
+    for (size_t i = 0; i < v.size(); ++i)
+        for (size_t j = i + 1; j < v.size(); ++j)
+            if (v[i].t0 < v[j].t1 && v[j].t0 < v[i].t1 && v[i].off < v[j].off + v[j].bytes && v[j].off < v[i].off + v[i].bytes) return true;
+    return false;
+}
+
+// Early fetches, after placement (see retime).  A fetch (or a piece of one) sits at address range R from op q
+// of the static schedule.  It may start at any earlier op from which R is free: nothing else that the
+// placement put into R is live then.  Because every other block keeps its address and its lifetime, the
+// placement stays valid, and the pool's extent does not change.
+static void hoist_fetches(Plan& p, size_t soft_bwd) {
+    const std::vector<Span> spans = spans_of(p);
+    const int f0 = p.first_bwd_op, nt = (int)p.ops.size();
+    std::vector<size_t> before(nt + 1, 0);  // live bytes before each op
+    {
+        size_t live = 0;
+        for (int t = 0; t < nt; ++t) {
+            before[t] = live;
+            const Op& o = p.ops[t];
+            if (o.kind != OP_ALLOC && o.kind != OP_FREE) continue;
+            const Block& b = p.blocks[o.block];
+            const size_t bytes = o.part < 0 ? b.bytes : b.piece_bytes(o.part);
+            if (o.kind == OP_ALLOC) live += bytes; else live -= bytes;
+        }
+    }
+    std::vector<std::vector<int>> landing(nt + 1);
+    std::vector<char> skip(nt + 1, 0);
+    int lo = f0;
+    for (int q = f0; q + 1 < nt; ++q) {
+        const Op& a = p.ops[q];
+        const Op& c = p.ops[q + 1];
+        if (a.kind != OP_ALLOC || (c.kind != OP_PREFETCH && c.kind != OP_ONDEMAND) || c.block != a.block || c.part != a.part) continue;
+        const Block& b = p.blocks[a.block];
+        const size_t s = a.part < 0 ? b.bytes : b.piece_bytes(a.part);
+        const size_t r0 = b.offset + (a.part < 0 ? 0 : (size_t)a.part * b.part_bytes), r1 = r0 + s;
+        int ready = lo;
+        for (const Span& v : spans)
+            if (v.t0 < q && v.off < r1 && r0 < v.off + v.bytes && !(v.block == a.block)) ready = std::max(ready, v.t1);
+        int j = q;
+        while (j > ready && before[j - 1] + s <= soft_bwd) --j;
+        if (j < q) {
+            for (int t = j; t <= q; ++t) before[t] += s;
+            landing[j].push_back(q);
+            skip[q] = skip[q + 1] = 1;
+            lo = j;
+        } else {
+            lo = q + 2;
+        }
+    }
+    std::vector<Op> out;
+    out.reserve(p.ops.size() + 32);
+    auto emit_landing = [&](int t) {
+        for (int q : landing[t]) {
+            Op a = p.ops[q], c = p.ops[q + 1];
+            a.layer = c.layer = p.ops[t].layer;
+            c.kind = OP_PREFETCH;
+            out.push_back(a);
+            out.push_back(c);
+        }
+    };
+    for (int t = 0; t < nt; ++t) {
+        const Op& o = p.ops[t];
+        if (o.kind != OP_SAMPLE) emit_landing(t);
+        if (!skip[t]) out.push_back(o);
+        else if (o.kind == OP_ONDEMAND) {  // the copy left: what stays is the wait that an on-demand fetch implies
+            Op w = o;
+            w.kind = OP_WAIT_COPY;
+            out.push_back(w);
+        }
+        if (o.kind == OP_SAMPLE) emit_landing(t);
+    }
+    p.ops.swap(out);
+}
+
+// Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
+    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
+    p.ok = false;
+    p.fill_pm = p.fill_bwd_pm = 0;
+    // budget * fill / 1000 rounded down to a block boundary, in integers
+    auto soft = [&](int pm) { return (size_t)((unsigned __int128)budget * (unsigned)pm / 1000u) / kAlign * kAlign; };
+    const bool windows = (fill_pm > 0 || fill_bwd_pm > 0) && n.budget;
+    if (windows) {
+        retime(n, p, soft(fill_pm));
+        p.fill_pm = fill_pm;
+    }
+    measure_plan(p);
     p.extent = place_blocks(p, p.persistent);
     if (p.extent > budget) {
         p.fail_where = "placement";
         p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
         return;
+    }
+    if (windows && fill_bwd_pm > 0) {
+        const Plan kept = p;
+        hoist_fetches(p, soft(fill_bwd_pm));
+        measure_plan(p);
+        p.fill_bwd_pm = fill_bwd_pm;
+        if (plan_overlaps(p)) p = kept;  // cannot happen by construction; a plan that fails the check is never run
     }
     p.ok = true;
 }
@@ -822,22 +954,11 @@ static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
         // The set was chosen by live bytes; when no placement of the blocks fits the budget either (the live
         // peak then sits within a fraction of a percent of it), the largest remaining candidate is added.
         for (;;) {
-            // the largest forward share that can be placed with backward on the static schedule, then the largest
-            // backward share under it
-            int ff = -1;
+            // the largest forward share for which the blocks can be placed (the backward windows come out of the
+            // placement and never make it fail)
             for (int f : kFills) {
-                compile_plan(n, policy, algo, p, &set, true, f, 0);
-                if (p.ok) { ff = f; break; }
-            }
-            if (ff >= 0) {
-                Plan q;
-                for (int fb : kFills) {
-                    if (fb == 0) break;  // p already holds (ff, 0)
-                    compile_plan(n, policy, algo, q, &set, true, ff, fb);
-                    if (q.ok) { p = q; break; }
-                }
-                n.plan = p; n.policy = policy; n.effective = policy;
-                return VDNN_OK;
+                compile_plan(n, policy, algo, p, &set, true, f, f ? 1000 : 0);
+                if (p.ok) { n.plan = p; n.policy = policy; n.effective = policy; return VDNN_OK; }
             }
             int pick = -2;
             for (int b = -1; b < (int)n.layers.size(); ++b)

@@ -80,6 +80,12 @@ struct Block {
     size_t offset = 0;
     bool persistent = false;
     size_t host_off = 0;  // offset in the pinned arena (buffers that are offloaded)
+    int buf = -2;  // feature-map buffer the block holds (-1 = network input), -2 = something else
+    // Range lending (transfer windows): while an offloaded block is away its address range takes in later
+    // feature maps (tenants), and the fetch of the same buffer (twin) returns to it.  Tenants and twin are
+    // placed together with the host, at fixed distances from its offset.
+    int host = -1;        // block whose range this one lives in
+    size_t host_rel = 0;  // byte distance from the host's offset
     // A block that is copied in pieces: `parts` pieces of part_bytes (the last one shorter), which share the
     // block's address range but are released (forward) or allocated (backward) one by one.
     int parts = 1;

@@ -8,7 +8,7 @@ from oracle import memsched as ms
 from oracle import net as onet
 from synth import gen, nets
 from tests.gpu_util import TOL, dev, rel_err
-from tests.sched_util import fit_reference
+from tests.sched_util import assert_windows_match, fit_reference
 
 pytestmark = pytest.mark.gpu
 
@@ -162,8 +162,9 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
         if n.try_policy("fit") != B.OK:   # placement may need more than the live peak right at the lower end
             n.close()
             continue
-        chosen, algo, ref = fit_reference(n, net, budget, part)
-        assert n.offload_set() == chosen and [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+        chosen, algo, ref, lent, twins = fit_reference(n, net, budget, part)
+        assert n.offload_set() == chosen
+        assert_windows_match(n.trace(), ref["trace"], lent, twins)
         n.close()
         got = run_gpu(B, net, x, labels, weights, "fit", budget=budget, capture=False, part=part)
         assert got["loss"] == base["loss"], budget
