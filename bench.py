@@ -26,7 +26,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs summarised in profiles/conv_fwd_vgg16_c4_2_b256.txt, each scaled by what the same counter reads
 # for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 0.832e9.
-ROOFLINE_TRAFFIC_BYTES = 2.519e9
+ROOFLINE_TRAFFIC_BYTES = 2.405e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 
 
@@ -66,7 +66,10 @@ def streams():
     return _STREAMS
 
 
-def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=None, iters=5):
+def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=None, iters=5, ramp_ms=0):
+    """ramp_ms: before timing, keep the GPU busy for about that long with a kernel of another name (the
+    backward-filter pass), so that the clocks have settled and a profiler's average over ALL launches of the
+    timed kernel agrees with the average over the timed ones."""
     import torch
     stream = streams()[0]
     rows = []
@@ -82,6 +85,15 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
         # workspace of the faster algorithm (packed W + partial sums of split tiles; ignored when it does not apply)
         nws = max(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1), B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1), 4)
         wsp = torch.empty(nws // 4, device="cuda")
+        if ramp_ms:
+            nb = B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)
+            ws = torch.empty(max(nb, 4) // 4, device="cuda")
+            dw = torch.empty_like(wt)
+            t0 = time.perf_counter()
+            while (time.perf_counter() - t0) * 1e3 < ramp_ms:
+                B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream)
+                stream.synchronize()
+            del ws, dw
         if "fwd" in which:
             ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp), stream, iters=iters)
             row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9
@@ -105,7 +117,7 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
 def roofline(B, batch):
     """Dominant kernel: the 128x128 implicit-GEMM convolution tile kernel, on the most common VGG-16
     shape (c4_2 / c4_3 forward: 256 x 512 x 28 x 28 -> 512 channels, 947 GFLOP per launch)."""
-    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c4_2",), iters=10)[0]
+    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c4_2",), iters=20, ramp_ms=300)[0]
     ach = row["fwd_tflops"]
     return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 c4_2 b%d" % batch, achieved=ach,
                 peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=ROOFLINE_TRAFFIC_BYTES,
@@ -126,14 +138,20 @@ def cpu_baseline(sample_batch):
                 sample="one fwd+bwd step of VGG-16 at batch %d (%.1f s); per-image cost of the direct loops does not depend on the batch" % (sample_batch, dt))
 
 
-def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
+def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None):
     """policy: none | conv | all | dyn | fit, optionally with ":m" for the memory-optimal convolution algorithm;
     or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille."""
     import torch
     n = B.Net(net, budget)
+    if window_part_mib is not None:
+        n.set_window_part(int(window_part_mib * (1 << 20)))
     if policy.startswith("set:"):
         _, ids, *fills = policy.split(":")
         status = n.try_offload_set({int(v) for v in ids.split("+") if v}, *[int(f) for f in fills])
+    elif policy.startswith("fit:"):     # the offload set that fit chooses, with the window shares given
+        status = n.try_policy("fit")
+        if status == B.OK:
+            status = n.try_offload_set(n.offload_set(), *[int(f) for f in policy.split(":")[1:]])
     else:
         if ":" in policy:
             policy, algo = policy.split(":")
@@ -153,11 +171,13 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     fwd_ms = bwd_ms = stall = d2h = h2d = 0.0
+    per_step = []
     for _ in range(steps):
         loss = n.forward(x_dev, lab_dev)
         n.backward()
         st = n.stats()
         fwd_ms += st["fwd_ms"]; bwd_ms += st["bwd_ms"]; stall += st["stall_ms"]; d2h += st["d2h_gbps"]; h2d += st["h2d_gbps"]
+        per_step.append(round(st["fwd_ms"] + st["bwd_ms"], 1))
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
     st = n.stats()
@@ -168,7 +188,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup):
                n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
                d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
                conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"], window_fill_bwd_pm=st["window_fill_bwd_pm"],
-               offload_set=sorted(n.offload_set()))
+               offload_set=sorted(n.offload_set()), per_step_ms=per_step)
     if st["offloaded_bytes"]:
         # the step cannot be shorter than the time the host link needs for the bytes of each pass
         link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
@@ -188,8 +208,9 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--budget-gib", type=float, default=12.0)
     ap.add_argument("--policies", default="none,conv,dyn,all,fit")
-    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "overfeat", "googlenet", "vgg16"],
+    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "overfeat", "googlenet", "vgg16", "vgg116", "vgg416"],
                     help="vgg16 is the benchmark; the others are the paper's remaining workloads (side measurements)")
+    ap.add_argument("--window-part-mib", type=float, default=None, help="side workloads: piece size of the transfer windows (0 = whole blocks)")
     ap.add_argument("--kernel-only", action="store_true", help="only the roofline kernel (for rocprofv3 runs)")
     ap.add_argument("--calibrate-copy", action="store_true", help="with --kernel-only: also run a 1 GiB plain copy kernel")
     ap.add_argument("--kernel-table", action="store_true", help="also time every VGG-16 convolution, three passes each")
@@ -222,12 +243,17 @@ def main():
 
     if args.workload != "vgg16":
         # side measurement of another workload: its own batch and budget, policies as asked; one JSON line, no roofline
-        defaults = {"tiny": (8, 4 / 1024), "alexnet": (128, 1.0), "overfeat": (128, 2.0), "googlenet": (128, 3.0)}
+        defaults = {"tiny": (8, 4 / 1024), "alexnet": (128, 1.0), "overfeat": (128, 2.0), "googlenet": (128, 3.0),
+                    "vgg116": (32, 12.0), "vgg416": (32, 12.0)}   # the very deep VGGs of Section 5.4
         batch, gib = defaults[args.workload]
-        net = nets.CONFIGS[args.workload](batch)
+        if args.budget_gib != 12.0:
+            gib = args.budget_gib
+        deep = {"vgg116": 20, "vgg416": 80}
+        net = nets.vgg(batch, extra_per_group=deep[args.workload]) if args.workload in deep else nets.CONFIGS[args.workload](batch)
         x, labels, weights = gen.make(net)
         x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
-        res = {pol: run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else int(gib * GIB), args.steps, args.warmup)
+        res = {pol: run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else int(gib * GIB), args.steps, args.warmup,
+                               args.window_part_mib)
                for pol in args.policies.split(",")}
         print(json.dumps({"workload": args.workload, "batch": batch, "budget_gib": gib, "policies": res}))
         return

@@ -1165,13 +1165,23 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
             case OP_ONDEMAND: {
                 // The copy may start once everything enqueued so far on the compute stream has finished:
                 // for an offload that is the producer of X; for a fetch it covers the last users of whatever
-                // occupied the destination's address range before.
-                NEWEV(e_ready);
-                HIPCHK(hipEventRecord(n.events[e_ready], n.sc));
-                HIPCHK(hipStreamWaitEvent(n.sm, n.events[e_ready], 0));
-                NEWEV(e0);
+                // occupied the destination's address range before.  Pieces of one block that are issued in a
+                // row share that edge (nothing was enqueued on the compute stream in between) and are timed
+                // as one transfer, which keeps the number of events per step low.
+                int prev = t - 1;
+                while (prev >= first && (p.ops[prev].kind == OP_ALLOC || p.ops[prev].kind == OP_FREE || p.ops[prev].kind == OP_SAMPLE)) --prev;  // these enqueue nothing
+                const bool follows = prev >= first && p.ops[prev].kind == o.kind && p.ops[prev].block == o.block && o.kind != OP_ONDEMAND;
+                int e_ready = -1, e0 = -1;
+                if (!follows) {
+                    NEWEV(er);
+                    e_ready = er;
+                    HIPCHK(hipEventRecord(n.events[e_ready], n.sc));
+                    HIPCHK(hipStreamWaitEvent(n.sm, n.events[e_ready], 0));
+                    NEWEV(es);
+                    e0 = es;
+                    HIPCHK(hipEventRecord(n.events[e0], n.sm));
+                }
                 NEWEV(e1);
-                HIPCHK(hipEventRecord(n.events[e0], n.sm));
                 const Block& b = p.blocks[o.block];
                 const size_t bytes = o.part < 0 ? b.raw : b.piece_raw(o.part);
                 const size_t shift = o.part < 0 ? 0 : (size_t)o.part * b.part_bytes;
@@ -1182,7 +1192,8 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
                     else HIPCHK(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, n.sm));
                 }
                 HIPCHK(hipEventRecord(n.events[e1], n.sm));
-                n.copies.push_back({e0, e1, bytes, o.kind == OP_OFFLOAD ? 0 : 1});
+                if (follows) { n.copies.back().e1 = e1; n.copies.back().bytes += bytes; }
+                else n.copies.push_back({e0, e1, bytes, o.kind == OP_OFFLOAD ? 0 : 1});
                 n.copy_done_event[(size_t)o.block * kSlots + o.part + 1] = e1;
                 if (o.kind == OP_ONDEMAND) {
                     n.stalls.push_back({e_ready, e1});
@@ -1193,9 +1204,15 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
             case OP_WAIT_COPY: {
                 const int e1 = n.copy_done_event[(size_t)o.block * kSlots + o.part + 1];
                 if (e1 < 0) { n.err = "internal: wait for a copy that was never issued"; return VDNN_ERR_STATE; }
-                NEWEV(e_here);
-                HIPCHK(hipEventRecord(n.events[e_here], n.sc));
-                n.stalls.push_back({e_here, e1});
+                // consecutive waits (pieces of one block) are timed as one stall: from here to the last copy awaited
+                int prev = t - 1;
+                while (prev >= first && (p.ops[prev].kind == OP_ALLOC || p.ops[prev].kind == OP_FREE || p.ops[prev].kind == OP_SAMPLE)) --prev;  // these enqueue nothing
+                if (prev >= first && p.ops[prev].kind == OP_WAIT_COPY && !n.stalls.empty()) n.stalls.back().e_copy = e1;
+                else {
+                    NEWEV(e_here);
+                    HIPCHK(hipEventRecord(n.events[e_here], n.sc));
+                    n.stalls.push_back({e_here, e1});
+                }
                 HIPCHK(hipStreamWaitEvent(n.sc, n.events[e1], 0));
                 break;
             }
