@@ -138,7 +138,22 @@ def cpu_baseline(sample_batch):
                 sample="one fwd+bwd step of VGG-16 at batch %d (%.1f s); per-image cost of the direct loops does not depend on the batch" % (sample_batch, dt))
 
 
-def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None):
+def per_layer_sync_bound(trace, layer_ms, d2h_gbps, h2d_gbps):
+    """Step time that the paper's end-of-layer synchronisation allows (Section 3.2): a layer cannot end before
+    its own computation and the transfer issued with it have both ended.  trace: the planned step; layer_ms:
+    (forward, backward) per-layer compute times measured without offloading."""
+    fwd, bwd = layer_ms
+    off, pre = [0] * len(fwd), [0] * len(bwd)
+    for t in trace:
+        if t[1] == "offload":
+            off[int(t[0][1:])] += t[3]
+        elif t[1] in ("prefetch", "ondemand"):
+            pre[int(t[0][1:])] += t[3]
+    ms = sum(max(c, b / (d2h_gbps * 1e6)) for c, b in zip(fwd, off)) + sum(max(c, b / (h2d_gbps * 1e6)) for c, b in zip(bwd, pre))
+    return ms
+
+
+def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None, layer_ms=None):
     """policy: none | conv | all | dyn | fit, optionally with ":m" for the memory-optimal convolution algorithm;
     or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille."""
     import torch
@@ -181,6 +196,12 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
     st = n.stats()
+    if policy == "none" and layer_ms is not None:   # one more step with an event per layer: per-layer compute times
+        n.set_layer_timing(True)
+        n.forward(x_dev, lab_dev)
+        n.backward()
+        layer_ms.extend(n.layer_times())
+        n.set_layer_timing(False)
     out = dict(status="ok", img_per_s=net["batch"] / dt, ms_per_step=dt * 1e3, fwd_ms=fwd_ms / steps, bwd_ms=bwd_ms / steps,
                stall_ms=stall / steps, loss=loss, effective_policy=st["effective_policy"], budget_bytes=budget,
                peak_bytes=st["peak_bytes"], pool_extent_bytes=st["pool_extent_bytes"], avg_bytes=st["avg_bytes_layerstep"],
@@ -194,6 +215,10 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
         link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
         out["link_bound_img_per_s"] = net["batch"] / link_s
         out["link_frac_of_peak"] = (st["offloaded_bytes"] + st["prefetched_bytes"]) / dt / (LINK_PEAK_GBPS * 1e9)
+        if layer_ms and st["window_fill_pm"] == 0 and st["window_fill_bwd_pm"] == 0:
+            ms = per_layer_sync_bound(n.trace(), layer_ms, d2h / steps, h2d / steps)
+            out["per_layer_sync_bound_ms"] = ms
+            out["per_layer_sync_bound_img_per_s"] = net["batch"] / (ms / 1e3)
     n.close()
     del n
     torch.cuda.empty_cache()
@@ -262,8 +287,10 @@ def main():
     x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
     budget = int(args.budget_gib * GIB)
     policies = {}
+    layer_ms = []   # filled by the no-offload run; the offloading policies are compared with the bound it implies
     for pol in args.policies.split(","):
-        policies[pol] = run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else budget, args.steps, args.warmup)
+        policies[pol] = run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else budget, args.steps, args.warmup,
+                                   layer_ms=layer_ms)
         print("[bench] %s: %s" % (pol, json.dumps(policies[pol])), file=sys.stderr, flush=True)
     head = policies.get("all") or next(iter(policies.values()))
     none = policies.get("none")

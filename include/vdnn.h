@@ -196,6 +196,14 @@ size_t vdnn_output_count(const vdnn_net_t*, int layer); /* elements of the layer
 vdnn_status_t vdnn_capture_output(vdnn_net_t*, int layer, float* dst /*host*/);
 vdnn_status_t vdnn_capture_grad(vdnn_net_t*, int layer, float* dst /*host*/);
 
+/* Per-layer times of the compute stream (Section 3.2's argument is per layer: a transfer hides behind a layer
+ * whose computation takes longer than the copy).  With timing on, every pass records an event at the start of
+ * each layer; a layer's time runs from its start to the start of the next layer of the pass (or the end of
+ * the pass) and therefore includes any wait for a transfer.  vdnn_layer_times copies the times of the last
+ * forward and backward pass (milliseconds; count = number of layers; VDNN_ERR_STATE before a timed step). */
+vdnn_status_t vdnn_set_layer_timing(vdnn_net_t*, int32_t on);
+vdnn_status_t vdnn_layer_times(const vdnn_net_t*, float* fwd_ms /*host*/, float* bwd_ms /*host*/, size_t count);
+
 /* The planned step as text, one op per line: "<where> <op> <tag> <bytes> [<offset>]" with
  * where = create | F<layer> | B<layer>, op = alloc | free | offload | prefetch | ondemand | compute.
  * Writes at most cap bytes (NUL-terminated) and stores the full length in *needed. */

@@ -65,6 +65,8 @@ EXPORTS = {
     "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32, C.c_int32], _i),
     "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
     "vdnn_set_window_part": ([_vp, _sz], _i),
+    "vdnn_set_layer_timing": ([_vp, C.c_int32], _i),
+    "vdnn_layer_times": ([_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), _sz], _i),
     "vdnn_forward": ([_vp, _vp, _vp, C.POINTER(C.c_float)], _i),
     "vdnn_backward": ([_vp], _i),
     "vdnn_mem_stats": ([_vp, C.POINTER(MemStats)], _i),
@@ -177,6 +179,16 @@ class Net:
         arr = (C.c_int32 * max(len(ids), 1))(*ids)
         fb = window_fill_pm if window_fill_bwd_pm is None else window_fill_bwd_pm
         return lib.vdnn_set_offload_set(self.h, arr, len(ids), window_fill_pm, fb)
+
+    def set_layer_timing(self, on=True):
+        self._chk(lib.vdnn_set_layer_timing(self.h, int(on)))
+
+    def layer_times(self):
+        """(forward ms, backward ms) per layer of the last timed step."""
+        k = len(self.net["layers"])
+        f, b = (C.c_float * k)(), (C.c_float * k)()
+        self._chk(lib.vdnn_layer_times(self.h, f, b, k))
+        return list(f), list(b)
 
     def set_window_part(self, part_bytes):
         self._chk(lib.vdnn_set_window_part(self.h, part_bytes))

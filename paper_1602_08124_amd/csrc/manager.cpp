@@ -1153,6 +1153,12 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
         const Op& o = p.ops[t];
         switch (o.kind) {
             case OP_SAMPLE:
+                if (n.time_layers) {
+                    NEWEV(e);
+                    HIPCHK(hipEventRecord(n.events[e], n.sc));
+                    n.layer_marks.push_back({o.layer, e});
+                }
+                break;
             case OP_ALLOC:
             case OP_FREE:
                 break;  // placement is static: nothing to do at run time
@@ -1251,6 +1257,16 @@ static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
         HIPCHK(hipEventElapsedTime(&ms, n.events[n.ev_b0], n.events[n.ev_b1]));
         n.bwd_ms = ms;
     }
+    if (n.time_layers) {  // a layer's time runs from its start to the start of the next one (or the end of the pass)
+        std::vector<float>& out = bwd ? n.layer_bwd_ms : n.layer_fwd_ms;
+        out.assign(n.layers.size(), 0.f);
+        for (size_t i = 0; i < n.layer_marks.size(); ++i) {
+            const int e_next = i + 1 < n.layer_marks.size() ? n.layer_marks[i + 1].second : (bwd ? n.ev_b1 : n.ev_f1);
+            HIPCHK(hipEventElapsedTime(&ms, n.events[n.layer_marks[i].second], n.events[e_next]));
+            out[n.layer_marks[i].first] = ms;
+        }
+    }
+    n.layer_marks.clear();
     for (auto& c : n.copies) {
         HIPCHK(hipEventElapsedTime(&ms, n.events[c.e0], n.events[c.e1]));
         (c.dir == 0 ? n.d2h_ms : n.h2d_ms) += ms;
@@ -1434,6 +1450,7 @@ vdnn_status_t vdnn_forward(vdnn_net_t* np, const float* input, const int32_t* la
     n.events_used = 0;
     n.copies.clear();
     n.stalls.clear();
+    n.layer_marks.clear();
     { NEWEV(e); n.ev_f0 = e; }
     { NEWEV(e); n.ev_f1 = e; }
     HIPCHK(hipEventRecord(n.events[n.ev_f0], n.sc));
@@ -1498,6 +1515,20 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
     s.d2h_gbps = n->d2h_ms > 0 ? (double)p.offloaded / (n->d2h_ms * 1e6) : 0.0;
     s.h2d_gbps = n->h2d_ms > 0 ? (double)p.prefetched / (n->h2d_ms * 1e6) : 0.0;
     *out = s;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_layer_timing(vdnn_net_t* n, int32_t on) {
+    if (!n) return VDNN_ERR_INVALID_ARG;
+    n->time_layers = on != 0;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_layer_times(const vdnn_net_t* n, float* fwd_ms, float* bwd_ms, size_t count) {
+    if (!n || !fwd_ms || !bwd_ms || count != n->layers.size()) return VDNN_ERR_INVALID_ARG;
+    if (n->layer_fwd_ms.size() != count || n->layer_bwd_ms.size() != count) return VDNN_ERR_STATE;
+    memcpy(fwd_ms, n->layer_fwd_ms.data(), count * sizeof(float));
+    memcpy(bwd_ms, n->layer_bwd_ms.data(), count * sizeof(float));
     return VDNN_OK;
 }
 

@@ -154,6 +154,9 @@ struct vdnn_net {
     struct Stall { int e_compute, e_copy; };
     std::vector<Stall> stalls;
     int ev_f0 = -1, ev_f1 = -1, ev_b0 = -1, ev_b1 = -1;
+    bool time_layers = false;                    // record an event at the start of every layer's fwd / bwd
+    std::vector<std::pair<int, int>> layer_marks;  // (layer, event) in execution order of the current pass
+    std::vector<float> layer_fwd_ms, layer_bwd_ms;
     std::vector<int> copy_done_event;  // per block: event recorded after its last copy
 
     vdnn::Buffer& B(int id) { return bufs[id + 1]; }

@@ -331,3 +331,30 @@ def test_error_paths_on_the_device(B):
         assert np.array_equal(tight.get_weight_grad(i), n.get_weight_grad(i))
     tight.close()
     n.close()
+
+
+def test_layer_times_add_up(B):
+    """Per-layer times of the compute stream: one entry per layer and pass, non-negative, adding up to the
+    pass times that the statistics report; unavailable before a timed step."""
+    net = small_vgg()
+    x, labels, weights = gen.make(net)
+    n = B.Net(net, 0)
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    import ctypes as C
+    k = len(net["layers"])
+    f, b = (C.c_float * k)(), (C.c_float * k)()
+    assert B.lib.vdnn_layer_times(n.h, f, b, k) == B.ERR_STATE
+    assert B.lib.vdnn_layer_times(n.h, f, b, k + 1) == B.ERR_INVALID_ARG
+    n.set_layer_timing(True)
+    for pol in ("none", "all"):
+        n.set_policy(pol)
+        n.forward(dev(x), dev(labels))
+        n.backward()
+        fwd, bwd = n.layer_times()
+        st = n.stats()
+        assert len(fwd) == len(bwd) == k and min(fwd) >= 0 and min(bwd) >= 0
+        assert sum(fwd) <= st["fwd_ms"] * 1.001 + 1e-3 and sum(fwd) >= 0.5 * st["fwd_ms"]
+        assert sum(bwd) <= st["bwd_ms"] * 1.001 + 1e-3 and sum(bwd) >= 0.5 * st["bwd_ms"]
+    n.close()
