@@ -278,7 +278,10 @@ template <int BM, int BN, int WM, int WN, int BK>
 __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastParams p) {
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
-    constexpr int LDA = BM + 1, LDB = BN + 1;
+    // A half-wave stores BK consecutive k (rows of LDS) x 32/BK consecutive columns: a row pitch of 32/BK words
+    // (mod 32) spreads them over all 32 banks; fragment reads are 32 consecutive words and never conflict.
+    constexpr int PAD = BK >= 32 ? 1 : 32 / BK;
+    constexpr int LDA = BM + PAD, LDB = BN + PAD;
     constexpr int EA = BM * BK / kThreads, EB = BN * BK / kThreads;
     constexpr int RSTEP = kThreads / BK;  // 8 rows between a thread's elements
     extern __shared__ float smem[];
@@ -323,6 +326,7 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     float ra[EA], rb[EB];
+    const bool full_rows = row0 + BM <= p.K;  // uniform
     auto load_step = [&](int k0) {
         const int m = k0 + kk;
         const bool vm = m < kend;
@@ -337,10 +341,15 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
         // another image's data (never stored) or out of range (0).
         const uint32_t a_base = vm ? (n * (uint32_t)p.K * (uint32_t)PQ + pq + a_rowpart) * 4u : kOobOffset;
         const uint32_t b_voff = okb ? (n * (uint32_t)p.C * (uint32_t)HW + (uint32_t)(ih * p.W + iw) + b_chpart) * 4u : kOobOffset;
+        if (full_rows) {  // no row of the tile lies past K: the row step can ride in the scalar offset
 #pragma unroll
-        for (int j = 0; j < EA; ++j) {
-            const uint32_t v = vm ? a_base + (uint32_t)(j * RSTEP) * (uint32_t)(PQ * 4) : kOobOffset;
-            ra[j] = buf_load(rs_dy, v, 0);
+            for (int j = 0; j < EA; ++j) ra[j] = buf_load(rs_dy, a_base, (uint32_t)(j * RSTEP) * (uint32_t)(PQ * 4));
+        } else {
+#pragma unroll
+            for (int j = 0; j < EA; ++j) {
+                const uint32_t v = vm ? a_base + (uint32_t)(j * RSTEP) * (uint32_t)(PQ * 4) : kOobOffset;
+                ra[j] = buf_load(rs_dy, v, 0);
+            }
         }
 #pragma unroll
         for (int j = 0; j < EB; ++j) rb[j] = buf_load(rs_x, b_voff, (uint32_t)(j * RSTEP) * (uint32_t)(HW * 4));

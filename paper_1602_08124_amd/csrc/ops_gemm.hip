@@ -309,7 +309,8 @@ size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S
 template <int BM, int BN, int WM, int WN, int BK = 32>
 static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
     auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN, BK>;
-    constexpr size_t smem = sizeof(float) * 2 * BK * ((BM + 1) + (BN + 1));
+    constexpr int PAD = BK >= 32 ? 1 : 32 / BK;  // as in the kernel
+    constexpr size_t smem = sizeof(float) * 2 * BK * ((BM + PAD) + (BN + PAD));
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
