@@ -240,6 +240,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true", help="with --kernel-only: also run a 1 GiB plain copy kernel")
     ap.add_argument("--kernel-table", action="store_true", help="also time every VGG-16 convolution, three passes each")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true", help="skip the roofline kernel (for a profile of the steps alone)")
     ap.add_argument("--cpu-sample-batch", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -298,7 +299,7 @@ def main():
         for p in policies.values():
             if p.get("status") == "ok":
                 p["vs_no_offload"] = p["img_per_s"] / none["img_per_s"]
-    rf = roofline(B, args.batch)
+    rf = None if args.no_roofline else roofline(B, args.batch)
     out = {
         "metric": "img/s VGG-16 b%d fp32 under %g GiB budget (vDNN_all)" % (args.batch, args.budget_gib),
         "value": head.get("img_per_s"), "unit": "img/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
