@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvdnn.so")
-SOURCES = ["ops_gemm.hip", "ops_elem.hip", "ops_api.cpp", "manager.cpp"]
+SOURCES = ["ops_gemm.hip", "ops_elem.hip", "ops_api.cpp", "graph.cpp", "planner.cpp", "manager.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-x", "hip"]
 

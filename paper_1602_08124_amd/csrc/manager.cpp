@@ -1,995 +1,14 @@
-// vDNN memory manager: graph construction, step planning (policy -> ops + block placement) and
-// execution on two HIP streams.  See manager.h for the overall shape.
+// vDNN memory manager, device side: pool and pinned arena, execution of a planned step on two HIP streams, timing,
+// and the C ABI.  Graph construction lives in graph.cpp, planning in planner.cpp; see manager.h for the overall shape.
 #include "manager.h"
 
 #include <algorithm>
-#include <cstdarg>
-#include <cstdio>
-#include <new>
 #include <cstring>
-#include <map>
-#include <set>
+#include <new>
 
 #include "ops.h"
 
 using namespace vdnn;
-
-namespace {
-
-bool in_place(int type) { return type == VDNN_RELU; }
-bool needs_x_in_bwd(int type) { return type == VDNN_CONV || type == VDNN_MAXPOOL || type == VDNN_FC || type == VDNN_SOFTMAX_CE; }
-const char* type_name(int t) {
-    static const char* n[] = {"conv", "relu", "maxpool", "avgpool", "fc", "concat", "softmax_ce"};
-    return (t >= 0 && t <= 6) ? n[t] : "?";
-}
-
-std::string fmt(const char* f, ...) {
-    char b[512];
-    va_list ap;
-    va_start(ap, f);
-    vsnprintf(b, sizeof b, f, ap);
-    va_end(ap);
-    return b;
-}
-
-int buf_of(const vdnn_net& n, int layer) { return layer < 0 ? -1 : n.layers[layer].buf; }
-
-void shape_of(const vdnn_net& n, int layer, int* C, int* H, int* W) {
-    if (layer < 0) { *C = n.in_c; *H = n.in_h; *W = n.in_w; }
-    else { *C = n.layers[layer].C; *H = n.layers[layer].H; *W = n.layers[layer].W; }
-}
-
-}  // namespace
-
-// ---------------------------------------------------------------------------------------------
-// graph
-// ---------------------------------------------------------------------------------------------
-static vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::string& err) {
-    if (d->batch <= 0 || d->in_c <= 0 || d->in_h <= 0 || d->in_w <= 0 || d->n_layers <= 0 || !d->layers) {
-        err = "bad network dimensions";
-        return VDNN_ERR_INVALID_ARG;
-    }
-    n.batch = d->batch; n.in_c = d->in_c; n.in_h = d->in_h; n.in_w = d->in_w;
-    const int L = d->n_layers;
-    n.layers.resize(L);
-    std::vector<int> n_consumers(L + 1, 0);
-    for (int i = 0; i < L; ++i) {
-        const vdnn_layer_desc_t& s = d->layers[i];
-        Layer& l = n.layers[i];
-        l.type = s.type; l.out = s.out_channels; l.k = s.kernel; l.stride = s.stride; l.pad = s.pad;
-        if (s.type < 0 || s.type > VDNN_SOFTMAX_CE) { err = fmt("layer %d: unknown type %d", i, s.type); return VDNN_ERR_INVALID_ARG; }
-        const int want_min = s.type == VDNN_CONCAT ? 2 : 1, want_max = s.type == VDNN_CONCAT ? VDNN_MAX_INPUTS : 1;
-        if (s.n_inputs < want_min || s.n_inputs > want_max) { err = fmt("layer %d: bad number of inputs %d", i, s.n_inputs); return VDNN_ERR_INVALID_ARG; }
-        for (int j = 0; j < s.n_inputs; ++j) {
-            const int src = s.inputs[j];
-            if (src < -1 || src >= i) { err = fmt("layer %d: input %d is not an earlier layer", i, src); return VDNN_ERR_INVALID_ARG; }
-            if (src >= 0 && n.layers[src].type == VDNN_SOFTMAX_CE) { err = fmt("layer %d consumes the loss", i); return VDNN_ERR_INVALID_ARG; }
-            if (std::find(l.inputs.begin(), l.inputs.end(), src) != l.inputs.end()) { err = fmt("layer %d: duplicate input %d", i, src); return VDNN_ERR_INVALID_ARG; }
-            l.inputs.push_back(src);
-            n_consumers[src + 1]++;
-        }
-        int C, H, W;
-        shape_of(n, l.inputs[0], &C, &H, &W);
-        switch (l.type) {
-            case VDNN_CONV:
-                if (l.out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0) { err = fmt("layer %d: bad conv geometry", i); return VDNN_ERR_INVALID_ARG; }
-                l.C = l.out; l.H = (H + 2 * l.pad - l.k) / l.stride + 1; l.W = (W + 2 * l.pad - l.k) / l.stride + 1;
-                if (H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) { err = fmt("layer %d: window larger than image", i); return VDNN_ERR_INVALID_ARG; }
-                l.wcount = (size_t)l.out * C * l.k * l.k;
-                break;
-            case VDNN_MAXPOOL:
-            case VDNN_AVGPOOL:
-                if (l.k <= 0 || l.stride <= 0 || l.pad < 0 || l.pad >= l.k || H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) { err = fmt("layer %d: bad pool geometry", i); return VDNN_ERR_INVALID_ARG; }
-                l.C = C; l.H = (H + 2 * l.pad - l.k) / l.stride + 1; l.W = (W + 2 * l.pad - l.k) / l.stride + 1;
-                break;
-            case VDNN_FC:
-                if (l.out <= 0) { err = fmt("layer %d: bad fc size", i); return VDNN_ERR_INVALID_ARG; }
-                l.C = l.out; l.H = 1; l.W = 1;
-                l.wcount = (size_t)l.out * C * H * W;
-                break;
-            case VDNN_CONCAT: {
-                int csum = 0;
-                for (int src : l.inputs) {
-                    int c2, h2, w2;
-                    shape_of(n, src, &c2, &h2, &w2);
-                    if (h2 != H || w2 != W) { err = fmt("layer %d: concat inputs differ in size", i); return VDNN_ERR_INVALID_ARG; }
-                    csum += c2;
-                }
-                l.C = csum; l.H = H; l.W = W;
-                break;
-            }
-            case VDNN_RELU:
-                l.C = C; l.H = H; l.W = W;
-                break;
-            case VDNN_SOFTMAX_CE:
-                if (i != L - 1) { err = "softmax_ce must be the last layer"; return VDNN_ERR_INVALID_ARG; }
-                l.C = l.H = l.W = 0;
-                break;
-        }
-        if (l.type != VDNN_SOFTMAX_CE && (l.H <= 0 || l.W <= 0)) { err = fmt("layer %d: empty output", i); return VDNN_ERR_INVALID_ARG; }
-        l.buf = in_place(l.type) ? buf_of(n, l.inputs[0]) : i;
-    }
-    if (n.layers[L - 1].type != VDNN_SOFTMAX_CE) { err = "the last layer must be softmax_ce"; return VDNN_ERR_INVALID_ARG; }
-    for (int i = 0; i < L; ++i) {
-        if (in_place(n.layers[i].type) && n_consumers[n.layers[i].inputs[0] + 1] != 1) {
-            err = fmt("layer %d: an in-place layer must be the only consumer of its input", i);
-            return VDNN_ERR_INVALID_ARG;
-        }
-        if (n.layers[i].type != VDNN_SOFTMAX_CE && n_consumers[i + 1] == 0) { err = fmt("layer %d: output is never consumed", i); return VDNN_ERR_INVALID_ARG; }
-    }
-    if (n_consumers[0] == 0) { err = "the network input is never consumed"; return VDNN_ERR_INVALID_ARG; }
-    n.bufs.assign(L + 1, Buffer());
-    for (int b = -1; b < L; ++b) {
-        if (b >= 0 && (n.layers[b].buf != b || n.layers[b].type == VDNN_SOFTMAX_CE)) continue;
-        Buffer& B = n.B(b);
-        shape_of(n, b, &B.C, &B.H, &B.W);
-        B.count = (size_t)n.batch * B.C * B.H * B.W;
-        if (B.count >= 0x7fffffffULL) { err = fmt("feature map %d has 2^31 or more elements", b); return VDNN_ERR_UNSUPPORTED; }
-    }
-    for (int i = 0; i < L; ++i) {
-        const Layer& l = n.layers[i];
-        if (in_place(l.type)) {
-            if (l.buf < 0) { err = "an in-place layer cannot overwrite the network input"; return VDNN_ERR_INVALID_ARG; }
-            n.B(l.buf).inplace.push_back(i);
-        } else {
-            for (int src : l.inputs) n.B(buf_of(n, src)).readers.push_back(i);
-        }
-    }
-    for (int b = -1; b < L; ++b) {
-        Buffer& B = n.B(b);
-        if (!B.count) continue;
-        for (int r : B.readers)
-            if (needs_x_in_bwd(n.layers[r].type)) B.bwd_users.push_back(r);
-        for (int r : B.inplace) B.bwd_users.push_back(r);
-        std::sort(B.bwd_users.begin(), B.bwd_users.end());
-    }
-    // ReLU folding.  Forward: a CONV whose output holds exactly one in-place ReLU applies it in its
-    // epilogue.  Backward: when a feature map holds exactly one in-place ReLU and has a single reader
-    // that is a CONV or max-POOL layer, that reader masks its dX store with (X > 0), which is the
-    // ReLU's backward computation.  Values are identical to running the ReLU kernels separately.
-    for (int b = 0; b < L; ++b) {
-        Buffer& B = n.B(b);
-        if (!B.count || B.inplace.size() != 1) continue;
-        const int r = B.inplace[0];
-        if (n.layers[b].type == VDNN_CONV) { n.layers[b].relu_after = r; n.layers[r].fwd_folded_into = b; }
-        if (B.readers.size() == 1) {
-            const int m = B.readers[0];
-            if (n.layers[m].type == VDNN_CONV || n.layers[m].type == VDNN_MAXPOOL) { n.layers[m].relu_before = r; n.layers[r].bwd_folded_into = m; }
-        }
-    }
-    n.cap_out.assign(L, nullptr);
-    n.cap_grad.assign(L, nullptr);
-    return VDNN_OK;
-}
-
-// A test hook on the tensors in between switches the folding off for that pair, so that the hook
-// still sees the unfused intermediate value.
-static bool fold_fwd(const vdnn_net& n, int conv) {
-    const int r = n.layers[conv].relu_after;
-    return r >= 0 && !n.cap_out[conv];
-}
-static bool fold_bwd(const vdnn_net& n, int reader) {
-    const int r = n.layers[reader].relu_before;
-    return r >= 0 && !n.cap_grad[r];
-}
-
-// ---------------------------------------------------------------------------------------------
-// workspace of a layer (partial sums of reduction-split GEMMs)
-// ---------------------------------------------------------------------------------------------
-static size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false) {
-    const Layer& l = n.layers[i];
-    int C, H, W;
-    shape_of(n, l.inputs[0], &C, &H, &W);
-    if (l.type == VDNN_CONV && memopt) return 0;  // the memory-optimal algorithm needs X, Y, W only
-    if (l.type == VDNN_CONV && !bwd) return conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
-    if (l.type == VDNN_CONV && bwd) {
-        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
-        return std::max(conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad),
-                        need_dx ? conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad) : (size_t)0);
-    }
-    if (l.type == VDNN_FC) {
-        const int I = C * H * W;
-        if (!bwd) return fc_workspace(n.batch, I, l.out, 0);
-        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
-        return std::max(fc_workspace(n.batch, I, l.out, 2), need_dx ? fc_workspace(n.batch, I, l.out, 1) : (size_t)0);
-    }
-    return 0;
-}
-
-static bool selected(const vdnn_net& n, int b, int policy) {
-    const Buffer& B = n.B(b);
-    if (B.bwd_users.empty()) return false;
-    bool conv = false, pool = false;
-    for (int r : B.readers) {
-        const int t = n.layers[r].type;
-        conv |= t == VDNN_CONV;
-        pool |= t == VDNN_MAXPOOL || t == VDNN_AVGPOOL;
-    }
-    if (policy == VDNN_POLICY_ALL) return conv || pool;
-    if (policy == VDNN_POLICY_CONV) return conv;
-    return false;
-}
-
-// ---------------------------------------------------------------------------------------------
-// planning
-// ---------------------------------------------------------------------------------------------
-namespace {
-
-struct Compiler {
-    const vdnn_net& n;
-    Plan& p;
-    size_t budget;  // aligned; SIZE_MAX/4 when unlimited
-    size_t live = 0;
-    int phase = 0, layer = -1;
-    std::vector<size_t> samples;
-    bool failed = false;
-
-    Compiler(const vdnn_net& net, Plan& plan, size_t b) : n(net), p(plan), budget(b) {}
-
-    std::string where() const {
-        if (phase == 0) return "create";
-        return fmt("%c%d", phase == 1 ? 'F' : 'B', layer);
-    }
-
-    Op& emit(OpKind k) {
-        Op o;
-        o.kind = k; o.phase = phase; o.layer = layer;
-        p.ops.push_back(o);
-        return p.ops.back();
-    }
-
-    int alloc(const std::string& tag, size_t raw, bool persistent = false) {
-        Block b;
-        b.tag = tag; b.raw = raw; b.bytes = align_up(std::max<size_t>(raw, 1));
-        b.persistent = persistent;
-        b.t0 = (int)p.ops.size(); b.t1 = -1;
-        if (live + b.bytes > budget) {
-            failed = true;
-            p.fail_where = where();
-            p.fail_why = fmt("%s: allocating %zu bytes for %s with %zu live exceeds the budget of %zu", where().c_str(), b.bytes,
-                             tag.c_str(), live, budget);
-            return -1;
-        }
-        live += b.bytes;
-        p.peak = std::max(p.peak, live);
-        p.blocks.push_back(b);
-        const int id = (int)p.blocks.size() - 1;
-        emit(OP_ALLOC).block = id;
-        return id;
-    }
-
-    void release(int id) {
-        live -= p.blocks[id].bytes;
-        emit(OP_FREE).block = id;
-        p.blocks[id].t1 = (int)p.ops.size();
-    }
-};
-
-}  // namespace
-
-// Placement of the transient blocks above the persistent region.  Blocks are taken in a priority
-// order and each takes the lowest offset at which it overlaps no already placed block whose lifetime
-// intersects its own.  The live-byte peak is the lower bound of the address range.  Four orders are
-// tried first (by size; by lifetime; by size x lifetime; by allocation time); if none reaches the bound, the
-// same priorities are perturbed with seeded noise for a bounded number of rounds and the best placement
-// wins.  On the paper's workloads this reaches the bound (no fragmentation) within a few rounds.
-//
-// A block that moves in pieces occupies a staircase in (time x address): one rectangle per piece, at fixed
-// distances from the block's offset.  It takes the lowest offset at which none of its rectangles meets a
-// placed one; later blocks see its rectangles one by one and can move into the part of the range a piece
-// has left (or not yet taken).
-//
-// A host, its tenants and its twin (see retime) form one such object too: the tenants' rectangles and the
-// twin's staircase lie inside the host's range by construction, so the group is placed as a whole.
-namespace {
-struct Rect { size_t off, bytes; int t0, t1; };
-struct Unit {
-    std::vector<Rect> rects;                         // offsets relative to the unit's offset
-    std::vector<std::pair<int, size_t>> members;     // (block, distance from the unit's offset)
-    size_t bytes = 0;                                // address range the unit spans
-    int t0 = 1 << 30, t1 = 0;
-};
-}
-
-static std::vector<Unit> make_units(const Plan& p) {
-    std::vector<Unit> units;
-    std::vector<int> unit_of(p.blocks.size(), -1);
-    auto add = [&](Unit& u, int id, size_t rel) {
-        const Block& b = p.blocks[id];
-        u.members.push_back({id, rel});
-        for (int i = 0; i < b.parts; ++i) {
-            const Rect r{rel + (b.parts == 1 ? 0 : (size_t)i * b.part_bytes), b.piece_bytes(i), b.parts == 1 ? b.t0 : b.part_t0[i],
-                         b.parts == 1 ? b.t1 : b.part_t1[i]};
-            u.rects.push_back(r);
-            u.bytes = std::max(u.bytes, r.off + r.bytes);
-            u.t0 = std::min(u.t0, r.t0);
-            u.t1 = std::max(u.t1, r.t1);
-        }
-    };
-    for (int id = 0; id < (int)p.blocks.size(); ++id) {
-        if (p.blocks[id].persistent || p.blocks[id].host >= 0) continue;
-        unit_of[id] = (int)units.size();
-        units.emplace_back();
-        add(units.back(), id, 0);
-    }
-    for (int id = 0; id < (int)p.blocks.size(); ++id)
-        if (!p.blocks[id].persistent && p.blocks[id].host >= 0) add(units[unit_of[p.blocks[id].host]], id, p.blocks[id].host_rel);
-    return units;
-}
-
-static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, size_t base, const std::vector<double>& key,
-                              std::vector<size_t>& offsets) {
-    std::vector<int> order(units.size());
-    for (size_t i = 0; i < units.size(); ++i) order[i] = (int)i;
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key[a] > key[b]; });
-    std::vector<Rect> placed;  // absolute offsets
-    offsets.assign(n_blocks, 0);
-    size_t extent = base;
-    std::vector<std::pair<size_t, size_t>> conf;
-    std::vector<Rect> near;
-    for (int ui : order) {
-        const Unit& u = units[ui];
-        size_t off = base;
-        if (u.rects.size() == 1) {
-            conf.clear();
-            for (const Rect& q : placed)
-                if (q.t0 < u.t1 && u.t0 < q.t1) conf.push_back({q.off, q.bytes});
-            std::sort(conf.begin(), conf.end());
-            for (auto& c : conf) {
-                if (off + u.bytes <= c.first) break;
-                off = std::max(off, c.first + c.second);
-            }
-        } else {
-            near.clear();
-            for (const Rect& q : placed)
-                if (q.t0 < u.t1 && u.t0 < q.t1) near.push_back(q);
-            auto fits = [&](size_t o) {
-                for (const Rect& r : u.rects)
-                    for (const Rect& q : near)
-                        if (q.t0 < r.t1 && r.t0 < q.t1 && o + r.off < q.off + q.bytes && q.off < o + r.off + r.bytes) return false;
-                return true;
-            };
-            std::vector<size_t> cands{base};
-            for (const Rect& r : u.rects)
-                for (const Rect& q : near)
-                    if (q.t0 < r.t1 && r.t0 < q.t1 && q.off + q.bytes >= base + r.off) cands.push_back(q.off + q.bytes - r.off);
-            std::sort(cands.begin(), cands.end());
-            for (size_t o : cands)
-                if (fits(o)) { off = o; break; }   // sliding down from above every neighbour stops at one of the candidates
-        }
-        for (const Rect& r : u.rects) placed.push_back({off + r.off, r.bytes, r.t0, r.t1});
-        for (auto& m : u.members) offsets[m.first] = off + m.second;
-        extent = std::max(extent, off + u.bytes);
-    }
-    return extent;
-}
-
-static size_t place_blocks(Plan& p, size_t base) {
-    const std::vector<Unit> units = make_units(p);
-    if (units.empty()) return base;
-    const size_t n = units.size();
-    std::vector<double> size(n), life(n), area(n), start(n), key(n);
-    for (size_t i = 0; i < n; ++i) {
-        // ties: earlier blocks first (the sort is stable)
-        size[i] = (double)units[i].bytes;
-        life[i] = (double)(units[i].t1 - units[i].t0);
-        area[i] = size[i] * life[i];
-        start[i] = (double)(p.ops.size() + 2 - units[i].t0);  // allocation order: what a run-time first-fit allocator would do
-    }
-    std::vector<size_t> best, cur;
-    size_t best_extent = (size_t)-1;
-    constexpr int kKinds = 4;
-    const std::vector<double>* base_keys[kKinds] = {&size, &life, &area, &start};
-    for (int kind = 0; kind < kKinds; ++kind) {
-        const size_t e = place_with_keys(units, p.blocks.size(), base, *base_keys[kind], cur);
-        if (e < best_extent) { best_extent = e; best = cur; }
-    }
-    uint64_t rng = 0x9E3779B97F4A7C15ull;  // fixed seed: the plan is a pure function of (net, policy, budget)
-    auto next = [&]() { rng = rng * 6364136223846793005ull + 1442695040888963407ull; return (double)(rng >> 11) / 9007199254740992.0; };
-    const double noises[4] = {0.1, 0.3, 0.6, 1.0};
-    for (int round = 0; round < 300 && best_extent > p.peak; ++round) {
-        const std::vector<double>& k0 = *base_keys[(int)(next() * kKinds) % kKinds];
-        const double noise = noises[(int)(next() * 4) % 4];
-        for (size_t i = 0; i < n; ++i) key[i] = k0[i] * (1.0 + noise * (next() - 0.5));
-        const size_t e = place_with_keys(units, p.blocks.size(), base, key, cur);
-        if (e < best_extent) { best_extent = e; best = cur; }
-    }
-    for (const Unit& u : units)
-        for (auto& m : u.members) p.blocks[m.first].offset = best[m.first];
-    return best_extent;
-}
-
-// Compiles one training step under a static policy (NONE / ALL / CONV) and a convolution algorithm
-// mode: performance-optimal everywhere, memory-optimal everywhere, or greedy (performance-optimal
-// unless that layer's workspace would overflow the budget: Section 3.3, phase 3 of vDNN_dyn).
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm);
-
-// offload_set (indexed by buffer id + 1), when given, replaces the policy's choice of feature maps;
-// place = false stops after the byte accounting (p.ok then only says that the live total fits).
-static void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set = nullptr,
-                         bool place = true, int fill_pm = 0, int fill_bwd_pm = 0) {
-    p = Plan();
-    p.policy = policy;
-    p.algo = algo;
-    p.memopt_fwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
-    p.memopt_bwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
-    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
-    Compiler c(n, p, budget);
-    const int L = (int)n.layers.size();
-    std::vector<int> res(L + 1, -1), grad(L + 1, -1);        // buffer id + 1 -> block
-    std::vector<char> on_host(L + 1, 0);
-    std::vector<std::vector<int>> offloaded_at(L);            // layer -> buffers it offloaded
-    std::vector<int> host_block(L + 1, -1);                   // buffer -> block it was offloaded from (for host_off)
-    std::vector<int> w_block(L, -1), dw_block(L, -1);
-    size_t pinned = 0;
-    std::vector<size_t> host_off(L + 1, 0);
-
-#define CHECK_FAIL() do { if (c.failed) return; } while (0)
-
-    // ---- create: persistent blocks --------------------------------------------------------
-    c.phase = 0;
-    for (int i = 0; i < L; ++i) {
-        if (!n.layers[i].wcount) continue;
-        w_block[i] = c.alloc(fmt("W%d", i), n.layers[i].wcount * 4, true); CHECK_FAIL();
-        dw_block[i] = c.alloc(fmt("dW%d", i), n.layers[i].wcount * 4, true); CHECK_FAIL();
-    }
-    p.labels_block = c.alloc("labels", (size_t)n.batch * 4, true); CHECK_FAIL();
-    p.loss_block = c.alloc("loss", 4, true); CHECK_FAIL();
-    p.persistent = c.live;
-    {   // persistent blocks are packed from offset 0 in creation order: their place never depends on the policy
-        size_t off = 0;
-        for (Block& b : p.blocks) { b.offset = off; off += b.bytes; b.t0 = 0; b.t1 = 1 << 30; }
-    }
-
-    // ---- forward --------------------------------------------------------------------------
-    c.phase = 1; c.layer = -1;
-    p.first_fwd_op = (int)p.ops.size();
-    res[0] = c.alloc("B-1", n.B(-1).count * 4); CHECK_FAIL();
-    p.blocks[res[0]].buf = -1;
-    {
-        Op& o = c.emit(OP_LOAD_INPUT);
-        o.out_block = res[0];
-    }
-    for (int i = 0; i < L; ++i) {
-        const Layer& l = n.layers[i];
-        c.layer = i;
-        c.emit(OP_SAMPLE);
-        c.samples.push_back(c.live);
-        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); p.blocks[res[i + 1]].buf = i; }
-        size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
-        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
-        int wsb = -1;
-        if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
-        std::vector<int> in_bufs;
-        for (int src : l.inputs) in_bufs.push_back(buf_of(n, src));
-        if (!in_place(l.type)) {
-            for (int b : in_bufs) {
-                if (n.B(b).readers.back() == i && (offload_set ? (bool)(*offload_set)[b + 1] : selected(n, b, policy))) {
-                    Op& o = c.emit(OP_OFFLOAD);
-                    o.block = res[b + 1]; o.buf = b;
-                    host_off[b + 1] = pinned;
-                    p.blocks[res[b + 1]].host_off = pinned;
-                    pinned += align_up(n.B(b).count * 4);
-                    p.offloaded += n.B(b).count * 4;
-                    p.n_offload++;
-                    offloaded_at[i].push_back(b);
-                }
-            }
-        }
-        {
-            Op& o = c.emit(OP_FWD);
-            for (int b : in_bufs) o.in_blocks.push_back(res[b + 1]);
-            o.out_block = res[l.buf + 1];
-            o.ws_block = wsb;
-        }
-        if (wsb >= 0) c.release(wsb);
-        for (int b : offloaded_at[i]) {
-            Op& o = c.emit(OP_WAIT_COPY);
-            o.block = res[b + 1]; o.buf = b;
-            c.release(res[b + 1]);
-            res[b + 1] = -1;
-            on_host[b + 1] = 1;
-        }
-        if (!in_place(l.type))
-            for (int b : in_bufs)
-                if (res[b + 1] >= 0 && n.B(b).readers.back() == i && n.B(b).bwd_users.empty()) { c.release(res[b + 1]); res[b + 1] = -1; }
-    }
-
-    // ---- backward -------------------------------------------------------------------------
-    c.phase = 2;
-    p.first_bwd_op = (int)p.ops.size();
-    auto fetch = [&](int b, OpKind kind) -> bool {
-        res[b + 1] = c.alloc(fmt("B%d", b), n.B(b).count * 4);
-        if (c.failed) return false;
-        p.blocks[res[b + 1]].buf = b;
-        p.blocks[res[b + 1]].host_off = host_off[b + 1];
-        on_host[b + 1] = 0;
-        Op& o = c.emit(kind);
-        o.block = res[b + 1]; o.buf = b;
-        p.prefetched += n.B(b).count * 4;
-        return true;
-    };
-    for (int m = L - 1; m >= 0; --m) {
-        const Layer& l = n.layers[m];
-        c.layer = m;
-        c.emit(OP_SAMPLE);
-        c.samples.push_back(c.live);
-        // findPrefetchLayer (Fig. code_prefetch): nearest preceding layer whose offloaded X is still on the host;
-        // the search window ends at the first CONV layer that has nothing to prefetch.
-        std::vector<int> issued;
-        for (int j = m - 1; j >= 0; --j) {
-            std::vector<int> pending;
-            for (int b : offloaded_at[j]) if (on_host[b + 1]) pending.push_back(b);
-            if (!pending.empty()) {
-                for (int b : pending) { if (!fetch(b, OP_PREFETCH)) return; p.n_prefetch++; issued.push_back(b); }
-                break;
-            }
-            if (n.layers[j].type == VDNN_CONV) break;
-        }
-        std::vector<int> in_bufs;
-        for (int src : l.inputs) in_bufs.push_back(buf_of(n, src));
-        std::vector<int> needed;
-        if (in_place(l.type)) needed.push_back(l.buf);
-        else if (needs_x_in_bwd(l.type)) needed = in_bufs;
-        for (int b : needed)
-            if (on_host[b + 1]) { if (!fetch(b, OP_ONDEMAND)) return; p.n_ondemand++; }
-        std::vector<int> gout(in_bufs.size(), -1), gacc(in_bufs.size(), -1), temps;
-        if (!in_place(l.type)) {
-            for (size_t k = 0; k < in_bufs.size(); ++k) {
-                const int b = in_bufs[k];
-                if (b < 0) continue;
-                if (grad[b + 1] < 0) { grad[b + 1] = c.alloc(fmt("dB%d", b), n.B(b).count * 4); CHECK_FAIL(); gout[k] = grad[b + 1]; }
-                else { const int t = c.alloc(fmt("T%d", b), n.B(b).count * 4); CHECK_FAIL(); temps.push_back(t); gout[k] = t; gacc[k] = grad[b + 1]; }
-            }
-        }
-        size_t ws = layer_workspace(n, m, true, p.memopt_bwd[m]);
-        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_bwd[m] = 1; ws = 0; }
-        int wsb = -1;
-        if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
-        {
-            Op& o = c.emit(OP_BWD);
-            for (int b : in_bufs) o.in_blocks.push_back(res[b + 1]);
-            o.out_block = l.type == VDNN_SOFTMAX_CE ? -1 : res[l.buf + 1];
-            o.gin_block = l.type == VDNN_SOFTMAX_CE ? -1 : grad[l.buf + 1];
-            o.gout_blocks = gout; o.gacc_blocks = gacc; o.ws_block = wsb;
-        }
-        if (wsb >= 0) c.release(wsb);
-        for (int t : temps) c.release(t);
-        for (int b : issued) {  // end-of-layer synchronisation with the prefetch issued for this layer
-            Op& o = c.emit(OP_WAIT_COPY);
-            o.block = res[b + 1]; o.buf = b;
-        }
-        if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { c.release(grad[m + 1]); grad[m + 1] = -1; }
-        for (int b = -1; b < L; ++b)
-            if (res[b + 1] >= 0 && !n.B(b).bwd_users.empty() && n.B(b).bwd_users.front() == m) { c.release(res[b + 1]); res[b + 1] = -1; }
-    }
-#undef CHECK_FAIL
-    p.pinned = pinned;
-    p.w_block = w_block;
-    p.dw_block = dw_block;
-    p.offload_set.assign(L + 1, 0);
-    for (int i = 0; i < L; ++i)
-        for (int b : offloaded_at[i]) p.offload_set[b + 1] = 1;
-    for (int i = 0; i < L; ++i)
-        if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
-    if (place) finish_plan(n, p, fill_pm, fill_bwd_pm);
-    else p.ok = true;
-}
-
-// Budget-aware transfer windows (not in the paper, which synchronises the two streams at the end of every
-// layer: Section 3.2).  The transfers of the static schedule stay; what moves is when the pool gives up or
-// takes the memory.
-//   forward:  the release of an offloaded X (and the wait for its copy) is held back; held blocks queue in
-//             copy order; an allocation that would pass `soft` first lets the oldest go, until the live total
-//             fits.  The range of X is lent out while X is away: a feature map that is not offloaded itself
-//             and had to let something go becomes a tenant of the block released last, lined up from the low
-//             end of its range (pieces go from the low end upwards), and keeps letting pieces go until that
-//             host has room for it; when a host runs out of pieces the next held block takes over.  The rest
-//             go at the end of forward propagation;
-//   backward: a block that moves in pieces is fetched from its top piece down, the mirror image of forward;
-//             a fetch returns to the range its buffer had in forward propagation (as the host's twin) when
-//             every tenant has left by then; the wait for a fetch moves to just before the first computation
-//             that reads it.  Once the blocks have addresses, hoist_fetches moves every fetch (allocation +
-//             copy), in the order of the static schedule, to the earliest point, not before the previous
-//             fetch, from which its own address range is free and live bytes plus its size stay within
-//             `soft_bwd`, up to its original place.
-static void retime(const vdnn_net& n, Plan& p, size_t soft) {
-    const int L = (int)n.layers.size();
-    constexpr int kMaxParts = 32;
-    // Blocks larger than the part size move in at most kMaxParts pieces of equal (aligned) size.
-    auto split = [&](int block) {
-        Block& b = p.blocks[block];
-        if (!n.part_bytes || b.bytes <= n.part_bytes) return 1;
-        const size_t k = std::min<size_t>(kMaxParts, (b.bytes + n.part_bytes - 1) / n.part_bytes);
-        b.part_bytes = align_up((b.bytes + k - 1) / k);
-        b.parts = (int)((b.bytes + b.part_bytes - 1) / b.part_bytes);
-        return b.parts;
-    };
-    std::vector<Op> out;
-    out.reserve(p.ops.size() + 64);
-    for (int t = 0; t < p.first_fwd_op; ++t) out.push_back(p.ops[t]);
-    size_t live = p.persistent;
-    struct Held { Op wait, free; size_t bytes; };
-    std::vector<Held> held;
-    size_t held_head = 0;
-    std::vector<size_t> released(p.blocks.size(), 0), taken(p.blocks.size(), 0);  // per host: bytes given up / lent so far
-    std::vector<int> fwd_block_of(L + 1, -1);  // buffer id + 1 -> the block that was offloaded
-    int host = -1;                             // block released last
-    auto let_go = [&](int layer) {
-        Held& h = held[held_head++];
-        h.wait.layer = h.free.layer = layer;
-        out.push_back(h.wait);
-        out.push_back(h.free);
-        live -= h.bytes;
-        host = h.free.block;
-        released[host] += h.bytes;
-    };
-    for (int t = p.first_fwd_op; t < p.first_bwd_op; ++t) {
-        const Op& o = p.ops[t];
-        if (o.kind == OP_OFFLOAD) {
-            fwd_block_of[o.buf + 1] = o.block;
-            const int k = split(o.block);
-            for (int i = 0; i < k; ++i) {
-                Op c = o;
-                c.part = k == 1 ? -1 : i;
-                out.push_back(c);
-            }
-            continue;
-        }
-        if (o.kind == OP_WAIT_COPY && t + 1 < p.first_bwd_op && p.ops[t + 1].kind == OP_FREE && p.ops[t + 1].block == o.block) {
-            const Block& b = p.blocks[o.block];
-            for (int i = 0; i < b.parts; ++i) {
-                Held h{o, p.ops[t + 1], b.piece_bytes(i)};
-                h.wait.part = h.free.part = b.parts == 1 ? -1 : i;
-                held.push_back(h);
-            }
-            ++t;
-            continue;
-        }
-        if (o.kind == OP_ALLOC) {
-            const size_t s = p.blocks[o.block].bytes;
-            if (live + s > soft) {
-                // a feature map that is not offloaded itself moves into the range of the block released last
-                Block& me = p.blocks[o.block];
-                const bool rents = me.buf >= -1 && !p.offload_set[me.buf + 1];
-                auto room = [&]() { return host >= 0 ? released[host] - taken[host] : (size_t)0; };
-                while (held_head < held.size() && (live + s > soft || (rents && room() < s))) let_go(o.layer);
-                if (rents && room() >= s) {
-                    me.host = host;
-                    me.host_rel = taken[host];
-                    taken[host] += s;
-                }
-            }
-            live += s;
-        } else if (o.kind == OP_FREE) {
-            live -= p.blocks[o.block].bytes;
-        }
-        out.push_back(o);
-    }
-    while (held_head < held.size()) let_go(L - 1);
-    const int new_first_bwd = (int)out.size();
-
-    // backward: fetches stay where the static schedule has them (hoist_fetches moves them once the blocks have
-    // addresses), but are cut into pieces, top piece first, and awaited just before their first reader
-    const std::vector<Op> bw(p.ops.begin() + p.first_bwd_op, p.ops.end());
-    const int nb = (int)bw.size();
-    std::vector<int> freed_at(p.blocks.size(), -1);  // block -> backward op that releases it
-    for (int t = 0; t < nb; ++t)
-        if (bw[t].kind == OP_FREE) freed_at[bw[t].block] = t;
-    std::vector<std::vector<int>> await(p.blocks.size());  // block -> pieces whose copy the first reader has to wait for
-    std::vector<char> waited(p.blocks.size(), 0);
-    for (int t = 0; t < nb; ++t) {
-        const Op& o = bw[t];
-        if (o.kind == OP_ALLOC && t + 1 < nb && (bw[t + 1].kind == OP_PREFETCH || bw[t + 1].kind == OP_ONDEMAND) && bw[t + 1].block == o.block) {
-            const int block = o.block;
-            const int k = split(block);
-            // the fetch returns to the range its buffer had in forward propagation when every tenant has left by then
-            const int fwd_block = fwd_block_of[p.blocks[block].buf + 1];
-            if (fwd_block >= 0) {
-                bool any = false, gone = true;
-                for (size_t b = 0; b < p.blocks.size(); ++b)
-                    if (p.blocks[b].host == fwd_block) { any = true; gone = gone && freed_at[b] >= 0 && freed_at[b] < t; }
-                if (any && gone) { p.blocks[block].host = fwd_block; p.blocks[block].host_rel = 0; }
-            }
-            for (int i = k - 1; i >= 0; --i) {
-                Op a = o, c = bw[t + 1];
-                a.part = c.part = k == 1 ? -1 : i;
-                out.push_back(a);
-                out.push_back(c);
-                if (c.kind == OP_PREFETCH) await[block].push_back(c.part);  // an on-demand fetch waits by itself
-            }
-            ++t;
-            continue;
-        }
-        if (o.kind == OP_WAIT_COPY && !await[o.block].empty()) continue;  // re-issued below, before the first reader
-        if (o.kind == OP_BWD) {
-            std::vector<int> reads = o.in_blocks;
-            reads.push_back(o.out_block);
-            for (int b : reads)
-                if (b >= 0 && !await[b].empty() && !waited[b]) {
-                    for (int part : await[b]) {
-                        Op w;
-                        w.kind = OP_WAIT_COPY; w.phase = 2; w.layer = o.layer; w.block = b; w.part = part;
-                        out.push_back(w);
-                    }
-                    waited[b] = 1;
-                }
-        }
-        out.push_back(o);
-    }
-    p.ops.swap(out);
-    p.first_bwd_op = new_first_bwd;
-}
-
-// Lifetimes of blocks and pieces in op indices, live-byte statistics and copy counts of the op list.
-static void measure_plan(Plan& p) {
-    size_t live = 0;
-    double sum = 0.0;
-    size_t n_samples = 0;
-    p.peak = 0; p.n_offload = p.n_prefetch = p.n_ondemand = 0;
-    for (Block& b : p.blocks) {
-        b.t0 = b.t1 = -1;
-        b.part_t0.assign(b.parts, -1);
-        b.part_t1.assign(b.parts, -1);
-    }
-    for (int t = 0; t < (int)p.ops.size(); ++t) {
-        const Op& o = p.ops[t];
-        if (o.kind == OP_ALLOC || o.kind == OP_FREE) {
-            Block& b = p.blocks[o.block];
-            const size_t bytes = o.part < 0 ? b.bytes : b.piece_bytes(o.part);
-            for (int i = 0; i < b.parts; ++i) {
-                if (o.part >= 0 && i != o.part) continue;
-                if (o.kind == OP_ALLOC) b.part_t0[i] = t; else b.part_t1[i] = t + 1;
-            }
-            if (o.kind == OP_ALLOC) { if (b.t0 < 0) b.t0 = t; live += bytes; p.peak = std::max(p.peak, live); }
-            else { b.t1 = t + 1; live -= bytes; }
-        }
-        else if (o.kind == OP_SAMPLE) { sum += (double)live; ++n_samples; }
-        else if (o.kind == OP_OFFLOAD) p.n_offload++;   // copies issued: a block that moves in pieces counts once per piece
-        else if (o.kind == OP_PREFETCH) p.n_prefetch++;
-        else if (o.kind == OP_ONDEMAND) p.n_ondemand++;
-    }
-    const int t_end = (int)p.ops.size() + 1;
-    for (Block& b : p.blocks) {
-        if (b.persistent) { b.t0 = 0; b.t1 = 1 << 30; }
-        else if (b.t1 < 0) b.t1 = t_end;  // still live at the end of the step (nothing should be)
-        for (int i = 0; i < b.parts; ++i) {
-            if (b.persistent) { b.part_t0[i] = 0; b.part_t1[i] = 1 << 30; }
-            else if (b.part_t1[i] < 0) b.part_t1[i] = t_end;
-        }
-    }
-    p.avg = n_samples ? sum / (double)n_samples : 0.0;
-}
-
-namespace {
-struct Span { size_t off, bytes; int t0, t1, block; };
-}
-static std::vector<Span> spans_of(const Plan& p) {
-    std::vector<Span> v;
-    for (int id = 0; id < (int)p.blocks.size(); ++id) {
-        const Block& b = p.blocks[id];
-        if (b.persistent) continue;
-        for (int i = 0; i < b.parts; ++i)
-            v.push_back({b.offset + (b.parts == 1 ? 0 : (size_t)i * b.part_bytes), b.piece_bytes(i), b.parts == 1 ? b.t0 : b.part_t0[i],
-                         b.parts == 1 ? b.t1 : b.part_t1[i], id});
-    }
-    return v;
-}
-
-// True when two pieces of memory that are live at the same time share an address.
-static bool plan_overlaps(const Plan& p) {
-    const std::vector<Span> v = spans_of(p);
-    for (size_t i = 0; i < v.size(); ++i)
-        for (size_t j = i + 1; j < v.size(); ++j)
-            if (v[i].t0 < v[j].t1 && v[j].t0 < v[i].t1 && v[i].off < v[j].off + v[j].bytes && v[j].off < v[i].off + v[i].bytes) return true;
-    return false;
-}
-
-// Early fetches, after placement (see retime).  A fetch (or a piece of one) sits at address range R from op q
-// of the static schedule.  It may start at any earlier op from which R is free: nothing else that the
-// placement put into R is live then.  Because every other block keeps its address and its lifetime, the
-// placement stays valid, and the pool's extent does not change.
-static void hoist_fetches(Plan& p, size_t soft_bwd) {
-    const std::vector<Span> spans = spans_of(p);
-    const int f0 = p.first_bwd_op, nt = (int)p.ops.size();
-    std::vector<size_t> before(nt + 1, 0);  // live bytes before each op
-    {
-        size_t live = 0;
-        for (int t = 0; t < nt; ++t) {
-            before[t] = live;
-            const Op& o = p.ops[t];
-            if (o.kind != OP_ALLOC && o.kind != OP_FREE) continue;
-            const Block& b = p.blocks[o.block];
-            const size_t bytes = o.part < 0 ? b.bytes : b.piece_bytes(o.part);
-            if (o.kind == OP_ALLOC) live += bytes; else live -= bytes;
-        }
-    }
-    std::vector<std::vector<int>> landing(nt + 1);
-    std::vector<char> skip(nt + 1, 0);
-    int lo = f0;
-    for (int q = f0; q + 1 < nt; ++q) {
-        const Op& a = p.ops[q];
-        const Op& c = p.ops[q + 1];
-        if (a.kind != OP_ALLOC || (c.kind != OP_PREFETCH && c.kind != OP_ONDEMAND) || c.block != a.block || c.part != a.part) continue;
-        const Block& b = p.blocks[a.block];
-        const size_t s = a.part < 0 ? b.bytes : b.piece_bytes(a.part);
-        const size_t r0 = b.offset + (a.part < 0 ? 0 : (size_t)a.part * b.part_bytes), r1 = r0 + s;
-        int ready = lo;
-        for (const Span& v : spans)
-            if (v.t0 < q && v.off < r1 && r0 < v.off + v.bytes && !(v.block == a.block)) ready = std::max(ready, v.t1);
-        int j = q;
-        while (j > ready && before[j - 1] + s <= soft_bwd) --j;
-        if (j < q) {
-            for (int t = j; t <= q; ++t) before[t] += s;
-            landing[j].push_back(q);
-            skip[q] = skip[q + 1] = 1;
-            lo = j;
-        } else {
-            lo = q + 2;
-        }
-    }
-    std::vector<Op> out;
-    out.reserve(p.ops.size() + 32);
-    auto emit_landing = [&](int t) {
-        for (int q : landing[t]) {
-            Op a = p.ops[q], c = p.ops[q + 1];
-            a.layer = c.layer = p.ops[t].layer;
-            c.kind = OP_PREFETCH;
-            out.push_back(a);
-            out.push_back(c);
-        }
-    };
-    for (int t = 0; t < nt; ++t) {
-        const Op& o = p.ops[t];
-        if (o.kind != OP_SAMPLE) emit_landing(t);
-        if (!skip[t]) out.push_back(o);
-        else if (o.kind == OP_ONDEMAND) {  // the copy left: what stays is the wait that an on-demand fetch implies
-            Op w = o;
-            w.kind = OP_WAIT_COPY;
-            out.push_back(w);
-        }
-        if (o.kind == OP_SAMPLE) emit_landing(t);
-    }
-    p.ops.swap(out);
-}
-
-// Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
-    const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
-    p.ok = false;
-    p.fill_pm = p.fill_bwd_pm = 0;
-    // budget * fill / 1000 rounded down to a block boundary, in integers
-    auto soft = [&](int pm) { return (size_t)((unsigned __int128)budget * (unsigned)pm / 1000u) / kAlign * kAlign; };
-    const bool windows = (fill_pm > 0 || fill_bwd_pm > 0) && n.budget;
-    if (windows) {
-        retime(n, p, soft(fill_pm));
-        p.fill_pm = fill_pm;
-    }
-    measure_plan(p);
-    p.extent = place_blocks(p, p.persistent);
-    if (p.extent > budget) {
-        p.fail_where = "placement";
-        p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
-        return;
-    }
-    if (windows && fill_bwd_pm > 0) {
-        const Plan kept = p;
-        hoist_fetches(p, soft(fill_bwd_pm));
-        measure_plan(p);
-        p.fill_bwd_pm = fill_bwd_pm;
-        if (plan_overlaps(p)) p = kept;  // cannot happen by construction; a plan that fails the check is never run
-    }
-    p.ok = true;
-}
-
-static size_t baseline_bytes(const vdnn_net& n) {
-    const int L = (int)n.layers.size();
-    size_t fm = 0, wb = 0, gmax = 0, wmax = 0;
-    for (int b = -1; b < L; ++b) {
-        const size_t s = n.B(b).count ? align_up(n.B(b).count * 4) : 0;
-        fm += s;
-        if (b >= 0) gmax = std::max(gmax, s);
-    }
-    for (int i = 0; i < L; ++i) {
-        if (n.layers[i].wcount) wb += 2 * align_up(n.layers[i].wcount * 4);
-        wmax = std::max(wmax, std::max(layer_workspace(n, i, false), layer_workspace(n, i, true)));
-    }
-    return fm + wb + 2 * gmax + align_up(wmax);
-}
-
-// Section 3.3, "Dynamic vDNN".  Trainability of a pass is decided by the planner, which performs
-// exactly the allocations a real pass would (the paper's profiling passes only use pass/fail).
-//   1. all with the memory-optimal algorithm: can the network be trained at all;
-//   2. performance-optimal algorithms without offloading, else with conv, else with all;
-//   3. greedy per-layer algorithm downgrade under conv, then under all; else back to 1.
-//
-// VDNN_POLICY_FIT is not one of the paper's policies.  It takes the observation behind vDNN_dyn (offload no
-// more than the budget asks for) one step further: the offload set is built from single feature maps, and the
-// transfers get budget-aware windows (see retime).
-static bool fits_with(const vdnn_net& n, const std::vector<char>& set, int algo) {
-    Plan q;
-    compile_plan(n, VDNN_POLICY_FIT, algo, q, &set, false);
-    return q.ok;
-}
-
-// Start with nothing offloaded.  While the step does not fit: add the smallest remaining candidate whose
-// addition makes it fit; if there is none, add the largest remaining one (ties: lower id) and repeat.
-static bool fit_select(const vdnn_net& n, int algo, std::vector<char>& set) {
-    const int L = (int)n.layers.size();
-    std::vector<int> cands;
-    for (int b = -1; b < L; ++b)
-        if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL)) cands.push_back(b);
-    set.assign(L + 1, 0);
-    while (!fits_with(n, set, algo)) {
-        std::vector<int> rest;
-        for (int b : cands)
-            if (!set[b + 1]) rest.push_back(b);
-        if (rest.empty()) return false;
-        std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return n.B(a).count < n.B(b).count; });
-        bool done = false;
-        for (int b : rest) {
-            set[b + 1] = 1;
-            if (fits_with(n, set, algo)) { done = true; break; }
-            set[b + 1] = 0;
-        }
-        if (done) break;
-        int pick = rest[0];
-        for (int b : rest)
-            if (n.B(b).count > n.B(pick).count) pick = b;  // rest is ascending by (size, id): the first of the largest wins
-        set[pick + 1] = 1;
-    }
-    return true;
-}
-
-static const int kFills[] = {1000, 990, 980, 970, 960, 950, 940, 930, 920, 910, 900, 880, 860, 840, 820, 800, 750, 700, 600, 500, 0};
-
-static vdnn_status_t plan_policy(vdnn_net& n, int policy) {
-    Plan p;
-    if (policy == VDNN_POLICY_FIT) {
-        std::vector<char> set;
-        int algo = -1;
-        for (int a : {VDNN_ALGO_PERF, VDNN_ALGO_GREEDY, VDNN_ALGO_MEM})
-            if (fit_select(n, a, set)) { algo = a; break; }
-        if (algo < 0) { n.err = "fit: the step does not fit even with every CONV/POOL input offloaded and no workspace"; return VDNN_ERR_OOM_DEVICE; }
-        // The set was chosen by live bytes; when no placement of the blocks fits the budget either (the live
-        // peak then sits within a fraction of a percent of it), the largest remaining candidate is added.
-        for (;;) {
-            // the largest forward share for which the blocks can be placed (the backward windows come out of the
-            // placement and never make it fail)
-            for (int f : kFills) {
-                compile_plan(n, policy, algo, p, &set, true, f, f ? 1000 : 0);
-                if (p.ok) { n.plan = p; n.policy = policy; n.effective = policy; return VDNN_OK; }
-            }
-            int pick = -2;
-            for (int b = -1; b < (int)n.layers.size(); ++b)
-                if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL) && !set[b + 1] && (pick == -2 || n.B(b).count > n.B(pick).count)) pick = b;
-            if (pick == -2) break;
-            set[pick + 1] = 1;
-        }
-        n.err = p.fail_why;
-        return VDNN_ERR_OOM_DEVICE;
-    }
-    if (policy == VDNN_POLICY_DYN) {
-        Plan first;
-        compile_plan(n, VDNN_POLICY_ALL, VDNN_ALGO_MEM, first);
-        if (!first.ok) { n.err = "vDNN_dyn: even vDNN_all with the memory-optimal algorithm does not fit: " + first.fail_why; return VDNN_ERR_OOM_DEVICE; }
-        const int order[3] = {VDNN_POLICY_NONE, VDNN_POLICY_CONV, VDNN_POLICY_ALL};
-        for (int pol : order) {
-            compile_plan(n, pol, VDNN_ALGO_PERF, p);
-            if (p.ok) { n.plan = p; n.policy = policy; n.effective = pol; return VDNN_OK; }
-        }
-        for (int pol : {VDNN_POLICY_CONV, VDNN_POLICY_ALL}) {
-            compile_plan(n, pol, VDNN_ALGO_GREEDY, p);
-            if (p.ok) { n.plan = p; n.policy = policy; n.effective = pol; return VDNN_OK; }
-        }
-        n.plan = first; n.policy = policy; n.effective = VDNN_POLICY_ALL;
-        return VDNN_OK;
-    }
-    compile_plan(n, policy, n.static_algo, p);
-    if (!p.ok) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
-    n.plan = p; n.policy = policy; n.effective = policy;
-    return VDNN_OK;
-}
 
 // ---------------------------------------------------------------------------------------------
 // device plumbing

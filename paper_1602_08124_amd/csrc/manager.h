@@ -10,6 +10,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <algorithm>
+#include <cstdarg>
+#include <cstdio>
 #include <string>
 #include <vector>
 
@@ -162,3 +164,47 @@ struct vdnn_net {
     vdnn::Buffer& B(int id) { return bufs[id + 1]; }
     const vdnn::Buffer& B(int id) const { return bufs[id + 1]; }
 };
+
+// ---- shared by graph.cpp, planner.cpp and manager.cpp ----------------------------------------------------
+namespace vdnn {
+
+inline bool in_place(int type) { return type == VDNN_RELU; }
+inline bool needs_x_in_bwd(int type) { return type == VDNN_CONV || type == VDNN_MAXPOOL || type == VDNN_FC || type == VDNN_SOFTMAX_CE; }
+inline const char* type_name(int t) {
+    static const char* n[] = {"conv", "relu", "maxpool", "avgpool", "fc", "concat", "softmax_ce"};
+    return (t >= 0 && t <= 6) ? n[t] : "?";
+}
+
+inline std::string fmt(const char* f, ...) {
+    char b[512];
+    va_list ap;
+    va_start(ap, f);
+    vsnprintf(b, sizeof b, f, ap);
+    va_end(ap);
+    return b;
+}
+
+inline int buf_of(const vdnn_net& n, int layer) { return layer < 0 ? -1 : n.layers[layer].buf; }
+
+inline void shape_of(const vdnn_net& n, int layer, int* C, int* H, int* W) {
+    if (layer < 0) { *C = n.in_c; *H = n.in_h; *W = n.in_w; }
+    else { *C = n.layers[layer].C; *H = n.layers[layer].H; *W = n.layers[layer].W; }
+}
+
+// graph.cpp
+vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::string& err);
+bool fold_fwd(const vdnn_net& n, int conv);     // the conv applies the ReLU living in its output
+bool fold_bwd(const vdnn_net& n, int reader);   // the reader applies the backward of the ReLU living in its input
+size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false);
+bool selected(const vdnn_net& n, int b, int policy);
+size_t baseline_bytes(const vdnn_net& n);
+
+// planner.cpp
+// offload_set (indexed by buffer id + 1), when given, replaces the policy's choice of feature maps; place = false
+// stops after the byte accounting (p.ok then only says that the live total fits); fill_pm / fill_bwd_pm > 0 turn the
+// transfer windows on.
+void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set = nullptr, bool place = true,
+                  int fill_pm = 0, int fill_bwd_pm = 0);
+vdnn_status_t plan_policy(vdnn_net& n, int policy);
+
+}  // namespace vdnn
