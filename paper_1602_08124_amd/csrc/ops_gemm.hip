@@ -370,7 +370,10 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     RowMajorOut eo;
     eo.out = splits > 1 ? (float*)ws : dw;
     eo.rows = K; eo.cols = CRS; eo.ld = CRS; eo.slice = (size_t)K * CRS;
-    hipError_t e = K <= 64 ? bwdf_cfg<64, 128, 1, 4>(pa, g, eo, splits, st) : bwdf_cfg<128, 128, 2, 2>(pa, g, eo, splits, st);
+    // a first layer has few columns (C*R*S = 27 for RGB 3x3): narrow column tiles waste less of the matrix pipe
+    hipError_t e;
+    if (CRS <= 64) e = K <= 64 ? bwdf_cfg<64, 64, 2, 2>(pa, g, eo, splits, st) : bwdf_cfg<128, 64, 4, 1>(pa, g, eo, splits, st);
+    else e = K <= 64 ? bwdf_cfg<64, 128, 1, 4>(pa, g, eo, splits, st) : bwdf_cfg<128, 128, 2, 2>(pa, g, eo, splits, st);
     if (e != hipSuccess) return e;
     if (splits > 1) return launch_reduce((const float*)ws, dw, (size_t)K * CRS, splits, st);
     return hipSuccess;
