@@ -549,7 +549,7 @@ def retime(trace, budget, fill_pm, part_bytes=PART_BYTES, lent=None, twins=None)
         if t[1] == "alloc" and i + 1 < len(bwd) and bwd[i + 1][1] in ("prefetch", "ondemand") and bwd[i + 1][2] == t[2]:
             size_of[t[2]] = t[3]
             tenants = [tn for tn, (h, _) in lent.items() if h == t[2]]
-            if tenants and all(freed_at[tn] < i for tn in tenants):
+            if tenants and all(freed_at.get(tn, -1) < i for tn in tenants):   # not in freed_at: released in forward already
                 twins.add(t[2])
             for tag, size, raw in reversed(pieces(t[2], bwd[i + 1][3])):
                 out.append((t[0], "alloc", tag, size))

@@ -487,7 +487,7 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
             if (fwd_block >= 0) {
                 bool any = false, gone = true;
                 for (size_t b = 0; b < p.blocks.size(); ++b)
-                    if (p.blocks[b].host == fwd_block) { any = true; gone = gone && freed_at[b] >= 0 && freed_at[b] < t; }
+                    if (p.blocks[b].host == fwd_block) { any = true; gone = gone && freed_at[b] < t; }  // -1: released in forward already
                 if (any && gone) { p.blocks[block].host = fwd_block; p.blocks[block].host_rel = 0; }
             }
             for (int i = k - 1; i >= 0; --i) {

@@ -210,3 +210,51 @@ def shapes(net):
         else:
             raise ValueError(t)
     return out, wshape
+
+
+def random_net(seed, batch=2, in_hw=20, max_layers=10):
+    """A random small network for fuzzing the planners and the kernels on irregular graphs: chains of
+    conv / pool layers with random geometry, conv layers without a ReLU, forks whose branches are joined
+    by a concat (branches of different depth, a feature map read by several layers), FC head."""
+    import random
+    rnd = random.Random(seed)
+    b = _Builder("random%d" % seed, batch, rnd.choice((1, 3, 4)), in_hw, in_hw + rnd.choice((0, 3)))
+    h, w = b.net["in_h"], b.net["in_w"]
+    src = -1
+    n = 0
+    while n < max_layers and min(h, w) >= 4:
+        kind = rnd.random()
+        if kind < 0.45:      # conv, same-size
+            k = rnd.choice((1, 3, 3, 5))
+            src = b.conv(rnd.choice((4, 8, 16, 24)), k, pad=k // 2, relu=rnd.random() < 0.8, inputs=[src])
+        elif kind < 0.6:     # strided or unpadded conv
+            k = rnd.choice((2, 3))
+            st = rnd.choice((1, 2))
+            src = b.conv(rnd.choice((8, 16)), k, stride=st, pad=0, inputs=[src])
+            h, w = (h - k) // st + 1, (w - k) // st + 1
+        elif kind < 0.75:    # pool
+            k, st, pd = rnd.choice(((2, 2, 0), (3, 2, 1), (3, 1, 1), (3, 2, 0)))
+            if rnd.random() < 0.8:
+                src = b.maxpool(k, st, pd, inputs=[src])
+            else:
+                b.last = src
+                src = b.avgpool(k, st, pd)
+            h, w = (h + 2 * pd - k) // st + 1, (w + 2 * pd - k) // st + 1
+        else:                # fork: 2-3 branches of depth 1-2 over the same source, joined by a concat
+            outs = []
+            for _ in range(rnd.choice((2, 3))):
+                t = src
+                for _ in range(rnd.choice((1, 2))):
+                    k = rnd.choice((1, 3))
+                    t = b.conv(rnd.choice((4, 8)), k, pad=k // 2, relu=rnd.random() < 0.7, inputs=[t])
+                outs.append(t)
+            if rnd.random() < 0.5:
+                t = b.maxpool(3, 1, 1, inputs=[src])
+                outs.append(b.conv(4, 1, inputs=[t]))
+            src = b.add("concat", outs)
+        n += 1
+    b.last = src
+    if rnd.random() < 0.5:
+        b.fc(rnd.choice((8, 16)))
+    b.fc(rnd.choice((3, 5, 10)), relu=False)
+    return b.done()

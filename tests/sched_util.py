@@ -35,7 +35,7 @@ def fit_reference(n, net, budget, part=None):
     part = ms.PART_BYTES if part is None else part
     chosen, _, _ = ms.fit(net, budget or 1 << 50, 0)
     extra = len(n.offload_set()) - len(chosen)
-    assert 0 <= extra <= 3, (n.offload_set(), chosen)
+    assert extra >= 0, (n.offload_set(), chosen)
     st = n.stats()
     assert st["window_fill_pm"] in ms.FILLS_PM and st["window_fill_bwd_pm"] in (0, 1000)
     windows = bool(budget) and (st["window_fill_pm"] > 0 or st["window_fill_bwd_pm"] > 0)

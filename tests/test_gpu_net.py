@@ -358,3 +358,35 @@ def test_layer_times_add_up(B):
         assert sum(fwd) <= st["fwd_ms"] * 1.001 + 1e-3 and sum(fwd) >= 0.5 * st["fwd_ms"]
         assert sum(bwd) <= st["bwd_ms"] * 1.001 + 1e-3 and sum(bwd) >= 0.5 * st["bwd_ms"]
     n.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_graphs_on_the_device(B, seed):
+    """Fuzz on irregular graphs (uneven forks, convs without ReLU, strided and unpadded layers, odd sizes): the
+    no-offload step against the oracle, and every offloading policy (with windows cut into small pieces) bit for bit
+    against the no-offload step."""
+    net = nets.random_net(100 + seed, batch=3)
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 300 + seed)
+    got = run_gpu(B, net, x, labels, weights, "none")
+    fwd = onet.forward(net, x, labels, weights)[0]
+    for i, y in enumerate(fwd):
+        if net["layers"][i]["type"] != "softmax_ce":
+            assert rel_err(got["outs"][i].reshape(y.shape), y) < TOL, i
+    ref = onet.step(net, x, labels, weights, outs_override=got["outs"])
+    assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
+    for i in weights:
+        assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+    base = run_gpu(B, net, x, labels, weights, "none", capture=False)
+    lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
+    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+    for pol, budget in (("all", 0), ("conv", 0), ("dyn", (lo + hi) // 2), ("fit", (lo + hi) // 2), ("fit", lo + (hi - lo) // 4)):
+        n = B.Net(net, budget)
+        n.set_window_part(2048)
+        ok = n.try_policy(pol) == B.OK
+        n.close()
+        if not ok:
+            continue
+        r = run_gpu(B, net, x, labels, weights, pol, budget=budget, capture=False, part=2048)
+        assert r["loss"] == base["loss"], (pol, budget)
+        for i in weights:
+            assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
