@@ -201,7 +201,12 @@ def workspace_bytes(net, info, i, phase, memopt=False):
         # backward-filter: partial sums of the split reduction; with input channels a multiple of 64
         # the faster kernel always stages dW through the workspace (at least one copy)
         if c % 64 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
-            filt = gemm_splits(k, c * l["k"] * l["k"], n * p * q) * wbytes
+            if c == 64 and rs % 3 == 0:
+                # 64-channel layers run column tiles of three taps: the split count follows from that tile count
+                tiles = _cdiv(k, 64 if k <= 64 else 128) * (rs // 3)
+                filt = max(1, min(TARGET_BLOCKS // tiles, _cdiv(n * p * q, MIN_SPLIT_LEN))) * wbytes
+            else:
+                filt = gemm_splits(k, c * l["k"] * l["k"], n * p * q) * wbytes
         else:
             filt = _ws(k, c * l["k"] * l["k"], n * p * q)
         return max(filt, packed)

@@ -274,7 +274,7 @@ struct BwdFilterFastParams {
     int tiles_m, tiles_n, splits, ksplit;
 };
 
-template <int BM, int BN, int WM, int WN, int BK>
+template <int BM, int BN, int WM, int WN, int BK, int TAPS = 1>
 __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastParams p) {
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
@@ -295,8 +295,13 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
     const int t2 = logical - split * tiles;
     const int tile_n = t2 / p.tiles_m, tile_m = t2 - tile_n * p.tiles_m;
     const int row0 = tile_m * BM, col0 = tile_n * BN;
-    const int tap = col0 / p.C, c0 = col0 - tap * p.C;  // uniform: the tile lies inside one tap
-    const int tr = tap / p.S, ts = tap - tr * p.S;
+    // TAPS == 1: the tile lies inside one tap.  TAPS > 1 (narrow layers, C == BN / TAPS): the tile covers TAPS whole
+    // taps, CW = BN / TAPS channels each, so that a 64-channel layer still gets a wide tile.
+    constexpr int CW = BN / TAPS;
+    const int tap = col0 / p.C, c0 = col0 - tap * p.C;  // uniform
+    int tr[TAPS], ts[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) { tr[t] = (tap + t) / p.S; ts[t] = (tap + t) - tr[t] * p.S; }
     const int kbeg = split * p.ksplit;
     const int kend = min(p.M, kbeg + p.ksplit);
     const int nk = (kend - kbeg + BK - 1) / BK;
@@ -335,12 +340,16 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
         const uint32_t pq = mm - n * (uint32_t)PQ;
         const uint32_t pp = fd_div(pq, p.fd_q);
         const uint32_t qq = pq - pp * (uint32_t)p.Q;
-        const int ih = (int)pp * p.stride - p.pad + tr, iw = (int)qq * p.stride - p.pad + ts;
-        const bool okb = vm && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+        uint32_t b_voff[TAPS];
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            const int ih = (int)pp * p.stride - p.pad + tr[t], iw = (int)qq * p.stride - p.pad + ts[t];
+            const bool okb = vm && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            b_voff[t] = okb ? (n * (uint32_t)p.C * (uint32_t)HW + (uint32_t)(ih * p.W + iw) + b_chpart) * 4u : kOobOffset;
+        }
         // A: everything in the vector offset, so that rows past K (ragged last row tile) are either
         // another image's data (never stored) or out of range (0).
         const uint32_t a_base = vm ? (n * (uint32_t)p.K * (uint32_t)PQ + pq + a_rowpart) * 4u : kOobOffset;
-        const uint32_t b_voff = okb ? (n * (uint32_t)p.C * (uint32_t)HW + (uint32_t)(ih * p.W + iw) + b_chpart) * 4u : kOobOffset;
         if (full_rows) {  // no row of the tile lies past K: the row step can ride in the scalar offset
 #pragma unroll
             for (int j = 0; j < EA; ++j) ra[j] = buf_load(rs_dy, a_base, (uint32_t)(j * RSTEP) * (uint32_t)(PQ * 4));
@@ -352,7 +361,10 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
             }
         }
 #pragma unroll
-        for (int j = 0; j < EB; ++j) rb[j] = buf_load(rs_x, b_voff, (uint32_t)(j * RSTEP) * (uint32_t)(HW * 4));
+        for (int j = 0; j < EB; ++j) {  // column r_first + j * RSTEP: tap (j * RSTEP) / CW, channel r_first + (j * RSTEP) % CW
+            static_assert(TAPS == 1 || CW % RSTEP == 0, "a thread's columns must not straddle taps");
+            rb[j] = buf_load(rs_x, b_voff[TAPS == 1 ? 0 : (j * RSTEP) / CW], (uint32_t)(TAPS == 1 ? j * RSTEP : (j * RSTEP) % CW) * (uint32_t)(HW * 4));
+        }
     };
     auto store_step = [&](int buf) {
 #pragma unroll

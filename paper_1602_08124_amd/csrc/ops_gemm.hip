@@ -299,16 +299,28 @@ static bool bwdf_fast_ok(int N, int C, int H, int W, int K, int P, int Q) {
     return C % 64 == 0 && (long long)N * C * H * W * 4 < 0xfffffff0LL && (long long)N * K * P * Q * 4 < 0xfffffff0LL;
 }
 
+// 64-channel layers run column tiles of three taps (192 columns); their split count follows from that tile count.
+static bool bwdf_three_taps(int C, int R, int S) { return C == 64 && (R * S) % 3 == 0; }
+
+static int bwdf_splits(int N, int C, int H, int W, int K, int R, int S, int P, int Q) {
+    const long long M = (long long)N * P * Q;
+    if (bwdf_fast_ok(N, C, H, W, K, P, Q) && bwdf_three_taps(C, R, S)) {
+        const long long tiles = (long long)cdiv(K, K <= 64 ? 64 : 128) * (R * S / 3);
+        return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv(M, 2048)));
+    }
+    return gemm_splits(K, (long long)C * R * S, M);
+}
+
 size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (bwdf_fast_ok(N, C, H, W, K, P, Q))
-        return (size_t)gemm_splits(K, (long long)C * R * S, (long long)N * P * Q) * K * C * R * S * sizeof(float);
+        return (size_t)bwdf_splits(N, C, H, W, K, R, S, P, Q) * K * C * R * S * sizeof(float);
     return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
 }
 
-template <int BM, int BN, int WM, int WN, int BK = 32>
+template <int BM, int BN, int WM, int WN, int BK = 32, int TAPS = 1>
 static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
-    auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN, BK>;
+    auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN, BK, TAPS>;
     constexpr int PAD = BK >= 32 ? 1 : 32 / BK;  // as in the kernel
     constexpr size_t smem = sizeof(float) * 2 * BK * ((BM + PAD) + (BN + PAD));
     static bool attr_set = false;
@@ -339,7 +351,7 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     const int CRS = C * R * S;
-    int splits = gemm_splits(K, CRS, (long long)N * P * Q);
+    int splits = bwdf_splits(N, C, H, W, K, R, S, P, Q);
     const size_t need_ws = conv_bwd_filter_workspace(N, C, H, W, K, R, S, stride, pad);
     const bool have_ws = ws && ws_bytes >= need_ws;
     if (!have_ws) splits = 1;  // memory-optimal algorithm: no workspace, the whole reduction in one workgroup per tile
@@ -357,6 +369,8 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
         // K-step 16 (33 KB of LDS, 4 workgroups per CU) for the 128-row tiles, 32 for the 64-row ones: measured
         // 127 against 121 TFLOP/s on VGG-16's 128..512-channel layers, 105 against 94 on the 64-channel one
         if (C % 128 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 128, 1, 4, 32>(fp, st) : bwdf_fast_cfg<128, 128, 2, 2, 16>(fp, st);
+        else if (bwdf_three_taps(C, R, S))  // 64-channel layers: tiles of three taps (192 columns) instead of one
+            e = K <= 64 ? bwdf_fast_cfg<64, 192, 2, 2, 16, 3>(fp, st) : bwdf_fast_cfg<128, 192, 2, 2, 16, 3>(fp, st);
         else e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2, 32>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1, 16>(fp, st);
         if (e != hipSuccess) return e;
         const size_t total = (size_t)K * CRS;

@@ -202,3 +202,28 @@ def test_very_deep_vgg_batch_32(B, extra, check_identity):
         assert loss == base_loss
         for i in weights:
             assert np.array_equal(dw[i], base_dw[i]), i
+
+
+def test_vgg16_b256_step_against_the_oracle_at_full_size(B):
+    """End-to-end parity of the benchmark configuration itself: loss and sampled weight-gradient entries of one
+    VGG-16 batch-256 step against tests/golden/vgg16_b256_step.json, which tests/golden/make_vgg16_b256_golden.py wrote
+    from the fp64 CPU oracle alone (the batch in chunks: losses average, weight gradients add).  Error measure as
+    everywhere: largest deviation over the samples relative to the largest element of the oracle's tensor."""
+    import json
+    import os
+    import torch
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "vgg16_b256_step.json")
+    gold = json.load(open(path))
+    net = nets.vgg16(256)
+    x, labels, weights = gen.make(net)
+    xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
+    loss, dw, st, _ = _run(B, net, xd, ld, weights, "none", 0)
+    assert abs(loss - gold["loss"]) < TOL * abs(gold["loss"])
+    assert sorted(int(i) for i in gold["layers"]) == sorted(weights)
+    for i, g in gold["layers"].items():
+        mine = dw[int(i)].reshape(-1).astype(np.float64)
+        assert list(dw[int(i)].shape) == g["shape"]
+        err = np.abs(mine[np.array(g["index"])] - np.array(g["value"])).max() / g["max_abs"]
+        assert err < TOL, (i, err)
+        assert abs(np.abs(mine).max() - g["max_abs"]) < 10 * TOL * g["max_abs"], i
+        assert abs(np.sqrt((mine * mine).sum()) - g["l2"]) < 10 * TOL * g["l2"], i
