@@ -88,12 +88,12 @@ typedef struct {
     uint64_t offloaded_bytes, prefetched_bytes; /* per step, device->host and host->device */
     uint64_t pinned_host_bytes;
     uint64_t workspace_bytes;     /* largest transient workspace of the step */
-    int32_t n_offload, n_prefetch, n_ondemand_fetch;
+    int32_t n_offload, n_prefetch, n_ondemand_fetch; /* copies per step (a block that moves in pieces: one per piece) */
     int32_t effective_policy;     /* what DYN resolved to; otherwise the policy set */
     int32_t conv_algo;            /* vdnn_conv_algo_t of the current plan */
     int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
     int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the forward transfer windows fill; 0 = static schedule */
-    int32_t window_fill_bwd_pm;   /* the same for backward propagation */
+    int32_t window_fill_bwd_pm;   /* > 0: backward fetches are issued early, while live bytes stay within that share */
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
