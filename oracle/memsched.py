@@ -48,9 +48,8 @@ def gemm_splits(m, n, kred):
 
 
 def conv_slots(rows):
-    """Resident workgroups of the packed-weight convolution kernel on 256 CUs: 4 per CU for the
-    128 x 128 tile (more than 64 output rows), 3 per CU for the 256-pixel tiles."""
-    return 768 if rows <= 64 else 1024
+    """Resident workgroups of the packed-weight convolution kernel on 256 CUs: 4 per CU for every tile shape."""
+    return 1024
 
 
 def conv_packed_workspace(wcount, rows, m, cred, rs):

@@ -65,12 +65,17 @@ __global__ void pack_weights_kernel(const float* __restrict__ w, float* __restri
 // 4 waves per SIMD (4 workgroups per CU: 128 registers per lane, 40 KB of LDS each for the 128x128 tile)
 // keep the matrix pipe busier than the 3 the register allocator would settle for: 136-138 against 132-134 TFLOP/s
 // (the same attribute on the backward-filter kernel measured no gain).
+// Row pitch padding of the LDS tiles.  Lanes store consecutive rows and read 32 consecutive words, so no pitch
+// conflicts; the 256-pixel tiles go without padding, which makes four of them (40 KB each) fit one CU's LDS.
+template <int BN>
+constexpr int kConvFastPad = BN >= 256 ? 0 : 32;
+
 template <int BM, int BN, int WM, int WN, bool SPLIT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_fast_kernel(ConvFastParams p) {
     constexpr int BK = 16;
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "wave tiling");
-    constexpr int PADA = 32, PADB = 32;
+    constexpr int PADA = kConvFastPad<BN>, PADB = kConvFastPad<BN>;
     constexpr int LDA = BM + PADA, LDB = BN + PADB;
     constexpr int EA = BM * BK / kThreads, EB = BN * BK / kThreads;
     constexpr int KSA = kThreads / BM > 0 ? kThreads / BM : 1;  // k distance between a thread's A elements

@@ -108,7 +108,7 @@ static bool fast_ok(long long src_elems, long long w_elems, int cred, int R, int
 // 128 registers per lane), 3 per CU for the 256-pixel tiles (45-48 KB of LDS).  Workgroups are dispatched in
 // rounds of this many; when the last round would be mostly empty, or when there are fewer tiles than this
 // altogether, the reduction of those tiles is split across the idle workgroups.
-static int conv_slots(int rows) { return rows <= 64 ? 768 : 1024; }
+static int conv_slots(int /*rows*/) { return 1024; }  // 4 workgroups per CU for every tile shape (registers: 4 waves per SIMD; LDS: <= 40 KB each)
 
 struct TailSplit {
     int full_tiles, tail_tiles, splits, steps_per_split;
@@ -143,7 +143,7 @@ template <int BM, int BN, int WM, int WN>
 static hipError_t conv_fast_cfg(ConvFastParams& p, const TailSplit& ts, float* partial, hipStream_t st) {
     auto kern = conv_fast_kernel<BM, BN, WM, WN, false>;
     auto kern_split = conv_fast_kernel<BM, BN, WM, WN, true>;
-    constexpr size_t smem = sizeof(float) * 2 * 16 * ((BM + 32) + (BN + 32));
+    constexpr size_t smem = sizeof(float) * 2 * 16 * ((BM + kConvFastPad<BN>) + (BN + kConvFastPad<BN>));
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
