@@ -238,3 +238,24 @@ def test_vgg16_b256_step_against_the_oracle_at_full_size(B):
         else:
             assert d.max() < 3e-3 and np.sqrt((d * d).mean()) < 1e-3, (i, d.max())
         assert abs(np.sqrt((mine * mine).sum()) - g["l2"]) < 1e-3 * g["l2"], i
+
+
+def test_vgg16_full_resolution_decisions_shared_with_the_oracle(B):
+    """The counterpart of the test above: VGG-16 at full resolution and depth with a batch small enough for an oracle
+    backward pass (2 images), the oracle deciding ReLU signs and pooling arg-max from the GPU's forward values.  With the
+    decisions shared every weight gradient meets 1e-4, the convolution layers included: what separates the two sides
+    at full size is the decisions, not the arithmetic of the kernels."""
+    import torch
+    from oracle import net as onet
+    from tests.gpu_util import rel_err
+    net = nets.vgg16(2)
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 77)
+    hooks = tuple(range(len(net["layers"])))
+    loss, dw, st, caps = _run(B, net, torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda(), weights, "none", 0, hooks)
+    ref = onet.step(net, x, labels, weights, outs_override=caps)
+    assert abs(loss - ref["loss"]) < TOL * abs(ref["loss"])
+    for i, y in enumerate(ref["outs"]):
+        if net["layers"][i]["type"] != "softmax_ce":
+            assert rel_err(caps[i].reshape(y.shape), y) < TOL, i
+    for i in weights:
+        assert rel_err(dw[i], ref["dw"][i]) < TOL, i
