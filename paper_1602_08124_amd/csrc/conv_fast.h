@@ -237,10 +237,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 
 // Finishes the tiles whose reduction was split: adds the partial sums of a tile in split order (fixed:
 // results do not depend on scheduling) and stores through the same epilogue as the unsplit kernel.
-// One workgroup per tile; lanes walk along pixels.
+// kFixupChunks workgroups per tile, each a band of rows; lanes walk along pixels.
+constexpr int kFixupChunks = 8;
+
 template <int BM, int BN>
 __global__ __launch_bounds__(kThreads) void conv_split_fixup_kernel(ConvFastParams p) {
-    const int tile_local = blockIdx.x;
+    static_assert(BM % kFixupChunks == 0, "row bands");
+    const int tile_local = blockIdx.x / kFixupChunks, chunk = blockIdx.x - tile_local * kFixupChunks;
     const int tile = p.tile_begin + tile_local;
     const int tile_n = tile / p.tiles_m, tile_m = tile - tile_n * p.tiles_m;
     const int row0 = tile_m * BM, col0 = tile_n * BN;
@@ -248,8 +251,10 @@ __global__ __launch_bounds__(kThreads) void conv_split_fixup_kernel(ConvFastPara
     float* obase = p.out.base(0);
     const int col = threadIdx.x % BN;
     const ConvOut::Col c = p.out.col(col0 + col);
-    for (int row = threadIdx.x / BN; row < BM; row += kThreads / BN) {
+    const int r_end = (chunk + 1) * (BM / kFixupChunks);
+    for (int row = chunk * (BM / kFixupChunks) + threadIdx.x / BN; row < r_end; row += kThreads / BN) {
         float acc = pb[row * BN + col];
+#pragma unroll 4
         for (int s = 1; s < p.splits; ++s) acc += pb[(size_t)s * (BM * BN) + row * BN + col];
         p.out.put(obase, row0 + row, c, acc);
     }

@@ -168,7 +168,7 @@ static hipError_t conv_fast_cfg(ConvFastParams& p, const TailSplit& ts, float* p
         VDNN_LAUNCH(kern_split, dim3((unsigned)(ts.tail_tiles * ts.splits)), dim3(kThreads), smem, st, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH((conv_split_fixup_kernel<BM, BN>), dim3((unsigned)ts.tail_tiles), dim3(kThreads), 0, st, p);
+        VDNN_LAUNCH((conv_split_fixup_kernel<BM, BN>), dim3((unsigned)ts.tail_tiles * kFixupChunks), dim3(kThreads), 0, st, p);
         return hipGetLastError();
     }
     return hipSuccess;
