@@ -125,43 +125,48 @@ __global__ void maxpool_bwd_kernel(const float* __restrict__ x, const float* __r
     }
 }
 
-// 3x3 windows (stride 1 or 2, any padding below 3): same rule, but the 5x5 neighbourhood that all windows
-// containing the element lie in is loaded into registers once (cells outside the image read as -inf, which
-// never wins), and the candidate windows are evaluated from registers with compile-time indices.
+// 3x3 windows (stride 1 or 2, any padding below 3): same rule, one thread per 2x2 block of dX.  For stride 2 the
+// block is aligned so that its first row and column start a window; then 2x2 windows (4x4 for stride 1) cover
+// it, and they all lie in a 5x5 (6x6) neighbourhood of X that the thread loads into registers once (cells
+// outside the image read as -inf, which never wins).  Every window's arg-max is found once and credited to the
+// block element it falls on: 25 loads and 4 arg-max searches per four outputs instead of per output.
 template <int STRIDE>
 __global__ void maxpool3_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, int H, int W,
-                                    int P, int Q, int pad, uint32_t total, FD fw, FD fh, int relu_mask) {
+                                    int P, int Q, int pad, uint32_t total, FD fbw, FD fbh, int nbh, int nbw, int relu_mask) {
+    constexpr int NWIN = 4 / STRIDE;            // window starts per axis that can touch the block
+    constexpr int NB = (NWIN - 1) * STRIDE + 3;  // neighbourhood edge: 5 (stride 2) or 6 (stride 1)
+    const int shift = STRIDE == 2 ? (pad & 1) : 0;  // block origin = 2 * index - shift: (origin + pad) is a multiple of the stride
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-        const uint32_t t = fdiv(i, fw);
-        const int w = (int)(i - t * W);
-        const uint32_t nc = fdiv(t, fh);
-        const int h = (int)(t - nc * H);
+        const uint32_t t = fdiv(i, fbw);
+        const int w0 = 2 * (int)(i - t * (uint32_t)nbw) - shift;
+        const uint32_t nc = fdiv(t, fbh);
+        const int h0 = 2 * (int)(t - nc * (uint32_t)nbh) - shift;
         const float* xp = x + (size_t)nc * H * W;
         const float* gp = dy + (size_t)nc * P * Q;
-        float nb[5][5];
+        float nb[NB][NB];  // rows h0 - 2 .., columns w0 - 2 ..
 #pragma unroll
-        for (int a = 0; a < 5; ++a) {
-            const int hh = h + a - 2;
+        for (int a = 0; a < NB; ++a) {
+            const int hh = h0 - 2 + a;
             const bool okh = (unsigned)hh < (unsigned)H;
             const int hc = min(max(hh, 0), H - 1);
 #pragma unroll
-            for (int b = 0; b < 5; ++b) {
-                const int ww = w + b - 2;
+            for (int b = 0; b < NB; ++b) {
+                const int ww = w0 - 2 + b;
                 const bool ok = okh && (unsigned)ww < (unsigned)W;
                 const float v = xp[hc * W + min(max(ww, 0), W - 1)];
                 nb[a][b] = ok ? v : -INFINITY;
             }
         }
-        float acc = 0.f;
-        // window starts (h0, w0) = (h - 2 + a, w - 2 + b), a, b in 0..2, ascending = ascending (p, q)
+        float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+        // window starts (h0 - 2 + a * STRIDE, w0 - 2 + b * STRIDE), ascending = ascending (p, q)
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
-            const int hn = h - 2 + a + pad;  // = p * STRIDE
+        for (int a = 0; a < NWIN; ++a) {
+            const int hn = h0 - 2 + a * STRIDE + pad;  // = p * STRIDE
             const int p = hn / STRIDE;
             const bool okp = hn >= 0 && (hn % STRIDE) == 0 && p < P;
 #pragma unroll
-            for (int b = 0; b < 3; ++b) {
-                const int wn = w - 2 + b + pad;
+            for (int b = 0; b < NWIN; ++b) {
+                const int wn = w0 - 2 + b * STRIDE + pad;
                 const int q = wn / STRIDE;
                 const bool okq = wn >= 0 && (wn % STRIDE) == 0 && q < Q;
                 float best = -INFINITY;
@@ -170,14 +175,30 @@ __global__ void maxpool3_bwd_kernel(const float* __restrict__ x, const float* __
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
                     for (int s2 = 0; s2 < 3; ++s2) {
-                        const float v = nb[a + r][b + s2];
-                        if (v > best) { best = v; br = a + r; bs = b + s2; }
+                        const float v = nb[a * STRIDE + r][b * STRIDE + s2];
+                        if (v > best) { best = v; br = a * STRIDE + r; bs = b * STRIDE + s2; }
                     }
-                if (okp && okq && br == 2 && bs == 2) acc += gp[p * Q + q];
+                if (okp && okq && (unsigned)(br - 2) < 2u && (unsigned)(bs - 2) < 2u) {
+                    const float g = gp[p * Q + q];
+#pragma unroll
+                    for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < 2; ++dw)
+                            if (br == 2 + dh && bs == 2 + dw) acc[dh][dw] += g;
+                }
             }
         }
-        if (relu_mask && !(nb[2][2] > 0.f)) acc = 0.f;
-        dx[i] = acc;
+#pragma unroll
+        for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+            for (int dw = 0; dw < 2; ++dw) {
+                const int h = h0 + dh, w = w0 + dw;
+                if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+                    float v = acc[dh][dw];
+                    if (relu_mask && !(nb[2 + dh][2 + dw] > 0.f)) v = 0.f;
+                    dx[(size_t)nc * H * W + (size_t)h * W + w] = v;
+                }
+            }
     }
 }
 
@@ -299,12 +320,15 @@ hipError_t maxpool_bwd(const float* x, const float* dy, float* dx, int N, int C,
         return hipGetLastError();
     }
     if (k == 3 && (stride == 1 || stride == 2)) {
+        const int shift = stride == 2 ? (pad & 1) : 0;
+        const int nbh = (H - 1 + shift) / 2 + 1, nbw = (W - 1 + shift) / 2 + 1;  // 2x2 blocks of dX per plane
+        const size_t blocks = (size_t)N * C * nbh * nbw;
         if (stride == 1)
-            VDNN_LAUNCH(maxpool3_bwd_kernel<1>, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)total,
-                        make_fd(W), make_fd(H), relu_mask);
+            VDNN_LAUNCH(maxpool3_bwd_kernel<1>, dim3(grid_for(blocks, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)blocks,
+                        make_fd(nbw), make_fd(nbh), nbh, nbw, relu_mask);
         else
-            VDNN_LAUNCH(maxpool3_bwd_kernel<2>, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)total,
-                        make_fd(W), make_fd(H), relu_mask);
+            VDNN_LAUNCH(maxpool3_bwd_kernel<2>, dim3(grid_for(blocks, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, pad, (uint32_t)blocks,
+                        make_fd(nbw), make_fd(nbh), nbh, nbw, relu_mask);
         return hipGetLastError();
     }
     VDNN_LAUNCH(maxpool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, dy, dx, H, W, P, Q, k, stride, pad,

@@ -194,7 +194,8 @@ def test_relu(B, count):
 
 
 POOLS = [(2, 3, 8, 8, 2, 2, 0), (3, 5, 12, 20, 2, 2, 0), (2, 2, 6, 10, 2, 2, 0), (1, 2, 7, 8, 2, 2, 0), (2, 5, 13, 13, 3, 2, 0), (3, 4, 14, 14, 3, 2, 1), (2, 6, 7, 9, 3, 1, 1), (1, 2, 7, 7, 7, 1, 0),
-         (2, 3, 55, 55, 3, 2, 0), (1, 3, 6, 6, 2, 2, 0)]
+         (2, 3, 55, 55, 3, 2, 0), (1, 3, 6, 6, 2, 2, 0), (2, 3, 9, 11, 3, 2, 2), (1, 2, 5, 5, 3, 1, 0), (2, 2, 3, 3, 3, 1, 1), (1, 1, 4, 7, 3, 2, 1),
+         (2, 3, 28, 28, 3, 1, 1), (2, 3, 112, 112, 3, 2, 1), (1, 2, 3, 4, 3, 1, 2), (1, 2, 6, 5, 3, 2, 0), (3, 2, 27, 27, 3, 2, 0)]
 
 
 @pytest.mark.parametrize("cfg", POOLS)
@@ -214,6 +215,10 @@ def test_maxpool(B, cfg):
     dx.fill_(float("nan"))
     B.op_maxpool_bwd(dev(x), dev(dy), dx, k, st, pd, relu_mask=True)
     assert rel_err(host(dx), L.relu_bwd(x, L.maxpool_bwd(x, dy, k, st, pd))) < 1e-6
+    # ties everywhere (few distinct values, many zeros as after a ReLU): the first maximum of a window wins
+    xt = np.maximum(np.round(x * 2.0), 0.0).astype(np.float32)
+    B.op_maxpool_bwd(dev(xt), dev(dy), dx, k, st, pd)
+    assert rel_err(host(dx), L.maxpool_bwd(xt, dy, k, st, pd)) < 1e-6
 
 
 @pytest.mark.parametrize("cfg", POOLS)
