@@ -197,9 +197,9 @@ def workspace_bytes(net, info, i, phase, memopt=False):
         packed = 0
         if need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0 and 4 * n * k * p * q < 0xfffffff0:
             packed = conv_packed_workspace(wbytes // 4, c, n * h * w, k, rs)
-        # backward-filter: partial sums of the split reduction; with input channels a multiple of 64
+        # backward-filter: partial sums of the split reduction; with input channels a multiple of 32
         # the faster kernel always stages dW through the workspace (at least one copy)
-        if c % 64 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
+        if c % 32 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
             if c == 64 and rs % 3 == 0:
                 # 64-channel layers run column tiles of three taps: the split count follows from that tile count
                 tiles = _cdiv(k, 64 if k <= 64 else 128) * (rs // 3)

@@ -292,11 +292,11 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
 // -------------------------------------------------------------------------------------------
 // convolution backward-filter
 // -------------------------------------------------------------------------------------------
-// Fast path: input channels a multiple of 64 (a column tile of 64 or 128 never straddles two filter
-// taps), both tensors below 4 GiB.  It always goes through the workspace (the column order there is
+// Fast path: input channels a multiple of 32 (a column tile of 32, 64, 96 or 128 columns that divides C never
+// straddles two filter taps), both tensors below 4 GiB.  It always goes through the workspace (the column order there is
 // tap-major and the final pass permutes it back), so the workspace is max(splits, 1) copies of dW.
 static bool bwdf_fast_ok(int N, int C, int H, int W, int K, int P, int Q) {
-    return C % 64 == 0 && (long long)N * C * H * W * 4 < 0xfffffff0LL && (long long)N * K * P * Q * 4 < 0xfffffff0LL;
+    return C % 32 == 0 && (long long)N * C * H * W * 4 < 0xfffffff0LL && (long long)N * K * P * Q * 4 < 0xfffffff0LL;
 }
 
 // 64-channel layers run column tiles of three taps (192 columns); their split count follows from that tile count.
@@ -368,10 +368,13 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
         hipError_t e;
         // K-step 16 (33 KB of LDS, 4 workgroups per CU) for the 128-row tiles, 32 for the 64-row ones: measured
         // 127 against 121 TFLOP/s on VGG-16's 128..512-channel layers, 105 against 94 on the 64-channel one
+        // column tiles lie inside one tap, so their width divides C: 128, else 96 or 64, else 32
         if (C % 128 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 128, 1, 4, 32>(fp, st) : bwdf_fast_cfg<128, 128, 2, 2, 16>(fp, st);
         else if (bwdf_three_taps(C, R, S))  // 64-channel layers: tiles of three taps (192 columns) instead of one
             e = K <= 64 ? bwdf_fast_cfg<64, 192, 2, 2, 16, 3>(fp, st) : bwdf_fast_cfg<128, 192, 2, 2, 16, 3>(fp, st);
-        else e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2, 32>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1, 16>(fp, st);
+        else if (C % 96 == 0) e = bwdf_fast_cfg<128, 96, 4, 1, 16>(fp, st);
+        else if (C % 64 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2, 32>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1, 16>(fp, st);
+        else e = bwdf_fast_cfg<128, 32, 4, 1, 16>(fp, st);
         if (e != hipSuccess) return e;
         const size_t total = (size_t)K * CRS;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
