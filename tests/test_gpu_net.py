@@ -231,10 +231,11 @@ def test_two_steps_in_a_row_and_policy_switch(B):
     n.close()
 
 
-@pytest.mark.parametrize("policy", ["none", "all"])
+@pytest.mark.parametrize("policy", ["none", "all", "fit"])
 def test_training_iterations_follow_the_oracle(B, policy):
     """Five SGD iterations (forward, backward, update) on the Tiny net: the loss trajectory and the final weights
-    follow the fp64 oracle, and the loss goes down."""
+    follow the fp64 oracle, and the loss goes down.  (fit: under a budget that forces it to offload, with the
+    transfer windows cut into small pieces.)"""
     net = nets.tiny(8)
     x, labels, weights = gen.make(net)
     lr = 0.05
@@ -244,8 +245,10 @@ def test_training_iterations_follow_the_oracle(B, policy):
         r = onet.step(net, x, labels, ow)
         ref_losses.append(r["loss"])
         ow = onet.sgd_update(ow, r["dw"], lr)
-    n = B.Net(net, 4 << 20)
+    n = B.Net(net, 1850000 if policy == "fit" else 4 << 20)
+    n.set_window_part(16384)
     n.set_policy(policy)
+    assert policy != "fit" or n.stats()["offloaded_bytes"] > 0
     n.attach_torch()
     for i, w in weights.items():
         n.set_weights(i, w)
