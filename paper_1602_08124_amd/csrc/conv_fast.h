@@ -24,6 +24,11 @@ __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t vof
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
 }
 
+// 16 bytes; the address needs dword alignment only
+__device__ __forceinline__ float4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+}
+
 constexpr uint32_t kOobOffset = 0xfffffff0u;  // >= num_records of any buffer: the load returns 0
 
 struct ConvFastParams {
@@ -70,7 +75,10 @@ __global__ void pack_weights_kernel(const float* __restrict__ w, float* __restri
 template <int BN>
 constexpr int kConvFastPad = BN >= 256 ? 0 : 32;
 
-template <int BM, int BN, int WM, int WN, bool SPLIT>
+// QUAD = true (host-checked: rows a multiple of 4, 64+ rows per tile): a thread fetches four neighbouring weight rows
+// with one 16-byte load and puts them to LDS with one 16-byte store (measured +0.5..1 %).  The same for four pixels of
+// the gathered operand measured 4-5 % slower: two taps of three shift the pixels off 16-byte alignment.
+template <int BM, int BN, int WM, int WN, bool SPLIT, bool QUAD = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_fast_kernel(ConvFastParams p) {
     constexpr int BK = 16;
     constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
@@ -81,7 +89,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     constexpr int KSA = kThreads / BM > 0 ? kThreads / BM : 1;  // k distance between a thread's A elements
     constexpr int KSB = kThreads / BN > 0 ? kThreads / BN : 1;
     static_assert(EA >= 1 && EB >= 1, "tile too small");
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* As = smem;
     float* Bs = smem + 2 * BK * LDA;
 
@@ -120,10 +128,30 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int l32 = lane & 31, khalf = lane >> 5;
-    const int a_off = khalf * LDA + wm * (TM * 32) + l32;
-    const int b_off = khalf * LDB + wn * (TN * 32) + l32;
+    // A wave that owns two 32-wide MFMA blocks along a tile dimension interleaves them: block i takes the tile
+    // positions 2*l + i of the wave's 64.  The two values a lane feeds to the two blocks then sit next to each
+    // other in LDS, one 8-byte read with an immediate offset fetches both (no address arithmetic in the K loop),
+    // and in the epilogue a lane holds two neighbouring pixels of each row.
+    constexpr bool PAIR_M = TM == 2, PAIR_N = TN == 2;
+    const int a_off = khalf * LDA + wm * (TM * 32) + (PAIR_M ? 2 * l32 : l32);
+    const int b_off = khalf * LDB + wn * (TN * 32) + (PAIR_N ? 2 * l32 : l32);
+    // tile row of element v of MFMA block i, tile column of this lane in MFMA block j
+    auto tile_row = [&](int i, int v) {
+        const int rr = 4 * khalf + 8 * (v / 4) + (v % 4);
+        return wm * (TM * 32) + (PAIR_M ? 2 * rr + i : i * 32 + rr);
+    };
+    auto tile_col = [&](int j) { return wn * (TN * 32) + (PAIR_N ? 2 * l32 + j : j * 32 + l32); };
     float* a_st = As + a_k0 * LDA + a_row;
     float* b_st = Bs + b_k0 * LDB + b_row;
+
+    // ---- QUAD: thread owns weight rows 4*aq .. 4*aq+3 and k = ak0 + j * KPA ----
+    constexpr int QA = BM / 4;                 // quads per k row
+    constexpr int KPA = kThreads / QA;         // k rows covered by one pass of the workgroup
+    constexpr int NA = BK / KPA > 0 ? BK / KPA : 1;  // passes
+    static_assert(!QUAD || (KPA <= BK && LDA % 4 == 0), "quad loads need 64+ rows per tile");
+    const int aq = tid % QA, ak0 = tid / QA;
+    const uint32_t a_voff4 = (row0 + 4 * aq < p.rows) ? (uint32_t)((ak0 * p.rows + row0 + 4 * aq) * 4) : kOobOffset;
+    float4* a_st4 = reinterpret_cast<float4*>(As + ak0 * LDA + 4 * aq);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -144,13 +172,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     float ra[EA], rb[EB];
 
     auto load_step = [&](int step) {
-        const int ih = ih0 + r, iw = iw0 + s;
+        // tap and channel block are the same for the whole workgroup: what derives from them stays in scalar registers
+        const int rr = __builtin_amdgcn_readfirstlane(r), ss = __builtin_amdgcn_readfirstlane(s);
+        const uint32_t a_s = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)step * (uint32_t)(16 * p.rows * 4)));
+        const uint32_t b_s = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)cb * (uint32_t)(16 * HW * 4)));
+        if constexpr (QUAD) {
+#pragma unroll
+            for (int j = 0; j < NA; ++j) {
+                const float4 v = buf_load4(rs_w, a_voff4, a_s + (uint32_t)(j * KPA) * (uint32_t)(p.rows * 4));
+                ra[4 * j] = v.x, ra[4 * j + 1] = v.y, ra[4 * j + 2] = v.z, ra[4 * j + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EA; ++j) ra[j] = buf_load(rs_w, a_voff, a_s + (uint32_t)(j * KSA) * (uint32_t)(p.rows * 4));
+        }
+        const int ih = ih0 + rr, iw = iw0 + ss;
         const bool ok = vm && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
         const uint32_t b_voff = ok ? (uint32_t)(pix_base + ih * p.W + iw) * 4u : kOobOffset;
-        const uint32_t a_s = (uint32_t)step * (uint32_t)(16 * p.rows * 4);
-        const uint32_t b_s = (uint32_t)cb * (uint32_t)(16 * HW * 4);
-#pragma unroll
-        for (int j = 0; j < EA; ++j) ra[j] = buf_load(rs_w, a_voff, a_s + (uint32_t)(j * KSA) * (uint32_t)(p.rows * 4));
 #pragma unroll
         for (int j = 0; j < EB; ++j) rb[j] = buf_load(rs_src, b_voff, b_s + (uint32_t)(j * KSB) * (uint32_t)(HW * 4));
         // advance (cb, r, s): taps fastest, then channel block
@@ -163,8 +201,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
         }
     };
     auto store_step = [&](int buf) {
+        if constexpr (QUAD) {
 #pragma unroll
-        for (int j = 0; j < EA; ++j) a_st[buf * BK * LDA + j * KSA * LDA] = ra[j];
+            for (int j = 0; j < NA; ++j)
+                a_st4[(buf * BK * LDA + j * KPA * LDA) / 4] = make_float4(ra[4 * j], ra[4 * j + 1], ra[4 * j + 2], ra[4 * j + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < EA; ++j) a_st[buf * BK * LDA + j * KSA * LDA] = ra[j];
+        }
 #pragma unroll
         for (int j = 0; j < EB; ++j) b_st[buf * BK * LDB + j * KSB * LDB] = rb[j];
     };
@@ -182,18 +226,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
         const float* bt = Bs + cur * BK * LDB + b_off;
         // operand fragments are read from LDS one k-pair ahead of the MFMAs that consume them
         float a[2][TM], b[2][TN];
+        auto fetch_a = [&](float (&dst)[TM], const float* src) {
+            if constexpr (PAIR_M) {
+                const float2 v = *reinterpret_cast<const float2*>(src);
+                dst[0] = v.x, dst[1] = v.y;
+            } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = at[i * 32];
+                for (int i = 0; i < TM; ++i) dst[i] = src[i * 32];
+            }
+        };
+        auto fetch_b = [&](float (&dst)[TN], const float* src) {
+            if constexpr (PAIR_N) {
+                const float2 v = *reinterpret_cast<const float2*>(src);
+                dst[0] = v.x, dst[1] = v.y;
+            } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = bt[j * 32];
+                for (int j = 0; j < TN; ++j) dst[j] = src[j * 32];
+            }
+        };
+        fetch_a(a[0], at);
+        fetch_b(b[0], bt);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             const int c = (kk >> 1) & 1, nx = c ^ 1;
             if (kk + 2 < BK) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[nx][i] = at[(kk + 2) * LDA + i * 32];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[nx][j] = bt[(kk + 2) * LDB + j * 32];
+                fetch_a(a[nx], at + (kk + 2) * LDA);
+                fetch_b(b[nx], bt + (kk + 2) * LDB);
             }
             __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of the MFMAs below
 #pragma unroll
@@ -202,35 +260,48 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+            // the next step's tile goes to LDS half-way through this one: its write latency hides behind the
+            // remaining MFMAs instead of standing between the last MFMA and the barrier
+            if (kk == BK / 2 && more) {
+                store_step(cur ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (more) store_step(cur ^ 1);
         __syncthreads();
     }
 
     if constexpr (SPLIT) {  // raw partial sums, tile-local [BM][BN]; conv_split_fixup_kernel finishes the tile
         float* pb = p.partial + (size_t)(tile_local * p.splits + split) * (BM * BN);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = wn * (TN * 32) + j * 32 + l32;
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int rbase = wm * (TM * 32) + i * 32 + 4 * khalf;
+            for (int v = 0; v < 16; ++v) {
+                float* prow = pb + tile_row(i, v) * BN;
+                if constexpr (PAIR_N) {
+                    *reinterpret_cast<float2*>(prow + tile_col(0)) = make_float2(acc[i][0][v], acc[i][1][v]);
+                } else {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) pb[(rbase + 8 * (v / 4) + (v % 4)) * BN + col] = acc[i][j][v];
+                    for (int j = 0; j < TN; ++j) prow[tile_col(j)] = acc[i][j][v];
+                }
             }
-        }
         return;
     }
     if constexpr (SPLIT) return;
     float* obase = p.out.base(0);
+    if constexpr (PAIR_N) {
+        const ConvOut::Col c0 = p.out.col(col0 + tile_col(0)), c1 = p.out.col(col0 + tile_col(1));
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const ConvOut::Col c = p.out.col(col0 + wn * (TN * 32) + j * 32 + l32);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rbase = row0 + wm * (TM * 32) + i * 32 + 4 * khalf;
+            for (int v = 0; v < 16; ++v) p.out.put2(obase, row0 + tile_row(i, v), c0, c1, acc[i][0][v], acc[i][1][v]);
+    } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) p.out.put(obase, rbase + 8 * (v / 4) + (v % 4), c, acc[i][j][v]);
+        for (int j = 0; j < TN; ++j) {
+            const ConvOut::Col c = p.out.col(col0 + tile_col(j));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) p.out.put(obase, row0 + tile_row(i, v), c, acc[i][j][v]);
         }
     }
 }
@@ -294,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
     constexpr int EA = BM * BK / kThreads, EB = BN * BK / kThreads;
     constexpr int RSTEP = kThreads / BK;  // 8 rows between a thread's elements
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* As = smem;
     float* Bs = smem + 2 * BK * LDA;
 
@@ -327,8 +398,15 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int l32 = lane & 31, khalf = lane >> 5;
-    const int a_off = khalf * LDA + wm * (TM * 32) + l32;
-    const int b_off = khalf * LDB + wn * (TN * 32) + l32;
+    // interleaved MFMA blocks and 8-byte fragment reads as in conv_fast_kernel (the row pitch must be even for those)
+    constexpr bool PAIR_M = TM == 2 && LDA % 2 == 0, PAIR_N = TN == 2 && LDB % 2 == 0;
+    const int a_off = khalf * LDA + wm * (TM * 32) + (PAIR_M ? 2 * l32 : l32);
+    const int b_off = khalf * LDB + wn * (TN * 32) + (PAIR_N ? 2 * l32 : l32);
+    auto tile_row = [&](int i, int v) {
+        const int rr = 4 * khalf + 8 * (v / 4) + (v % 4);
+        return wm * (TM * 32) + (PAIR_M ? 2 * rr + i : i * 32 + rr);
+    };
+    auto tile_col = [&](int j) { return wn * (TN * 32) + (PAIR_N ? 2 * l32 + j : j * 32 + l32); };
     float* a_st = As + kk * LDA + r_first;
     float* b_st = Bs + kk * LDB + r_first;
 
@@ -395,18 +473,32 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
         const float* at = As + cur * BK * LDA + a_off;
         const float* bt = Bs + cur * BK * LDB + b_off;
         float a[2][TM], b[2][TN];
+        auto fetch_a = [&](float (&dst)[TM], const float* src) {
+            if constexpr (PAIR_M) {
+                const float2 v = *reinterpret_cast<const float2*>(src);
+                dst[0] = v.x, dst[1] = v.y;
+            } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = at[i * 32];
+                for (int i = 0; i < TM; ++i) dst[i] = src[i * 32];
+            }
+        };
+        auto fetch_b = [&](float (&dst)[TN], const float* src) {
+            if constexpr (PAIR_N) {
+                const float2 v = *reinterpret_cast<const float2*>(src);
+                dst[0] = v.x, dst[1] = v.y;
+            } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = bt[j * 32];
+                for (int j = 0; j < TN; ++j) dst[j] = src[j * 32];
+            }
+        };
+        fetch_a(a[0], at);
+        fetch_b(b[0], bt);
 #pragma unroll
         for (int k2 = 0; k2 < BK; k2 += 2) {
             const int c = (k2 >> 1) & 1, nx = c ^ 1;
             if (k2 + 2 < BK) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[nx][i] = at[(k2 + 2) * LDA + i * 32];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[nx][j] = bt[(k2 + 2) * LDB + j * 32];
+                fetch_a(a[nx], at + (k2 + 2) * LDA);
+                fetch_b(b[nx], bt + (k2 + 2) * LDB);
             }
             __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of the MFMAs below
 #pragma unroll
@@ -415,26 +507,31 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+            if (k2 == BK / 2 && more) {  // as in conv_fast_kernel
+                store_step(cur ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (more) store_step(cur ^ 1);
         __syncthreads();
     }
 
     const int CRS = p.C * p.R * p.S;
     float* obase = p.ws + (size_t)split * p.K * CRS;
+    // columns are < CRS (column tiles are never ragged here); CRS and a pair's first column are even
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = col0 + wn * (TN * 32) + j * 32 + l32;  // < CRS: column tiles are never ragged here
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rbase = row0 + wm * (TM * 32) + i * 32 + 4 * khalf;
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + tile_row(i, v);
+            if (row >= p.K) continue;
+            float* orow = obase + (size_t)row * CRS + col0;
+            if constexpr (PAIR_N) {
+                *reinterpret_cast<float2*>(orow + tile_col(0)) = make_float2(acc[i][0][v], acc[i][1][v]);
+            } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = rbase + 8 * (v / 4) + (v % 4);
-                if (row < p.K) obase[(size_t)row * CRS + col] = acc[i][j][v];
+                for (int j = 0; j < TN; ++j) orow[tile_col(j)] = acc[i][j][v];
             }
         }
-    }
 }
 
 // dW[k][c][rs] = sum_s ws[s][k][rs*C + c], s ascending

@@ -341,6 +341,25 @@ struct ConvOut {
             base[idx] = v;
         }
     }
+    // Two neighbouring pixels (c1 is the column after c0, c0's pixel index even) of one row: a single 8-byte store
+    // when both lie in the same image plane at an even offset, two plain stores otherwise.
+    __device__ void put2(float* base, int row, const Col& c0, const Col& c1, float v0, float v1) const {
+        if (c1.ok && c1.off == c0.off + 1 && !(PQ & 1) && !(c0.off & 1)) {
+            if (relu) v0 = v0 > 0.f ? v0 : 0.f, v1 = v1 > 0.f ? v1 : 0.f;
+            if (row < rows) {
+                const size_t idx = c0.off + (size_t)row * PQ;
+                if (mask) {
+                    const float2 m = *reinterpret_cast<const float2*>(mask + idx);
+                    if (!(m.x > 0.f)) v0 = 0.f;
+                    if (!(m.y > 0.f)) v1 = 0.f;
+                }
+                *reinterpret_cast<float2*>(base + idx) = make_float2(v0, v1);
+            }
+        } else {
+            put(base, row, c0, v0);
+            put(base, row, c1, v1);
+        }
+    }
     __device__ float* base(int) const { return out; }
 };
 

@@ -139,10 +139,10 @@ static TailSplit conv_tail_split(int rows, long long M, int cred, int RS) {
     return t;
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, bool QUAD = false>
 static hipError_t conv_fast_cfg(ConvFastParams& p, const TailSplit& ts, float* partial, hipStream_t st) {
-    auto kern = conv_fast_kernel<BM, BN, WM, WN, false>;
-    auto kern_split = conv_fast_kernel<BM, BN, WM, WN, true>;
+    auto kern = conv_fast_kernel<BM, BN, WM, WN, false, QUAD>;
+    auto kern_split = conv_fast_kernel<BM, BN, WM, WN, true, QUAD>;
     constexpr size_t smem = sizeof(float) * 2 * 16 * ((BM + kConvFastPad<BN>) + (BN + kConvFastPad<BN>));
     static bool attr_set = false;
     if (!attr_set) {
@@ -197,8 +197,9 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
     const TailSplit ts = conv_tail_split(eo.rows, p.M, cred, R * S);
     float* partial = ws + (wcount + 63) / 64 * 64;
     if (eo.rows <= 32) return conv_fast_cfg<32, 256, 1, 4>(p, ts, partial, st);
-    if (eo.rows <= 64) return conv_fast_cfg<64, 256, 1, 4>(p, ts, partial, st);
-    return conv_fast_cfg<128, 128, 2, 2>(p, ts, partial, st);
+    const bool quad = eo.rows % 4 == 0;  // weight rows by 16-byte loads
+    if (eo.rows <= 64) return quad ? conv_fast_cfg<64, 256, 1, 4, true>(p, ts, partial, st) : conv_fast_cfg<64, 256, 1, 4>(p, ts, partial, st);
+    return quad ? conv_fast_cfg<128, 128, 2, 2, true>(p, ts, partial, st) : conv_fast_cfg<128, 128, 2, 2>(p, ts, partial, st);
 }
 
 static size_t conv_fast_workspace(size_t wcount, int rows, long long M, int cred, int RS) {
