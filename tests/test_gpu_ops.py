@@ -40,6 +40,10 @@ CONV_SHAPES = [
     (2, 16, 30, 30, 64, 7, 2, 3),     # strided forward on the packed-weight kernel
     (2, 16, 33, 31, 48, 3, 1, 1),     # 64-row tile, ragged pixels
     (1, 16, 3, 3, 16, 3, 1, 1),       # tiny image: every tap but the centre hits padding somewhere
+    (2, 16, 12, 12, 38, 3, 1, 1),     # packed-weight kernel, rows not a multiple of 4 (one weight row per load), 64-row tile
+    (2, 32, 10, 14, 134, 3, 1, 1),    # the same on the 128-row tile; backward-data on the 32-row tile
+    (1, 256, 6, 6, 256, 3, 1, 1),     # two tiles, 144 K-steps: the split-reduction path with its fix-up, both directions
+    (3, 32, 5, 7, 64, 3, 1, 1),       # odd pixel count per image (35): neighbouring pixels of a lane may lie in two images
 ]
 
 
