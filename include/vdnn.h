@@ -50,6 +50,12 @@ typedef enum {
  * memory-optimal one (none).  GREEDY is what phase 3 of vDNN_dyn produces: performance-optimal except
  * where its workspace would overflow the budget. */
 typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdnn_conv_algo_t;
+/* Two kernels stand behind "performance-optimal": the packed-weight direct kernel everywhere, and on wide 3x3 layers
+ * (see vdnn_op_conv_fwd_workspace) the Winograd algorithm, which is faster and wants far more workspace.  A plan
+ * gives a layer the Winograd workspace where it fits the budget at that point of the step (always, without a
+ * budget) and the direct kernel's elsewhere; with an explicit offload set (FIT, vdnn_set_offload_set) the forward
+ * pass keeps the direct kernel, since it runs at the pace of the offloads.  Plans under different budgets may
+ * therefore differ in rounding; vdnn_set_winograd(net, 0) keeps every plan of the net on the direct kernel. */
 
 typedef enum {
     VDNN_CONV = 0,       /* cross-correlation, zero padding, no bias */
@@ -94,6 +100,8 @@ typedef struct {
     int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
     int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the forward transfer windows fill; 0 = static schedule */
     int32_t window_fill_bwd_pm;   /* > 0: backward fetches are issued early, while live bytes stay within that share */
+    int32_t n_winograd_convs;     /* CONV layers whose workspace holds the Winograd algorithm in fwd or bwd */
+    int32_t reserved_;
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
@@ -116,6 +124,9 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
  * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
  * stays usable with its previous plan). */
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
+/* enabled = 0: no plan of this net uses the Winograd algorithm (default: enabled).  Takes effect at the next
+ * vdnn_set_policy / vdnn_set_offload_set. */
+vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
 /* VDNN_POLICY_FIT goes beyond the paper.  Section 3.3 motivates vDNN_dyn by the cost of offloading more
  * than the budget asks for, and Section 3.1 by the distance between the two uses of X that a transfer can
  * hide behind; where arithmetic is fast relative to the host link, step time is simply bytes moved over
@@ -218,12 +229,19 @@ const char* vdnn_op_last_error(void);
 /* stream: hipStream_t or NULL.  Shapes: X [N][C][H][W], W [K][C][R][S], Y [N][K][P][Q] with
  * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream. */
 
-/* Two implicit-GEMM algorithms, in the sense of Section 2.2's memory-optimal / performance-optimal
- * pair: without workspace the gather works directly on W as stored; with a workspace of
- * vdnn_op_conv_*_workspace() bytes (one packed copy of W, 0 when the faster kernel does not apply:
- * reduction channels not a multiple of 16, strided backward-data, tensors of 4 GiB or more) the faster
- * kernel runs.  workspace may be NULL: then the no-workspace algorithm runs.  Same results to rounding
- * order; each algorithm is deterministic. */
+/* Convolution algorithms in the sense of Section 2.2's memory-optimal / performance-optimal trade-off:
+ *  - no workspace: implicit GEMM whose gather works directly on W as stored (memory-optimal);
+ *  - one packed copy of W (+ partial sums of split tiles): the faster implicit-GEMM kernel; applies when the reduction
+ *    channels are a multiple of 16, backward-data is unstrided and the tensors are below 4 GiB;
+ *  - Winograd F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers with even H and W, reduction channels a multiple of 16,
+ *    output channels of the pass a multiple of 4, and reduction channels x output channels >= 256 x 512: transformed
+ *    filter (16/9 of W) plus transformed input and products for a chunk of images (at most the chunk size below).
+ * vdnn_op_conv_*_workspace() returns the bytes of the fastest algorithm that applies to the shape (0: only the first).
+ * vdnn_op_conv_fwd / _bwd_data run the fastest algorithm the given workspace has room for (NULL: the first).  Results
+ * agree to rounding (Winograd: a few 1e-6 of the largest output); each algorithm is deterministic. */
+/* Process-wide chunk size of the Winograd workspace in bytes (0 restores the default, 512 MiB).  Workspace sizes and
+ * plans derive from it: set it before creating nets, not while one exists. */
+void vdnn_op_set_winograd_chunk_bytes(size_t bytes);
 size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 /* Y = conv(X, W); relu != 0 applies max(.,0) to the result in the same kernel. */

@@ -52,6 +52,22 @@ def conv_slots(rows):
     return 1024
 
 
+WINOGRAD_CHUNK_BYTES = 512 << 20
+
+
+def winograd_workspace(n, cred, h, w, rows, k, stride, pad):
+    """Workspace of the F(2x2,3x3) Winograd algorithm where the library runs it (0 elsewhere): 3x3 / stride 1 / pad 1,
+    even image sides, reduction channels a multiple of 16 and at least 256, rows a multiple of 4, reduction channels x
+    rows at least 256 x 512.  Transformed filter (16 x cred x rows floats, rounded up to 256 bytes) plus transformed
+    input and products (16 x (cred + rows) floats per 2x2 output tile) for as many images as fit the chunk size."""
+    if not (k == 3 and stride == 1 and pad == 1 and h % 2 == 0 and w % 2 == 0 and cred % 16 == 0 and rows % 4 == 0
+            and cred >= 256 and cred * rows >= 256 * 512):
+        return 0
+    per_image = 16 * (cred + rows) * (h // 2) * (w // 2) * 4
+    nb = max(1, min(n, WINOGRAD_CHUNK_BYTES // per_image))
+    return _cdiv(16 * cred * rows, 64) * 64 * 4 + nb * per_image
+
+
 def conv_packed_workspace(wcount, rows, m, cred, rs):
     """Workspace of the packed-weight convolution kernel: a packed copy of W (rounded up to 256 bytes), plus
     partial sums for the tiles whose reduction is split because the last round of workgroups would be
@@ -176,9 +192,10 @@ def selected(net, info, b, policy):
     return False
 
 
-def workspace_bytes(net, info, i, phase, memopt=False):
-    """Transient workspace of layer i: partial sums of reduction-split GEMMs and packed weights.
-    memopt: the CONV layer runs the memory-optimal algorithm, which needs X, Y and W only (Section 2.2)."""
+def workspace_bytes(net, info, i, phase, memopt=False, direct=False):
+    """Transient workspace of layer i: partial sums of reduction-split GEMMs, packed weights, Winograd transforms.
+    memopt: the CONV layer runs the memory-optimal algorithm, which needs X, Y and W only (Section 2.2).
+    direct: a CONV layer wide enough for the Winograd algorithm is sized for the direct kernel instead."""
     l = net["layers"][i]
     n = net["batch"]
     c, h, w = info["shp"](l["inputs"][0])
@@ -191,12 +208,14 @@ def workspace_bytes(net, info, i, phase, memopt=False):
         rs = l["k"] * l["k"]
         if phase == "fwd":
             if c % 16 == 0 and 4 * n * c * h * w < 0xfffffff0:
-                return conv_packed_workspace(wbytes // 4, k, n * p * q, c, rs)
+                return ((0 if direct else winograd_workspace(n, c, h, w, k, l["k"], l["stride"], l["pad"]))
+                        or conv_packed_workspace(wbytes // 4, k, n * p * q, c, rs))
             return 0
         need_dx = info["bufof"](l["inputs"][0]) >= 0
         packed = 0
         if need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0 and 4 * n * k * p * q < 0xfffffff0:
-            packed = conv_packed_workspace(wbytes // 4, c, n * h * w, k, rs)
+            packed = ((0 if direct else winograd_workspace(n, k, h, w, c, l["k"], l["stride"], l["pad"]))
+                      or conv_packed_workspace(wbytes // 4, c, n * h * w, k, rs))
         # backward-filter: partial sums of the split reduction; with input channels a multiple of 32
         # the faster kernel always stages dW through the workspace (at least one copy)
         if c % 32 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
@@ -231,11 +250,12 @@ def baseline_bytes(net):
     return fm + wb + 2 * gmax + _al(wmax)
 
 
-def simulate(net, policy, budget, algo="p", offload_set=None):
+def simulate(net, policy, budget, algo="p", offload_set=None, winograd=True):
     """One training step under a static policy ("none" | "all" | "conv") and a convolution algorithm
     mode: "p" performance-optimal (workspace), "m" memory-optimal (none), "greedy" = performance-optimal
     except where that layer's workspace would overflow the budget (Section 3.3, phase 3 of vDNN_dyn).
     offload_set: when given, exactly these buffers are offloaded (the policy argument is then unused).
+    winograd: False keeps every layer on the direct kernel (the library's vdnn_set_winograd(net, 0)).
     Returns a dict with status ("ok" | "oom"), where it failed, peak / average / final pool bytes,
     transfer counts, the number of CONV layers on the memory-optimal algorithm and the ordered op trace."""
     info = analyse(net)
@@ -246,6 +266,7 @@ def simulate(net, policy, budget, algo="p", offload_set=None):
     samples = []
     st = dict(offloaded_bytes=0, prefetched_bytes=0, n_offload=0, n_prefetch=0, n_ondemand_fetch=0)
     memopt = set()  # CONV layers downgraded (or set) to the memory-optimal algorithm in either pass
+    wino = set()    # CONV layers given the Winograd workspace in either pass
 
     def layer_ws(i, phase):
         conv = layers[i]["type"] == "conv"
@@ -253,6 +274,13 @@ def simulate(net, policy, budget, algo="p", offload_set=None):
             memopt.add(i)
             return 0
         ws = workspace_bytes(net, info, i, phase)
+        direct = workspace_bytes(net, info, i, phase, direct=True) if conv else ws
+        if conv and ws and (not winograd or (offload_set is not None and phase == "fwd") or pool.live + _al(ws) > pool.budget):
+            # the Winograd algorithm runs where its workspace fits at this point; elsewhere the direct kernel stays;
+            # with an explicit offload set the forward pass keeps the direct kernel everywhere
+            ws = direct
+        if conv and ws > direct:
+            wino.add(i)
         if conv and algo == "greedy" and ws and pool.live + _al(ws) > pool.budget:
             memopt.add(i)
             return 0
@@ -375,23 +403,24 @@ def simulate(net, policy, budget, algo="p", offload_set=None):
         out["persistent_bytes"] = persistent
     out.update(st)
     out["n_memopt_convs"] = len(memopt)
+    out["n_winograd_convs"] = len(wino)
     return out
 
 
-def dynamic(net, budget):
+def dynamic(net, budget, winograd=True):
     """vDNN_dyn (Section 3.3, "Dynamic vDNN").  Pass 1: all with the memory-optimal algorithm must fit.
     Pass 2: performance-optimal algorithms with no offloading, else conv, else all - adopt the first
     that fits.  Pass 3: greedy per-layer downgrade under conv, then all; else the configuration of pass 1.
     Returns (policy or None, algorithm mode, result of the adopted pass)."""
-    first = simulate(net, "all", budget, "m")
+    first = simulate(net, "all", budget, "m", winograd=winograd)
     if first["status"] != "ok":
         return None, None, first
     for pol in ("none", "conv", "all"):
-        r = simulate(net, pol, budget, "p")
+        r = simulate(net, pol, budget, "p", winograd=winograd)
         if r["status"] == "ok":
             return pol, "p", r
     for pol in ("conv", "all"):
-        r = simulate(net, pol, budget, "greedy")
+        r = simulate(net, pol, budget, "greedy", winograd=winograd)
         if r["status"] == "ok":
             return pol, "greedy", r
     return "all", "m", first
@@ -421,7 +450,7 @@ def fit_candidates(net):
     return [b for b in sorted(info["nbytes"]) if selected(net, info, b, "all")]
 
 
-def fit_select(net, budget, algo="p"):
+def fit_select(net, budget, algo="p", winograd=True):
     """Offload set for "fit": start empty; while the step does not fit, add the SMALLEST remaining candidate
     whose addition makes it fit, and if there is none add the LARGEST remaining one (ties: lower id) and
     repeat.  Returns the set, or None when even every candidate together does not fit."""
@@ -430,7 +459,7 @@ def fit_select(net, budget, algo="p"):
     chosen = set()
 
     def fits(s):
-        return simulate(net, "none", budget, algo, offload_set=s)["status"] == "ok"
+        return simulate(net, "none", budget, algo, offload_set=s, winograd=winograd)["status"] == "ok"
 
     while not fits(chosen):
         rest = [b for b in cands if b not in chosen]
@@ -612,14 +641,14 @@ def trace_stats(trace):
     return st
 
 
-def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, windows=None):
+def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, windows=None, winograd=True):
     """The "fit" policy: offload set from fit_select (performance-optimal algorithms first, then the greedy
     downgrade, then memory-optimal everywhere), transfer windows from retime.  windows (default: fill_pm > 0)
     = False keeps the static schedule of the chosen set.  extra: that many more candidates, largest first (ties: lower id), join the
     set (what the library does when it finds no placement of the blocks inside the budget).
     Returns (offload set, algorithm mode, result dict) or (None, None, None)."""
     for algo in ("p", "greedy", "m"):
-        chosen = fit_select(net, budget, algo)
+        chosen = fit_select(net, budget, algo, winograd)
         if chosen is not None:
             break
     else:
@@ -628,7 +657,7 @@ def fit(net, budget, fill_pm=1000, part_bytes=PART_BYTES, extra=0, windows=None)
     for _ in range(extra):
         rest = [b for b in fit_candidates(net) if b not in chosen]
         chosen.add(max(rest, key=lambda b: (info["nbytes"][b], -b)))
-    r = simulate(net, "none", budget, algo, offload_set=chosen)
+    r = simulate(net, "none", budget, algo, offload_set=chosen, winograd=winograd)
     if (fill_pm > 0 if windows is None else windows) and budget:
         r["trace"] = retime(r["trace"], budget, fill_pm, part_bytes)
         r.update(trace_stats(r["trace"]))

@@ -50,6 +50,7 @@ class MemStats(C.Structure):
                 ("n_offload", C.c_int32), ("n_prefetch", C.c_int32), ("n_ondemand_fetch", C.c_int32),
                 ("effective_policy", C.c_int32), ("conv_algo", C.c_int32), ("n_memopt_convs", C.c_int32),
                 ("window_fill_pm", C.c_int32), ("window_fill_bwd_pm", C.c_int32),
+                ("n_winograd_convs", C.c_int32), ("reserved_", C.c_int32),
                 ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("stall_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double)]
 
@@ -62,6 +63,7 @@ EXPORTS = {
     "vdnn_create": ([C.POINTER(NetDesc), _sz, C.POINTER(_vp)], _i),
     "vdnn_set_policy": ([_vp, _i], _i),
     "vdnn_set_conv_algo": ([_vp, _i], _i),
+    "vdnn_set_winograd": ([_vp, C.c_int32], _i),
     "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32, C.c_int32], _i),
     "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
     "vdnn_set_window_part": ([_vp, _sz], _i),
@@ -83,6 +85,7 @@ EXPORTS = {
     "vdnn_last_error": ([_vp], C.c_char_p),
     "vdnn_destroy": ([_vp], None),
     "vdnn_op_last_error": ([], C.c_char_p),
+    "vdnn_op_set_winograd_chunk_bytes": ([_sz], None),
     "vdnn_op_conv_fwd_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_data_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
@@ -161,6 +164,9 @@ class Net:
 
     def set_policy(self, policy):
         self._chk(lib.vdnn_set_policy(self.h, POLICY[policy]))
+
+    def set_winograd(self, enabled):
+        self._chk(lib.vdnn_set_winograd(self.h, 1 if enabled else 0))
 
     def set_conv_algo(self, algo):
         """"p" (performance-optimal, workspace), "m" (memory-optimal) or "greedy"; applies at the next set_policy."""
@@ -296,6 +302,10 @@ def _ck(s, what):
 # ---- single-layer entry points on torch CUDA tensors (marshalling only) -------------------------
 def _ws_args(ws):
     return (ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0)
+
+
+def op_set_winograd_chunk_bytes(nbytes):
+    lib.vdnn_op_set_winograd_chunk_bytes(int(nbytes))
 
 
 def op_conv_fwd_workspace(x_shape, w_shape, stride, pad):

@@ -47,6 +47,11 @@ struct ConvFastParams {
     int tile_begin, n_tiles, splits, steps_per_split;
     float* partial;
     ConvOut out;
+    // groups > 1 (unsplit launches only): `groups` independent problems of the same shape in one launch, group g
+    // reading src + g * src_gstride, wp + g * wp_gstride and writing out + g * out_gstride (strides in elements);
+    // the grid is n_tiles * groups workgroups.  Used for the 16 element-wise products of the Winograd algorithm.
+    int groups = 1;
+    size_t src_gstride = 0, wp_gstride = 0, out_gstride = 0;
 };
 
 // Wp[((cb*RS + rs)*16 + ci)][row]:
@@ -95,14 +100,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 
     const int tid = threadIdx.x;
     const int nsplit = SPLIT ? p.splits : 1;
-    const int logical = xcd_remap(blockIdx.x, p.n_tiles * nsplit);
+    int logical = xcd_remap(blockIdx.x, p.n_tiles * nsplit * (SPLIT ? 1 : p.groups));
+    // the same for the whole workgroup; said explicitly so that the buffer resources below stay in scalar registers
+    const int group = SPLIT ? 0 : __builtin_amdgcn_readfirstlane(logical / p.n_tiles);
+    if constexpr (!SPLIT) logical -= group * p.n_tiles;
     const int tile_local = logical / nsplit, split = logical - tile_local * nsplit;
     const int tile = (SPLIT ? p.tile_begin : 0) + tile_local;
     const int tile_n = tile / p.tiles_m, tile_m = tile - tile_n * p.tiles_m;
     const int row0 = tile_m * BM, col0 = tile_n * BN;
 
-    const __amdgpu_buffer_rsrc_t rs_src = make_rsrc(p.src, p.src_bytes);
-    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.wp, p.wp_bytes);
+    const __amdgpu_buffer_rsrc_t rs_src = make_rsrc(p.src + (size_t)group * p.src_gstride, p.src_bytes);
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.wp + (size_t)group * p.wp_gstride, p.wp_bytes);
 
     // ---- A (weights): thread owns row a_row and k = a_k0 + j*KSA ----
     const int a_row = tid % BM, a_k0 = tid / BM;
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
         return;
     }
     if constexpr (SPLIT) return;
-    float* obase = p.out.base(0);
+    float* obase = p.out.base(0) + (size_t)group * p.out_gstride;
     if constexpr (PAIR_N) {
         const ConvOut::Col c0 = p.out.col(col0 + tile_col(0)), c1 = p.out.col(col0 + tile_col(1));
 #pragma unroll

@@ -144,16 +144,21 @@ bool fold_bwd(const vdnn_net& n, int reader) {
 // ---------------------------------------------------------------------------------------------
 // workspace of a layer (partial sums of reduction-split GEMMs)
 // ---------------------------------------------------------------------------------------------
-size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt) {
+// direct: a CONV layer that could run the Winograd algorithm is sized for the packed-weight direct kernel instead
+size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt, bool direct) {
     const Layer& l = n.layers[i];
     int C, H, W;
     shape_of(n, l.inputs[0], &C, &H, &W);
     if (l.type == VDNN_CONV && memopt) return 0;  // the memory-optimal algorithm needs X, Y, W only
-    if (l.type == VDNN_CONV && !bwd) return conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+    if (l.type == VDNN_CONV && !bwd)
+        return direct ? conv_fwd_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
+                      : conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
     if (l.type == VDNN_CONV && bwd) {
         const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
-        return std::max(conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad),
-                        need_dx ? conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad) : (size_t)0);
+        const size_t dx = !need_dx ? 0
+                          : direct ? conv_bwd_data_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
+                                   : conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+        return std::max(conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad), dx);
     }
     if (l.type == VDNN_FC) {
         const int I = C * H * W;

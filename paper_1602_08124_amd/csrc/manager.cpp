@@ -328,6 +328,12 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t* n, vdnn_conv_algo_t algo) {
     return VDNN_OK;
 }
 
+vdnn_status_t vdnn_set_winograd(vdnn_net_t* n, int32_t enabled) {
+    if (!n) return VDNN_ERR_INVALID_ARG;
+    n->winograd = enabled != 0;
+    return VDNN_OK;
+}
+
 vdnn_status_t vdnn_set_policy(vdnn_net_t* n, vdnn_policy_t policy) {
     if (!n || policy < VDNN_POLICY_NONE || policy > VDNN_POLICY_FIT) return VDNN_ERR_INVALID_ARG;
     n->fwd_done = false;
@@ -526,6 +532,7 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
         s.n_ondemand_fetch = p.n_ondemand;
         s.conv_algo = p.algo;
         s.n_memopt_convs = p.n_memopt;
+        s.n_winograd_convs = p.n_winograd;
         s.window_fill_pm = p.fill_pm;
         s.window_fill_bwd_pm = p.fill_bwd_pm;
     }

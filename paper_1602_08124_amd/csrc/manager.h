@@ -117,6 +117,7 @@ struct Plan {
     int algo = 0;                        // vdnn_conv_algo_t the plan was compiled with
     std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
     int n_memopt = 0;
+    int n_winograd = 0;                  // CONV layers whose fwd or bwd workspace is sized for the Winograd algorithm
     std::vector<char> offload_set;  // buffer id + 1 -> this step offloads it
     int fill_pm = 0, fill_bwd_pm = 0;  // share of the budget (per mille) the transfer windows may fill in forward / backward; 0 = static schedule
 };
@@ -131,6 +132,7 @@ struct vdnn_net {
     size_t part_bytes = (size_t)128 << 20;  // transfer windows move larger blocks in pieces of about this size (0 = whole blocks)
     int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
     int static_algo = VDNN_ALGO_PERF;
+    bool winograd = true;  // plans may size wide 3x3 layers for the Winograd algorithm
     vdnn::Plan plan;
     size_t baseline = 0;
 
@@ -195,7 +197,7 @@ inline void shape_of(const vdnn_net& n, int layer, int* C, int* H, int* W) {
 vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::string& err);
 bool fold_fwd(const vdnn_net& n, int conv);     // the conv applies the ReLU living in its output
 bool fold_bwd(const vdnn_net& n, int reader);   // the reader applies the backward of the ReLU living in its input
-size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false);
+size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false, bool direct = false);
 bool selected(const vdnn_net& n, int b, int policy);
 size_t baseline_bytes(const vdnn_net& n);
 

@@ -20,7 +20,13 @@ namespace vdnn {
 int gemm_splits(long long m, long long n, long long kred);
 size_t gemm_workspace_bytes(long long m, long long n, long long kred);
 
-// ws: room for a packed copy of W (conv_*_workspace bytes); with less the slower no-workspace kernel runs.
+// conv_*_workspace: bytes of the fastest algorithm for the shape (Winograd F(2x2,3x3) on wide 3x3 layers, else the
+// packed-weight direct kernel; 0 where only the no-workspace kernel applies).  conv_fwd / conv_bwd_data run the fastest
+// algorithm that the workspace they are given has room for.
+// conv_*_packed_workspace: bytes of the packed-weight direct kernel alone (what a Winograd-sized layer falls back to).
+void conv_set_winograd_chunk_bytes(size_t bytes);  // V + Mt bytes per chunk of images (0 = default 512 MiB)
+size_t conv_fwd_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+size_t conv_bwd_data_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R,

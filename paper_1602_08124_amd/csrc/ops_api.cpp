@@ -23,6 +23,8 @@ static bool conv_ok(int N, int C, int H, int W, int K, int R, int S, int stride,
 
 extern "C" {
 
+void vdnn_op_set_winograd_chunk_bytes(size_t bytes) { conv_set_winograd_chunk_bytes(bytes); }
+
 size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     if (!conv_ok(N, C, H, W, K, R, S, stride, pad)) return 0;
     return conv_fwd_workspace(N, C, H, W, K, R, S, stride, pad);

@@ -3,6 +3,7 @@
 // three FC products.  Reductions that would leave the chip idle are split across workgroups;
 // partial sums go to a caller-provided workspace and are added in a fixed order.
 #include "conv_fast.h"
+#include "winograd.h"
 #include "gemm_tile.h"
 #include "ops.h"
 
@@ -158,7 +159,7 @@ static hipError_t conv_fast_cfg(ConvFastParams& p, const TailSplit& ts, float* p
     const int total_steps = p.Cred / 16 * p.R * p.S;
     if (ts.full_tiles > 0) {
         p.tile_begin = 0; p.n_tiles = ts.full_tiles; p.splits = 1; p.steps_per_split = total_steps; p.partial = nullptr;
-        VDNN_LAUNCH(kern, dim3((unsigned)ts.full_tiles), dim3(kThreads), smem, st, p);
+        VDNN_LAUNCH(kern, dim3((unsigned)(ts.full_tiles * p.groups)), dim3(kThreads), smem, st, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -202,21 +203,109 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
     return quad ? conv_fast_cfg<128, 128, 2, 2, true>(p, ts, partial, st) : conv_fast_cfg<128, 128, 2, 2>(p, ts, partial, st);
 }
 
+// -------------------------------------------------------------------------------------------
+// Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, even H and W, reduction channels a multiple
+// of 16, rows a multiple of 4, and reduction channels x rows at least 256 x 512: measured on VGG-16 (256) the direct
+// kernel's 137 TFLOP/s become 196 at 512 x 512 channels (28 x 28), 182 (14 x 14), 163-170 at 256 x 512, and nothing
+// is gained at 256 x 256 and below, where the transforms' HBM traffic costs what the saved multiplications gain.
+// Workspace: U, then V and Mt for `nb` images, nb the largest count that keeps V + Mt within the chunk size.
+// -------------------------------------------------------------------------------------------
+static size_t g_wino_chunk_bytes = (size_t)512 << 20;
+
+void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? bytes : (size_t)512 << 20; }
+
+static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
+           (long long)cred * rows >= 256LL * 512 && N >= 1;
+}
+
+static int wino_chunk(int N, int cred, int H, int W, int rows) {
+    const size_t per_image = (size_t)16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
+    return (int)std::max<size_t>(1, std::min<size_t>((size_t)N, g_wino_chunk_bytes / per_image));
+}
+
+static size_t wino_workspace(int N, int cred, int H, int W, int rows) {
+    const size_t u = ((size_t)16 * cred * rows + 63) / 64 * 64 * sizeof(float);
+    return u + (size_t)wino_chunk(N, cred, H, W, rows) * 16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
+}
+
+// src [N][cred][H][W] -> out [N][rows][H][W]; w is the layer's KCRS filter; bwd selects which way it is applied.
+static hipError_t conv_winograd(const float* src, const float* w, float* ws, float* out, const float* mask, int relu, int N, int cred, int H,
+                                int W, int rows, int K, int C, int bwd, hipStream_t st) {
+    const int T = (H / 2) * (W / 2);
+    const int nb = wino_chunk(N, cred, H, W, rows);
+    float* u = ws;
+    float* v = ws + ((size_t)16 * cred * rows + 63) / 64 * 64;
+    float* mt = v + (size_t)16 * nb * cred * T;
+    const size_t wcount = (size_t)rows * cred;
+    VDNN_LAUNCH(wino_filter_kernel, dim3((unsigned)std::min<size_t>((wcount + 255) / 256, 4096)), dim3(256), 0, st, w, u, K, C, bwd);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int tb = T <= 64 ? 64 : 256;
+    for (int n0 = 0; n0 < N; n0 += nb) {
+        const int cur = std::min(nb, N - n0);
+        VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        ConvFastParams p;
+        p.src = v; p.wp = u;
+        p.src_bytes = (uint32_t)((size_t)cur * cred * T * 4);
+        p.wp_bytes = (uint32_t)((size_t)cred * rows * 4);
+        p.rows = rows;
+        p.Cred = cred; p.H = H / 2; p.W = W / 2;
+        p.R = 1; p.S = 1; p.stride = 1; p.pad = 0;
+        p.P = H / 2; p.Q = W / 2; p.M = cur * T;
+        p.fd_pq = make_fastdiv((uint32_t)T);
+        p.fd_q = make_fastdiv((uint32_t)(W / 2));
+        ConvOut eo;
+        eo.out = mt; eo.mask = nullptr; eo.rows = rows; eo.M = p.M; eo.PQ = T; eo.relu = 0; eo.fd_pq = p.fd_pq;
+        p.out = eo;
+        p.groups = 16;
+        p.src_gstride = (size_t)cur * cred * T;
+        p.wp_gstride = (size_t)cred * rows;
+        p.out_gstride = (size_t)cur * rows * T;
+        TailSplit ts;
+        ts.splits = 1; ts.steps_per_split = cred / 16; ts.bytes = 0; ts.tail_tiles = 0;
+        ts.full_tiles = rows <= 64 ? cdiv(p.M, 256) : cdiv(rows, 128) * cdiv(p.M, 128);
+        e = rows <= 64 ? conv_fast_cfg<64, 256, 1, 4, true>(p, ts, nullptr, st) : conv_fast_cfg<128, 128, 2, 2, true>(p, ts, nullptr, st);
+        if (e != hipSuccess) return e;
+        VDNN_LAUNCH(wino_output_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)rows, (unsigned)cur), dim3(tb), 0, st, (const float*)mt, out, mask, n0,
+                    cur, rows, H, W, relu);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 static size_t conv_fast_workspace(size_t wcount, int rows, long long M, int cred, int RS) {
     return (wcount + 63) / 64 * 64 * sizeof(float) + conv_tail_split(rows, M, cred, RS).bytes;
 }
 
-size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+// workspace of the packed-weight direct kernel (0: it does not apply)
+size_t conv_fwd_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     if (!fast_ok((long long)N * C * H * W, (long long)K * C * R * S, C, R, S)) return 0;
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     return conv_fast_workspace((size_t)K * C * R * S, K, (long long)N * P * Q, C, R * S);
 }
 
-size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+size_t conv_bwd_data_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (stride != 1 || pad > R - 1) return 0;
     if (!fast_ok((long long)N * K * P * Q, (long long)K * C * R * S, K, R, S)) return 0;
     return conv_fast_workspace((size_t)K * C * R * S, C, (long long)N * H * W, K, R * S);
+}
+
+// workspace of the fastest algorithm for the shape: Winograd where it applies, else the packed-weight direct kernel
+size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (packed && wino_ok(N, C, H, W, K, R, S, stride, pad)) return wino_workspace(N, C, H, W, K);
+    return packed;
+}
+
+size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (packed && wino_ok(N, K, H, W, C, R, S, stride, pad)) return wino_workspace(N, K, H, W, C);
+    return packed;
 }
 
 hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
@@ -230,8 +319,11 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
     wa.fd_rs = make_fastdiv(1);
     ConvOut eo;
     eo.out = y; eo.mask = nullptr; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
-    const size_t need = conv_fwd_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (need && ws && ws_bytes >= need) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
+    // the fastest algorithm the given workspace has room for
+    const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (packed && ws && wino_ok(N, C, H, W, K, R, S, stride, pad) && ws_bytes >= wino_workspace(N, C, H, W, K))
+        return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, st);
+    if (packed && ws && ws_bytes >= packed) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
 }
 
@@ -284,8 +376,10 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
     eo.out = dx; eo.mask = relu_mask; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
-    const size_t need = conv_bwd_data_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (need && ws && ws_bytes >= need)
+    const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+    if (packed && ws && wino_ok(N, K, H, W, C, R, S, stride, pad) && ws_bytes >= wino_workspace(N, K, H, W, C))
+        return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, st);
+    if (packed && ws && ws_bytes >= packed)
         return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
     return conv_gemm(wa, g, eo, st);
 }

@@ -212,6 +212,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
     p.algo = algo;
     p.memopt_fwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
     p.memopt_bwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
+    std::vector<char> wino(n.layers.size(), 0);  // CONV layers given the Winograd workspace in either pass
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     Compiler c(n, p, budget);
     const int L = (int)n.layers.size();
@@ -256,6 +257,11 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         c.samples.push_back(c.live);
         if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); p.blocks[res[i + 1]].buf = i; }
         size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
+        // The Winograd algorithm runs where its workspace fits at this point; elsewhere the layer keeps the direct kernel.
+        // With an explicit offload set the forward pass keeps the direct kernel everywhere: it runs at the pace of the
+        // offloads, which wait in memory for their copies, and a large workspace would only force them out earlier.
+        if (ws && l.type == VDNN_CONV && (!n.winograd || offload_set || c.live + align_up(ws) > budget)) ws = layer_workspace(n, i, false, p.memopt_fwd[i], true);
+        if (l.type == VDNN_CONV && ws > layer_workspace(n, i, false, p.memopt_fwd[i], true)) wino[i] = 1;
         if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
@@ -342,6 +348,8 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
             }
         }
         size_t ws = layer_workspace(n, m, true, p.memopt_bwd[m]);
+        if (ws && l.type == VDNN_CONV && (!n.winograd || c.live + align_up(ws) > budget)) ws = layer_workspace(n, m, true, p.memopt_bwd[m], true);
+        if (l.type == VDNN_CONV && ws > layer_workspace(n, m, true, p.memopt_bwd[m], true)) wino[m] = 1;
         if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_bwd[m] = 1; ws = 0; }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
@@ -371,6 +379,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         for (int b : offloaded_at[i]) p.offload_set[b + 1] = 1;
     for (int i = 0; i < L; ++i)
         if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
+    for (int i = 0; i < L; ++i) p.n_winograd += wino[i];
     if (place) finish_plan(n, p, fill_pm, fill_bwd_pm);
     else p.ok = true;
 }

@@ -1,0 +1,127 @@
+// Winograd F(2x2, 3x3) convolution (Lavin & Gray's minimal-filtering form) for 3x3, stride 1, pad 1 layers with even
+// H and W: Y = A^T [ (G g G^T) .* (B^T d B) ] A per 2x2 output tile, d the 4x4 input patch.  The 16 element-wise
+// products, summed over channels, are 16 independent GEMMs [rows x Cred] x [Cred x tiles] that run as one grouped
+// launch of conv_fast_kernel (a 1x1 convolution per group); 2.25x fewer multiplications than the direct form.
+// This is the kind of performance-optimal algorithm that pays with workspace (Section 2.2 of the paper): the
+// transformed filter U, the transformed input V and the products Mt live there, V and Mt for a chunk of images
+// at a time so that the workspace stays bounded.
+//
+// Layouts (T = (H/2)*(W/2) tiles per image, nb images per chunk):
+//   U [16][Cred][rows]      rows = output channels of the pass (K forward, C backward-data)
+//   V [16][nb][Cred][T]
+//   Mt[16][nb][rows][T]
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vdnn {
+
+// U[xi][cred][row] = (G g G^T)[xi] of the 3x3 filter g that pass `bwd` applies for (row, cred):
+// forward g = W[row][cred][.][.]; backward-data g = W[cred][row] with both taps flipped.
+__global__ void wino_filter_kernel(const float* __restrict__ w, float* __restrict__ u, int K, int C, int bwd) {
+    const int rows = bwd ? C : K, cred = bwd ? K : C;
+    const size_t total = (size_t)rows * cred;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int row = (int)(i % rows), cr = (int)(i / rows);
+        const float* g = bwd ? w + ((size_t)cr * C + row) * 9 : w + ((size_t)row * C + cr) * 9;
+        float f[3][3];
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = 0; b < 3; ++b) f[a][b] = bwd ? g[(2 - a) * 3 + (2 - b)] : g[a * 3 + b];
+        float t[4][3];  // G f
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            t[0][b] = f[0][b];
+            t[1][b] = 0.5f * (f[0][b] + f[1][b] + f[2][b]);
+            t[2][b] = 0.5f * (f[0][b] - f[1][b] + f[2][b]);
+            t[3][b] = f[2][b];
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const float o0 = t[a][0], o1 = 0.5f * (t[a][0] + t[a][1] + t[a][2]), o2 = 0.5f * (t[a][0] - t[a][1] + t[a][2]), o3 = t[a][2];
+            u[((size_t)(a * 4 + 0) * cred + cr) * rows + row] = o0;
+            u[((size_t)(a * 4 + 1) * cred + cr) * rows + row] = o1;
+            u[((size_t)(a * 4 + 2) * cred + cr) * rows + row] = o2;
+            u[((size_t)(a * 4 + 3) * cred + cr) * rows + row] = o3;
+        }
+    }
+}
+
+// V[xi][n][c][t] = (B^T d B)[xi], d = the 4x4 patch of src[n0 + n][c] whose top-left corner is (2*ty - 1, 2*tx - 1).
+// grid (ceil(T / blockDim.x), Cred, nb); lanes walk along tiles.
+__global__ void wino_input_kernel(const float* __restrict__ src, float* __restrict__ v, int n0, int nb, int C, int H, int W) {
+    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int c = blockIdx.y, n = blockIdx.z;
+    const int ty = t / TW, tx = t - ty * TW;
+    const float* plane = src + ((size_t)(n0 + n) * C + c) * H * W;
+    float d[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int ih = 2 * ty - 1 + i;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int iw = 2 * tx - 1 + j;
+            d[i][j] = ((unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W) ? plane[ih * W + iw] : 0.f;
+        }
+    }
+    float r[4][4];  // B^T d
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        r[0][j] = d[0][j] - d[2][j];
+        r[1][j] = d[1][j] + d[2][j];
+        r[2][j] = d[2][j] - d[1][j];
+        r[3][j] = d[1][j] - d[3][j];
+    }
+    const size_t gstride = (size_t)nb * C * T;
+    float* o = v + ((size_t)n * C + c) * T + t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[(size_t)(i * 4 + 0) * gstride] = r[i][0] - r[i][2];
+        o[(size_t)(i * 4 + 1) * gstride] = r[i][1] + r[i][2];
+        o[(size_t)(i * 4 + 2) * gstride] = r[i][2] - r[i][1];
+        o[(size_t)(i * 4 + 3) * gstride] = r[i][1] - r[i][3];
+    }
+}
+
+// out[n0 + n][row][2ty + i][2tx + j] = (A^T m A)[i][j], m[xi] = Mt[xi][n][row][t]; optional ReLU on the value
+// (forward) or zeroing where mask is not positive (backward-data with the preceding in-place ReLU folded in).
+// grid (ceil(T / blockDim.x), rows, nb).
+__global__ void wino_output_kernel(const float* __restrict__ mt, float* __restrict__ out, const float* __restrict__ mask, int n0, int nb,
+                                   int rows, int H, int W, int relu) {
+    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int row = blockIdx.y, n = blockIdx.z;
+    const int ty = t / TW, tx = t - ty * TW;
+    const size_t gstride = (size_t)nb * rows * T;
+    const float* mi = mt + ((size_t)n * rows + row) * T + t;
+    float m[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[i][j] = mi[(size_t)(i * 4 + j) * gstride];
+    float s[2][4];  // A^T m
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        s[0][j] = m[0][j] + m[1][j] + m[2][j];
+        s[1][j] = m[1][j] - m[2][j] - m[3][j];
+    }
+    const size_t base = (((size_t)(n0 + n) * rows + row) * H + 2 * ty) * W + 2 * tx;  // even: W is even
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        float y0 = s[i][0] + s[i][1] + s[i][2], y1 = s[i][1] - s[i][2] - s[i][3];
+        if (relu) y0 = y0 > 0.f ? y0 : 0.f, y1 = y1 > 0.f ? y1 : 0.f;
+        const size_t idx = base + (size_t)i * W;
+        if (mask) {
+            const float2 mk = *reinterpret_cast<const float2*>(mask + idx);
+            if (!(mk.x > 0.f)) y0 = 0.f;
+            if (!(mk.y > 0.f)) y1 = 0.f;
+        }
+        *reinterpret_cast<float2*>(out + idx) = make_float2(y0, y1);
+    }
+}
+
+}  // namespace vdnn

@@ -75,8 +75,11 @@ def test_conv_layer_full_size(B, cfg):
         assert abs(a - b) < 2e-5 * abs(a) + 1e-3
 
 
-def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=()):
+def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=False):
+    """winograd=False: every plan keeps the direct convolution kernel, so that runs under different budgets use the same
+    arithmetic and can be compared bit by bit (which layers get the Winograd workspace depends on the budget)."""
     n = B.Net(net, budget)
+    n.set_winograd(winograd)
     n.set_policy(policy)
     n.attach_torch()
     for i, w in weights.items():
@@ -124,13 +127,14 @@ def test_vgg16_b256_step_under_12_gib(B):
     for pol in ("all", "conv", "dyn", "fit"):
         loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G)
         if pol == "fit":
-            ref = ms.fit(net, 12 * G, st["window_fill_pm"])[2]
+            ref = ms.fit(net, 12 * G, st["window_fill_pm"], winograd=False)[2]
             assert st["n_offload"] == ref["n_offload"] > 2   # the two feature maps move in pieces
             assert st["peak_bytes"] >= ref["peak_bytes"]     # fetches issued early hold memory longer
             ref["peak_bytes"] = st["peak_bytes"]
             assert st["offloaded_bytes"] == 3288334336 + 822083584  # c1_1's output and pool1's output
         else:
-            ref = ms.simulate(net, st["effective_policy"], 12 * G)
+            ref = ms.simulate(net, st["effective_policy"], 12 * G, winograd=False)
+        assert st["n_winograd_convs"] == 0
         assert st["peak_bytes"] == ref["peak_bytes"] <= 12 * G
         assert st["offloaded_bytes"] == ref["offloaded_bytes"] == st["prefetched_bytes"]
         assert st["pool_extent_bytes"] <= 12 * G
@@ -148,6 +152,37 @@ def test_vgg16_b256_step_under_12_gib(B):
         assert loss == base_loss, pol
         for i in weights:
             assert np.array_equal(dw[i], base_dw[i]), (pol, i)
+
+
+def test_vgg16_b256_winograd_plans(B):
+    """What the library does by default: wide 3x3 layers get the Winograd workspace where it fits the budget at that
+    point of the step.  Which layers those are, and the peak that follows, equal the memory-schedule oracle; loss and
+    weight gradients agree with the all-direct run to rounding (plus the few ReLU / arg-max decisions that the
+    different rounding of the c4 / c5 outputs flips)."""
+    import torch
+    from tests.gpu_util import rel_err
+    net = nets.vgg16(256)
+    x, labels, weights = gen.make(net)
+    xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
+    base_loss, base_dw, base_st, _ = _run(B, net, xd, ld, weights, "none", 0)
+    assert base_st["n_winograd_convs"] == 0
+    seen = []
+    for pol, budget in (("none", 0), ("conv", 12 * G), ("fit", 12 * G)):
+        loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, budget, winograd=True)
+        if pol == "fit":
+            ref = ms.fit(net, budget, st["window_fill_pm"])[2]
+            assert st["peak_bytes"] >= ref["peak_bytes"]
+        else:
+            ref = ms.simulate(net, pol, budget if budget else 1 << 60)
+            assert st["peak_bytes"] == ref["peak_bytes"]
+        assert st["n_winograd_convs"] == ref["n_winograd_convs"] and st["offloaded_bytes"] == ref["offloaded_bytes"]
+        seen.append(st["n_winograd_convs"])
+        assert abs(loss - base_loss) < 1e-5 * abs(base_loss), pol
+        for i in weights:
+            # below the classifier the flipped decisions dominate, as against the fp64 oracle at this size
+            # (test_vgg16_b256_step_against_the_oracle_at_full_size): same bounds
+            assert rel_err(dw[i], base_dw[i]) < (TOL if net["layers"][i]["type"] == "fc" else 3e-3), (pol, i)
+    assert seen[0] == 6 and seen[1] > 0   # c4_1 ... c5_3 without a budget
 
 
 @pytest.mark.parametrize("name,policy,budget", [("alexnet", "conv", 1 * G), ("overfeat", "all", 2 * G), ("overfeat", "conv", 2 * G),
@@ -168,7 +203,7 @@ def test_other_workloads_full_size(B, name, policy, budget):
         assert ms.simulate(net, "none", budget)["status"] == "oom" and st["offloaded_bytes"] == st["prefetched_bytes"] > 0
         assert st["peak_bytes"] <= st["pool_extent_bytes"] <= budget and st["window_fill_pm"] > 0
     else:
-        ref = ms.simulate(net, st["effective_policy"], budget)
+        ref = ms.simulate(net, st["effective_policy"], budget, winograd=False)
         assert ref["status"] == "ok"
         assert st["peak_bytes"] == ref["peak_bytes"] <= budget and st["pool_extent_bytes"] <= budget
         assert st["offloaded_bytes"] == ref["offloaded_bytes"] and st["n_ondemand_fetch"] == ref["n_ondemand_fetch"]
@@ -187,7 +222,7 @@ def test_very_deep_vgg_batch_32(B, extra, check_identity):
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 50 + extra)
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
     loss, dw, st, _ = _run(B, net, xd, ld, weights, "all", 12 * G)
-    ref = ms.simulate(net, "all", 12 * G)
+    ref = ms.simulate(net, "all", 12 * G, winograd=False)
     info = ms.analyse(net)
     assert np.isfinite(loss)
     assert st["peak_bytes"] == ref["peak_bytes"] and st["offloaded_bytes"] == ref["offloaded_bytes"]
@@ -226,7 +261,7 @@ def test_vgg16_b256_step_against_the_oracle_at_full_size(B):
     net = nets.vgg16(256)
     x, labels, weights = gen.make(net)
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
-    loss, dw, st, _ = _run(B, net, xd, ld, weights, "none", 0)
+    loss, dw, st, _ = _run(B, net, xd, ld, weights, "none", 0, winograd=True)
     assert abs(loss - gold["loss"]) < TOL * abs(gold["loss"])
     assert sorted(int(i) for i in gold["layers"]) == sorted(weights)
     for i, g in gold["layers"].items():
@@ -251,7 +286,7 @@ def test_vgg16_full_resolution_decisions_shared_with_the_oracle(B):
     net = nets.vgg16(2)
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 77)
     hooks = tuple(range(len(net["layers"])))
-    loss, dw, st, caps = _run(B, net, torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda(), weights, "none", 0, hooks)
+    loss, dw, st, caps = _run(B, net, torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda(), weights, "none", 0, hooks, winograd=True)
     ref = onet.step(net, x, labels, weights, outs_override=caps)
     assert abs(loss - ref["loss"]) < TOL * abs(ref["loss"])
     for i, y in enumerate(ref["outs"]):

@@ -331,3 +331,75 @@ def test_conv_random_shapes(B, shape):
         dw = torch.full(wt.shape, float("nan"), device="cuda")
         B.op_conv_bwd_filter(xd, dyd, dw, _ws(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, st, pd)) if use_ws else None, st, pd)
         assert rel_err(host(dw), ref_dw) < TOL
+
+
+# ---- Winograd F(2x2,3x3): layers wide enough for the library to choose it (reduction channels x rows >= 256 x 512) ----
+WINO_SHAPES = [
+    # N, C, H, W, K
+    (2, 256, 8, 8, 512),     # forward: 256 -> 512; backward-data: 512 -> 256
+    (1, 512, 6, 10, 256),    # 15 tiles per image (odd), non-square image
+    (3, 512, 4, 4, 512),     # four tiles per image
+    (2, 272, 2, 2, 512),     # one tile per image; backward-data has a ragged row tile (272 rows); channels not a multiple of 32
+]
+
+
+def _wino_case(B, shape, chunk_bytes=0):
+    import torch
+    n, c, h, w, k = shape
+    x, wt = _t((n, c, h, w), 61), _t((k, c, 3, 3), 62)
+    dy = _t((n, k, h, w), 63)
+    xr = np.maximum(_t((n, c, h, w), 64), 0)
+    ref_y = L.conv_fwd(x, wt, 1, 1)
+    ref_dx = L.conv_bwd_data(dy, wt, x.shape, 1, 1)
+    B.op_set_winograd_chunk_bytes(chunk_bytes)
+    try:
+        nf = B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1)
+        nb = B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1)
+        # the transformed filter alone is 16/9 of W: the Winograd workspace, not the packed-weight one
+        assert nf > 16 * wt.size * 4 // 9 and nb > 16 * wt.size * 4 // 9
+        for relu in (False, True):
+            y = torch.full(ref_y.shape, float("nan"), device="cuda")
+            B.op_conv_fwd(dev(x), dev(wt), y, 1, 1, relu, ws=_ws(nf))
+            assert rel_err(host(y), np.maximum(ref_y, 0) if relu else ref_y) < TOL
+        dx = torch.full(x.shape, float("nan"), device="cuda")
+        B.op_conv_bwd_data(dev(dy), dev(wt), dx, 1, 1, ws=_ws(nb))
+        assert rel_err(host(dx), ref_dx) < TOL
+        dx.fill_(float("nan"))
+        B.op_conv_bwd_data(dev(dy), dev(wt), dx, 1, 1, ws=_ws(nb), relu_mask=dev(xr))
+        assert rel_err(host(dx), L.relu_bwd(xr, ref_dx)) < TOL
+        return nf, nb
+    finally:
+        B.op_set_winograd_chunk_bytes(0)
+
+
+@pytest.mark.parametrize("shape", WINO_SHAPES)
+def test_conv_winograd(B, shape):
+    _wino_case(B, shape)
+
+
+def test_conv_winograd_in_chunks(B):
+    """A chunk size that holds two images of five (chunks of 2, 2 and 1) and one that holds a single image."""
+    shape = (5, 256, 8, 8, 512)
+    per_image = 16 * (256 + 512) * 16 * 4
+    whole, _ = _wino_case(B, shape)
+    two, _ = _wino_case(B, shape, chunk_bytes=2 * per_image + 100)
+    one, _ = _wino_case(B, shape, chunk_bytes=per_image // 2)   # smaller than one image: still one image per chunk
+    assert whole - two == 3 * per_image and two - one == per_image
+
+
+def test_conv_workspace_levels(B):
+    """With room for the packed weights only, a Winograd-sized layer runs the packed-weight kernel; with less, the
+    no-workspace kernel: all three agree with the oracle."""
+    import torch
+    n, c, h, w, k = 2, 256, 8, 8, 512
+    x, wt = _t((n, c, h, w), 71), _t((k, c, 3, 3), 72)
+    ref = L.conv_fwd(x, wt, 1, 1)
+    full = B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1)
+    outs = []
+    assert full > 9 << 20  # 8.4 MB of transformed filter + 0.8 MB per image
+    for nbytes in (full, 8 << 20, 1024):  # 8 MiB: room for the packed weights (4.7 MB) and the split tiles' partial sums (2 MB)
+        y = torch.full(ref.shape, float("nan"), device="cuda")
+        B.op_conv_fwd(dev(x), dev(wt), y, 1, 1, False, ws=_ws(nbytes))
+        assert rel_err(host(y), ref) < TOL
+        outs.append(host(y))
+    assert not np.array_equal(outs[0], outs[1])  # different algorithms, different rounding

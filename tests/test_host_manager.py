@@ -474,3 +474,35 @@ def test_random_graphs_all_policies_match_oracle(seed):
         else:
             assert "placement" in n.last_error()
         n.close()
+
+
+def test_winograd_workspace_follows_the_budget(monkeypatch):
+    """Wide 3x3 layers are sized for the Winograd algorithm where that workspace fits at that point of the step, for the
+    direct kernel elsewhere, and never with vdnn_set_winograd(net, 0): layer counts, peaks and op traces (which
+    carry every workspace size) equal the oracle's, also under another chunk size."""
+    net = nets.vgg16(256)
+    none_peak = ms.simulate(net, "none", 1 << 60)["peak_bytes"]
+    counts = {}
+    for chunk in (0, 64 << 20):
+        binding.op_set_winograd_chunk_bytes(chunk)
+        monkeypatch.setattr(ms, "WINOGRAD_CHUNK_BYTES", chunk or (512 << 20))
+        try:
+            for pol, budget in (("none", 0), ("none", none_peak - (256 << 20)), ("conv", 12 * G), ("all", 12 * G), ("all", 11 * G)):
+                for on in (True, False):
+                    ref = ms.simulate(net, pol, budget or (1 << 60), winograd=on)
+                    n = binding.Net(net, budget)
+                    n.set_winograd(on)
+                    s = n.try_policy(pol)
+                    assert (s == binding.OK) == (ref["status"] == "ok"), (pol, budget, on)
+                    if s == binding.OK:
+                        st = n.stats()
+                        assert st["n_winograd_convs"] == ref["n_winograd_convs"] and st["peak_bytes"] == ref["peak_bytes"]
+                        assert st["workspace_bytes"] == max(t[3] for t in ref["trace"] if t[1] == "alloc" and t[2] == "WS")
+                        assert [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
+                        counts[chunk, pol, budget, on] = st["n_winograd_convs"]
+                    n.close()
+        finally:
+            binding.op_set_winograd_chunk_bytes(0)
+    assert counts[0, "none", 0, True] == 6 and counts[0, "none", 0, False] == 0      # c4_1 ... c5_3
+    assert 0 < counts[0, "none", none_peak - (256 << 20), True] < 6                    # some layers fall back to the direct kernel
+    assert counts[64 << 20, "none", 0, True] == 6
