@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 GIB = 1 << 30
 FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs summarised in profiles/conv_fwd_vgg16_c4_2_b256.txt, each scaled by what the same counter reads
-# for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 0.832e9.
+# runs summarised in profiles/conv_fwd_vgg16_c2_2_b256.txt, each scaled by what the same counter reads
+# for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 3.289e9.
 ROOFLINE_TRAFFIC_BYTES = 2.559e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 
@@ -116,11 +116,12 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
 
 
 def roofline(B, batch):
-    """Dominant kernel: the 128x128 implicit-GEMM convolution tile kernel, on the most common VGG-16
-    shape (c4_2 / c4_3 forward: 256 x 512 x 28 x 28 -> 512 channels, 947 GFLOP per launch)."""
-    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c4_2",), iters=20, ramp_ms=300)[0]
+    """Dominant kernel: the 128x128 implicit-GEMM convolution tile kernel (direct convolutions and the grouped GEMMs
+    of the Winograd layers), timed on the largest layer that runs it as a direct convolution in the step
+    (c2_2 forward: 256 x 128 x 112 x 112 -> 128 channels, 947 GFLOP per launch)."""
+    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c2_2",), iters=20, ramp_ms=300)[0]
     ach = row["fwd_tflops"]
-    return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 c4_2 b%d" % batch, achieved=ach,
+    return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 c2_2 b%d" % batch, achieved=ach,
                 peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=ROOFLINE_TRAFFIC_BYTES,
                 flop_per_launch=row["gflop"] * 1e9, ms_per_launch=row["fwd_ms"])
 

@@ -205,9 +205,10 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
 
 // -------------------------------------------------------------------------------------------
 // Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, even H and W, reduction channels a multiple
-// of 16, rows a multiple of 4, and reduction channels x rows at least 256 x 512: measured on VGG-16 (256) the direct
-// kernel's 137 TFLOP/s become 196 at 512 x 512 channels (28 x 28), 182 (14 x 14), 163-170 at 256 x 512, and nothing
-// is gained at 256 x 256 and below, where the transforms' HBM traffic costs what the saved multiplications gain.
+// of 16 and at least 256, rows a multiple of 4 and at least 256: measured on VGG-16 (256), in TFLOP/s of the direct
+// form's operation count, the direct kernel's 137 become 221 at 512 x 512 channels (28 x 28), 204 (14 x 14), 187 at
+// 256 x 512 and 157 at 256 x 256 (56 x 56); with 128 channels on either side the transforms' HBM traffic costs more
+// than the saved multiplications gain (123-125 against 135).
 // Workspace: U, then V and Mt for `nb` images, nb the largest count that keeps V + Mt within the chunk size.
 // -------------------------------------------------------------------------------------------
 static size_t g_wino_chunk_bytes = (size_t)512 << 20;
@@ -216,7 +217,7 @@ void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? 
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
-           (long long)cred * rows >= 256LL * 512 && N >= 1;
+           (long long)cred * rows >= 256LL * 256 && N >= 1;
 }
 
 static int wino_chunk(int N, int cred, int H, int W, int rows) {

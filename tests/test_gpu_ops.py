@@ -333,7 +333,7 @@ def test_conv_random_shapes(B, shape):
         assert rel_err(host(dw), ref_dw) < TOL
 
 
-# ---- Winograd F(2x2,3x3): layers wide enough for the library to choose it (reduction channels x rows >= 256 x 512) ----
+# ---- Winograd F(2x2,3x3): layers wide enough for the library to choose it (256 or more channels on both sides) ----
 WINO_SHAPES = [
     # N, C, H, W, K
     (2, 256, 8, 8, 512),     # forward: 256 -> 512; backward-data: 512 -> 256
