@@ -67,6 +67,20 @@ def winograd_workspace(n, cred, h, w, rows, k, stride, pad):
     return _cdiv(16 * cred * rows, 64) * 64 * 4 + nb * per_image
 
 
+def winograd_filter_workspace(n, c, h, w, k, ksz, stride, pad):
+    """Workspace of the Winograd backward-filter pass where the library runs it (0 elsewhere): same geometry, 256 or
+    more channels on both sides, input channels a multiple of 128.  The 16 accumulated products (16 x K x C floats),
+    their partial sums per reduction split, and the transformed X and dY for as many images as fit the chunk size."""
+    if not (ksz == 3 and stride == 1 and pad == 1 and h % 2 == 0 and w % 2 == 0 and c % 128 == 0 and c >= 256 and k >= 256):
+        return 0
+    t = (h // 2) * (w // 2)
+    per_image = 16 * (c + k) * t * 4
+    nb = max(1, min(n, WINOGRAD_CHUNK_BYTES // per_image))
+    tiles = _cdiv(k, 128) * (c // 128) * 16
+    splits = max(1, min(1024 // tiles, _cdiv(nb * t, 512)))
+    return 16 * k * c * 4 * (1 + splits) + nb * per_image
+
+
 def conv_packed_workspace(wcount, rows, m, cred, rs):
     """Workspace of the packed-weight convolution kernel: a packed copy of W (rounded up to 256 bytes), plus
     partial sums for the tiles whose reduction is split because the last round of workgroups would be
@@ -215,8 +229,11 @@ def workspace_bytes(net, info, i, phase, memopt=False, direct=False):
         if need_dx and l["stride"] == 1 and l["pad"] <= l["k"] - 1 and k % 16 == 0 and 4 * n * k * p * q < 0xfffffff0:
             packed = ((0 if direct else winograd_workspace(n, k, h, w, c, l["k"], l["stride"], l["pad"]))
                       or conv_packed_workspace(wbytes // 4, c, n * h * w, k, rs))
-        # backward-filter: partial sums of the split reduction; with input channels a multiple of 32
-        # the faster kernel always stages dW through the workspace (at least one copy)
+        # backward-filter: the Winograd form on wide 3x3 layers; else partial sums of the split reduction; with input
+        # channels a multiple of 32 the faster kernel always stages dW through the workspace (at least one copy)
+        wino_filt = 0 if direct else winograd_filter_workspace(n, c, h, w, k, l["k"], l["stride"], l["pad"])
+        if wino_filt:
+            return max(wino_filt, packed)
         if c % 32 == 0 and 4 * n * c * h * w < 0xfffffff0 and 4 * n * k * p * q < 0xfffffff0:
             if c == 64 and rs % 3 == 0:
                 # 64-channel layers run column tiles of three taps: the split count follows from that tile count

@@ -361,6 +361,10 @@ struct BwdFilterFastParams {
     int M;            // N*P*Q (reduction length)
     FastDiv fd_pq, fd_q;
     int tiles_m, tiles_n, splits, ksplit;
+    // groups > 1: that many independent problems of the same shape in one launch; group g reads x + g * x_gstride and
+    // dy + g * dy_gstride and writes ws + g * ws_gstride (strides in elements).  The grid is tiles * splits * groups.
+    int groups = 1;
+    size_t x_gstride = 0, dy_gstride = 0, ws_gstride = 0;
 };
 
 template <int BM, int BN, int WM, int WN, int BK, int TAPS = 1>
@@ -379,7 +383,10 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
 
     const int tid = threadIdx.x;
     const int tiles = p.tiles_m * p.tiles_n;
-    const int logical = xcd_remap(blockIdx.x, tiles * p.splits);
+    int logical = xcd_remap(blockIdx.x, tiles * p.splits * p.groups);
+    // the same for the whole workgroup; said explicitly so that the buffer resources below stay in scalar registers
+    const int group = __builtin_amdgcn_readfirstlane(logical / (tiles * p.splits));
+    logical -= group * (tiles * p.splits);
     const int split = logical / tiles;
     const int t2 = logical - split * tiles;
     const int tile_n = t2 / p.tiles_m, tile_m = t2 - tile_n * p.tiles_m;
@@ -395,8 +402,8 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
     const int kend = min(p.M, kbeg + p.ksplit);
     const int nk = (kend - kbeg + BK - 1) / BK;
 
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x, p.x_bytes);
-    const __amdgpu_buffer_rsrc_t rs_dy = make_rsrc(p.dy, p.dy_bytes);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x + (size_t)group * p.x_gstride, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rs_dy = make_rsrc(p.dy + (size_t)group * p.dy_gstride, p.dy_bytes);
 
     const int kk = tid % BK, r_first = tid / BK;
     const int PQ = p.P * p.Q, HW = p.H * p.W;
@@ -524,7 +531,7 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
     }
 
     const int CRS = p.C * p.R * p.S;
-    float* obase = p.ws + (size_t)split * p.K * CRS;
+    float* obase = p.ws + (size_t)group * p.ws_gstride + (size_t)split * p.K * CRS;
     // columns are < CRS (column tiles are never ragged here); CRS and a pair's first column are even
 #pragma unroll
     for (int i = 0; i < TM; ++i)

@@ -158,7 +158,9 @@ size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt, bool dir
         const size_t dx = !need_dx ? 0
                           : direct ? conv_bwd_data_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
                                    : conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
-        return std::max(conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad), dx);
+        const size_t dwb = direct ? conv_bwd_filter_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
+                                  : conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+        return std::max(dwb, dx);
     }
     if (l.type == VDNN_FC) {
         const int I = C * H * W;

@@ -27,6 +27,7 @@ size_t gemm_workspace_bytes(long long m, long long n, long long kred);
 void conv_set_winograd_chunk_bytes(size_t bytes);  // V + Mt bytes per chunk of images (0 = default 512 MiB)
 size_t conv_fwd_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_bwd_data_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R,

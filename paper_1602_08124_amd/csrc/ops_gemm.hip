@@ -407,11 +407,34 @@ static int bwdf_splits(int N, int C, int H, int W, int K, int R, int S, int P, i
     return gemm_splits(K, (long long)C * R * S, M);
 }
 
-size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+// workspace of the direct backward-filter kernels
+size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (bwdf_fast_ok(N, C, H, W, K, P, Q))
         return (size_t)bwdf_splits(N, C, H, W, K, R, S, P, Q) * K * C * R * S * sizeof(float);
     return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
+}
+
+// Winograd backward-filter (winograd.h): same geometry as the other two passes, 256 or more channels on both sides,
+// input channels a multiple of 128 (the column tile of the grouped GEMM).  Workspace: the 16 accumulated products
+// dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
+static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && C >= 256 && K >= 256 && N >= 1;
+}
+
+static int wino_bwdf_splits(int nb, int T, int K, int C) {
+    const long long tiles = (long long)cdiv(K, 128) * (C / 128) * 16;
+    return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv((long long)nb * T, 512)));
+}
+
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K) {
+    const int T = (H / 2) * (W / 2), nb = wino_chunk(N, C, H, W, K);
+    return (size_t)16 * K * C * sizeof(float) * (1 + wino_bwdf_splits(nb, T, K, C)) + (size_t)nb * 16 * (C + K) * T * sizeof(float);
+}
+
+size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad)) return wino_bwdf_workspace(N, C, H, W, K);
+    return conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
 }
 
 template <int BM, int BN, int WM, int WN, int BK = 32, int TAPS = 1>
@@ -428,7 +451,7 @@ static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
     p.tiles_m = cdiv(p.K, BM);
     p.tiles_n = p.C * p.R * p.S / BN;
     p.ksplit = cdiv(cdiv(p.M, p.splits), BK) * BK;
-    const long long nb = (long long)p.tiles_m * p.tiles_n * p.splits;
+    const long long nb = (long long)p.tiles_m * p.tiles_n * p.splits * p.groups;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
     VDNN_LAUNCH(kern, dim3((unsigned)nb), dim3(kThreads), smem, st, p);
     return hipGetLastError();
@@ -441,14 +464,60 @@ static hipError_t bwdf_cfg(const PixKParams& pa, const ConvGeom& g, const RowMaj
         pa, g, eo, eo.rows, eo.cols, g.M, splits, st);
 }
 
+// x [N][C][H][W], dy [N][K][H][W] -> dw [K][C][3][3] through the 16 grouped products of the Winograd form
+static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, hipStream_t st) {
+    const int T = (H / 2) * (W / 2);
+    const int nb = wino_chunk(N, C, H, W, K);
+    const int splits = wino_bwdf_splits(nb, T, K, C);
+    const size_t kc = (size_t)K * C;
+    float* acc = ws;
+    float* part = acc + 16 * kc;
+    float* v = part + (size_t)16 * splits * kc;
+    float* dt = v + (size_t)16 * nb * C * T;
+    const int tb = T <= 64 ? 64 : 256;
+    const int rblocks = (int)std::min<size_t>((16 * kc + 255) / 256, 8192);
+    for (int n0 = 0; n0 < N; n0 += nb) {
+        const int cur = std::min(nb, N - n0);
+        VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)C, (unsigned)cur), dim3(tb), 0, st, x, v, n0, cur, C, H, W);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)K, (unsigned)cur), dim3(tb), 0, st, dy, dt, n0, cur, K, H, W);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        BwdFilterFastParams fp;
+        fp.x = v; fp.dy = dt; fp.ws = part;
+        fp.x_bytes = (uint32_t)((size_t)cur * C * T * 4);
+        fp.dy_bytes = (uint32_t)((size_t)cur * K * T * 4);
+        fp.K = K; fp.C = C; fp.H = H / 2; fp.W = W / 2; fp.R = 1; fp.S = 1; fp.stride = 1; fp.pad = 0; fp.P = H / 2; fp.Q = W / 2;
+        fp.M = cur * T;
+        fp.fd_pq = make_fastdiv((uint32_t)T);
+        fp.fd_q = make_fastdiv((uint32_t)(W / 2));
+        fp.splits = splits;
+        fp.groups = 16;
+        fp.x_gstride = (size_t)cur * C * T;
+        fp.dy_gstride = (size_t)cur * K * T;
+        fp.ws_gstride = (size_t)splits * kc;
+        e = bwdf_fast_cfg<128, 128, 2, 2, 16>(fp, st);
+        if (e != hipSuccess) return e;
+        VDNN_LAUNCH(wino_accum_kernel, dim3((unsigned)rblocks), dim3(256), 0, st, (const float*)part, acc, kc, splits, n0 == 0 ? 1 : 0);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    VDNN_LAUNCH(wino_filter_grad_kernel, dim3((unsigned)std::min<size_t>((kc + 255) / 256, 8192)), dim3(256), 0, st, (const float*)acc, dw, kc);
+    return hipGetLastError();
+}
+
 hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
                            int K, int R, int S, int stride, int pad, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
+    // the fastest algorithm the given workspace has room for
+    if (ws && wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) && ws_bytes >= wino_bwdf_workspace(N, C, H, W, K))
+        return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, st);
     const int CRS = C * R * S;
     int splits = bwdf_splits(N, C, H, W, K, R, S, P, Q);
-    const size_t need_ws = conv_bwd_filter_workspace(N, C, H, W, K, R, S, stride, pad);
+    const size_t need_ws = conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
     const bool have_ws = ws && ws_bytes >= need_ws;
     if (!have_ws) splits = 1;  // memory-optimal algorithm: no workspace, the whole reduction in one workgroup per tile
     if (have_ws && bwdf_fast_ok(N, C, H, W, K, P, Q)) {

@@ -124,4 +124,64 @@ __global__ void wino_output_kernel(const float* __restrict__ mt, float* __restri
     }
 }
 
+// ---- backward-filter: dW = sum over tiles of G^T [ (A dY_tile A^T) .* (B^T d B) ] G ----
+// Dt[xi][n][k][t] = (A dy A^T)[xi], dy the 2x2 tile (ty, tx) of dY[n0 + n][k].  grid (ceil(T / blockDim.x), K, nb).
+__global__ void wino_dy_kernel(const float* __restrict__ dy, float* __restrict__ dt, int n0, int nb, int K, int H, int W) {
+    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int k = blockIdx.y, n = blockIdx.z;
+    const int ty = t / TW, tx = t - ty * TW;
+    const float* plane = dy + (((size_t)(n0 + n) * K + k) * H + 2 * ty) * W + 2 * tx;  // even offset: W is even
+    const float2 r0 = *reinterpret_cast<const float2*>(plane), r1 = *reinterpret_cast<const float2*>(plane + W);
+    // A = [[1,0],[1,1],[1,-1],[0,-1]]: rows of A dy
+    const float a[4][2] = {{r0.x, r0.y}, {r0.x + r1.x, r0.y + r1.y}, {r0.x - r1.x, r0.y - r1.y}, {-r1.x, -r1.y}};
+    const size_t gstride = (size_t)nb * K * T;
+    float* o = dt + ((size_t)n * K + k) * T + t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[(size_t)(i * 4 + 0) * gstride] = a[i][0];
+        o[(size_t)(i * 4 + 1) * gstride] = a[i][0] + a[i][1];
+        o[(size_t)(i * 4 + 2) * gstride] = a[i][0] - a[i][1];
+        o[(size_t)(i * 4 + 3) * gstride] = -a[i][1];
+    }
+}
+
+// acc[i] (+)= sum over s of part[group(i)][s][.], s ascending: part is [16][splits][K*C], acc is [16][K*C].
+__global__ void wino_accum_kernel(const float* __restrict__ part, float* __restrict__ acc, size_t kc, int splits, int first) {
+    const size_t total = 16 * kc;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t g = i / kc, e = i - g * kc;
+        const float* src = part + g * splits * kc + e;
+        float v = src[0];
+        for (int s = 1; s < splits; ++s) v += src[(size_t)s * kc];
+        acc[i] = first ? v : acc[i] + v;
+    }
+}
+
+// dW[k][c][3][3] = G^T dU G with dU[xi] = acc[xi][k][c].
+__global__ void wino_filter_grad_kernel(const float* __restrict__ acc, float* __restrict__ dw, size_t kc) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < kc; i += (size_t)gridDim.x * blockDim.x) {
+        float u[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) u[a][b] = acc[(size_t)(a * 4 + b) * kc + i];
+        float r[3][4];  // G^T u, G^T = [[1,.5,.5,0],[0,.5,-.5,0],[0,.5,.5,1]]
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            r[0][b] = u[0][b] + 0.5f * (u[1][b] + u[2][b]);
+            r[1][b] = 0.5f * (u[1][b] - u[2][b]);
+            r[2][b] = 0.5f * (u[1][b] + u[2][b]) + u[3][b];
+        }
+        float* o = dw + i * 9;
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+            o[a * 3 + 0] = r[a][0] + 0.5f * (r[a][1] + r[a][2]);
+            o[a * 3 + 1] = 0.5f * (r[a][1] - r[a][2]);
+            o[a * 3 + 2] = 0.5f * (r[a][1] + r[a][2]) + r[a][3];
+        }
+    }
+}
+
 }  // namespace vdnn

@@ -179,9 +179,10 @@ def test_vgg16_b256_winograd_plans(B):
         seen.append(st["n_winograd_convs"])
         assert abs(loss - base_loss) < 1e-5 * abs(base_loss), pol
         for i in weights:
-            # below the classifier the flipped decisions dominate, as against the fp64 oracle at this size
-            # (test_vgg16_b256_step_against_the_oracle_at_full_size): same bounds
-            assert rel_err(dw[i], base_dw[i]) < (TOL if net["layers"][i]["type"] == "fc" else 3e-3), (pol, i)
+            # the flipped decisions dominate, as against the fp64 oracle at this size
+            # (test_vgg16_b256_step_against_the_oracle_at_full_size): same bound.  Every element is compared here, so the
+            # classifier's gradients show their few flipped ReLUs too (the oracle test samples 400 entries per tensor).
+            assert rel_err(dw[i], base_dw[i]) < 3e-3, (pol, i)
     assert seen[0] == 8 and seen[1] > 0   # c3_2 ... c5_3 without a budget
 
 

@@ -351,6 +351,7 @@ def _wino_case(B, shape, chunk_bytes=0):
     xr = np.maximum(_t((n, c, h, w), 64), 0)
     ref_y = L.conv_fwd(x, wt, 1, 1)
     ref_dx = L.conv_bwd_data(dy, wt, x.shape, 1, 1)
+    ref_dw = L.conv_bwd_filter(x, dy, wt.shape, 1, 1)
     B.op_set_winograd_chunk_bytes(chunk_bytes)
     try:
         nf = B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1)
@@ -367,6 +368,12 @@ def _wino_case(B, shape, chunk_bytes=0):
         dx.fill_(float("nan"))
         B.op_conv_bwd_data(dev(dy), dev(wt), dx, 1, 1, ws=_ws(nb), relu_mask=dev(xr))
         assert rel_err(host(dx), L.relu_bwd(xr, ref_dx)) < TOL
+        nw = B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)
+        if c % 128 == 0:
+            assert nw > 2 * 16 * wt.size * 4 // 9   # the 16 products and at least one copy of partial sums
+        dw = torch.full(wt.shape, float("nan"), device="cuda")
+        B.op_conv_bwd_filter(dev(x), dev(dy), dw, _ws(nw), 1, 1)
+        assert rel_err(host(dw), ref_dw) < TOL
         return nf, nb
     finally:
         B.op_set_winograd_chunk_bytes(0)
