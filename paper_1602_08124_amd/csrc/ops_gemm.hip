@@ -205,10 +205,10 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
 
 // -------------------------------------------------------------------------------------------
 // Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, even H and W, reduction channels a multiple
-// of 16 and at least 256, rows a multiple of 4 and at least 256: measured on VGG-16 (256), in TFLOP/s of the direct
-// form's operation count, the direct kernel's 137 become 221 at 512 x 512 channels (28 x 28), 204 (14 x 14), 187 at
-// 256 x 512 and 157 at 256 x 256 (56 x 56); with 128 channels on either side the transforms' HBM traffic costs more
-// than the saved multiplications gain (123-125 against 135).
+// of 16 and at least 256, rows a multiple of 4 and at least 128: measured on VGG-16 (256), in TFLOP/s of the direct
+// form's operation count, the direct kernel's 137 become 234 at 512 x 512 channels (28 x 28), 208 (14 x 14), 196-205 at
+// 256 x 512, 176-180 at 256 x 256 (56 x 56) and 153 at 256 -> 128; with 128 reduction channels the transforms' HBM
+// traffic costs what the saved multiplications gain (131 against 136).
 // Workspace: U, then V and Mt for `nb` images, nb the largest count that keeps V + Mt within the chunk size.
 // -------------------------------------------------------------------------------------------
 static size_t g_wino_chunk_bytes = (size_t)512 << 20;
@@ -217,12 +217,25 @@ void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? 
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
-           (long long)cred * rows >= 256LL * 256 && N >= 1;
+           rows >= 128 && N >= 1;
 }
 
 static int wino_chunk(int N, int cred, int H, int W, int rows) {
     const size_t per_image = (size_t)16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
     return (int)std::max<size_t>(1, std::min<size_t>((size_t)N, g_wino_chunk_bytes / per_image));
+}
+
+// V for images [n0, n0 + cur) of src
+static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cred, int H, int W, hipStream_t st) {
+    const int T = (H / 2) * (W / 2);
+    if (H * W <= kWinoPlaneMax && cur <= 65535) {
+        const int tb = T <= 64 ? 64 : 256;
+        VDNN_LAUNCH(wino_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(tb), sizeof(float) * (H + 2) * (W + 2), st, src, v, n0, cur, cred, H, W);
+    } else {
+        const int tb = T <= 64 ? 64 : 256;
+        VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
+    }
+    return hipGetLastError();
 }
 
 static size_t wino_workspace(int N, int cred, int H, int W, int rows) {
@@ -245,8 +258,7 @@ static hipError_t conv_winograd(const float* src, const float* w, float* ws, flo
     const int tb = T <= 64 ? 64 : 256;
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
-        VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
-        e = hipGetLastError();
+        e = wino_input(src, v, n0, cur, cred, H, W, st);
         if (e != hipSuccess) return e;
         ConvFastParams p;
         p.src = v; p.wp = u;
@@ -415,11 +427,11 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
     return gemm_workspace_bytes(K, (long long)C * R * S, (long long)N * P * Q);
 }
 
-// Winograd backward-filter (winograd.h): same geometry as the other two passes, 256 or more channels on both sides,
-// input channels a multiple of 128 (the column tile of the grouped GEMM).  Workspace: the 16 accumulated products
+// Winograd backward-filter (winograd.h): same geometry as the other two passes, input channels a multiple of 128 (the
+// column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 140 against 131 TFLOP/s).  Workspace: the 16 accumulated products
 // dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && C >= 256 && K >= 256 && N >= 1;
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && K >= 256 && N >= 1;
 }
 
 static int wino_bwdf_splits(int nb, int T, int K, int C) {
@@ -478,8 +490,7 @@ static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw,
     const int rblocks = (int)std::min<size_t>((16 * kc + 255) / 256, 8192);
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
-        VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)C, (unsigned)cur), dim3(tb), 0, st, x, v, n0, cur, C, H, W);
-        hipError_t e = hipGetLastError();
+        hipError_t e = wino_input(x, v, n0, cur, C, H, W, st);
         if (e != hipSuccess) return e;
         VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)K, (unsigned)cur), dim3(tb), 0, st, dy, dt, n0, cur, K, H, W);
         e = hipGetLastError();

@@ -86,6 +86,48 @@ __global__ void wino_input_kernel(const float* __restrict__ src, float* __restri
     }
 }
 
+// The same transform for planes of at most kWinoPlaneMax pixels: one workgroup per (c, n) plane stages the plane with
+// its zero border in LDS (each input element read from memory once, coalesced) and its threads walk over the tiles.
+// grid (Cred, nb); dynamic LDS (H + 2) * (W + 2) floats.
+constexpr int kWinoPlaneMax = 4096;
+__global__ void wino_input_plane_kernel(const float* __restrict__ src, float* __restrict__ v, int n0, int nb, int C, int H, int W) {
+    extern __shared__ __align__(16) float plane[];
+    const int c = blockIdx.x, n = blockIdx.y;
+    const int PW = W + 2, TW = W >> 1, T = (H >> 1) * TW;
+    const float* g = src + ((size_t)(n0 + n) * C + c) * H * W;
+    for (int i = threadIdx.x; i < PW; i += blockDim.x) plane[i] = 0.f, plane[(H + 1) * PW + i] = 0.f;
+    for (int i = threadIdx.x; i < H; i += blockDim.x) plane[(i + 1) * PW] = 0.f, plane[(i + 1) * PW + W + 1] = 0.f;
+    for (int i = threadIdx.x; i < (H * W) >> 1; i += blockDim.x) {  // W is even: pairs never straddle rows
+        const float2 e = reinterpret_cast<const float2*>(g)[i];
+        const int h = (2 * i) / W, w = 2 * i - h * W;
+        plane[(h + 1) * PW + w + 1] = e.x;
+        plane[(h + 1) * PW + w + 2] = e.y;
+    }
+    __syncthreads();
+    const size_t gstride = (size_t)nb * C * T;
+    for (int t = threadIdx.x; t < T; t += blockDim.x) {
+        const int ty = t / TW, tx = t - ty * TW;
+        const float* p0 = plane + 2 * ty * PW + 2 * tx;
+        float r[4][4];  // B^T d
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float d0 = p0[j], d1 = p0[PW + j], d2 = p0[2 * PW + j], d3 = p0[3 * PW + j];
+            r[0][j] = d0 - d2;
+            r[1][j] = d1 + d2;
+            r[2][j] = d2 - d1;
+            r[3][j] = d1 - d3;
+        }
+        float* o = v + ((size_t)n * C + c) * T + t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[(size_t)(i * 4 + 0) * gstride] = r[i][0] - r[i][2];
+            o[(size_t)(i * 4 + 1) * gstride] = r[i][1] + r[i][2];
+            o[(size_t)(i * 4 + 2) * gstride] = r[i][2] - r[i][1];
+            o[(size_t)(i * 4 + 3) * gstride] = r[i][1] - r[i][3];
+        }
+    }
+}
+
 // out[n0 + n][row][2ty + i][2tx + j] = (A^T m A)[i][j], m[xi] = Mt[xi][n][row][t]; optional ReLU on the value
 // (forward) or zeroing where mask is not positive (backward-data with the preceding in-place ReLU folded in).
 // grid (ceil(T / blockDim.x), rows, nb).
