@@ -27,7 +27,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs summarised in profiles/conv_fwd_vgg16_c2_2_b256.txt, each scaled by what the same counter reads
 # for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 3.289e9.
-ROOFLINE_TRAFFIC_BYTES = 2.559e9
+ROOFLINE_TRAFFIC_BYTES = 3.580e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 
 
