@@ -29,6 +29,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 3.289e9.
 ROOFLINE_TRAFFIC_BYTES = 3.580e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
+WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
 
 
 def conv_layers_vgg16(batch):
@@ -160,6 +161,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
     or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille."""
     import torch
     n = B.Net(net, budget)
+    n.set_winograd(WINOGRAD)
     if window_part_mib is not None:
         n.set_window_part(int(window_part_mib * (1 << 20)))
     if policy.startswith("set:"):
@@ -243,8 +245,11 @@ def main():
     ap.add_argument("--kernel-table", action="store_true", help="also time every VGG-16 convolution, three passes each")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true", help="skip the roofline kernel (for a profile of the steps alone)")
+    ap.add_argument("--no-winograd", action="store_true", help="keep every plan on the direct convolution kernels (side measurement)")
     ap.add_argument("--cpu-sample-batch", type=int, default=1)
     args = ap.parse_args()
+    global WINOGRAD
+    WINOGRAD = not args.no_winograd
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the vDNN step is a single-GPU method); use --gpus 1", file=sys.stderr)
         sys.exit(2)

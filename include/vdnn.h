@@ -53,7 +53,7 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
 /* Two kernels stand behind "performance-optimal": the packed-weight direct kernel everywhere, and on wide 3x3 layers
  * (see vdnn_op_conv_fwd_workspace) the Winograd algorithm, which is faster and wants far more workspace.  A plan
  * gives a layer the Winograd workspace where it fits the budget at that point of the step (always, without a
- * budget) and the direct kernel's elsewhere; with an explicit offload set (FIT, vdnn_set_offload_set) the forward
+ * budget) and the direct kernel's elsewhere; with an explicit, non-empty offload set (FIT, vdnn_set_offload_set) the forward
  * pass keeps the direct kernel, since it runs at the pace of the offloads.  Plans under different budgets may
  * therefore differ in rounding; vdnn_set_winograd(net, 0) keeps every plan of the net on the direct kernel. */
 

@@ -291,9 +291,9 @@ def simulate(net, policy, budget, algo="p", offload_set=None, winograd=True):
             return 0
         ws = workspace_bytes(net, info, i, phase)
         direct = workspace_bytes(net, info, i, phase, direct=True) if conv else ws
-        if conv and ws and (not winograd or (offload_set is not None and phase == "fwd") or pool.live + _al(ws) > pool.budget):
+        if conv and ws and (not winograd or (offload_set and phase == "fwd") or pool.live + _al(ws) > pool.budget):
             # the Winograd algorithm runs where its workspace fits at this point; elsewhere the direct kernel stays;
-            # with an explicit offload set the forward pass keeps the direct kernel everywhere
+            # with an explicit, non-empty offload set the forward pass keeps the direct kernel everywhere
             ws = direct
         if conv and ws > direct:
             wino.add(i)

@@ -213,6 +213,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
     p.memopt_fwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
     p.memopt_bwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
     std::vector<char> wino(n.layers.size(), 0);  // CONV layers given the Winograd workspace in either pass
+    const bool set_offloads = offload_set && std::find(offload_set->begin(), offload_set->end(), (char)1) != offload_set->end();
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     Compiler c(n, p, budget);
     const int L = (int)n.layers.size();
@@ -258,9 +259,9 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); p.blocks[res[i + 1]].buf = i; }
         size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
         // The Winograd algorithm runs where its workspace fits at this point; elsewhere the layer keeps the direct kernel.
-        // With an explicit offload set the forward pass keeps the direct kernel everywhere: it runs at the pace of the
+        // With an explicit, non-empty offload set the forward pass keeps the direct kernel everywhere: it runs at the pace of the
         // offloads, which wait in memory for their copies, and a large workspace would only force them out earlier.
-        if (ws && l.type == VDNN_CONV && (!n.winograd || offload_set || c.live + align_up(ws) > budget)) ws = layer_workspace(n, i, false, p.memopt_fwd[i], true);
+        if (ws && l.type == VDNN_CONV && (!n.winograd || set_offloads || c.live + align_up(ws) > budget)) ws = layer_workspace(n, i, false, p.memopt_fwd[i], true);
         if (l.type == VDNN_CONV && ws > layer_workspace(n, i, false, p.memopt_fwd[i], true)) wino[i] = 1;
         if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
         int wsb = -1;
