@@ -217,12 +217,12 @@ void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? 
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
-           rows >= 128 && N >= 1;
+           rows >= 128 && N >= 1 && cred <= 65535 && rows <= 65535;  // the transforms' grids carry channels and images in y and z
 }
 
 static int wino_chunk(int N, int cred, int H, int W, int rows) {
     const size_t per_image = (size_t)16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
-    return (int)std::max<size_t>(1, std::min<size_t>((size_t)N, g_wino_chunk_bytes / per_image));
+    return (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
 }
 
 // V for images [n0, n0 + cur) of src
@@ -431,7 +431,7 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
 // column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 140 against 131 TFLOP/s).  Workspace: the 16 accumulated products
 // dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && K >= 256 && N >= 1;
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535;
 }
 
 static int wino_bwdf_splits(int nb, int T, int K, int C) {

@@ -233,6 +233,7 @@ def test_trace_buffer_truncation_and_null_arguments():
     assert binding.lib.vdnn_mem_stats(n.h, None) == binding.ERR_INVALID_ARG
     assert binding.lib.vdnn_set_policy(n.h, 7) == binding.ERR_INVALID_ARG
     assert binding.lib.vdnn_set_conv_algo(n.h, 9) == binding.ERR_INVALID_ARG
+    assert binding.lib.vdnn_set_winograd(None, 1) == binding.ERR_INVALID_ARG and binding.lib.vdnn_set_winograd(n.h, 0) == binding.OK
     assert binding.lib.vdnn_set_weights(n.h, 1, None, 0) == binding.ERR_INVALID_ARG
     assert binding.lib.vdnn_weight_count(n.h, 99) == 0 and binding.lib.vdnn_weight_count(n.h, 0) == 16 * 3 * 9
     assert binding.lib.vdnn_output_count(n.h, 0) == 2 * 16 * 32 * 32
@@ -506,3 +507,31 @@ def test_winograd_workspace_follows_the_budget(monkeypatch):
     assert counts[0, "none", 0, True] == 9 and counts[0, "none", 0, False] == 0      # c3_1 (backward only) ... c5_3
     assert 0 < counts[0, "none", none_peak - (256 << 20), True] < 9                    # some layers fall back to the direct kernel
     assert counts[64 << 20, "none", 0, True] == 9
+
+
+def test_convolution_workspace_levels_by_shape():
+    """Which algorithm the workspace query sizes for (the sizes are the oracle's closed forms): Winograd needs 3x3,
+    stride 1, pad 1, even sides and wide layers; everything else gets the packed-weight kernel or nothing."""
+    def info_net(c, h, k, ksz, st, pd):
+        b = nets._Builder("one_conv", 4, c, h, h)
+        b.conv(k, ksz, st, pd)
+        b.fc(10, relu=False)
+        return b.done()
+    cases = [(256, 8, 128, 3, 1, 1, True), (256, 8, 124, 3, 1, 1, False), (240, 8, 256, 3, 1, 1, False), (256, 9, 256, 3, 1, 1, False),
+             (256, 8, 256, 3, 2, 1, False), (256, 8, 256, 3, 1, 0, False), (256, 8, 256, 5, 1, 2, False), (512, 14, 512, 3, 1, 1, True)]
+    for c, h, k, ksz, st, pd, wino in cases:
+        net = info_net(c, h, k, ksz, st, pd)
+        info = ms.analyse(net)
+        fwd = binding.op_conv_fwd_workspace((4, c, h, h), (k, c, ksz, ksz), st, pd)
+        assert fwd == ms.workspace_bytes(net, info, 0, "fwd"), (c, h, k, ksz, st, pd)
+        direct = ms.workspace_bytes(net, info, 0, "fwd", direct=True)
+        assert (fwd > direct) == wino, (c, h, k, ksz, st, pd)
+        p = (h + 2 * pd - ksz) // st + 1
+        if st == 1 and p == h:
+            # backward: the larger of the filter pass and the data pass, as a plan sizes it (the first layer needs no dX,
+            # so query the two passes one by one)
+            bd = binding.op_conv_bwd_data_workspace((4, c, h, h), (k, c, ksz, ksz), st, pd)
+            bf = binding.op_conv_bwd_filter_workspace((4, c, h, h), (k, c, ksz, ksz), st, pd)
+            assert bf == ms.workspace_bytes(net, info, 0, "bwd"), (c, h, k)
+            want = (ms.winograd_workspace(4, k, h, h, c, ksz, st, pd) or ms.conv_packed_workspace(k * c * ksz * ksz, c, 4 * h * h, k, ksz * ksz))
+            assert bd == (want if k % 16 == 0 else 0)   # the packed kernels need reduction channels in multiples of 16
