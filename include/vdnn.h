@@ -233,7 +233,7 @@ const char* vdnn_op_last_error(void);
  *  - no workspace: implicit GEMM whose gather works directly on W as stored (memory-optimal);
  *  - one packed copy of W (+ partial sums of split tiles): the faster implicit-GEMM kernel; applies when the reduction
  *    channels are a multiple of 16, backward-data is unstrided and the tensors are below 4 GiB;
- *  - Winograd F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers with even H and W, reduction channels a multiple of 16,
+ *  - Winograd F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers, reduction channels a multiple of 16,
  *    at least 256 of them, output channels of the pass a multiple of 4 and at least 128 (backward-filter: input
  *    channels a multiple of 128, 256 or more output channels): transformed
  *    filter (16/9 of W) plus transformed input and products for a chunk of images (at most the chunk size below).

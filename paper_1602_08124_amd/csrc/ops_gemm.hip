@@ -204,7 +204,7 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
 }
 
 // -------------------------------------------------------------------------------------------
-// Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, even H and W, reduction channels a multiple
+// Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, reduction channels a multiple
 // of 16 and at least 256, rows a multiple of 4 and at least 128: measured on VGG-16 (256), in TFLOP/s of the direct
 // form's operation count, the direct kernel's 137 become 234 at 512 x 512 channels (28 x 28), 208 (14 x 14), 196-205 at
 // 256 x 512, 176-180 at 256 x 256 (56 x 56) and 153 at 256 -> 128; with 128 reduction channels the transforms' HBM
@@ -216,21 +216,22 @@ static size_t g_wino_chunk_bytes = (size_t)512 << 20;
 void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? bytes : (size_t)512 << 20; }
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
            rows >= 128 && N >= 1 && cred <= 65535 && rows <= 65535;  // the transforms' grids carry channels and images in y and z
 }
 
 static int wino_chunk(int N, int cred, int H, int W, int rows) {
-    const size_t per_image = (size_t)16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
+    const size_t per_image = (size_t)16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
     return (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
 }
 
 // V for images [n0, n0 + cur) of src
 static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cred, int H, int W, hipStream_t st) {
-    const int T = (H / 2) * (W / 2);
+    const int T = ((H + 1) / 2) * ((W + 1) / 2);
     if (H * W <= kWinoPlaneMax && cur <= 65535) {
         const int tb = T <= 64 ? 64 : 256;
-        VDNN_LAUNCH(wino_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(tb), sizeof(float) * (H + 2) * (W + 2), st, src, v, n0, cur, cred, H, W);
+        VDNN_LAUNCH(wino_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(tb), sizeof(float) * (2 * ((H + 1) / 2) + 2) * (2 * ((W + 1) / 2) + 2), st,
+                    src, v, n0, cur, cred, H, W);
     } else {
         const int tb = T <= 64 ? 64 : 256;
         VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
@@ -240,13 +241,13 @@ static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cr
 
 static size_t wino_workspace(int N, int cred, int H, int W, int rows) {
     const size_t u = ((size_t)16 * cred * rows + 63) / 64 * 64 * sizeof(float);
-    return u + (size_t)wino_chunk(N, cred, H, W, rows) * 16 * (cred + rows) * (H / 2) * (W / 2) * sizeof(float);
+    return u + (size_t)wino_chunk(N, cred, H, W, rows) * 16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
 }
 
 // src [N][cred][H][W] -> out [N][rows][H][W]; w is the layer's KCRS filter; bwd selects which way it is applied.
 static hipError_t conv_winograd(const float* src, const float* w, float* ws, float* out, const float* mask, int relu, int N, int cred, int H,
                                 int W, int rows, int K, int C, int bwd, hipStream_t st) {
-    const int T = (H / 2) * (W / 2);
+    const int T = ((H + 1) / 2) * ((W + 1) / 2);
     const int nb = wino_chunk(N, cred, H, W, rows);
     float* u = ws;
     float* v = ws + ((size_t)16 * cred * rows + 63) / 64 * 64;
@@ -265,11 +266,11 @@ static hipError_t conv_winograd(const float* src, const float* w, float* ws, flo
         p.src_bytes = (uint32_t)((size_t)cur * cred * T * 4);
         p.wp_bytes = (uint32_t)((size_t)cred * rows * 4);
         p.rows = rows;
-        p.Cred = cred; p.H = H / 2; p.W = W / 2;
+        p.Cred = cred; p.H = (H + 1) / 2; p.W = (W + 1) / 2;
         p.R = 1; p.S = 1; p.stride = 1; p.pad = 0;
-        p.P = H / 2; p.Q = W / 2; p.M = cur * T;
+        p.P = (H + 1) / 2; p.Q = (W + 1) / 2; p.M = cur * T;
         p.fd_pq = make_fastdiv((uint32_t)T);
-        p.fd_q = make_fastdiv((uint32_t)(W / 2));
+        p.fd_q = make_fastdiv((uint32_t)((W + 1) / 2));
         ConvOut eo;
         eo.out = mt; eo.mask = nullptr; eo.rows = rows; eo.M = p.M; eo.PQ = T; eo.relu = 0; eo.fd_pq = p.fd_pq;
         p.out = eo;
@@ -431,7 +432,7 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
 // column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 140 against 131 TFLOP/s).  Workspace: the 16 accumulated products
 // dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && H % 2 == 0 && W % 2 == 0 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535;
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535;
 }
 
 static int wino_bwdf_splits(int nb, int T, int K, int C) {
@@ -440,7 +441,7 @@ static int wino_bwdf_splits(int nb, int T, int K, int C) {
 }
 
 static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K) {
-    const int T = (H / 2) * (W / 2), nb = wino_chunk(N, C, H, W, K);
+    const int T = ((H + 1) / 2) * ((W + 1) / 2), nb = wino_chunk(N, C, H, W, K);
     return (size_t)16 * K * C * sizeof(float) * (1 + wino_bwdf_splits(nb, T, K, C)) + (size_t)nb * 16 * (C + K) * T * sizeof(float);
 }
 
@@ -478,7 +479,7 @@ static hipError_t bwdf_cfg(const PixKParams& pa, const ConvGeom& g, const RowMaj
 
 // x [N][C][H][W], dy [N][K][H][W] -> dw [K][C][3][3] through the 16 grouped products of the Winograd form
 static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, hipStream_t st) {
-    const int T = (H / 2) * (W / 2);
+    const int T = ((H + 1) / 2) * ((W + 1) / 2);
     const int nb = wino_chunk(N, C, H, W, K);
     const int splits = wino_bwdf_splits(nb, T, K, C);
     const size_t kc = (size_t)K * C;
@@ -499,10 +500,10 @@ static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw,
         fp.x = v; fp.dy = dt; fp.ws = part;
         fp.x_bytes = (uint32_t)((size_t)cur * C * T * 4);
         fp.dy_bytes = (uint32_t)((size_t)cur * K * T * 4);
-        fp.K = K; fp.C = C; fp.H = H / 2; fp.W = W / 2; fp.R = 1; fp.S = 1; fp.stride = 1; fp.pad = 0; fp.P = H / 2; fp.Q = W / 2;
+        fp.K = K; fp.C = C; fp.H = (H + 1) / 2; fp.W = (W + 1) / 2; fp.R = 1; fp.S = 1; fp.stride = 1; fp.pad = 0; fp.P = (H + 1) / 2; fp.Q = (W + 1) / 2;
         fp.M = cur * T;
         fp.fd_pq = make_fastdiv((uint32_t)T);
-        fp.fd_q = make_fastdiv((uint32_t)(W / 2));
+        fp.fd_q = make_fastdiv((uint32_t)((W + 1) / 2));
         fp.splits = splits;
         fp.groups = 16;
         fp.x_gstride = (size_t)cur * C * T;

@@ -1,12 +1,12 @@
-// Winograd F(2x2, 3x3) convolution (Lavin & Gray's minimal-filtering form) for 3x3, stride 1, pad 1 layers with even
-// H and W: Y = A^T [ (G g G^T) .* (B^T d B) ] A per 2x2 output tile, d the 4x4 input patch.  The 16 element-wise
+// Winograd F(2x2, 3x3) convolution (Lavin & Gray's minimal-filtering form) for 3x3, stride 1, pad 1 layers (an odd
+// H or W is covered by tiles that hang over the edge: their extra inputs are zeros, their extra outputs are dropped): Y = A^T [ (G g G^T) .* (B^T d B) ] A per 2x2 output tile, d the 4x4 input patch.  The 16 element-wise
 // products, summed over channels, are 16 independent GEMMs [rows x Cred] x [Cred x tiles] that run as one grouped
 // launch of conv_fast_kernel (a 1x1 convolution per group); 2.25x fewer multiplications than the direct form.
 // This is the kind of performance-optimal algorithm that pays with workspace (Section 2.2 of the paper): the
 // transformed filter U, the transformed input V and the products Mt live there, V and Mt for a chunk of images
 // at a time so that the workspace stays bounded.
 //
-// Layouts (T = (H/2)*(W/2) tiles per image, nb images per chunk):
+// Layouts (T = ceil(H/2)*ceil(W/2) tiles per image, nb images per chunk):
 //   U [16][Cred][rows]      rows = output channels of the pass (K forward, C backward-data)
 //   V [16][nb][Cred][T]
 //   Mt[16][nb][rows][T]
@@ -51,7 +51,7 @@ __global__ void wino_filter_kernel(const float* __restrict__ w, float* __restric
 // V[xi][n][c][t] = (B^T d B)[xi], d = the 4x4 patch of src[n0 + n][c] whose top-left corner is (2*ty - 1, 2*tx - 1).
 // grid (ceil(T / blockDim.x), Cred, nb); lanes walk along tiles.
 __global__ void wino_input_kernel(const float* __restrict__ src, float* __restrict__ v, int n0, int nb, int C, int H, int W) {
-    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int TW = (W + 1) >> 1, T = ((H + 1) >> 1) * TW;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const int c = blockIdx.y, n = blockIdx.z;
@@ -88,20 +88,31 @@ __global__ void wino_input_kernel(const float* __restrict__ src, float* __restri
 
 // The same transform for planes of at most kWinoPlaneMax pixels: one workgroup per (c, n) plane stages the plane with
 // its zero border in LDS (each input element read from memory once, coalesced) and its threads walk over the tiles.
-// grid (Cred, nb); dynamic LDS (H + 2) * (W + 2) floats.
+// grid (Cred, nb); dynamic LDS (2 ceil(H/2) + 2) * (2 ceil(W/2) + 2) floats.
 constexpr int kWinoPlaneMax = 4096;
 __global__ void wino_input_plane_kernel(const float* __restrict__ src, float* __restrict__ v, int n0, int nb, int C, int H, int W) {
     extern __shared__ __align__(16) float plane[];
     const int c = blockIdx.x, n = blockIdx.y;
-    const int PW = W + 2, TW = W >> 1, T = (H >> 1) * TW;
+    const int TW = (W + 1) >> 1, TH = (H + 1) >> 1, T = TH * TW;
+    const int PW = 2 * TW + 2, PH = 2 * TH + 2;  // the plane with its zero border, rounded up to whole tiles
     const float* g = src + ((size_t)(n0 + n) * C + c) * H * W;
-    for (int i = threadIdx.x; i < PW; i += blockDim.x) plane[i] = 0.f, plane[(H + 1) * PW + i] = 0.f;
-    for (int i = threadIdx.x; i < H; i += blockDim.x) plane[(i + 1) * PW] = 0.f, plane[(i + 1) * PW + W + 1] = 0.f;
-    for (int i = threadIdx.x; i < (H * W) >> 1; i += blockDim.x) {  // W is even: pairs never straddle rows
-        const float2 e = reinterpret_cast<const float2*>(g)[i];
-        const int h = (2 * i) / W, w = 2 * i - h * W;
-        plane[(h + 1) * PW + w + 1] = e.x;
-        plane[(h + 1) * PW + w + 2] = e.y;
+    if ((W & 1) == 0) {
+        for (int i = threadIdx.x; i < PW; i += blockDim.x) plane[i] = 0.f, plane[(H + 1) * PW + i] = 0.f;
+        if (H & 1) for (int i = threadIdx.x; i < PW; i += blockDim.x) plane[(H + 2) * PW + i] = 0.f;
+        for (int i = threadIdx.x; i < H; i += blockDim.x) plane[(i + 1) * PW] = 0.f, plane[(i + 1) * PW + W + 1] = 0.f;
+        for (int i = threadIdx.x; i < (H * W) >> 1; i += blockDim.x) {  // W is even: pairs never straddle rows
+            const float2 e = reinterpret_cast<const float2*>(g)[i];
+            const int h = (2 * i) / W, w = 2 * i - h * W;
+            plane[(h + 1) * PW + w + 1] = e.x;
+            plane[(h + 1) * PW + w + 2] = e.y;
+        }
+    } else {
+        for (int i = threadIdx.x; i < PH * PW; i += blockDim.x) plane[i] = 0.f;
+        __syncthreads();
+        for (int i = threadIdx.x; i < H * W; i += blockDim.x) {
+            const int h = i / W, w = i - h * W;
+            plane[(h + 1) * PW + w + 1] = g[i];
+        }
     }
     __syncthreads();
     const size_t gstride = (size_t)nb * C * T;
@@ -133,7 +144,7 @@ __global__ void wino_input_plane_kernel(const float* __restrict__ src, float* __
 // grid (ceil(T / blockDim.x), rows, nb).
 __global__ void wino_output_kernel(const float* __restrict__ mt, float* __restrict__ out, const float* __restrict__ mask, int n0, int nb,
                                    int rows, int H, int W, int relu) {
-    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int TW = (W + 1) >> 1, T = ((H + 1) >> 1) * TW;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const int row = blockIdx.y, n = blockIdx.z;
@@ -151,31 +162,49 @@ __global__ void wino_output_kernel(const float* __restrict__ mt, float* __restri
         s[0][j] = m[0][j] + m[1][j] + m[2][j];
         s[1][j] = m[1][j] - m[2][j] - m[3][j];
     }
-    const size_t base = (((size_t)(n0 + n) * rows + row) * H + 2 * ty) * W + 2 * tx;  // even: W is even
+    const size_t base = (((size_t)(n0 + n) * rows + row) * H + 2 * ty) * W + 2 * tx;  // even when W is even
+    const bool right = 2 * tx + 1 < W;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
+        if (2 * ty + i >= H) break;
         float y0 = s[i][0] + s[i][1] + s[i][2], y1 = s[i][1] - s[i][2] - s[i][3];
         if (relu) y0 = y0 > 0.f ? y0 : 0.f, y1 = y1 > 0.f ? y1 : 0.f;
         const size_t idx = base + (size_t)i * W;
-        if (mask) {
-            const float2 mk = *reinterpret_cast<const float2*>(mask + idx);
-            if (!(mk.x > 0.f)) y0 = 0.f;
-            if (!(mk.y > 0.f)) y1 = 0.f;
+        if ((W & 1) == 0) {
+            if (mask) {
+                const float2 mk = *reinterpret_cast<const float2*>(mask + idx);
+                if (!(mk.x > 0.f)) y0 = 0.f;
+                if (!(mk.y > 0.f)) y1 = 0.f;
+            }
+            *reinterpret_cast<float2*>(out + idx) = make_float2(y0, y1);
+        } else {
+            if (mask && !(mask[idx] > 0.f)) y0 = 0.f;
+            out[idx] = y0;
+            if (right) {
+                if (mask && !(mask[idx + 1] > 0.f)) y1 = 0.f;
+                out[idx + 1] = y1;
+            }
         }
-        *reinterpret_cast<float2*>(out + idx) = make_float2(y0, y1);
     }
 }
 
 // ---- backward-filter: dW = sum over tiles of G^T [ (A dY_tile A^T) .* (B^T d B) ] G ----
 // Dt[xi][n][k][t] = (A dy A^T)[xi], dy the 2x2 tile (ty, tx) of dY[n0 + n][k].  grid (ceil(T / blockDim.x), K, nb).
 __global__ void wino_dy_kernel(const float* __restrict__ dy, float* __restrict__ dt, int n0, int nb, int K, int H, int W) {
-    const int TW = W >> 1, T = (H >> 1) * TW;
+    const int TW = (W + 1) >> 1, T = ((H + 1) >> 1) * TW;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const int k = blockIdx.y, n = blockIdx.z;
     const int ty = t / TW, tx = t - ty * TW;
-    const float* plane = dy + (((size_t)(n0 + n) * K + k) * H + 2 * ty) * W + 2 * tx;  // even offset: W is even
-    const float2 r0 = *reinterpret_cast<const float2*>(plane), r1 = *reinterpret_cast<const float2*>(plane + W);
+    const float* plane = dy + (((size_t)(n0 + n) * K + k) * H + 2 * ty) * W + 2 * tx;
+    float2 r0, r1;
+    if (((W | H) & 1) == 0) {  // even offsets, every tile inside the image
+        r0 = *reinterpret_cast<const float2*>(plane), r1 = *reinterpret_cast<const float2*>(plane + W);
+    } else {
+        const bool right = 2 * tx + 1 < W, below = 2 * ty + 1 < H;
+        r0 = make_float2(plane[0], right ? plane[1] : 0.f);
+        r1 = make_float2(below ? plane[W] : 0.f, below && right ? plane[W + 1] : 0.f);
+    }
     // A = [[1,0],[1,1],[1,-1],[0,-1]]: rows of A dy
     const float a[4][2] = {{r0.x, r0.y}, {r0.x + r1.x, r0.y + r1.y}, {r0.x - r1.x, r0.y - r1.y}, {-r1.x, -r1.y}};
     const size_t gstride = (size_t)nb * K * T;

@@ -511,13 +511,13 @@ def test_winograd_workspace_follows_the_budget(monkeypatch):
 
 def test_convolution_workspace_levels_by_shape():
     """Which algorithm the workspace query sizes for (the sizes are the oracle's closed forms): Winograd needs 3x3,
-    stride 1, pad 1, even sides and wide layers; everything else gets the packed-weight kernel or nothing."""
+    stride 1, pad 1 and wide layers (odd sides included); everything else gets the packed-weight kernel or nothing."""
     def info_net(c, h, k, ksz, st, pd):
         b = nets._Builder("one_conv", 4, c, h, h)
         b.conv(k, ksz, st, pd)
         b.fc(10, relu=False)
         return b.done()
-    cases = [(256, 8, 128, 3, 1, 1, True), (256, 8, 124, 3, 1, 1, False), (240, 8, 256, 3, 1, 1, False), (256, 9, 256, 3, 1, 1, False),
+    cases = [(256, 8, 128, 3, 1, 1, True), (256, 8, 124, 3, 1, 1, False), (240, 8, 256, 3, 1, 1, False), (256, 9, 256, 3, 1, 1, True),
              (256, 8, 256, 3, 2, 1, False), (256, 8, 256, 3, 1, 0, False), (256, 8, 256, 5, 1, 2, False), (512, 14, 512, 3, 1, 1, True)]
     for c, h, k, ksz, st, pd, wino in cases:
         net = info_net(c, h, k, ksz, st, pd)
