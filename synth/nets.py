@@ -212,13 +212,15 @@ def shapes(net):
     return out, wshape
 
 
-def random_net(seed, batch=2, in_hw=20, max_layers=10):
+def random_net(seed, batch=2, in_hw=20, max_layers=10, wide=False):
     """A random small network for fuzzing the planners and the kernels on irregular graphs: chains of
     conv / pool layers with random geometry, conv layers without a ReLU, forks whose branches are joined
-    by a concat (branches of different depth, a feature map read by several layers), FC head."""
+    by a concat (branches of different depth, a feature map read by several layers), FC head.
+    wide: channel counts of 128 ... 384 instead of 4 ... 24 (layers wide enough for every convolution algorithm)."""
     import random
     rnd = random.Random(seed)
-    b = _Builder("random%d" % seed, batch, rnd.choice((1, 3, 4)), in_hw, in_hw + rnd.choice((0, 3)))
+    cw = 32 if wide else 1   # 4, 8 -> 128, 256; 16 -> 512; 24 -> 768
+    b = _Builder("random%d%s" % (seed, "w" if wide else ""), batch, 256 if wide else rnd.choice((1, 3, 4)), in_hw, in_hw + rnd.choice((0, 3)))
     h, w = b.net["in_h"], b.net["in_w"]
     src = -1
     n = 0
@@ -226,11 +228,11 @@ def random_net(seed, batch=2, in_hw=20, max_layers=10):
         kind = rnd.random()
         if kind < 0.45:      # conv, same-size
             k = rnd.choice((1, 3, 3, 5))
-            src = b.conv(rnd.choice((4, 8, 16, 24)), k, pad=k // 2, relu=rnd.random() < 0.8, inputs=[src])
+            src = b.conv(rnd.choice((4, 8, 8, 12) if wide else (4, 8, 16, 24)) * cw, k, pad=k // 2, relu=rnd.random() < 0.8, inputs=[src])
         elif kind < 0.6:     # strided or unpadded conv
             k = rnd.choice((2, 3))
             st = rnd.choice((1, 2))
-            src = b.conv(rnd.choice((8, 16)), k, stride=st, pad=0, inputs=[src])
+            src = b.conv(rnd.choice((4, 8) if wide else (8, 16)) * cw, k, stride=st, pad=0, inputs=[src])
             h, w = (h - k) // st + 1, (w - k) // st + 1
         elif kind < 0.75:    # pool
             k, st, pd = rnd.choice(((2, 2, 0), (3, 2, 1), (3, 1, 1), (3, 2, 0)))
@@ -246,11 +248,11 @@ def random_net(seed, batch=2, in_hw=20, max_layers=10):
                 t = src
                 for _ in range(rnd.choice((1, 2))):
                     k = rnd.choice((1, 3))
-                    t = b.conv(rnd.choice((4, 8)), k, pad=k // 2, relu=rnd.random() < 0.7, inputs=[t])
+                    t = b.conv(rnd.choice((4, 8)) * cw, k, pad=k // 2, relu=rnd.random() < 0.7, inputs=[t])
                 outs.append(t)
             if rnd.random() < 0.5:
                 t = b.maxpool(3, 1, 1, inputs=[src])
-                outs.append(b.conv(4, 1, inputs=[t]))
+                outs.append(b.conv(4 * cw, 1, inputs=[t]))
             src = b.add("concat", outs)
         n += 1
     b.last = src

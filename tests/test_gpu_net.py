@@ -44,8 +44,9 @@ def small_googlenet(batch=2):
     return nets.googlenet(batch, in_hw=64, modules=mods)
 
 
-def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=None, part=None):
+def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=None, part=None, winograd=True):
     n = B.Net(net, budget)
+    n.set_winograd(winograd)
     if algo:
         n.set_conv_algo(algo)
     if part is not None:
@@ -393,3 +394,54 @@ def test_random_graphs_on_the_device(B, seed):
         assert r["loss"] == base["loss"], (pol, budget)
         for i in weights:
             assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
+
+
+@pytest.mark.parametrize("seed,chunk", [(104, 0), (108, 300000), (113, 0), (122, 300000), (124, 0)])
+def test_random_wide_graphs_on_the_device(B, seed, chunk, monkeypatch):
+    """The same fuzz with 128 ... 384 channels on 8 x 8 images, where plans give 3x3 layers the Winograd workspace (in
+    one piece, or with a chunk size that holds a single image): the no-offload step against the oracle with the
+    library's choice of algorithms; which layers run the Winograd algorithm and the peak equal the memory-schedule
+    oracle's under every policy; with the direct kernels pinned every offloading policy is bit-identical to no-offload."""
+    net = nets.random_net(seed, batch=3, in_hw=8, wide=True)
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 400 + seed)
+    B.op_set_winograd_chunk_bytes(chunk)
+    monkeypatch.setattr(ms, "WINOGRAD_CHUNK_BYTES", chunk or (512 << 20))
+    try:
+        got = run_gpu(B, net, x, labels, weights, "none")
+        sim = ms.simulate(net, "none", 1 << 50)
+        assert got["stats"]["n_winograd_convs"] == sim["n_winograd_convs"] >= 2 and got["stats"]["peak_bytes"] == sim["peak_bytes"]
+        fwd = onet.forward(net, x, labels, weights)[0]
+        for i, y in enumerate(fwd):
+            if net["layers"][i]["type"] != "softmax_ce":
+                assert rel_err(got["outs"][i].reshape(y.shape), y) < TOL, i
+        ref = onet.step(net, x, labels, weights, outs_override=got["outs"])
+        assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
+        for i in weights:
+            assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+        base = run_gpu(B, net, x, labels, weights, "none", capture=False, winograd=False)
+        assert base["stats"]["n_winograd_convs"] == 0
+        lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
+        hi = sim["peak_bytes"]
+        for pol, budget in (("all", 0), ("conv", (lo + hi) // 2), ("conv", 0), ("fit", (lo + hi) // 2)):
+            for on in (True, False):
+                n = B.Net(net, budget)
+                n.set_winograd(on)
+                n.set_window_part(2048)
+                ok = n.try_policy(pol) == B.OK
+                n.close()
+                if not ok:
+                    continue
+                r = run_gpu(B, net, x, labels, weights, pol, budget=budget, capture=False, part=2048, winograd=on)
+                if pol != "fit":
+                    want = ms.simulate(net, pol, budget or (1 << 50), winograd=on)
+                    assert r["stats"]["n_winograd_convs"] == want["n_winograd_convs"] and r["stats"]["peak_bytes"] == want["peak_bytes"]
+                if on:   # another mix of algorithms than the base run: equal to rounding
+                    assert abs(r["loss"] - base["loss"]) < 1e-5 * abs(base["loss"])
+                    for i in weights:
+                        assert rel_err(r["dw"][i], base["dw"][i]) < TOL, (pol, budget, i)
+                else:
+                    assert r["loss"] == base["loss"], (pol, budget)
+                    for i in weights:
+                        assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
+    finally:
+        B.op_set_winograd_chunk_bytes(0)
