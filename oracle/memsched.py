@@ -60,7 +60,7 @@ def winograd_workspace(n, cred, h, w, rows, k, stride, pad):
     reduction channels a multiple of 16 and at least 256, rows a multiple of 4 and at least 128.  Transformed filter (16 x cred x rows floats, rounded up to 256 bytes) plus transformed
     input and products (16 x (cred + rows) floats per 2x2 output tile) for as many images as fit the chunk size."""
     if not (k == 3 and stride == 1 and pad == 1 and cred % 16 == 0 and rows % 4 == 0
-            and 256 <= cred <= 65535 and 128 <= rows <= 65535):
+            and 256 <= cred <= 65535 and 128 <= rows <= 65535 and ((h + 1) // 2) * ((w + 1) // 2) <= 32768):
         return 0
     per_image = 16 * (cred + rows) * ((h + 1) // 2) * ((w + 1) // 2) * 4
     nb = max(1, min(n, 65535, WINOGRAD_CHUNK_BYTES // per_image))
@@ -71,7 +71,8 @@ def winograd_filter_workspace(n, c, h, w, k, ksz, stride, pad):
     """Workspace of the Winograd backward-filter pass where the library runs it (0 elsewhere): same geometry, input
     channels a multiple of 128, 256 or more output channels.  The 16 accumulated products (16 x K x C floats),
     their partial sums per reduction split, and the transformed X and dY for as many images as fit the chunk size."""
-    if not (ksz == 3 and stride == 1 and pad == 1 and c % 128 == 0 and c <= 65535 and 256 <= k <= 65535):
+    if not (ksz == 3 and stride == 1 and pad == 1 and c % 128 == 0 and c <= 65535 and 256 <= k <= 65535
+            and ((h + 1) // 2) * ((w + 1) // 2) <= 32768):
         return 0
     t = ((h + 1) // 2) * ((w + 1) // 2)
     per_image = 16 * (c + k) * t * 4

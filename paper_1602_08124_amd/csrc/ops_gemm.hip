@@ -217,7 +217,8 @@ void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? 
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
-           rows >= 128 && N >= 1 && cred <= 65535 && rows <= 65535;  // the transforms' grids carry channels and images in y and z
+           rows >= 128 && N >= 1 && cred <= 65535 && rows <= 65535 &&  // the transforms' grids carry channels and images in y and z
+           (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;         // and index (channel, tile) with 32 bits
 }
 
 static int wino_chunk(int N, int cred, int H, int W, int rows) {
@@ -256,7 +257,6 @@ static hipError_t conv_winograd(const float* src, const float* w, float* ws, flo
     VDNN_LAUNCH(wino_filter_kernel, dim3((unsigned)std::min<size_t>((wcount + 255) / 256, 4096)), dim3(256), 0, st, w, u, K, C, bwd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int tb = T <= 64 ? 64 : 256;
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
         e = wino_input(src, v, n0, cur, cred, H, W, st);
@@ -283,8 +283,8 @@ static hipError_t conv_winograd(const float* src, const float* w, float* ws, flo
         ts.full_tiles = rows <= 64 ? cdiv(p.M, 256) : cdiv(rows, 128) * cdiv(p.M, 128);
         e = rows <= 64 ? conv_fast_cfg<64, 256, 1, 4, true>(p, ts, nullptr, st) : conv_fast_cfg<128, 128, 2, 2, true>(p, ts, nullptr, st);
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH(wino_output_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)rows, (unsigned)cur), dim3(tb), 0, st, (const float*)mt, out, mask, n0,
-                    cur, rows, H, W, relu);
+        VDNN_LAUNCH(wino_output_kernel, dim3((unsigned)cdiv(rows * T, 256), (unsigned)cur), dim3(256), 0, st, (const float*)mt, out, mask, n0, cur,
+                    rows, H, W, relu);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -432,7 +432,8 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
 // column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 140 against 131 TFLOP/s).  Workspace: the 16 accumulated products
 // dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535;
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535 &&
+           (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;
 }
 
 static int wino_bwdf_splits(int nb, int T, int K, int C) {
@@ -487,13 +488,12 @@ static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw,
     float* part = acc + 16 * kc;
     float* v = part + (size_t)16 * splits * kc;
     float* dt = v + (size_t)16 * nb * C * T;
-    const int tb = T <= 64 ? 64 : 256;
     const int rblocks = (int)std::min<size_t>((16 * kc + 255) / 256, 8192);
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
         hipError_t e = wino_input(x, v, n0, cur, C, H, W, st);
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)K, (unsigned)cur), dim3(tb), 0, st, dy, dt, n0, cur, K, H, W);
+        VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(K * T, 256), (unsigned)cur), dim3(256), 0, st, dy, dt, n0, cur, K, H, W);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         BwdFilterFastParams fp;

@@ -141,13 +141,13 @@ __global__ void wino_input_plane_kernel(const float* __restrict__ src, float* __
 
 // out[n0 + n][row][2ty + i][2tx + j] = (A^T m A)[i][j], m[xi] = Mt[xi][n][row][t]; optional ReLU on the value
 // (forward) or zeroing where mask is not positive (backward-data with the preceding in-place ReLU folded in).
-// grid (ceil(T / blockDim.x), rows, nb).
+// grid (ceil(rows * T / blockDim.x), nb): lanes walk along (row, tile), which is contiguous in Mt.
 __global__ void wino_output_kernel(const float* __restrict__ mt, float* __restrict__ out, const float* __restrict__ mask, int n0, int nb,
                                    int rows, int H, int W, int relu) {
     const int TW = (W + 1) >> 1, T = ((H + 1) >> 1) * TW;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= T) return;
-    const int row = blockIdx.y, n = blockIdx.z;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * T) return;
+    const int row = i / T, t = i - row * T, n = blockIdx.y;
     const int ty = t / TW, tx = t - ty * TW;
     const size_t gstride = (size_t)nb * rows * T;
     const float* mi = mt + ((size_t)n * rows + row) * T + t;
@@ -189,12 +189,13 @@ __global__ void wino_output_kernel(const float* __restrict__ mt, float* __restri
 }
 
 // ---- backward-filter: dW = sum over tiles of G^T [ (A dY_tile A^T) .* (B^T d B) ] G ----
-// Dt[xi][n][k][t] = (A dy A^T)[xi], dy the 2x2 tile (ty, tx) of dY[n0 + n][k].  grid (ceil(T / blockDim.x), K, nb).
+// Dt[xi][n][k][t] = (A dy A^T)[xi], dy the 2x2 tile (ty, tx) of dY[n0 + n][k].  grid (ceil(K * T / blockDim.x), nb):
+// lanes walk along (k, tile), which is contiguous in Dt.
 __global__ void wino_dy_kernel(const float* __restrict__ dy, float* __restrict__ dt, int n0, int nb, int K, int H, int W) {
     const int TW = (W + 1) >> 1, T = ((H + 1) >> 1) * TW;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= T) return;
-    const int k = blockIdx.y, n = blockIdx.z;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K * T) return;
+    const int k = i / T, t = i - k * T, n = blockIdx.y;
     const int ty = t / TW, tx = t - ty * TW;
     const float* plane = dy + (((size_t)(n0 + n) * K + k) * H + 2 * ty) * W + 2 * tx;
     float2 r0, r1;
