@@ -255,8 +255,11 @@ vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, 
                                     int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
                                     void* stream);
 /* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
- * order (deterministic, no atomics).  With workspace NULL or smaller than required the memory-optimal
- * algorithm runs instead: no split, one workgroup per output tile (much slower on long reductions). */
+ * order (deterministic, no atomics).  The workspace query returns the bytes of the fastest algorithm for the shape
+ * (Winograd where the rule above admits it: the 16 accumulated products, their partial sums, and the transformed
+ * X and dY of a chunk of images); with less the direct split kernel runs if its partial sums fit, and with workspace
+ * NULL or too small for those the memory-optimal algorithm: no split, one workgroup per output tile (much slower on
+ * long reductions). */
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
                                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
