@@ -414,3 +414,27 @@ def test_conv_workspace_levels(B):
         assert rel_err(host(y), ref) < TOL
         outs.append(host(y))
     assert not np.array_equal(outs[0], outs[1])  # different algorithms, different rounding
+
+
+def test_conv_winograd_is_deterministic(B):
+    """No atomics anywhere in the Winograd path (partial sums and image chunks are added in a fixed order): two runs of
+    each pass give the same bits, chunked or not."""
+    import torch
+    n, c, h, w, k = 5, 256, 8, 8, 384
+    x, wt, dy = dev(_t((n, c, h, w), 81)), dev(_t((k, c, 3, 3), 82)), dev(_t((n, k, h, w), 83))
+    for chunk in (0, 2 * 16 * (c + k) * 16 * 4 + 64):
+        B.op_set_winograd_chunk_bytes(chunk)
+        try:
+            runs = []
+            for _ in range(2):
+                y = torch.empty((n, k, h, w), device="cuda")
+                dx = torch.empty((n, c, h, w), device="cuda")
+                dw = torch.empty((k, c, 3, 3), device="cuda")
+                B.op_conv_fwd(x, wt, y, 1, 1, True, ws=_ws(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1)))
+                B.op_conv_bwd_data(dy, wt, dx, 1, 1, ws=_ws(B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1)))
+                B.op_conv_bwd_filter(x, dy, dw, _ws(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)), 1, 1)
+                runs.append((host(y), host(dx), host(dw)))
+            for a, b in zip(*runs):
+                assert np.array_equal(a, b)
+        finally:
+            B.op_set_winograd_chunk_bytes(0)
