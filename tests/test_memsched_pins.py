@@ -179,3 +179,30 @@ def test_dynamic_policy_phases():
     tr = ms.simulate(net, "all", 1 << 50, "m")["trace"]
     conv_layers = {i for i, l in enumerate(net["layers"]) if l["type"] == "conv"}
     assert not [t for t in tr if t[1] == "alloc" and t[2] == "WS" and int(t[0][1:]) in conv_layers]
+
+
+def test_winograd_workspace_closed_forms():
+    """The Winograd workspace rules evaluated by hand for VGG-16 (256) layers: transformed filter 16*C*K floats, then
+    16*(C + K) floats per 2x2 output tile for as many images as fit 512 MiB; backward-filter: the 16 products once
+    plus once per reduction split, then the same chunk."""
+    MiB = 1 << 20
+    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image, 41 images per chunk
+    assert ms.winograd_workspace(256, 512, 28, 28, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 41 * 12845056
+    assert 41 * 12845056 <= 512 * MiB < 42 * 12845056
+    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 167 images per chunk
+    assert ms.winograd_workspace(256, 512, 14, 14, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 167 * 3211264
+    # a batch smaller than the chunk: all of it
+    assert ms.winograd_workspace(8, 512, 14, 14, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 8 * 3211264
+    # 13 x 13 (odd sides): 7 x 7 tiles as well
+    assert ms.winograd_workspace(8, 384, 13, 13, 256, 3, 1, 1) == 16 * 384 * 256 * 4 + 8 * 16 * 640 * 49 * 4
+    # not wide enough, not 3x3, strided, unpadded: no Winograd
+    for args in ((256, 128, 28, 28, 512, 3, 1, 1), (256, 512, 28, 28, 64, 3, 1, 1), (256, 512, 28, 28, 512, 5, 1, 2),
+                 (256, 512, 28, 28, 512, 3, 2, 1), (256, 512, 28, 28, 512, 3, 1, 0), (256, 520, 28, 28, 512, 3, 1, 1)):
+        assert ms.winograd_workspace(*args) == 0, args
+    # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits of the
+    # 41 * 196 = 8036 tile positions
+    assert ms.winograd_filter_workspace(256, 512, 28, 28, 512, 3, 1, 1) == 16 * 512 * 512 * 4 * (1 + 4) + 41 * 12845056
+    # c3_2: 256 -> 256 at 56 x 56: 784 tiles, 25 690 112 bytes per image, 20 per chunk; 2 x 2 tiles x 16 = 64 workgroups -> 16 splits
+    assert ms.winograd_filter_workspace(256, 256, 56, 56, 256, 3, 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 20 * 25690112
+    assert ms.winograd_filter_workspace(256, 192, 56, 56, 256, 3, 1, 1) == 0      # input channels not a multiple of 128
+    assert ms.winograd_filter_workspace(256, 256, 56, 56, 128, 3, 1, 1) == 0      # fewer than 256 output channels
