@@ -206,8 +206,8 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
 // -------------------------------------------------------------------------------------------
 // Winograd F(2x2, 3x3): see winograd.h.  Eligible: 3x3, stride 1, pad 1, reduction channels a multiple
 // of 16 and at least 256, rows a multiple of 4 and at least 128: measured on VGG-16 (256), in TFLOP/s of the direct
-// form's operation count, the direct kernel's 137 become 234 at 512 x 512 channels (28 x 28), 208 (14 x 14), 196-205 at
-// 256 x 512, 176-180 at 256 x 256 (56 x 56) and 153 at 256 -> 128; with 128 reduction channels the transforms' HBM
+// form's operation count, the direct kernel's 137 become 234 at 512 x 512 channels (28 x 28), 212 (14 x 14), 196-205 at
+// 256 x 512, 185 at 256 x 256 (56 x 56) and 156 at 256 -> 128; with 128 reduction channels the transforms' HBM
 // traffic costs what the saved multiplications gain (131 against 136).
 // Workspace: U, then V and Mt for `nb` images, nb the largest count that keeps V + Mt within the chunk size.
 // -------------------------------------------------------------------------------------------
@@ -429,8 +429,9 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
 }
 
 // Winograd backward-filter (winograd.h): same geometry as the other two passes, input channels a multiple of 128 (the
-// column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 140 against 131 TFLOP/s).  Workspace: the 16 accumulated products
-// dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt for a chunk of images.
+// column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 158 against 131 TFLOP/s).
+// Workspace: the 16 accumulated products dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt
+// for a chunk of images.
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535 &&
            (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;
