@@ -150,7 +150,9 @@ vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
  *
  * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
  * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
- * input's id); each must be one that ALL would offload, else VDNN_ERR_INVALID_ARG.  window_fill_pm,
+ * input's id); each must be one that ALL would offload or the input of an FC layer (the paper manages the feature
+ * extraction layers only and notes, at the start of Section 3, that the classification layers could be treated alike
+ * for a smaller saving), else VDNN_ERR_INVALID_ARG.  window_fill_pm,
  * window_fill_bwd_pm (forward, backward): 0 = the paper's synchronisation, 1..1000 = transfer windows; forward
  * releases are postponed while live bytes stay within that share of the budget, backward fetches are issued
  * early while live bytes stay within that share of the budget and the address range is free.  Uses the

@@ -348,8 +348,14 @@ vdnn_status_t vdnn_set_offload_set(vdnn_net_t* np, const int32_t* buffers, size_
     std::vector<char> set(L + 1, 0);
     for (size_t i = 0; i < count; ++i) {
         const int b = buffers[i];
-        if (b < -1 || b >= L || !n.B(b).count || !selected(n, b, VDNN_POLICY_ALL)) {
-            n.err = fmt("set_offload_set: %d is not a feature map that a CONV or POOL layer reads and backward propagation needs", b);
+        // what ALL would offload, and (Section 3, opening: the same idea applies to the classification layers) the X of FC layers
+        bool ok = b >= -1 && b < L && n.B(b).count && !n.B(b).bwd_users.empty();
+        if (ok && !selected(n, b, VDNN_POLICY_ALL)) {
+            ok = false;
+            for (int r : n.B(b).readers) ok |= n.layers[r].type == VDNN_FC;
+        }
+        if (!ok) {
+            n.err = fmt("set_offload_set: %d is not a feature map that a CONV, POOL or FC layer reads and backward propagation needs", b);
             return VDNN_ERR_INVALID_ARG;
         }
         set[b + 1] = 1;

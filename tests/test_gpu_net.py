@@ -194,6 +194,40 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
         n.close()
 
 
+@pytest.mark.parametrize("name,mk", NETS)
+def test_classifier_inputs_can_be_offloaded_too(B, name, mk):
+    """The paper manages the feature extraction layers and notes (Section 3, opening) that the classification
+    layers could be handled the same way: an explicit offload set may name the inputs of FC layers.  Values stay
+    bit-identical, the bytes moved are those of the chosen maps, and the step equals the memory-schedule oracle's."""
+    net = mk()
+    info = ms.analyse(net)
+    fc_inputs = {b for b in info["nbytes"] if any(net["layers"][r]["type"] == "fc" for r in info["readers"][b])}
+    assert fc_inputs
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 23)
+    base = run_gpu(B, net, x, labels, weights, "none", capture=False)
+    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+    for chosen, fill in ((fc_inputs, 0), (fc_inputs | set(ms.fit_candidates(net)), 0), (fc_inputs | set(ms.fit_candidates(net)), 900)):
+        n = B.Net(net, hi)
+        n.set_window_part(8192)
+        n.set_offload_set(chosen, fill)
+        assert n.offload_set() == chosen
+        ref = ms.simulate(net, "none", 1 << 50, offload_set=chosen)
+        n.attach_torch()
+        for i, w in weights.items():
+            n.set_weights(i, w)
+        for _ in range(2):
+            loss = n.forward(dev(x), dev(labels))
+            n.backward()
+            assert loss == base["loss"], (sorted(chosen), fill)
+            for i, w in weights.items():
+                assert np.array_equal(n.get_weight_grad(i, w.shape), base["dw"][i]), (sorted(chosen), fill, i)
+        st = n.stats()
+        assert st["offloaded_bytes"] == st["prefetched_bytes"] == ref["offloaded_bytes"] == sum(info["nbytes"][b] for b in chosen)
+        if not fill:
+            assert st["peak_bytes"] == ref["peak_bytes"]
+        n.close()
+
+
 def test_tiny_config_under_4_mib_budget(B):
     """The first benchmark configuration: Tiny CNN, batch 8, vDNN_all, 4 MiB budget."""
     net = nets.tiny(8)

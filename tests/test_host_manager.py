@@ -315,7 +315,11 @@ def test_explicit_offload_sets_and_window_fills_match_oracle():
     for mk, batch in ((nets.alexnet, 8), (nets.fork_join, 4), (lambda b: nets.googlenet(b, in_hw=64, modules=nets._INCEPTION[:4]), 4),
                       (lambda b: nets.vgg(b, in_hw=32), 8)):
         net = mk(batch)
-        cands = ms.fit_candidates(net)
+        info = ms.analyse(net)
+        # what vDNN_all would offload, and the inputs of the classification layers (Section 3, opening)
+        fc_inputs = [b for b in sorted(info["nbytes"]) if any(net["layers"][r]["type"] == "fc" for r in info["readers"][b])]
+        assert fc_inputs
+        cands = sorted(set(ms.fit_candidates(net)) | set(fc_inputs))
         peak_all = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
         peak_none = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
         for trial in range(12):
@@ -345,11 +349,14 @@ def test_explicit_offload_sets_and_window_fills_match_oracle():
                     assert "placement" in n.last_error() or fill == fill_bwd == 0
                 n.close()
     assert n_ok > 200 and n_lent > 200 and n_twins > 50, (n_ok, n_lent, n_twins)   # the cases do exercise lending
-    # what is not a CONV/POOL input that backward needs is refused
+    # what is not a CONV / POOL / FC input that backward needs is refused
     net = nets.tiny(8)
     n = binding.Net(net, 0)
-    fc_in = [i for i, l in enumerate(net["layers"]) if l["type"] == "fc"][0] - 1
-    assert n.try_offload_set({net["layers"][fc_in]["inputs"][0] if net["layers"][fc_in]["type"] == "relu" else fc_in}) == binding.ERR_INVALID_ARG
+    fc = [i for i, l in enumerate(net["layers"]) if l["type"] == "fc"][0]
+    fc_in = net["layers"][fc]["inputs"][0]
+    fc_in = net["layers"][fc_in]["inputs"][0] if net["layers"][fc_in]["type"] == "relu" else fc_in
+    assert n.try_offload_set({fc_in}) == binding.OK and n.offload_set() == {fc_in}
+    assert n.try_offload_set({fc}) == binding.ERR_INVALID_ARG      # the logits: only the loss layer reads them
     assert n.try_offload_set({len(net["layers"])}) == binding.ERR_INVALID_ARG
     assert n.try_offload_set({-2}) == binding.ERR_INVALID_ARG
     assert n.try_offload_set(set(), 1001) == binding.ERR_INVALID_ARG
