@@ -229,7 +229,8 @@ void vdnn_destroy(vdnn_net_t*);
 /* Message of the last failing vdnn_op_* call of this thread. */
 const char* vdnn_op_last_error(void);
 /* stream: hipStream_t or NULL.  Shapes: X [N][C][H][W], W [K][C][R][S], Y [N][K][P][Q] with
- * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream. */
+ * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream.  A tensor may have at most 2^31 - 2 elements:
+ * larger shapes return VDNN_ERR_INVALID_ARG before anything is launched (vdnn_create: VDNN_ERR_UNSUPPORTED). */
 
 /* Convolution algorithms in the sense of Section 2.2's memory-optimal / performance-optimal trade-off:
  *  - no workspace: implicit GEMM whose gather works directly on W as stored (memory-optimal);

@@ -3,6 +3,8 @@ configuration bench.py times.  The oracle cannot run these sizes whole, so it is
 sampled outputs one by one (each sample is a small sub-problem cut out of the GPU's own input
 tensors), and properties that hold at any size are checked on the whole tensors: the adjoint
 identities of the bilinear map and bit-identical results with and without offloading."""
+import zlib
+
 import numpy as np
 import pytest
 
@@ -37,6 +39,9 @@ FULL_LAYERS = [
     ("googlenet stem", 128, 3, 224, 224, 64, 7, 2, 3),
     ("googlenet 4a 1x1", 128, 480, 14, 14, 192, 1, 1, 0),
     ("googlenet 4b 5x5 reduce->5x5", 128, 24, 14, 14, 64, 5, 1, 2),
+    # the largest tensors the library takes: X, Y, dX and dY of 2^31 - 2^25 elements (8.5 GB) each; above 4 GiB the
+    # packed-weight kernels step aside (32-bit byte offsets) and the generic ones index elements with 32 bits
+    ("largest tensors", 63, 32, 1024, 1024, 32, 3, 1, 1),
 ]
 
 
@@ -44,7 +49,7 @@ FULL_LAYERS = [
 def test_conv_layer_full_size(B, cfg):
     import torch
     name, n, c, h, w, k, r, st, pd = cfg
-    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
     g = torch.Generator(device="cuda").manual_seed(1234)
     x = torch.randn((n, c, h, w), device="cuda", generator=g)
     wt = torch.randn((k, c, r, r), device="cuda", generator=g) * float(np.sqrt(2.0 / (c * r * r)))
@@ -65,14 +70,18 @@ def test_conv_layer_full_size(B, cfg):
     B.op_conv_fwd(x, wt, y, st, pd, False, ws=wsp)
     a = float((y.double() * dy.double()).sum())
     cc = float((wt.double() * dw.double()).sum())
-    assert abs(a - cc) < 2e-5 * abs(a) + 1e-3
+    # dY is independent of Y, so <Y,dY> is one draw from a distribution around 0 whose spread is |Y| |dY| / sqrt(count):
+    # rounding errors scale with that spread, not with where the draw happened to land
+    spread = float(y.double().norm() * dy.double().norm()) / np.sqrt(y.numel())
+    bound = 2e-5 * max(abs(a), spread) + 1e-3
+    assert abs(a - cc) < bound
     if st == 1:
         B.op_conv_bwd_data(dy, wt, dx, st, pd, ws=wsp)
         dxh = host(dx)
         assert np.isfinite(dxh).all()
         assert sampled_conv_bwd_data_check(dyh, wh, dxh, pd, rng) < TOL
         b = float((x.double() * dx.double()).sum())
-        assert abs(a - b) < 2e-5 * abs(a) + 1e-3
+        assert abs(a - b) < bound
 
 
 def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=False):

@@ -289,6 +289,15 @@ def test_invalid_arguments_are_rejected(B):
     assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), None, x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
+    # tensors of 2^31 - 1 elements or more are refused before anything is launched (kernels index with 32 bits)
+    big = (64, 32, 1024, 1024)   # 2^31 elements
+    p = x.data_ptr()
+    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_data(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, None, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_filter(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, 1, 1, 1024, 1024, 2048, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG   # the output is what is too large
+    assert lib.vdnn_op_maxpool_fwd(p, p, *big, 2, 2, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_maxpool_bwd(p, p, p, *big, 2, 2, 0, 0, None) == B.ERR_INVALID_ARG
 
 
 def _random_conv_shapes(count, seed):
