@@ -300,24 +300,28 @@ def test_invalid_arguments_are_rejected(B):
     assert lib.vdnn_op_maxpool_bwd(p, p, p, *big, 2, 2, 0, 0, None) == B.ERR_INVALID_ARG
 
 
-def _random_conv_shapes(count, seed):
+def _random_conv_shapes(count, seed, wide=False):
+    """wide: windows up to 11, stride up to 4, images up to 39 pixels a side, channel counts up to 384 on either side,
+    at most 3e9 multiply-adds per pass."""
     r = np.random.default_rng(seed)
     out = []
     while len(out) < count:
-        k_sz = int(r.choice([1, 2, 3, 3, 3, 5, 7]))
-        st = int(r.choice([1, 1, 1, 2, 3]))
+        k_sz = int(r.choice([1, 2, 3, 3, 3, 3, 4, 5, 7, 11] if wide else [1, 2, 3, 3, 3, 5, 7]))
+        st = int(r.choice([1, 1, 1, 2, 3, 4] if wide else [1, 1, 1, 2, 3]))
         pd = int(r.integers(0, k_sz))
-        c = int(r.choice([1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
-        k = int(r.choice([1, 7, 16, 33, 64, 96, 130]))
-        h, w = int(r.integers(1, 25)), int(r.integers(1, 25))
-        n = int(r.integers(1, 5))
+        c = int(r.choice([1, 2, 3, 4, 8, 15, 16, 17, 32, 48, 64, 96, 100, 128, 160, 256, 272, 384] if wide else [1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
+        k = int(r.choice([1, 2, 4, 7, 16, 31, 32, 33, 64, 65, 96, 128, 130, 256, 260, 384] if wide else [1, 7, 16, 33, 64, 96, 130]))
+        h, w = (int(r.integers(1, 40)), int(r.integers(1, 40))) if wide else (int(r.integers(1, 25)), int(r.integers(1, 25)))
+        n = int(r.integers(1, 6 if wide else 5))
         if h + 2 * pd < k_sz or w + 2 * pd < k_sz:
+            continue
+        if wide and n * c * h * w * k * k_sz * k_sz > 3e9:
             continue
         out.append((n, c, h, w, k, k_sz, st, pd))
     return out
 
 
-@pytest.mark.parametrize("shape", _random_conv_shapes(48, 20260101), ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shape", _random_conv_shapes(48, 20260101) + _random_conv_shapes(64, 20260102, wide=True), ids=lambda s: "x".join(map(str, s)))
 def test_conv_random_shapes(B, shape):
     """Seeded random geometry (odd sizes, one-pixel images, even windows, stride 3, channel counts on both sides of
     every tile and algorithm boundary): all three convolution passes, with and without workspace."""
