@@ -141,8 +141,9 @@ vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
  *       offloaded itself and had to release something becomes a tenant of the block released last, lined up
  *       from the low end of that range;
  *       backward: the fetch of X returns to the range X had (once its tenants are gone), and every fetch is
- *       issued as early as its own address range is free in the placement of the blocks; the compute stream
- *       waits for a fetch just before the first computation that reads it.
+ *       issued as early as its own address range is free in the placement of the blocks (which, where the budget
+ *       allows, keeps that range clear from the point at which live bytes alone would admit the fetch); the compute
+ *       stream waits for a fetch just before the first computation that reads it.
  *       The forward share is the largest of 100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 % for which the
  *       blocks can be placed inside the budget (window_fill_pm in the stats; window_fill_bwd_pm = 1000 when
  *       fetches are issued early).

@@ -116,8 +116,9 @@ static std::vector<Unit> make_units(const Plan& p) {
     return units;
 }
 
+// limit: an order whose placement passes this extent is given up at once ((size_t)-1 is returned)
 static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, size_t base, const std::vector<double>& key,
-                              std::vector<size_t>& offsets) {
+                              std::vector<size_t>& offsets, size_t limit = (size_t)-1) {
     std::vector<int> order(units.size());
     for (size_t i = 0; i < units.size(); ++i) order[i] = (int)i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key[a] > key[b]; });
@@ -156,6 +157,7 @@ static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, s
             for (size_t o : cands)
                 if (fits(o)) { off = o; break; }   // sliding down from above every neighbour stops at one of the candidates
         }
+        if (off + u.bytes > limit) return (size_t)-1;
         for (const Rect& r : u.rects) placed.push_back({off + r.off, r.bytes, r.t0, r.t1});
         for (auto& m : u.members) offsets[m.first] = off + m.second;
         extent = std::max(extent, off + u.bytes);
@@ -163,10 +165,25 @@ static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, s
     return extent;
 }
 
-static size_t place_blocks(Plan& p, size_t base) {
+// good_enough: the search stops at the first placement whose extent is at most this (0: only at the lower bound);
+// rounds: how many perturbed orders are tried after the four plain ones.
+static size_t place_blocks(Plan& p, size_t base, size_t good_enough = 0, int rounds = 300) {
     const std::vector<Unit> units = make_units(p);
     if (units.empty()) return base;
     const size_t n = units.size();
+    // lower bound of the extent: the largest number of bytes whose lifetimes (as placement sees them) overlap
+    size_t bound = base;
+    {
+        std::vector<std::pair<int, long long>> ev;
+        for (const Unit& u : units)
+            for (const Rect& r : u.rects) { ev.push_back({r.t0, (long long)r.bytes}); ev.push_back({r.t1, -(long long)r.bytes}); }
+        std::sort(ev.begin(), ev.end());   // at equal times releases (negative) come first: lifetimes are half-open
+        long long live = 0, top = 0;
+        for (auto& e : ev) { live += e.second; top = std::max(top, live); }
+        bound = base + (size_t)top;
+    }
+    const size_t target = std::max(bound, good_enough);
+    const size_t limit = good_enough ? good_enough : (size_t)-1;   // with a goal, orders that miss it need not be finished
     std::vector<double> size(n), life(n), area(n), start(n), key(n);
     for (size_t i = 0; i < n; ++i) {
         // ties: earlier blocks first (the sort is stable)
@@ -179,20 +196,21 @@ static size_t place_blocks(Plan& p, size_t base) {
     size_t best_extent = (size_t)-1;
     constexpr int kKinds = 4;
     const std::vector<double>* base_keys[kKinds] = {&size, &life, &area, &start};
-    for (int kind = 0; kind < kKinds; ++kind) {
-        const size_t e = place_with_keys(units, p.blocks.size(), base, *base_keys[kind], cur);
+    for (int kind = 0; kind < kKinds && best_extent > target; ++kind) {
+        const size_t e = place_with_keys(units, p.blocks.size(), base, *base_keys[kind], cur, limit);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
     uint64_t rng = 0x9E3779B97F4A7C15ull;  // fixed seed: the plan is a pure function of (net, policy, budget)
     auto next = [&]() { rng = rng * 6364136223846793005ull + 1442695040888963407ull; return (double)(rng >> 11) / 9007199254740992.0; };
     const double noises[4] = {0.1, 0.3, 0.6, 1.0};
-    for (int round = 0; round < 300 && best_extent > p.peak; ++round) {
+    for (int round = 0; round < rounds && best_extent > target; ++round) {
         const std::vector<double>& k0 = *base_keys[(int)(next() * kKinds) % kKinds];
         const double noise = noises[(int)(next() * 4) % 4];
         for (size_t i = 0; i < n; ++i) key[i] = k0[i] * (1.0 + noise * (next() - 0.5));
-        const size_t e = place_with_keys(units, p.blocks.size(), base, key, cur);
+        const size_t e = place_with_keys(units, p.blocks.size(), base, key, cur, limit);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
+    if (best_extent == (size_t)-1) return best_extent;   // no order stayed within the limit: offsets untouched
     for (const Unit& u : units)
         for (auto& m : u.members) p.blocks[m.first].offset = best[m.first];
     return best_extent;
@@ -662,6 +680,56 @@ static void hoist_fetches(Plan& p, size_t soft_bwd) {
     p.ops.swap(out);
 }
 
+// Before placement: how early could each fetch start if only live bytes counted?  The answer is written into the
+// lifetimes that placement sees (not into the op list), so that placement keeps the fetch's address range clear
+// from then on and hoist_fetches finds it free.  Inside a host's range the tenants still come first: a piece of a
+// twin cannot start before the tenants that overlap it have left.  Returns whether any lifetime was extended.
+static bool reserve_fetch_ranges(Plan& p, size_t soft_bwd) {
+    const int f0 = p.first_bwd_op, nt = (int)p.ops.size();
+    std::vector<size_t> before(nt + 1, 0);
+    {
+        size_t live = 0;
+        for (int t = 0; t < nt; ++t) {
+            before[t] = live;
+            const Op& o = p.ops[t];
+            if (o.kind != OP_ALLOC && o.kind != OP_FREE) continue;
+            const Block& b = p.blocks[o.block];
+            const size_t bytes = o.part < 0 ? b.bytes : b.piece_bytes(o.part);
+            if (o.kind == OP_ALLOC) live += bytes; else live -= bytes;
+        }
+    }
+    bool any = false;
+    int lo = f0;
+    for (int q = f0; q + 1 < nt; ++q) {
+        const Op& a = p.ops[q];
+        const Op& c = p.ops[q + 1];
+        if (a.kind != OP_ALLOC || (c.kind != OP_PREFETCH && c.kind != OP_ONDEMAND) || c.block != a.block || c.part != a.part) continue;
+        Block& b = p.blocks[a.block];
+        const size_t s = a.part < 0 ? b.bytes : b.piece_bytes(a.part);
+        int ready = lo;
+        if (b.host >= 0) {
+            const size_t r0 = b.host_rel + (a.part < 0 ? 0 : (size_t)a.part * b.part_bytes), r1 = r0 + s;
+            for (int id = 0; id < (int)p.blocks.size(); ++id) {
+                const Block& t = p.blocks[id];
+                if (id == a.block || t.host != b.host || t.t0 >= q) continue;
+                if (t.host_rel < r1 && r0 < t.host_rel + t.bytes) ready = std::max(ready, t.t1);
+            }
+        }
+        int j = q;
+        while (j > ready && before[j - 1] + s <= soft_bwd) --j;
+        if (j < q) {
+            for (int t = j; t <= q; ++t) before[t] += s;
+            if (a.part < 0) b.t0 = j;
+            else { b.part_t0[a.part] = j; b.t0 = std::min(b.t0, j); }
+            any = true;
+            lo = j;
+        } else {
+            lo = q + 2;
+        }
+    }
+    return any;
+}
+
 // Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
 static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
@@ -682,6 +750,21 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
         return;
     }
     if (windows && fill_bwd_pm > 0) {
+        // A step that can be placed is placed once more with the ranges of the fetches kept clear from as early as
+        // live bytes allow (for the whole share of the budget, then for less): the first such placement that fits the
+        // budget replaces the plain one, and hoist_fetches then finds those ranges free.
+        static const int kReserve[] = {1000, 900, 800};
+        for (int pm : kReserve) {
+            if (pm > fill_bwd_pm) continue;
+            Plan q = p;
+            if (!reserve_fetch_ranges(q, soft(pm))) break;
+            const size_t e = place_blocks(q, q.persistent, budget, p.blocks.size() <= 600 ? 300 : 0);
+            if (e <= budget) {
+                for (size_t i = 0; i < p.blocks.size(); ++i) p.blocks[i].offset = q.blocks[i].offset;
+                p.extent = e;
+                break;
+            }
+        }
         const Plan kept = p;
         hoist_fetches(p, soft(fill_bwd_pm));
         measure_plan(p);
