@@ -27,7 +27,7 @@ shares its input's buffers; FC/loss inputs are never offloaded; sizes are rounde
 
 ALIGN = 256
 TARGET_BLOCKS = 1024
-MIN_SPLIT_LEN = 2048
+MIN_SPLIT_LEN = 512
 IN_PLACE = ("relu",)
 NEEDS_X_IN_BWD = ("conv", "maxpool", "fc", "softmax_ce")
 

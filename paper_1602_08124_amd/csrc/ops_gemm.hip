@@ -14,10 +14,14 @@ namespace vdnn {
 // -------------------------------------------------------------------------------------------
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
+// A split is worth a workgroup from 512 reduction elements on (16 K-steps of 32): with 2048 the 1x1 and late 3x3 layers of
+// the GoogLeNet-shaped net, whose reductions are 6 272 ... 100 352 pixels long, filled a tenth of the chip in backward-filter
+// (measured with 2048 / 1024 / 512 / 256: GoogLeNet 4744 / 5248 / 5390 / 5264 img/s, AlexNet 14 340 / 15 200 / 15 730 / 15 970).
+constexpr int kMinReduction = 512;
 int gemm_splits(long long m, long long n, long long kred) {
     const int bm = m <= 64 ? 64 : 128;
     const long long tiles = (long long)cdiv(m, bm) * cdiv(n, 128);
-    long long s = std::min<long long>(1024 / tiles, cdiv(kred, 2048));
+    long long s = std::min<long long>(1024 / tiles, cdiv(kred, kMinReduction));
     return (int)std::max<long long>(1, s);
 }
 
@@ -415,7 +419,7 @@ static int bwdf_splits(int N, int C, int H, int W, int K, int R, int S, int P, i
     const long long M = (long long)N * P * Q;
     if (bwdf_fast_ok(N, C, H, W, K, P, Q) && bwdf_three_taps(C, R, S)) {
         const long long tiles = (long long)cdiv(K, K <= 64 ? 64 : 128) * (R * S / 3);
-        return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv(M, 2048)));
+        return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv(M, kMinReduction)));
     }
     return gemm_splits(K, (long long)C * R * S, M);
 }

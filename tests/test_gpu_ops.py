@@ -128,7 +128,7 @@ def test_conv_bwd_filter_is_split_and_deterministic(B):
     shape = (8, 8, 64, 64, 16, 3, 1, 1)
     n, c, h, w, k, r, st, pd = shape
     nbytes = B.op_conv_bwd_filter_workspace((n, c, h, w), (k, c, r, r), st, pd)
-    assert nbytes == 16 * k * c * r * r * 4  # reduction of 32768 split 16 ways
+    assert nbytes == 64 * k * c * r * r * 4  # reduction of 32768 in 64 pieces of 512
     x, dy = dev(_t((n, c, h, w), 7)), dev(_t((n, k, h, w), 8))
     outs = []
     for _ in range(3):
