@@ -349,8 +349,8 @@ namespace vdnn {
 // Columns are ordered tap-major and a column tile never straddles two taps (C is a multiple of the
 // tile width), so the tap and the image-border test are the same for the whole workgroup and are
 // evaluated once per K-step per thread.  Lanes walk along pixels (contiguous in NCHW).
-// Partial sums of reduction split s go to ws[s][k][tap*C + c]; reduce_permute_kernel adds the splits
-// in order and writes dW in [K][C][R][S] order.
+// Partial sums of reduction split s go to ws[s][k][tap*C + c]; the launcher's reduction pass adds the splits
+// in a fixed order and writes dW in [K][C][R][S] order.
 // ---------------------------------------------------------------------------------------------
 struct BwdFilterFastParams {
     const float* x;   // [N][C][H][W]
@@ -547,20 +547,6 @@ __global__ __launch_bounds__(kThreads) void conv_bwdf_fast_kernel(BwdFilterFastP
                 for (int j = 0; j < TN; ++j) orow[tile_col(j)] = acc[i][j][v];
             }
         }
-}
-
-// dW[k][c][rs] = sum_s ws[s][k][rs*C + c], s ascending
-__global__ void reduce_permute_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int RS, int splits) {
-    const size_t total = (size_t)K * C * RS;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int rs = (int)(i % RS);
-        const int c = (int)((i / RS) % C);
-        const size_t k = i / ((size_t)RS * C);
-        const size_t src = k * (size_t)C * RS + (size_t)rs * C + c;
-        float acc = ws[src];
-        for (int s = 1; s < splits; ++s) acc += ws[(size_t)s * total + src];
-        dw[i] = acc;
-    }
 }
 
 }  // namespace vdnn

@@ -30,20 +30,48 @@ size_t gemm_workspace_bytes(long long m, long long n, long long kred) {
     return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
 }
 
-// out[i] = sum_s ws[s * slice + i], s ascending (deterministic)
-__global__ void reduce_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, size_t count, int splits) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-        float acc = ws[i];
-        for (int s = 1; s < splits; ++s) acc += ws[(size_t)s * count + i];
-        out[i] = acc;
+// out[perm(i)] = sum_s ws[s * count + i].  G lanes share an output: lane g adds slices g, g + G, ... in ascending order, then
+// the G partial sums are added in ascending g, so the order is fixed (deterministic) for a given shape.  A small output with many
+// slices (the 1x1 and narrow layers: 4096 outputs, hundreds of slices) would otherwise run on a handful of workgroups.
+// perm: identity (C = 0), or from the backward-filter kernels' [k][tap][c] order to dW's [k][c][tap].
+template <int G>
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, size_t count, int splits,
+                                                            int C, int RS) {
+    constexpr int E = 256 / G;  // outputs per workgroup and pass
+    __shared__ float part[G][E];
+    const int e = threadIdx.x % E, g = threadIdx.x / E;
+    for (size_t base = (size_t)blockIdx.x * E; base < count; base += (size_t)gridDim.x * E) {  // the same trip count for the whole workgroup
+        const size_t i = base + e;
+        float acc = 0.f;
+        if (i < count)
+            for (int s = g; s < splits; s += G) acc += ws[(size_t)s * count + i];
+        if constexpr (G > 1) {
+            part[g][e] = acc;
+            __syncthreads();
+            if (g == 0) {
+#pragma unroll
+                for (int k = 1; k < G; ++k) acc += part[k][e];
+            }
+        }
+        if (g == 0 && i < count) {
+            size_t o = i;
+            if (C) {
+                const size_t crs = (size_t)C * RS, k = i / crs, r = i - k * crs;
+                o = k * crs + (r % C) * RS + r / C;
+            }
+            out[o] = acc;
+        }
+        if constexpr (G > 1) __syncthreads();
     }
 }
 
-static hipError_t launch_reduce(const float* ws, float* out, size_t count, int splits, hipStream_t st) {
-    const int threads = 256;
-    const int blocks = (int)std::min<size_t>((count + threads - 1) / threads, 4096);
-    VDNN_LAUNCH(reduce_splits_kernel, dim3(blocks), dim3(threads), 0, st, ws, out, count, splits);
+// C, RS: see the kernel (0, 0: no permutation)
+static hipError_t launch_reduce(const float* ws, float* out, size_t count, int splits, hipStream_t st, int C = 0, int RS = 0) {
+    const int G = (count <= 16384 && splits >= 64) ? 16 : (count <= 131072 && splits >= 16) ? 4 : 1;
+    const int blocks = (int)std::min<size_t>((count + 256 / G - 1) / (256 / G), 4096);
+    if (G == 16) VDNN_LAUNCH(reduce_splits_kernel<16>, dim3(blocks), dim3(256), 0, st, ws, out, count, splits, C, RS);
+    else if (G == 4) VDNN_LAUNCH(reduce_splits_kernel<4>, dim3(blocks), dim3(256), 0, st, ws, out, count, splits, C, RS);
+    else VDNN_LAUNCH(reduce_splits_kernel<1>, dim3(blocks), dim3(256), 0, st, ws, out, count, splits, C, RS);
     return hipGetLastError();
 }
 
@@ -558,10 +586,7 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
         else if (C % 64 == 0) e = K <= 64 ? bwdf_fast_cfg<64, 64, 2, 2, 32>(fp, st) : bwdf_fast_cfg<128, 64, 4, 1, 16>(fp, st);
         else e = bwdf_fast_cfg<128, 32, 4, 1, 16>(fp, st);
         if (e != hipSuccess) return e;
-        const size_t total = (size_t)K * CRS;
-        const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-        VDNN_LAUNCH(reduce_permute_kernel, dim3(blocks), dim3(256), 0, st, (const float*)ws, dw, K, C, R * S, splits);
-        return hipGetLastError();
+        return launch_reduce((const float*)ws, dw, (size_t)K * CRS, splits, st, C, R * S);  // adds the splits, [k][tap][c] -> [k][c][tap]
     }
     ConvGeom g = make_geom(x, N, C, H, W, R, S, stride, pad, P, Q);
     PixKParams pa;
