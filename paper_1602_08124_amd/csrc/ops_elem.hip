@@ -88,6 +88,64 @@ __global__ void maxpool_fwd_kernel(const float* __restrict__ x, float* __restric
     }
 }
 
+// 3x3 windows, stride 1 or 2: one thread per 2x2 block of outputs.  Their four windows lie in a 4x4 (stride 1) or 5x5
+// (stride 2) patch of X that the thread loads once (cells outside the image read as -inf): 4 or 6.25 loads per output
+// instead of 9, and the decode of the output index once per four outputs.  Windows are scanned in the same order and
+// with the same comparison as in maxpool_fwd_kernel, so the values are the same bits.
+template <int STRIDE>
+__global__ void maxpool3_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H, int W, int P, int Q, int pad, uint32_t total,
+                                    FD fbq, FD fbp, int nbp, int nbq) {
+    constexpr int NB = STRIDE + 3;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const uint32_t t = fdiv(i, fbq);
+        const int q0 = 2 * (int)(i - t * (uint32_t)nbq);
+        const uint32_t nc = fdiv(t, fbp);
+        const int p0 = 2 * (int)(t - nc * (uint32_t)nbp);
+        const float* xp = x + (size_t)nc * H * W;
+        const int h0 = p0 * STRIDE - pad, w0 = q0 * STRIDE - pad;
+        float nb[NB][NB];
+#pragma unroll
+        for (int a = 0; a < NB; ++a) {
+            const int hh = h0 + a;
+            const bool okh = (unsigned)hh < (unsigned)H;
+            const int hc = min(max(hh, 0), H - 1);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int ww = w0 + b;
+                const bool ok = okh && (unsigned)ww < (unsigned)W;
+                const float v = xp[hc * W + min(max(ww, 0), W - 1)];
+                nb[a][b] = ok ? v : -INFINITY;
+            }
+        }
+        float out[2][2];
+#pragma unroll
+        for (int dp = 0; dp < 2; ++dp)
+#pragma unroll
+            for (int dq = 0; dq < 2; ++dq) {
+                float best = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) {
+                        const float v = nb[dp * STRIDE + r][dq * STRIDE + s];
+                        if (v > best) best = v;
+                    }
+                out[dp][dq] = best;
+            }
+        float* yp = y + (size_t)nc * P * Q;
+#pragma unroll
+        for (int dp = 0; dp < 2; ++dp) {
+            if (p0 + dp >= P) continue;
+            float* row = yp + (size_t)(p0 + dp) * Q + q0;
+            if (q0 + 1 < Q && !(Q & 1)) *reinterpret_cast<float2*>(row) = make_float2(out[dp][0], out[dp][1]);  // q0 and Q even: 8-byte aligned
+            else {
+                row[0] = out[dp][0];
+                if (q0 + 1 < Q) row[1] = out[dp][1];
+            }
+        }
+    }
+}
+
 // One thread per dX element: visit every window that contains it, recompute that window's first
 // maximum (row-major scan, strict >) and take the window's dY if this element is it.  Windows are
 // visited in ascending (p, q), so overlapping windows add up in a fixed order.  relu_mask: the
@@ -301,6 +359,17 @@ hipError_t maxpool_fwd(const float* x, float* y, int N, int C, int H, int W, int
     if (k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 4 == 0) {
         const uint32_t t2 = (uint32_t)(total / 2);
         VDNN_LAUNCH(maxpool2x2_fwd_kernel, dim3(grid_for(t2, 256)), dim3(256), 0, st, x, y, W, Q / 2, t2, make_fd(Q / 2));
+        return hipGetLastError();
+    }
+    if (k == 3 && (stride == 1 || stride == 2)) {
+        const int nbp = (P + 1) / 2, nbq = (Q + 1) / 2;  // 2x2 blocks of Y per plane
+        const size_t blocks = (size_t)N * C * nbp * nbq;
+        if (stride == 1)
+            VDNN_LAUNCH(maxpool3_fwd_kernel<1>, dim3(grid_for(blocks, 256)), dim3(256), 0, st, x, y, H, W, P, Q, pad, (uint32_t)blocks,
+                        make_fd(nbq), make_fd(nbp), nbp, nbq);
+        else
+            VDNN_LAUNCH(maxpool3_fwd_kernel<2>, dim3(grid_for(blocks, 256)), dim3(256), 0, st, x, y, H, W, P, Q, pad, (uint32_t)blocks,
+                        make_fd(nbq), make_fd(nbp), nbp, nbq);
         return hipGetLastError();
     }
     VDNN_LAUNCH(maxpool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, H, W, P, Q, k, stride, pad,
