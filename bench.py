@@ -6,9 +6,10 @@ with the vDNN memory manager under a 12 GiB device budget.
 
 Prints ONE JSON line.  `value` is images/s with vDNN_dyn, the paper's proposed policy, under 12 GiB (inputs resident
 in HBM; on this machine dyn adopts conv);
-the `policies` object gives the same measurement for none (unlimited budget), conv, dyn, all and for
+the `policies` object gives the same measurement for none (unlimited budget), conv, all, dyn and for
 fit (beyond the paper: per-feature-map offload set with budget-aware transfer windows), with peak pool
-bytes and achieved host-link GB/s.  `roofline` times the dominant kernel (the
+bytes and achieved host-link GB/s.  dyn runs after conv and all: the host link, which it runs at the pace of, has
+on some machines delivered about half its rate during the first seconds of a process.  `roofline` times the dominant kernel (the
 implicit-GEMM convolution) with HIP events on its own stream; `cpu_baseline` times the CPU oracle
 on a bounded sample of the same workload.
 """
@@ -236,7 +237,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--budget-gib", type=float, default=12.0)
-    ap.add_argument("--policies", default="none,conv,dyn,all,fit")
+    ap.add_argument("--policies", default="none,conv,all,dyn,fit")
     ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "overfeat", "googlenet", "vgg16", "vgg116", "vgg416"],
                     help="vgg16 is the benchmark; the others are the paper's remaining workloads (side measurements)")
     ap.add_argument("--window-part-mib", type=float, default=None, help="side workloads: piece size of the transfer windows (0 = whole blocks)")
