@@ -129,7 +129,9 @@ def roofline(B, batch):
 
 
 def cpu_baseline(sample_batch):
-    """The CPU oracle, as it stands, on one training step of VGG-16 at a small batch."""
+    """The CPU oracle, as it stands, on one training step of VGG-16 at a small batch.  Its loops run in parallel over
+    (image, channel) pairs or, for backward-data, over images only, so the batch has to give every core an image's worth of
+    work: 8 images take most of a minute on 16 cores."""
     from oracle import net as onet
     from synth import gen, nets
     net = nets.vgg16(sample_batch)
@@ -139,7 +141,7 @@ def cpu_baseline(sample_batch):
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
     return dict(value=sample_batch / dt, unit="img/s", cores=cores, kind="oracle",
-                sample="one fwd+bwd step of VGG-16 at batch %d (%.1f s); per-image cost of the direct loops does not depend on the batch" % (sample_batch, dt))
+                sample="one fwd+bwd step of VGG-16 at batch %d in %.1f s on %d threads (the benchmark's batch is 256: the same layers, 1/%d of the images)" % (sample_batch, dt, cores, 256 // sample_batch))
 
 
 def per_layer_sync_bound(trace, layer_ms, d2h_gbps, h2d_gbps):
@@ -247,7 +249,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true", help="skip the roofline kernel (for a profile of the steps alone)")
     ap.add_argument("--no-winograd", action="store_true", help="keep every plan on the direct convolution kernels (side measurement)")
-    ap.add_argument("--cpu-sample-batch", type=int, default=1)
+    ap.add_argument("--cpu-sample-batch", type=int, default=8)
     args = ap.parse_args()
     global WINOGRAD
     WINOGRAD = not args.no_winograd
@@ -278,7 +280,7 @@ def main():
     if args.workload != "vgg16":
         # side measurement of another workload: its own batch and budget, policies as asked; one JSON line, no roofline
         defaults = {"tiny": (8, 4 / 1024), "alexnet": (128, 1.0), "overfeat": (128, 2.0), "googlenet": (128, 3.0),
-                    "vgg116": (32, 12.0), "vgg416": (32, 12.0)}   # the very deep VGGs of Section 5.4
+                    "vgg116": (32, 12.0), "vgg416": (32, 12.0)}   # the very deep VGGs of Section 5.5
         batch, gib = defaults[args.workload]
         if args.budget_gib != 12.0:
             gib = args.budget_gib

@@ -50,12 +50,23 @@ typedef enum {
  * memory-optimal one (none).  GREEDY is what phase 3 of vDNN_dyn produces: performance-optimal except
  * where its workspace would overflow the budget. */
 typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdnn_conv_algo_t;
-/* Two kernels stand behind "performance-optimal": the packed-weight direct kernel everywhere, and on wide 3x3 layers
- * (see vdnn_op_conv_fwd_workspace) the Winograd algorithm, which is faster and wants far more workspace.  A plan
- * gives a layer the Winograd workspace where it fits the budget at that point of the step (always, without a
- * budget) and the direct kernel's elsewhere; with an explicit, non-empty offload set (FIT, vdnn_set_offload_set) the forward
- * pass keeps the direct kernel, since it runs at the pace of the offloads.  Plans under different budgets may
- * therefore differ in rounding; vdnn_set_winograd(net, 0) keeps every plan of the net on the direct kernel. */
+/* The kernels behind those algorithms.  Every pass of a CONV layer (forward, backward-data, backward-filter) can run
+ *   GATHER    implicit GEMM that gathers X, dY and W as stored: no workspace, any shape (the memory-optimal algorithm);
+ *   PACKED    implicit GEMM on a packed copy of W, with a deterministic split of long or ragged reductions: workspace
+ *             of about |W| (backward-filter: one |W| per split); needs reduction channels in multiples of 16 (32 for
+ *             backward-filter), an unstrided backward-data pass and tensors below 4 GiB;
+ *   WINOGRAD  F(2x2,3x3) minimal filtering on wide 3x3 / stride 1 / pad 1 layers: 2.25x fewer multiplications, a
+ *             workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk of images).
+ * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: by the order above until
+ * vdnn_profile has measured them on the GPU, by measured time afterwards.  The first entry is the layer's
+ * performance-optimal algorithm, the last the memory-optimal one.  EVERY plan of the net (whatever the policy and the
+ * budget) takes the first entry under VDNN_ALGO_PERF and fails with VDNN_ERR_OOM_DEVICE where that workspace does not
+ * fit, so that plans under different policies and budgets compute the same bits; only VDNN_ALGO_GREEDY moves a layer
+ * down its list (first entry whose workspace fits at that point of the step), and results then differ in rounding.
+ * vdnn_set_winograd(net, 0) takes the Winograd kernel off every list of the net. */
+typedef enum { VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2 } vdnn_conv_kernel_t;
+typedef enum { VDNN_PASS_FWD = 0, VDNN_PASS_BWD_DATA = 1, VDNN_PASS_BWD_FILTER = 2 } vdnn_conv_pass_t;
+#define VDNN_NO_KERNEL ((size_t)-1) /* vdnn_op_conv_workspace: the kernel does not apply to the shape */
 
 typedef enum {
     VDNN_CONV = 0,       /* cross-correlation, zero padding, no bias */
@@ -100,8 +111,8 @@ typedef struct {
     int32_t n_memopt_convs;       /* CONV layers running the memory-optimal algorithm in fwd or bwd */
     int32_t window_fill_pm;       /* FIT / explicit set: share of the budget (per mille) the forward transfer windows fill; 0 = static schedule */
     int32_t window_fill_bwd_pm;   /* > 0: backward fetches are issued early, while live bytes stay within that share */
-    int32_t n_winograd_convs;     /* CONV layers whose workspace holds the Winograd algorithm in fwd or bwd */
-    int32_t reserved_;
+    int32_t n_winograd_convs;     /* CONV layers that run the Winograd kernel in any pass */
+    int32_t n_downgraded_convs;   /* CONV layers that VDNN_ALGO_GREEDY moved off their performance-optimal entry in fwd or bwd */
     /* measured on the last executed step (0 until one has run) */
     double fwd_ms, bwd_ms, stall_ms, d2h_ms, h2d_ms, d2h_gbps, h2d_gbps;
 } vdnn_mem_stats_t;
@@ -124,9 +135,17 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
  * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
  * stays usable with its previous plan). */
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
-/* enabled = 0: no plan of this net uses the Winograd algorithm (default: enabled).  Takes effect at the next
+/* enabled = 0: no plan of this net uses the Winograd kernel (default: enabled).  Takes effect at the next
  * vdnn_set_policy / vdnn_set_offload_set. */
 vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
+/* The list described above, as workspace bytes: entry 0 is what VDNN_ALGO_PERF allocates for the layer's forward
+ * (bwd = 0) or backward (bwd != 0: the larger of backward-data and backward-filter) computation, the following entries
+ * are what VDNN_ALGO_GREEDY falls back to, in order.  CONV: at least one entry, the last is 0.  FC: one entry (its
+ * reduction-split partial sums).  Other layers: none.  count receives the number of entries, at most cap are written. */
+vdnn_status_t vdnn_layer_workspace_options(const vdnn_net_t*, int layer, int32_t bwd, uint64_t* bytes /*host, may be NULL*/, size_t cap,
+                                           size_t* count);
+/* The kernels (vdnn_conv_kernel_t) the current plan runs for a CONV layer's forward, backward-data and backward-filter pass. */
+vdnn_status_t vdnn_layer_kernels(const vdnn_net_t*, int layer, int32_t kernels[3] /*host*/);
 /* VDNN_POLICY_FIT goes beyond the paper.  Section 3.3 motivates vDNN_dyn by the cost of offloading more
  * than the budget asks for, and Section 3.1 by the distance between the two uses of X that a transfer can
  * hide behind; where arithmetic is fast relative to the host link, step time is simply bytes moved over
@@ -147,7 +166,7 @@ vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
  *       The forward share is the largest of 100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 % for which the
  *       blocks can be placed inside the budget (window_fill_pm in the stats; window_fill_bwd_pm = 1000 when
  *       fetches are issued early).
- * Values computed are bit-identical to every other policy.
+ * Values computed are bit-identical to every other policy (all plans of a net run the same kernels, see vdnn_conv_kernel_t).
  *
  * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
  * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
@@ -176,7 +195,8 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);
 /* Forward propagation, layers 0..L-1 (Section 2.2; offload per Section 3.2 "Memory Offload").
  * input: (device) batch*in_c*in_h*in_w floats; labels: (device) batch int32 in [0, classes).
  * Both are copied into the pool before use.  loss_out: (host) mean softmax-CE loss.
- * Returns after the forward pass has completed on the GPU. */
+ * Returns after the forward pass has completed on the GPU.  A label outside [0, classes) is never used as an index:
+ * the call then returns VDNN_ERR_INVALID_ARG after the pass (loss_out untouched, no backward pass possible). */
 vdnn_status_t vdnn_forward(vdnn_net_t*, const float* input, const int32_t* labels, float* loss_out);
 
 /* Backward propagation, layers L-1..0 (Eq. chain_rule; prefetch per Section 3.2 "Memory Prefetch").
@@ -203,6 +223,13 @@ size_t vdnn_weight_count(const vdnn_net_t*, int layer); /* 0 for layers without 
  * weight gradients.  Plain SGD on every layer: W <- W - learning_rate * dW.  Call after vdnn_backward. */
 vdnn_status_t vdnn_sgd_step(vdnn_net_t*, float learning_rate);
 size_t vdnn_output_count(const vdnn_net_t*, int layer); /* elements of the layer's output */
+
+/* Copies a layer's output as it stands at the end of forward propagation (layer = -1: the logits, i.e. the input of the
+ * loss layer); valid between a completed vdnn_forward and the vdnn_backward that follows.  An in-place ReLU shares its
+ * producer's feature map, so for both layers this is the value after the ReLU.  The copy comes from the pool, or from the
+ * pinned host arena when the current plan has offloaded that feature map.  VDNN_ERR_STATE when the feature map was released
+ * during forward propagation because no backward computation reads it (use vdnn_capture_output for those). */
+vdnn_status_t vdnn_get_output(vdnn_net_t*, int layer, float* dst /*host*/, size_t count);
 
 /* Test hooks: copy layer's output Y (right after its forward computation) / the gradient w.r.t.
  * its output dY (right before its backward computation) to a host array during the next
@@ -233,17 +260,22 @@ const char* vdnn_op_last_error(void);
  * P = (H + 2 pad - R)/stride + 1.  Asynchronous on the stream.  A tensor may have at most 2^31 - 2 elements:
  * larger shapes return VDNN_ERR_INVALID_ARG before anything is launched (vdnn_create: VDNN_ERR_UNSUPPORTED). */
 
-/* Convolution algorithms in the sense of Section 2.2's memory-optimal / performance-optimal trade-off:
- *  - no workspace: implicit GEMM whose gather works directly on W as stored (memory-optimal);
- *  - one packed copy of W (+ partial sums of split tiles): the faster implicit-GEMM kernel; applies when the reduction
+/* Convolution kernels in the sense of Section 2.2's memory-optimal / performance-optimal trade-off (vdnn_conv_kernel_t):
+ *  - GATHER: no workspace, implicit GEMM whose gather works directly on W as stored (memory-optimal);
+ *  - PACKED: one packed copy of W (+ partial sums of split tiles): the faster implicit-GEMM kernel; applies when the reduction
  *    channels are a multiple of 16, backward-data is unstrided and the tensors are below 4 GiB;
- *  - Winograd F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers, reduction channels a multiple of 16,
+ *  - WINOGRAD F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers, reduction channels a multiple of 16,
  *    at least 256 of them, output channels of the pass a multiple of 4 and at least 128 (backward-filter: input
  *    channels a multiple of 128, 256 or more output channels): transformed
  *    filter (16/9 of W) plus transformed input and products for a chunk of images (at most the chunk size below).
- * vdnn_op_conv_*_workspace() returns the bytes of the fastest algorithm that applies to the shape (0: only the first).
- * vdnn_op_conv_fwd / _bwd_data run the fastest algorithm the given workspace has room for (NULL: the first).  Results
- * agree to rounding (Winograd: a few 1e-6 of the largest output); each algorithm is deterministic. */
+ * vdnn_op_conv_workspace(pass, kernel, shape) returns the bytes that kernel needs (VDNN_NO_KERNEL: it does not apply);
+ * vdnn_op_conv_*_workspace() the bytes of the fastest kernel that applies to the shape (0: only GATHER).
+ * The three conv entry points take the kernel to run: an explicit one returns VDNN_ERR_INVALID_ARG where it does not
+ * apply or workspace_bytes is too small for it (nothing is launched); VDNN_KERNEL_AUTO runs the fastest kernel the
+ * given workspace has room for (NULL: GATHER).  Results
+ * agree to rounding (Winograd: a few 1e-6 of the largest output); each kernel is deterministic. */
+size_t vdnn_op_conv_workspace(int pass /*vdnn_conv_pass_t*/, int kernel /*vdnn_conv_kernel_t, not AUTO*/, int N, int C, int H, int W, int K,
+                              int R, int S, int stride, int pad);
 /* Process-wide chunk size of the Winograd workspace in bytes (0 restores the default, 512 MiB).  Workspace sizes and
  * plans derive from it: set it before creating nets, not while one exists. */
 void vdnn_op_set_winograd_chunk_bytes(size_t bytes);
@@ -251,13 +283,13 @@ size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int 
 size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 /* Y = conv(X, W); relu != 0 applies max(.,0) to the result in the same kernel. */
 vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
-                               int H, int W, int K, int R, int S, int stride, int pad, int relu, void* stream);
+                               int H, int W, int K, int R, int S, int stride, int pad, int relu, int kernel, void* stream);
 /* dX = sum over the forward terms that touched it (Eq. chain_rule).  relu_mask (may be NULL): a tensor of
  * dX's shape, the output of an in-place ReLU that produced X; dX is zeroed where it is not positive,
  * which is that ReLU's backward computation folded into this kernel's store. */
 vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
                                     int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
-                                    void* stream);
+                                    int kernel, void* stream);
 /* dW; the reduction over N*P*Q is split, partial sums go to workspace and are added in a fixed
  * order (deterministic, no atomics).  The workspace query returns the bytes of the fastest algorithm for the shape
  * (Winograd where the rule above admits it: the 16 accumulated products, their partial sums, and the transformed
@@ -266,7 +298,7 @@ vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, 
  * long reductions). */
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
-                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream);
+                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kernel, void* stream);
 
 /* FC: Y[N][O] = X[N][I] W[O][I]^T ; dX = dY W ; dW = dY^T X.  Same workspace rule (too little: no split). */
 size_t vdnn_op_fc_workspace(int N, int I, int O, int which /*0 fwd, 1 bwd-data, 2 bwd-filter*/);
@@ -286,7 +318,8 @@ vdnn_status_t vdnn_op_maxpool_bwd(const float* x, const float* dy, float* dx, in
                                   int pad, int relu_mask, void* stream);
 vdnn_status_t vdnn_op_avgpool_fwd(const float* x, float* y, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
 vdnn_status_t vdnn_op_avgpool_bwd(const float* dy, float* dx, int N, int C, int H, int W, int k, int stride, int pad, void* stream);
-/* loss: (device) one float, mean over the batch.  dz = (softmax(z) - onehot)/N. */
+/* loss: (device) one float, mean over the batch.  dz = (softmax(z) - onehot)/N.  A label outside [0, classes) is never
+ * used as an index: its row makes the loss NaN, and its dz has no onehot term. */
 vdnn_status_t vdnn_op_softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, void* stream);
 vdnn_status_t vdnn_op_softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, void* stream);
 /* to_big != 0 (concat forward):  big[n][c_off + c][hw] = small[n][c][hw], src = small, dst = big.

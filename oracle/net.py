@@ -51,7 +51,7 @@ def forward(net, x, labels, weights):
     return outs, loss
 
 
-def step(net, x, labels, weights, want_dx_input=False, outs_override=None):
+def step(net, x, labels, weights, want_dx_input=False, outs_override=None, dy_hook=None):
     """One forward + backward pass.  Returns dict(outs, loss, dw {layer: array}, dx {tensor id: array}).
 
     outs_override: {layer id: array} - layer outputs to run the BACKWARD pass from instead of this
@@ -59,7 +59,10 @@ def step(net, x, labels, weights, want_dx_input=False, outs_override=None):
     discrete decisions from forward values (which window element is the maximum, whether an activation
     is positive); an fp32 forward pass that differs from the fp64 one in the last bit can decide one of
     them differently, which moves a whole gradient term.  A comparison that hands the other side's
-    forward values in here makes both sides decide on the same numbers."""
+    forward values in here makes both sides decide on the same numbers.
+
+    dy_hook: called as dy_hook(layer id, dY) with the gradient with respect to each layer's output, just before
+    that layer's backward computation (observation only)."""
     x = np.asarray(x, np.float64)
     outs, loss = forward(net, x, labels, weights)
     own_outs = outs
@@ -92,6 +95,8 @@ def step(net, x, labels, weights, want_dx_input=False, outs_override=None):
             give(src, dz.reshape(a.shape))
             continue
         dy = grads.pop(i)
+        if dy_hook is not None:
+            dy_hook(i, dy)
         if t == "conv":
             dw[i] = L.conv_bwd_filter(a, dy, weights[i].shape, st, pd)
             if src >= 0 or want_dx_input:

@@ -50,7 +50,7 @@ class MemStats(C.Structure):
                 ("n_offload", C.c_int32), ("n_prefetch", C.c_int32), ("n_ondemand_fetch", C.c_int32),
                 ("effective_policy", C.c_int32), ("conv_algo", C.c_int32), ("n_memopt_convs", C.c_int32),
                 ("window_fill_pm", C.c_int32), ("window_fill_bwd_pm", C.c_int32),
-                ("n_winograd_convs", C.c_int32), ("reserved_", C.c_int32),
+                ("n_winograd_convs", C.c_int32), ("n_downgraded_convs", C.c_int32),
                 ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("stall_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double)]
 
@@ -64,6 +64,8 @@ EXPORTS = {
     "vdnn_set_policy": ([_vp, _i], _i),
     "vdnn_set_conv_algo": ([_vp, _i], _i),
     "vdnn_set_winograd": ([_vp, C.c_int32], _i),
+    "vdnn_layer_workspace_options": ([_vp, _i, C.c_int32, C.POINTER(C.c_uint64), _sz, C.POINTER(_sz)], _i),
+    "vdnn_layer_kernels": ([_vp, _i, C.POINTER(C.c_int32)], _i),
     "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32, C.c_int32], _i),
     "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
     "vdnn_set_window_part": ([_vp, _sz], _i),
@@ -79,6 +81,7 @@ EXPORTS = {
     "vdnn_sgd_step": ([_vp, C.c_float], _i),
     "vdnn_weight_count": ([_vp, _i], _sz),
     "vdnn_output_count": ([_vp, _i], _sz),
+    "vdnn_get_output": ([_vp, _i, _vp, _sz], _i),
     "vdnn_capture_output": ([_vp, _i, _vp], _i),
     "vdnn_capture_grad": ([_vp, _i, _vp], _i),
     "vdnn_trace": ([_vp, C.c_char_p, _sz, C.POINTER(_sz)], _i),
@@ -88,10 +91,11 @@ EXPORTS = {
     "vdnn_op_set_winograd_chunk_bytes": ([_sz], None),
     "vdnn_op_conv_fwd_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_data_workspace": ([_i] * 9, _sz),
-    "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
-    "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp, _vp], _i),
+    "vdnn_op_conv_workspace": ([_i] * 11, _sz),
+    "vdnn_op_conv_fwd": ([_vp] * 4 + [_sz] + [_i] * 11 + [_vp], _i),
+    "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp, _i, _vp], _i),
     "vdnn_op_conv_bwd_filter_workspace": ([_i] * 9, _sz),
-    "vdnn_op_conv_bwd_filter": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp], _i),
+    "vdnn_op_conv_bwd_filter": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
     "vdnn_op_fc_workspace": ([_i] * 4, _sz),
     "vdnn_op_fc_fwd": ([_vp] * 4 + [_sz] + [_i] * 3 + [_vp], _i),
     "vdnn_op_fc_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 3 + [_vp], _i),
@@ -167,6 +171,20 @@ class Net:
 
     def set_winograd(self, enabled):
         self._chk(lib.vdnn_set_winograd(self.h, 1 if enabled else 0))
+
+    def workspace_options(self, layer, bwd):
+        """Workspace bytes of the ways a layer can run, performance-optimal first (see vdnn_layer_workspace_options)."""
+        k = _sz(0)
+        self._chk(lib.vdnn_layer_workspace_options(self.h, layer, int(bwd), None, 0, C.byref(k)))
+        arr = (C.c_uint64 * max(k.value, 1))()
+        self._chk(lib.vdnn_layer_workspace_options(self.h, layer, int(bwd), arr, k.value, C.byref(k)))
+        return list(arr[:k.value])
+
+    def layer_kernels(self, layer):
+        """(forward, backward-data, backward-filter) kernel names of a CONV layer in the current plan."""
+        arr = (C.c_int32 * 3)()
+        self._chk(lib.vdnn_layer_kernels(self.h, layer, arr))
+        return tuple(KERNEL_NAME[v] for v in arr)
 
     def set_conv_algo(self, algo):
         """"p" (performance-optimal, workspace), "m" (memory-optimal) or "greedy"; applies at the next set_policy."""
@@ -267,6 +285,14 @@ class Net:
     def sgd_step(self, lr):
         self._chk(lib.vdnn_sgd_step(self.h, lr))
 
+    def get_output(self, layer=-1):
+        """A layer's output at the end of forward propagation (-1: the logits), as a flat fp32 array."""
+        import numpy as np
+        src = self.net["layers"][-1]["inputs"][0] if layer == -1 else layer
+        out = np.empty(self.output_count(src), np.float32)
+        self._chk(lib.vdnn_get_output(self.h, layer, out.ctypes.data, out.size))
+        return out
+
     def capture_output(self, layer, arr):
         self._chk(lib.vdnn_capture_output(self.h, layer, arr.ctypes.data if arr is not None else None))
 
@@ -320,19 +346,40 @@ def op_conv_bwd_data_workspace(x_shape, w_shape, stride, pad):
     return lib.vdnn_op_conv_bwd_data_workspace(n, c, h, wd, k, r, s, stride, pad)
 
 
-def op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None, ws=None):
+KERNEL = {"auto": -1, "gather": 0, "packed": 1, "winograd": 2}
+KERNEL_NAME = {v: k for k, v in KERNEL.items()}
+PASS = {"fwd": 0, "bwd_data": 1, "bwd_filter": 2}
+NO_KERNEL = C.c_size_t(-1).value
+
+
+def op_conv_workspace(pass_, kernel, x_shape, w_shape, stride, pad):
+    """Workspace bytes of one kernel for one pass, or None where the kernel does not apply to the shape."""
+    n, c, h, wd = x_shape
+    k, _, r, s = w_shape
+    v = lib.vdnn_op_conv_workspace(PASS[pass_], KERNEL[kernel], n, c, h, wd, k, r, s, stride, pad)
+    return None if v == NO_KERNEL else v
+
+
+def try_op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None, ws=None, kernel="auto"):
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
-    _ck(lib.vdnn_op_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride, pad,
-                             int(relu), _stream_ptr(stream)), "conv_fwd")
+    return lib.vdnn_op_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride, pad,
+                                int(relu), KERNEL[kernel], _stream_ptr(stream))
 
 
-def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None, relu_mask=None):
+def op_conv_fwd(x, w, y, stride, pad, relu=False, stream=None, ws=None, kernel="auto"):
+    _ck(try_op_conv_fwd(x, w, y, stride, pad, relu, stream, ws, kernel), "conv_fwd")
+
+
+def try_op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None, relu_mask=None, kernel="auto"):
     n, c, h, wd = dx.shape
     k, _, r, s = w.shape
-    _ck(lib.vdnn_op_conv_bwd_data(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride,
-                                  pad, relu_mask.data_ptr() if relu_mask is not None else None, _stream_ptr(stream)),
-        "conv_bwd_data")
+    return lib.vdnn_op_conv_bwd_data(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride,
+                                     pad, relu_mask.data_ptr() if relu_mask is not None else None, KERNEL[kernel], _stream_ptr(stream))
+
+
+def op_conv_bwd_data(dy, w, dx, stride, pad, stream=None, ws=None, relu_mask=None, kernel="auto"):
+    _ck(try_op_conv_bwd_data(dy, w, dx, stride, pad, stream, ws, relu_mask, kernel), "conv_bwd_data")
 
 
 def op_conv_bwd_filter_workspace(x_shape, w_shape, stride, pad):
@@ -341,12 +388,15 @@ def op_conv_bwd_filter_workspace(x_shape, w_shape, stride, pad):
     return lib.vdnn_op_conv_bwd_filter_workspace(n, c, h, wd, k, r, s, stride, pad)
 
 
-def op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None):
+def try_op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None, kernel="auto"):
     n, c, h, wd = x.shape
     k, _, r, s = dw.shape
-    _ck(lib.vdnn_op_conv_bwd_filter(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), ws.data_ptr() if ws is not None else None,
-                                    ws.numel() * ws.element_size() if ws is not None else 0, n, c, h, wd, k, r, s, stride,
-                                    pad, _stream_ptr(stream)), "conv_bwd_filter")
+    return lib.vdnn_op_conv_bwd_filter(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), *_ws_args(ws), n, c, h, wd, k, r, s, stride,
+                                       pad, KERNEL[kernel], _stream_ptr(stream))
+
+
+def op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None, kernel="auto"):
+    _ck(try_op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream, kernel), "conv_bwd_filter")
 
 
 def op_fc_workspace(n, i, o, which):

@@ -142,33 +142,66 @@ bool fold_bwd(const vdnn_net& n, int reader) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// workspace of a layer (partial sums of reduction-split GEMMs)
+// how each layer can run: kernels, workspace, cost (Section 2.2: algorithms trade workspace for speed; Section 3.3:
+// vDNN_dyn profiles them per layer)
 // ---------------------------------------------------------------------------------------------
-// direct: a CONV layer that could run the Winograd algorithm is sized for the packed-weight direct kernel instead
-size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt, bool direct) {
-    const Layer& l = n.layers[i];
-    int C, H, W;
-    shape_of(n, l.inputs[0], &C, &H, &W);
-    if (l.type == VDNN_CONV && memopt) return 0;  // the memory-optimal algorithm needs X, Y, W only
-    if (l.type == VDNN_CONV && !bwd)
-        return direct ? conv_fwd_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
-                      : conv_fwd_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
-    if (l.type == VDNN_CONV && bwd) {
+// Keeps, in ascending cost, the options that a greedy choice could ever take: one that needs at least as much
+// workspace as a cheaper one never is.
+static void sort_and_prune(std::vector<KernelOption>& v) {
+    std::stable_sort(v.begin(), v.end(), [](const KernelOption& a, const KernelOption& b) { return a.cost < b.cost; });
+    std::vector<KernelOption> keep;
+    for (const KernelOption& o : v)
+        if (keep.empty() || o.ws < keep.back().ws) keep.push_back(o);
+    v.swap(keep);
+}
+
+void build_kernel_options(vdnn_net& n) {
+    const int L = (int)n.layers.size();
+    n.options_fwd.assign(L, {});
+    n.options_bwd.assign(L, {});
+    if ((int)n.profile.size() != L) n.profile.assign(L, LayerProfile());
+    for (int i = 0; i < L; ++i) {
+        const Layer& l = n.layers[i];
+        int C, H, W;
+        shape_of(n, l.inputs[0], &C, &H, &W);
+        if (l.type == VDNN_FC) {
+            const int I = C * H * W;
+            const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
+            KernelOption f, b;
+            f.ws = fc_workspace(n.batch, I, l.out, 0);
+            b.ws = std::max(fc_workspace(n.batch, I, l.out, 2), need_dx ? fc_workspace(n.batch, I, l.out, 1) : (size_t)0);
+            n.options_fwd[i].push_back(f);
+            n.options_bwd[i].push_back(b);
+            continue;
+        }
+        if (l.type != VDNN_CONV) continue;
+        const LayerProfile& pr = n.profile[i];
+        auto ws_of = [&](int pass, int k) { return conv_workspace(pass, k, n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad); };
+        // unprofiled: Winograd before the packed-weight kernel before the gather kernel (measured on the paper's workloads)
+        auto cost_of = [&](int pass, int k) { return n.profiled && pr.conv[pass][k] >= 0 ? (double)pr.conv[pass][k] : (double)(kNumKernels - k); };
+        auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (k != kKernelWinograd || n.winograd); };
+        for (int k = 0; k < kNumKernels; ++k) {
+            if (!usable(kPassFwd, k)) continue;
+            KernelOption o;
+            o.fwd = k; o.ws = ws_of(kPassFwd, k); o.cost = cost_of(kPassFwd, k);
+            n.options_fwd[i].push_back(o);
+        }
         const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
-        const size_t dx = !need_dx ? 0
-                          : direct ? conv_bwd_data_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
-                                   : conv_bwd_data_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
-        const size_t dwb = direct ? conv_bwd_filter_packed_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad)
-                                  : conv_bwd_filter_workspace(n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
-        return std::max(dwb, dx);
+        for (int kf = 0; kf < kNumKernels; ++kf) {
+            if (!usable(kPassBwdFilter, kf)) continue;
+            for (int kd = 0; kd < kNumKernels; ++kd) {
+                if (need_dx ? !usable(kPassBwdData, kd) : kd != kKernelGather) continue;
+                KernelOption o;
+                o.bf = kf; o.bd = kd;
+                o.ws = std::max(ws_of(kPassBwdFilter, kf), need_dx ? ws_of(kPassBwdData, kd) : (size_t)0);
+                o.cost = cost_of(kPassBwdFilter, kf) + (need_dx ? cost_of(kPassBwdData, kd) : 0.0);
+                n.options_bwd[i].push_back(o);
+            }
+        }
+        sort_and_prune(n.options_fwd[i]);
+        sort_and_prune(n.options_bwd[i]);
+        // the last option is always the memory-optimal algorithm: gather kernels, no workspace
     }
-    if (l.type == VDNN_FC) {
-        const int I = C * H * W;
-        if (!bwd) return fc_workspace(n.batch, I, l.out, 0);
-        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
-        return std::max(fc_workspace(n.batch, I, l.out, 2), need_dx ? fc_workspace(n.batch, I, l.out, 1) : (size_t)0);
-    }
-    return 0;
 }
 
 bool selected(const vdnn_net& n, int b, int policy) {
@@ -195,7 +228,7 @@ size_t baseline_bytes(const vdnn_net& n) {
     }
     for (int i = 0; i < L; ++i) {
         if (n.layers[i].wcount) wb += 2 * align_up(n.layers[i].wcount * 4);
-        wmax = std::max(wmax, std::max(layer_workspace(n, i, false), layer_workspace(n, i, true)));
+        if (!n.options_fwd[i].empty()) wmax = std::max(wmax, std::max(n.options_fwd[i][0].ws, n.options_bwd[i][0].ws));
     }
     return fm + wb + 2 * gmax + align_up(wmax);
 }

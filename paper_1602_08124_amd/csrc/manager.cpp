@@ -89,7 +89,7 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
     switch (l.type) {
         case VDNN_CONV:
             HIPCHK(conv_fwd(x, blk(n, n.plan.w_block[o.layer]), y, blk(n, o.ws_block), wsb0, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
-                            fold_fwd(n, o.layer) ? 1 : 0, n.sc));
+                            fold_fwd(n, o.layer) ? 1 : 0, o.kern[0], n.sc));
             break;
         case VDNN_RELU:
             if (l.fwd_folded_into >= 0 && fold_fwd(n, l.fwd_folded_into)) break;  // done in the conv's epilogue
@@ -113,7 +113,9 @@ static vdnn_status_t run_fwd(vdnn_net& n, const Op& o) {
             break;
         }
         case VDNN_SOFTMAX_CE:
-            HIPCHK(softmax_ce_fwd(x, (const int32_t*)blk(n, n.plan.labels_block), blk(n, n.plan.loss_block), N, C * H * W, n.sc));
+            // the loss block is 256 bytes: the loss in its first word, the count of out-of-range labels in its second
+            HIPCHK(softmax_ce_fwd(x, (const int32_t*)blk(n, n.plan.labels_block), blk(n, n.plan.loss_block), (int32_t*)blk(n, n.plan.loss_block) + 1, N,
+                                  C * H * W, n.sc));
             break;
     }
     return VDNN_OK;
@@ -130,9 +132,9 @@ static vdnn_status_t run_bwd(vdnn_net& n, const Op& o) {
     const size_t wsb = o.ws_block >= 0 ? n.plan.blocks[o.ws_block].bytes : 0;
     switch (l.type) {
         case VDNN_CONV:
-            HIPCHK(conv_bwd_filter(x, dy, blk(n, n.plan.dw_block[o.layer]), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, n.sc));
+            HIPCHK(conv_bwd_filter(x, dy, blk(n, n.plan.dw_block[o.layer]), blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, o.kern[2], n.sc));
             if (dx) HIPCHK(conv_bwd_data(dy, blk(n, n.plan.w_block[o.layer]), dx, blk(n, o.ws_block), wsb, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad,
-                                         fold_bwd(n, o.layer) ? x : nullptr, n.sc));
+                                         fold_bwd(n, o.layer) ? x : nullptr, o.kern[1], n.sc));
             break;
         case VDNN_RELU:
             if (l.bwd_folded_into >= 0 && fold_bwd(n, l.bwd_folded_into)) break;  // done in the reader's dX store
@@ -313,6 +315,7 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc, size_t gpu_mem_budget, vd
     vdnn_status_t s = build_graph(*n, desc, err);
     if (s != VDNN_OK) { delete n; return s; }
     n->budget = gpu_mem_budget;
+    build_kernel_options(*n);
     n->baseline = baseline_bytes(*n);
     s = plan_policy(*n, VDNN_POLICY_NONE);
     // A network that does not fit without offloading is still a valid object: the caller is
@@ -331,6 +334,7 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t* n, vdnn_conv_algo_t algo) {
 vdnn_status_t vdnn_set_winograd(vdnn_net_t* n, int32_t enabled) {
     if (!n) return VDNN_ERR_INVALID_ARG;
     n->winograd = enabled != 0;
+    build_kernel_options(*n);
     return VDNN_OK;
 }
 
@@ -460,6 +464,31 @@ vdnn_status_t vdnn_sgd_step(vdnn_net_t* np, float learning_rate) {
     return VDNN_OK;
 }
 
+vdnn_status_t vdnn_get_output(vdnn_net_t* np, int layer, float* dst, size_t count) {
+    if (!np || !dst) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    const int L = (int)n.layers.size();
+    if (layer == -1) layer = n.layers[L - 1].inputs[0];  // the logits: what the loss layer reads
+    if (layer < 0 || layer >= L || n.layers[layer].type == VDNN_SOFTMAX_CE || count != vdnn_output_count(np, layer)) {
+        n.err = "get_output: wrong layer or count";
+        return VDNN_ERR_INVALID_ARG;
+    }
+    if (!n.fwd_done) { n.err = "get_output: only between a completed forward pass and the backward pass that follows it"; return VDNN_ERR_STATE; }
+    const int b = n.layers[layer].buf;
+    const Plan& p = n.plan;
+    // where the feature map is at the end of forward propagation: in the pinned arena when the plan offloads it, else in the
+    // block that is still live when backward propagation starts
+    int dev_block = -1, host_block = -1;
+    for (int t = p.first_fwd_op; t < p.first_bwd_op; ++t)
+        if (p.ops[t].kind == OP_OFFLOAD && p.ops[t].buf == b) host_block = p.ops[t].block;
+    for (int id = 0; id < (int)p.blocks.size() && host_block < 0; ++id)
+        if (p.blocks[id].buf == b && !p.blocks[id].persistent && p.blocks[id].t0 < p.first_bwd_op && p.blocks[id].t1 > p.first_bwd_op) dev_block = id;
+    if (host_block >= 0) memcpy(dst, n.pinned + p.blocks[host_block].host_off, count * 4);
+    else if (dev_block >= 0) HIPCHK(hipMemcpy(dst, blk(n, dev_block), count * 4, hipMemcpyDeviceToHost));
+    else { n.err = fmt("get_output: the output of layer %d was released during forward propagation (no backward computation reads it)", layer); return VDNN_ERR_STATE; }
+    return VDNN_OK;
+}
+
 vdnn_status_t vdnn_capture_output(vdnn_net_t* n, int layer, float* dst) {
     if (!n || layer < 0 || layer >= (int)n->layers.size()) return VDNN_ERR_INVALID_ARG;
     n->cap_out[layer] = dst;
@@ -490,10 +519,15 @@ vdnn_status_t vdnn_forward(vdnn_net_t* np, const float* input, const int32_t* la
     HIPCHK(hipEventRecord(n.events[n.ev_f1], n.sc));
     HIPCHK(hipStreamSynchronize(n.sc));
     HIPCHK(hipStreamSynchronize(n.sm));
-    float loss = 0.f;
-    HIPCHK(hipMemcpy(&loss, blk(n, n.plan.loss_block), 4, hipMemcpyDeviceToHost));
+    struct { float loss; int32_t bad_labels; } res = {0.f, 0};
+    HIPCHK(hipMemcpy(&res, blk(n, n.plan.loss_block), sizeof res, hipMemcpyDeviceToHost));
+    const float loss = res.loss;
     s = finish_timing(n, false);
     if (s != VDNN_OK) return s;
+    if (res.bad_labels) {
+        n.err = fmt("%d of the %d labels are outside [0, classes)", res.bad_labels, n.batch);
+        return VDNN_ERR_INVALID_ARG;
+    }
     if (loss_out) *loss_out = loss;
     n.fwd_done = true;
     return VDNN_OK;
@@ -539,6 +573,7 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
         s.conv_algo = p.algo;
         s.n_memopt_convs = p.n_memopt;
         s.n_winograd_convs = p.n_winograd;
+        s.n_downgraded_convs = p.n_downgraded;
         s.window_fill_pm = p.fill_pm;
         s.window_fill_bwd_pm = p.fill_bwd_pm;
     }
@@ -547,6 +582,22 @@ vdnn_status_t vdnn_mem_stats(const vdnn_net_t* n, vdnn_mem_stats_t* out) {
     s.d2h_gbps = n->d2h_ms > 0 ? (double)p.offloaded / (n->d2h_ms * 1e6) : 0.0;
     s.h2d_gbps = n->h2d_ms > 0 ? (double)p.prefetched / (n->h2d_ms * 1e6) : 0.0;
     *out = s;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_layer_workspace_options(const vdnn_net_t* n, int layer, int32_t bwd, uint64_t* bytes, size_t cap, size_t* count) {
+    if (!n || !count || layer < 0 || layer >= (int)n->layers.size()) return VDNN_ERR_INVALID_ARG;
+    const std::vector<KernelOption>& v = (bwd ? n->options_bwd : n->options_fwd)[layer];
+    for (size_t k = 0; k < v.size() && k < cap && bytes; ++k) bytes[k] = v[k].ws;
+    *count = v.size();
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_layer_kernels(const vdnn_net_t* n, int layer, int32_t kernels[3]) {
+    if (!n || !kernels || layer < 0 || layer >= (int)n->layers.size() || n->layers[layer].type != VDNN_CONV) return VDNN_ERR_INVALID_ARG;
+    if (!n->plan.ok) return VDNN_ERR_STATE;
+    const KernelOption &f = n->options_fwd[layer][n->plan.opt_fwd[layer]], &b = n->options_bwd[layer][n->plan.opt_bwd[layer]];
+    kernels[0] = f.fwd; kernels[1] = b.bd; kernels[2] = b.bf;
     return VDNN_OK;
 }
 

@@ -72,6 +72,22 @@ struct Op {
     std::vector<int> gout_blocks;  // dX per input (-1 = not needed); a temp block when accumulate is set
     std::vector<int> gacc_blocks;  // when >= 0: add gout_blocks[i] into this block afterwards
     int ws_block = -1;
+    int kern[3] = {0, 0, 0};       // CONV: the kernel of forward / backward-data / backward-filter (ops.h)
+};
+
+// One way to run a CONV layer's forward computation (fwd) or its backward computation (bd + bf, which share one
+// workspace block): the kernels, the workspace they need and what they cost (milliseconds once the layer has
+// been profiled, a rank before).  Section 3.3: the profiled algorithms of a layer, fastest first.
+struct KernelOption {
+    int fwd = 0, bd = 0, bf = 0;
+    size_t ws = 0;
+    double cost = 0.0;
+};
+
+// Section 3.3, "Dynamic vDNN": what the profiling passes measure.  Times in milliseconds, < 0 = not measured.
+struct LayerProfile {
+    float conv[3][3] = {{-1, -1, -1}, {-1, -1, -1}, {-1, -1, -1}};  // CONV: [pass][kernel]
+    float fwd = -1, bwd = -1;                                        // every layer: the kernels its plan entry runs
 };
 
 struct Block {
@@ -115,9 +131,11 @@ struct Plan {
     int labels_block = -1, loss_block = -1;
     std::vector<int> w_block, dw_block;  // per layer: persistent blocks of W and dW (-1 for layers without weights)
     int algo = 0;                        // vdnn_conv_algo_t the plan was compiled with
-    std::vector<char> memopt_fwd, memopt_bwd;  // per layer: CONV runs the no-workspace algorithm
+    std::vector<char> memopt_fwd, memopt_bwd;  // per layer: the mode (memory-optimal, or a greedy downgrade) put the CONV layer on the no-workspace kernel
+    std::vector<int> opt_fwd, opt_bwd;   // per CONV layer: index of the KernelOption the plan runs (-1 elsewhere)
     int n_memopt = 0;
-    int n_winograd = 0;                  // CONV layers whose fwd or bwd workspace is sized for the Winograd algorithm
+    int n_downgraded = 0;                // CONV layers that the greedy mode moved off their performance-optimal option in fwd or bwd
+    int n_winograd = 0;                  // CONV layers that run the Winograd kernel in any pass
     std::vector<char> offload_set;  // buffer id + 1 -> this step offloads it
     int fill_pm = 0, fill_bwd_pm = 0;  // share of the budget (per mille) the transfer windows may fill in forward / backward; 0 = static schedule
 };
@@ -132,7 +150,14 @@ struct vdnn_net {
     size_t part_bytes = (size_t)128 << 20;  // transfer windows move larger blocks in pieces of about this size (0 = whole blocks)
     int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
     int static_algo = VDNN_ALGO_PERF;
-    bool winograd = true;  // plans may size wide 3x3 layers for the Winograd algorithm
+    bool winograd = true;  // the Winograd kernel is among the options of wide 3x3 layers
+    // Per layer, how it can run, preference order (first = performance-optimal, last of a CONV layer = memory-optimal, no
+    // workspace).  Every plan of the net takes its kernels from here, so that plans under different policies and budgets
+    // compute the same bits; only the greedy mode (Section 3.3, phase 3) moves a layer down its list.
+    std::vector<std::vector<vdnn::KernelOption>> options_fwd, options_bwd;
+    std::vector<vdnn::LayerProfile> profile;
+    bool profiled = false;
+    double link_d2h_gbps = 0.0, link_h2d_gbps = 0.0;  // measured by the profiling pass (0: not measured)
     vdnn::Plan plan;
     size_t baseline = 0;
 
@@ -197,7 +222,7 @@ inline void shape_of(const vdnn_net& n, int layer, int* C, int* H, int* W) {
 vdnn_status_t build_graph(vdnn_net& n, const vdnn_net_desc_t* d, std::string& err);
 bool fold_fwd(const vdnn_net& n, int conv);     // the conv applies the ReLU living in its output
 bool fold_bwd(const vdnn_net& n, int reader);   // the reader applies the backward of the ReLU living in its input
-size_t layer_workspace(const vdnn_net& n, int i, bool bwd, bool memopt = false, bool direct = false);
+void build_kernel_options(vdnn_net& n);  // from shapes, n.winograd and, when there is one, the profile
 bool selected(const vdnn_net& n, int b, int policy);
 size_t baseline_bytes(const vdnn_net& n);
 

@@ -35,17 +35,24 @@ size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R,
     return conv_bwd_data_workspace(N, C, H, W, K, R, S, stride, pad);
 }
 
+size_t vdnn_op_conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (!conv_ok(N, C, H, W, K, R, S, stride, pad) || pass < 0 || pass > 2) return VDNN_NO_KERNEL;
+    return conv_workspace(pass, kernel, N, C, H, W, K, R, S, stride, pad);
+}
+
+static bool kernel_ok(int kernel) { return kernel >= VDNN_KERNEL_AUTO && kernel <= VDNN_KERNEL_WINOGRAD; }
+
 vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
-                               int H, int W, int K, int R, int S, int stride, int pad, int relu, void* stream) {
-    if (!x || !w || !y || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_fwd(x, w, y, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu, (hipStream_t)stream));
+                               int H, int W, int K, int R, int S, int stride, int pad, int relu, int kernel, void* stream) {
+    if (!x || !w || !y || !conv_ok(N, C, H, W, K, R, S, stride, pad) || !kernel_ok(kernel)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_fwd(x, w, y, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu, kernel, (hipStream_t)stream));
 }
 
 vdnn_status_t vdnn_op_conv_bwd_data(const float* dy, const float* w, float* dx, void* workspace, size_t workspace_bytes, int N,
                                     int C, int H, int W, int K, int R, int S, int stride, int pad, const float* relu_mask,
-                                    void* stream) {
-    if (!dy || !w || !dx || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_bwd_data(dy, w, dx, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu_mask, (hipStream_t)stream));
+                                    int kernel, void* stream) {
+    if (!dy || !w || !dx || !conv_ok(N, C, H, W, K, R, S, stride, pad) || !kernel_ok(kernel)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_bwd_data(dy, w, dx, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, relu_mask, kernel, (hipStream_t)stream));
 }
 
 size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
@@ -54,9 +61,9 @@ size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int 
 }
 
 vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
-                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, void* stream) {
-    if (!x || !dy || !dw || !conv_ok(N, C, H, W, K, R, S, stride, pad)) return VDNN_ERR_INVALID_ARG;
-    return st(conv_bwd_filter(x, dy, dw, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, (hipStream_t)stream));
+                                      int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kernel, void* stream) {
+    if (!x || !dy || !dw || !conv_ok(N, C, H, W, K, R, S, stride, pad) || !kernel_ok(kernel)) return VDNN_ERR_INVALID_ARG;
+    return st(conv_bwd_filter(x, dy, dw, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, kernel, (hipStream_t)stream));
 }
 
 size_t vdnn_op_fc_workspace(int N, int I, int O, int which) {
@@ -119,7 +126,7 @@ vdnn_status_t vdnn_op_avgpool_bwd(const float* dy, float* dx, int N, int C, int 
 
 vdnn_status_t vdnn_op_softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, void* stream) {
     if (!z || !labels || !loss || N <= 0 || classes <= 0) return VDNN_ERR_INVALID_ARG;
-    return st(softmax_ce_fwd(z, labels, loss, N, classes, (hipStream_t)stream));
+    return st(softmax_ce_fwd(z, labels, loss, nullptr, N, classes, (hipStream_t)stream));
 }
 
 vdnn_status_t vdnn_op_softmax_ce_bwd(const float* z, const int32_t* labels, float* dz, int N, int classes, void* stream) {

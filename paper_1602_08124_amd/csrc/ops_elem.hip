@@ -440,11 +440,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One workgroup; each wavefront takes rows wave, wave + nw, ...; the per-wave partial losses are
 // added by one thread in wave order, so the result does not depend on scheduling.
+// A label outside [0, classes) reads nothing: its row contributes NaN to the loss, and the number of such rows goes
+// to *bad when the caller gave a place for it.
 __global__ __launch_bounds__(1024) void softmax_ce_fwd_kernel(const float* __restrict__ z, const int32_t* __restrict__ labels,
-                                                               float* __restrict__ loss, int N, int classes) {
+                                                               float* __restrict__ loss, int32_t* __restrict__ bad, int N, int classes) {
     __shared__ float part[16];
+    __shared__ int nbad[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     float wloss = 0.f;
+    int wbad = 0;
     for (int n = wave; n < N; n += nw) {
         const float* row = z + (size_t)n * classes;
         float m = -INFINITY;
@@ -453,14 +457,19 @@ __global__ __launch_bounds__(1024) void softmax_ce_fwd_kernel(const float* __res
         float s = 0.f;
         for (int j = lane; j < classes; j += 64) s += expf(row[j] - m);
         s = wave_sum(s);
-        wloss += m + logf(s) - row[labels[n]];
+        const int lab = labels[n];
+        const bool ok = lab >= 0 && lab < classes;
+        wbad += !ok;
+        wloss += m + logf(s) - (ok ? row[lab] : NAN);
     }
-    if (lane == 0) part[wave] = wloss;
+    if (lane == 0) { part[wave] = wloss; nbad[wave] = wbad; }
     __syncthreads();
     if (threadIdx.x == 0) {
         float t = 0.f;
-        for (int w = 0; w < nw; ++w) t += part[w];
+        int b = 0;
+        for (int w = 0; w < nw; ++w) { t += part[w]; b += nbad[w]; }
         *loss = t / (float)N;
+        if (bad) *bad = b;
     }
 }
 
@@ -483,9 +492,9 @@ __global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const float* __rest
     for (int j = lane; j < classes; j += 64) out[j] = (expf(row[j] - lse) - (j == lab ? 1.f : 0.f)) * invn;
 }
 
-hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int N, int classes, hipStream_t st) {
+hipError_t softmax_ce_fwd(const float* z, const int32_t* labels, float* loss, int32_t* bad_labels, int N, int classes, hipStream_t st) {
     if (N <= 0 || classes <= 0) return hipErrorInvalidValue;
-    VDNN_LAUNCH(softmax_ce_fwd_kernel, dim3(1), dim3(1024), 0, st, z, labels, loss, N, classes);
+    VDNN_LAUNCH(softmax_ce_fwd_kernel, dim3(1), dim3(1024), 0, st, z, labels, loss, bad_labels, N, classes);
     return hipGetLastError();
 }
 

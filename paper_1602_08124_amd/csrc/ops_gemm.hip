@@ -2,12 +2,24 @@
 // (implicit GEMM on fp32 MFMA, Section 2.2's "memory-optimal" algorithm: X, Y, W only) and the
 // three FC products.  Reductions that would leave the chip idle are split across workgroups;
 // partial sums go to a caller-provided workspace and are added in a fixed order.
+#include <atomic>
+
 #include "conv_fast.h"
 #include "winograd.h"
 #include "gemm_tile.h"
 #include "ops.h"
 
 namespace vdnn {
+
+// A kernel that wants more than the default dynamic LDS size has to be told so once.  The entry points are process-wide,
+// so the "already done" flag of each kernel instantiation is atomic; two threads that both find it unset both set the same
+// attribute value, which is harmless.
+static hipError_t allow_smem(std::atomic<bool>& done, const void* kern, size_t smem) {
+    if (done.load(std::memory_order_acquire)) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) done.store(true, std::memory_order_release);
+    return e;
+}
 
 // -------------------------------------------------------------------------------------------
 // split heuristic (shared by the workspace query and the launch)
@@ -80,12 +92,8 @@ static hipError_t launch_tile(const typename LA::Params& pa, const typename LB::
                               int ktot, int splits, hipStream_t st) {
     auto kern = gemm_tile_kernel<BM, BN, BK, WM, WN, PADA, PADB, LA, LB, EP>;
     constexpr size_t smem = gemm_smem_bytes<BM, BN, BK, PADA, PADB>();
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<bool> attr_set{false};  // per instantiation
+    if (hipError_t e = allow_smem(attr_set, (const void*)kern, smem); e != hipSuccess) return e;
     GridInfo gi;
     gi.tiles_m = cdiv(rows, BM);
     gi.tiles_n = cdiv(cols, BN);
@@ -177,14 +185,9 @@ static hipError_t conv_fast_cfg(ConvFastParams& p, const TailSplit& ts, float* p
     auto kern = conv_fast_kernel<BM, BN, WM, WN, false, QUAD>;
     auto kern_split = conv_fast_kernel<BM, BN, WM, WN, true, QUAD>;
     constexpr size_t smem = sizeof(float) * 2 * 16 * ((BM + kConvFastPad<BN>) + (BN + kConvFastPad<BN>));
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)kern_split, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<bool> attr_set{false}, attr_set_split{false};
+    if (hipError_t e = allow_smem(attr_set, (const void*)kern, smem); e != hipSuccess) return e;
+    if (hipError_t e = allow_smem(attr_set_split, (const void*)kern_split, smem); e != hipSuccess) return e;
     p.tiles_m = cdiv(p.rows, BM);
     p.tiles_n = cdiv(p.M, BN);
     if ((long long)p.tiles_m * p.tiles_n != (long long)ts.full_tiles + ts.tail_tiles) return hipErrorInvalidValue;
@@ -354,8 +357,51 @@ size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, 
     return packed;
 }
 
+static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K);
+
+// Bytes of workspace a kernel needs for a pass over the shape; kNoKernel where that kernel does not apply.
+size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (kernel == kKernelGather) return 0;  // works on X, Y and W as stored, for every shape
+    if (kernel != kKernelPacked && kernel != kKernelWinograd) return kNoKernel;
+    if (pass == kPassFwd) {
+        const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+        if (!packed) return kNoKernel;
+        if (kernel == kKernelPacked) return packed;
+        return wino_ok(N, C, H, W, K, R, S, stride, pad) ? wino_workspace(N, C, H, W, K) : kNoKernel;
+    }
+    if (pass == kPassBwdData) {
+        const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+        if (!packed) return kNoKernel;
+        if (kernel == kKernelPacked) return packed;
+        return wino_ok(N, K, H, W, C, R, S, stride, pad) ? wino_workspace(N, K, H, W, C) : kNoKernel;
+    }
+    if (pass == kPassBwdFilter) {
+        if (kernel == kKernelWinograd) return wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) ? wino_bwdf_workspace(N, C, H, W, K) : kNoKernel;
+        const size_t split = conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+        return split ? split : kNoKernel;  // no split and no tap-major staging: the same launch as the gather kernel
+    }
+    return kNoKernel;
+}
+
+// kernel == kKernelAuto: the fastest kernel whose workspace the caller's has room for.  Otherwise exactly that kernel;
+// hipErrorInvalidValue when it does not apply to the shape or the workspace is too small for it.
+static int resolve_kernel(int pass, int kernel, const void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
+                          int pad) {
+    if (kernel == kKernelAuto) {
+        for (int k : {kKernelWinograd, kKernelPacked}) {
+            const size_t need = conv_workspace(pass, k, N, C, H, W, K, R, S, stride, pad);
+            if (need != kNoKernel && ws && ws_bytes >= need) return k;
+        }
+        return kKernelGather;
+    }
+    const size_t need = conv_workspace(pass, kernel, N, C, H, W, K, R, S, stride, pad);
+    if (need == kNoKernel || (need && (!ws || ws_bytes < need))) return -2;
+    return kernel;
+}
+
 hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
-                    int pad, int relu, hipStream_t st) {
+                    int pad, int relu, int kernel, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
@@ -365,11 +411,10 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
     wa.fd_rs = make_fastdiv(1);
     ConvOut eo;
     eo.out = y; eo.mask = nullptr; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
-    // the fastest algorithm the given workspace has room for
-    const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (packed && ws && wino_ok(N, C, H, W, K, R, S, stride, pad) && ws_bytes >= wino_workspace(N, C, H, W, K))
-        return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, st);
-    if (packed && ws && ws_bytes >= packed) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
+    const int use = resolve_kernel(kPassFwd, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
+    if (use == -2) return hipErrorInvalidValue;
+    if (use == kKernelWinograd) return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, st);
+    if (use == kKernelPacked) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
 }
 
@@ -403,10 +448,12 @@ __global__ void conv_bwd_data_direct_kernel(const float* __restrict__ dy, const 
 }
 
 hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
-                         int pad, const float* relu_mask, hipStream_t st) {
+                         int pad, const float* relu_mask, int kernel, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
+    const int use = resolve_kernel(kPassBwdData, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
+    if (use == -2) return hipErrorInvalidValue;
     if (stride != 1 || pad > R - 1 || pad > S - 1) {
         const size_t total = (size_t)N * C * H * W;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 65535 * 4);
@@ -422,11 +469,8 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
     eo.out = dx; eo.mask = relu_mask; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
-    const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (packed && ws && wino_ok(N, K, H, W, C, R, S, stride, pad) && ws_bytes >= wino_workspace(N, K, H, W, C))
-        return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, st);
-    if (packed && ws && ws_bytes >= packed)
-        return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
+    if (use == kKernelWinograd) return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, st);
+    if (use == kKernelPacked) return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
     return conv_gemm(wa, g, eo, st);
 }
 
@@ -489,12 +533,8 @@ static hipError_t bwdf_fast_cfg(BwdFilterFastParams& p, hipStream_t st) {
     auto kern = conv_bwdf_fast_kernel<BM, BN, WM, WN, BK, TAPS>;
     constexpr int PAD = BK >= 32 ? 1 : 32 / BK;  // as in the kernel
     constexpr size_t smem = sizeof(float) * 2 * BK * ((BM + PAD) + (BN + PAD));
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<bool> attr_set{false};
+    if (hipError_t e = allow_smem(attr_set, (const void*)kern, smem); e != hipSuccess) return e;
     p.tiles_m = cdiv(p.K, BM);
     p.tiles_n = p.C * p.R * p.S / BN;
     p.ksplit = cdiv(cdiv(p.M, p.splits), BK) * BK;
@@ -553,17 +593,16 @@ static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw,
 }
 
 hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
-                           int K, int R, int S, int stride, int pad, hipStream_t st) {
+                           int K, int R, int S, int stride, int pad, int kernel, hipStream_t st) {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     if (P <= 0 || Q <= 0) return hipErrorInvalidValue;
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
-    // the fastest algorithm the given workspace has room for
-    if (ws && wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) && ws_bytes >= wino_bwdf_workspace(N, C, H, W, K))
-        return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, st);
+    const int use = resolve_kernel(kPassBwdFilter, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
+    if (use == -2) return hipErrorInvalidValue;
+    if (use == kKernelWinograd) return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, st);
     const int CRS = C * R * S;
     int splits = bwdf_splits(N, C, H, W, K, R, S, P, Q);
-    const size_t need_ws = conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
-    const bool have_ws = ws && ws_bytes >= need_ws;
+    const bool have_ws = use == kKernelPacked;
     if (!have_ws) splits = 1;  // memory-optimal algorithm: no workspace, the whole reduction in one workgroup per tile
     if (have_ws && bwdf_fast_ok(N, C, H, W, K, P, Q)) {
         BwdFilterFastParams fp;

@@ -228,10 +228,10 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
     p = Plan();
     p.policy = policy;
     p.algo = algo;
-    p.memopt_fwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
-    p.memopt_bwd.assign(n.layers.size(), algo == VDNN_ALGO_MEM);
-    std::vector<char> wino(n.layers.size(), 0);  // CONV layers given the Winograd workspace in either pass
-    const bool set_offloads = offload_set && std::find(offload_set->begin(), offload_set->end(), (char)1) != offload_set->end();
+    p.memopt_fwd.assign(n.layers.size(), 0);
+    p.memopt_bwd.assign(n.layers.size(), 0);
+    p.opt_fwd.assign(n.layers.size(), -1);
+    p.opt_bwd.assign(n.layers.size(), -1);
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     Compiler c(n, p, budget);
     const int L = (int)n.layers.size();
@@ -242,6 +242,16 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
     std::vector<int> w_block(L, -1), dw_block(L, -1);
     size_t pinned = 0;
     std::vector<size_t> host_off(L + 1, 0);
+    // Which of a layer's options runs (Section 3.3): the performance-optimal one (the first), the memory-optimal one
+    // (the last: no workspace), or, greedy, the first whose workspace fits the budget at this point of the step.
+    auto choose = [&](const std::vector<KernelOption>& opts) -> int {
+        if (opts.empty()) return -1;
+        if (algo == VDNN_ALGO_MEM) return (int)opts.size() - 1;
+        if (algo == VDNN_ALGO_GREEDY)
+            for (size_t k = 0; k < opts.size(); ++k)
+                if (!opts[k].ws || c.live + align_up(opts[k].ws) <= budget) return (int)k;
+        return 0;
+    };
 
 #define CHECK_FAIL() do { if (c.failed) return; } while (0)
 
@@ -275,13 +285,12 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         c.emit(OP_SAMPLE);
         c.samples.push_back(c.live);
         if (!in_place(l.type) && l.type != VDNN_SOFTMAX_CE) { res[i + 1] = c.alloc(fmt("B%d", i), n.B(i).count * 4); CHECK_FAIL(); p.blocks[res[i + 1]].buf = i; }
-        size_t ws = layer_workspace(n, i, false, p.memopt_fwd[i]);
-        // The Winograd algorithm runs where its workspace fits at this point; elsewhere the layer keeps the direct kernel.
-        // With an explicit, non-empty offload set the forward pass keeps the direct kernel everywhere: it runs at the pace of the
-        // offloads, which wait in memory for their copies, and a large workspace would only force them out earlier.
-        if (ws && l.type == VDNN_CONV && (!n.winograd || set_offloads || c.live + align_up(ws) > budget)) ws = layer_workspace(n, i, false, p.memopt_fwd[i], true);
-        if (l.type == VDNN_CONV && ws > layer_workspace(n, i, false, p.memopt_fwd[i], true)) wino[i] = 1;
-        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_fwd[i] = 1; ws = 0; }
+        const int pick = choose(n.options_fwd[i]);
+        const size_t ws = pick >= 0 ? n.options_fwd[i][pick].ws : 0;
+        if (l.type == VDNN_CONV) {
+            p.opt_fwd[i] = pick;
+            p.memopt_fwd[i] = algo == VDNN_ALGO_MEM || (pick > 0 && pick == (int)n.options_fwd[i].size() - 1);
+        }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
         std::vector<int> in_bufs;
@@ -305,6 +314,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
             for (int b : in_bufs) o.in_blocks.push_back(res[b + 1]);
             o.out_block = res[l.buf + 1];
             o.ws_block = wsb;
+            if (l.type == VDNN_CONV) o.kern[0] = n.options_fwd[i][pick].fwd;
         }
         if (wsb >= 0) c.release(wsb);
         for (int b : offloaded_at[i]) {
@@ -366,10 +376,12 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
                 else { const int t = c.alloc(fmt("T%d", b), n.B(b).count * 4); CHECK_FAIL(); temps.push_back(t); gout[k] = t; gacc[k] = grad[b + 1]; }
             }
         }
-        size_t ws = layer_workspace(n, m, true, p.memopt_bwd[m]);
-        if (ws && l.type == VDNN_CONV && (!n.winograd || c.live + align_up(ws) > budget)) ws = layer_workspace(n, m, true, p.memopt_bwd[m], true);
-        if (l.type == VDNN_CONV && ws > layer_workspace(n, m, true, p.memopt_bwd[m], true)) wino[m] = 1;
-        if (ws && l.type == VDNN_CONV && algo == VDNN_ALGO_GREEDY && c.live + align_up(ws) > budget) { p.memopt_bwd[m] = 1; ws = 0; }
+        const int pick = choose(n.options_bwd[m]);
+        const size_t ws = pick >= 0 ? n.options_bwd[m][pick].ws : 0;
+        if (l.type == VDNN_CONV) {
+            p.opt_bwd[m] = pick;
+            p.memopt_bwd[m] = algo == VDNN_ALGO_MEM || (pick > 0 && pick == (int)n.options_bwd[m].size() - 1);
+        }
         int wsb = -1;
         if (ws) { wsb = c.alloc("WS", ws); CHECK_FAIL(); p.max_ws = std::max(p.max_ws, ws); }
         {
@@ -378,6 +390,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
             o.out_block = l.type == VDNN_SOFTMAX_CE ? -1 : res[l.buf + 1];
             o.gin_block = l.type == VDNN_SOFTMAX_CE ? -1 : grad[l.buf + 1];
             o.gout_blocks = gout; o.gacc_blocks = gacc; o.ws_block = wsb;
+            if (l.type == VDNN_CONV) { o.kern[1] = n.options_bwd[m][pick].bd; o.kern[2] = n.options_bwd[m][pick].bf; }
         }
         if (wsb >= 0) c.release(wsb);
         for (int t : temps) c.release(t);
@@ -398,7 +411,12 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         for (int b : offloaded_at[i]) p.offload_set[b + 1] = 1;
     for (int i = 0; i < L; ++i)
         if (n.layers[i].type == VDNN_CONV && (p.memopt_fwd[i] || p.memopt_bwd[i])) p.n_memopt++;
-    for (int i = 0; i < L; ++i) p.n_winograd += wino[i];
+    for (int i = 0; i < L; ++i) {
+        if (n.layers[i].type != VDNN_CONV) continue;
+        const KernelOption &f = n.options_fwd[i][p.opt_fwd[i]], &b = n.options_bwd[i][p.opt_bwd[i]];
+        p.n_winograd += f.fwd == kKernelWinograd || b.bd == kKernelWinograd || b.bf == kKernelWinograd;
+        p.n_downgraded += algo == VDNN_ALGO_GREEDY && (p.opt_fwd[i] > 0 || p.opt_bwd[i] > 0);
+    }
     if (place) finish_plan(n, p, fill_pm, fill_bwd_pm);
     else p.ok = true;
 }

@@ -13,6 +13,7 @@ from oracle import memsched as ms
 from synth import gen, nets
 from tests.gpu_util import TOL, dev, host
 from tests.sampled import sampled_conv_bwd_data_check, sampled_conv_bwd_filter_check, sampled_conv_fwd_check
+from tests.sched_util import check_schedule, lib_ws
 
 pytestmark = pytest.mark.gpu
 G = 1 << 30
@@ -84,12 +85,14 @@ def test_conv_layer_full_size(B, cfg):
         assert abs(a - b) < bound
 
 
-def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=False):
-    """winograd=False: every plan keeps the direct convolution kernel, so that runs under different budgets use the same
-    arithmetic and can be compared bit by bit (which layers get the Winograd workspace depends on the budget)."""
+def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=True):
+    """The library's default settings unless winograd=False (no plan uses the Winograd kernel)."""
     n = B.Net(net, budget)
     n.set_winograd(winograd)
     n.set_policy(policy)
+    if policy == "fit" and budget:
+        st = n.stats()
+        check_schedule(net, n.trace(), st["pool_extent_bytes"], n.offload_set(), st["persistent_bytes"])
     n.attach_torch()
     for i, w in weights.items():
         n.set_weights(i, w)
@@ -101,14 +104,17 @@ def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=Fal
     n.backward()
     dw = {i: n.get_weight_grad(i, w.shape) for i, w in weights.items()}
     st = n.stats()
+    st["ws"] = lib_ws(n, net)
+    convs = [i for i, l in enumerate(net["layers"]) if l["type"] == "conv"]
+    st["kernels"] = {i: n.layer_kernels(i) for i in convs}
     n.close()
     return loss, dw, st, caps
 
 
 def test_vgg16_b256_step_under_12_gib(B):
-    """The benchmark configuration itself: VGG-16, batch 256, vDNN_all / conv / dyn under 12 GiB against the
-    no-offload run: bit-identical loss and weight gradients, statistics equal to the memory-schedule oracle,
-    and sampled layer outputs against the CPU oracle evaluated on the captured layer inputs."""
+    """The benchmark configuration itself, with the library's default settings: VGG-16, batch 256, vDNN_all / conv / dyn
+    (and fit) under 12 GiB against the no-offload run: bit-identical loss and weight gradients, statistics equal to the
+    memory-schedule oracle, and sampled layer outputs against the CPU oracle evaluated on the captured layer inputs."""
     import torch
     net = nets.vgg16(256)
     x, labels, weights = gen.make(net)
@@ -133,20 +139,18 @@ def test_vgg16_b256_step_under_12_gib(B):
     # invariants: every dW finite, and identical bits under every offloading policy
     for i, d in base_dw.items():
         assert np.isfinite(d).all(), i
+    assert base_st["n_winograd_convs"] == 9   # c3_1 (backward only) ... c5_3
     for pol in ("all", "conv", "dyn", "fit"):
         loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G)
+        assert st["conv_algo"] == "p" and st["kernels"] == base_st["kernels"]   # every plan of a net runs the same kernels
         if pol == "fit":
-            ref = ms.fit(net, 12 * G, st["window_fill_pm"], winograd=False)[2]
-            assert st["n_offload"] == ref["n_offload"] > 2   # the two feature maps move in pieces
-            assert st["peak_bytes"] >= ref["peak_bytes"]     # fetches issued early hold memory longer
-            ref["peak_bytes"] = st["peak_bytes"]
-            assert st["offloaded_bytes"] == 3288334336 + 822083584  # c1_1's output and pool1's output
+            assert st["n_offload"] > 2                         # feature maps move in pieces
+            assert 0 < st["offloaded_bytes"] == st["prefetched_bytes"] < 9299820544   # fewer bytes than vDNN_conv moves
         else:
-            ref = ms.simulate(net, st["effective_policy"], 12 * G, winograd=False)
-        assert st["n_winograd_convs"] == 0
-        assert st["peak_bytes"] == ref["peak_bytes"] <= 12 * G
-        assert st["offloaded_bytes"] == ref["offloaded_bytes"] == st["prefetched_bytes"]
-        assert st["pool_extent_bytes"] <= 12 * G
+            ref = ms.simulate(net, st["effective_policy"], 12 * G, ws=st["ws"])
+            assert st["peak_bytes"] == ref["peak_bytes"] <= 12 * G
+            assert st["offloaded_bytes"] == ref["offloaded_bytes"] == st["prefetched_bytes"]
+        assert st["peak_bytes"] <= st["pool_extent_bytes"] <= 12 * G
         if pol == "all":
             assert st["offloaded_bytes"] == 15568207872
         if pol == "dyn":
@@ -163,36 +167,24 @@ def test_vgg16_b256_step_under_12_gib(B):
             assert np.array_equal(dw[i], base_dw[i]), (pol, i)
 
 
-def test_vgg16_b256_winograd_plans(B):
-    """What the library does by default: wide 3x3 layers get the Winograd workspace where it fits the budget at that
-    point of the step.  Which layers those are, and the peak that follows, equal the memory-schedule oracle; loss and
-    weight gradients agree with the all-direct run to rounding (plus the few ReLU / arg-max decisions that the
-    different rounding of the c4 / c5 outputs flips)."""
+def test_vgg16_b256_direct_kernels_only(B):
+    """vdnn_set_winograd(net, 0): no plan runs the Winograd kernel, the step agrees with the default one to rounding (the
+    loss to 1e-5; the gradients are held to the oracle separately, in test_step_against_the_oracle_at_full_size), and
+    offloading is bit-identical to no offloading here too."""
     import torch
-    from tests.gpu_util import rel_err
     net = nets.vgg16(256)
     x, labels, weights = gen.make(net)
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
-    base_loss, base_dw, base_st, _ = _run(B, net, xd, ld, weights, "none", 0)
-    assert base_st["n_winograd_convs"] == 0
-    seen = []
-    for pol, budget in (("none", 0), ("conv", 12 * G), ("fit", 12 * G)):
-        loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, budget, winograd=True)
-        if pol == "fit":
-            ref = ms.fit(net, budget, st["window_fill_pm"])[2]
-            assert st["peak_bytes"] >= ref["peak_bytes"]
-        else:
-            ref = ms.simulate(net, pol, budget if budget else 1 << 60)
-            assert st["peak_bytes"] == ref["peak_bytes"]
-        assert st["n_winograd_convs"] == ref["n_winograd_convs"] and st["offloaded_bytes"] == ref["offloaded_bytes"]
-        seen.append(st["n_winograd_convs"])
-        assert abs(loss - base_loss) < 1e-5 * abs(base_loss), pol
+    wino_loss, _, wino_st, _ = _run(B, net, xd, ld, weights, "none", 0)
+    base_loss, base_dw, base_st, _ = _run(B, net, xd, ld, weights, "none", 0, winograd=False)
+    assert wino_st["n_winograd_convs"] == 9 and base_st["n_winograd_convs"] == 0
+    assert base_st["peak_bytes"] < wino_st["peak_bytes"]
+    assert abs(wino_loss - base_loss) < 1e-5 * abs(base_loss)
+    for pol in ("conv", "fit"):
+        loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G, winograd=False)
+        assert st["n_winograd_convs"] == 0 and loss == base_loss
         for i in weights:
-            # the flipped decisions dominate, as against the fp64 oracle at this size
-            # (test_vgg16_b256_step_against_the_oracle_at_full_size): same bound.  Every element is compared here, so the
-            # classifier's gradients show their few flipped ReLUs too (the oracle test samples 400 entries per tensor).
-            assert rel_err(dw[i], base_dw[i]) < 3e-3, (pol, i)
-    assert seen[0] == 9 and seen[1] > 0   # c3_1 (backward only) ... c5_3 without a budget
+            assert np.array_equal(dw[i], base_dw[i]), (pol, i)
 
 
 @pytest.mark.parametrize("name,policy,budget", [("alexnet", "conv", 1 * G), ("overfeat", "all", 2 * G), ("overfeat", "conv", 2 * G),
@@ -209,14 +201,18 @@ def test_other_workloads_full_size(B, name, policy, budget):
     assert np.isfinite(base_loss) and 1.0 < base_loss < 60.0
     loss, dw, st, _ = _run(B, net, xd, ld, weights, policy, budget)
     if policy == "fit":
-        # the schedule itself is checked against the oracle on the CPU (host tests); here: it offloads, within the budget
-        assert ms.simulate(net, "none", budget)["status"] == "oom" and st["offloaded_bytes"] == st["prefetched_bytes"] > 0
+        # the schedule itself is checked in _run (tests/sched_util.py); here: it offloads, within the budget
+        assert ms.simulate(net, "none", budget, ws=st["ws"])["status"] == "oom" and st["offloaded_bytes"] == st["prefetched_bytes"] > 0
         assert st["peak_bytes"] <= st["pool_extent_bytes"] <= budget and st["window_fill_pm"] > 0
     else:
-        ref = ms.simulate(net, st["effective_policy"], budget, winograd=False)
+        ref = ms.simulate(net, st["effective_policy"], budget, st["conv_algo"], ws=st["ws"])
         assert ref["status"] == "ok"
         assert st["peak_bytes"] == ref["peak_bytes"] <= budget and st["pool_extent_bytes"] <= budget
         assert st["offloaded_bytes"] == ref["offloaded_bytes"] and st["n_ondemand_fetch"] == ref["n_ondemand_fetch"]
+    if st["conv_algo"] != "p":
+        # a greedy plan (vDNN_dyn, phase 3) runs other kernels where a workspace does not fit: equal to rounding
+        assert abs(loss - base_loss) < 1e-5 * abs(base_loss) and st["n_downgraded_convs"] > 0
+        return
     assert loss == base_loss
     for i in weights:
         assert np.isfinite(dw[i]).all()
@@ -225,20 +221,20 @@ def test_other_workloads_full_size(B, name, policy, budget):
 
 @pytest.mark.parametrize("extra,check_identity", [(20, True), (80, False)])
 def test_very_deep_vgg_batch_32(B, extra, check_identity):
-    """Section 5.4: VGG-116 ... VGG-416 at batch 32.  The baseline allocation grows to tens of GB while vDNN keeps
+    """Section 5.5: VGG-116 ... VGG-416 at batch 32.  The baseline allocation grows to tens of GB while vDNN keeps
     the GPU-side footprint to a few GB, with most feature maps on the host."""
     import torch
     net = nets.vgg(batch=32, extra_per_group=extra)
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 50 + extra)
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
     loss, dw, st, _ = _run(B, net, xd, ld, weights, "all", 12 * G)
-    ref = ms.simulate(net, "all", 12 * G, winograd=False)
+    ref = ms.simulate(net, "all", 12 * G, ws=st["ws"])
     info = ms.analyse(net)
     assert np.isfinite(loss)
     assert st["peak_bytes"] == ref["peak_bytes"] and st["offloaded_bytes"] == ref["offloaded_bytes"]
     host_fraction = st["offloaded_bytes"] / sum(info["nbytes"].values())
     assert host_fraction > 0.8
-    # Section 5.4 quotes 67.1 GB for the baseline of VGG-416 (ours: 70.1 GB without cuDNN's workspace
+    # Section 5.5 quotes 67.1 GB for the baseline of VGG-416 (ours: 70.1 GB without cuDNN's workspace
     # accounting) and a GPU-side footprint of a few GB under vDNN
     assert st["baseline_bytes"] > (18e9 if extra == 20 else 60e9)
     assert st["peak_bytes"] < 0.2 * st["baseline_bytes"] and st["peak_bytes"] < 12 * G
@@ -249,58 +245,120 @@ def test_very_deep_vgg_batch_32(B, extra, check_identity):
             assert np.array_equal(dw[i], base_dw[i]), i
 
 
-def test_vgg16_b256_step_against_the_oracle_at_full_size(B):
-    """End-to-end parity of the benchmark configuration itself: loss and sampled weight-gradient entries of one
-    VGG-16 batch-256 step against tests/golden/vgg16_b256_step.json, which tests/golden/make_vgg16_b256_golden.py wrote
-    from the fp64 CPU oracle alone (the batch in chunks: losses average, weight gradients add).  Error measure as
-    everywhere: largest deviation over the samples relative to the largest element of the oracle's tensor.
+GOLDEN = [("vgg16", "dyn", 12 * G, 2), ("alexnet", "conv", 1 * G, 4), ("overfeat", "all", 2 * G, 4), ("googlenet", "dyn", 3 * G, 4)]
 
-    The loss and the FC gradients meet 1e-4.  Below the classifier the two sides no longer decide alike: the arg-max of
-    a pooling window and the sign test of a ReLU are taken from forward values, 3.9 G of them here, and where the fp32
-    and the fp64 forward pass differ in the last bits some thousand of them fall on opposite sides; each moves a whole
-    gradient term, and the deviation grows layer by layer towards the input (measured 1e-4 at c5 to 1.5e-3 at c1_1, rms
-    a third of that).  The small-network tests remove the effect by letting the oracle decide from the GPU's forward
-    values; that needs all forward values on the host and an oracle backward pass, which at this size takes an hour.
-    Here the bound for the convolution layers is therefore 3e-3 (max) and 1e-3 (rms); tests/test_oracle_pins.py shows
-    on the oracle alone that perturbing forward values by 1e-6 moves gradients by that much."""
+
+def full_size_oracle_report(B, name, policy, budget, k_images, winograd=True):
+    """One step of a benchmark configuration at its stated size, policy and budget, every layer's output and every
+    gradient map captured, against (a) tests/golden/<name>_b<batch>_step.json, which tests/golden/make_step_golden.py wrote
+    from the fp64 CPU oracle alone, and (b) the oracle run here on the first k_images images of the same batch, its backward
+    pass deciding ReLU signs and pooling arg-max from the GPU's forward values.  Returns the measurements; the test below
+    asserts on them.  Error measure as everywhere: largest deviation relative to the largest element of the oracle's tensor."""
     import json
     import os
     import torch
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "vgg16_b256_step.json")
-    gold = json.load(open(path))
-    net = nets.vgg16(256)
-    x, labels, weights = gen.make(net)
-    xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
-    loss, dw, st, _ = _run(B, net, xd, ld, weights, "none", 0, winograd=True)
-    assert abs(loss - gold["loss"]) < TOL * abs(gold["loss"])
-    assert sorted(int(i) for i in gold["layers"]) == sorted(weights)
-    for i, g in gold["layers"].items():
-        mine = dw[int(i)].reshape(-1).astype(np.float64)
-        assert list(dw[int(i)].shape) == g["shape"]
-        d = np.abs(mine[np.array(g["index"])] - np.array(g["value"])) / g["max_abs"]
-        if net["layers"][int(i)]["type"] == "fc":
-            assert d.max() < TOL, (i, d.max())
-        else:
-            assert d.max() < 3e-3 and np.sqrt((d * d).mean()) < 1e-3, (i, d.max())
-        assert abs(np.sqrt((mine * mine).sum()) - g["l2"]) < 1e-3 * g["l2"], i
-
-
-def test_vgg16_full_resolution_decisions_shared_with_the_oracle(B):
-    """The counterpart of the test above: VGG-16 at full resolution and depth with a batch small enough for an oracle
-    backward pass (2 images), the oracle deciding ReLU signs and pooling arg-max from the GPU's forward values.  With the
-    decisions shared every weight gradient meets 1e-4, the convolution layers included: what separates the two sides
-    at full size is the decisions, not the arithmetic of the kernels."""
-    import torch
     from oracle import net as onet
-    from tests.gpu_util import rel_err
-    net = nets.vgg16(2)
-    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 77)
-    hooks = tuple(range(len(net["layers"])))
-    loss, dw, st, caps = _run(B, net, torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda(), weights, "none", 0, hooks, winograd=True)
-    ref = onet.step(net, x, labels, weights, outs_override=caps)
-    assert abs(loss - ref["loss"]) < TOL * abs(ref["loss"])
-    for i, y in enumerate(ref["outs"]):
-        if net["layers"][i]["type"] != "softmax_ce":
-            assert rel_err(caps[i].reshape(y.shape), y) < TOL, i
+    from tests.gpu_util import count_decision_flips, rel_err
+    make = nets.CONFIGS[name]
+    net = make()
+    batch = net["batch"]
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "%s_b%d_step.json" % (name, batch))
+    gold = json.load(open(path))
+    x, labels, weights = gen.make(net)
+    n = B.Net(net, budget)
+    n.set_winograd(winograd)
+    n.set_policy(policy)
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    nl = len(net["layers"])
+    outs = {i: np.empty(n.output_count(i), np.float32) for i in range(nl - 1)}
+    grads = {i: np.empty(n.output_count(i), np.float32) for i in range(nl - 1)}
+    for i in range(nl - 1):
+        n.capture_output(i, outs[i])
+        n.capture_grad(i, grads[i])
+    loss = n.forward(torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda())
+    n.backward()
+    dw = {i: n.get_weight_grad(i, w.shape) for i, w in weights.items()}
+    st = n.stats()
+    n.close()
+    rep = dict(name=name, stats=st, loss_err=abs(loss - gold["loss"]) / abs(gold["loss"]), fwd={}, dy={}, dw={}, shared={})
+    # (a) the golden step: sampled forward values, sampled gradient-map entries, sampled weight-gradient entries
+    for key, mine in (("fwd", outs), ("dy", grads)):
+        for i, g in gold[key].items():
+            d = np.abs(mine[int(i)][np.array(g["index"])].astype(np.float64) - np.array(g["value"])) / g["max_abs"]
+            rep[key][int(i)] = dict(max=float(d.max()), beyond=float((d > TOL).mean()), samples=len(d))
+    for i, g in gold["layers"].items():
+        flat = dw[int(i)].reshape(-1).astype(np.float64)
+        assert list(dw[int(i)].shape) == g["shape"]
+        d = np.abs(flat[np.array(g["index"])] - np.array(g["value"])) / g["max_abs"]
+        rep["dw"][int(i)] = dict(max=float(d.max()), rms=float(np.sqrt((d * d).mean())), l2_err=abs(float(np.sqrt((flat * flat).sum())) - g["l2"]) / g["l2"])
+    # (b) the first k images, decisions shared: every element of every output and every gradient map
+    part = make(k_images)
+    per = {i: outs[i].size // batch for i in outs}
+    ov = {i: outs[i][:k_images * per[i]] for i in outs}
+    dys = {}
+    ref = onet.step(part, x[:k_images], labels[:k_images], weights, outs_override=ov,
+                    dy_hook=lambda i, g: dys.__setitem__(i, g * (k_images / batch)))
+    rep["shared"]["fwd_max"] = max(rel_err(ov[i], ref["outs"][i]) for i in ov)
+    rep["shared"]["dy"] = {i: rel_err(grads[i][:k_images * per[i]], dys[i]) for i in dys if i in grads}
+    rep["shared"]["flips"] = count_decision_flips(part, ov, ref["outs"])
+    # what the differing decisions alone do to the weight gradients: the oracle deciding for itself against the oracle
+    # deciding from the GPU's values, same k images.  A weight gradient is a mean over images and the images' decision
+    # terms are independent, so over the whole batch the effect shrinks by sqrt(k / batch).
+    pure = onet.step(part, x[:k_images], labels[:k_images], weights)
     for i in weights:
-        assert rel_err(dw[i], ref["dw"][i]) < TOL, i
+        e = (pure["dw"][i] - ref["dw"][i]).reshape(-1)
+        scale = gold["layers"][str(i)]["max_abs"]
+        rep["dw"][i]["decisions_rms"] = float(np.sqrt((e * e).mean())) * np.sqrt(k_images / batch) / scale
+        rep["dw"][i]["decisions_max"] = float(np.abs(e).max()) * np.sqrt(k_images / batch) / scale
+    rep["margins"] = gold.get("margins", {})
+    rep["thresholds"] = gold.get("thresholds", [])
+    return rep
+
+
+def print_report(rep):
+    print("%s: loss error %.2e; forward (first images, all elements) %.2e; %d decisions differ on those images" %
+          (rep["name"], rep["loss_err"], rep["shared"]["fwd_max"], rep["shared"]["flips"]))
+    for i in sorted(rep["fwd"]):
+        f, d = rep["fwd"][i], rep["dy"][i]
+        line = "  layer %3d  Y max %.1e | dY vs golden: max %.1e, %.1f %% of %d samples beyond 1e-4 | dY with shared decisions %.1e" % (
+            i, f["max"], d["max"], 100 * d["beyond"], d["samples"], rep["shared"]["dy"].get(i, float("nan")))
+        if i in rep["dw"]:
+            w = rep["dw"][i]
+            line += " | dW vs golden: max %.1e rms %.1e; decisions alone predict rms %.1e max %.1e" % (w["max"], w["rms"], w["decisions_rms"], w["decisions_max"])
+        print(line)
+
+
+@pytest.mark.parametrize("name,policy,budget,k_images", GOLDEN, ids=[g[0] for g in GOLDEN])
+def test_step_against_the_oracle_at_full_size(B, name, policy, budget, k_images):
+    """End-to-end parity of the four full-size configurations, each under its own policy and budget, against the fp64 oracle.
+
+    What holds to 1e-4 without qualification: the loss, every sampled forward value of every layer, the gradients of the
+    classifier.  Below the classifier backward propagation takes discrete decisions from forward values (Eq. chain_rule through
+    ReLU and max-pooling: which activations are positive, which element of a window is the largest), and an fp32 forward pass
+    that is right to 1e-6 still puts a few of millions of near-ties on the other side; each moves whole gradient terms.  The test
+    shows that this, and nothing else, separates the two sides:
+      - with the decisions shared (the oracle's backward pass run from the GPU's forward values, on the first images of the
+        batch, every element compared) every gradient map of every layer meets 1e-4;
+      - against the oracle deciding for itself (the golden file) the gradient maps deviate in a minority of sampled positions;
+      - the deviation of the weight gradients from the golden file is of the size that the differing decisions alone produce
+        in the oracle (measured here on those images, scaled to the batch)."""
+    rep = full_size_oracle_report(B, name, policy, budget, k_images)
+    print_report(rep)
+    net = nets.CONFIGS[name]()
+    assert rep["stats"]["peak_bytes"] <= budget
+    assert rep["loss_err"] < TOL
+    assert max(f["max"] for f in rep["fwd"].values()) < TOL
+    assert rep["shared"]["fwd_max"] < TOL
+    assert max(rep["shared"]["dy"].values()) < TOL, rep["shared"]["dy"]
+    first_fc = min(i for i, l in enumerate(net["layers"]) if l["type"] == "fc")
+    for i, w in rep["dw"].items():
+        assert w["l2_err"] < 1e-3, i
+        if i >= first_fc and rep["dy"][i]["beyond"] == 0:
+            assert w["max"] < TOL, (i, w)
+        else:
+            assert w["rms"] < TOL + 4 * w["decisions_rms"], (i, w)
+            assert w["max"] < TOL + 6 * max(w["decisions_max"], 3 * w["decisions_rms"]), (i, w)
+    for i, d in rep["dy"].items():
+        assert d["beyond"] < 0.5, (i, d)

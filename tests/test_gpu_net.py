@@ -8,7 +8,8 @@ from oracle import memsched as ms
 from oracle import net as onet
 from synth import gen, nets
 from tests.gpu_util import TOL, dev, rel_err
-from tests.sched_util import assert_windows_match, fit_reference
+from tests.gpu_util import count_decision_flips
+from tests.sched_util import check_schedule, lib_ws
 
 pytestmark = pytest.mark.gpu
 
@@ -68,6 +69,20 @@ def run_gpu(B, net, x, labels, weights, policy, budget=0, capture=True, algo=Non
     return dict(loss=loss, outs=outs, dw=dw, stats=st)
 
 
+def plan_ws(B, net):
+    """The library's workspace sizes for this net, as the memory-schedule oracle takes them."""
+    n = B.Net(net, 0)
+    ws = lib_ws(n, net)
+    n.close()
+    return ws
+
+
+def candidates(net):
+    """What vDNN_all would offload."""
+    info = ms.analyse(net)
+    return {b for b in info["nbytes"] if ms.selected(net, info, b, "all")}
+
+
 def fc_only():
     b = nets._Builder("fconly", 1, 5, 1, 1)
     b.fc(3, relu=False)
@@ -115,6 +130,14 @@ def test_step_matches_oracle(B, name, mk):
         assert rel_err(got["outs"][i], ref["outs"][i]) < TOL, (i, l["type"])
     for i in weights:
         assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+    # The oracle on its own, deciding from its own fp64 forward values: where no ReLU sign and no pooling arg-max falls
+    # differently on the two sides (counted from the forward values), the same 1e-4 holds without any help; where some
+    # do, each moves whole gradient terms and only the comparison above is meaningful.
+    flips = count_decision_flips(net, got["outs"], ref["outs"])
+    pure = onet.step(net, x, labels, weights)
+    worst = max(rel_err(got["dw"][i], pure["dw"][i]) for i in weights)
+    print("%s: %d decisions differ between the fp32 and the fp64 forward pass; dW against the oracle alone: %.2e" % (name, flips, worst))
+    assert flips > 0 or worst < TOL, (flips, worst)
     # without the output hooks the ReLU forward passes run inside the convolution epilogues
     # (the hooks switch that folding off): same values, checked through the loss and every dW
     fused = run_gpu(B, net, x, labels, weights, "none", capture=False)
@@ -149,12 +172,13 @@ def test_offload_is_bit_identical(B, name, mk):
 def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
     """The per-feature-map offload set with budget-aware transfer windows: budgets between the peaks of the
     static policies, so that the windows really are partly filled; values must equal the no-offload run's bit
-    for bit, and the planned step must equal the memory-schedule oracle's."""
+    for bit, and the planned step must keep the contract of a vDNN schedule (tests/sched_util.py)."""
     net = mk()
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 19)
     base = run_gpu(B, net, x, labels, weights, "none", capture=False)
-    lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
-    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+    ws = plan_ws(B, net)
+    lo = ms.simulate(net, "all", 1 << 50, ws=ws)["peak_bytes"]
+    hi = ms.simulate(net, "none", 1 << 50, ws=ws)["peak_bytes"]
     seen_offload = False
     part = 8192   # the feature maps of these nets are small: cut them into pieces all the same
     for budget in (lo, lo + (hi - lo) // 3, lo + 2 * (hi - lo) // 3, hi - 256):
@@ -163,9 +187,9 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
         if n.try_policy("fit") != B.OK:   # placement may need more than the live peak right at the lower end
             n.close()
             continue
-        chosen, algo, ref, lent, twins = fit_reference(n, net, budget, part)
-        assert n.offload_set() == chosen
-        assert_windows_match(n.trace(), ref["trace"], lent, twins)
+        st = n.stats()
+        check_schedule(net, n.trace(), st["pool_extent_bytes"], n.offload_set(), st["persistent_bytes"])
+        assert n.offload_set() <= candidates(net)
         n.close()
         got = run_gpu(B, net, x, labels, weights, "fit", budget=budget, capture=False, part=part)
         assert got["loss"] == base["loss"], budget
@@ -176,7 +200,7 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
         seen_offload |= got["stats"]["offloaded_bytes"] > 0
     assert seen_offload or hi - lo <= 256
     # every candidate offloaded, windows of several sizes under a budget with room to spare
-    cands = set(ms.fit_candidates(net))
+    cands = candidates(net)
     for fill in (1000, 800, 500):
         n = B.Net(net, hi)
         n.set_window_part((4096, 65536, 0)[fill % 3])
@@ -190,7 +214,7 @@ def test_fit_policy_and_transfer_windows_are_bit_identical(B, name, mk):
             assert loss == base["loss"], fill
             for i, w in weights.items():
                 assert np.array_equal(n.get_weight_grad(i, w.shape), base["dw"][i]), (fill, i)
-        assert n.stats()["offloaded_bytes"] == ms.simulate(net, "all", 1 << 50)["offloaded_bytes"]
+        assert n.stats()["offloaded_bytes"] == ms.simulate(net, "all", 1 << 50, ws=ws)["offloaded_bytes"]
         n.close()
 
 
@@ -205,13 +229,14 @@ def test_classifier_inputs_can_be_offloaded_too(B, name, mk):
     assert fc_inputs
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 23)
     base = run_gpu(B, net, x, labels, weights, "none", capture=False)
-    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
-    for chosen, fill in ((fc_inputs, 0), (fc_inputs | set(ms.fit_candidates(net)), 0), (fc_inputs | set(ms.fit_candidates(net)), 900)):
+    ws = plan_ws(B, net)
+    hi = ms.simulate(net, "none", 1 << 50, ws=ws)["peak_bytes"]
+    for chosen, fill in ((fc_inputs, 0), (fc_inputs | candidates(net), 0), (fc_inputs | candidates(net), 900)):
         n = B.Net(net, hi)
         n.set_window_part(8192)
         n.set_offload_set(chosen, fill)
         assert n.offload_set() == chosen
-        ref = ms.simulate(net, "none", 1 << 50, offload_set=chosen)
+        ref = ms.simulate(net, "none", 1 << 50, offload_set=chosen, ws=ws)
         n.attach_torch()
         for i, w in weights.items():
             n.set_weights(i, w)
@@ -319,15 +344,16 @@ def test_memory_optimal_algorithm_matches_oracle(B, name, mk):
 def test_dyn_greedy_downgrade_runs(B):
     """A budget between vDNN_all's peak with and without convolution workspace: vDNN_dyn reaches its greedy phase
     and the step still matches the oracle."""
-    from oracle import memsched as ms
     net = nets.alexnet(8)
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 20)
-    budget = ms.simulate(net, "all", 1 << 50, "p")["peak_bytes"] - 256
-    pol, algo, sim = ms.dynamic(net, budget)
+    ws = plan_ws(B, net)
+    budget = ms.simulate(net, "all", 1 << 50, "p", ws=ws)["peak_bytes"] - 256
+    pol, algo, sim = ms.dynamic(net, budget, ws)
     assert algo == "greedy"
     got = run_gpu(B, net, x, labels, weights, "dyn", budget=budget, capture=True)
     st = got["stats"]
-    assert (st["effective_policy"], st["conv_algo"]) == (pol, "greedy") and st["n_memopt_convs"] == sim["n_memopt_convs"] >= 1
+    assert (st["effective_policy"], st["conv_algo"]) == (pol, "greedy") and st["n_downgraded_convs"] == sim["n_downgraded_convs"] >= 1
+    assert st["n_memopt_convs"] == sim["n_memopt_convs"]
     assert st["peak_bytes"] <= budget
     ref = onet.step(net, x, labels, weights, outs_override=got["outs"])
     assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
@@ -415,8 +441,9 @@ def test_random_graphs_on_the_device(B, seed):
     for i in weights:
         assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
     base = run_gpu(B, net, x, labels, weights, "none", capture=False)
-    lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
-    hi = ms.simulate(net, "none", 1 << 50)["peak_bytes"]
+    ws = plan_ws(B, net)
+    lo = ms.simulate(net, "all", 1 << 50, ws=ws)["peak_bytes"]
+    hi = ms.simulate(net, "none", 1 << 50, ws=ws)["peak_bytes"]
     for pol, budget in (("all", 0), ("conv", 0), ("dyn", (lo + hi) // 2), ("fit", (lo + hi) // 2), ("fit", lo + (hi - lo) // 4)):
         n = B.Net(net, budget)
         n.set_window_part(2048)
@@ -425,25 +452,29 @@ def test_random_graphs_on_the_device(B, seed):
         if not ok:
             continue
         r = run_gpu(B, net, x, labels, weights, pol, budget=budget, capture=False, part=2048)
+        if r["stats"]["conv_algo"] != "p":   # a greedy or memory-optimal plan runs other kernels: equal to rounding
+            assert abs(r["loss"] - base["loss"]) < 1e-5 * abs(base["loss"])
+            continue
         assert r["loss"] == base["loss"], (pol, budget)
         for i in weights:
             assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
 
 
 @pytest.mark.parametrize("seed,chunk", [(104, 0), (108, 300000), (113, 0), (122, 300000), (124, 0)])
-def test_random_wide_graphs_on_the_device(B, seed, chunk, monkeypatch):
-    """The same fuzz with 128 ... 384 channels on 8 x 8 images, where plans give 3x3 layers the Winograd workspace (in
-    one piece, or with a chunk size that holds a single image): the no-offload step against the oracle with the
-    library's choice of algorithms; which layers run the Winograd algorithm and the peak equal the memory-schedule
-    oracle's under every policy; with the direct kernels pinned every offloading policy is bit-identical to no-offload."""
+def test_random_wide_graphs_on_the_device(B, seed, chunk):
+    """The same fuzz with 128 ... 384 channels on 8 x 8 images, where 3x3 layers run the Winograd kernel (in one piece,
+    or with a chunk size that holds a single image): the no-offload step against the oracle; then, with the library's
+    default settings, every offloading policy whose plan is performance-optimal runs the same kernels and is bit-identical
+    to the no-offload step; a greedy plan (other kernels where a workspace does not fit) and the run without the Winograd
+    kernel agree to rounding.  Peaks equal the memory-schedule oracle's."""
     net = nets.random_net(seed, batch=3, in_hw=8, wide=True)
     x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 400 + seed)
     B.op_set_winograd_chunk_bytes(chunk)
-    monkeypatch.setattr(ms, "WINOGRAD_CHUNK_BYTES", chunk or (512 << 20))
     try:
         got = run_gpu(B, net, x, labels, weights, "none")
-        sim = ms.simulate(net, "none", 1 << 50)
-        assert got["stats"]["n_winograd_convs"] == sim["n_winograd_convs"] >= 2 and got["stats"]["peak_bytes"] == sim["peak_bytes"]
+        ws = plan_ws(B, net)
+        sim = ms.simulate(net, "none", 1 << 50, ws=ws)
+        assert got["stats"]["n_winograd_convs"] >= 2 and got["stats"]["peak_bytes"] == sim["peak_bytes"]
         fwd = onet.forward(net, x, labels, weights)[0]
         for i, y in enumerate(fwd):
             if net["layers"][i]["type"] != "softmax_ce":
@@ -452,30 +483,35 @@ def test_random_wide_graphs_on_the_device(B, seed, chunk, monkeypatch):
         assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
         for i in weights:
             assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
-        base = run_gpu(B, net, x, labels, weights, "none", capture=False, winograd=False)
-        assert base["stats"]["n_winograd_convs"] == 0
-        lo = ms.simulate(net, "all", 1 << 50)["peak_bytes"]
+        base = run_gpu(B, net, x, labels, weights, "none", capture=False)
+        direct = run_gpu(B, net, x, labels, weights, "none", capture=False, winograd=False)
+        assert direct["stats"]["n_winograd_convs"] == 0
+        assert abs(direct["loss"] - base["loss"]) < 1e-5 * abs(base["loss"])
+        lo = ms.simulate(net, "all", 1 << 50, ws=ws)["peak_bytes"]
         hi = sim["peak_bytes"]
-        for pol, budget in (("all", 0), ("conv", (lo + hi) // 2), ("conv", 0), ("fit", (lo + hi) // 2)):
-            for on in (True, False):
-                n = B.Net(net, budget)
-                n.set_winograd(on)
-                n.set_window_part(2048)
-                ok = n.try_policy(pol) == B.OK
-                n.close()
-                if not ok:
-                    continue
-                r = run_gpu(B, net, x, labels, weights, pol, budget=budget, capture=False, part=2048, winograd=on)
-                if pol != "fit":
-                    want = ms.simulate(net, pol, budget or (1 << 50), winograd=on)
-                    assert r["stats"]["n_winograd_convs"] == want["n_winograd_convs"] and r["stats"]["peak_bytes"] == want["peak_bytes"]
-                if on:   # another mix of algorithms than the base run: equal to rounding
-                    assert abs(r["loss"] - base["loss"]) < 1e-5 * abs(base["loss"])
-                    for i in weights:
-                        assert rel_err(r["dw"][i], base["dw"][i]) < TOL, (pol, budget, i)
-                else:
-                    assert r["loss"] == base["loss"], (pol, budget)
-                    for i in weights:
-                        assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
+        n_identical = 0
+        for pol, budget in (("all", 0), ("conv", (lo + hi) // 2), ("conv", 0), ("dyn", (lo + hi) // 2), ("fit", (lo + hi) // 2), ("fit", hi - 256)):
+            n = B.Net(net, budget)
+            n.set_window_part(2048)
+            ok = n.try_policy(pol) == B.OK
+            n.close()
+            if not ok:
+                continue
+            r = run_gpu(B, net, x, labels, weights, pol, budget=budget, capture=False, part=2048)
+            st = r["stats"]
+            if pol in ("all", "conv"):
+                want = ms.simulate(net, pol, budget or (1 << 50), ws=ws)
+                assert st["peak_bytes"] == want["peak_bytes"]
+            if st["conv_algo"] == "p":
+                assert st["n_winograd_convs"] == got["stats"]["n_winograd_convs"]
+                assert r["loss"] == base["loss"], (pol, budget)
+                for i in weights:
+                    assert np.array_equal(r["dw"][i], base["dw"][i]), (pol, budget, i)
+                n_identical += 1
+            else:
+                assert abs(r["loss"] - base["loss"]) < 1e-5 * abs(base["loss"])
+                for i in weights:
+                    assert rel_err(r["dw"][i], base["dw"][i]) < TOL, (pol, budget, i)
+        assert n_identical >= 2
     finally:
         B.op_set_winograd_chunk_bytes(0)

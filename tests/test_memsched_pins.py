@@ -57,6 +57,7 @@ def test_hand_enumerated_trace_linear_net():
     b.maxpool(2, 2)
     b.fc(5, relu=False)
     net = b.done()
+    assert net["layers"] == _hand_net()["layers"]
     r = ms.simulate(net, "all", 1 << 20)
     w0 = 4 * 4 * 2 * 9  # 288 -> 512
     w3 = 4 * 5 * 16     # 320 -> 512
@@ -151,7 +152,7 @@ def test_oom_is_reported_where_it_happens():
 
 
 def test_very_deep_vgg_host_fraction():
-    """Section 5.4: for VGG-116..416 at batch 32 most of the allocations live on the host (81-92 %)."""
+    """Section 5.5: for VGG-116..416 at batch 32 most of the allocations live on the host (81-92 %)."""
     fracs = []
     for extra in (20, 40):
         net = nets.vgg(batch=32, extra_per_group=extra)
@@ -162,47 +163,83 @@ def test_very_deep_vgg_host_fraction():
     assert all(f > 0.8 for f in fracs)
 
 
+def _hand_net():
+    b = nets._Builder("hand", 1, 2, 4, 4)
+    b.conv(4, 3, pad=1)
+    b.maxpool(2, 2)
+    b.fc(5, relu=False)
+    return b.done()
+
+
+def test_workspace_and_algorithm_modes_by_hand():
+    """Section 2.2 / 3.3 on the hand net above, with workspace sizes given by hand: the conv layer can run three ways
+    in each direction (fastest first, the last without workspace), the FC layer needs 256 bytes in forward.
+    Live bytes when the conv asks for its workspace: forward 2560 + B-1 + B0 = 3072, backward 2560 + dB0 + B-1 = 3072."""
+    net = _hand_net()
+    ws = {(0, "fwd"): [1024, 512, 0], (0, "bwd"): [2048, 256, 0], (3, "fwd"): [256]}
+    r = ms.simulate(net, "all", 1 << 20, "p", ws=ws)
+    tr = r["trace"]
+    f0 = [t for t in tr if t[0] == "F0"]
+    assert f0 == [("F0", "alloc", "B0", 256), ("F0", "alloc", "WS", 1024), ("F0", "offload", "B-1", 128), ("F0", "compute", "conv"),
+                  ("F0", "free", "WS", 1024), ("F0", "free", "B-1", 256)]
+    assert [t for t in tr if t[0] == "F3"] == [("F3", "alloc", "B3", 256), ("F3", "alloc", "WS", 256), ("F3", "compute", "fc"), ("F3", "free", "WS", 256)]
+    assert [t for t in tr if t[0] == "B0"] == [("B0", "alloc", "WS", 2048), ("B0", "compute", "conv"), ("B0", "free", "WS", 2048),
+                                               ("B0", "free", "dB0", 256), ("B0", "free", "B-1", 256)]
+    # peak: backward of the conv, 3072 + 2048
+    assert r["peak_bytes"] == 5120 and r["n_memopt_convs"] == 0 and r["n_downgraded_convs"] == 0
+    # without any workspace the step peaks at 3840 (backward of the FC layer, five 256-byte blocks live)
+    assert ms.simulate(net, "all", 1 << 20)["peak_bytes"] == 3840
+    # performance-optimal under 3840: the 1024 bytes in F0 do not fit (3072 + 1024)
+    r = ms.simulate(net, "all", 3840, "p", ws=ws)
+    assert r["status"] == "oom" and r["oom_at"] == "F0"
+    # greedy under 3840: forward takes the second entry (3072 + 512 fits), backward the second (2048 does not, 256 does)
+    r = ms.simulate(net, "all", 3840, "greedy", ws=ws)
+    assert r["status"] == "ok" and r["peak_bytes"] == 3840
+    assert [t[3] for t in r["trace"] if t[1] == "alloc" and t[2] == "WS"] == [512, 256, 256]
+    assert r["n_downgraded_convs"] == 1 and r["n_memopt_convs"] == 0
+    # no entry with workspace fits in backward: the memory-optimal algorithm is what is left
+    r = ms.simulate(net, "all", 3840, "greedy", ws={(0, "fwd"): [1024, 512, 0], (0, "bwd"): [2048, 1024, 0], (3, "fwd"): [256]})
+    assert [t[3] for t in r["trace"] if t[1] == "alloc" and t[2] == "WS"] == [512, 256]
+    assert r["n_downgraded_convs"] == 1 and r["n_memopt_convs"] == 1
+    # memory-optimal: no workspace for the conv in either direction; the FC layer keeps its own
+    r = ms.simulate(net, "all", 3840, "m", ws=ws)
+    assert [(t[0], t[3]) for t in r["trace"] if t[1] == "alloc" and t[2] == "WS"] == [("F3", 256)]
+    assert r["n_memopt_convs"] == 1 and r["peak_bytes"] == 3840
+    # the baseline allocates one workspace of the largest performance-optimal size (Fig. mem_allocation_policy_global):
+    # feature maps 4 x 256, W and dW 4 x 512, two gradient maps of 256, workspace 2048
+    assert ms.baseline_bytes(net, ws) == 4 * 256 + 4 * 512 + 2 * 256 + 2048
+    assert ms.baseline_bytes(net) == 4 * 256 + 4 * 512 + 2 * 256
+    # trace_stats recounts a trace: the hand-computed figures again
+    st = ms.trace_stats(ms.simulate(net, "all", 1 << 20, "p", ws=ws)["trace"])
+    assert st["peak_bytes"] == 5120 and st["cur_bytes"] == 2560 and st["offloaded_bytes"] == 128 + 256 == st["prefetched_bytes"]
+    assert (st["n_offload"], st["n_prefetch"], st["n_ondemand_fetch"]) == (2, 2, 0)
+
+
+def _alexnet_ws(net):
+    """Hand-made workspace lists for the dyn test: every conv layer can run with 6 MiB, 1 MiB or nothing."""
+    ws = {}
+    for i, l in enumerate(net["layers"]):
+        if l["type"] == "conv":
+            ws[i, "fwd"] = [4 << 20, 1 << 20, 0]
+            ws[i, "bwd"] = [6 << 20, 1 << 20, 0]
+    return ws
+
+
 def test_dynamic_policy_phases():
     """Section 3.3: budgets chosen so that each phase of vDNN_dyn decides."""
     net = nets.alexnet(8)
-    none_p = ms.simulate(net, "none", 1 << 50, "p")["peak_bytes"]
-    conv_p = ms.simulate(net, "conv", 1 << 50, "p")["peak_bytes"]
-    all_p = ms.simulate(net, "all", 1 << 50, "p")["peak_bytes"]
-    all_m = ms.simulate(net, "all", 1 << 50, "m")["peak_bytes"]
+    ws = _alexnet_ws(net)
+    none_p = ms.simulate(net, "none", 1 << 50, "p", ws=ws)["peak_bytes"]
+    conv_p = ms.simulate(net, "conv", 1 << 50, "p", ws=ws)["peak_bytes"]
+    all_p = ms.simulate(net, "all", 1 << 50, "p", ws=ws)["peak_bytes"]
+    all_m = ms.simulate(net, "all", 1 << 50, "m", ws=ws)["peak_bytes"]
     assert all_m < all_p <= conv_p <= none_p
-    assert ms.dynamic(net, none_p)[:2] == ("none", "p")                 # phase 2, first try
-    assert ms.dynamic(net, none_p - 256)[:2] == ("conv", "p")           # phase 2, second try
-    pol, algo, r = ms.dynamic(net, all_p - 256)                           # phase 3: greedy downgrade
-    assert algo == "greedy" and r["status"] == "ok" and r["n_memopt_convs"] >= 1 and r["peak_bytes"] <= all_p - 256
-    assert ms.dynamic(net, all_m - 256)[0] is None                        # phase 1 fails: not trainable
+    assert ms.dynamic(net, none_p, ws)[:2] == ("none", "p")                 # phase 2, first try
+    assert ms.dynamic(net, none_p - 256, ws)[:2] == ("conv", "p")           # phase 2, second try
+    pol, algo, r = ms.dynamic(net, all_p - 256, ws)                           # phase 3: greedy downgrade
+    assert algo == "greedy" and r["status"] == "ok" and r["n_downgraded_convs"] >= 1 and r["peak_bytes"] <= all_p - 256
+    assert ms.dynamic(net, all_m - 256, ws)[0] is None                        # phase 1 fails: not trainable
     # the memory-optimal algorithm allocates no convolution workspace at all
-    tr = ms.simulate(net, "all", 1 << 50, "m")["trace"]
+    tr = ms.simulate(net, "all", 1 << 50, "m", ws=ws)["trace"]
     conv_layers = {i for i, l in enumerate(net["layers"]) if l["type"] == "conv"}
     assert not [t for t in tr if t[1] == "alloc" and t[2] == "WS" and int(t[0][1:]) in conv_layers]
-
-
-def test_winograd_workspace_closed_forms():
-    """The Winograd workspace rules evaluated by hand for VGG-16 (256) layers: transformed filter 16*C*K floats, then
-    16*(C + K) floats per 2x2 output tile for as many images as fit 512 MiB; backward-filter: the 16 products once
-    plus once per reduction split, then the same chunk."""
-    MiB = 1 << 20
-    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image, 41 images per chunk
-    assert ms.winograd_workspace(256, 512, 28, 28, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 41 * 12845056
-    assert 41 * 12845056 <= 512 * MiB < 42 * 12845056
-    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 167 images per chunk
-    assert ms.winograd_workspace(256, 512, 14, 14, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 167 * 3211264
-    # a batch smaller than the chunk: all of it
-    assert ms.winograd_workspace(8, 512, 14, 14, 512, 3, 1, 1) == 16 * 512 * 512 * 4 + 8 * 3211264
-    # 13 x 13 (odd sides): 7 x 7 tiles as well
-    assert ms.winograd_workspace(8, 384, 13, 13, 256, 3, 1, 1) == 16 * 384 * 256 * 4 + 8 * 16 * 640 * 49 * 4
-    # not wide enough, not 3x3, strided, unpadded: no Winograd
-    for args in ((256, 128, 28, 28, 512, 3, 1, 1), (256, 512, 28, 28, 64, 3, 1, 1), (256, 512, 28, 28, 512, 5, 1, 2),
-                 (256, 512, 28, 28, 512, 3, 2, 1), (256, 512, 28, 28, 512, 3, 1, 0), (256, 520, 28, 28, 512, 3, 1, 1)):
-        assert ms.winograd_workspace(*args) == 0, args
-    # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits of the
-    # 41 * 196 = 8036 tile positions
-    assert ms.winograd_filter_workspace(256, 512, 28, 28, 512, 3, 1, 1) == 16 * 512 * 512 * 4 * (1 + 4) + 41 * 12845056
-    # c3_2: 256 -> 256 at 56 x 56: 784 tiles, 25 690 112 bytes per image, 20 per chunk; 2 x 2 tiles x 16 = 64 workgroups -> 16 splits
-    assert ms.winograd_filter_workspace(256, 256, 56, 56, 256, 3, 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 20 * 25690112
-    assert ms.winograd_filter_workspace(256, 192, 56, 56, 256, 3, 1, 1) == 0      # input channels not a multiple of 128
-    assert ms.winograd_filter_workspace(256, 256, 56, 56, 128, 3, 1, 1) == 0      # fewer than 256 output channels
