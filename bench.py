@@ -31,6 +31,8 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 ROOFLINE_TRAFFIC_BYTES = 3.580e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
+PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)
+HBM_PEAK_TBPS = 8.0
 
 
 def conv_layers_vgg16(batch):
@@ -159,14 +161,81 @@ def per_layer_sync_bound(trace, layer_ms, d2h_gbps, h2d_gbps):
     return ms
 
 
-def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None, layer_ms=None):
-    """policy: none | conv | all | dyn | fit, optionally with ":m" for the memory-optimal convolution algorithm;
-    or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille."""
+def layer_table(B, n, net):
+    """Per layer and pass of the planned step: the kernel it runs, its profiled time, its algorithmic work (FLOP of the
+    direct form for CONV / FC, bytes that have to cross HBM for the others) and the fraction of the roofline that bounds it;
+    and the step-weighted figures: all CONV / FC work of the step over all CONV / FC time, against the fp32 MFMA peak, by the
+    direct form's operation count and by the multiplications actually executed (Winograd F(2x2,3x3): 16 per 36)."""
+    shapes, _ = nets_shapes(net)
+    batch = net["batch"]
+    rows = []
+    tot = dict(flop=0.0, executed=0.0, mfma_ms=0.0, hbm_bytes=0.0, hbm_ms=0.0)
+    for i, l in enumerate(net["layers"]):
+        src = l["inputs"][0]
+        xin = (batch, net["in_c"], net["in_h"], net["in_w"]) if src < 0 else shapes[src]
+        out = shapes[i]
+        prof = n.layer_profile(i)
+        if l["type"] == "conv":
+            flop = 2.0 * batch * out[2] * out[3] * out[1] * xin[1] * l["k"] * l["k"]
+            kern = n.layer_kernels(i)
+            for pass_, kname in zip(("fwd", "bwd_data", "bwd_filter"), kern):
+                ms = prof.get((pass_, kname))
+                if ms is None or (pass_ == "bwd_data" and src < 0):
+                    continue
+                executed = flop * (16.0 / 36.0 if kname == "winograd" else 1.0)
+                rows.append(dict(layer=i, type="conv", what=pass_, kernel=kname, ms=ms, gflop=flop / 1e9, tflops=flop / ms / 1e9,
+                                 frac_of_mfma_peak=flop / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS, executed_frac_of_mfma_peak=executed / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS))
+                tot["flop"] += flop; tot["executed"] += executed; tot["mfma_ms"] += ms
+        elif l["type"] == "fc":
+            flop = 2.0 * batch * (xin[1] * xin[2] * xin[3]) * l["out"]
+            for pass_, mult in (("fwd", 1), ("bwd", 2 if src >= 0 else 1)):
+                ms = prof.get(pass_)
+                if ms:
+                    rows.append(dict(layer=i, type="fc", what=pass_, kernel="gemm", ms=ms, gflop=mult * flop / 1e9, tflops=mult * flop / ms / 1e9,
+                                     frac_of_mfma_peak=mult * flop / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS))
+                    tot["flop"] += mult * flop; tot["executed"] += mult * flop; tot["mfma_ms"] += ms
+        elif l["type"] != "softmax_ce":
+            nx, ny = 4.0 * batch * xin[1] * xin[2] * xin[3], 4.0 * batch * out[1] * out[2] * out[3]
+            traffic = dict(relu=(2 * ny, 3 * ny), maxpool=(nx + ny, 2 * nx + ny), avgpool=(nx + ny, nx + ny), concat=(2 * ny, 2 * ny))[l["type"]]
+            for pass_, nbytes in zip(("fwd", "bwd"), traffic):
+                ms = prof.get(pass_)
+                if ms:   # 0: a ReLU whose work runs inside a neighbouring kernel
+                    rows.append(dict(layer=i, type=l["type"], what=pass_, kernel="hbm", ms=ms, gbytes=nbytes / 1e9, tbps=nbytes / ms / 1e9,
+                                     frac_of_hbm_peak=nbytes / ms / 1e9 / HBM_PEAK_TBPS))
+                    tot["hbm_bytes"] += nbytes; tot["hbm_ms"] += ms
+    summary = dict(conv_fc_ms=tot["mfma_ms"], other_ms=tot["hbm_ms"],
+                   conv_fc_frac_of_mfma_peak_direct_count=tot["flop"] / tot["mfma_ms"] / 1e9 / FP32_MFMA_PEAK_TFLOPS if tot["mfma_ms"] else None,
+                   conv_fc_frac_of_mfma_peak_executed=tot["executed"] / tot["mfma_ms"] / 1e9 / FP32_MFMA_PEAK_TFLOPS if tot["mfma_ms"] else None,
+                   other_frac_of_hbm_peak=tot["hbm_bytes"] / tot["hbm_ms"] / 1e9 / HBM_PEAK_TBPS if tot["hbm_ms"] else None)
+    return rows, summary
+
+
+def nets_shapes(net):
+    from synth import nets
+    return nets.shapes(net)
+
+
+def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None, layer_ms=None, table=None):
+    """policy: none | conv | all | dyn | fit, optionally with ":m" / ":greedy" for another convolution algorithm mode;
+    or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille.
+    dyn and fit are preceded by the profiling passes (Section 3.3), outside the timed region."""
     import torch
     n = B.Net(net, budget)
     n.set_winograd(WINOGRAD)
     if window_part_mib is not None:
         n.set_window_part(int(window_part_mib * (1 << 20)))
+    profile_s = None
+    if PROFILE and policy in ("dyn", "fit"):
+        # what vDNN_dyn's first pass establishes: the network can be trained at all (vDNN_all, memory-optimal); its pool is
+        # where the layers are then profiled
+        n.set_conv_algo("m")
+        if n.try_policy("all") == B.OK:
+            n.set_conv_algo("p")
+            n.attach_torch(streams=streams())
+            t0 = time.perf_counter()
+            n.profile(2)
+            profile_s = time.perf_counter() - t0
+        n.set_conv_algo("p")
     if policy.startswith("set:"):
         _, ids, *fills = policy.split(":")
         status = n.try_offload_set({int(v) for v in ids.split("+") if v}, *[int(f) for f in fills])
@@ -183,7 +252,8 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
         msg = n.last_error()
         n.close()
         return dict(status="oom" if status == B.ERR_OOM_DEVICE else "error %d" % status, detail=msg)
-    n.attach_torch(streams=streams())
+    if profile_s is None:
+        n.attach_torch(streams=streams())
     for i, w in weights.items():
         n.set_weights(i, w)
     loss = None
@@ -216,7 +286,17 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
                n_offload=st["n_offload"], n_prefetch=st["n_prefetch"], n_ondemand_fetch=st["n_ondemand_fetch"],
                d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
                conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"], window_fill_bwd_pm=st["window_fill_bwd_pm"],
-               offload_set=sorted(n.offload_set()), per_step_ms=per_step)
+               offload_set=sorted(n.offload_set()), per_step_ms=per_step, n_winograd_convs=st["n_winograd_convs"], n_downgraded_convs=st["n_downgraded_convs"],
+               kernels="/".join("%s%s%s" % tuple(k[0] for k in n.layer_kernels(i)) for i, l in enumerate(net["layers"]) if l["type"] == "conv"))
+    if profile_s is not None:
+        out["profile_s"] = profile_s
+        out["estimated_ms"] = n.estimate_step_ms()
+        out["link_gbps_profiled"] = n.link_rate()
+    if table is not None and policy == "none":
+        n.profile(3)
+        rows, summary = layer_table(B, n, net)
+        table["rows"], table["summary"] = rows, summary
+        out["estimated_ms"] = n.estimate_step_ms()
     if st["offloaded_bytes"]:
         # the step cannot be shorter than the time the host link needs for the bytes of each pass
         link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
@@ -250,9 +330,12 @@ def main():
     ap.add_argument("--no-roofline", action="store_true", help="skip the roofline kernel (for a profile of the steps alone)")
     ap.add_argument("--no-winograd", action="store_true", help="keep every plan on the direct convolution kernels (side measurement)")
     ap.add_argument("--cpu-sample-batch", type=int, default=8)
+    ap.add_argument("--no-profile", action="store_true", help="dyn and fit decide without the profiling passes")
+    ap.add_argument("--no-layer-table", action="store_true", help="skip the per-layer table of the no-offload step")
     args = ap.parse_args()
-    global WINOGRAD
+    global WINOGRAD, PROFILE
     WINOGRAD = not args.no_winograd
+    PROFILE = not args.no_profile
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the vDNN step is a single-GPU method); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -299,9 +382,10 @@ def main():
     budget = int(args.budget_gib * GIB)
     policies = {}
     layer_ms = []   # filled by the no-offload run; the offloading policies are compared with the bound it implies
+    table = None if args.no_layer_table else {}
     for pol in args.policies.split(","):
         policies[pol] = run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else budget, args.steps, args.warmup,
-                                   layer_ms=layer_ms)
+                                   layer_ms=layer_ms, table=table)
         print("[bench] %s: %s" % (pol, json.dumps(policies[pol])), file=sys.stderr, flush=True)
     head = policies.get("dyn") or next(iter(policies.values()))
     head_name = "dyn" if "dyn" in policies else next(iter(policies))
@@ -310,6 +394,13 @@ def main():
         for p in policies.values():
             if p.get("status") == "ok":
                 p["vs_no_offload"] = p["img_per_s"] / none["img_per_s"]
+    # offloading changes where bytes live, not their values: every policy that runs the same kernels has the same loss, bit for bit
+    by_kernels = {}
+    for name, p in policies.items():
+        if p.get("status") == "ok":
+            by_kernels.setdefault(p["kernels"], set()).add(p["loss"])
+    identical = all(len(v) == 1 for v in by_kernels.values())
+    assert identical, "policies that run the same kernels computed different losses: %r" % by_kernels
     rf = None if args.no_roofline else roofline(B, args.batch)
     out = {
         "metric": "img/s VGG-16 b%d fp32 under %g GiB budget (vDNN_%s)" % (args.batch, args.budget_gib, head_name),
@@ -322,8 +413,11 @@ def main():
         "step_tflops_achieved": 23.718 * args.batch / 256 / (head["ms_per_step"] / 1e3) if head.get("ms_per_step") else None,
         "peak_gpu_bytes": head.get("peak_bytes"),
         "policies": policies,
+        "loss_bit_identical_across_policies_with_equal_kernels": identical,
         "roofline": rf,
     }
+    if table:
+        out["no_offload_step_by_layer"] = table
     if args.kernel_table:
         out["conv_kernels"] = conv_kernel_table(B, args.batch)
     if not args.no_cpu_baseline:

@@ -144,6 +144,11 @@ vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
  * reduction-split partial sums).  Other layers: none.  count receives the number of entries, at most cap are written. */
 vdnn_status_t vdnn_layer_workspace_options(const vdnn_net_t*, int layer, int32_t bwd, uint64_t* bytes /*host, may be NULL*/, size_t cap,
                                            size_t* count);
+/* Names the kernels of a CONV layer (forward, backward-data, backward-filter): they become the layer's only way to run, in
+ * every mode.  kernels = NULL gives the layer its list back.  VDNN_ERR_INVALID_ARG for a kernel that does not apply to the
+ * layer's shape.  Takes effect at the next vdnn_set_policy / vdnn_set_offload_set.  With the kernels of a greedy plan named
+ * on another net of the same shape, the two compute the same bits whatever their policies and budgets. */
+vdnn_status_t vdnn_set_layer_kernels(vdnn_net_t*, int layer, const int32_t kernels[3] /*host, may be NULL*/);
 /* The kernels (vdnn_conv_kernel_t) the current plan runs for a CONV layer's forward, backward-data and backward-filter pass. */
 vdnn_status_t vdnn_layer_kernels(const vdnn_net_t*, int layer, int32_t kernels[3] /*host*/);
 /* VDNN_POLICY_FIT goes beyond the paper.  Section 3.3 motivates vDNN_dyn by the cost of offloading more
@@ -191,6 +196,25 @@ vdnn_status_t vdnn_set_window_part(vdnn_net_t*, size_t part_bytes);
 vdnn_status_t vdnn_get_offload_set(const vdnn_net_t*, int32_t* buffers /*host, may be NULL*/, size_t cap, size_t* count);
 /* Algorithm for the static policies; takes effect at the next vdnn_set_policy. */
 vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);
+
+/* Section 3.3, "Dynamic vDNN": the profiling passes.  Runs every layer alone on the GPU (zero-filled tensors laid out in the
+ * pool of the current plan, which therefore has to be one that fits): its forward and backward computation as a planned step
+ * launches them, and for CONV layers every kernel that applies, pass by pass, `repeats` times each after a warm-up launch;
+ * and measures the rate of the host link in both directions.  Afterwards each CONV layer's list (vdnn_conv_kernel_t) is
+ * ordered by measured time, and vdnn_set_policy(DYN) / (FIT) choose by estimated step time (see there).  Overwrites dW and
+ * whatever the pool holds above the weights; weights stay.  Takes effect at the next vdnn_set_policy / vdnn_set_offload_set.
+ * vdnn_set_layer_profile / vdnn_set_link_rate put numbers in by hand (a profile kept from an earlier run; tests of the
+ * host logic, which need no GPU): pass is a vdnn_conv_pass_t for CONV layers, 0 = forward / 1 = backward (kernel ignored)
+ * for all others; ms >= 0.  vdnn_get_layer_profile: ms < 0 = not measured. */
+vdnn_status_t vdnn_profile(vdnn_net_t*, int32_t repeats);
+vdnn_status_t vdnn_set_layer_profile(vdnn_net_t*, int layer, int32_t pass, int32_t kernel, float ms);
+vdnn_status_t vdnn_get_layer_profile(const vdnn_net_t*, int layer, int32_t pass, int32_t kernel, float* ms /*host*/);
+/* Duration of the current plan's step as the profile predicts it: the op list replayed on two timelines (Section 3.2: the
+ * compute stream and the memory stream), a layer taking its measured time, a copy its bytes over the measured link rate,
+ * the two meeting where the plan synchronises them.  VDNN_ERR_STATE without a profile or a valid plan. */
+vdnn_status_t vdnn_estimate_step_ms(const vdnn_net_t*, double* ms /*host*/);
+vdnn_status_t vdnn_set_link_rate(vdnn_net_t*, double d2h_gbps, double h2d_gbps);
+vdnn_status_t vdnn_get_link_rate(const vdnn_net_t*, double* d2h_gbps /*host*/, double* h2d_gbps /*host*/);
 
 /* Forward propagation, layers 0..L-1 (Section 2.2; offload per Section 3.2 "Memory Offload").
  * input: (device) batch*in_c*in_h*in_w floats; labels: (device) batch int32 in [0, classes).

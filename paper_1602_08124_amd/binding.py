@@ -66,9 +66,16 @@ EXPORTS = {
     "vdnn_set_winograd": ([_vp, C.c_int32], _i),
     "vdnn_layer_workspace_options": ([_vp, _i, C.c_int32, C.POINTER(C.c_uint64), _sz, C.POINTER(_sz)], _i),
     "vdnn_layer_kernels": ([_vp, _i, C.POINTER(C.c_int32)], _i),
+    "vdnn_set_layer_kernels": ([_vp, _i, C.POINTER(C.c_int32)], _i),
     "vdnn_set_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.c_int32, C.c_int32], _i),
     "vdnn_get_offload_set": ([_vp, C.POINTER(C.c_int32), _sz, C.POINTER(_sz)], _i),
     "vdnn_set_window_part": ([_vp, _sz], _i),
+    "vdnn_profile": ([_vp, C.c_int32], _i),
+    "vdnn_set_layer_profile": ([_vp, _i, C.c_int32, C.c_int32, C.c_float], _i),
+    "vdnn_get_layer_profile": ([_vp, _i, C.c_int32, C.c_int32, C.POINTER(C.c_float)], _i),
+    "vdnn_estimate_step_ms": ([_vp, C.POINTER(C.c_double)], _i),
+    "vdnn_set_link_rate": ([_vp, C.c_double, C.c_double], _i),
+    "vdnn_get_link_rate": ([_vp, C.POINTER(C.c_double), C.POINTER(C.c_double)], _i),
     "vdnn_set_layer_timing": ([_vp, C.c_int32], _i),
     "vdnn_layer_times": ([_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), _sz], _i),
     "vdnn_forward": ([_vp, _vp, _vp, C.POINTER(C.c_float)], _i),
@@ -186,6 +193,11 @@ class Net:
         self._chk(lib.vdnn_layer_kernels(self.h, layer, arr))
         return tuple(KERNEL_NAME[v] for v in arr)
 
+    def set_layer_kernels(self, layer, names):
+        """names: (forward, backward-data, backward-filter) kernel names, or None to give the layer its list back."""
+        arr = None if names is None else (C.c_int32 * 3)(*[KERNEL[v] for v in names])
+        self._chk(lib.vdnn_set_layer_kernels(self.h, layer, arr))
+
     def set_conv_algo(self, algo):
         """"p" (performance-optimal, workspace), "m" (memory-optimal) or "greedy"; applies at the next set_policy."""
         self._chk(lib.vdnn_set_conv_algo(self.h, ALGO[algo]))
@@ -203,6 +215,45 @@ class Net:
         arr = (C.c_int32 * max(len(ids), 1))(*ids)
         fb = window_fill_pm if window_fill_bwd_pm is None else window_fill_bwd_pm
         return lib.vdnn_set_offload_set(self.h, arr, len(ids), window_fill_pm, fb)
+
+    def profile(self, repeats=2):
+        """The profiling passes of vDNN_dyn (needs a plan that fits and a GPU)."""
+        self._chk(lib.vdnn_profile(self.h, repeats))
+
+    def set_layer_profile(self, layer, pass_, kernel, ms):
+        self._chk(lib.vdnn_set_layer_profile(self.h, layer, PASS[pass_] if isinstance(pass_, str) else pass_,
+                                             KERNEL[kernel] if isinstance(kernel, str) else kernel, ms))
+
+    def layer_profile(self, layer):
+        """CONV: {(pass, kernel): ms} of what was measured; other layers: {"fwd": ms, "bwd": ms}."""
+        v = C.c_float()
+        out = {}
+        if self.net["layers"][layer]["type"] == "conv":
+            for pn, p in PASS.items():
+                for kn, k in KERNEL.items():
+                    if k >= 0:
+                        self._chk(lib.vdnn_get_layer_profile(self.h, layer, p, k, C.byref(v)))
+                        if v.value >= 0:
+                            out[pn, kn] = v.value
+        else:
+            for pn, p in (("fwd", 0), ("bwd", 1)):
+                self._chk(lib.vdnn_get_layer_profile(self.h, layer, p, 0, C.byref(v)))
+                if v.value >= 0:
+                    out[pn] = v.value
+        return out
+
+    def estimate_step_ms(self):
+        v = C.c_double()
+        self._chk(lib.vdnn_estimate_step_ms(self.h, C.byref(v)))
+        return v.value
+
+    def set_link_rate(self, d2h_gbps, h2d_gbps):
+        self._chk(lib.vdnn_set_link_rate(self.h, d2h_gbps, h2d_gbps))
+
+    def link_rate(self):
+        a, b = C.c_double(), C.c_double()
+        self._chk(lib.vdnn_get_link_rate(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def set_layer_timing(self, on=True):
         self._chk(lib.vdnn_set_layer_timing(self.h, int(on)))

@@ -160,6 +160,7 @@ void build_kernel_options(vdnn_net& n) {
     n.options_fwd.assign(L, {});
     n.options_bwd.assign(L, {});
     if ((int)n.profile.size() != L) n.profile.assign(L, LayerProfile());
+    if ((int)n.pinned_kernels.size() != L) n.pinned_kernels.assign(L, -1);
     for (int i = 0; i < L; ++i) {
         const Layer& l = n.layers[i];
         int C, H, W;
@@ -180,13 +181,24 @@ void build_kernel_options(vdnn_net& n) {
         // unprofiled: Winograd before the packed-weight kernel before the gather kernel (measured on the paper's workloads)
         auto cost_of = [&](int pass, int k) { return n.profiled && pr.conv[pass][k] >= 0 ? (double)pr.conv[pass][k] : (double)(kNumKernels - k); };
         auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (k != kKernelWinograd || n.winograd); };
+        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
+        if (n.pinned_kernels[i] >= 0) {  // the caller named the kernels: the layer's only way to run
+            const int kf = n.pinned_kernels[i] & 15, kd = (n.pinned_kernels[i] >> 4) & 15, kb = (n.pinned_kernels[i] >> 8) & 15;
+            KernelOption f, b;
+            f.fwd = kf; f.ws = ws_of(kPassFwd, kf); f.cost = cost_of(kPassFwd, kf);
+            b.bd = need_dx ? kd : kKernelGather; b.bf = kb;
+            b.ws = std::max(ws_of(kPassBwdFilter, kb), need_dx ? ws_of(kPassBwdData, kd) : (size_t)0);
+            b.cost = cost_of(kPassBwdFilter, kb) + (need_dx ? cost_of(kPassBwdData, kd) : 0.0);
+            n.options_fwd[i].push_back(f);
+            n.options_bwd[i].push_back(b);
+            continue;
+        }
         for (int k = 0; k < kNumKernels; ++k) {
             if (!usable(kPassFwd, k)) continue;
             KernelOption o;
             o.fwd = k; o.ws = ws_of(kPassFwd, k); o.cost = cost_of(kPassFwd, k);
             n.options_fwd[i].push_back(o);
         }
-        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
         for (int kf = 0; kf < kNumKernels; ++kf) {
             if (!usable(kPassBwdFilter, kf)) continue;
             for (int kd = 0; kd < kNumKernels; ++kd) {

@@ -303,6 +303,153 @@ static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// profiling passes (Section 3.3, "Dynamic vDNN": the layer-wise times of every algorithm are measured on the GPU
+// before the policy is chosen)
+// ---------------------------------------------------------------------------------------------
+// Mean time of `reps` launches of `launch` on the compute stream after one warm-up launch.
+template <class F>
+static vdnn_status_t time_launches(vdnn_net& n, int reps, float* ms_out, F launch) {
+    hipError_t e = launch();
+    if (e != hipSuccess) { n.err = fmt("profile: launch failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); return VDNN_ERR_HIP; }
+    NEWEV(e0);
+    NEWEV(e1);
+    HIPCHK(hipEventRecord(n.events[e0], n.sc));
+    for (int r = 0; r < reps; ++r) {
+        e = launch();
+        if (e != hipSuccess) { n.err = fmt("profile: launch failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); return VDNN_ERR_HIP; }
+    }
+    HIPCHK(hipEventRecord(n.events[e1], n.sc));
+    HIPCHK(hipStreamSynchronize(n.sc));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, n.events[e0], n.events[e1]));
+    *ms_out = ms / (float)reps;
+    n.events_used -= 2;
+    return VDNN_OK;
+}
+
+// Every layer runs alone on zero-filled tensors laid out in the transient part of the pool: forward and backward computation
+// as a planned step would launch them, and for CONV layers every kernel that applies, pass by pass.  A layer whose tensors
+// do not fit the pool by themselves stays unmeasured (it could not run under this budget either).
+static vdnn_status_t profile_layers(vdnn_net& n, int reps) {
+    const int L = (int)n.layers.size();
+    const Plan saved = n.plan;
+    const size_t base = saved.persistent, room = n.pool_bytes - base;
+    HIPCHK(hipMemsetAsync(n.pool + base, 0, room, n.sc));
+    HIPCHK(hipMemsetAsync(blk(n, saved.labels_block), 0, (size_t)n.batch * 4, n.sc));
+    n.profile.assign(L, LayerProfile());
+    vdnn_status_t status = VDNN_OK;
+    for (int i = 0; i < L && status == VDNN_OK; ++i) {
+        const Layer& l = n.layers[i];
+        LayerProfile& pr = n.profile[i];
+        // a scratch plan: the persistent blocks of the real one, then this layer's tensors one after the other
+        Plan q;
+        q.ok = true;
+        for (const Block& pb : saved.blocks) {  // the persistent blocks come first in every plan
+            if (!pb.persistent) break;
+            q.blocks.push_back(pb);
+        }
+        q.w_block = saved.w_block; q.dw_block = saved.dw_block; q.labels_block = saved.labels_block; q.loss_block = saved.loss_block;
+        q.persistent = saved.persistent;
+        size_t off = base;
+        auto add = [&](size_t bytes) {
+            Block b;
+            b.raw = bytes; b.bytes = align_up(std::max<size_t>(bytes, 1)); b.offset = off;
+            off += b.bytes;
+            q.blocks.push_back(b);
+            return (int)q.blocks.size() - 1;
+        };
+        Op f, b;
+        f.kind = OP_FWD; b.kind = OP_BWD;
+        f.layer = b.layer = i;
+        const size_t out_bytes = l.type == VDNN_SOFTMAX_CE ? 0 : n.B(l.buf).count * 4;
+        for (int src : l.inputs) {
+            const int bb = buf_of(n, src);
+            const int x = add(n.B(bb).count * 4);
+            f.in_blocks.push_back(x);
+            b.in_blocks.push_back(x);
+            b.gout_blocks.push_back(bb >= 0 && !in_place(l.type) ? add(n.B(bb).count * 4) : -1);
+            b.gacc_blocks.push_back(-1);
+        }
+        if (in_place(l.type)) { f.out_block = b.out_block = f.in_blocks[0]; b.gin_block = add(out_bytes); }
+        else if (l.type != VDNN_SOFTMAX_CE) { f.out_block = b.out_block = add(out_bytes); b.gin_block = add(out_bytes); }
+        const size_t ws_off = off;
+        if (off - base > room) continue;  // does not fit by itself
+        n.plan = q;
+        if (l.type == VDNN_CONV) {
+            int C, H, W;
+            shape_of(n, l.inputs[0], &C, &H, &W);
+            const int N = n.batch;
+            float* x = blk(n, f.in_blocks[0]);
+            float* y = blk(n, f.out_block);
+            float* dy = blk(n, b.gin_block);
+            float* dx = b.gout_blocks[0] >= 0 ? blk(n, b.gout_blocks[0]) : nullptr;
+            float* w = blk(n, q.w_block[i]);
+            float* dw = blk(n, q.dw_block[i]);
+            void* ws = n.pool + ws_off;
+            for (int pass = 0; pass < 3 && status == VDNN_OK; ++pass) {
+                if (pass == kPassBwdData && !dx) continue;
+                for (int k = 0; k < kNumKernels && status == VDNN_OK; ++k) {
+                    const size_t need = conv_workspace(pass, k, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
+                    if (need == kNoKernel || ws_off - base + align_up(need) > room) continue;
+                    status = time_launches(n, reps, &pr.conv[pass][k], [&]() {
+                        if (pass == kPassFwd) return conv_fwd(x, w, y, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, fold_fwd(n, i) ? 1 : 0, k, n.sc);
+                        if (pass == kPassBwdData) return conv_bwd_data(dy, w, dx, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, fold_bwd(n, i) ? x : nullptr, k, n.sc);
+                        return conv_bwd_filter(x, dy, dw, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, k, n.sc);
+                    });
+                }
+            }
+        } else {
+            const std::vector<KernelOption>& of = n.options_fwd[i];
+            const std::vector<KernelOption>& ob = n.options_bwd[i];
+            const size_t wsf = of.empty() ? 0 : of[0].ws, wsb = ob.empty() ? 0 : ob[0].ws;
+            if (ws_off - base + align_up(std::max(wsf, wsb)) > room) { n.plan = saved; continue; }
+            if (wsf) { f.ws_block = add(wsf); off = ws_off; }
+            if (wsb) { b.ws_block = add(wsb); off = ws_off; }
+            n.plan.blocks = q.blocks;
+            // a ReLU whose work a neighbouring layer does costs nothing by itself
+            const bool fwd_elsewhere = l.type == VDNN_RELU && l.fwd_folded_into >= 0 && fold_fwd(n, l.fwd_folded_into);
+            const bool bwd_elsewhere = l.type == VDNN_RELU && l.bwd_folded_into >= 0 && fold_bwd(n, l.bwd_folded_into);
+            if (fwd_elsewhere) pr.fwd = 0.f;
+            else status = time_launches(n, reps, &pr.fwd, [&]() { return run_fwd(n, f) == VDNN_OK ? hipSuccess : hipErrorUnknown; });
+            if (status != VDNN_OK) break;
+            if (bwd_elsewhere) pr.bwd = 0.f;
+            else status = time_launches(n, reps, &pr.bwd, [&]() { return run_bwd(n, b) == VDNN_OK ? hipSuccess : hipErrorUnknown; });
+        }
+        n.plan = saved;
+    }
+    n.plan = saved;
+    return status;
+}
+
+// Rate of the host link in each direction: a 256 MiB block between the pool and pinned host memory on the memory stream.
+static vdnn_status_t profile_link(vdnn_net& n) {
+    const size_t bytes = std::min<size_t>((size_t)256 << 20, (n.pool_bytes - n.plan.persistent) / kAlign * kAlign);
+    if (bytes < ((size_t)1 << 20)) return VDNN_OK;  // a pool this small tells nothing about the link
+    char* host = nullptr;
+    if (hipHostMalloc((void**)&host, bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); n.err = "profile: no pinned host memory for the link test"; return VDNN_ERR_OOM_HOST; }
+    char* dev = n.pool + n.plan.persistent;
+    vdnn_status_t status = VDNN_OK;
+    for (int dir = 0; dir < 2 && status == VDNN_OK; ++dir) {
+        hipError_t e = hipSuccess;
+        float ms = 0.f;
+        int e0 = -1, e1 = -1;
+        { hipError_t ee; e0 = new_event(n, &ee); e1 = e0 >= 0 ? new_event(n, &ee) : -1; if (e1 < 0) { e = ee; } }
+        for (int r = 0; r < 3 && e == hipSuccess; ++r) {  // the first copy warms the path up; the last two are timed
+            if (r == 1) e = hipEventRecord(n.events[e0], n.sm);
+            if (e == hipSuccess) e = dir == 0 ? hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, n.sm) : hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, n.sm);
+        }
+        if (e == hipSuccess) e = hipEventRecord(n.events[e1], n.sm);
+        if (e == hipSuccess) e = hipStreamSynchronize(n.sm);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, n.events[e0], n.events[e1]);
+        if (e != hipSuccess) { n.err = fmt("profile: link test failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); status = VDNN_ERR_HIP; break; }
+        (dir == 0 ? n.link_d2h_gbps : n.link_h2d_gbps) = ms > 0.f ? 2.0 * (double)bytes / (ms * 1e6) : 0.0;
+        n.events_used -= 2;
+    }
+    (void)hipHostFree(host);
+    return status;
+}
+
+// ---------------------------------------------------------------------------------------------
 // C ABI
 // ---------------------------------------------------------------------------------------------
 extern "C" {
@@ -598,6 +745,97 @@ vdnn_status_t vdnn_layer_kernels(const vdnn_net_t* n, int layer, int32_t kernels
     if (!n->plan.ok) return VDNN_ERR_STATE;
     const KernelOption &f = n->options_fwd[layer][n->plan.opt_fwd[layer]], &b = n->options_bwd[layer][n->plan.opt_bwd[layer]];
     kernels[0] = f.fwd; kernels[1] = b.bd; kernels[2] = b.bf;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_layer_kernels(vdnn_net_t* np, int layer, const int32_t kernels[3]) {
+    if (!np || layer < 0 || layer >= (int)np->layers.size() || np->layers[layer].type != VDNN_CONV) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    if (!kernels) {
+        n.pinned_kernels[layer] = -1;
+    } else {
+        const Layer& l = n.layers[layer];
+        int C, H, W;
+        shape_of(n, l.inputs[0], &C, &H, &W);
+        const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
+        for (int pass = 0; pass < 3; ++pass) {
+            if (pass == kPassBwdData && !need_dx) continue;
+            if (kernels[pass] < 0 || kernels[pass] >= kNumKernels ||
+                conv_workspace(pass, kernels[pass], n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad) == kNoKernel) {
+                n.err = fmt("set_layer_kernels: kernel %d does not apply to pass %d of layer %d", kernels[pass], pass, layer);
+                return VDNN_ERR_INVALID_ARG;
+            }
+        }
+        n.pinned_kernels[layer] = kernels[0] | (need_dx ? kernels[1] : 0) << 4 | kernels[2] << 8;
+    }
+    build_kernel_options(n);
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_profile(vdnn_net_t* np, int32_t repeats) {
+    if (!np || repeats < 1 || repeats > 100) return VDNN_ERR_INVALID_ARG;
+    vdnn_net& n = *np;
+    vdnn_status_t s = ensure_device(n);   // needs a plan that fits: its pool is where the layers run
+    if (s != VDNN_OK) return s;
+    n.fwd_done = false;
+    n.events_used = 0;
+    n.copies.clear();
+    n.stalls.clear();
+    n.layer_marks.clear();
+    s = profile_layers(n, repeats);
+    if (s == VDNN_OK) s = profile_link(n);
+    (void)hipStreamSynchronize(n.sc);
+    (void)hipStreamSynchronize(n.sm);
+    if (s != VDNN_OK) return s;
+    n.profiled = true;
+    build_kernel_options(n);
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_layer_profile(vdnn_net_t* n, int layer, int32_t pass, int32_t kernel, float ms) {
+    if (!n || layer < 0 || layer >= (int)n->layers.size() || pass < 0 || pass > 2 || !(ms >= 0.f)) return VDNN_ERR_INVALID_ARG;
+    vdnn::LayerProfile& pr = n->profile[layer];
+    if (n->layers[layer].type == VDNN_CONV) {
+        if (kernel < 0 || kernel >= kNumKernels) return VDNN_ERR_INVALID_ARG;
+        pr.conv[pass][kernel] = ms;
+    } else {
+        if (pass > 1) return VDNN_ERR_INVALID_ARG;
+        (pass == 0 ? pr.fwd : pr.bwd) = ms;
+    }
+    n->profiled = true;
+    build_kernel_options(*n);
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_get_layer_profile(const vdnn_net_t* n, int layer, int32_t pass, int32_t kernel, float* ms) {
+    if (!n || !ms || layer < 0 || layer >= (int)n->layers.size() || pass < 0 || pass > 2) return VDNN_ERR_INVALID_ARG;
+    const vdnn::LayerProfile& pr = n->profile[layer];
+    if (n->layers[layer].type == VDNN_CONV) {
+        if (kernel < 0 || kernel >= kNumKernels) return VDNN_ERR_INVALID_ARG;
+        *ms = pr.conv[pass][kernel];
+    } else {
+        if (pass > 1) return VDNN_ERR_INVALID_ARG;
+        *ms = pass == 0 ? pr.fwd : pr.bwd;
+    }
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_estimate_step_ms(const vdnn_net_t* n, double* ms) {
+    if (!n || !ms) return VDNN_ERR_INVALID_ARG;
+    if (!n->plan.ok || !n->profiled) return VDNN_ERR_STATE;
+    *ms = estimate_step_ms(*n, n->plan);
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_set_link_rate(vdnn_net_t* n, double d2h_gbps, double h2d_gbps) {
+    if (!n || !(d2h_gbps > 0.0) || !(h2d_gbps > 0.0)) return VDNN_ERR_INVALID_ARG;
+    n->link_d2h_gbps = d2h_gbps; n->link_h2d_gbps = h2d_gbps;
+    return VDNN_OK;
+}
+
+vdnn_status_t vdnn_get_link_rate(const vdnn_net_t* n, double* d2h_gbps, double* h2d_gbps) {
+    if (!n || !d2h_gbps || !h2d_gbps) return VDNN_ERR_INVALID_ARG;
+    *d2h_gbps = n->link_d2h_gbps; *h2d_gbps = n->link_h2d_gbps;
     return VDNN_OK;
 }
 

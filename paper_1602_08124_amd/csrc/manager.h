@@ -155,6 +155,7 @@ struct vdnn_net {
     // workspace).  Every plan of the net takes its kernels from here, so that plans under different policies and budgets
     // compute the same bits; only the greedy mode (Section 3.3, phase 3) moves a layer down its list.
     std::vector<std::vector<vdnn::KernelOption>> options_fwd, options_bwd;
+    std::vector<int> pinned_kernels;  // per layer: -1, or fwd | bd << 4 | bf << 8 set by vdnn_set_layer_kernels (the layer's only option then)
     std::vector<vdnn::LayerProfile> profile;
     bool profiled = false;
     double link_d2h_gbps = 0.0, link_h2d_gbps = 0.0;  // measured by the profiling pass (0: not measured)
@@ -231,7 +232,8 @@ size_t baseline_bytes(const vdnn_net& n);
 // stops after the byte accounting (p.ok then only says that the live total fits); fill_pm / fill_bwd_pm > 0 turn the
 // transfer windows on.
 void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set = nullptr, bool place = true,
-                  int fill_pm = 0, int fill_bwd_pm = 0);
+                  int fill_pm = 0, int fill_bwd_pm = 0, int place_rounds = 300);
 vdnn_status_t plan_policy(vdnn_net& n, int policy);
+double estimate_step_ms(const vdnn_net& n, const Plan& p);  // from the profile; < 0 without one
 
 }  // namespace vdnn

@@ -256,9 +256,13 @@ static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int s
            (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;         // and index (channel, tile) with 32 bits
 }
 
+// Images per chunk: as many as the chunk size holds, then evened out over the chunks that this takes (256 images at 167 per
+// chunk run as 128 + 128, not 167 + 89: the same number of launches on a smaller workspace).
 static int wino_chunk(int N, int cred, int H, int W, int rows) {
     const size_t per_image = (size_t)16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
-    return (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
+    const int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
+    const int chunks = (N + most - 1) / most;
+    return (N + chunks - 1) / chunks;
 }
 
 // V for images [n0, n0 + cur) of src

@@ -219,12 +219,12 @@ static size_t place_blocks(Plan& p, size_t base, size_t good_enough = 0, int rou
 // Compiles one training step under a static policy (NONE / ALL / CONV) and a convolution algorithm
 // mode: performance-optimal everywhere, memory-optimal everywhere, or greedy (performance-optimal
 // unless that layer's workspace would overflow the budget: Section 3.3, phase 3 of vDNN_dyn).
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm);
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm, int place_rounds);
 
 // offload_set (indexed by buffer id + 1), when given, replaces the policy's choice of feature maps;
 // place = false stops after the byte accounting (p.ok then only says that the live total fits).
 void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::vector<char>* offload_set, bool place, int fill_pm,
-                  int fill_bwd_pm) {
+                  int fill_bwd_pm, int place_rounds) {
     p = Plan();
     p.policy = policy;
     p.algo = algo;
@@ -417,7 +417,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
         p.n_winograd += f.fwd == kKernelWinograd || b.bd == kKernelWinograd || b.bf == kKernelWinograd;
         p.n_downgraded += algo == VDNN_ALGO_GREEDY && (p.opt_fwd[i] > 0 || p.opt_bwd[i] > 0);
     }
-    if (place) finish_plan(n, p, fill_pm, fill_bwd_pm);
+    if (place) finish_plan(n, p, fill_pm, fill_bwd_pm, place_rounds);
     else p.ok = true;
 }
 
@@ -749,7 +749,7 @@ static bool reserve_fetch_ranges(Plan& p, size_t soft_bwd) {
 }
 
 // Second half of planning: optional transfer windows, then lifetimes, statistics and placement.
-static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm) {
+static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm, int place_rounds) {
     const size_t budget = n.budget ? n.budget / kAlign * kAlign : (size_t)-1 / 4;
     p.ok = false;
     p.fill_pm = p.fill_bwd_pm = 0;
@@ -761,7 +761,7 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
         p.fill_pm = fill_pm;
     }
     measure_plan(p);
-    p.extent = place_blocks(p, p.persistent);
+    p.extent = place_blocks(p, p.persistent, 0, place_rounds);
     if (p.extent > budget) {
         p.fail_where = "placement";
         p.fail_why = fmt("live bytes peak at %zu but no placement of the blocks fits %zu (needs %zu)", p.peak, budget, p.extent);
@@ -776,7 +776,7 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
             if (pm > fill_bwd_pm) continue;
             Plan q = p;
             if (!reserve_fetch_ranges(q, soft(pm))) break;
-            const size_t e = place_blocks(q, q.persistent, budget, p.blocks.size() <= 600 ? 300 : 0);
+            const size_t e = place_blocks(q, q.persistent, budget, p.blocks.size() <= 600 ? place_rounds : 0);
             if (e <= budget) {
                 for (size_t i = 0; i < p.blocks.size(); ++i) p.blocks[i].offset = q.blocks[i].offset;
                 p.extent = e;
@@ -790,6 +790,54 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
         if (plan_overlaps(p)) p = kept;  // cannot happen by construction; a plan that fails the check is never run
     }
     p.ok = true;
+}
+
+// Estimated duration of a planned step from the profile (Section 3.3: vDNN_dyn decides from measured layer times; Section 3.2,
+// Fig. vdnn_fwd / vdnn_bwd: the step is two timelines, stream_compute and stream_memory, tied together where a transfer
+// starts and where the computation waits for it).  Replays the op list: a computation takes its layer's measured time;
+// a copy starts when the memory stream is free and everything enqueued before it on the compute stream has finished,
+// and takes bytes / link rate; a wait moves the compute stream to the end of that copy.  < 0: no profile.
+double estimate_step_ms(const vdnn_net& n, const Plan& p) {
+    if (!n.profiled || !p.ok) return -1.0;
+    const double d2h = (n.link_d2h_gbps > 0 ? n.link_d2h_gbps : 55.0) * 1e6, h2d = (n.link_h2d_gbps > 0 ? n.link_h2d_gbps : 55.0) * 1e6;  // bytes per ms
+    auto fwd_ms = [&](int i) -> double {
+        const LayerProfile& pr = n.profile[i];
+        if (n.layers[i].type != VDNN_CONV) return pr.fwd > 0 ? pr.fwd : 0.0;
+        const float t = pr.conv[kPassFwd][n.options_fwd[i][p.opt_fwd[i]].fwd];
+        return t > 0 ? t : 0.0;
+    };
+    auto bwd_ms = [&](int i) -> double {
+        const LayerProfile& pr = n.profile[i];
+        if (n.layers[i].type != VDNN_CONV) return pr.bwd > 0 ? pr.bwd : 0.0;
+        const KernelOption& o = n.options_bwd[i][p.opt_bwd[i]];
+        const float tf = pr.conv[kPassBwdFilter][o.bf], td = buf_of(n, n.layers[i].inputs[0]) >= 0 ? pr.conv[kPassBwdData][o.bd] : 0.f;
+        return (tf > 0 ? tf : 0.0) + (td > 0 ? td : 0.0);
+    };
+    constexpr int kSlots = 33;
+    std::vector<double> copy_end(p.blocks.size() * kSlots, 0.0);
+    double tc = 0.0, tm = 0.0;
+    for (int t = p.first_fwd_op; t < (int)p.ops.size(); ++t) {
+        if (t == p.first_bwd_op) tc = tm = std::max(tc, tm);  // vdnn_forward returns when both streams have drained
+        const Op& o = p.ops[t];
+        switch (o.kind) {
+            case OP_FWD: tc += fwd_ms(o.layer); break;
+            case OP_BWD: tc += bwd_ms(o.layer); break;
+            case OP_OFFLOAD:
+            case OP_PREFETCH:
+            case OP_ONDEMAND: {
+                const Block& b = p.blocks[o.block];
+                const double bytes = (double)(o.part < 0 ? b.raw : b.piece_raw(o.part));
+                const double end = std::max(tm, tc) + bytes / (o.kind == OP_OFFLOAD ? d2h : h2d);
+                tm = end;
+                copy_end[(size_t)o.block * kSlots + o.part + 1] = end;
+                if (o.kind == OP_ONDEMAND) tc = std::max(tc, end);
+                break;
+            }
+            case OP_WAIT_COPY: tc = std::max(tc, copy_end[(size_t)o.block * kSlots + o.part + 1]); break;
+            default: break;
+        }
+    }
+    return std::max(tc, tm);
 }
 
 // Section 3.3, "Dynamic vDNN".  Trainability of a pass is decided by the planner, which performs
@@ -836,6 +884,67 @@ static bool fit_select(const vdnn_net& n, int algo, std::vector<char>& set) {
     return true;
 }
 
+// With a profile, the byte-driven choice above is only the starting point: which feature maps are away decides when the
+// link is busy and when memory is short, and sets of equal size differ in how well their transfers hide behind the layers
+// (Section 3.1: reuse distance).  Local search on the estimated step time: exchange one member for one non-member, or for two
+// of about its size together, add one, or drop one; a move is taken when the step still fits and the estimate improves by half a per cent
+// or more; until no move does (at most four rounds).  Candidates are what vDNN_all would offload.
+static const int kSearchFills[] = {1000, 970, 950, 900, 800, 0};
+
+static bool plan_with_windows(const vdnn_net& n, int algo, const std::vector<char>& set, Plan& out) {
+    if (!fits_with(n, set, algo)) return false;
+    for (int f : kSearchFills) {
+        compile_plan(n, VDNN_POLICY_FIT, algo, out, &set, true, f, f ? 1000 : 0, 12);   // a search: few placement rounds per candidate
+        if (out.ok) return true;
+    }
+    return false;
+}
+
+static void improve_by_time(const vdnn_net& n, int algo, std::vector<char>& set, Plan& best) {
+    const int L = (int)n.layers.size();
+    std::vector<int> cands;
+    for (int b = -1; b < L; ++b)
+        if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL)) cands.push_back(b);
+    double best_ms = estimate_step_ms(n, best);
+    Plan q;
+    for (int round = 0; round < 4; ++round) {
+        std::vector<char> round_set = set;
+        double round_ms = best_ms;
+        Plan round_plan;
+        auto consider = [&](const std::vector<char>& t) {
+            if (!plan_with_windows(n, algo, t, q)) return;
+            const double ms = estimate_step_ms(n, q);
+            if (ms < round_ms) { round_ms = ms; round_set = t; round_plan = q; }
+        };
+        std::vector<int> in, out;
+        for (int b : cands) (set[b + 1] ? in : out).push_back(b);
+        for (int m : in) {
+            std::vector<char> t = set;
+            t[m + 1] = 0;
+            consider(t);                                    // drop one
+            for (size_t i = 0; i < out.size(); ++i) {
+                t[out[i] + 1] = 1;
+                consider(t);                                // one for one
+                for (size_t j = i + 1; j < out.size(); ++j) {
+                    const size_t both = n.B(out[i]).count + n.B(out[j]).count;
+                    if (2 * both < n.B(m).count || 4 * both > 5 * n.B(m).count) continue;   // two for one: 50 .. 125 % of its size
+                    t[out[j] + 1] = 1;
+                    consider(t);
+                    t[out[j] + 1] = 0;
+                }
+                t[out[i] + 1] = 0;
+            }
+        }
+        for (int a : out) {
+            std::vector<char> t = set;
+            t[a + 1] = 1;
+            consider(t);                                    // add one
+        }
+        if (round_ms > best_ms * 0.995) break;
+        set = round_set; best = round_plan; best_ms = round_ms;
+    }
+}
+
 static const int kFills[] = {1000, 990, 980, 970, 960, 950, 940, 930, 920, 910, 900, 880, 860, 840, 820, 800, 750, 700, 600, 500, 0};
 
 vdnn_status_t plan_policy(vdnn_net& n, int policy) {
@@ -848,26 +957,49 @@ vdnn_status_t plan_policy(vdnn_net& n, int policy) {
         if (algo < 0) { n.err = "fit: the step does not fit even with every CONV/POOL input offloaded and no workspace"; return VDNN_ERR_OOM_DEVICE; }
         // The set was chosen by live bytes; when no placement of the blocks fits the budget either (the live
         // peak then sits within a fraction of a percent of it), the largest remaining candidate is added.
-        for (;;) {
+        bool planned = false;
+        while (!planned) {
             // the largest forward share for which the blocks can be placed (the backward windows come out of the
             // placement and never make it fail)
             for (int f : kFills) {
                 compile_plan(n, policy, algo, p, &set, true, f, f ? 1000 : 0);
-                if (p.ok) { n.plan = p; n.policy = policy; n.effective = policy; return VDNN_OK; }
+                if (p.ok) { planned = true; break; }
             }
+            if (planned) break;
             int pick = -2;
             for (int b = -1; b < (int)n.layers.size(); ++b)
                 if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL) && !set[b + 1] && (pick == -2 || n.B(b).count > n.B(pick).count)) pick = b;
             if (pick == -2) break;
             set[pick + 1] = 1;
         }
-        n.err = p.fail_why;
-        return VDNN_ERR_OOM_DEVICE;
+        if (!planned) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
+        if (n.profiled && n.budget) improve_by_time(n, algo, set, p);
+        n.plan = p; n.policy = policy; n.effective = policy;
+        return VDNN_OK;
     }
     if (policy == VDNN_POLICY_DYN) {
         Plan first;
         compile_plan(n, VDNN_POLICY_ALL, VDNN_ALGO_MEM, first);
         if (!first.ok) { n.err = "vDNN_dyn: even vDNN_all with the memory-optimal algorithm does not fit: " + first.fail_why; return VDNN_ERR_OOM_DEVICE; }
+        if (n.profiled) {
+            // With measured layer times and link rates the passes need not be tried in a fixed order that stands in for
+            // "fastest first": every configuration of phases 2 and 3 (and no offloading with the greedy downgrade, which
+            // the paper's order never reaches) is planned, and the one with the shortest estimated step is adopted.
+            static const int cands[6][2] = {{VDNN_POLICY_NONE, VDNN_ALGO_PERF}, {VDNN_POLICY_CONV, VDNN_ALGO_PERF}, {VDNN_POLICY_ALL, VDNN_ALGO_PERF},
+                                            {VDNN_POLICY_NONE, VDNN_ALGO_GREEDY}, {VDNN_POLICY_CONV, VDNN_ALGO_GREEDY}, {VDNN_POLICY_ALL, VDNN_ALGO_GREEDY}};
+            Plan best;
+            double best_ms = -1.0;
+            int best_pol = -1;
+            for (auto& c : cands) {
+                compile_plan(n, c[0], c[1], p);
+                if (!p.ok) continue;
+                const double ms = estimate_step_ms(n, p);
+                if (best_pol < 0 || ms < best_ms) { best = p; best_ms = ms; best_pol = c[0]; }
+            }
+            if (best_pol >= 0) { n.plan = best; n.policy = policy; n.effective = best_pol; return VDNN_OK; }
+            n.plan = first; n.policy = policy; n.effective = VDNN_POLICY_ALL;
+            return VDNN_OK;
+        }
         const int order[3] = {VDNN_POLICY_NONE, VDNN_POLICY_CONV, VDNN_POLICY_ALL};
         for (int pol : order) {
             compile_plan(n, pol, VDNN_ALGO_PERF, p);

@@ -85,10 +85,15 @@ def test_conv_layer_full_size(B, cfg):
         assert abs(a - b) < bound
 
 
-def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=True):
-    """The library's default settings unless winograd=False (no plan uses the Winograd kernel)."""
+def _run(B, net, x_dev, lab_dev, weights, policy, budget, hooks=(), winograd=True, algo=None, kernels=None):
+    """The library's default settings unless winograd=False (no plan uses the Winograd kernel), algo names another
+    algorithm mode for a static policy, or kernels = {conv layer: (fwd, bwd-data, bwd-filter)} names the kernels."""
     n = B.Net(net, budget)
     n.set_winograd(winograd)
+    if algo:
+        n.set_conv_algo(algo)
+    for i, names in (kernels or {}).items():
+        n.set_layer_kernels(i, names)
     n.set_policy(policy)
     if policy == "fit" and budget:
         st = n.stats()
@@ -187,32 +192,38 @@ def test_vgg16_b256_direct_kernels_only(B):
             assert np.array_equal(dw[i], base_dw[i]), (pol, i)
 
 
-@pytest.mark.parametrize("name,policy,budget", [("alexnet", "conv", 1 * G), ("overfeat", "all", 2 * G), ("overfeat", "conv", 2 * G),
-                                                ("googlenet", "dyn", 3 * G), ("googlenet", "all", 3 * G),
-                                                ("alexnet", "fit", 900 << 20), ("googlenet", "fit", 2 * G), ("vgg116_b32", "fit", 4 * G)])
-def test_other_workloads_full_size(B, name, policy, budget):
-    """AlexNet / OverFeat / GoogLeNet shaped workloads at batch 128 under their budgets: bit-identical to the
-    no-offload run, statistics equal to the memory-schedule oracle."""
+# The static policies run the performance-optimal kernels and fail where a workspace does not fit (the paper's vDNN_conv (p));
+# where the stated budget is too small for that, the configuration runs the greedy mode (Section 3.3).
+OTHER = [("alexnet", "conv", "greedy", 1 * G), ("overfeat", "all", None, 2 * G), ("overfeat", "conv", "greedy", 2 * G),
+         ("googlenet", "dyn", None, 3 * G), ("googlenet", "all", None, 3 * G), ("alexnet", "fit", None, 900 << 20),
+         ("googlenet", "fit", None, 2 * G), ("vgg116_b32", "fit", None, 4 * G)]
+
+
+@pytest.mark.parametrize("name,policy,algo,budget", OTHER)
+def test_other_workloads_full_size(B, name, policy, algo, budget):
+    """AlexNet / OverFeat / GoogLeNet shaped workloads at batch 128 under their budgets: statistics equal to the
+    memory-schedule oracle, and bit-identical to a no-offload run without a budget that runs the same kernels (those of the
+    performance-optimal mode by itself; those the plan reports, named layer by layer, after a greedy downgrade)."""
     import torch
     net = nets.vgg(batch=32, extra_per_group=20) if name == "vgg116_b32" else nets.CONFIGS[name]()
     x, labels, weights = gen.make(net)
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
-    base_loss, base_dw, _, _ = _run(B, net, xd, ld, weights, "none", 0)
-    assert np.isfinite(base_loss) and 1.0 < base_loss < 60.0
-    loss, dw, st, _ = _run(B, net, xd, ld, weights, policy, budget)
+    loss, dw, st, _ = _run(B, net, xd, ld, weights, policy, budget, algo=algo)
+    assert np.isfinite(loss) and 1.0 < loss < 60.0
+    if algo == "greedy":
+        assert st["conv_algo"] == "greedy" and st["n_downgraded_convs"] > 0
+    base_loss, base_dw, base_st, _ = _run(B, net, xd, ld, weights, "none", 0, kernels=None if st["conv_algo"] == "p" else st["kernels"])
+    assert base_st["kernels"] == st["kernels"]
     if policy == "fit":
         # the schedule itself is checked in _run (tests/sched_util.py); here: it offloads, within the budget
-        assert ms.simulate(net, "none", budget, ws=st["ws"])["status"] == "oom" and st["offloaded_bytes"] == st["prefetched_bytes"] > 0
+        assert ms.simulate(net, "none", budget, st["conv_algo"], ws=st["ws"])["status"] == "oom" and st["offloaded_bytes"] == st["prefetched_bytes"] > 0
         assert st["peak_bytes"] <= st["pool_extent_bytes"] <= budget and st["window_fill_pm"] > 0
     else:
         ref = ms.simulate(net, st["effective_policy"], budget, st["conv_algo"], ws=st["ws"])
         assert ref["status"] == "ok"
         assert st["peak_bytes"] == ref["peak_bytes"] <= budget and st["pool_extent_bytes"] <= budget
         assert st["offloaded_bytes"] == ref["offloaded_bytes"] and st["n_ondemand_fetch"] == ref["n_ondemand_fetch"]
-    if st["conv_algo"] != "p":
-        # a greedy plan (vDNN_dyn, phase 3) runs other kernels where a workspace does not fit: equal to rounding
-        assert abs(loss - base_loss) < 1e-5 * abs(base_loss) and st["n_downgraded_convs"] > 0
-        return
+        assert st["n_downgraded_convs"] == ref["n_downgraded_convs"]
     assert loss == base_loss
     for i in weights:
         assert np.isfinite(dw[i]).all()
@@ -245,15 +256,20 @@ def test_very_deep_vgg_batch_32(B, extra, check_identity):
             assert np.array_equal(dw[i], base_dw[i]), i
 
 
-GOLDEN = [("vgg16", "dyn", 12 * G, 2), ("alexnet", "conv", 1 * G, 4), ("overfeat", "all", 2 * G, 4), ("googlenet", "dyn", 3 * G, 4)]
+GOLDEN = [("vgg16", "dyn", 12 * G, 3), ("alexnet", "conv:greedy", 1 * G, 6), ("overfeat", "all", 2 * G, 6), ("googlenet", "dyn", 3 * G, 6)]
 
 
 def full_size_oracle_report(B, name, policy, budget, k_images, winograd=True):
     """One step of a benchmark configuration at its stated size, policy and budget, every layer's output and every
-    gradient map captured, against (a) tests/golden/<name>_b<batch>_step.json, which tests/golden/make_step_golden.py wrote
-    from the fp64 CPU oracle alone, and (b) the oracle run here on the first k_images images of the same batch, its backward
-    pass deciding ReLU signs and pooling arg-max from the GPU's forward values.  Returns the measurements; the test below
-    asserts on them.  Error measure as everywhere: largest deviation relative to the largest element of the oracle's tensor."""
+    gradient map captured, against
+      (a) tests/golden/<name>_b<batch>_step.json, which tests/golden/make_step_golden.py wrote from the fp64 CPU oracle alone:
+          loss, sampled forward values, sampled gradient-map entries, sampled weight-gradient entries;
+      (b) the oracle run here on k_images images of the same batch -- the first image whose golden samples all agree, and the
+          images whose golden samples disagree most -- twice: deciding ReLU signs and pooling arg-max from the GPU's forward
+          values ("shared"), and deciding for itself ("pure"); every element of every output and gradient map is compared;
+      (c) the defining sum of sampled weight-gradient entries, evaluated in fp64 from the GPU's own X and dY of the whole batch.
+    Returns the measurements; the test below asserts on them.  Error measure as everywhere: largest deviation relative to
+    the largest element of the oracle's tensor."""
     import json
     import os
     import torch
@@ -267,6 +283,9 @@ def full_size_oracle_report(B, name, policy, budget, k_images, winograd=True):
     x, labels, weights = gen.make(net)
     n = B.Net(net, budget)
     n.set_winograd(winograd)
+    if ":" in policy:
+        policy, algo = policy.split(":")
+        n.set_conv_algo(algo)
     n.set_policy(policy)
     n.attach_torch()
     for i, w in weights.items():
@@ -282,51 +301,78 @@ def full_size_oracle_report(B, name, policy, budget, k_images, winograd=True):
     dw = {i: n.get_weight_grad(i, w.shape) for i, w in weights.items()}
     st = n.stats()
     n.close()
-    rep = dict(name=name, stats=st, loss_err=abs(loss - gold["loss"]) / abs(gold["loss"]), fwd={}, dy={}, dw={}, shared={})
-    # (a) the golden step: sampled forward values, sampled gradient-map entries, sampled weight-gradient entries
+    rep = dict(name=name, stats=st, loss_err=abs(loss - gold["loss"]) / abs(gold["loss"]), fwd={}, dy={}, dw={}, images={})
+    per = {i: outs[i].size // batch for i in outs}
+    # (a) the golden step
+    outliers = np.zeros(batch, np.int64)   # per image: sampled gradient-map entries beyond 1e-4
     for key, mine in (("fwd", outs), ("dy", grads)):
         for i, g in gold[key].items():
-            d = np.abs(mine[int(i)][np.array(g["index"])].astype(np.float64) - np.array(g["value"])) / g["max_abs"]
+            idx = np.array(g["index"])
+            d = np.abs(mine[int(i)][idx].astype(np.float64) - np.array(g["value"])) / g["max_abs"]
             rep[key][int(i)] = dict(max=float(d.max()), beyond=float((d > TOL).mean()), samples=len(d))
+            if key == "dy":
+                np.add.at(outliers, idx[d > TOL] // per[int(i)], 1)
+    rep["flagged_images"] = int((outliers > 0).sum())
     for i, g in gold["layers"].items():
         flat = dw[int(i)].reshape(-1).astype(np.float64)
         assert list(dw[int(i)].shape) == g["shape"]
         d = np.abs(flat[np.array(g["index"])] - np.array(g["value"])) / g["max_abs"]
         rep["dw"][int(i)] = dict(max=float(d.max()), rms=float(np.sqrt((d * d).mean())), l2_err=abs(float(np.sqrt((flat * flat).sum())) - g["l2"]) / g["l2"])
-    # (b) the first k images, decisions shared: every element of every output and every gradient map
-    part = make(k_images)
-    per = {i: outs[i].size // batch for i in outs}
-    ov = {i: outs[i][:k_images * per[i]] for i in outs}
-    dys = {}
-    ref = onet.step(part, x[:k_images], labels[:k_images], weights, outs_override=ov,
-                    dy_hook=lambda i, g: dys.__setitem__(i, g * (k_images / batch)))
-    rep["shared"]["fwd_max"] = max(rel_err(ov[i], ref["outs"][i]) for i in ov)
-    rep["shared"]["dy"] = {i: rel_err(grads[i][:k_images * per[i]], dys[i]) for i in dys if i in grads}
-    rep["shared"]["flips"] = count_decision_flips(part, ov, ref["outs"])
-    # what the differing decisions alone do to the weight gradients: the oracle deciding for itself against the oracle
-    # deciding from the GPU's values, same k images.  A weight gradient is a mean over images and the images' decision
-    # terms are independent, so over the whole batch the effect shrinks by sqrt(k / batch).
-    pure = onet.step(part, x[:k_images], labels[:k_images], weights)
+    # (b) k images under the oracle, decisions shared and not
+    clean = [int(j) for j in np.nonzero(outliers == 0)[0][:1]]
+    worst = [int(j) for j in np.argsort(-outliers, kind="stable") if outliers[j] > 0][:k_images - len(clean)]
+    chosen = clean + worst
+    part = make(len(chosen))
+    xs, ls = x[chosen], labels[chosen]
+    scale = len(chosen) / batch
+    ov = {i: np.ascontiguousarray(outs[i].reshape(batch, -1)[chosen]) for i in outs}
+    gv = {i: grads[i].reshape(batch, -1)[chosen] for i in grads}
+    shared_dy, pure_dy = {}, {}
+    ref = onet.step(part, xs, ls, weights, outs_override=ov, dy_hook=lambda i, g: shared_dy.__setitem__(i, g.reshape(len(chosen), -1) * scale))
+    pure = onet.step(part, xs, ls, weights, dy_hook=lambda i, g: pure_dy.__setitem__(i, g.reshape(len(chosen), -1) * scale))
+    rep["shared_fwd_max"] = max(rel_err(ov[i], ref["outs"][i]) for i in ov)
+    for j, img in enumerate(chosen):
+        one = make(1)
+        flips = count_decision_flips(one, {i: ov[i][j:j + 1] for i in ov}, [o[j:j + 1] if o.ndim else o for o in ref["outs"]])
+        rep["images"][img] = dict(golden_outliers=int(outliers[img]), flips=flips,
+                                  shared_dy=max(rel_err(gv[i][j], shared_dy[i][j]) * np.abs(shared_dy[i][j]).max() / np.abs(shared_dy[i]).max() for i in shared_dy if i in gv),
+                                  pure_dy=max(rel_err(gv[i][j], pure_dy[i][j]) * np.abs(pure_dy[i][j]).max() / np.abs(pure_dy[i]).max() for i in pure_dy if i in gv))
+    rep["shared_dy"] = {i: rel_err(gv[i], shared_dy[i]) for i in shared_dy if i in gv}
     for i in weights:
         e = (pure["dw"][i] - ref["dw"][i]).reshape(-1)
-        scale = gold["layers"][str(i)]["max_abs"]
-        rep["dw"][i]["decisions_rms"] = float(np.sqrt((e * e).mean())) * np.sqrt(k_images / batch) / scale
-        rep["dw"][i]["decisions_max"] = float(np.abs(e).max()) * np.sqrt(k_images / batch) / scale
-    rep["margins"] = gold.get("margins", {})
-    rep["thresholds"] = gold.get("thresholds", [])
+        rep["dw"][i]["decisions_on_chosen"] = float(np.abs(e).max()) * scale / gold["layers"][str(i)]["max_abs"]
+    # (c) the weight gradients from the GPU's own X and dY, whole batch
+    rng = np.random.default_rng(11)
+    shapes, _ = nets.shapes(net)
+    for i, w in weights.items():
+        layer = net["layers"][i]
+        src = layer["inputs"][0]
+        xin = x if src < 0 else outs[src].reshape(shapes[src])
+        dy = grads[i].reshape(shapes[i])
+        if layer["type"] == "conv":
+            rep["dw"][i]["from_own_x_dy"] = sampled_conv_bwd_filter_check(xin, dy, dw[i], layer["stride"], layer["pad"], rng, pairs=4)
+        else:
+            x2, dy2 = xin.reshape(batch, -1).astype(np.float64), dy.reshape(batch, -1).astype(np.float64)
+            rows = rng.integers(0, dw[i].shape[0], 8)
+            want = dy2[:, rows].T @ x2
+            rep["dw"][i]["from_own_x_dy"] = float(np.abs(dw[i][rows].astype(np.float64) - want).max() / np.abs(dw[i]).max())
     return rep
 
 
 def print_report(rep):
-    print("%s: loss error %.2e; forward (first images, all elements) %.2e; %d decisions differ on those images" %
-          (rep["name"], rep["loss_err"], rep["shared"]["fwd_max"], rep["shared"]["flips"]))
+    print("%s: loss error %.2e; forward on the chosen images, all elements: %.2e; %d of the batch's images have gradient-map samples beyond 1e-4 of the golden file" %
+          (rep["name"], rep["loss_err"], rep["shared_fwd_max"], rep["flagged_images"]))
+    for img, r in rep["images"].items():
+        print("  image %3d: %3d golden samples beyond 1e-4, %3d decisions differ; gradient maps vs the oracle with shared decisions %.1e, vs the oracle alone %.1e" %
+              (img, r["golden_outliers"], r["flips"], r["shared_dy"], r["pure_dy"]))
     for i in sorted(rep["fwd"]):
         f, d = rep["fwd"][i], rep["dy"][i]
         line = "  layer %3d  Y max %.1e | dY vs golden: max %.1e, %.1f %% of %d samples beyond 1e-4 | dY with shared decisions %.1e" % (
-            i, f["max"], d["max"], 100 * d["beyond"], d["samples"], rep["shared"]["dy"].get(i, float("nan")))
+            i, f["max"], d["max"], 100 * d["beyond"], d["samples"], rep["shared_dy"].get(i, float("nan")))
         if i in rep["dw"]:
             w = rep["dw"][i]
-            line += " | dW vs golden: max %.1e rms %.1e; decisions alone predict rms %.1e max %.1e" % (w["max"], w["rms"], w["decisions_rms"], w["decisions_max"])
+            line += " | dW vs golden: max %.1e rms %.1e; from own X, dY %.1e; decisions on the chosen images move it by %.1e" % (
+                w["max"], w["rms"], w["from_own_x_dy"], w["decisions_on_chosen"])
         print(line)
 
 
@@ -334,31 +380,33 @@ def print_report(rep):
 def test_step_against_the_oracle_at_full_size(B, name, policy, budget, k_images):
     """End-to-end parity of the four full-size configurations, each under its own policy and budget, against the fp64 oracle.
 
-    What holds to 1e-4 without qualification: the loss, every sampled forward value of every layer, the gradients of the
-    classifier.  Below the classifier backward propagation takes discrete decisions from forward values (Eq. chain_rule through
-    ReLU and max-pooling: which activations are positive, which element of a window is the largest), and an fp32 forward pass
-    that is right to 1e-6 still puts a few of millions of near-ties on the other side; each moves whole gradient terms.  The test
-    shows that this, and nothing else, separates the two sides:
-      - with the decisions shared (the oracle's backward pass run from the GPU's forward values, on the first images of the
-        batch, every element compared) every gradient map of every layer meets 1e-4;
-      - against the oracle deciding for itself (the golden file) the gradient maps deviate in a minority of sampled positions;
-      - the deviation of the weight gradients from the golden file is of the size that the differing decisions alone produce
-        in the oracle (measured here on those images, scaled to the batch)."""
+    What holds to 1e-4 without qualification: the loss and every sampled forward value of every layer.  Backward propagation
+    takes discrete decisions from forward values (Eq. chain_rule through ReLU and max-pooling: which activations are positive,
+    which element of a window is the largest), and an fp32 forward pass that is right to 1e-6 still puts a few of the millions of
+    near-ties of an image on the other side than the fp64 pass; each such decision moves whole gradient terms of that image, in
+    the layer where it happens and in every layer below.  The test shows from values that this, and nothing else, separates the
+    GPU's gradients from the oracle's:
+      - images whose golden gradient-map samples all agree to 1e-4 have no differing decision (checked on the first of them),
+        and there the GPU's gradient maps equal the oracle's own, every element, to 1e-4;
+      - images whose golden samples disagree do have differing decisions (checked on the worst of them), and with the oracle
+        deciding from the GPU's forward values their gradient maps agree as well, every element, to 1e-4;
+      - the weight gradients are the defining sums over the GPU's own X and dY (sampled entries, fp64, whole batch) to 1e-4.
+    The distance of the weight gradients to the golden file is printed beside what the differing decisions of the chosen images
+    alone do to them; it is bounded here only as a sanity check (1e-2), since its size is a property of the near-ties of the
+    data, not of the kernels."""
     rep = full_size_oracle_report(B, name, policy, budget, k_images)
     print_report(rep)
-    net = nets.CONFIGS[name]()
     assert rep["stats"]["peak_bytes"] <= budget
     assert rep["loss_err"] < TOL
     assert max(f["max"] for f in rep["fwd"].values()) < TOL
-    assert rep["shared"]["fwd_max"] < TOL
-    assert max(rep["shared"]["dy"].values()) < TOL, rep["shared"]["dy"]
-    first_fc = min(i for i, l in enumerate(net["layers"]) if l["type"] == "fc")
+    assert rep["shared_fwd_max"] < TOL
+    assert max(rep["shared_dy"].values()) < TOL, rep["shared_dy"]
+    for img, r in rep["images"].items():
+        assert r["shared_dy"] < TOL, (img, r)
+        if r["golden_outliers"]:
+            assert r["flips"] > 0, (img, r)          # a disagreement with the golden file has its cause in a decision
+        if r["flips"] == 0:
+            assert r["pure_dy"] < TOL, (img, r)      # no decision differs: the oracle needs no help
     for i, w in rep["dw"].items():
-        assert w["l2_err"] < 1e-3, i
-        if i >= first_fc and rep["dy"][i]["beyond"] == 0:
-            assert w["max"] < TOL, (i, w)
-        else:
-            assert w["rms"] < TOL + 4 * w["decisions_rms"], (i, w)
-            assert w["max"] < TOL + 6 * max(w["decisions_max"], 3 * w["decisions_rms"]), (i, w)
-    for i, d in rep["dy"].items():
-        assert d["beyond"] < 0.5, (i, d)
+        assert w["from_own_x_dy"] < TOL, (i, w)
+        assert w["l2_err"] < 1e-3 and w["max"] < 1e-2, (i, w)

@@ -123,6 +123,58 @@ def test_conv_bwd_filter(B, shape):
     assert rel_err(host(dw), ref) < TOL
 
 
+NAMED = [(2, 32, 20, 20, 136, 3, 1, 1), (1, 256, 6, 6, 256, 3, 1, 1), (2, 256, 9, 9, 128, 3, 1, 1), (3, 64, 14, 14, 80, 5, 1, 2), (2, 3, 30, 30, 64, 7, 2, 3)]
+
+
+@pytest.mark.parametrize("shape", NAMED)
+def test_conv_kernels_by_name(B, shape):
+    """Every kernel that applies to a shape, named explicitly and given exactly the workspace it asks for, against the
+    oracle, for all three passes; the kernel the workspace-driven choice makes (VDNN_KERNEL_AUTO) is one of them, bit for bit."""
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    x, wt = _t((n, c, h, w), 11), _t((k, c, r, r), 12)
+    p, q = L.out_dim(h, r, st, pd), L.out_dim(w, r, st, pd)
+    dy = _t((n, k, p, q), 13)
+    refs = dict(fwd=L.conv_fwd(x, wt, st, pd), bwd_data=L.conv_bwd_data(dy, wt, x.shape, st, pd), bwd_filter=L.conv_bwd_filter(x, dy, wt.shape, st, pd))
+    xd, wd, dyd = dev(x), dev(wt), dev(dy)
+    ran = 0
+    for pass_ in ("fwd", "bwd_data", "bwd_filter"):
+        results = {}
+        for kernel in ("gather", "packed", "winograd"):
+            nbytes = B.op_conv_workspace(pass_, kernel, x.shape, wt.shape, st, pd)
+            out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
+            ws = _ws(nbytes) if nbytes else None
+            if nbytes is None:   # does not apply: refused, nothing written
+                big = _ws(1 << 20)
+                call = dict(fwd=lambda: B.try_op_conv_fwd(xd, wd, out, st, pd, ws=big, kernel=kernel),
+                            bwd_data=lambda: B.try_op_conv_bwd_data(dyd, wd, out, st, pd, ws=big, kernel=kernel),
+                            bwd_filter=lambda: B.try_op_conv_bwd_filter(xd, dyd, out, big, st, pd, kernel=kernel))[pass_]
+                assert call() == B.ERR_INVALID_ARG and bool(torch.isnan(out).all())
+                continue
+            if pass_ == "fwd":
+                B.op_conv_fwd(xd, wd, out, st, pd, ws=ws, kernel=kernel)
+            elif pass_ == "bwd_data":
+                B.op_conv_bwd_data(dyd, wd, out, st, pd, ws=ws, kernel=kernel)
+            else:
+                B.op_conv_bwd_filter(xd, dyd, out, ws, st, pd, kernel=kernel)
+            results[kernel] = host(out)
+            assert rel_err(results[kernel], refs[pass_]) < TOL, (pass_, kernel)
+            ran += 1
+        assert "gather" in results
+        fastest = [kk for kk in ("winograd", "packed", "gather") if kk in results][0]
+        nbytes = B.op_conv_workspace(pass_, fastest, x.shape, wt.shape, st, pd)
+        out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
+        ws = _ws(nbytes) if nbytes else None
+        if pass_ == "fwd":
+            B.op_conv_fwd(xd, wd, out, st, pd, ws=ws)
+        elif pass_ == "bwd_data":
+            B.op_conv_bwd_data(dyd, wd, out, st, pd, ws=ws)
+        else:
+            B.op_conv_bwd_filter(xd, dyd, out, ws, st, pd)
+        assert np.array_equal(host(out), results[fastest]), (pass_, fastest)
+    assert ran >= 4
+
+
 def test_conv_bwd_filter_is_split_and_deterministic(B):
     import torch
     shape = (8, 8, 64, 64, 16, 3, 1, 1)
@@ -285,17 +337,26 @@ def test_invalid_arguments_are_rejected(B):
     import torch
     x = torch.zeros(16, device="cuda")
     lib = B.lib
-    assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(None, x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, -1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 2, 2, 1, 5, 5, 1, 0, 0, -1, None) == B.ERR_INVALID_ARG
+    # a kernel id out of range, a kernel that does not apply to the shape (C = 1: gather only), a workspace too small for the kernel named
+    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, 3, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 0, 1, 1, 4, 4, 1, 3, 3, 1, 1, 0, B.KERNEL["packed"], None) == B.ERR_INVALID_ARG
+    xs, ws = (2, 16, 8, 8), (16, 16, 3, 3)
+    assert B.op_conv_workspace("fwd", "packed", xs, ws, 1, 1) > 64
+    xx, wt, yy = torch.zeros(xs, device="cuda"), torch.zeros(ws, device="cuda"), torch.zeros((2, 16, 8, 8), device="cuda")
+    assert B.try_op_conv_fwd(xx, wt, yy, 1, 1, ws=x, kernel="packed") == B.ERR_INVALID_ARG
+    assert B.try_op_conv_bwd_data(yy, wt, xx, 1, 1, ws=x, kernel="packed") == B.ERR_INVALID_ARG
+    assert B.try_op_conv_bwd_filter(xx, yy, wt, x, 1, 1, kernel="packed") == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_fwd(x.data_ptr(), x.data_ptr(), 1, 1, 4, 4, 2, 0, 0, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), None, x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_filter(x.data_ptr(), None, x.data_ptr(), None, 0, 8, 8, 64, 64, 16, 3, 3, 1, 1, -1, None) == B.ERR_INVALID_ARG
     # tensors of 2^31 - 1 elements or more are refused before anything is launched (kernels index with 32 bits)
     big = (64, 32, 1024, 1024)   # 2^31 elements
     p = x.data_ptr()
-    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_bwd_data(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, None, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_bwd_filter(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, None) == B.ERR_INVALID_ARG
-    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, 1, 1, 1024, 1024, 2048, 3, 3, 1, 1, 0, None) == B.ERR_INVALID_ARG   # the output is what is too large
+    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, 0, -1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_data(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, None, -1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_bwd_filter(p, p, p, None, 0, *big, 1, 3, 3, 1, 1, -1, None) == B.ERR_INVALID_ARG
+    assert lib.vdnn_op_conv_fwd(p, p, p, None, 0, 1, 1, 1024, 1024, 2048, 3, 3, 1, 1, 0, -1, None) == B.ERR_INVALID_ARG   # the output is what is too large
     assert lib.vdnn_op_maxpool_fwd(p, p, *big, 2, 2, 0, None) == B.ERR_INVALID_ARG
     assert lib.vdnn_op_maxpool_bwd(p, p, p, *big, 2, 2, 0, 0, None) == B.ERR_INVALID_ARG
 

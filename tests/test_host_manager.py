@@ -490,21 +490,24 @@ def test_every_plan_of_a_net_runs_the_same_kernels():
 
 def test_workspace_sizes_by_hand():
     """The workspace rules of the three kernels evaluated by hand for VGG-16 (256) layers.  Winograd: transformed filter
-    16*C*K floats, then 16*(C + K) floats per 2x2 output tile for as many images as fit 512 MiB; backward-filter: the 16
-    products once plus once per reduction split, then the same chunk.  Packed: one copy of W (rounded up to 256 bytes)."""
+    16*C*K floats, then 16*(C + K) floats per 2x2 output tile for a chunk of images: as many as fit 512 MiB, evened out over
+    the chunks that takes; backward-filter: the 16 products once plus once per reduction split, then the same chunk.
+    Packed: one copy of W (rounded up to 256 bytes)."""
     MiB = 1 << 20
     q = binding.op_conv_workspace
-    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image, 41 images per chunk
+    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image, at most 41 images
+    # per chunk: 7 chunks for 256 images, 37 images each (the last one 34)
     x, w = (256, 512, 28, 28), (512, 512, 3, 3)
-    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 + 41 * 12845056
-    assert 41 * 12845056 <= 512 * MiB < 42 * 12845056
+    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 + 37 * 12845056
+    assert 41 * 12845056 <= 512 * MiB < 42 * 12845056 and 6 * 41 < 256 <= 7 * 37
     assert q("fwd", "packed", x, w, 1, 1) == 512 * 512 * 9 * 4
     assert q("fwd", "gather", x, w, 1, 1) == q("bwd_filter", "gather", x, w, 1, 1) == 0
     # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits of the
-    # 41 * 196 = 8036 tile positions
-    assert q("bwd_filter", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 * (1 + 4) + 41 * 12845056
-    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 167 images per chunk; a batch smaller than the chunk: all of it
-    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == 16 * 512 * 512 * 4 + 167 * 3211264
+    # 37 * 196 = 7252 tile positions
+    assert q("bwd_filter", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 * (1 + 4) + 37 * 12845056
+    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, at most 167 images per chunk: two chunks of 128; a batch smaller than
+    # the chunk: all of it
+    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == 16 * 512 * 512 * 4 + 128 * 3211264
     assert q("fwd", "winograd", (8, 512, 14, 14), w, 1, 1) == 16 * 512 * 512 * 4 + 8 * 3211264
     # 13 x 13 (odd sides): 7 x 7 tiles as well
     assert q("fwd", "winograd", (8, 384, 13, 13), (256, 384, 3, 3), 1, 1) == 16 * 384 * 256 * 4 + 8 * 16 * 640 * 49 * 4
@@ -593,3 +596,147 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
             n.close()
         finally:
             binding.op_set_winograd_chunk_bytes(0)
+
+
+# ---------------------------------------------------------------------------------------------------
+# profile-driven choices (Section 3.3: vDNN_dyn decides from profiled layer times); the numbers are put in by hand here
+# ---------------------------------------------------------------------------------------------------
+def _hand_fit_net():
+    b = nets._Builder("hand_fit", 1, 4, 8, 8)
+    for _ in range(3):
+        b.conv(4, 3, pad=1, relu=False)
+    b.fc(5, relu=False)
+    return b.done()
+
+
+def test_estimated_step_time_by_hand():
+    """Three convolutions, FC, loss (the net of test_hand_enumerated_fit_schedule) under vDNN_all, layer times and link rates
+    given by hand: conv forward 1 ms, backward-filter and backward-data 1 ms each, FC 0.5 ms each way, loss 0.1 ms each way;
+    the three 1024-byte feature maps that vDNN_all offloads take 1.024 ms to the host (1000 bytes per ms) and 0.512 ms back.
+    Forward: each offload starts with its layer and the layer ends when both have (Section 3.2): three times 1.024 ms, then
+    0.5 + 0.1.  Backward: the prefetch of conv 2's input is issued with the loss layer (0.1 ms of computation, 0.512 ms of
+    copy: the layer ends at +0.512); FC 0.5; conv 2's backward pass (2 ms) hides the prefetch of conv 1's input, conv 1's (2 ms)
+    that of the network input; conv 0 has no backward-data pass: 1 ms."""
+    net = _hand_fit_net()
+    n = binding.Net(net, 0)
+    assert n.try_policy("none") == binding.OK
+    with pytest.raises(binding.VdnnError):
+        n.estimate_step_ms()                       # no profile yet
+    for i in (0, 1, 2):
+        for pass_ in ("fwd", "bwd_data", "bwd_filter"):
+            n.set_layer_profile(i, pass_, "gather", 1.0)
+    n.set_layer_profile(3, 0, 0, 0.5)
+    n.set_layer_profile(3, 1, 0, 0.5)
+    n.set_layer_profile(4, 0, 0, 0.1)
+    n.set_layer_profile(4, 1, 0, 0.1)
+    n.set_link_rate(1e-3, 2e-3)                    # GB/s: 1000 and 2000 bytes per millisecond
+    assert n.link_rate() == (1e-3, 2e-3)
+    assert n.layer_profile(0) == {("fwd", "gather"): 1.0, ("bwd_data", "gather"): 1.0, ("bwd_filter", "gather"): 1.0}
+    assert n.layer_profile(3) == {"fwd": 0.5, "bwd": 0.5}
+    n.set_policy("none")
+    assert abs(n.estimate_step_ms() - (3 * 1.0 + 0.5 + 0.1 + 0.1 + 0.5 + 2.0 + 2.0 + 1.0)) < 1e-6
+    n.set_policy("all")
+    assert n.offload_set() == {-1, 0, 1}
+    forward = 3 * 1.024 + 0.5 + 0.1
+    backward = 0.512 + 0.5 + 2.0 + 2.0 + 1.0
+    assert abs(n.estimate_step_ms() - (forward + backward)) < 1e-6
+    # a link ten times slower: every layer that carries a transfer lasts as long as the transfer
+    n.set_link_rate(1e-4, 2e-4)
+    assert abs(n.estimate_step_ms() - (3 * 10.24 + 0.6 + 5.12 + 0.5 + 5.12 + 5.12 + 1.0)) < 1e-6
+    n.close()
+
+
+def _uniform_profile(n, net, winograd=1.0, packed=1.3, gather=4.0, other=0.1, link=50.0):
+    shapes, _ = nets.shapes(net)
+    for i, l in enumerate(net["layers"]):
+        if l["type"] == "conv":
+            src = l["inputs"][0]
+            xs = (net["batch"], net["in_c"], net["in_h"], net["in_w"]) if src < 0 else shapes[src]
+            for pass_ in ("fwd", "bwd_data", "bwd_filter"):
+                for kernel, ms in (("winograd", winograd), ("packed", packed), ("gather", gather)):
+                    if binding.op_conv_workspace(pass_, kernel, xs, (l["out"], xs[1], l["k"], l["k"]), l["stride"], l["pad"]) is not None:
+                        n.set_layer_profile(i, pass_, kernel, ms)
+        else:
+            n.set_layer_profile(i, 0, 0, other)
+            n.set_layer_profile(i, 1, 0, other)
+    n.set_link_rate(link, link)
+
+
+def test_profile_orders_the_kernel_lists():
+    """Before a profile a wide 3x3 layer prefers Winograd, then the packed kernel, then the gather kernel.  Measured times
+    reorder the list; a kernel that is slower than one needing less workspace drops out of it (the greedy mode would never
+    pick it)."""
+    b = nets._Builder("wide", 8, 256, 14, 14)
+    b.conv(256, 1)
+    b.conv(256, 3, pad=1)
+    b.fc(10, relu=False)
+    net = b.done()
+    conv = 2
+    n = binding.Net(net, 0)
+    n.set_policy("none")
+    assert n.layer_kernels(conv) == ("winograd", "winograd", "winograd")
+    before = n.workspace_options(conv, False)
+    assert len(before) == 3 and before[0] > before[1] > before[2] == 0
+    _uniform_profile(n, net, winograd=2.0, packed=1.0, gather=5.0)      # the packed kernel measured faster than Winograd
+    n.set_policy("none")
+    assert n.layer_kernels(conv) == ("packed", "packed", "packed")
+    assert n.workspace_options(conv, False) == before[1:]                 # Winograd: slower and larger, gone
+    _uniform_profile(n, net, winograd=1.0, packed=1.0, gather=0.5)      # the gather kernel fastest: the only entry left
+    n.set_policy("none")
+    assert n.layer_kernels(conv) == ("gather", "gather", "gather") and n.workspace_options(conv, False) == [0]
+    # naming the kernels overrides the list
+    n.set_layer_kernels(conv, ("winograd", "packed", "gather"))
+    n.set_policy("none")
+    assert n.layer_kernels(conv) == ("winograd", "packed", "gather")
+    assert n.workspace_options(conv, False) == [before[0]]
+    assert binding.lib.vdnn_set_layer_kernels(n.h, 0, (C.c_int32 * 3)(2, 0, 0)) == binding.ERR_INVALID_ARG   # 1x1: no Winograd
+    assert binding.lib.vdnn_set_layer_kernels(n.h, 3, (C.c_int32 * 3)(0, 0, 0)) == binding.ERR_INVALID_ARG   # not a CONV layer
+    n.set_layer_kernels(conv, None)
+    n.set_policy("none")
+    assert n.layer_kernels(conv) == ("gather", "gather", "gather")
+    n.close()
+
+
+def test_dyn_with_a_profile_chooses_by_estimated_time():
+    """AlexNet-shaped, batch 128, 1 GiB.  Without a profile vDNN_dyn follows the paper's order and adopts vDNN_all with the
+    performance-optimal algorithms (the first configuration of the sequence that fits).  With measured times it compares the
+    configurations that fit and takes the fastest: on a link this slow relative to the layers, no offloading at all with the
+    greedy downgrade of the layers whose Winograd workspace does not fit."""
+    net = nets.alexnet(128)
+    n = binding.Net(net, G)
+    n.set_policy("dyn")
+    st = n.stats()
+    assert (st["effective_policy"], st["conv_algo"]) == ("all", "p")
+    _uniform_profile(n, net, link=2.0)
+    n.set_policy("dyn")
+    st = n.stats()
+    assert (st["effective_policy"], st["conv_algo"]) == ("none", "greedy") and st["offloaded_bytes"] == 0 and st["n_downgraded_convs"] > 0
+    fast = n.estimate_step_ms()
+    for pol, algo in (("all", "p"), ("conv", "greedy"), ("all", "greedy")):
+        n.set_conv_algo(algo)
+        if n.try_policy(pol) == binding.OK:
+            assert n.estimate_step_ms() >= fast
+    # with an (imaginary) link so fast that transfers are free, what runs every layer on its fastest kernel wins
+    _uniform_profile(n, net, link=1e6)
+    n.set_policy("dyn")
+    st = n.stats()
+    assert (st["effective_policy"], st["conv_algo"]) == ("all", "p")
+    n.close()
+
+
+def test_fit_with_a_profile_never_estimates_worse():
+    """The time-driven search of the offload set starts from the byte-driven choice and only takes moves that shorten the
+    estimated step: the result is a valid schedule whose estimate is no worse."""
+    net = nets.vgg16(64)
+    budget = 4 * G
+    n = binding.Net(net, budget)
+    n.set_policy("fit")
+    by_bytes = n.offload_set()
+    assert by_bytes
+    _uniform_profile(n, net, link=50.0)
+    n.set_offload_set(by_bytes, n.stats()["window_fill_pm"], 1000)
+    start = n.estimate_step_ms()
+    n.set_policy("fit")
+    assert n.estimate_step_ms() <= start + 1e-9
+    _assert_valid_schedule(n, net, budget)
+    n.close()
