@@ -326,6 +326,72 @@ def test_training_iterations_follow_the_oracle(B, policy):
     n.close()
 
 
+def test_fifty_training_iterations(B):
+    """The paper's measurement runs take 50 iterations of training (Section 5.4).  Fifty SGD iterations of the Tiny
+    configuration under vDNN_all and its 4 MiB budget: the loss falls, and its whole trajectory and the final weights
+    follow the fp64 oracle's (5e-4: fifty updates let rounding differences and the odd differing decision accumulate)."""
+    net = nets.tiny(8)
+    x, labels, weights = gen.make(net)
+    lr, iters = 0.02, 50
+    ow = {i: w.astype(np.float64) for i, w in weights.items()}
+    ref_losses = []
+    for _ in range(iters):
+        r = onet.step(net, x, labels, ow)
+        ref_losses.append(r["loss"])
+        ow = onet.sgd_update(ow, r["dw"], lr)
+    n = B.Net(net, 4 << 20)
+    n.set_policy("all")
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    xd, ld = dev(x), dev(labels)
+    losses = []
+    for _ in range(iters):
+        losses.append(n.forward(xd, ld))
+        n.backward()
+        n.sgd_step(lr)
+    assert n.stats()["offloaded_bytes"] > 0
+    assert ref_losses[-1] < 0.2 * ref_losses[0]
+    worst = max(abs(a - b) / abs(b) for a, b in zip(losses, ref_losses))
+    print("50 iterations: loss %.4f -> %.4f (oracle %.4f -> %.4f), largest relative deviation of the trajectory %.2e" %
+          (losses[0], losses[-1], ref_losses[0], ref_losses[-1], worst))
+    assert worst < 5e-4
+    for i, w in weights.items():
+        assert rel_err(n.get_weights(i, w.shape), ow[i]) < 5e-4
+    n.close()
+
+
+def test_get_output_reads_the_pool_or_the_host_arena(B):
+    """vdnn_get_output between forward and backward: the same values as the capture hooks see, whether the feature map is
+    still in the pool (no offloading) or in the pinned arena (vDNN_all); the logits are layer -1."""
+    net = small_vgg()
+    x, labels, weights = gen.make(net, seed=gen.BASE_SEED + 31)
+    base = run_gpu(B, net, x, labels, weights, "none")
+    last_relu = {}
+    for i, l in enumerate(net["layers"]):          # an in-place ReLU shares its producer's feature map: the value after it
+        if l["type"] == "relu":
+            last_relu[l["inputs"][0]] = i
+    for pol in ("none", "all"):
+        n = B.Net(net, 0)
+        n.set_policy(pol)
+        n.attach_torch()
+        for i, w in weights.items():
+            n.set_weights(i, w)
+        assert B.lib.vdnn_get_output(n.h, 0, np.empty(1, np.float32).ctypes.data, 1) == B.ERR_INVALID_ARG   # wrong count
+        k = n.output_count(0)
+        buf = np.empty(k, np.float32)
+        assert B.lib.vdnn_get_output(n.h, 0, buf.ctypes.data, k) == B.ERR_STATE                              # no forward yet
+        n.forward(dev(x), dev(labels))
+        logits_layer = net["layers"][-1]["inputs"][0]
+        assert np.array_equal(n.get_output(-1), base["outs"][logits_layer])
+        for i, l in enumerate(net["layers"][:-1]):
+            want = base["outs"][last_relu.get(i, i)]
+            assert np.array_equal(n.get_output(i), want), (pol, i)
+        n.backward()
+        assert B.lib.vdnn_get_output(n.h, 0, buf.ctypes.data, k) == B.ERR_STATE                              # the step is over
+        n.close()
+
+
 @pytest.mark.parametrize("name,mk", [("tiny", lambda: nets.tiny(8)), ("small_vgg", small_vgg), ("small_googlenet", small_googlenet)])
 def test_memory_optimal_algorithm_matches_oracle(B, name, mk):
     """Section 2.2: the memory-optimal convolution algorithm (X, Y, W only, no workspace) computes the same
@@ -359,6 +425,40 @@ def test_dyn_greedy_downgrade_runs(B):
     assert abs(got["loss"] - ref["loss"]) < TOL * abs(ref["loss"])
     for i in weights:
         assert rel_err(got["dw"][i], ref["dw"][i]) < TOL, i
+
+
+def test_labels_out_of_range_are_an_error_not_a_fault(B):
+    """A label outside [0, classes) is never used as an index: vdnn_forward reports it, the op-level entry point returns a
+    NaN loss, and the net keeps working with good labels afterwards."""
+    import torch
+    net = nets.tiny(8)
+    x, labels, weights = gen.make(net)
+    n = B.Net(net, 0)
+    n.attach_torch()
+    for i, w in weights.items():
+        n.set_weights(i, w)
+    good = n.forward(dev(x), dev(labels))
+    n.backward()
+    for bad_value in (-1, 10, 2 ** 30, -2 ** 31):
+        bad = labels.copy()
+        bad[3] = bad_value
+        loss = np.float32(0)
+        import ctypes as C
+        out = C.c_float(-7.0)
+        s = B.lib.vdnn_forward(n.h, dev(x).data_ptr(), dev(bad).data_ptr(), C.byref(out))
+        assert s == B.ERR_INVALID_ARG and out.value == -7.0 and "labels" in n.last_error()
+        assert B.lib.vdnn_backward(n.h) == B.ERR_STATE
+    assert n.forward(dev(x), dev(labels)) == good
+    n.backward()
+    n.close()
+    z = torch.zeros((4, 10), device="cuda")
+    lab = torch.tensor([0, 3, 10, 9], dtype=torch.int32, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    B.op_softmax_ce_fwd(z, lab, loss)
+    assert bool(torch.isnan(loss).all())
+    dz = torch.empty_like(z)
+    B.op_softmax_ce_bwd(z, lab, dz)
+    assert bool(torch.isfinite(dz).all()) and abs(float(dz[2].sum()) - 0.25) < 1e-6   # no onehot term for the bad row
 
 
 def test_error_paths_on_the_device(B):
