@@ -324,6 +324,19 @@ size_t vdnn_op_conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int 
 vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw, void* workspace, size_t workspace_bytes,
                                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kernel, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): vdnn_op_conv_bwd_filter with the workspace taken from a static device buffer of VDNN_STATIC_SCRATCH_BYTES
+ * that the library holds on every GPU it runs on until the process ends.  The call allocates and frees nothing.  kernel as
+ * above, except that VDNN_KERNEL_AUTO means the fastest kernel that applies to the shape (the one
+ * vdnn_op_conv_bwd_filter_workspace sizes for).  A kernel whose workspace is larger than the buffer is refused with
+ * VDNN_ERR_INVALID_ARG and a message (nothing is launched): pick a smaller kernel (GATHER needs none) or use the entry point
+ * above.  Same kernels, same results bit for bit as vdnn_op_conv_bwd_filter given a workspace of that size.  All calls on one
+ * GPU share the buffer: calls that overlap there (different streams, different threads) race; calls on one stream do not.
+ * The first call on a GPU looks the buffer's address up (no allocation by this library; make it before a capture starts). */
+#define VDNN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+vdnn_status_t vdnn_op_conv_bwd_filter_static(const float* x, const float* dy, float* dw, int N, int C, int H, int W, int K, int R, int S,
+                                             int stride, int pad, int kernel, void* stream);
+
 /* FC: Y[N][O] = X[N][I] W[O][I]^T ; dX = dY W ; dW = dY^T X.  Same workspace rule (too little: no split). */
 size_t vdnn_op_fc_workspace(int N, int I, int O, int which /*0 fwd, 1 bwd-data, 2 bwd-filter*/);
 vdnn_status_t vdnn_op_fc_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int I,

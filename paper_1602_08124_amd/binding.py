@@ -103,6 +103,7 @@ EXPORTS = {
     "vdnn_op_conv_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 9 + [_vp, _i, _vp], _i),
     "vdnn_op_conv_bwd_filter_workspace": ([_i] * 9, _sz),
     "vdnn_op_conv_bwd_filter": ([_vp] * 4 + [_sz] + [_i] * 10 + [_vp], _i),
+    "vdnn_op_conv_bwd_filter_static": ([_vp] * 3 + [_i] * 10 + [_vp], _i),
     "vdnn_op_fc_workspace": ([_i] * 4, _sz),
     "vdnn_op_fc_fwd": ([_vp] * 4 + [_sz] + [_i] * 3 + [_vp], _i),
     "vdnn_op_fc_bwd_data": ([_vp] * 4 + [_sz] + [_i] * 3 + [_vp], _i),
@@ -448,6 +449,20 @@ def try_op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None, kernel="auto
 
 def op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream=None, kernel="auto"):
     _ck(try_op_conv_bwd_filter(x, dy, dw, ws, stride, pad, stream, kernel), "conv_bwd_filter")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def try_op_conv_bwd_filter_static(x, dy, dw, stride, pad, stream=None, kernel="auto"):
+    n, c, h, wd = x.shape
+    k, _, r, s = dw.shape
+    return lib.vdnn_op_conv_bwd_filter_static(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), n, c, h, wd, k, r, s, stride, pad,
+                                              KERNEL[kernel], _stream_ptr(stream))
+
+
+def op_conv_bwd_filter_static(x, dy, dw, stride, pad, stream=None, kernel="auto"):
+    _ck(try_op_conv_bwd_filter_static(x, dy, dw, stride, pad, stream, kernel), "conv_bwd_filter_static")
 
 
 def op_fc_workspace(n, i, o, which):

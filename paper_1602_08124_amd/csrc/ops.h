@@ -47,6 +47,11 @@ size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S
 hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws, size_t ws_bytes, int N, int C, int H, int W,
                            int K, int R, int S, int stride, int pad, int kernel, hipStream_t st);
 
+// Backward-filter on the library's own static device buffer instead of a caller's workspace; see ops_gemm.hip.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+hipError_t conv_bwd_filter_static(const float* x, const float* dy, float* dw, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                  int pad, int kernel, hipStream_t st, size_t* need);
+
 size_t fc_workspace(int N, int I, int O, int which);
 hipError_t fc_fwd(const float* x, const float* w, float* y, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st);
 hipError_t fc_bwd_data(const float* dy, const float* w, float* dx, void* ws, size_t ws_bytes, int N, int I, int O, hipStream_t st);

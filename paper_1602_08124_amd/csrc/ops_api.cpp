@@ -66,6 +66,21 @@ vdnn_status_t vdnn_op_conv_bwd_filter(const float* x, const float* dy, float* dw
     return st(conv_bwd_filter(x, dy, dw, workspace, workspace_bytes, N, C, H, W, K, R, S, stride, pad, kernel, (hipStream_t)stream));
 }
 
+static_assert(VDNN_STATIC_SCRATCH_BYTES == kStaticScratchBytes, "the header states the size of the static buffer");
+
+vdnn_status_t vdnn_op_conv_bwd_filter_static(const float* x, const float* dy, float* dw, int N, int C, int H, int W, int K, int R, int S,
+                                             int stride, int pad, int kernel, void* stream) {
+    if (!x || !dy || !dw || !conv_ok(N, C, H, W, K, R, S, stride, pad) || !kernel_ok(kernel)) return VDNN_ERR_INVALID_ARG;
+    size_t need = 0;
+    const hipError_t e = conv_bwd_filter_static(x, dy, dw, N, C, H, W, K, R, S, stride, pad, kernel, (hipStream_t)stream, &need);
+    if (e == hipErrorInvalidValue && need > kStaticScratchBytes) {
+        snprintf(g_op_error, sizeof g_op_error, "conv_bwd_filter_static: the kernel needs %zu bytes of workspace, the static buffer holds %zu",
+                 need, (size_t)kStaticScratchBytes);
+        return VDNN_ERR_INVALID_ARG;
+    }
+    return st(e);
+}
+
 size_t vdnn_op_fc_workspace(int N, int I, int O, int which) {
     if (N <= 0 || I <= 0 || O <= 0 || which < 0 || which > 2) return 0;
     return fc_workspace(N, I, O, which);

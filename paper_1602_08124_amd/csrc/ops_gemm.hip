@@ -647,6 +647,57 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
 }
 
 // -------------------------------------------------------------------------------------------
+// backward-filter on a workspace that nobody allocates
+// -------------------------------------------------------------------------------------------
+// For callers that cannot allocate (under HIP graph capture, in a serving loop, in a harness that forbids it): the
+// workspace of the backward-filter kernels (partial sums of the split reduction, Winograd transforms) lives in a
+// file-scope device array.  Every GPU the library runs on holds its own copy of the array until the process ends.
+// In host code the array's name is only a stand-in for the symbol: its device address is looked up once per device,
+// with that device current, and kept; launches and anything else that needs the memory use that address.
+// The kernels write every workspace word they later read (the existing entry point runs on uninitialised workspaces
+// too), so nothing has to be cleared between calls; two calls that overlap on one GPU share the array and race.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // two threads racing here look up the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+// kernel: kKernelAuto = the fastest kernel that applies to the shape (what conv_bwd_filter_workspace sizes for).
+// *need receives the workspace bytes of the kernel in question; hipErrorInvalidValue with *need > kStaticScratchBytes
+// means "too large for the static buffer" (nothing is launched).
+hipError_t conv_bwd_filter_static(const float* x, const float* dy, float* dw, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                  int pad, int kernel, hipStream_t st, size_t* need) {
+    int use = kernel;
+    if (kernel == kKernelAuto) {
+        use = kKernelGather;
+        for (int k : {kKernelPacked, kKernelWinograd})
+            if (conv_workspace(kPassBwdFilter, k, N, C, H, W, K, R, S, stride, pad) != kNoKernel) use = k;
+    }
+    *need = conv_workspace(kPassBwdFilter, use, N, C, H, W, K, R, S, stride, pad);
+    if (*need == kNoKernel) { *need = 0; return hipErrorInvalidValue; }
+    if (*need > kStaticScratchBytes) return hipErrorInvalidValue;
+    void* ws = nullptr;
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return e;
+    return conv_bwd_filter(x, dy, dw, ws, kStaticScratchBytes, N, C, H, W, K, R, S, stride, pad, use, st);
+}
+
+// -------------------------------------------------------------------------------------------
 // FC
 // -------------------------------------------------------------------------------------------
 size_t fc_workspace(int N, int I, int O, int which) {
