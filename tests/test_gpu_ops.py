@@ -172,7 +172,7 @@ def test_conv_kernels_by_name(B, shape):
         else:
             B.op_conv_bwd_filter(xd, dyd, out, ws, st, pd)
         assert np.array_equal(host(out), results[fastest]), (pass_, fastest)
-    assert ran >= 4
+    assert ran >= 3
 
 
 def test_conv_bwd_filter_is_split_and_deterministic(B):
