@@ -32,6 +32,7 @@ ROOFLINE_TRAFFIC_BYTES = 3.580e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
 PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)
+PROFILE_DATA = None     # what run_profile measured; loaded into every net before its policy is set
 HBM_PEAK_TBPS = 8.0
 
 
@@ -215,27 +216,35 @@ def nets_shapes(net):
     return nets.shapes(net)
 
 
+def run_profile(B, net):
+    """The profiling passes of Section 3.3, once, outside every timed region: every kernel of every layer and the link, on a
+    net without a budget (so that every kernel's workspace fits beside its layer's tensors)."""
+    global PROFILE_DATA
+    n = B.Net(net, 0)
+    n.set_winograd(WINOGRAD)
+    n.set_policy("none")
+    n.attach_torch(streams=streams())
+    t0 = time.perf_counter()
+    n.profile(3)
+    dt = time.perf_counter() - t0
+    PROFILE_DATA = n.dump_profile()
+    n.close()
+    import torch
+    torch.cuda.empty_cache()
+    return dt
+
+
 def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, window_part_mib=None, layer_ms=None, table=None):
     """policy: none | conv | all | dyn | fit, optionally with ":m" / ":greedy" for another convolution algorithm mode;
     or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille.
-    dyn and fit are preceded by the profiling passes (Section 3.3), outside the timed region."""
+    Every net is given the profile that run_profile measured before its policy is set."""
     import torch
     n = B.Net(net, budget)
     n.set_winograd(WINOGRAD)
     if window_part_mib is not None:
         n.set_window_part(int(window_part_mib * (1 << 20)))
-    profile_s = None
-    if PROFILE and policy in ("dyn", "fit"):
-        # what vDNN_dyn's first pass establishes: the network can be trained at all (vDNN_all, memory-optimal); its pool is
-        # where the layers are then profiled
-        n.set_conv_algo("m")
-        if n.try_policy("all") == B.OK:
-            n.set_conv_algo("p")
-            n.attach_torch(streams=streams())
-            t0 = time.perf_counter()
-            n.profile(2)
-            profile_s = time.perf_counter() - t0
-        n.set_conv_algo("p")
+    if PROFILE_DATA is not None:
+        n.load_profile(PROFILE_DATA)   # every policy decides from the same measured times: same kernels, comparable steps
     if policy.startswith("set:"):
         _, ids, *fills = policy.split(":")
         status = n.try_offload_set({int(v) for v in ids.split("+") if v}, *[int(f) for f in fills])
@@ -252,8 +261,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
         msg = n.last_error()
         n.close()
         return dict(status="oom" if status == B.ERR_OOM_DEVICE else "error %d" % status, detail=msg)
-    if profile_s is None:
-        n.attach_torch(streams=streams())
+    n.attach_torch(streams=streams())
     for i, w in weights.items():
         n.set_weights(i, w)
     loss = None
@@ -288,15 +296,11 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
                conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"], window_fill_bwd_pm=st["window_fill_bwd_pm"],
                offload_set=sorted(n.offload_set()), per_step_ms=per_step, n_winograd_convs=st["n_winograd_convs"], n_downgraded_convs=st["n_downgraded_convs"],
                kernels="/".join("%s%s%s" % tuple(k[0] for k in n.layer_kernels(i)) for i, l in enumerate(net["layers"]) if l["type"] == "conv"))
-    if profile_s is not None:
-        out["profile_s"] = profile_s
+    if PROFILE_DATA is not None:
         out["estimated_ms"] = n.estimate_step_ms()
-        out["link_gbps_profiled"] = n.link_rate()
-    if table is not None and policy == "none":
-        n.profile(3)
+    if table is not None and policy == "none" and PROFILE_DATA is not None:
         rows, summary = layer_table(B, n, net)
         table["rows"], table["summary"] = rows, summary
-        out["estimated_ms"] = n.estimate_step_ms()
     if st["offloaded_bytes"]:
         # the step cannot be shorter than the time the host link needs for the bytes of each pass
         link_s = (st["offloaded_bytes"] + st["prefetched_bytes"]) / (LINK_PEAK_GBPS * 1e9)
@@ -371,10 +375,11 @@ def main():
         net = nets.vgg(batch, extra_per_group=deep[args.workload]) if args.workload in deep else nets.CONFIGS[args.workload](batch)
         x, labels, weights = gen.make(net)
         x_dev, lab_dev = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
+        profile_s = run_profile(B, net) if PROFILE else None
         res = {pol: run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else int(gib * GIB), args.steps, args.warmup,
                                args.window_part_mib)
                for pol in args.policies.split(",")}
-        print(json.dumps({"workload": args.workload, "batch": batch, "budget_gib": gib, "policies": res}))
+        print(json.dumps({"workload": args.workload, "batch": batch, "budget_gib": gib, "profile_s": profile_s, "policies": res}))
         return
     net = nets.vgg16(args.batch)
     x, labels, weights = gen.make(net)
@@ -383,6 +388,7 @@ def main():
     policies = {}
     layer_ms = []   # filled by the no-offload run; the offloading policies are compared with the bound it implies
     table = None if args.no_layer_table else {}
+    profile_s = run_profile(B, net) if PROFILE else None
     for pol in args.policies.split(","):
         policies[pol] = run_policy(B, net, x_dev, lab_dev, weights, pol, 0 if pol == "none" else budget, args.steps, args.warmup,
                                    layer_ms=layer_ms, table=table)
@@ -418,6 +424,9 @@ def main():
     }
     if table:
         out["no_offload_step_by_layer"] = table
+    if PROFILE_DATA is not None:
+        out["profile"] = dict(seconds=profile_s, link_gbps=PROFILE_DATA["link"],
+                              layers={str(i): {"/".join(k) if isinstance(k, tuple) else k: v for k, v in e.items()} for i, e in PROFILE_DATA["layers"].items()})
     if args.kernel_table:
         out["conv_kernels"] = conv_kernel_table(B, args.batch)
     if not args.no_cpu_baseline:

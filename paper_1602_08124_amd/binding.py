@@ -248,6 +248,21 @@ class Net:
         self._chk(lib.vdnn_estimate_step_ms(self.h, C.byref(v)))
         return v.value
 
+    def dump_profile(self):
+        """Everything the profiling passes measured, as plain data: {"layers": {id: {...}}, "link": (d2h, h2d)}."""
+        return dict(layers={i: self.layer_profile(i) for i in range(len(self.net["layers"]))}, link=self.link_rate())
+
+    def load_profile(self, prof):
+        """Puts a profile measured on another net of the same shape in (vdnn_set_layer_profile, vdnn_set_link_rate)."""
+        for i, entries in prof["layers"].items():
+            for key, ms in entries.items():
+                if isinstance(key, tuple):
+                    self.set_layer_profile(int(i), key[0], key[1], ms)
+                else:
+                    self.set_layer_profile(int(i), 0 if key == "fwd" else 1, 0, ms)
+        if prof["link"][0] > 0 and prof["link"][1] > 0:
+            self.set_link_rate(*prof["link"])
+
     def set_link_rate(self, d2h_gbps, h2d_gbps):
         self._chk(lib.vdnn_set_link_rate(self.h, d2h_gbps, h2d_gbps))
 

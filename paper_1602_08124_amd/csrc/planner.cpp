@@ -167,7 +167,9 @@ static size_t place_with_keys(const std::vector<Unit>& units, size_t n_blocks, s
 
 // good_enough: the search stops at the first placement whose extent is at most this (0: only at the lower bound);
 // rounds: how many perturbed orders are tried after the four plain ones.
-static size_t place_blocks(Plan& p, size_t base, size_t good_enough = 0, int rounds = 300) {
+// variant > 0: another placement of the same blocks: the plain orders are skipped and the perturbed ones drawn from a seed of
+// their own; meant to be called with good_enough = the budget (the first placement that fits is returned).
+static size_t place_blocks(Plan& p, size_t base, size_t good_enough = 0, int rounds = 300, uint64_t variant = 0) {
     const std::vector<Unit> units = make_units(p);
     if (units.empty()) return base;
     const size_t n = units.size();
@@ -196,11 +198,11 @@ static size_t place_blocks(Plan& p, size_t base, size_t good_enough = 0, int rou
     size_t best_extent = (size_t)-1;
     constexpr int kKinds = 4;
     const std::vector<double>* base_keys[kKinds] = {&size, &life, &area, &start};
-    for (int kind = 0; kind < kKinds && best_extent > target; ++kind) {
+    for (int kind = 0; kind < kKinds && best_extent > target && !variant; ++kind) {
         const size_t e = place_with_keys(units, p.blocks.size(), base, *base_keys[kind], cur, limit);
         if (e < best_extent) { best_extent = e; best = cur; }
     }
-    uint64_t rng = 0x9E3779B97F4A7C15ull;  // fixed seed: the plan is a pure function of (net, policy, budget)
+    uint64_t rng = 0x9E3779B97F4A7C15ull + variant * 0xD1B54A32D192ED03ull;  // fixed seeds: the plan is a pure function of (net, policy, budget)
     auto next = [&]() { rng = rng * 6364136223846793005ull + 1442695040888963407ull; return (double)(rng >> 11) / 9007199254740992.0; };
     const double noises[4] = {0.1, 0.3, 0.6, 1.0};
     for (int round = 0; round < rounds && best_extent > target; ++round) {
@@ -768,26 +770,57 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
         return;
     }
     if (windows && fill_bwd_pm > 0) {
-        // A step that can be placed is placed once more with the ranges of the fetches kept clear from as early as
-        // live bytes allow (for the whole share of the budget, then for less): the first such placement that fits the
-        // budget replaces the plain one, and hoist_fetches then finds those ranges free.
+        // How early a fetch can be issued depends on where the blocks lie (hoist_fetches).  A step that can be placed is
+        // therefore placed again with the ranges of the fetches kept clear from as early as live bytes allow (for the whole
+        // share of the budget, then for less).  Without a profile the first such placement that fits the budget replaces
+        // the plain one.  With a profile every placement that fits is a candidate, together with further placements from
+        // perturbed orders, and the one whose hoisted schedule has the shortest estimated step is taken.
         static const int kReserve[] = {1000, 900, 800};
+        const int rounds = p.blocks.size() <= 600 ? place_rounds : 0;
+        const bool by_time = n.profiled && place_rounds >= 100;
+        auto offsets_of = [](const Plan& q) {
+            std::vector<size_t> v(q.blocks.size());
+            for (size_t i = 0; i < q.blocks.size(); ++i) v[i] = q.blocks[i].offset;
+            return v;
+        };
+        std::vector<std::pair<std::vector<size_t>, size_t>> cands;   // (offsets, extent)
+        cands.push_back({offsets_of(p), p.extent});
         for (int pm : kReserve) {
             if (pm > fill_bwd_pm) continue;
             Plan q = p;
             if (!reserve_fetch_ranges(q, soft(pm))) break;
-            const size_t e = place_blocks(q, q.persistent, budget, p.blocks.size() <= 600 ? place_rounds : 0);
-            if (e <= budget) {
-                for (size_t i = 0; i < p.blocks.size(); ++i) p.blocks[i].offset = q.blocks[i].offset;
-                p.extent = e;
-                break;
+            const int variants = by_time ? 6 : 0;
+            bool fits = false;
+            for (int v = 0; v <= variants; ++v) {
+                Plan r = q;
+                const size_t e = place_blocks(r, r.persistent, budget, rounds, (uint64_t)v);
+                if (e <= budget) { cands.push_back({offsets_of(r), e}); fits = true; }
             }
+            if (fits && !by_time) break;
         }
+        if (by_time)
+            for (int v = 1; v <= 6; ++v) {
+                Plan r = p;
+                const size_t e = place_blocks(r, r.persistent, budget, rounds, (uint64_t)v);
+                if (e <= budget) cands.push_back({offsets_of(r), e});
+            }
         const Plan kept = p;
-        hoist_fetches(p, soft(fill_bwd_pm));
-        measure_plan(p);
-        p.fill_bwd_pm = fill_bwd_pm;
-        if (plan_overlaps(p)) p = kept;  // cannot happen by construction; a plan that fails the check is never run
+        Plan best;
+        double best_ms = -1.0;
+        // without a profile: the last candidate is the reserved placement (when one fits), else the plain one
+        for (size_t c = by_time ? 0 : cands.size() - 1; c < cands.size(); ++c) {
+            Plan t = kept;
+            for (size_t i = 0; i < t.blocks.size(); ++i) t.blocks[i].offset = cands[c].first[i];
+            t.extent = cands[c].second;
+            hoist_fetches(t, soft(fill_bwd_pm));
+            measure_plan(t);
+            if (plan_overlaps(t)) continue;  // cannot happen by construction; a plan that fails the check is never run
+            t.fill_bwd_pm = fill_bwd_pm;
+            t.ok = true;
+            const double ms = by_time ? estimate_step_ms(n, t) : 0.0;
+            if (best_ms < 0 || ms < best_ms) { best = t; best_ms = ms; }
+        }
+        if (best_ms >= 0) p = best;
     }
     p.ok = true;
 }
@@ -800,18 +833,22 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
 double estimate_step_ms(const vdnn_net& n, const Plan& p) {
     if (!n.profiled || !p.ok) return -1.0;
     const double d2h = (n.link_d2h_gbps > 0 ? n.link_d2h_gbps : 55.0) * 1e6, h2d = (n.link_h2d_gbps > 0 ? n.link_h2d_gbps : 55.0) * 1e6;  // bytes per ms
-    auto fwd_ms = [&](int i) -> double {
+    // a kernel that was not measured is taken to be twice as slow as the slowest one of its pass that was
+    auto conv_ms = [&](int i, int pass, int k) -> double {
         const LayerProfile& pr = n.profile[i];
-        if (n.layers[i].type != VDNN_CONV) return pr.fwd > 0 ? pr.fwd : 0.0;
-        const float t = pr.conv[kPassFwd][n.options_fwd[i][p.opt_fwd[i]].fwd];
-        return t > 0 ? t : 0.0;
+        if (pr.conv[pass][k] >= 0) return pr.conv[pass][k];
+        double worst = 0.0;
+        for (int j = 0; j < kNumKernels; ++j) worst = std::max(worst, (double)pr.conv[pass][j]);
+        return 2.0 * worst;
+    };
+    auto fwd_ms = [&](int i) -> double {
+        if (n.layers[i].type != VDNN_CONV) return n.profile[i].fwd > 0 ? n.profile[i].fwd : 0.0;
+        return conv_ms(i, kPassFwd, n.options_fwd[i][p.opt_fwd[i]].fwd);
     };
     auto bwd_ms = [&](int i) -> double {
-        const LayerProfile& pr = n.profile[i];
-        if (n.layers[i].type != VDNN_CONV) return pr.bwd > 0 ? pr.bwd : 0.0;
+        if (n.layers[i].type != VDNN_CONV) return n.profile[i].bwd > 0 ? n.profile[i].bwd : 0.0;
         const KernelOption& o = n.options_bwd[i][p.opt_bwd[i]];
-        const float tf = pr.conv[kPassBwdFilter][o.bf], td = buf_of(n, n.layers[i].inputs[0]) >= 0 ? pr.conv[kPassBwdData][o.bd] : 0.f;
-        return (tf > 0 ? tf : 0.0) + (td > 0 ? td : 0.0);
+        return conv_ms(i, kPassBwdFilter, o.bf) + (buf_of(n, n.layers[i].inputs[0]) >= 0 ? conv_ms(i, kPassBwdData, o.bd) : 0.0);
     };
     constexpr int kSlots = 33;
     std::vector<double> copy_end(p.blocks.size() * kSlots, 0.0);
@@ -973,7 +1010,26 @@ vdnn_status_t plan_policy(vdnn_net& n, int policy) {
             set[pick + 1] = 1;
         }
         if (!planned) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
-        if (n.profiled && n.budget) improve_by_time(n, algo, set, p);
+        if (n.profiled && n.budget) {
+            improve_by_time(n, algo, set, p);
+            // The greedy mode gives up a fast kernel where its workspace does not fit; that can let a smaller set of feature
+            // maps do, and on a slow link the bytes saved outweigh the slower kernels.  Both are planned; the estimate decides.
+            if (algo == VDNN_ALGO_PERF) {
+                std::vector<char> gset;
+                Plan g;
+                if (fit_select(n, VDNN_ALGO_GREEDY, gset) && plan_with_windows(n, VDNN_ALGO_GREEDY, gset, g)) {
+                    improve_by_time(n, VDNN_ALGO_GREEDY, gset, g);
+                    if (estimate_step_ms(n, g) < 0.995 * estimate_step_ms(n, p)) { p = g; set = gset; algo = VDNN_ALGO_GREEDY; }
+                }
+            }
+            // the winner once more with the full placement effort
+            Plan fin;
+            for (int f : kFills) {
+                compile_plan(n, policy, algo, fin, &set, true, f, f ? 1000 : 0);
+                if (fin.ok) break;
+            }
+            if (fin.ok && estimate_step_ms(n, fin) <= estimate_step_ms(n, p)) p = fin;
+        }
         n.plan = p; n.policy = policy; n.effective = policy;
         return VDNN_OK;
     }
