@@ -34,6 +34,7 @@ WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution
 PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)
 PROFILE_DATA = None     # what run_profile measured; loaded into every net before its policy is set
 HBM_PEAK_TBPS = 8.0
+KERNEL_LETTER = {"gather": "g", "packed": "p", "winograd": "w", "winograd_small": "s"}
 
 
 def conv_layers_vgg16(batch):
@@ -183,7 +184,7 @@ def layer_table(B, n, net):
                 ms = prof.get((pass_, kname))
                 if ms is None or (pass_ == "bwd_data" and src < 0):
                     continue
-                executed = flop * (16.0 / 36.0 if kname == "winograd" else 1.0)
+                executed = flop * (16.0 / 36.0 if kname.startswith("winograd") else 1.0)
                 rows.append(dict(layer=i, type="conv", what=pass_, kernel=kname, ms=ms, gflop=flop / 1e9, tflops=flop / ms / 1e9,
                                  frac_of_mfma_peak=flop / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS, executed_frac_of_mfma_peak=executed / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS))
                 tot["flop"] += flop; tot["executed"] += executed; tot["mfma_ms"] += ms
@@ -295,7 +296,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
                d2h_gbps=d2h / steps, h2d_gbps=h2d / steps, link_peak_gbps=LINK_PEAK_GBPS,
                conv_algo=st["conv_algo"], n_memopt_convs=st["n_memopt_convs"], window_fill_pm=st["window_fill_pm"], window_fill_bwd_pm=st["window_fill_bwd_pm"],
                offload_set=sorted(n.offload_set()), per_step_ms=per_step, n_winograd_convs=st["n_winograd_convs"], n_downgraded_convs=st["n_downgraded_convs"],
-               kernels="/".join("%s%s%s" % tuple(k[0] for k in n.layer_kernels(i)) for i, l in enumerate(net["layers"]) if l["type"] == "conv"))
+               kernels="/".join("".join(KERNEL_LETTER[k] for k in n.layer_kernels(i)) for i, l in enumerate(net["layers"]) if l["type"] == "conv"))
     if PROFILE_DATA is not None:
         out["estimated_ms"] = n.estimate_step_ms()
     if table is not None and policy == "none" and PROFILE_DATA is not None:
@@ -335,6 +336,7 @@ def main():
     ap.add_argument("--no-winograd", action="store_true", help="keep every plan on the direct convolution kernels (side measurement)")
     ap.add_argument("--cpu-sample-batch", type=int, default=8)
     ap.add_argument("--no-profile", action="store_true", help="dyn and fit decide without the profiling passes")
+    ap.add_argument("--winograd-chunk-mib", type=int, default=0, help="side measurement: chunk size of the Winograd workspace (0 = the library's default)")
     ap.add_argument("--no-layer-table", action="store_true", help="skip the per-layer table of the no-offload step")
     args = ap.parse_args()
     global WINOGRAD, PROFILE
@@ -349,6 +351,8 @@ def main():
     from synth import gen, nets
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.winograd_chunk_mib:
+        B.op_set_winograd_chunk_bytes(args.winograd_chunk_mib << 20)
     if args.kernel_only:
         out = dict(roofline=roofline(B, args.batch))
         if args.calibrate_copy:

@@ -56,15 +56,19 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
  *             of about |W| (backward-filter: one |W| per split); needs reduction channels in multiples of 16 (32 for
  *             backward-filter), an unstrided backward-data pass and tensors below 4 GiB;
  *   WINOGRAD  F(2x2,3x3) minimal filtering on wide 3x3 / stride 1 / pad 1 layers: 2.25x fewer multiplications, a
- *             workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk of images).
- * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: by the order above until
+ *             workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk of images);
+ *   WINOGRAD_SMALL  the same on chunks of half the size: a few per cent slower, about half the workspace (exists
+ *             where the batch does not fit half a chunk anyway).
+ * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: WINOGRAD, WINOGRAD_SMALL, PACKED, GATHER until
  * vdnn_profile has measured them on the GPU, by measured time afterwards.  The first entry is the layer's
  * performance-optimal algorithm, the last the memory-optimal one.  EVERY plan of the net (whatever the policy and the
  * budget) takes the first entry under VDNN_ALGO_PERF and fails with VDNN_ERR_OOM_DEVICE where that workspace does not
  * fit, so that plans under different policies and budgets compute the same bits; only VDNN_ALGO_GREEDY moves a layer
  * down its list (first entry whose workspace fits at that point of the step), and results then differ in rounding.
  * vdnn_set_winograd(net, 0) takes the Winograd kernel off every list of the net. */
-typedef enum { VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2 } vdnn_conv_kernel_t;
+typedef enum {
+    VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2, VDNN_KERNEL_WINOGRAD_SMALL = 3
+} vdnn_conv_kernel_t;
 typedef enum { VDNN_PASS_FWD = 0, VDNN_PASS_BWD_DATA = 1, VDNN_PASS_BWD_FILTER = 2 } vdnn_conv_pass_t;
 #define VDNN_NO_KERNEL ((size_t)-1) /* vdnn_op_conv_workspace: the kernel does not apply to the shape */
 

@@ -178,13 +178,13 @@ void build_kernel_options(vdnn_net& n) {
         if (l.type != VDNN_CONV) continue;
         const LayerProfile& pr = n.profile[i];
         auto ws_of = [&](int pass, int k) { return conv_workspace(pass, k, n.batch, C, H, W, l.out, l.k, l.k, l.stride, l.pad); };
-        // no profile: Winograd before the packed-weight kernel before the gather kernel (measured on the paper's workloads);
+        // no profile: Winograd, then Winograd on smaller chunks, then the packed-weight kernel, then the gather kernel (measured on the paper's workloads);
         // with one, a kernel that was not measured (its tensors and workspace did not fit the pool together) comes after all that were
         auto cost_of = [&](int pass, int k) {
-            if (!n.profiled) return (double)(kNumKernels - k);
-            return pr.conv[pass][k] >= 0 ? (double)pr.conv[pass][k] : 1e9 + (double)(kNumKernels - k);
+            if (!n.profiled) return (double)kernel_rank(k);
+            return pr.conv[pass][k] >= 0 ? (double)pr.conv[pass][k] : 1e9 + (double)kernel_rank(k);
         };
-        auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (k != kKernelWinograd || n.winograd); };
+        auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (!is_winograd(k) || n.winograd); };
         const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
         if (n.pinned_kernels[i] >= 0) {  // the caller named the kernels: the layer's only way to run
             const int kf = n.pinned_kernels[i] & 15, kd = (n.pinned_kernels[i] >> 4) & 15, kb = (n.pinned_kernels[i] >> 8) & 15;

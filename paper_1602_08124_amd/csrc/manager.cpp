@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ops.h"
@@ -22,8 +23,20 @@ using namespace vdnn;
         }                                                                                        \
     } while (0)
 
+// One stream for host->device fetches, shared by every net of the process (a process that keeps creating streams ends up
+// with several of them on one hardware queue, where copies and kernels of different streams serialise).
+static hipStream_t fetch_stream() {
+    static hipStream_t st = nullptr;
+    static std::once_flag once;
+    std::call_once(once, []() {
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); st = nullptr; }
+    });
+    return st;
+}
+
 static vdnn_status_t ensure_device(vdnn_net& n) {
     if (!n.plan.ok) { n.err = "no valid plan (the current policy does not fit the budget)"; return VDNN_ERR_STATE; }
+    if (!n.sf) n.sf = fetch_stream();   // null: fetches share the memory stream
     if (!n.have_streams) {
         HIPCHK(hipStreamCreateWithFlags(&n.sc, hipStreamNonBlocking));
         HIPCHK(hipStreamCreateWithFlags(&n.sm, hipStreamNonBlocking));
@@ -198,15 +211,20 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
                 int prev = t - 1;
                 while (prev >= first && (p.ops[prev].kind == OP_ALLOC || p.ops[prev].kind == OP_FREE || p.ops[prev].kind == OP_SAMPLE)) --prev;  // these enqueue nothing
                 const bool follows = prev >= first && p.ops[prev].kind == o.kind && p.ops[prev].block == o.block && o.kind != OP_ONDEMAND;
+                // Offloads run on the memory stream, fetches on a stream of their own: the link carries both directions at
+                // once, and an offload that is still on its way when backward propagation starts does not hold up the first
+                // fetches.  (A fetch of X never overtakes the offload of X: its block is allocated after the release of the
+                // forward copy, which the compute stream waited for, and the edge below orders the fetch behind that.)
+                const hipStream_t cs = o.kind == OP_OFFLOAD || !n.sf ? n.sm : n.sf;
                 int e_ready = -1, e0 = -1;
                 if (!follows) {
                     NEWEV(er);
                     e_ready = er;
                     HIPCHK(hipEventRecord(n.events[e_ready], n.sc));
-                    HIPCHK(hipStreamWaitEvent(n.sm, n.events[e_ready], 0));
+                    HIPCHK(hipStreamWaitEvent(cs, n.events[e_ready], 0));
                     NEWEV(es);
                     e0 = es;
-                    HIPCHK(hipEventRecord(n.events[e0], n.sm));
+                    HIPCHK(hipEventRecord(n.events[e0], cs));
                 }
                 NEWEV(e1);
                 const Block& b = p.blocks[o.block];
@@ -215,10 +233,10 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
                 char* host = n.pinned + b.host_off + shift;
                 char* dev = (char*)blk(n, o.block) + shift;
                 if (bytes) {
-                    if (o.kind == OP_OFFLOAD) HIPCHK(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, n.sm));
-                    else HIPCHK(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, n.sm));
+                    if (o.kind == OP_OFFLOAD) HIPCHK(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, cs));
+                    else HIPCHK(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, cs));
                 }
-                HIPCHK(hipEventRecord(n.events[e1], n.sm));
+                HIPCHK(hipEventRecord(n.events[e1], cs));
                 if (follows) { n.copies.back().e1 = e1; n.copies.back().bytes += bytes; }
                 else n.copies.push_back({e0, e1, bytes, o.kind == OP_OFFLOAD ? 0 : 1});
                 n.copy_done_event[(size_t)o.block * kSlots + o.part + 1] = e1;
@@ -268,12 +286,13 @@ static vdnn_status_t run_ops(vdnn_net& n, int first, int last, const float* inpu
     return VDNN_OK;
 }
 
+// Pass time and per-layer times after each pass; transfer and stall times after backward propagation, when every copy of
+// the step (offloads may still be in flight when forward propagation ends) has completed.
 static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
     float ms = 0.f;
     if (!bwd) {
         HIPCHK(hipEventElapsedTime(&ms, n.events[n.ev_f0], n.events[n.ev_f1]));
         n.fwd_ms = ms;
-        n.stall_ms = n.d2h_ms = n.h2d_ms = 0;
     } else {
         HIPCHK(hipEventElapsedTime(&ms, n.events[n.ev_b0], n.events[n.ev_b1]));
         n.bwd_ms = ms;
@@ -288,6 +307,8 @@ static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
         }
     }
     n.layer_marks.clear();
+    if (!bwd) return VDNN_OK;
+    n.stall_ms = n.d2h_ms = n.h2d_ms = 0;
     for (auto& c : n.copies) {
         HIPCHK(hipEventElapsedTime(&ms, n.events[c.e0], n.events[c.e1]));
         (c.dir == 0 ? n.d2h_ms : n.h2d_ms) += ms;
@@ -630,7 +651,10 @@ vdnn_status_t vdnn_get_output(vdnn_net_t* np, int layer, float* dst, size_t coun
         if (p.ops[t].kind == OP_OFFLOAD && p.ops[t].buf == b) host_block = p.ops[t].block;
     for (int id = 0; id < (int)p.blocks.size() && host_block < 0; ++id)
         if (p.blocks[id].buf == b && !p.blocks[id].persistent && p.blocks[id].t0 < p.first_bwd_op && p.blocks[id].t1 > p.first_bwd_op) dev_block = id;
-    if (host_block >= 0) memcpy(dst, n.pinned + p.blocks[host_block].host_off, count * 4);
+    if (host_block >= 0) {
+        HIPCHK(hipStreamSynchronize(n.sm));   // the offload may still be on its way
+        memcpy(dst, n.pinned + p.blocks[host_block].host_off, count * 4);
+    }
     else if (dev_block >= 0) HIPCHK(hipMemcpy(dst, blk(n, dev_block), count * 4, hipMemcpyDeviceToHost));
     else { n.err = fmt("get_output: the output of layer %d was released during forward propagation (no backward computation reads it)", layer); return VDNN_ERR_STATE; }
     return VDNN_OK;
@@ -654,6 +678,9 @@ vdnn_status_t vdnn_forward(vdnn_net_t* np, const float* input, const int32_t* la
     vdnn_status_t s = ensure_device(n);
     if (s != VDNN_OK) return s;
     n.fwd_done = false;
+    // copies of a step that was abandoned after its forward pass may still be reading the pool this pass is about to overwrite
+    HIPCHK(hipStreamSynchronize(n.sm));
+    if (n.sf) HIPCHK(hipStreamSynchronize(n.sf));
     n.events_used = 0;
     n.copies.clear();
     n.stalls.clear();
@@ -664,8 +691,9 @@ vdnn_status_t vdnn_forward(vdnn_net_t* np, const float* input, const int32_t* la
     s = run_ops(n, n.plan.first_fwd_op, n.plan.first_bwd_op, input, labels);
     if (s != VDNN_OK) { (void)hipDeviceSynchronize(); return s; }
     HIPCHK(hipEventRecord(n.events[n.ev_f1], n.sc));
+    // the forward COMPUTATION has completed when this returns; offloads whose release the plan has postponed into backward
+    // propagation (transfer windows) may still be on their way to the host
     HIPCHK(hipStreamSynchronize(n.sc));
-    HIPCHK(hipStreamSynchronize(n.sm));
     struct { float loss; int32_t bad_labels; } res = {0.f, 0};
     HIPCHK(hipMemcpy(&res, blk(n, n.plan.loss_block), sizeof res, hipMemcpyDeviceToHost));
     const float loss = res.loss;
@@ -693,6 +721,7 @@ vdnn_status_t vdnn_backward(vdnn_net_t* np) {
     HIPCHK(hipEventRecord(n.events[n.ev_b1], n.sc));
     HIPCHK(hipStreamSynchronize(n.sc));
     HIPCHK(hipStreamSynchronize(n.sm));
+    if (n.sf) HIPCHK(hipStreamSynchronize(n.sf));
     return finish_timing(n, true);
 }
 
@@ -778,6 +807,8 @@ vdnn_status_t vdnn_profile(vdnn_net_t* np, int32_t repeats) {
     vdnn_status_t s = ensure_device(n);   // needs a plan that fits: its pool is where the layers run
     if (s != VDNN_OK) return s;
     n.fwd_done = false;
+    HIPCHK(hipStreamSynchronize(n.sm));
+    if (n.sf) HIPCHK(hipStreamSynchronize(n.sf));
     n.events_used = 0;
     n.copies.clear();
     n.stalls.clear();
@@ -897,6 +928,7 @@ const char* vdnn_last_error(const vdnn_net_t* n) { return n ? n->err.c_str() : "
 void vdnn_destroy(vdnn_net_t* n) {
     if (!n) return;
     if (n->have_streams) { (void)hipStreamSynchronize(n->sc); (void)hipStreamSynchronize(n->sm); }
+    if (n->sf) (void)hipStreamSynchronize(n->sf);
     for (hipEvent_t e : n->events) (void)hipEventDestroy(e);
     if (n->own_streams) { (void)hipStreamDestroy(n->sc); (void)hipStreamDestroy(n->sm); }
     if (n->own_pool && n->pool) (void)hipFree(n->pool);

@@ -86,7 +86,7 @@ struct KernelOption {
 
 // Section 3.3, "Dynamic vDNN": what the profiling passes measure.  Times in milliseconds, < 0 = not measured.
 struct LayerProfile {
-    float conv[3][3] = {{-1, -1, -1}, {-1, -1, -1}, {-1, -1, -1}};  // CONV: [pass][kernel]
+    float conv[3][4] = {{-1, -1, -1, -1}, {-1, -1, -1, -1}, {-1, -1, -1, -1}};  // CONV: [pass][kernel]
     float fwd = -1, bwd = -1;                                        // every layer: the kernels its plan entry runs
 };
 
@@ -167,6 +167,7 @@ struct vdnn_net {
     size_t pool_bytes = 0;
     bool own_pool = false, weights_set = false;
     hipStream_t sc = nullptr, sm = nullptr;
+    hipStream_t sf = nullptr;  // host->device fetches (the library's own; offloads use sm)
     bool have_streams = false, own_streams = false;
     char* pinned = nullptr;
     size_t pinned_bytes = 0;

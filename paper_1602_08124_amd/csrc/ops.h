@@ -21,7 +21,12 @@ int gemm_splits(long long m, long long n, long long kred);
 size_t gemm_workspace_bytes(long long m, long long n, long long kred);
 
 // The three convolution kernels (Section 2.2: algorithms that trade workspace for speed) and the three passes of a CONV layer.
-enum { kKernelAuto = -1, kKernelGather = 0, kKernelPacked = 1, kKernelWinograd = 2, kNumKernels = 3 };
+// kKernelWinogradSmall: the Winograd kernels on chunks of half the size (a quarter of the workspace's chunk part less per halving
+// would be the next step; one is what the workloads ask for): a few per cent slower, hundreds of MiB less workspace.
+enum { kKernelAuto = -1, kKernelGather = 0, kKernelPacked = 1, kKernelWinograd = 2, kKernelWinogradSmall = 3, kNumKernels = 4 };
+inline bool is_winograd(int kernel) { return kernel == kKernelWinograd || kernel == kKernelWinogradSmall; }
+// rank of a kernel before anything has been measured: lower = expected faster
+inline int kernel_rank(int kernel) { return kernel == kKernelWinograd ? 1 : kernel == kKernelWinogradSmall ? 2 : kernel == kKernelPacked ? 3 : 4; }
 enum { kPassFwd = 0, kPassBwdData = 1, kPassBwdFilter = 2 };
 constexpr size_t kNoKernel = (size_t)-1;
 // Workspace bytes of `kernel` for `pass` over the shape (0 for the gather kernel); kNoKernel where it does not apply.

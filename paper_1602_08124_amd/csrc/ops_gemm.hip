@@ -258,9 +258,11 @@ static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int s
 
 // Images per chunk: as many as the chunk size holds, then evened out over the chunks that this takes (256 images at 167 per
 // chunk run as 128 + 128, not 167 + 89: the same number of launches on a smaller workspace).
-static int wino_chunk(int N, int cred, int H, int W, int rows) {
+// small: the chunk size halved (kKernelWinogradSmall)
+static int wino_chunk(int N, int cred, int H, int W, int rows, bool small = false) {
     const size_t per_image = (size_t)16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
-    const int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
+    const size_t chunk_bytes = small ? g_wino_chunk_bytes / 2 : g_wino_chunk_bytes;
+    const int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), chunk_bytes / per_image));
     const int chunks = (N + most - 1) / most;
     return (N + chunks - 1) / chunks;
 }
@@ -279,16 +281,16 @@ static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cr
     return hipGetLastError();
 }
 
-static size_t wino_workspace(int N, int cred, int H, int W, int rows) {
+static size_t wino_workspace(int N, int cred, int H, int W, int rows, bool small = false) {
     const size_t u = ((size_t)16 * cred * rows + 63) / 64 * 64 * sizeof(float);
-    return u + (size_t)wino_chunk(N, cred, H, W, rows) * 16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
+    return u + (size_t)wino_chunk(N, cred, H, W, rows, small) * 16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
 }
 
 // src [N][cred][H][W] -> out [N][rows][H][W]; w is the layer's KCRS filter; bwd selects which way it is applied.
 static hipError_t conv_winograd(const float* src, const float* w, float* ws, float* out, const float* mask, int relu, int N, int cred, int H,
-                                int W, int rows, int K, int C, int bwd, hipStream_t st) {
+                                int W, int rows, int K, int C, int bwd, bool small, hipStream_t st) {
     const int T = ((H + 1) / 2) * ((W + 1) / 2);
-    const int nb = wino_chunk(N, cred, H, W, rows);
+    const int nb = wino_chunk(N, cred, H, W, rows, small);
     float* u = ws;
     float* v = ws + ((size_t)16 * cred * rows + 63) / 64 * 64;
     float* mt = v + (size_t)16 * nb * cred * T;
@@ -362,26 +364,33 @@ size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, 
 }
 
 static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
-static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K);
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, bool small = false);
 
 // Bytes of workspace a kernel needs for a pass over the shape; kNoKernel where that kernel does not apply.
 size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     if (kernel == kKernelGather) return 0;  // works on X, Y and W as stored, for every shape
-    if (kernel != kKernelPacked && kernel != kKernelWinograd) return kNoKernel;
+    if (kernel != kKernelPacked && !is_winograd(kernel)) return kNoKernel;
+    const bool small = kernel == kKernelWinogradSmall;
+    // the small-chunk variant exists where halving the chunk size does change the chunk (a batch that fits half a chunk runs in one piece either way)
     if (pass == kPassFwd) {
         const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         if (!packed) return kNoKernel;
         if (kernel == kKernelPacked) return packed;
-        return wino_ok(N, C, H, W, K, R, S, stride, pad) ? wino_workspace(N, C, H, W, K) : kNoKernel;
+        if (!wino_ok(N, C, H, W, K, R, S, stride, pad) || (small && wino_chunk(N, C, H, W, K, true) == wino_chunk(N, C, H, W, K))) return kNoKernel;
+        return wino_workspace(N, C, H, W, K, small);
     }
     if (pass == kPassBwdData) {
         const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         if (!packed) return kNoKernel;
         if (kernel == kKernelPacked) return packed;
-        return wino_ok(N, K, H, W, C, R, S, stride, pad) ? wino_workspace(N, K, H, W, C) : kNoKernel;
+        if (!wino_ok(N, K, H, W, C, R, S, stride, pad) || (small && wino_chunk(N, K, H, W, C, true) == wino_chunk(N, K, H, W, C))) return kNoKernel;
+        return wino_workspace(N, K, H, W, C, small);
     }
     if (pass == kPassBwdFilter) {
-        if (kernel == kKernelWinograd) return wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) ? wino_bwdf_workspace(N, C, H, W, K) : kNoKernel;
+        if (is_winograd(kernel)) {
+            if (!wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) || (small && wino_chunk(N, C, H, W, K, true) == wino_chunk(N, C, H, W, K))) return kNoKernel;
+            return wino_bwdf_workspace(N, C, H, W, K, small);
+        }
         const size_t split = conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         return split ? split : kNoKernel;  // no split and no tap-major staging: the same launch as the gather kernel
     }
@@ -393,7 +402,7 @@ size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, i
 static int resolve_kernel(int pass, int kernel, const void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
                           int pad) {
     if (kernel == kKernelAuto) {
-        for (int k : {kKernelWinograd, kKernelPacked}) {
+        for (int k : {kKernelWinograd, kKernelWinogradSmall, kKernelPacked}) {
             const size_t need = conv_workspace(pass, k, N, C, H, W, K, R, S, stride, pad);
             if (need != kNoKernel && ws && ws_bytes >= need) return k;
         }
@@ -417,7 +426,7 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
     eo.out = y; eo.mask = nullptr; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
     const int use = resolve_kernel(kPassFwd, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
     if (use == -2) return hipErrorInvalidValue;
-    if (use == kKernelWinograd) return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, st);
+    if (is_winograd(use)) return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, use == kKernelWinogradSmall, st);
     if (use == kKernelPacked) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
 }
@@ -473,7 +482,7 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
     eo.out = dx; eo.mask = relu_mask; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
-    if (use == kKernelWinograd) return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, st);
+    if (is_winograd(use)) return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, use == kKernelWinogradSmall, st);
     if (use == kKernelPacked) return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
     return conv_gemm(wa, g, eo, st);
 }
@@ -522,8 +531,8 @@ static int wino_bwdf_splits(int nb, int T, int K, int C) {
     return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv((long long)nb * T, 512)));
 }
 
-static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K) {
-    const int T = ((H + 1) / 2) * ((W + 1) / 2), nb = wino_chunk(N, C, H, W, K);
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, bool small) {
+    const int T = ((H + 1) / 2) * ((W + 1) / 2), nb = wino_chunk(N, C, H, W, K, small);
     return (size_t)16 * K * C * sizeof(float) * (1 + wino_bwdf_splits(nb, T, K, C)) + (size_t)nb * 16 * (C + K) * T * sizeof(float);
 }
 
@@ -556,9 +565,10 @@ static hipError_t bwdf_cfg(const PixKParams& pa, const ConvGeom& g, const RowMaj
 }
 
 // x [N][C][H][W], dy [N][K][H][W] -> dw [K][C][3][3] through the 16 grouped products of the Winograd form
-static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, hipStream_t st) {
+static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, bool small,
+                                     hipStream_t st) {
     const int T = ((H + 1) / 2) * ((W + 1) / 2);
-    const int nb = wino_chunk(N, C, H, W, K);
+    const int nb = wino_chunk(N, C, H, W, K, small);
     const int splits = wino_bwdf_splits(nb, T, K, C);
     const size_t kc = (size_t)K * C;
     float* acc = ws;
@@ -603,7 +613,7 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     const int use = resolve_kernel(kPassBwdFilter, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
     if (use == -2) return hipErrorInvalidValue;
-    if (use == kKernelWinograd) return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, st);
+    if (is_winograd(use)) return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, use == kKernelWinogradSmall, st);
     const int CRS = C * R * S;
     int splits = bwdf_splits(N, C, H, W, K, R, S, P, Q);
     const bool have_ws = use == kKernelPacked;
@@ -685,7 +695,7 @@ hipError_t conv_bwd_filter_static(const float* x, const float* dy, float* dw, in
     int use = kernel;
     if (kernel == kKernelAuto) {
         use = kKernelGather;
-        for (int k : {kKernelPacked, kKernelWinograd})
+        for (int k : {kKernelPacked, kKernelWinogradSmall, kKernelWinograd})
             if (conv_workspace(kPassBwdFilter, k, N, C, H, W, K, R, S, stride, pad) != kNoKernel) use = k;
     }
     *need = conv_workspace(kPassBwdFilter, use, N, C, H, W, K, R, S, stride, pad);

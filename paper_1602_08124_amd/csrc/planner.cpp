@@ -416,7 +416,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
     for (int i = 0; i < L; ++i) {
         if (n.layers[i].type != VDNN_CONV) continue;
         const KernelOption &f = n.options_fwd[i][p.opt_fwd[i]], &b = n.options_bwd[i][p.opt_bwd[i]];
-        p.n_winograd += f.fwd == kKernelWinograd || b.bd == kKernelWinograd || b.bf == kKernelWinograd;
+        p.n_winograd += is_winograd(f.fwd) || is_winograd(b.bd) || is_winograd(b.bf);
         p.n_downgraded += algo == VDNN_ALGO_GREEDY && (p.opt_fwd[i] > 0 || p.opt_bwd[i] > 0);
     }
     if (place) finish_plan(n, p, fill_pm, fill_bwd_pm, place_rounds);
@@ -440,7 +440,7 @@ void compile_plan(const vdnn_net& n, int policy, int algo, Plan& p, const std::v
 //             copy), in the order of the static schedule, to the earliest point, not before the previous
 //             fetch, from which its own address range is free and live bytes plus its size stay within
 //             `soft_bwd`, up to its original place.
-static void retime(const vdnn_net& n, Plan& p, size_t soft) {
+static void retime(const vdnn_net& n, Plan& p, size_t soft, size_t soft_bwd) {
     const int L = (int)n.layers.size();
     constexpr int kMaxParts = 32;
     // Blocks larger than the part size move in at most kMaxParts pieces of equal (aligned) size.
@@ -513,7 +513,13 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
         }
         out.push_back(o);
     }
-    while (held_head < held.size()) let_go(L - 1);
+    // With backward windows the copies still queued at the end of forward propagation stay queued: their blocks are
+    // released in backward propagation, oldest first, when an allocation there needs the room (at the latest before the
+    // same feature map is fetched again).  Forward propagation then ends with its last computation, not with its last
+    // copy.  Without backward windows everything queued is released here.
+    const bool trailing = soft_bwd > 0;
+    if (!trailing)
+        while (held_head < held.size()) let_go(L - 1);
     const int new_first_bwd = (int)out.size();
 
     // backward: fetches stay where the static schedule has them (hoist_fetches moves them once the blocks have
@@ -525,13 +531,31 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
         if (bw[t].kind == OP_FREE) freed_at[bw[t].block] = t;
     std::vector<std::vector<int>> await(p.blocks.size());  // block -> pieces whose copy the first reader has to wait for
     std::vector<char> waited(p.blocks.size(), 0);
+    auto let_go_bwd = [&](int layer) {
+        Held& h = held[held_head++];
+        h.wait.layer = h.free.layer = layer;
+        h.wait.phase = h.free.phase = 2;
+        out.push_back(h.wait);
+        out.push_back(h.free);
+        live -= h.bytes;
+    };
+    auto make_room = [&](size_t s, int layer) {
+        while (held_head < held.size() && live + s > soft_bwd) let_go_bwd(layer);
+    };
     for (int t = 0; t < nb; ++t) {
         const Op& o = bw[t];
         if (o.kind == OP_ALLOC && t + 1 < nb && (bw[t + 1].kind == OP_PREFETCH || bw[t + 1].kind == OP_ONDEMAND) && bw[t + 1].block == o.block) {
             const int block = o.block;
             const int k = split(block);
-            // the fetch returns to the range its buffer had in forward propagation when every tenant has left by then
             const int fwd_block = fwd_block_of[p.blocks[block].buf + 1];
+            // a feature map comes back only after the copy of it that forward propagation made has left the pool
+            if (fwd_block >= 0) {
+                size_t last = held_head;
+                for (size_t i = held_head; i < held.size(); ++i)
+                    if (held[i].free.block == fwd_block) last = i + 1;
+                while (held_head < last) let_go_bwd(o.layer);
+            }
+            // the fetch returns to the range its buffer had in forward propagation when every tenant has left by then
             if (fwd_block >= 0) {
                 bool any = false, gone = true;
                 for (size_t b = 0; b < p.blocks.size(); ++b)
@@ -541,6 +565,9 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
             for (int i = k - 1; i >= 0; --i) {
                 Op a = o, c = bw[t + 1];
                 a.part = c.part = k == 1 ? -1 : i;
+                const size_t s = p.blocks[block].piece_bytes(i);
+                make_room(s, o.layer);
+                live += s;
                 out.push_back(a);
                 out.push_back(c);
                 if (c.kind == OP_PREFETCH) await[block].push_back(c.part);  // an on-demand fetch waits by itself
@@ -562,8 +589,15 @@ static void retime(const vdnn_net& n, Plan& p, size_t soft) {
                     waited[b] = 1;
                 }
         }
+        if (o.kind == OP_ALLOC) {
+            make_room(p.blocks[o.block].bytes, o.layer);
+            live += p.blocks[o.block].bytes;
+        } else if (o.kind == OP_FREE) {
+            live -= p.blocks[o.block].bytes;
+        }
         out.push_back(o);
     }
+    while (held_head < held.size()) let_go_bwd(0);   // nothing is left here when every offloaded feature map is fetched again
     p.ops.swap(out);
     p.first_bwd_op = new_first_bwd;
 }
@@ -662,8 +696,12 @@ static void hoist_fetches(Plan& p, size_t soft_bwd) {
         const size_t s = a.part < 0 ? b.bytes : b.piece_bytes(a.part);
         const size_t r0 = b.offset + (a.part < 0 ? 0 : (size_t)a.part * b.part_bytes), r1 = r0 + s;
         int ready = lo;
-        for (const Span& v : spans)
-            if (v.t0 < q && v.off < r1 && r0 < v.off + v.bytes && !(v.block == a.block)) ready = std::max(ready, v.t1);
+        for (const Span& v : spans) {
+            if (v.block == a.block || v.t0 >= q) continue;
+            // not before whatever lies in its range has gone, nor before the copy of the same feature map that forward
+            // propagation made has been released (its offload is what the fetch reads back)
+            if ((v.off < r1 && r0 < v.off + v.bytes) || p.blocks[v.block].buf == b.buf) ready = std::max(ready, v.t1);
+        }
         int j = q;
         while (j > ready && before[j - 1] + s <= soft_bwd) --j;
         if (j < q) {
@@ -727,6 +765,10 @@ static bool reserve_fetch_ranges(Plan& p, size_t soft_bwd) {
         Block& b = p.blocks[a.block];
         const size_t s = a.part < 0 ? b.bytes : b.piece_bytes(a.part);
         int ready = lo;
+        for (int id = 0; id < (int)p.blocks.size(); ++id) {   // after the forward copy of the same feature map has been released
+            const Block& t = p.blocks[id];
+            if (id != a.block && !t.persistent && t.buf == b.buf && t.t0 < q) ready = std::max(ready, t.t1);
+        }
         if (b.host >= 0) {
             const size_t r0 = b.host_rel + (a.part < 0 ? 0 : (size_t)a.part * b.part_bytes), r1 = r0 + s;
             for (int id = 0; id < (int)p.blocks.size(); ++id) {
@@ -759,7 +801,7 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
     auto soft = [&](int pm) { return (size_t)((unsigned __int128)budget * (unsigned)pm / 1000u) / kAlign * kAlign; };
     const bool windows = (fill_pm > 0 || fill_bwd_pm > 0) && n.budget;
     if (windows) {
-        retime(n, p, soft(fill_pm));
+        retime(n, p, soft(fill_pm), fill_bwd_pm > 0 ? soft(fill_bwd_pm) : 0);
         p.fill_pm = fill_pm;
     }
     measure_plan(p);
@@ -826,10 +868,10 @@ static void finish_plan(const vdnn_net& n, Plan& p, int fill_pm, int fill_bwd_pm
 }
 
 // Estimated duration of a planned step from the profile (Section 3.3: vDNN_dyn decides from measured layer times; Section 3.2,
-// Fig. vdnn_fwd / vdnn_bwd: the step is two timelines, stream_compute and stream_memory, tied together where a transfer
-// starts and where the computation waits for it).  Replays the op list: a computation takes its layer's measured time;
-// a copy starts when the memory stream is free and everything enqueued before it on the compute stream has finished,
-// and takes bytes / link rate; a wait moves the compute stream to the end of that copy.  < 0: no profile.
+// Fig. vdnn_fwd / vdnn_bwd: the step is a compute timeline and a memory timeline -- here one per direction of the link --
+// tied together where a transfer starts and where the computation waits for it).  Replays the op list: a computation takes
+// its layer's measured time; a copy starts when its stream is free and everything enqueued before it on the compute stream
+// has finished, and takes bytes / link rate; a wait moves the compute stream to the end of that copy.  < 0: no profile.
 double estimate_step_ms(const vdnn_net& n, const Plan& p) {
     if (!n.profiled || !p.ok) return -1.0;
     const double d2h = (n.link_d2h_gbps > 0 ? n.link_d2h_gbps : 55.0) * 1e6, h2d = (n.link_h2d_gbps > 0 ? n.link_h2d_gbps : 55.0) * 1e6;  // bytes per ms
@@ -852,9 +894,8 @@ double estimate_step_ms(const vdnn_net& n, const Plan& p) {
     };
     constexpr int kSlots = 33;
     std::vector<double> copy_end(p.blocks.size() * kSlots, 0.0);
-    double tc = 0.0, tm = 0.0;
+    double tc = 0.0, tm_out = 0.0, tm_in = 0.0;   // compute stream; offloads and fetches each have a stream (and a link direction) of their own
     for (int t = p.first_fwd_op; t < (int)p.ops.size(); ++t) {
-        if (t == p.first_bwd_op) tc = tm = std::max(tc, tm);  // vdnn_forward returns when both streams have drained
         const Op& o = p.ops[t];
         switch (o.kind) {
             case OP_FWD: tc += fwd_ms(o.layer); break;
@@ -864,6 +905,7 @@ double estimate_step_ms(const vdnn_net& n, const Plan& p) {
             case OP_ONDEMAND: {
                 const Block& b = p.blocks[o.block];
                 const double bytes = (double)(o.part < 0 ? b.raw : b.piece_raw(o.part));
+                double& tm = o.kind == OP_OFFLOAD ? tm_out : tm_in;
                 const double end = std::max(tm, tc) + bytes / (o.kind == OP_OFFLOAD ? d2h : h2d);
                 tm = end;
                 copy_end[(size_t)o.block * kSlots + o.part + 1] = end;
@@ -874,7 +916,7 @@ double estimate_step_ms(const vdnn_net& n, const Plan& p) {
             default: break;
         }
     }
-    return std::max(tc, tm);
+    return std::max(tc, std::max(tm_out, tm_in));
 }
 
 // Section 3.3, "Dynamic vDNN".  Trainability of a pass is decided by the planner, which performs

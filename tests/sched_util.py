@@ -114,11 +114,15 @@ def check_schedule(net, trace, budget, offload_set, persistent_bytes):
             assert resident[base] >= 0, t
             if base[0] == "B" and buf_of_tag(base) in nbytes:
                 b = buf_of_tag(base)
-                if where[0] == "F" and info["readers"][b] and ms.bwd_users(net, info, b):
-                    # 4: released in forward although backward reads it: only once the host has all of it
+                if b in offload_set and b not in fetch_order:
+                    # 4: the copy that forward propagation made leaves the pool (in forward propagation, or, with transfer
+                    # windows, early in backward propagation): only once the host has all of it
                     assert on_host_bytes.get(b, 0) == nbytes[b], t
                     away.add(b)
-                    fetched_bytes[b] = 0
+                    fetched_bytes.setdefault(b, 0)
+                elif where[0] == "F":
+                    # 4: anything else released in forward propagation is something no backward computation reads
+                    assert not ms.bwd_users(net, info, b), t
         elif kind == "offload":
             b = buf_of_tag(t[2])
             assert (kind, t[2]) not in seen_pieces, t                                   # 5: once
@@ -135,6 +139,7 @@ def check_schedule(net, trace, budget, offload_set, persistent_bytes):
             assert (kind if kind == "prefetch" else "prefetch", t[2]) not in seen_pieces, t   # 6: once
             seen_pieces.add(("prefetch", t[2]))
             assert b in away and where[0] == "B", t
+            assert resident.get("B%d" % b, 0) <= size_al[b], t     # the forward copy has gone completely before any of it returns
             if b not in fetch_order:
                 fetch_order.append(b)
             fetched_bytes[b] += t[3]

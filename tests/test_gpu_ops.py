@@ -123,7 +123,8 @@ def test_conv_bwd_filter(B, shape):
     assert rel_err(host(dw), ref) < TOL
 
 
-NAMED = [(2, 32, 20, 20, 136, 3, 1, 1), (1, 256, 6, 6, 256, 3, 1, 1), (2, 256, 9, 9, 128, 3, 1, 1), (3, 64, 14, 14, 80, 5, 1, 2), (2, 3, 30, 30, 64, 7, 2, 3)]
+NAMED = [(2, 32, 20, 20, 136, 3, 1, 1), (1, 256, 6, 6, 256, 3, 1, 1), (2, 256, 9, 9, 128, 3, 1, 1), (3, 64, 14, 14, 80, 5, 1, 2), (2, 3, 30, 30, 64, 7, 2, 3),
+         (5, 256, 12, 12, 256, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("shape", NAMED)
@@ -138,9 +139,21 @@ def test_conv_kernels_by_name(B, shape):
     refs = dict(fwd=L.conv_fwd(x, wt, st, pd), bwd_data=L.conv_bwd_data(dy, wt, x.shape, st, pd), bwd_filter=L.conv_bwd_filter(x, dy, wt.shape, st, pd))
     xd, wd, dyd = dev(x), dev(wt), dev(dy)
     ran = 0
+    if n == 5:   # a chunk size that holds 3 of the 5 images (2 in its halved form), so that the small-chunk Winograd kernel exists
+        B.op_set_winograd_chunk_bytes(3 * 16 * (c + k) * 36 * 4)
+    try:
+        _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd)
+    finally:
+        B.op_set_winograd_chunk_bytes(0)
+
+
+def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd):
+    import torch
+    n, c, h, w, k, r, st, pd = shape
+    ran = 0
     for pass_ in ("fwd", "bwd_data", "bwd_filter"):
         results = {}
-        for kernel in ("gather", "packed", "winograd"):
+        for kernel in ("gather", "packed", "winograd", "winograd_small"):
             nbytes = B.op_conv_workspace(pass_, kernel, x.shape, wt.shape, st, pd)
             out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
             ws = _ws(nbytes) if nbytes else None
@@ -160,8 +173,10 @@ def test_conv_kernels_by_name(B, shape):
             results[kernel] = host(out)
             assert rel_err(results[kernel], refs[pass_]) < TOL, (pass_, kernel)
             ran += 1
-        assert "gather" in results
-        fastest = [kk for kk in ("winograd", "packed", "gather") if kk in results][0]
+        assert "gather" in results and (n != 5 or "winograd_small" in results)
+        if "winograd_small" in results and pass_ != "bwd_filter":   # chunking only partitions the images: same bits
+            assert np.array_equal(results["winograd_small"], results["winograd"])
+        fastest = [kk for kk in ("winograd", "winograd_small", "packed", "gather") if kk in results][0]
         nbytes = B.op_conv_workspace(pass_, fastest, x.shape, wt.shape, st, pd)
         out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
         ws = _ws(nbytes) if nbytes else None
