@@ -57,8 +57,9 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
  *             backward-filter), an unstrided backward-data pass and tensors below 4 GiB;
  *   WINOGRAD  F(2x2,3x3) minimal filtering on wide 3x3 / stride 1 / pad 1 layers: 2.25x fewer multiplications, a
  *             workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk of images);
- *   WINOGRAD_SMALL  the same on chunks of half the size: a few per cent slower, about half the workspace (exists
- *             where the batch does not fit half a chunk anyway).
+ *   WINOGRAD_SMALL  the same on chunks of half as many images: a few per cent slower, about half the workspace (exists
+ *             where a chunk of WINOGRAD holds two images or more).  Forward and backward-data results are the same
+ *             bits as WINOGRAD's (the chunks partition the images); backward-filter sums over the chunks and differs in rounding.
  * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: WINOGRAD, WINOGRAD_SMALL, PACKED, GATHER until
  * vdnn_profile has measured them on the GPU, by measured time afterwards.  The first entry is the layer's
  * performance-optimal algorithm, the last the memory-optimal one.  EVERY plan of the net (whatever the policy and the

@@ -21,8 +21,8 @@ int gemm_splits(long long m, long long n, long long kred);
 size_t gemm_workspace_bytes(long long m, long long n, long long kred);
 
 // The three convolution kernels (Section 2.2: algorithms that trade workspace for speed) and the three passes of a CONV layer.
-// kKernelWinogradSmall: the Winograd kernels on chunks of half the size (a quarter of the workspace's chunk part less per halving
-// would be the next step; one is what the workloads ask for): a few per cent slower, hundreds of MiB less workspace.
+// kKernelWinogradSmall: the Winograd kernels on chunks of half as many images (a further halving would be the next step; one is
+// what the workloads ask for): a few per cent slower, about half the workspace.
 enum { kKernelAuto = -1, kKernelGather = 0, kKernelPacked = 1, kKernelWinograd = 2, kKernelWinogradSmall = 3, kNumKernels = 4 };
 inline bool is_winograd(int kernel) { return kernel == kKernelWinograd || kernel == kKernelWinogradSmall; }
 // rank of a kernel before anything has been measured: lower = expected faster

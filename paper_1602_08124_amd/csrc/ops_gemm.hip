@@ -258,12 +258,15 @@ static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int s
 
 // Images per chunk: as many as the chunk size holds, then evened out over the chunks that this takes (256 images at 167 per
 // chunk run as 128 + 128, not 167 + 89: the same number of launches on a smaller workspace).
-// small: the chunk size halved (kKernelWinogradSmall)
+// small: half as many images per chunk as that, evened out the same way (kKernelWinogradSmall); equal to the full count
+// only where that is one image.
 static int wino_chunk(int N, int cred, int H, int W, int rows, bool small = false) {
     const size_t per_image = (size_t)16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
-    const size_t chunk_bytes = small ? g_wino_chunk_bytes / 2 : g_wino_chunk_bytes;
-    const int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), chunk_bytes / per_image));
-    const int chunks = (N + most - 1) / most;
+    int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
+    int chunks = (N + most - 1) / most;
+    if (!small) return (N + chunks - 1) / chunks;
+    most = ((N + chunks - 1) / chunks + 1) / 2;
+    chunks = (N + most - 1) / most;
     return (N + chunks - 1) / chunks;
 }
 
