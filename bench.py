@@ -34,7 +34,7 @@ WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution
 PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)
 PROFILE_DATA = None     # what run_profile measured; loaded into every net before its policy is set
 HBM_PEAK_TBPS = 8.0
-KERNEL_LETTER = {"gather": "g", "packed": "p", "winograd": "w", "winograd_small": "s"}
+KERNEL_LETTER = {"gather": "g", "packed": "p", "winograd": "w", "winograd_small": "s", "winograd4": "W", "winograd4_small": "S"}
 
 
 def conv_layers_vgg16(batch):

@@ -68,7 +68,8 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
  * down its list (first entry whose workspace fits at that point of the step), and results then differ in rounding.
  * vdnn_set_winograd(net, 0) takes the Winograd kernel off every list of the net. */
 typedef enum {
-    VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2, VDNN_KERNEL_WINOGRAD_SMALL = 3
+    VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2, VDNN_KERNEL_WINOGRAD_SMALL = 3,
+    VDNN_KERNEL_WINOGRAD4 = 4, VDNN_KERNEL_WINOGRAD4_SMALL = 5
 } vdnn_conv_kernel_t;
 typedef enum { VDNN_PASS_FWD = 0, VDNN_PASS_BWD_DATA = 1, VDNN_PASS_BWD_FILTER = 2 } vdnn_conv_pass_t;
 #define VDNN_NO_KERNEL ((size_t)-1) /* vdnn_op_conv_workspace: the kernel does not apply to the shape */

@@ -413,7 +413,7 @@ def op_conv_bwd_data_workspace(x_shape, w_shape, stride, pad):
     return lib.vdnn_op_conv_bwd_data_workspace(n, c, h, wd, k, r, s, stride, pad)
 
 
-KERNEL = {"auto": -1, "gather": 0, "packed": 1, "winograd": 2, "winograd_small": 3}
+KERNEL = {"auto": -1, "gather": 0, "packed": 1, "winograd": 2, "winograd_small": 3, "winograd4": 4, "winograd4_small": 5}
 KERNEL_NAME = {v: k for k, v in KERNEL.items()}
 PASS = {"fwd": 0, "bwd_data": 1, "bwd_filter": 2}
 NO_KERNEL = C.c_size_t(-1).value

@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "../../include/vdnn.h"
+#include "ops.h"
 
 namespace vdnn {
 
@@ -86,7 +87,11 @@ struct KernelOption {
 
 // Section 3.3, "Dynamic vDNN": what the profiling passes measure.  Times in milliseconds, < 0 = not measured.
 struct LayerProfile {
-    float conv[3][4] = {{-1, -1, -1, -1}, {-1, -1, -1, -1}, {-1, -1, -1, -1}};  // CONV: [pass][kernel]
+    float conv[3][kNumKernels];                                      // CONV: [pass][kernel]; -1 = not measured
+    LayerProfile() {
+        for (auto& pass : conv)
+            for (float& ms : pass) ms = -1.f;
+    }
     float fwd = -1, bwd = -1;                                        // every layer: the kernels its plan entry runs
 };
 

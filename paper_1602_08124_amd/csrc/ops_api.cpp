@@ -40,7 +40,7 @@ size_t vdnn_op_conv_workspace(int pass, int kernel, int N, int C, int H, int W, 
     return conv_workspace(pass, kernel, N, C, H, W, K, R, S, stride, pad);
 }
 
-static bool kernel_ok(int kernel) { return kernel >= VDNN_KERNEL_AUTO && kernel <= VDNN_KERNEL_WINOGRAD_SMALL; }
+static bool kernel_ok(int kernel) { return kernel >= VDNN_KERNEL_AUTO && kernel <= VDNN_KERNEL_WINOGRAD4_SMALL; }
 
 vdnn_status_t vdnn_op_conv_fwd(const float* x, const float* w, float* y, void* workspace, size_t workspace_bytes, int N, int C,
                                int H, int W, int K, int R, int S, int stride, int pad, int relu, int kernel, void* stream) {

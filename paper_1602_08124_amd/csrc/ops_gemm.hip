@@ -6,6 +6,7 @@
 
 #include "conv_fast.h"
 #include "winograd.h"
+#include "winograd4.h"
 #include "gemm_tile.h"
 #include "ops.h"
 
@@ -250,19 +251,30 @@ static size_t g_wino_chunk_bytes = (size_t)512 << 20;
 
 void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? bytes : (size_t)512 << 20; }
 
-static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && cred % 16 == 0 && rows % 4 == 0 && cred >= 256 &&
+// m: the output tile's side, 2 (F(2x2, 3x3), winograd.h) or 4 (F(4x4, 3x3), winograd4.h); (m + 2)^2 grouped products.
+static inline int wino_tiles(int H, int W, int m) { return cdiv(H, m) * cdiv(W, m); }
+static inline int wino_groups(int m) { return (m + 2) * (m + 2); }
+
+static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad, int m) {
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && cred % 16 == 0 && rows % 4 == 0 && cred >= (m == 4 ? 128 : 256) &&
            rows >= 128 && N >= 1 && cred <= 65535 && rows <= 65535 &&  // the transforms' grids carry channels and images in y and z
-           (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;         // and index (channel, tile) with 32 bits
+           (long long)wino_tiles(H, W, m) <= 32768 &&                  // and index (channel, tile) with 32 bits
+           (long long)H * W <= (1 << 24);
 }
 
-// Images per chunk: as many as the chunk size holds, then evened out over the chunks that this takes (256 images at 167 per
-// chunk run as 128 + 128, not 167 + 89: the same number of launches on a smaller workspace).
-// small: half as many images per chunk as that, evened out the same way (kKernelWinogradSmall); equal to the full count
+// Images per chunk: as many as keep the whole workspace within the chunk size (what does not depend on the chunk comes off
+// first: the transformed filter; for backward-filter, `bwdf`, the products and the most partial sums a split can take), at
+// least one; then evened out over the chunks that this takes (256 images at 167 per chunk run as 128 + 128, not 167 + 89:
+// the same number of launches on a smaller workspace).
+// small: half as many images per chunk as that, evened out the same way (the _SMALL kernels); equal to the full count
 // only where that is one image.
-static int wino_chunk(int N, int cred, int H, int W, int rows, bool small = false) {
-    const size_t per_image = (size_t)16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
-    int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), g_wino_chunk_bytes / per_image));
+static int wino_chunk(int N, int cred, int H, int W, int rows, int m, bool small = false, bool bwdf = false) {
+    const size_t G = (size_t)wino_groups(m);
+    const size_t per_image = G * (cred + rows) * wino_tiles(H, W, m) * sizeof(float);
+    size_t fixed = (G * cred * rows + 63) / 64 * 64 * sizeof(float);
+    if (bwdf) fixed = G * cred * rows * sizeof(float) * (1 + std::max<long long>(1, 1024 / ((long long)cdiv(rows, 128) * (cred / 128) * (long long)G)));
+    const size_t room = g_wino_chunk_bytes > fixed ? g_wino_chunk_bytes - fixed : 0;
+    int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), room / per_image));
     int chunks = (N + most - 1) / most;
     if (!small) return (N + chunks - 1) / chunks;
     most = ((N + chunks - 1) / chunks + 1) / 2;
@@ -271,54 +283,62 @@ static int wino_chunk(int N, int cred, int H, int W, int rows, bool small = fals
 }
 
 // V for images [n0, n0 + cur) of src
-static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cred, int H, int W, hipStream_t st) {
-    const int T = ((H + 1) / 2) * ((W + 1) / 2);
-    if (H * W <= kWinoPlaneMax && cur <= 65535) {
-        const int tb = T <= 64 ? 64 : 256;
+static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cred, int H, int W, int m, hipStream_t st) {
+    const int T = wino_tiles(H, W, m);
+    const int tb = T <= 64 ? 64 : 256;
+    if (m == 4) {
+        const size_t plane_bytes = sizeof(float) * (4 * cdiv(H, 4) + 2) * (4 * cdiv(W, 4) + 4);
+        if (plane_bytes <= kWino4PlaneBytesMax && cur <= 65535) {
+            VDNN_LAUNCH(wino4_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(256), plane_bytes, st, src, v, n0, cur, cred, H, W);
+        } else {
+            VDNN_LAUNCH(wino4_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
+        }
+    } else if (H * W <= kWinoPlaneMax && cur <= 65535) {
         VDNN_LAUNCH(wino_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(tb), sizeof(float) * (2 * ((H + 1) / 2) + 2) * (2 * ((W + 1) / 2) + 2), st,
                     src, v, n0, cur, cred, H, W);
     } else {
-        const int tb = T <= 64 ? 64 : 256;
         VDNN_LAUNCH(wino_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
     }
     return hipGetLastError();
 }
 
-static size_t wino_workspace(int N, int cred, int H, int W, int rows, bool small = false) {
-    const size_t u = ((size_t)16 * cred * rows + 63) / 64 * 64 * sizeof(float);
-    return u + (size_t)wino_chunk(N, cred, H, W, rows, small) * 16 * (cred + rows) * ((H + 1) / 2) * ((W + 1) / 2) * sizeof(float);
+static size_t wino_workspace(int N, int cred, int H, int W, int rows, int m, bool small = false) {
+    const int G = wino_groups(m);
+    const size_t u = ((size_t)G * cred * rows + 63) / 64 * 64 * sizeof(float);
+    return u + (size_t)wino_chunk(N, cred, H, W, rows, m, small) * G * (cred + rows) * wino_tiles(H, W, m) * sizeof(float);
 }
 
 // src [N][cred][H][W] -> out [N][rows][H][W]; w is the layer's KCRS filter; bwd selects which way it is applied.
 static hipError_t conv_winograd(const float* src, const float* w, float* ws, float* out, const float* mask, int relu, int N, int cred, int H,
-                                int W, int rows, int K, int C, int bwd, bool small, hipStream_t st) {
-    const int T = ((H + 1) / 2) * ((W + 1) / 2);
-    const int nb = wino_chunk(N, cred, H, W, rows, small);
+                                int W, int rows, int K, int C, int bwd, int m, bool small, hipStream_t st) {
+    const int T = wino_tiles(H, W, m), G = wino_groups(m);
+    const int nb = wino_chunk(N, cred, H, W, rows, m, small);
     float* u = ws;
-    float* v = ws + ((size_t)16 * cred * rows + 63) / 64 * 64;
-    float* mt = v + (size_t)16 * nb * cred * T;
+    float* v = ws + ((size_t)G * cred * rows + 63) / 64 * 64;
+    float* mt = v + (size_t)G * nb * cred * T;
     const size_t wcount = (size_t)rows * cred;
-    VDNN_LAUNCH(wino_filter_kernel, dim3((unsigned)std::min<size_t>((wcount + 255) / 256, 4096)), dim3(256), 0, st, w, u, K, C, bwd);
+    if (m == 4) VDNN_LAUNCH(wino4_filter_kernel, dim3((unsigned)std::min<size_t>((wcount + 255) / 256, 4096)), dim3(256), 0, st, w, u, K, C, bwd);
+    else VDNN_LAUNCH(wino_filter_kernel, dim3((unsigned)std::min<size_t>((wcount + 255) / 256, 4096)), dim3(256), 0, st, w, u, K, C, bwd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
-        e = wino_input(src, v, n0, cur, cred, H, W, st);
+        e = wino_input(src, v, n0, cur, cred, H, W, m, st);
         if (e != hipSuccess) return e;
         ConvFastParams p;
         p.src = v; p.wp = u;
         p.src_bytes = (uint32_t)((size_t)cur * cred * T * 4);
         p.wp_bytes = (uint32_t)((size_t)cred * rows * 4);
         p.rows = rows;
-        p.Cred = cred; p.H = (H + 1) / 2; p.W = (W + 1) / 2;
+        p.Cred = cred; p.H = cdiv(H, m); p.W = cdiv(W, m);
         p.R = 1; p.S = 1; p.stride = 1; p.pad = 0;
-        p.P = (H + 1) / 2; p.Q = (W + 1) / 2; p.M = cur * T;
+        p.P = cdiv(H, m); p.Q = cdiv(W, m); p.M = cur * T;
         p.fd_pq = make_fastdiv((uint32_t)T);
-        p.fd_q = make_fastdiv((uint32_t)((W + 1) / 2));
+        p.fd_q = make_fastdiv((uint32_t)cdiv(W, m));
         ConvOut eo;
         eo.out = mt; eo.mask = nullptr; eo.rows = rows; eo.M = p.M; eo.PQ = T; eo.relu = 0; eo.fd_pq = p.fd_pq;
         p.out = eo;
-        p.groups = 16;
+        p.groups = G;
         p.src_gstride = (size_t)cur * cred * T;
         p.wp_gstride = (size_t)cred * rows;
         p.out_gstride = (size_t)cur * rows * T;
@@ -327,8 +347,12 @@ static hipError_t conv_winograd(const float* src, const float* w, float* ws, flo
         ts.full_tiles = rows <= 64 ? cdiv(p.M, 256) : cdiv(rows, 128) * cdiv(p.M, 128);
         e = rows <= 64 ? conv_fast_cfg<64, 256, 1, 4, true>(p, ts, nullptr, st) : conv_fast_cfg<128, 128, 2, 2, true>(p, ts, nullptr, st);
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH(wino_output_kernel, dim3((unsigned)cdiv(rows * T, 256), (unsigned)cur), dim3(256), 0, st, (const float*)mt, out, mask, n0, cur,
-                    rows, H, W, relu);
+        if (m == 4)
+            VDNN_LAUNCH(wino4_output_kernel, dim3((unsigned)cdiv(rows * T, 256), (unsigned)cur), dim3(256), 0, st, (const float*)mt, out, mask, n0, cur,
+                        rows, H, W, relu);
+        else
+            VDNN_LAUNCH(wino_output_kernel, dim3((unsigned)cdiv(rows * T, 256), (unsigned)cur), dim3(256), 0, st, (const float*)mt, out, mask, n0, cur,
+                        rows, H, W, relu);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -353,46 +377,34 @@ size_t conv_bwd_data_packed_workspace(int N, int C, int H, int W, int K, int R, 
     return conv_fast_workspace((size_t)K * C * R * S, C, (long long)N * H * W, K, R * S);
 }
 
-// workspace of the fastest algorithm for the shape: Winograd where it applies, else the packed-weight direct kernel
-size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (packed && wino_ok(N, C, H, W, K, R, S, stride, pad)) return wino_workspace(N, C, H, W, K);
-    return packed;
-}
-
-size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
-    if (packed && wino_ok(N, K, H, W, C, R, S, stride, pad)) return wino_workspace(N, K, H, W, C);
-    return packed;
-}
-
-static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
-static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, bool small = false);
+static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int m);
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, int m, bool small = false);
 
 // Bytes of workspace a kernel needs for a pass over the shape; kNoKernel where that kernel does not apply.
 size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     if (kernel == kKernelGather) return 0;  // works on X, Y and W as stored, for every shape
     if (kernel != kKernelPacked && !is_winograd(kernel)) return kNoKernel;
-    const bool small = kernel == kKernelWinogradSmall;
-    // the small-chunk variant exists where halving the chunk size does change the chunk (a batch that fits half a chunk runs in one piece either way)
+    const bool small = winograd_small(kernel);
+    const int m = winograd_tile(kernel);
+    // a small-chunk variant exists where halving the chunk does change it (one image per chunk cannot be halved)
     if (pass == kPassFwd) {
         const size_t packed = conv_fwd_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         if (!packed) return kNoKernel;
         if (kernel == kKernelPacked) return packed;
-        if (!wino_ok(N, C, H, W, K, R, S, stride, pad) || (small && wino_chunk(N, C, H, W, K, true) == wino_chunk(N, C, H, W, K))) return kNoKernel;
-        return wino_workspace(N, C, H, W, K, small);
+        if (!wino_ok(N, C, H, W, K, R, S, stride, pad, m) || (small && wino_chunk(N, C, H, W, K, m, true) == wino_chunk(N, C, H, W, K, m))) return kNoKernel;
+        return wino_workspace(N, C, H, W, K, m, small);
     }
     if (pass == kPassBwdData) {
         const size_t packed = conv_bwd_data_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         if (!packed) return kNoKernel;
         if (kernel == kKernelPacked) return packed;
-        if (!wino_ok(N, K, H, W, C, R, S, stride, pad) || (small && wino_chunk(N, K, H, W, C, true) == wino_chunk(N, K, H, W, C))) return kNoKernel;
-        return wino_workspace(N, K, H, W, C, small);
+        if (!wino_ok(N, K, H, W, C, R, S, stride, pad, m) || (small && wino_chunk(N, K, H, W, C, m, true) == wino_chunk(N, K, H, W, C, m))) return kNoKernel;
+        return wino_workspace(N, K, H, W, C, m, small);
     }
     if (pass == kPassBwdFilter) {
         if (is_winograd(kernel)) {
-            if (!wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad) || (small && wino_chunk(N, C, H, W, K, true) == wino_chunk(N, C, H, W, K))) return kNoKernel;
-            return wino_bwdf_workspace(N, C, H, W, K, small);
+            if (!wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad, m) || (small && wino_chunk(N, C, H, W, K, m, true, true) == wino_chunk(N, C, H, W, K, m, false, true))) return kNoKernel;
+            return wino_bwdf_workspace(N, C, H, W, K, m, small);
         }
         const size_t split = conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
         return split ? split : kNoKernel;  // no split and no tap-major staging: the same launch as the gather kernel
@@ -400,12 +412,32 @@ size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, i
     return kNoKernel;
 }
 
+// The kernels in the order kKernelAuto tries them (the order of kernel_rank).
+static constexpr int kAutoOrder[] = {kKernelWinograd4, kKernelWinograd4Small, kKernelWinograd, kKernelWinogradSmall, kKernelPacked};
+
+// workspace of the fastest kernel for the shape and pass (0: only the gather kernel applies)
+static size_t fastest_workspace(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    for (int k : kAutoOrder) {
+        const size_t need = conv_workspace(pass, k, N, C, H, W, K, R, S, stride, pad);
+        if (need != kNoKernel) return need;
+    }
+    return 0;
+}
+
+size_t conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    return fastest_workspace(kPassFwd, N, C, H, W, K, R, S, stride, pad);
+}
+
+size_t conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    return fastest_workspace(kPassBwdData, N, C, H, W, K, R, S, stride, pad);
+}
+
 // kernel == kKernelAuto: the fastest kernel whose workspace the caller's has room for.  Otherwise exactly that kernel;
 // hipErrorInvalidValue when it does not apply to the shape or the workspace is too small for it.
 static int resolve_kernel(int pass, int kernel, const void* ws, size_t ws_bytes, int N, int C, int H, int W, int K, int R, int S, int stride,
                           int pad) {
     if (kernel == kKernelAuto) {
-        for (int k : {kKernelWinograd, kKernelWinogradSmall, kKernelPacked}) {
+        for (int k : kAutoOrder) {
             const size_t need = conv_workspace(pass, k, N, C, H, W, K, R, S, stride, pad);
             if (need != kNoKernel && ws && ws_bytes >= need) return k;
         }
@@ -429,7 +461,7 @@ hipError_t conv_fwd(const float* x, const float* w, float* y, void* ws, size_t w
     eo.out = y; eo.mask = nullptr; eo.rows = K; eo.M = g.M; eo.PQ = P * Q; eo.relu = relu; eo.fd_pq = g.fd_pq;
     const int use = resolve_kernel(kPassFwd, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
     if (use == -2) return hipErrorInvalidValue;
-    if (is_winograd(use)) return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, use == kKernelWinogradSmall, st);
+    if (is_winograd(use)) return conv_winograd(x, w, (float*)ws, y, nullptr, relu, N, C, H, W, K, K, C, 0, winograd_tile(use), winograd_small(use), st);
     if (use == kKernelPacked) return conv_fast(x, w, (float*)ws, eo, N, C, H, W, K, C, R, S, stride, pad, P, Q, 0, st);
     return conv_gemm(wa, g, eo, st);
 }
@@ -485,7 +517,7 @@ hipError_t conv_bwd_data(const float* dy, const float* w, float* dx, void* ws, s
     wa.fd_rs = make_fastdiv((uint32_t)(R * S));
     ConvOut eo;
     eo.out = dx; eo.mask = relu_mask; eo.rows = C; eo.M = g.M; eo.PQ = H * W; eo.relu = 0; eo.fd_pq = g.fd_pq;
-    if (is_winograd(use)) return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, use == kKernelWinogradSmall, st);
+    if (is_winograd(use)) return conv_winograd(dy, w, (float*)ws, dx, relu_mask, 0, N, K, H, W, C, K, C, 1, winograd_tile(use), winograd_small(use), st);
     if (use == kKernelPacked) return conv_fast(dy, w, (float*)ws, eo, N, K, P, Q, K, C, R, S, 1, R - 1 - pad, H, W, 1, st);
     return conv_gemm(wa, g, eo, st);
 }
@@ -524,24 +556,23 @@ size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R
 // column tile of the grouped GEMM), 256 or more output channels (128 -> 256 measured 158 against 131 TFLOP/s).
 // Workspace: the 16 accumulated products dU [16][K][C], their per-split partial sums [16][splits][K][C], then V and Dt
 // for a chunk of images.
-static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= 256 && N >= 1 && C <= 65535 && K <= 65535 &&
-           (long long)((H + 1) / 2) * ((W + 1) / 2) <= 32768;
+static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int m) {
+    return R == 3 && S == 3 && stride == 1 && pad == 1 && C % 128 == 0 && K >= (m == 4 ? 128 : 256) && N >= 1 && C <= 65535 && K <= 65535 &&
+           (long long)wino_tiles(H, W, m) <= 32768 && (long long)H * W <= (1 << 24);
 }
 
-static int wino_bwdf_splits(int nb, int T, int K, int C) {
-    const long long tiles = (long long)cdiv(K, 128) * (C / 128) * 16;
+static int wino_bwdf_splits(int nb, int T, int K, int C, int m) {
+    const long long tiles = (long long)cdiv(K, 128) * (C / 128) * wino_groups(m);
     return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv((long long)nb * T, 512)));
 }
 
-static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, bool small) {
-    const int T = ((H + 1) / 2) * ((W + 1) / 2), nb = wino_chunk(N, C, H, W, K, small);
-    return (size_t)16 * K * C * sizeof(float) * (1 + wino_bwdf_splits(nb, T, K, C)) + (size_t)nb * 16 * (C + K) * T * sizeof(float);
+static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, int m, bool small) {
+    const int T = wino_tiles(H, W, m), nb = wino_chunk(N, C, H, W, K, m, small, true), G = wino_groups(m);
+    return (size_t)G * K * C * sizeof(float) * (1 + wino_bwdf_splits(nb, T, K, C, m)) + (size_t)nb * G * (C + K) * T * sizeof(float);
 }
 
 size_t conv_bwd_filter_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
-    if (wino_bwdf_ok(N, C, H, W, K, R, S, stride, pad)) return wino_bwdf_workspace(N, C, H, W, K);
-    return conv_bwd_filter_packed_workspace(N, C, H, W, K, R, S, stride, pad);
+    return fastest_workspace(kPassBwdFilter, N, C, H, W, K, R, S, stride, pad);
 }
 
 template <int BM, int BN, int WM, int WN, int BK = 32, int TAPS = 1>
@@ -567,45 +598,47 @@ static hipError_t bwdf_cfg(const PixKParams& pa, const ConvGeom& g, const RowMaj
         pa, g, eo, eo.rows, eo.cols, g.M, splits, st);
 }
 
-// x [N][C][H][W], dy [N][K][H][W] -> dw [K][C][3][3] through the 16 grouped products of the Winograd form
-static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, bool small,
+// x [N][C][H][W], dy [N][K][H][W] -> dw [K][C][3][3] through the grouped products of the Winograd form
+static hipError_t conv_bwdf_winograd(const float* x, const float* dy, float* dw, float* ws, int N, int C, int H, int W, int K, int m, bool small,
                                      hipStream_t st) {
-    const int T = ((H + 1) / 2) * ((W + 1) / 2);
-    const int nb = wino_chunk(N, C, H, W, K, small);
-    const int splits = wino_bwdf_splits(nb, T, K, C);
+    const int T = wino_tiles(H, W, m), G = wino_groups(m);
+    const int nb = wino_chunk(N, C, H, W, K, m, small, true);
+    const int splits = wino_bwdf_splits(nb, T, K, C, m);
     const size_t kc = (size_t)K * C;
     float* acc = ws;
-    float* part = acc + 16 * kc;
-    float* v = part + (size_t)16 * splits * kc;
-    float* dt = v + (size_t)16 * nb * C * T;
-    const int rblocks = (int)std::min<size_t>((16 * kc + 255) / 256, 8192);
+    float* part = acc + G * kc;
+    float* v = part + (size_t)G * splits * kc;
+    float* dt = v + (size_t)G * nb * C * T;
+    const int rblocks = (int)std::min<size_t>((G * kc + 255) / 256, 8192);
     for (int n0 = 0; n0 < N; n0 += nb) {
         const int cur = std::min(nb, N - n0);
-        hipError_t e = wino_input(x, v, n0, cur, C, H, W, st);
+        hipError_t e = wino_input(x, v, n0, cur, C, H, W, m, st);
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(K * T, 256), (unsigned)cur), dim3(256), 0, st, dy, dt, n0, cur, K, H, W);
+        if (m == 4) VDNN_LAUNCH(wino4_dy_kernel, dim3((unsigned)cdiv(K * T, 256), (unsigned)cur), dim3(256), 0, st, dy, dt, n0, cur, K, H, W);
+        else VDNN_LAUNCH(wino_dy_kernel, dim3((unsigned)cdiv(K * T, 256), (unsigned)cur), dim3(256), 0, st, dy, dt, n0, cur, K, H, W);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         BwdFilterFastParams fp;
         fp.x = v; fp.dy = dt; fp.ws = part;
         fp.x_bytes = (uint32_t)((size_t)cur * C * T * 4);
         fp.dy_bytes = (uint32_t)((size_t)cur * K * T * 4);
-        fp.K = K; fp.C = C; fp.H = (H + 1) / 2; fp.W = (W + 1) / 2; fp.R = 1; fp.S = 1; fp.stride = 1; fp.pad = 0; fp.P = (H + 1) / 2; fp.Q = (W + 1) / 2;
+        fp.K = K; fp.C = C; fp.H = cdiv(H, m); fp.W = cdiv(W, m); fp.R = 1; fp.S = 1; fp.stride = 1; fp.pad = 0; fp.P = cdiv(H, m); fp.Q = cdiv(W, m);
         fp.M = cur * T;
         fp.fd_pq = make_fastdiv((uint32_t)T);
-        fp.fd_q = make_fastdiv((uint32_t)((W + 1) / 2));
+        fp.fd_q = make_fastdiv((uint32_t)cdiv(W, m));
         fp.splits = splits;
-        fp.groups = 16;
+        fp.groups = G;
         fp.x_gstride = (size_t)cur * C * T;
         fp.dy_gstride = (size_t)cur * K * T;
         fp.ws_gstride = (size_t)splits * kc;
         e = bwdf_fast_cfg<128, 128, 2, 2, 16>(fp, st);
         if (e != hipSuccess) return e;
-        VDNN_LAUNCH(wino_accum_kernel, dim3((unsigned)rblocks), dim3(256), 0, st, (const float*)part, acc, kc, splits, n0 == 0 ? 1 : 0);
+        VDNN_LAUNCH(wino_accum_kernel, dim3((unsigned)rblocks), dim3(256), 0, st, (const float*)part, acc, kc, splits, G, n0 == 0 ? 1 : 0);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    VDNN_LAUNCH(wino_filter_grad_kernel, dim3((unsigned)std::min<size_t>((kc + 255) / 256, 8192)), dim3(256), 0, st, (const float*)acc, dw, kc);
+    if (m == 4) VDNN_LAUNCH(wino4_filter_grad_kernel, dim3((unsigned)std::min<size_t>((kc + 255) / 256, 8192)), dim3(256), 0, st, (const float*)acc, dw, kc);
+    else VDNN_LAUNCH(wino_filter_grad_kernel, dim3((unsigned)std::min<size_t>((kc + 255) / 256, 8192)), dim3(256), 0, st, (const float*)acc, dw, kc);
     return hipGetLastError();
 }
 
@@ -616,7 +649,7 @@ hipError_t conv_bwd_filter(const float* x, const float* dy, float* dw, void* ws,
     if (!fits_i32((long long)N * C * H * W) || !fits_i32((long long)N * K * P * Q)) return hipErrorInvalidValue;
     const int use = resolve_kernel(kPassBwdFilter, kernel, ws, ws_bytes, N, C, H, W, K, R, S, stride, pad);
     if (use == -2) return hipErrorInvalidValue;
-    if (is_winograd(use)) return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, use == kKernelWinogradSmall, st);
+    if (is_winograd(use)) return conv_bwdf_winograd(x, dy, dw, (float*)ws, N, C, H, W, K, winograd_tile(use), winograd_small(use), st);
     const int CRS = C * R * S;
     int splits = bwdf_splits(N, C, H, W, K, R, S, P, Q);
     const bool have_ws = use == kKernelPacked;
@@ -698,8 +731,8 @@ hipError_t conv_bwd_filter_static(const float* x, const float* dy, float* dw, in
     int use = kernel;
     if (kernel == kKernelAuto) {
         use = kKernelGather;
-        for (int k : {kKernelPacked, kKernelWinogradSmall, kKernelWinograd})
-            if (conv_workspace(kPassBwdFilter, k, N, C, H, W, K, R, S, stride, pad) != kNoKernel) use = k;
+        for (int k : kAutoOrder)
+            if (conv_workspace(kPassBwdFilter, k, N, C, H, W, K, R, S, stride, pad) != kNoKernel) { use = k; break; }
     }
     *need = conv_workspace(kPassBwdFilter, use, N, C, H, W, K, R, S, stride, pad);
     if (*need == kNoKernel) { *need = 0; return hipErrorInvalidValue; }

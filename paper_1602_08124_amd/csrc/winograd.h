@@ -219,9 +219,9 @@ __global__ void wino_dy_kernel(const float* __restrict__ dy, float* __restrict__
     }
 }
 
-// acc[i] (+)= sum over s of part[group(i)][s][.], s ascending: part is [16][splits][K*C], acc is [16][K*C].
-__global__ void wino_accum_kernel(const float* __restrict__ part, float* __restrict__ acc, size_t kc, int splits, int first) {
-    const size_t total = 16 * kc;
+// acc[i] (+)= sum over s of part[group(i)][s][.], s ascending: part is [groups][splits][K*C], acc is [groups][K*C].
+__global__ void wino_accum_kernel(const float* __restrict__ part, float* __restrict__ acc, size_t kc, int splits, int groups, int first) {
+    const size_t total = (size_t)groups * kc;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const size_t g = i / kc, e = i - g * kc;
         const float* src = part + g * splits * kc + e;

@@ -144,7 +144,7 @@ def test_vgg16_b256_step_under_12_gib(B):
     # invariants: every dW finite, and identical bits under every offloading policy
     for i, d in base_dw.items():
         assert np.isfinite(d).all(), i
-    assert base_st["n_winograd_convs"] == 9   # c3_1 (backward only) ... c5_3
+    assert base_st["n_winograd_convs"] == 10   # c2_2 ... c5_3
     for pol in ("all", "conv", "dyn", "fit"):
         loss, dw, st, _ = _run(B, net, xd, ld, weights, pol, 12 * G)
         assert st["conv_algo"] == "p" and st["kernels"] == base_st["kernels"]   # every plan of a net runs the same kernels
@@ -182,7 +182,7 @@ def test_vgg16_b256_direct_kernels_only(B):
     xd, ld = torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()
     wino_loss, _, wino_st, _ = _run(B, net, xd, ld, weights, "none", 0)
     base_loss, base_dw, base_st, _ = _run(B, net, xd, ld, weights, "none", 0, winograd=False)
-    assert wino_st["n_winograd_convs"] == 9 and base_st["n_winograd_convs"] == 0
+    assert wino_st["n_winograd_convs"] == 10 and base_st["n_winograd_convs"] == 0
     assert base_st["peak_bytes"] < wino_st["peak_bytes"]
     assert abs(wino_loss - base_loss) < 1e-5 * abs(base_loss)
     for pol in ("conv", "fit"):
@@ -194,7 +194,7 @@ def test_vgg16_b256_direct_kernels_only(B):
 
 # The static policies run the performance-optimal kernels and fail where a workspace does not fit (the paper's vDNN_conv (p));
 # where the stated budget is too small for that, the configuration runs the greedy mode (Section 3.3).
-OTHER = [("alexnet", "conv", "greedy", 1 * G), ("overfeat", "all", None, 2 * G), ("overfeat", "conv", None, 2 * G),
+OTHER = [("alexnet", "conv", "greedy", 1 * G), ("overfeat", "all", None, 2 * G), ("overfeat", "conv", "greedy", 2 * G),
          ("googlenet", "dyn", None, 3 * G), ("googlenet", "all", None, 3 * G), ("alexnet", "fit", None, 900 << 20),
          ("googlenet", "fit", None, 2 * G), ("vgg116_b32", "fit", None, 4 * G)]
 

@@ -124,7 +124,7 @@ def test_conv_bwd_filter(B, shape):
 
 
 NAMED = [(2, 32, 20, 20, 136, 3, 1, 1), (1, 256, 6, 6, 256, 3, 1, 1), (2, 256, 9, 9, 128, 3, 1, 1), (3, 64, 14, 14, 80, 5, 1, 2), (2, 3, 30, 30, 64, 7, 2, 3),
-         (5, 256, 12, 12, 256, 3, 1, 1)]
+         (5, 256, 12, 12, 256, 3, 1, 1), (2, 256, 14, 14, 256, 3, 1, 1), (1, 256, 95, 93, 128, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("shape", NAMED)
@@ -153,7 +153,7 @@ def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd):
     ran = 0
     for pass_ in ("fwd", "bwd_data", "bwd_filter"):
         results = {}
-        for kernel in ("gather", "packed", "winograd", "winograd_small"):
+        for kernel in ("gather", "packed", "winograd", "winograd_small", "winograd4", "winograd4_small"):
             nbytes = B.op_conv_workspace(pass_, kernel, x.shape, wt.shape, st, pd)
             out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
             ws = _ws(nbytes) if nbytes else None
@@ -173,10 +173,12 @@ def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd):
             results[kernel] = host(out)
             assert rel_err(results[kernel], refs[pass_]) < TOL, (pass_, kernel)
             ran += 1
-        assert "gather" in results and (n != 5 or "winograd_small" in results)
-        if "winograd_small" in results and pass_ != "bwd_filter":   # chunking only partitions the images: same bits
-            assert np.array_equal(results["winograd_small"], results["winograd"])
-        fastest = [kk for kk in ("winograd", "winograd_small", "packed", "gather") if kk in results][0]
+        assert "gather" in results and (n != 5 or ("winograd_small" in results and "winograd4_small" in results))
+        assert "winograd4" in results or "winograd" not in results    # F(4x4) applies wherever F(2x2) does, and from 128 channels on
+        for full in ("winograd", "winograd4"):
+            if full + "_small" in results and pass_ != "bwd_filter":   # chunking only partitions the images: same bits
+                assert np.array_equal(results[full + "_small"], results[full])
+        fastest = [kk for kk in ("winograd4", "winograd4_small", "winograd", "winograd_small", "packed", "gather") if kk in results][0]
         nbytes = B.op_conv_workspace(pass_, fastest, x.shape, wt.shape, st, pd)
         out = torch.full(refs[pass_].shape, float("nan"), device="cuda")
         ws = _ws(nbytes) if nbytes else None

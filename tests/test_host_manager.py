@@ -516,7 +516,7 @@ def test_every_plan_of_a_net_runs_the_same_kernels():
         n.set_policy("none")
         want = {i: n.layer_kernels(i) for i in convs}
         n.close()
-        assert any("winograd" in k for k in want.values()) or mk is nets.googlenet
+        assert any(kk.startswith("winograd") for k in want.values() for kk in k) or mk is nets.googlenet
         n = binding.Net(net, budget)
         for pol in ("none", "conv", "all", "dyn", "fit"):
             if n.try_policy(pol) != binding.OK:
@@ -529,36 +529,61 @@ def test_every_plan_of_a_net_runs_the_same_kernels():
 
 
 def test_workspace_sizes_by_hand():
-    """The workspace rules of the three kernels evaluated by hand for VGG-16 (256) layers.  Winograd: transformed filter
-    16*C*K floats, then 16*(C + K) floats per 2x2 output tile for a chunk of images: as many as fit 512 MiB, evened out over
-    the chunks that takes; backward-filter: the 16 products once plus once per reduction split, then the same chunk.
-    Packed: one copy of W (rounded up to 256 bytes)."""
+    """The workspace rules of the kernels evaluated by hand for VGG-16 (256) layers.  Winograd F(2x2, 3x3): transformed filter
+    16*C*K floats, then 16*(C + K) floats per 2x2 output tile for a chunk of images: as many as keep the whole workspace
+    within 512 MiB, evened out over the chunks that takes; backward-filter: the 16 products once plus once per reduction
+    split, then the same chunk.  F(4x4, 3x3): the same with 36 products per 4x4 output tile.  Packed: one copy of W (rounded
+    up to 256 bytes)."""
     MiB = 1 << 20
     q = binding.op_conv_workspace
-    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image, at most 41 images
-    # per chunk: 7 chunks for 256 images, 37 images each (the last one 34)
+    # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image; beside the 16 MiB of
+    # the transformed filter 40 images fit: 7 chunks for 256 images, 37 images each (the last one 34)
     x, w = (256, 512, 28, 28), (512, 512, 3, 3)
-    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 + 37 * 12845056
-    assert 41 * 12845056 <= 512 * MiB < 42 * 12845056 and 6 * 41 < 256 <= 7 * 37
+    U = 16 * 512 * 512 * 4
+    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == U + 37 * 12845056
+    assert U + 40 * 12845056 <= 512 * MiB < U + 41 * 12845056 and 6 * 40 < 256 <= 7 * 37
     assert q("fwd", "packed", x, w, 1, 1) == 512 * 512 * 9 * 4
     assert q("fwd", "gather", x, w, 1, 1) == q("bwd_filter", "gather", x, w, 1, 1) == 0
-    # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits of the
-    # 37 * 196 = 7252 tile positions
-    assert q("bwd_filter", "winograd", x, w, 1, 1) == 16 * 512 * 512 * 4 * (1 + 4) + 37 * 12845056
-    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, at most 167 images per chunk: two chunks of 128; a batch smaller than
-    # the chunk: all of it
-    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == 16 * 512 * 512 * 4 + 128 * 3211264
-    assert q("fwd", "winograd", (8, 512, 14, 14), w, 1, 1) == 16 * 512 * 512 * 4 + 8 * 3211264
+    # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits; beside the
+    # products and their partial sums (5 U) 35 images fit: 8 chunks of 32
+    assert q("bwd_filter", "winograd", x, w, 1, 1) == U * (1 + 4) + 32 * 12845056
+    assert 5 * U + 35 * 12845056 <= 512 * MiB < 5 * U + 36 * 12845056
+    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 161 images fit: two chunks of 128; a batch smaller than the chunk: all of it
+    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == U + 128 * 3211264
+    assert q("fwd", "winograd", (8, 512, 14, 14), w, 1, 1) == U + 8 * 3211264
     # 13 x 13 (odd sides): 7 x 7 tiles as well
     assert q("fwd", "winograd", (8, 384, 13, 13), (256, 384, 3, 3), 1, 1) == 16 * 384 * 256 * 4 + 8 * 16 * 640 * 49 * 4
-    # c3_2 backward-filter: 256 -> 256 at 56 x 56: 784 tiles, 25 690 112 bytes per image, 20 per chunk; 2 x 2 tiles x 16 = 64 workgroups -> 16 splits
-    assert q("bwd_filter", "winograd", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 20 * 25690112
+    # c3_2 backward-filter: 256 -> 256 at 56 x 56: 784 tiles, 25 690 112 bytes per image; 2 x 2 tiles x 16 = 64 workgroups -> 16
+    # splits, 17 x 4 MiB; 18 images fit beside them: 15 chunks of 18
+    assert q("bwd_filter", "winograd", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 18 * 25690112
+    # F(4x4, 3x3) on c4_2: 49 tiles per image, 36 * 1024 * 49 * 4 = 7 225 344 bytes per image, 69 fit beside the 36 MiB filter:
+    # 4 chunks of 64; backward-filter: 4 x 4 tiles x 36 products = 576 workgroups: no split, 63 fit beside 2 x 36 MiB: 5 chunks of 52
+    U4 = 36 * 512 * 512 * 4
+    assert q("fwd", "winograd4", x, w, 1, 1) == q("bwd_data", "winograd4", x, w, 1, 1) == U4 + 64 * 7225344
+    assert U4 + 69 * 7225344 <= 512 * MiB < U4 + 70 * 7225344 and 3 * 69 < 256 <= 4 * 64
+    assert q("bwd_filter", "winograd4", x, w, 1, 1) == U4 * (1 + 1) + 52 * 7225344
+    assert q("fwd", "winograd4_small", x, w, 1, 1) == U4 + 32 * 7225344
+    # c5: 14 x 14 is covered by 4 x 4 tiles of 4 x 4: 2 359 296 bytes per image, two chunks of 128
+    assert q("fwd", "winograd4", (256, 512, 14, 14), w, 1, 1) == U4 + 128 * 36 * 1024 * 16 * 4
+    # c3_2 backward-filter: 196 tiles, 14 450 688 bytes per image; 2 x 2 x 36 = 144 workgroups -> 7 splits, 8 x 9 MiB; 31 images fit: 9 chunks of 29
+    assert q("bwd_filter", "winograd4", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 36 * 256 * 256 * 4 * (1 + 7) + 29 * 14450688
+    # F(4x4) moves 2.25 instead of 4 times the tensor through the workspace and pays from 128 channels on (c2_2, c3_1 forward)
+    assert q("fwd", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None and q("fwd", "winograd", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is None
+    assert q("bwd_filter", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None
+    assert q("fwd", "winograd4", (256, 64, 112, 112), (128, 64, 3, 3), 1, 1) is None and q("bwd_data", "winograd4", (256, 64, 112, 112), (128, 64, 3, 3), 1, 1) is None
+    # every Winograd workspace stays within the chunk size unless one image alone passes it
+    for kernel in ("winograd", "winograd4"):
+        for xs, ws_ in ((x, w), ((256, 256, 56, 56), (256, 256, 3, 3)), ((128, 1024, 12, 12), (1024, 1024, 3, 3)), ((256, 512, 14, 14), w)):
+            for pass_ in ("fwd", "bwd_data", "bwd_filter"):
+                assert q(pass_, kernel, xs, ws_, 1, 1) <= 512 * MiB, (kernel, xs, pass_)
     # not wide enough, not 3x3, strided, unpadded, channels not a multiple of 16: no Winograd
     for xs, ws_, st, pd in (((256, 128, 28, 28), (512, 128, 3, 3), 1, 1), ((256, 512, 28, 28), (64, 512, 3, 3), 1, 1),
                             ((256, 512, 28, 28), (512, 512, 5, 5), 1, 2), ((256, 512, 28, 28), (512, 512, 3, 3), 2, 1),
                             ((256, 512, 28, 28), (512, 512, 3, 3), 1, 0), ((256, 520, 28, 28), (512, 520, 3, 3), 1, 1)):
         assert q("fwd", "winograd", xs, ws_, st, pd) is None, (xs, ws_, st, pd)
+        assert (q("fwd", "winograd4", xs, ws_, st, pd) is None) == (xs[1] != 128), (xs, ws_, st, pd)
     assert q("bwd_filter", "winograd", (256, 192, 56, 56), (256, 192, 3, 3), 1, 1) is None      # input channels not a multiple of 128
+    assert q("bwd_filter", "winograd4", (256, 192, 56, 56), (256, 192, 3, 3), 1, 1) is None
     assert q("bwd_filter", "winograd", (256, 256, 56, 56), (128, 256, 3, 3), 1, 1) is None      # fewer than 256 output channels
     # the packed kernels need reduction channels in multiples of 16 (forward: C, backward-data: K; backward-filter: C in 32s
     # or a reduction worth splitting); the first layer of a net (C = 3) has only the gather kernel in forward
@@ -568,8 +593,8 @@ def test_workspace_sizes_by_hand():
     # c1_2 backward-filter: 64 channels, three-tap column tiles: 1 row tile x 3 column tiles -> 341 splits of |W|
     assert q("bwd_filter", "packed", (256, 64, 224, 224), (64, 64, 3, 3), 1, 1) == (1024 // 3) * 64 * 64 * 9 * 4
     # the fastest-kernel queries agree with the per-kernel ones
-    assert binding.op_conv_fwd_workspace(x, w, 1, 1) == q("fwd", "winograd", x, w, 1, 1)
-    assert binding.op_conv_fwd_workspace((256, 128, 56, 56), (256, 128, 3, 3), 1, 1) == q("fwd", "packed", (256, 128, 56, 56), (256, 128, 3, 3), 1, 1)
+    assert binding.op_conv_fwd_workspace(x, w, 1, 1) == q("fwd", "winograd4", x, w, 1, 1)
+    assert binding.op_conv_fwd_workspace((256, 64, 56, 56), (256, 64, 3, 3), 1, 1) == q("fwd", "packed", (256, 64, 56, 56), (256, 64, 3, 3), 1, 1)
 
 
 def test_a_plan_names_its_kernels():
@@ -590,7 +615,7 @@ def test_a_plan_names_its_kernels():
     assert net["layers"][conv]["type"] == "conv" and net["layers"][conv]["k"] == 3
     n = binding.Net(net, 0)
     n.set_policy("none")
-    assert n.layer_kernels(conv) == ("winograd", "winograd", "winograd") and n.stats()["n_winograd_convs"] == 1
+    assert n.layer_kernels(conv) == ("winograd4", "winograd4", "winograd4") and n.stats()["n_winograd_convs"] == 1
     n.set_winograd(False)
     n.set_policy("none")
     assert n.layer_kernels(conv) == ("packed", "packed", "packed") and n.stats()["n_winograd_convs"] == 0
@@ -602,7 +627,7 @@ def test_a_plan_names_its_kernels():
 
 
 def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
-    """Wide 3x3 layers of VGG-16 (256) run the Winograd kernel in every plan (9 layers: c3_1, backward only, ... c5_3); a
+    """Wide 3x3 layers of VGG-16 (256) run the Winograd kernels in every plan (10 layers: c2_2 ... c5_3); a
     budget that has no room for a layer's workspace fails the performance-optimal plan rather than changing the kernel
     behind the caller's back, and the greedy mode then moves that layer down its list."""
     net = nets.vgg16(256)
@@ -610,7 +635,7 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
     n.set_policy("none")
     ws = lib_ws(n, net)
     none_peak = n.stats()["peak_bytes"]
-    assert n.stats()["n_winograd_convs"] == 9
+    assert n.stats()["n_winograd_convs"] == 10
     none_kernels = {i: n.layer_kernels(i) for i, l in enumerate(net["layers"]) if l["type"] == "conv"}
     n.set_winograd(False)
     n.set_policy("none")
@@ -628,7 +653,7 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
     convs = [i for i, l in enumerate(net["layers"]) if l["type"] == "conv"]
     moved = [n.layer_kernels(i) for i in convs if n.layer_kernels(i) != none_kernels[i]]
     # the next entry of a wide layer's list is the same algorithm on chunks of half the size
-    assert len(moved) == st["n_downgraded_convs"] and all("winograd_small" in k or "packed" in k for k in moved)
+    assert len(moved) == st["n_downgraded_convs"] and all(any(kk not in ("winograd4", "gather") for kk in k) for k in moved)
     assert [t[:4] for t in n.trace()] == [tuple(t) for t in ref["trace"]]
     n.close()
     for chunk in (64 << 20, 0):
@@ -636,7 +661,7 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
         try:
             n = binding.Net(net, 0)
             n.set_policy("none")
-            assert n.stats()["n_winograd_convs"] == 9
+            assert n.stats()["n_winograd_convs"] == 10
             assert (n.stats()["workspace_bytes"] < 200 << 20) == (chunk != 0)
             n.close()
         finally:
@@ -698,7 +723,8 @@ def _uniform_profile(n, net, winograd=1.0, packed=1.3, gather=4.0, other=0.1, li
             src = l["inputs"][0]
             xs = (net["batch"], net["in_c"], net["in_h"], net["in_w"]) if src < 0 else shapes[src]
             for pass_ in ("fwd", "bwd_data", "bwd_filter"):
-                for kernel, ms in (("winograd", winograd), ("packed", packed), ("gather", gather)):
+                for kernel, ms in (("winograd4", 0.8 * winograd), ("winograd4_small", 0.85 * winograd), ("winograd", winograd),
+                                   ("winograd_small", 1.05 * winograd), ("packed", packed), ("gather", gather)):
                     if binding.op_conv_workspace(pass_, kernel, xs, (l["out"], xs[1], l["k"], l["k"]), l["stride"], l["pad"]) is not None:
                         n.set_layer_profile(i, pass_, kernel, ms)
         else:
@@ -719,15 +745,18 @@ def test_profile_orders_the_kernel_lists():
     conv = 2
     n = binding.Net(net, 0)
     n.set_policy("none")
-    assert n.layer_kernels(conv) == ("winograd", "winograd", "winograd")
+    assert n.layer_kernels(conv) == ("winograd4", "winograd4", "winograd4")
     before = n.workspace_options(conv, False)
     ws_of = lambda k: binding.op_conv_workspace("fwd", k, (8, 256, 14, 14), (256, 256, 3, 3), 1, 1)
-    # the packed kernel is expected slower than Winograd on half chunks and needs more workspace here: not on the list
-    assert before == [ws_of("winograd"), ws_of("winograd_small"), 0] and ws_of("packed") > ws_of("winograd_small")
+    # expected order F(4x4), F(4x4) on half chunks, F(2x2), F(2x2) on half chunks, packed, gather; an entry that needs no less
+    # workspace than one expected faster is not on the list (F(2x2) on full chunks, the packed kernel)
+    assert before == [ws_of("winograd4"), ws_of("winograd4_small"), ws_of("winograd_small"), 0]
+    assert ws_of("winograd") > ws_of("winograd4_small") > ws_of("winograd_small") and ws_of("packed") > ws_of("winograd_small")
     _uniform_profile(n, net, winograd=2.0, packed=1.0, gather=5.0)      # the packed kernel measured faster than Winograd
     n.set_policy("none")
     assert n.layer_kernels(conv) == ("packed", "packed", "packed")
-    assert n.workspace_options(conv, False) == [ws_of("packed"), 0]     # Winograd (and its unmeasured variant): slower and larger, gone
+    # the Winograd kernels on full chunks: slower and larger, gone; on half chunks they need less workspace and stay
+    assert n.workspace_options(conv, False) == [ws_of("packed"), ws_of("winograd4_small"), ws_of("winograd_small"), 0]
     _uniform_profile(n, net, winograd=1.0, packed=1.0, gather=0.5)      # the gather kernel fastest: the only entry left
     n.set_policy("none")
     assert n.layer_kernels(conv) == ("gather", "gather", "gather") and n.workspace_options(conv, False) == [0]
@@ -735,7 +764,7 @@ def test_profile_orders_the_kernel_lists():
     n.set_layer_kernels(conv, ("winograd", "packed", "gather"))
     n.set_policy("none")
     assert n.layer_kernels(conv) == ("winograd", "packed", "gather")
-    assert n.workspace_options(conv, False) == [before[0]]
+    assert n.workspace_options(conv, False) == [ws_of("winograd")]
     assert binding.lib.vdnn_set_layer_kernels(n.h, 0, (C.c_int32 * 3)(2, 0, 0)) == binding.ERR_INVALID_ARG   # 1x1: no Winograd
     assert binding.lib.vdnn_set_layer_kernels(n.h, 3, (C.c_int32 * 3)(0, 0, 0)) == binding.ERR_INVALID_ARG   # not a CONV layer
     n.set_layer_kernels(conv, None)

@@ -20,7 +20,8 @@ def B():
 
 # (N, C, H, W, K, kernel the shape resolves to): a split reduction over 25 088 pixels, the Winograd form, a small packed
 # case, a shape only the gather kernel takes -- in this order, so that each call finds the leftovers of a larger one
-CALLS = [(8, 64, 56, 56, 64, "packed"), (4, 256, 14, 14, 256, "winograd"), (2, 32, 14, 14, 48, "packed"), (3, 5, 9, 7, 6, "gather")]
+CALLS = [(8, 64, 56, 56, 64, "packed"), (4, 256, 14, 14, 256, "winograd4"), (2, 32, 14, 14, 48, "packed"), (3, 5, 9, 7, 6, "gather")]
+FASTEST_FIRST = ("winograd4", "winograd4_small", "winograd", "winograd_small", "packed", "gather")
 
 
 def test_static_scratch_backward_filter(B):
@@ -32,7 +33,7 @@ def test_static_scratch_backward_filter(B):
         dy = torch.randn((n, k, h, w), device="cuda", generator=g)
         need = B.op_conv_workspace("bwd_filter", kernel, x.shape, (k, c, 3, 3), 1, 1)
         assert need is not None and need <= B.STATIC_SCRATCH_BYTES
-        for better in ("winograd", "packed")[:("winograd", "packed", "gather").index(kernel)]:
+        for better in FASTEST_FIRST[:FASTEST_FIRST.index(kernel)]:
             assert B.op_conv_workspace("bwd_filter", better, x.shape, (k, c, 3, 3), 1, 1) is None   # `kernel` is the fastest that applies
         want = torch.full((k, c, 3, 3), float("nan"), device="cuda")
         ws.fill_(float("nan"))
@@ -47,7 +48,7 @@ def test_static_scratch_backward_filter(B):
     x = torch.randn((64, 512, 28, 28), device="cuda", generator=g)
     dy = torch.randn((64, 512, 28, 28), device="cuda", generator=g)
     dw = torch.zeros((512, 512, 3, 3), device="cuda")
-    assert B.op_conv_workspace("bwd_filter", "winograd", x.shape, dw.shape, 1, 1) > B.STATIC_SCRATCH_BYTES
+    assert B.op_conv_workspace("bwd_filter", "winograd4", x.shape, dw.shape, 1, 1) > B.STATIC_SCRATCH_BYTES
     assert B.try_op_conv_bwd_filter_static(x, dy, dw, 1, 1) == B.ERR_INVALID_ARG
     assert "static buffer holds" in B.lib.vdnn_op_last_error().decode()
     assert float(dw.abs().max()) == 0.0
