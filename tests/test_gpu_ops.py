@@ -138,16 +138,19 @@ def test_conv_kernels_by_name(B, shape):
     dy = _t((n, k, p, q), 13)
     refs = dict(fwd=L.conv_fwd(x, wt, st, pd), bwd_data=L.conv_bwd_data(dy, wt, x.shape, st, pd), bwd_filter=L.conv_bwd_filter(x, dy, wt.shape, st, pd))
     xd, wd, dyd = dev(x), dev(wt), dev(dy)
-    ran = 0
-    if n == 5:   # a chunk size that holds 3 of the 5 images (2 in its halved form), so that the small-chunk Winograd kernel exists
-        B.op_set_winograd_chunk_bytes(3 * 16 * (c + k) * 36 * 4)
-    try:
-        _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd)
-    finally:
-        B.op_set_winograd_chunk_bytes(0)
+    _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd)
+    if n == 5:
+        # a chunk size that leaves room for 2 images (F(2x2) forward and backward-data: 2 + 2 + 1) or for one at a time
+        B.op_set_winograd_chunk_bytes(7 << 20)
+        try:
+            assert B.op_conv_workspace("fwd", "winograd", x.shape, wt.shape, st, pd) == 16 * c * k * 4 + 2 * 16 * (c + k) * 36 * 4
+            assert B.op_conv_workspace("fwd", "winograd4", x.shape, wt.shape, st, pd) == 36 * c * k * 4 + 1 * 36 * (c + k) * 9 * 4
+            _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd, chunked=True)
+        finally:
+            B.op_set_winograd_chunk_bytes(0)
 
 
-def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd):
+def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd, chunked=False):
     import torch
     n, c, h, w, k, r, st, pd = shape
     ran = 0
@@ -173,7 +176,8 @@ def _named_kernels_body(B, shape, x, wt, dy, refs, xd, wd, dyd):
             results[kernel] = host(out)
             assert rel_err(results[kernel], refs[pass_]) < TOL, (pass_, kernel)
             ran += 1
-        assert "gather" in results and (n != 5 or ("winograd_small" in results and "winograd4_small" in results))
+        # 5 images run as chunks of 3 + 2 in the small-chunk forms
+        assert "gather" in results and (n != 5 or chunked or ("winograd_small" in results and "winograd4_small" in results))
         assert "winograd4" in results or "winograd" not in results    # F(4x4) applies wherever F(2x2) does, and from 128 channels on
         for full in ("winograd", "winograd4"):
             if full + "_small" in results and pass_ != "bwd_filter":   # chunking only partitions the images: same bits
@@ -480,11 +484,13 @@ def test_conv_winograd(B, shape):
 
 
 def test_conv_winograd_in_chunks(B):
-    """A chunk size that holds two images of five (chunks of 2, 2 and 1) and one that holds a single image."""
+    """A chunk size that leaves room for two images of five beside the transformed filter (chunks of 2, 2 and 1) and one that
+    holds a single image (F(4x4, 3x3), the fastest kernel for the shape: 2 x 2 tiles of 36 products per image)."""
     shape = (5, 256, 8, 8, 512)
-    per_image = 16 * (256 + 512) * 16 * 4
+    per_image = 36 * (256 + 512) * 4 * 4
     whole, _ = _wino_case(B, shape)
-    two, _ = _wino_case(B, shape, chunk_bytes=2 * per_image + 100)
+    assert whole == 36 * 256 * 512 * 4 + 5 * per_image
+    two, _ = _wino_case(B, shape, chunk_bytes=36 * 256 * 512 * 4 + 2 * per_image + 100)
     one, _ = _wino_case(B, shape, chunk_bytes=per_image // 2)   # smaller than one image: still one image per chunk
     assert whole - two == 3 * per_image and two - one == per_image
 
