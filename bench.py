@@ -28,6 +28,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs summarised in profiles/conv_fwd_vgg16_c2_2_b256.txt, each scaled by what the same counter reads
 # for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 3.289e9.
+ROOFLINE_LAYER = "c2_1"
 ROOFLINE_TRAFFIC_BYTES = 3.580e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
@@ -73,8 +74,9 @@ def streams():
     return _STREAMS
 
 
-def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=None, iters=5, ramp_ms=0):
-    """ramp_ms: before timing, keep the GPU busy for about that long with a kernel of another name (the
+def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=None, iters=5, ramp_ms=0, kernel="auto"):
+    """kernel: "auto" = the fastest kernel for each shape and pass, else that kernel (forward and backward-data).
+    ramp_ms: before timing, keep the GPU busy for about that long with a kernel of another name (the
     backward-filter pass), so that the clocks have settled and a profiler's average over ALL launches of the
     timed kernel agrees with the average over the timed ones."""
     import torch
@@ -90,23 +92,26 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
         row = dict(layer=name, gflop=flop / 1e9)
         torch.cuda.synchronize()
         # workspace of the faster algorithm (packed W + partial sums of split tiles; ignored when it does not apply)
-        nws = max(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1), B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1), 4)
+        if kernel == "auto":
+            nws = max(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1), B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1), 4)
+        else:
+            nws = max([B.op_conv_workspace(p, kernel, x.shape, wt.shape, 1, 1) or 0 for p in ("fwd", "bwd_data") if p in which and (p == "fwd" or c > 3)] + [4])
         wsp = torch.empty(nws // 4, device="cuda")
         if ramp_ms:
-            nb = B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)
+            nb = max(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1), B.op_conv_workspace("bwd_filter", "packed", x.shape, wt.shape, 1, 1) or 0)
             ws = torch.empty(max(nb, 4) // 4, device="cuda")
             dw = torch.empty_like(wt)
             t0 = time.perf_counter()
             while (time.perf_counter() - t0) * 1e3 < ramp_ms:
-                B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream)
+                B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream, kernel="packed" if kernel == "packed" else "auto")
                 stream.synchronize()
             del ws, dw
         if "fwd" in which:
-            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp, kernel), stream, iters=iters)
             row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9
         if "bwd_data" in which and c > 3:
             dx = torch.empty_like(x)
-            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream, wsp), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream, wsp, kernel=kernel), stream, iters=iters)
             row["bwd_data_ms"], row["bwd_data_tflops"] = ms, flop / ms / 1e9
             del dx
         if "bwd_filter" in which:
@@ -124,10 +129,10 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
 def roofline(B, batch):
     """Dominant kernel: the 128x128 implicit-GEMM convolution tile kernel (direct convolutions and the grouped GEMMs
     of the Winograd layers), timed on the largest layer that runs it as a direct convolution in the step
-    (c2_2 forward: 256 x 128 x 112 x 112 -> 128 channels, 947 GFLOP per launch)."""
-    row = conv_kernel_table(B, batch, which=("fwd",), layers=("c2_2",), iters=20, ramp_ms=300)[0]
+    (c2_1 forward: 256 x 64 x 112 x 112 -> 128 channels, 473.5 GFLOP per launch)."""
+    row = conv_kernel_table(B, batch, which=("fwd",), layers=(ROOFLINE_LAYER,), iters=20, ramp_ms=300, kernel="packed")[0]
     ach = row["fwd_tflops"]
-    return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 c2_2 b%d" % batch, achieved=ach,
+    return dict(bound="mfma", kernel="conv_fast_kernel<128,128,2,2> (implicit-GEMM conv forward), VGG-16 %s b%d" % (ROOFLINE_LAYER, batch), achieved=ach,
                 peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=ROOFLINE_TRAFFIC_BYTES,
                 flop_per_launch=row["gflop"] * 1e9, ms_per_launch=row["fwd_ms"])
 
@@ -167,7 +172,7 @@ def layer_table(B, n, net):
     """Per layer and pass of the planned step: the kernel it runs, its profiled time, its algorithmic work (FLOP of the
     direct form for CONV / FC, bytes that have to cross HBM for the others) and the fraction of the roofline that bounds it;
     and the step-weighted figures: all CONV / FC work of the step over all CONV / FC time, against the fp32 MFMA peak, by the
-    direct form's operation count and by the multiplications actually executed (Winograd F(2x2,3x3): 16 per 36)."""
+    direct form's operation count and by the multiplications actually executed (Winograd F(2x2,3x3): 16 per 36, F(4x4,3x3): 36 per 144)."""
     shapes, _ = nets_shapes(net)
     batch = net["batch"]
     rows = []
@@ -184,7 +189,11 @@ def layer_table(B, n, net):
                 ms = prof.get((pass_, kname))
                 if ms is None or (pass_ == "bwd_data" and src < 0):
                     continue
-                executed = flop * (16.0 / 36.0 if kname.startswith("winograd") else 1.0)
+                executed = flop
+                if kname.startswith("winograd"):   # (m + 2)^2 multiplications per m x m output tile instead of 9 m^2, tiles that hang over the edge included
+                    m = 4 if kname.startswith("winograd4") else 2
+                    tiles = -(-out[2] // m) * -(-out[3] // m)
+                    executed = flop * (m + 2) ** 2 * tiles / (9.0 * out[2] * out[3])
                 rows.append(dict(layer=i, type="conv", what=pass_, kernel=kname, ms=ms, gflop=flop / 1e9, tflops=flop / ms / 1e9,
                                  frac_of_mfma_peak=flop / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS, executed_frac_of_mfma_peak=executed / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS))
                 tot["flop"] += flop; tot["executed"] += executed; tot["mfma_ms"] += ms

@@ -254,6 +254,13 @@ void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? 
 // m: the output tile's side, 2 (F(2x2, 3x3), winograd.h) or 4 (F(4x4, 3x3), winograd4.h); (m + 2)^2 grouped products.
 static inline int wino_tiles(int H, int W, int m) { return cdiv(H, m) * cdiv(W, m); }
 static inline int wino_groups(int m) { return (m + 2) * (m + 2); }
+// Backward-filter splits the reduction over tile positions so that about 1024 workgroups run (four per compute unit);
+// the 36 products of F(4x4) come in counts that fill the last round badly (576 tiles of 128 x 128 for 512 x 512 channels),
+// and measured best with up to 2048 (c4_2: 3.18 ms unsplit, 2.74 ms in three splits; c5: 1.03 and 0.91).
+static inline int wino_bwdf_max_splits(int K, int C, int m) {
+    const long long tiles = (long long)cdiv(K, 128) * (C / 128) * wino_groups(m);
+    return (int)std::max<long long>(1, (m == 4 ? 2048 : 1024) / tiles);
+}
 
 static bool wino_ok(int N, int cred, int H, int W, int rows, int R, int S, int stride, int pad, int m) {
     return R == 3 && S == 3 && stride == 1 && pad == 1 && cred % 16 == 0 && rows % 4 == 0 && cred >= (m == 4 ? 128 : 256) &&
@@ -272,7 +279,7 @@ static int wino_chunk(int N, int cred, int H, int W, int rows, int m, bool small
     const size_t G = (size_t)wino_groups(m);
     const size_t per_image = G * (cred + rows) * wino_tiles(H, W, m) * sizeof(float);
     size_t fixed = (G * cred * rows + 63) / 64 * 64 * sizeof(float);
-    if (bwdf) fixed = G * cred * rows * sizeof(float) * (1 + std::max<long long>(1, 1024 / ((long long)cdiv(rows, 128) * (cred / 128) * (long long)G)));
+    if (bwdf) fixed = G * cred * rows * sizeof(float) * (1 + wino_bwdf_max_splits(rows, cred, m));
     const size_t room = g_wino_chunk_bytes > fixed ? g_wino_chunk_bytes - fixed : 0;
     int most = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)N, 65535), room / per_image));
     int chunks = (N + most - 1) / most;
@@ -289,7 +296,10 @@ static hipError_t wino_input(const float* src, float* v, int n0, int cur, int cr
     if (m == 4) {
         const size_t plane_bytes = sizeof(float) * (4 * cdiv(H, 4) + 2) * (4 * cdiv(W, 4) + 4);
         if (plane_bytes <= kWino4PlaneBytesMax && cur <= 65535) {
-            VDNN_LAUNCH(wino4_input_plane_kernel, dim3((unsigned)cred, (unsigned)cur), dim3(256), plane_bytes, st, src, v, n0, cur, cred, H, W);
+            // planes per workgroup: enough tiles for a few rounds of its 256 threads, within 32 KB of LDS (cred is a multiple of 16)
+            int pl = 1;
+            while (pl < 16 && pl * T < 512 && 2 * pl * plane_bytes <= (32 << 10)) pl *= 2;
+            VDNN_LAUNCH(wino4_input_plane_kernel, dim3((unsigned)(cred / pl), (unsigned)cur), dim3(256), pl * plane_bytes, st, src, v, n0, cur, cred, H, W, pl);
         } else {
             VDNN_LAUNCH(wino4_input_kernel, dim3((unsigned)cdiv(T, tb), (unsigned)cred, (unsigned)cur), dim3(tb), 0, st, src, v, n0, cur, cred, H, W);
         }
@@ -562,8 +572,7 @@ static bool wino_bwdf_ok(int N, int C, int H, int W, int K, int R, int S, int st
 }
 
 static int wino_bwdf_splits(int nb, int T, int K, int C, int m) {
-    const long long tiles = (long long)cdiv(K, 128) * (C / 128) * wino_groups(m);
-    return (int)std::max<long long>(1, std::min<long long>(1024 / tiles, cdiv((long long)nb * T, 512)));
+    return (int)std::max<long long>(1, std::min<long long>(wino_bwdf_max_splits(K, C, m), cdiv((long long)nb * T, 512)));
 }
 
 static size_t wino_bwdf_workspace(int N, int C, int H, int W, int K, int m, bool small) {

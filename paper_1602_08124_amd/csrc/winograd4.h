@@ -91,49 +91,61 @@ __global__ void wino4_filter_kernel(const float* __restrict__ w, float* __restri
 }
 
 // V[xi][n][c][t] = (B^T d B)[xi], d = the 6x6 patch of src[n0 + n][c] whose top-left corner is (4*ty - 1, 4*tx - 1).
-// One workgroup per (c, n) plane stages the plane with its zero border in LDS (rows of 4 ceil(W/4) + 4 floats, so that
-// every patch row starts on a 16-byte boundary); threads walk over the tiles.
-// grid (Cred, nb); dynamic LDS (4 ceil(H/4) + 2) * (4 ceil(W/4) + 4) floats, at most kWino4PlaneBytesMax (planes up to
-// about 124 x 124; larger ones take wino4_input_kernel).
+// One workgroup stages `pl` consecutive channel planes of an image with their zero borders in LDS (rows of 4 ceil(W/4) + 4
+// floats, so that every patch row starts on a 16-byte boundary); threads then walk over the pl * T tiles, which are
+// consecutive in V as well, so that every store of a wavefront is one contiguous run whatever the plane size.  pl divides
+// Cred and is chosen by the launcher: enough tiles for the workgroup's threads, LDS within kWino4PlaneBytesMax.
+// grid (Cred / pl, nb); dynamic LDS pl * (4 ceil(H/4) + 2) * (4 ceil(W/4) + 4) floats.
 constexpr size_t kWino4PlaneBytesMax = 64 << 10;
 __global__ __launch_bounds__(256) void wino4_input_plane_kernel(const float* __restrict__ src, float* __restrict__ v, int n0, int nb, int C, int H,
-                                                                 int W) {
+                                                                 int W, int pl) {
     extern __shared__ __align__(16) float plane4[];
-    const int c = blockIdx.x, n = blockIdx.y;
+    const int c0 = blockIdx.x * pl, n = blockIdx.y;
     const int TW = (W + 3) >> 2, TH = (H + 3) >> 2, T = TH * TW;
-    const int PW = 4 * TW + 4, PH = 4 * TH + 2;
-    const float* g = src + ((size_t)(n0 + n) * C + c) * H * W;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
-    for (int ph = wave; ph < PH; ph += waves) {
-        const int ih = ph - 1;
-        const bool row_in = (unsigned)ih < (unsigned)H;
-        for (int pw = lane; pw < PW; pw += 64) {
-            const int iw = pw - 1;
-            plane4[ph * PW + pw] = (row_in && (unsigned)iw < (unsigned)W) ? g[ih * W + iw] : 0.f;
+    const int PW = 4 * TW + 4, PH = 4 * TH + 2, PP = PH * PW;
+    const int HW = H * W;
+    const float* g = src + ((size_t)(n0 + n) * C + c0) * HW;
+    for (int i = threadIdx.x; i < (pl * PP) >> 2; i += blockDim.x) reinterpret_cast<float4*>(plane4)[i] = make_float4(0.f, 0.f, 0.f, 0.f);  // PW % 4 == 0
+    __syncthreads();
+    if ((W & 3) == 0) {  // rows of 16-byte groups: a group never straddles rows or planes
+        const int W4 = W >> 2, total4 = (pl * HW) >> 2;
+        for (int i = threadIdx.x; i < total4; i += blockDim.x) {
+            const float4 e = reinterpret_cast<const float4*>(g)[i];
+            const int row = i / W4, w4 = i - row * W4;  // row counts over all planes
+            const int p = row / H, ih = row - p * H;
+            float* d = plane4 + p * PP + (ih + 1) * PW + 4 * w4 + 1;
+            d[0] = e.x, d[1] = e.y, d[2] = e.z, d[3] = e.w;
+        }
+    } else {
+        for (int i = threadIdx.x; i < pl * HW; i += blockDim.x) {
+            const int p = i / HW, r = i - p * HW;
+            const int ih = r / W, iw = r - ih * W;
+            plane4[p * PP + (ih + 1) * PW + iw + 1] = g[i];
         }
     }
     __syncthreads();
     const size_t gstride = (size_t)nb * C * T;
-    for (int t = threadIdx.x; t < T; t += blockDim.x) {
+    for (int i = threadIdx.x; i < pl * T; i += blockDim.x) {
+        const int p = i / T, t = i - p * T;
         const int ty = t / TW, tx = t - ty * TW;
-        const float* p0 = plane4 + 4 * ty * PW + 4 * tx;
+        const float* p0 = plane4 + p * PP + 4 * ty * PW + 4 * tx;
         float r[6][6];  // r[j][.] = B^T applied down column j
         float d[6][6];
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
-            const float4 a = *reinterpret_cast<const float4*>(p0 + i * PW);
-            const float2 b = *reinterpret_cast<const float2*>(p0 + i * PW + 4);
-            d[i][0] = a.x, d[i][1] = a.y, d[i][2] = a.z, d[i][3] = a.w, d[i][4] = b.x, d[i][5] = b.y;
+        for (int a = 0; a < 6; ++a) {
+            const float4 lo = *reinterpret_cast<const float4*>(p0 + a * PW);
+            const float2 hi = *reinterpret_cast<const float2*>(p0 + a * PW + 4);
+            d[a][0] = lo.x, d[a][1] = lo.y, d[a][2] = lo.z, d[a][3] = lo.w, d[a][4] = hi.x, d[a][5] = hi.y;
         }
 #pragma unroll
         for (int j = 0; j < 6; ++j) w4_bt(d[0][j], d[1][j], d[2][j], d[3][j], d[4][j], d[5][j], r[j]);
-        float* o = v + ((size_t)n * C + c) * T + t;
+        float* o = v + ((size_t)n * C + c0) * T + i;  // planes c0 .. c0 + pl - 1 follow one another in V
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
+        for (int a = 0; a < 6; ++a) {
             float q[6];
-            w4_bt(r[0][i], r[1][i], r[2][i], r[3][i], r[4][i], r[5][i], q);
+            w4_bt(r[0][a], r[1][a], r[2][a], r[3][a], r[4][a], r[5][a], q);
 #pragma unroll
-            for (int j = 0; j < 6; ++j) o[(size_t)(i * 6 + j) * gstride] = q[j];
+            for (int j = 0; j < 6; ++j) o[(size_t)(a * 6 + j) * gstride] = q[j];
         }
     }
 }

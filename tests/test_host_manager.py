@@ -557,16 +557,18 @@ def test_workspace_sizes_by_hand():
     # splits, 17 x 4 MiB; 18 images fit beside them: 15 chunks of 18
     assert q("bwd_filter", "winograd", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 18 * 25690112
     # F(4x4, 3x3) on c4_2: 49 tiles per image, 36 * 1024 * 49 * 4 = 7 225 344 bytes per image, 69 fit beside the 36 MiB filter:
-    # 4 chunks of 64; backward-filter: 4 x 4 tiles x 36 products = 576 workgroups: no split, 63 fit beside 2 x 36 MiB: 5 chunks of 52
+    # 4 chunks of 64; backward-filter: 4 x 4 tiles x 36 products = 576 workgroups: up to 3 splits (2048 workgroups), 53 images fit
+    # beside 4 x 36 MiB: 5 chunks of 52
     U4 = 36 * 512 * 512 * 4
     assert q("fwd", "winograd4", x, w, 1, 1) == q("bwd_data", "winograd4", x, w, 1, 1) == U4 + 64 * 7225344
     assert U4 + 69 * 7225344 <= 512 * MiB < U4 + 70 * 7225344 and 3 * 69 < 256 <= 4 * 64
-    assert q("bwd_filter", "winograd4", x, w, 1, 1) == U4 * (1 + 1) + 52 * 7225344
+    assert q("bwd_filter", "winograd4", x, w, 1, 1) == U4 * (1 + 3) + 52 * 7225344
     assert q("fwd", "winograd4_small", x, w, 1, 1) == U4 + 32 * 7225344
     # c5: 14 x 14 is covered by 4 x 4 tiles of 4 x 4: 2 359 296 bytes per image, two chunks of 128
     assert q("fwd", "winograd4", (256, 512, 14, 14), w, 1, 1) == U4 + 128 * 36 * 1024 * 16 * 4
-    # c3_2 backward-filter: 196 tiles, 14 450 688 bytes per image; 2 x 2 x 36 = 144 workgroups -> 7 splits, 8 x 9 MiB; 31 images fit: 9 chunks of 29
-    assert q("bwd_filter", "winograd4", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 36 * 256 * 256 * 4 * (1 + 7) + 29 * 14450688
+    # c3_2 backward-filter: 196 tiles, 14 450 688 bytes per image; 2 x 2 x 36 = 144 workgroups -> up to 14 splits, 15 x 9 MiB; 27
+    # images fit: 10 chunks of 26, whose 26 * 196 tile positions make 10 splits of at least 512
+    assert q("bwd_filter", "winograd4", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 36 * 256 * 256 * 4 * (1 + 10) + 26 * 14450688
     # F(4x4) moves 2.25 instead of 4 times the tensor through the workspace and pays from 128 channels on (c2_2, c3_1 forward)
     assert q("fwd", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None and q("fwd", "winograd", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is None
     assert q("bwd_filter", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None
