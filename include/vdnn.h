@@ -55,18 +55,24 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
  *   PACKED    implicit GEMM on a packed copy of W, with a deterministic split of long or ragged reductions: workspace
  *             of about |W| (backward-filter: one |W| per split); needs reduction channels in multiples of 16 (32 for
  *             backward-filter), an unstrided backward-data pass and tensors below 4 GiB;
- *   WINOGRAD  F(2x2,3x3) minimal filtering on wide 3x3 / stride 1 / pad 1 layers: 2.25x fewer multiplications, a
- *             workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk of images);
+ *   WINOGRAD  F(2x2,3x3) minimal filtering on wide 3x3 / stride 1 / pad 1 layers (256 reduction channels or more): 2.25x
+ *             fewer multiplications, a workspace of hundreds of MiB (transformed filter, transformed tensors of a chunk
+ *             of images, together within the chunk size of vdnn_op_set_winograd_chunk_bytes unless one image passes it);
  *   WINOGRAD_SMALL  the same on chunks of half as many images: a few per cent slower, about half the workspace (exists
  *             where a chunk of WINOGRAD holds two images or more).  Forward and backward-data results are the same
  *             bits as WINOGRAD's (the chunks partition the images); backward-filter sums over the chunks and differs in rounding.
- * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: WINOGRAD, WINOGRAD_SMALL, PACKED, GATHER until
- * vdnn_profile has measured them on the GPU, by measured time afterwards.  The first entry is the layer's
+ *   WINOGRAD4, WINOGRAD4_SMALL  F(4x4,3x3): 4x fewer multiplications and transformed tensors of 2.25x instead of 4x the
+ *             tensor's size, from 128 reduction channels on; the fastest kernel where it applies (VGG-16 c3_2 forward at
+ *             batch 256: 3.2 ms against 5.0 ms for F(2x2) and 6.7 ms for PACKED).  Its transforms carry factors up to 8
+ *             and sixths: results lie about ten times further from the exact ones than F(2x2)'s, some 1e-5 of a tensor's
+ *             largest value (inside the 1e-4 this library is tested to).
+ * A net keeps, per CONV layer and direction, the list of ways it can run ordered by cost: WINOGRAD4, WINOGRAD4_SMALL,
+ * WINOGRAD, WINOGRAD_SMALL, PACKED, GATHER until vdnn_profile has measured them on the GPU, by measured time afterwards.  The first entry is the layer's
  * performance-optimal algorithm, the last the memory-optimal one.  EVERY plan of the net (whatever the policy and the
  * budget) takes the first entry under VDNN_ALGO_PERF and fails with VDNN_ERR_OOM_DEVICE where that workspace does not
  * fit, so that plans under different policies and budgets compute the same bits; only VDNN_ALGO_GREEDY moves a layer
  * down its list (first entry whose workspace fits at that point of the step), and results then differ in rounding.
- * vdnn_set_winograd(net, 0) takes the Winograd kernel off every list of the net. */
+ * vdnn_set_winograd(net, 0) takes the four Winograd kernels off every list of the net. */
 typedef enum {
     VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2, VDNN_KERNEL_WINOGRAD_SMALL = 3,
     VDNN_KERNEL_WINOGRAD4 = 4, VDNN_KERNEL_WINOGRAD4_SMALL = 5
@@ -225,12 +231,19 @@ vdnn_status_t vdnn_get_link_rate(const vdnn_net_t*, double* d2h_gbps /*host*/, d
 /* Forward propagation, layers 0..L-1 (Section 2.2; offload per Section 3.2 "Memory Offload").
  * input: (device) batch*in_c*in_h*in_w floats; labels: (device) batch int32 in [0, classes).
  * Both are copied into the pool before use.  loss_out: (host) mean softmax-CE loss.
- * Returns after the forward pass has completed on the GPU.  A label outside [0, classes) is never used as an index:
- * the call then returns VDNN_ERR_INVALID_ARG after the pass (loss_out untouched, no backward pass possible). */
+ * Returns once the forward computations have completed on the GPU and the loss has been read.  Under the schedules with
+ * transfer windows (VDNN_POLICY_FIT, vdnn_set_offload_set with a fill) offload copies may still be on their way then: they
+ * go on beside the first backward computations, and their device blocks are released there (Section 3.2 ends every
+ * offload with its layer; the paper's own policies do exactly that).  vdnn_get_output waits for the copy it reads.
+ * A label outside [0, classes) is never used as an index: the call then returns VDNN_ERR_INVALID_ARG after the pass
+ * (loss_out untouched, no backward pass possible). */
 vdnn_status_t vdnn_forward(vdnn_net_t*, const float* input, const int32_t* labels, float* loss_out);
 
 /* Backward propagation, layers L-1..0 (Eq. chain_rule; prefetch per Section 3.2 "Memory Prefetch").
- * Leaves every dW in the pool.  Returns after completion on the GPU. */
+ * Leaves every dW in the pool.  Returns after completion on the GPU: computations, offload copies that forward
+ * propagation left in flight, and fetches.  Offloads run on the memory stream, fetches on a stream the library owns
+ * (one per process, default priority), so that a fetch never queues behind an offload.  The transfer and stall figures of
+ * vdnn_mem_stats (d2h_ms, h2d_ms, d2h_gbps, h2d_gbps, stall_ms) are those of the whole step and final after this call. */
 vdnn_status_t vdnn_backward(vdnn_net_t*);
 
 /* Figures 11/12 of the paper: maximum and average memory, offloaded bytes; plus measured times. */
@@ -297,17 +310,22 @@ const char* vdnn_op_last_error(void);
  *  - WINOGRAD F(2x2,3x3) on 3x3 / stride 1 / pad 1 layers, reduction channels a multiple of 16,
  *    at least 256 of them, output channels of the pass a multiple of 4 and at least 128 (backward-filter: input
  *    channels a multiple of 128, 256 or more output channels): transformed
- *    filter (16/9 of W) plus transformed input and products for a chunk of images (at most the chunk size below).
+ *    filter (16/9 of W) plus transformed input and products for a chunk of images (together at most the chunk size below);
+ *  - WINOGRAD4 F(4x4,3x3) on the same layers and on those with 128 to 255 reduction channels (backward-filter: 128 or more
+ *    output channels): transformed filter 36/9 = 4 times W, transformed tensors 2.25 times the tensor;
+ *  - the _SMALL forms of both on chunks of half as many images.
  * vdnn_op_conv_workspace(pass, kernel, shape) returns the bytes that kernel needs (VDNN_NO_KERNEL: it does not apply);
  * vdnn_op_conv_*_workspace() the bytes of the fastest kernel that applies to the shape (0: only GATHER).
  * The three conv entry points take the kernel to run: an explicit one returns VDNN_ERR_INVALID_ARG where it does not
  * apply or workspace_bytes is too small for it (nothing is launched); VDNN_KERNEL_AUTO runs the fastest kernel the
  * given workspace has room for (NULL: GATHER).  Results
- * agree to rounding (Winograd: a few 1e-6 of the largest output); each kernel is deterministic. */
+ * agree to rounding (F(2x2): a few 1e-6 of the largest output, F(4x4): about 1e-5); each kernel is deterministic. */
 size_t vdnn_op_conv_workspace(int pass /*vdnn_conv_pass_t*/, int kernel /*vdnn_conv_kernel_t, not AUTO*/, int N, int C, int H, int W, int K,
                               int R, int S, int stride, int pad);
-/* Process-wide chunk size of the Winograd workspace in bytes (0 restores the default, 512 MiB).  Workspace sizes and
- * plans derive from it: set it before creating nets, not while one exists. */
+/* Process-wide chunk size of the Winograd workspaces in bytes (0 restores the default, 512 MiB): a workspace holds the
+ * transformed filter (backward-filter: the products and their partial sums) and the transformed tensors of as many
+ * images as fit beside it, at least one.  Workspace sizes and plans derive from it: set it before creating nets, not
+ * while one exists. */
 void vdnn_op_set_winograd_chunk_bytes(size_t bytes);
 size_t vdnn_op_conv_fwd_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t vdnn_op_conv_bwd_data_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
