@@ -249,6 +249,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
     or "set:<id>+<id>...:<fill>[:<fill_bwd>]" for an explicit offload set with transfer windows filling <fill> per mille.
     Every net is given the profile that run_profile measured before its policy is set."""
     import torch
+    t_plan = time.perf_counter()
     n = B.Net(net, budget)
     n.set_winograd(WINOGRAD)
     if window_part_mib is not None:
@@ -271,6 +272,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
         msg = n.last_error()
         n.close()
         return dict(status="oom" if status == B.ERR_OOM_DEVICE else "error %d" % status, detail=msg)
+    print("bench: %s planned in %.1f s" % (policy, time.perf_counter() - t_plan), file=sys.stderr, flush=True)   # a long plan must not look like a hang
     n.attach_torch(streams=streams())
     for i, w in weights.items():
         n.set_weights(i, w)
@@ -297,6 +299,7 @@ def run_policy(B, net, x_dev, lab_dev, weights, policy, budget, steps, warmup, w
         n.backward()
         layer_ms.extend(n.layer_times())
         n.set_layer_timing(False)
+    print("bench: %s %.1f ms per step" % (policy, dt * 1e3), file=sys.stderr, flush=True)
     out = dict(status="ok", img_per_s=net["batch"] / dt, ms_per_step=dt * 1e3, fwd_ms=fwd_ms / steps, bwd_ms=bwd_ms / steps,
                stall_ms=stall / steps, loss=loss, effective_policy=st["effective_policy"], budget_bytes=budget,
                peak_bytes=st["peak_bytes"], pool_extent_bytes=st["pool_extent_bytes"], avg_bytes=st["avg_bytes_layerstep"],

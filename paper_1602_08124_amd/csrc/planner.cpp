@@ -985,12 +985,18 @@ static void improve_by_time(const vdnn_net& n, int algo, std::vector<char>& set,
     for (int b = -1; b < L; ++b)
         if (n.B(b).count && selected(n, b, VDNN_POLICY_ALL)) cands.push_back(b);
     double best_ms = estimate_step_ms(n, best);
+    // Planning a candidate costs time in proportion to the step's blocks (VGG-16: 2 ms, VGG-116: 0.3 s), so the search gets a
+    // budget of candidate plans that shrinks with the graph: the few hundred that VGG-16's neighbourhoods hold, a few dozen
+    // for a net of hundreds of layers, where it is spent on the first moves in a fixed order (dropping a member, then exchanges).
+    long long budget = std::max<long long>(24, std::min<long long>(400, 60000 / std::max<size_t>(1, best.blocks.size())));
     Plan q;
-    for (int round = 0; round < 4; ++round) {
+    for (int round = 0; round < 4 && budget > 0; ++round) {
         std::vector<char> round_set = set;
         double round_ms = best_ms;
         Plan round_plan;
         auto consider = [&](const std::vector<char>& t) {
+            if (budget <= 0) return;
+            --budget;
             if (!plan_with_windows(n, algo, t, q)) return;
             const double ms = estimate_step_ms(n, q);
             if (ms < round_ms) { round_ms = ms; round_set = t; round_plan = q; }
@@ -1001,6 +1007,10 @@ static void improve_by_time(const vdnn_net& n, int algo, std::vector<char>& set,
             std::vector<char> t = set;
             t[m + 1] = 0;
             consider(t);                                    // drop one
+        }
+        for (int m : in) {
+            std::vector<char> t = set;
+            t[m + 1] = 0;
             for (size_t i = 0; i < out.size(); ++i) {
                 t[out[i] + 1] = 1;
                 consider(t);                                // one for one
@@ -1052,11 +1062,11 @@ vdnn_status_t plan_policy(vdnn_net& n, int policy) {
             set[pick + 1] = 1;
         }
         if (!planned) { n.err = p.fail_why; return VDNN_ERR_OOM_DEVICE; }
-        if (n.profiled && n.budget) {
+        if (n.profiled && n.budget && p.blocks.size() <= 2000) {   // (the largest graphs keep the byte-driven set: planning time)
             improve_by_time(n, algo, set, p);
             // The greedy mode gives up a fast kernel where its workspace does not fit; that can let a smaller set of feature
             // maps do, and on a slow link the bytes saved outweigh the slower kernels.  Both are planned; the estimate decides.
-            if (algo == VDNN_ALGO_PERF) {
+            if (algo == VDNN_ALGO_PERF && p.blocks.size() <= 600) {   // (not for the largest graphs: planning time)
                 std::vector<char> gset;
                 Plan g;
                 if (fit_select(n, VDNN_ALGO_GREEDY, gset) && plan_with_windows(n, VDNN_ALGO_GREEDY, gset, g)) {
