@@ -26,10 +26,10 @@ if ROOT not in sys.path:
 GIB = 1 << 30
 FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs summarised in profiles/conv_fwd_vgg16_c2_2_b256.txt, each scaled by what the same counter reads
-# for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 3.289e9.
+# runs summarised in profiles/conv_fwd_vgg16_c2_1_b256.txt, each scaled by what the same counter reads
+# for a plain 1 GiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  Algorithmic bytes: 2.467e9.
 ROOFLINE_LAYER = "c2_1"
-ROOFLINE_TRAFFIC_BYTES = 3.580e9
+ROOFLINE_TRAFFIC_BYTES = 2.500e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
 WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
 PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)

@@ -970,10 +970,12 @@ static bool fit_select(const vdnn_net& n, int algo, std::vector<char>& set) {
 // or more; until no move does (at most four rounds).  Candidates are what vDNN_all would offload.
 static const int kSearchFills[] = {1000, 970, 950, 900, 800, 0};
 
-static bool plan_with_windows(const vdnn_net& n, int algo, const std::vector<char>& set, Plan& out) {
+// place_rounds: 12 for a candidate of the search (few placement rounds each); the default effort for a plan that must not be
+// missed (the greedy mode fills the pool to the brim, and such a step needs more rounds to place)
+static bool plan_with_windows(const vdnn_net& n, int algo, const std::vector<char>& set, Plan& out, int place_rounds = 12) {
     if (!fits_with(n, set, algo)) return false;
     for (int f : kSearchFills) {
-        compile_plan(n, VDNN_POLICY_FIT, algo, out, &set, true, f, f ? 1000 : 0, 12);   // a search: few placement rounds per candidate
+        compile_plan(n, VDNN_POLICY_FIT, algo, out, &set, true, f, f ? 1000 : 0, place_rounds);
         if (out.ok) return true;
     }
     return false;
@@ -1069,7 +1071,7 @@ vdnn_status_t plan_policy(vdnn_net& n, int policy) {
             if (algo == VDNN_ALGO_PERF && p.blocks.size() <= 600) {   // (not for the largest graphs: planning time)
                 std::vector<char> gset;
                 Plan g;
-                if (fit_select(n, VDNN_ALGO_GREEDY, gset) && plan_with_windows(n, VDNN_ALGO_GREEDY, gset, g)) {
+                if (fit_select(n, VDNN_ALGO_GREEDY, gset) && plan_with_windows(n, VDNN_ALGO_GREEDY, gset, g, 300)) {
                     improve_by_time(n, VDNN_ALGO_GREEDY, gset, g);
                     if (estimate_step_ms(n, g) < 0.995 * estimate_step_ms(n, p)) { p = g; set = gset; algo = VDNN_ALGO_GREEDY; }
                 }

@@ -802,6 +802,22 @@ def test_dyn_with_a_profile_chooses_by_estimated_time():
     n.close()
 
 
+def test_fit_with_a_profile_considers_the_greedy_mode():
+    """AlexNet-shaped under 1 GiB has no room for the fastest kernels' workspaces without offloading.  On a slow link giving
+    three layers a slower kernel beats moving feature maps: fit finds that plan (as dyn does) although a step that fills the
+    pool to the brim takes more placement effort than a search candidate gets."""
+    net = nets.alexnet(128)
+    n = binding.Net(net, G)
+    _uniform_profile(n, net, link=5.0, winograd=0.5, packed=0.9, gather=3.0, other=0.05)
+    n.set_policy("dyn")
+    assert (n.stats()["effective_policy"], n.stats()["conv_algo"]) == ("none", "greedy")
+    dyn_ms = n.estimate_step_ms()
+    n.set_policy("fit")
+    assert n.stats()["conv_algo"] == "greedy" and n.estimate_step_ms() <= dyn_ms + 1e-9
+    _assert_valid_schedule(n, net, G)
+    n.close()
+
+
 def test_fit_with_a_profile_never_estimates_worse():
     """The time-driven search of the offload set starts from the byte-driven choice and only takes moves that shorten the
     estimated step: the result is a valid schedule whose estimate is no worse."""
