@@ -211,8 +211,9 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t*, vdnn_conv_algo_t);
 
 /* Section 3.3, "Dynamic vDNN": the profiling passes.  Runs every layer alone on the GPU (zero-filled tensors laid out in the
  * pool of the current plan, which therefore has to be one that fits): its forward and backward computation as a planned step
- * launches them, and for CONV layers every kernel that applies, pass by pass, `repeats` times each after a warm-up launch;
- * and measures the rate of the host link in both directions.  Afterwards each CONV layer's list (vdnn_conv_kernel_t) is
+ * launches them, and for CONV layers every kernel that applies, pass by pass, `repeats` times each after a warm-up launch
+ * (a kernel whose warm-up launch alone takes more than 8 times the fastest kernel measured for the pass, and more than
+ * 20 ms, is not repeated: that one time is its figure); and measures the rate of the host link in both directions.  Afterwards each CONV layer's list (vdnn_conv_kernel_t) is
  * ordered by measured time, and vdnn_set_policy(DYN) / (FIT) choose by estimated step time (see there).  Overwrites dW and
  * whatever the pool holds above the weights; weights stay.  Takes effect at the next vdnn_set_policy / vdnn_set_offload_set.
  * vdnn_set_layer_profile / vdnn_set_link_rate put numbers in by hand (a profile kept from an earlier run; tests of the

@@ -329,11 +329,24 @@ static vdnn_status_t finish_timing(vdnn_net& n, bool bwd) {
 // ---------------------------------------------------------------------------------------------
 // Mean time of `reps` launches of `launch` on the compute stream after one warm-up launch.
 template <class F>
-static vdnn_status_t time_launches(vdnn_net& n, int reps, float* ms_out, F launch) {
-    hipError_t e = launch();
-    if (e != hipSuccess) { n.err = fmt("profile: launch failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); return VDNN_ERR_HIP; }
+static vdnn_status_t time_launches(vdnn_net& n, int reps, float* ms_out, F launch, float give_up_ms = 0.f) {
     NEWEV(e0);
     NEWEV(e1);
+    // the warm-up launch is timed too: a kernel that takes more than give_up_ms (> 0) in it is hopeless against what has
+    // been measured already, and is not repeated (the gather kernel's unsplit backward-filter runs for most of a second
+    // on a large layer)
+    HIPCHK(hipEventRecord(n.events[e0], n.sc));
+    hipError_t e = launch();
+    if (e != hipSuccess) { n.err = fmt("profile: launch failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); n.events_used -= 2; return VDNN_ERR_HIP; }
+    HIPCHK(hipEventRecord(n.events[e1], n.sc));
+    HIPCHK(hipStreamSynchronize(n.sc));
+    float first_ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&first_ms, n.events[e0], n.events[e1]));
+    if (give_up_ms > 0.f && first_ms > give_up_ms) {
+        *ms_out = first_ms;
+        n.events_used -= 2;
+        return VDNN_OK;
+    }
     HIPCHK(hipEventRecord(n.events[e0], n.sc));
     for (int r = 0; r < reps; ++r) {
         e = launch();
@@ -409,14 +422,16 @@ static vdnn_status_t profile_layers(vdnn_net& n, int reps) {
             void* ws = n.pool + ws_off;
             for (int pass = 0; pass < 3 && status == VDNN_OK; ++pass) {
                 if (pass == kPassBwdData && !dx) continue;
-                for (int k = 0; k < kNumKernels && status == VDNN_OK; ++k) {
+                float best = -1.f;
+                for (int k = kNumKernels - 1; k >= 0 && status == VDNN_OK; --k) {   // the kernels expected fastest first
                     const size_t need = conv_workspace(pass, k, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad);
                     if (need == kNoKernel || ws_off - base + align_up(need) > room) continue;
                     status = time_launches(n, reps, &pr.conv[pass][k], [&]() {
                         if (pass == kPassFwd) return conv_fwd(x, w, y, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, fold_fwd(n, i) ? 1 : 0, k, n.sc);
                         if (pass == kPassBwdData) return conv_bwd_data(dy, w, dx, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, fold_bwd(n, i) ? x : nullptr, k, n.sc);
                         return conv_bwd_filter(x, dy, dw, ws, need, N, C, H, W, l.out, l.k, l.k, l.stride, l.pad, k, n.sc);
-                    });
+                    }, best > 0.f ? std::max(8.f * best, 20.f) : 0.f);
+                    if (status == VDNN_OK && (best < 0.f || pr.conv[pass][k] < best)) best = pr.conv[pass][k];
                 }
             }
         } else {
