@@ -469,7 +469,7 @@ static vdnn_status_t profile_link(vdnn_net& n) {
         hipError_t e = hipSuccess;
         float ms = 0.f;
         int e0 = -1, e1 = -1;
-        { hipError_t ee; e0 = new_event(n, &ee); e1 = e0 >= 0 ? new_event(n, &ee) : -1; if (e1 < 0) { e = ee; } }
+        { hipError_t ee = hipSuccess; e0 = new_event(n, &ee); e1 = e0 >= 0 ? new_event(n, &ee) : -1; if (e1 < 0) { e = ee; } }
         for (int r = 0; r < 3 && e == hipSuccess; ++r) {  // the first copy warms the path up; the last two are timed
             if (r == 1) e = hipEventRecord(n.events[e0], n.sm);
             if (e == hipSuccess) e = dir == 0 ? hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, n.sm) : hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, n.sm);
@@ -477,9 +477,9 @@ static vdnn_status_t profile_link(vdnn_net& n) {
         if (e == hipSuccess) e = hipEventRecord(n.events[e1], n.sm);
         if (e == hipSuccess) e = hipStreamSynchronize(n.sm);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, n.events[e0], n.events[e1]);
+        n.events_used -= (e0 >= 0) + (e1 >= 0);
         if (e != hipSuccess) { n.err = fmt("profile: link test failed: %s", hipGetErrorString(e)); (void)hipGetLastError(); status = VDNN_ERR_HIP; break; }
         (dir == 0 ? n.link_d2h_gbps : n.link_h2d_gbps) = ms > 0.f ? 2.0 * (double)bytes / (ms * 1e6) : 0.0;
-        n.events_used -= 2;
     }
     (void)hipHostFree(host);
     return status;
@@ -787,8 +787,13 @@ vdnn_status_t vdnn_layer_workspace_options(const vdnn_net_t* n, int layer, int32
 vdnn_status_t vdnn_layer_kernels(const vdnn_net_t* n, int layer, int32_t kernels[3]) {
     if (!n || !kernels || layer < 0 || layer >= (int)n->layers.size() || n->layers[layer].type != VDNN_CONV) return VDNN_ERR_INVALID_ARG;
     if (!n->plan.ok) return VDNN_ERR_STATE;
-    const KernelOption &f = n->options_fwd[layer][n->plan.opt_fwd[layer]], &b = n->options_bwd[layer][n->plan.opt_bwd[layer]];
-    kernels[0] = f.fwd; kernels[1] = b.bd; kernels[2] = b.bf;
+    // from the plan's own ops: what the step launches (the layer's lists may have been rebuilt since the plan was made)
+    kernels[0] = kernels[1] = kernels[2] = kKernelGather;
+    for (const Op& o : n->plan.ops) {
+        if (o.layer != layer) continue;
+        if (o.kind == OP_FWD) kernels[0] = o.kern[0];
+        if (o.kind == OP_BWD) { kernels[1] = o.kern[1]; kernels[2] = o.kern[2]; }
+    }
     return VDNN_OK;
 }
 

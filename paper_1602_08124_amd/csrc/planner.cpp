@@ -883,14 +883,16 @@ double estimate_step_ms(const vdnn_net& n, const Plan& p) {
         for (int j = 0; j < kNumKernels; ++j) worst = std::max(worst, (double)pr.conv[pass][j]);
         return 2.0 * worst;
     };
-    auto fwd_ms = [&](int i) -> double {
+    // the kernels come from the plan's own ops (the lists they were chosen from are re-sorted whenever the profile changes)
+    auto fwd_ms = [&](const Op& o) -> double {
+        const int i = o.layer;
         if (n.layers[i].type != VDNN_CONV) return n.profile[i].fwd > 0 ? n.profile[i].fwd : 0.0;
-        return conv_ms(i, kPassFwd, n.options_fwd[i][p.opt_fwd[i]].fwd);
+        return conv_ms(i, kPassFwd, o.kern[0]);
     };
-    auto bwd_ms = [&](int i) -> double {
+    auto bwd_ms = [&](const Op& o) -> double {
+        const int i = o.layer;
         if (n.layers[i].type != VDNN_CONV) return n.profile[i].bwd > 0 ? n.profile[i].bwd : 0.0;
-        const KernelOption& o = n.options_bwd[i][p.opt_bwd[i]];
-        return conv_ms(i, kPassBwdFilter, o.bf) + (buf_of(n, n.layers[i].inputs[0]) >= 0 ? conv_ms(i, kPassBwdData, o.bd) : 0.0);
+        return conv_ms(i, kPassBwdFilter, o.kern[2]) + (buf_of(n, n.layers[i].inputs[0]) >= 0 ? conv_ms(i, kPassBwdData, o.kern[1]) : 0.0);
     };
     constexpr int kSlots = 33;
     std::vector<double> copy_end(p.blocks.size() * kSlots, 0.0);
@@ -898,8 +900,8 @@ double estimate_step_ms(const vdnn_net& n, const Plan& p) {
     for (int t = p.first_fwd_op; t < (int)p.ops.size(); ++t) {
         const Op& o = p.ops[t];
         switch (o.kind) {
-            case OP_FWD: tc += fwd_ms(o.layer); break;
-            case OP_BWD: tc += bwd_ms(o.layer); break;
+            case OP_FWD: tc += fwd_ms(o); break;
+            case OP_BWD: tc += bwd_ms(o); break;
             case OP_OFFLOAD:
             case OP_PREFETCH:
             case OP_ONDEMAND: {

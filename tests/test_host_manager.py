@@ -628,6 +628,26 @@ def test_a_plan_names_its_kernels():
     n.close()
 
 
+def test_a_plan_keeps_naming_its_kernels_when_the_lists_change():
+    """vdnn_layer_kernels and the step-time estimate describe the CURRENT plan, also after something rebuilt the layers' lists
+    (a profile put in, the Winograd kernels switched off) and before the next vdnn_set_policy."""
+    net = nets.vgg(8, in_hw=32)
+    n = binding.Net(net, 0)
+    n.set_policy("none")
+    convs = [i for i, l in enumerate(net["layers"]) if l["type"] == "conv"]
+    before = {i: n.layer_kernels(i) for i in convs}
+    assert any(k[0].startswith("winograd") for k in before.values())
+    _uniform_profile(n, net, winograd=9.0, packed=1.0, gather=0.5)      # every list now starts with the gather kernel
+    assert {i: n.layer_kernels(i) for i in convs} == before
+    est = n.estimate_step_ms()
+    n.set_winograd(False)                                                 # lists get shorter
+    assert {i: n.layer_kernels(i) for i in convs} == before and n.estimate_step_ms() == est
+    n.set_policy("none")
+    assert all(k == ("gather", "gather", "gather") for k in (n.layer_kernels(i) for i in convs))
+    assert n.estimate_step_ms() < est
+    n.close()
+
+
 def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
     """Wide 3x3 layers of VGG-16 (256) run the Winograd kernels in every plan (10 layers: c2_2 ... c5_3); a
     budget that has no room for a layer's workspace fails the performance-optimal plan rather than changing the kernel
