@@ -1007,6 +1007,9 @@ static void improve_by_time(const vdnn_net& n, int algo, std::vector<char>& set,
         };
         std::vector<int> in, out;
         for (int b : cands) (set[b + 1] ? in : out).push_back(b);
+        // members from the smallest up: exchanging a small member has few candidates, and the budget should not run out on
+        // the many pairs that could stand in for the largest one before the small ones have had their turn
+        std::stable_sort(in.begin(), in.end(), [&](int a, int b) { return n.B(a).count < n.B(b).count; });
         for (int m : in) {
             std::vector<char> t = set;
             t[m + 1] = 0;
