@@ -13,7 +13,8 @@
  *   - tensors are fp32, NCHW, dense.  Pointers are marked (host) or (device) below.
  *   - the caller owns descriptors and host arrays (consumed before the call returns); the library
  *     owns the net, its pinned host arena and its events.  The device pool and the two streams are
- *     borrowed from the caller when vdnn_attach_device() is used, otherwise created by the library.
+ *     borrowed from the caller when vdnn_attach_device() is used, otherwise created by the library
+ *     (a third stream, on which fetches run, is always the library's own: one per process).
  *   - a net is not thread safe; calls on one net must be serialised by the caller.
  *   - all sizes are bytes unless a name says "count" (elements).
  */
@@ -141,8 +142,11 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
  * layer; DYN: the profiling-pass sequence with out-of-memory as the signal:
  *   1. all with the memory-optimal algorithm must fit (else VDNN_ERR_OOM_DEVICE);
  *   2. performance-optimal algorithms with none, then conv, then all: adopt the first that fits;
- *   3. greedy: conv, then all, with each CONV layer downgraded to the memory-optimal algorithm
- *      where its workspace would overflow the budget; else fall back to 1.
+ *   3. greedy: conv, then all, with each CONV layer moved down its list of kernels (vdnn_conv_kernel_t; the
+ *      last entry is the memory-optimal algorithm) where its workspace would overflow the budget; else fall back to 1.
+ * That order stands in for "fastest first".  After vdnn_profile (the paper's profiling passes, timed on the GPU) the
+ * configurations of 2 and 3, and no offloading with the greedy downgrade, are all planned, and the one whose estimated
+ * step (vdnn_estimate_step_ms) is shortest is adopted.
  * Static policies use the algorithm set by vdnn_set_conv_algo (default performance-optimal).
  * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
  * stays usable with its previous plan). */
@@ -173,7 +177,9 @@ vdnn_status_t vdnn_layer_kernels(const vdnn_net_t*, int layer, int32_t kernels[3
  *   (b) keeps the paper's transfers (offload with the last forward consumer, fetches in findPrefetchLayer
  *       order) but not its end-of-layer synchronisation:
  *       forward: an offloaded X is released only when a later allocation would otherwise pass a share of the
- *       budget (oldest copy first).  While X is away its address range is lent out: a feature map that is not
+ *       budget (oldest copy first); copies still on their way at the end of forward propagation are released in
+ *       backward propagation, when an allocation needs the room or before the same feature map's fetch.
+ *       While X is away its address range is lent out: a feature map that is not
  *       offloaded itself and had to release something becomes a tenant of the block released last, lined up
  *       from the low end of that range;
  *       backward: the fetch of X returns to the range X had (once its tenants are gone), and every fetch is
@@ -183,7 +189,11 @@ vdnn_status_t vdnn_layer_kernels(const vdnn_net_t*, int layer, int32_t kernels[3
  *       The forward share is the largest of 100, 99, ... 90, 88, ... 80, 75, 70, 60, 50, 0 % for which the
  *       blocks can be placed inside the budget (window_fill_pm in the stats; window_fill_bwd_pm = 1000 when
  *       fetches are issued early).
- * Values computed are bit-identical to every other policy (all plans of a net run the same kernels, see vdnn_conv_kernel_t).
+ *   (c) after vdnn_profile: improves the set of (a) by a local search on the estimated step time (drop a member,
+ *       exchange one for one or two others, add one), does the same under the greedy kernel mode, and keeps the plan
+ *       with the shortest estimate.
+ * Values computed are bit-identical to every other policy as long as the plan's mode is performance-optimal (all such
+ * plans of a net run the same kernels, see vdnn_conv_kernel_t; conv_algo in the stats tells).
  *
  * vdnn_set_offload_set: the same machinery with the set given by the caller.  buffers: (host) ids of feature
  * maps: -1 = the network input, otherwise the id of the layer that produces it (in-place ReLUs share their
