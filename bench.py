@@ -92,10 +92,12 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
         row = dict(layer=name, gflop=flop / 1e9)
         torch.cuda.synchronize()
         # workspace of the faster algorithm (packed W + partial sums of split tiles; ignored when it does not apply)
+        kern = {p: kernel if kernel == "auto" or B.op_conv_workspace(p, kernel, x.shape, wt.shape, 1, 1) is not None else "gather"
+                for p in ("fwd", "bwd_data", "bwd_filter")}   # a kernel that does not apply to the shape (C = 3): the gather kernel
         if kernel == "auto":
             nws = max(B.op_conv_fwd_workspace(x.shape, wt.shape, 1, 1), B.op_conv_bwd_data_workspace(x.shape, wt.shape, 1, 1), 4)
         else:
-            nws = max([B.op_conv_workspace(p, kernel, x.shape, wt.shape, 1, 1) or 0 for p in ("fwd", "bwd_data") if p in which and (p == "fwd" or c > 3)] + [4])
+            nws = max([B.op_conv_workspace(p, kern[p], x.shape, wt.shape, 1, 1) or 0 for p in ("fwd", "bwd_data") if p in which and (p == "fwd" or c > 3)] + [4])
         wsp = torch.empty(nws // 4, device="cuda")
         if ramp_ms:
             nb = max(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1), B.op_conv_workspace("bwd_filter", "packed", x.shape, wt.shape, 1, 1) or 0)
@@ -103,22 +105,22 @@ def conv_kernel_table(B, batch, which=("fwd", "bwd_data", "bwd_filter"), layers=
             dw = torch.empty_like(wt)
             t0 = time.perf_counter()
             while (time.perf_counter() - t0) * 1e3 < ramp_ms:
-                B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream, kernel="packed" if kernel == "packed" else "auto")
+                B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream, kernel=kern["bwd_filter"])
                 stream.synchronize()
             del ws, dw
         if "fwd" in which:
-            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp, kernel), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_fwd(x, wt, y, 1, 1, False, stream, wsp, kern["fwd"]), stream, iters=iters)
             row["fwd_ms"], row["fwd_tflops"] = ms, flop / ms / 1e9
         if "bwd_data" in which and c > 3:
             dx = torch.empty_like(x)
-            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream, wsp, kernel=kernel), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_bwd_data(y, wt, dx, 1, 1, stream, wsp, kernel=kern["bwd_data"]), stream, iters=iters)
             row["bwd_data_ms"], row["bwd_data_tflops"] = ms, flop / ms / 1e9
             del dx
         if "bwd_filter" in which:
-            nb = B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1)
+            nb = max(B.op_conv_bwd_filter_workspace(x.shape, wt.shape, 1, 1), B.op_conv_workspace("bwd_filter", "packed", x.shape, wt.shape, 1, 1) or 0)
             ws = torch.empty(max(nb, 4) // 4, device="cuda")
             dw = torch.empty_like(wt)
-            ms = time_kernel(lambda: B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream), stream, iters=iters)
+            ms = time_kernel(lambda: B.op_conv_bwd_filter(x, y, dw, ws, 1, 1, stream, kernel=kern["bwd_filter"]), stream, iters=iters)
             row["bwd_filter_ms"], row["bwd_filter_tflops"] = ms, flop / ms / 1e9
             del ws, dw
         rows.append(row)
@@ -444,7 +446,7 @@ def main():
         out["profile"] = dict(seconds=profile_s, link_gbps=PROFILE_DATA["link"],
                               layers={str(i): {"/".join(k) if isinstance(k, tuple) else k: v for k, v in e.items()} for i, e in PROFILE_DATA["layers"].items()})
     if args.kernel_table:
-        out["conv_kernels"] = conv_kernel_table(B, args.batch)
+        out["conv_kernels"] = conv_kernel_table(B, args.batch, kernel="auto" if WINOGRAD else "packed")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_batch)
     print(json.dumps(out))
