@@ -31,7 +31,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 ROOFLINE_LAYER = "c2_1"
 ROOFLINE_TRAFFIC_BYTES = 2.500e9
 LINK_PEAK_GBPS = 64.0  # PCIe Gen5 x16, per direction
-WINOGRAD = True         # --no-winograd: every plan keeps the direct convolution kernels
+WINOGRAD = 1            # vdnn_set_winograd level: --no-winograd = 0 (direct kernels only), --winograd-level 2 = only F(2x2,3x3)
 PROFILE = True          # --no-profile: dyn and fit decide without the profiling passes (the paper's fixed order; bytes)
 PROFILE_DATA = None     # what run_profile measured; loaded into every net before its policy is set
 HBM_PEAK_TBPS = 8.0
@@ -348,13 +348,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true", help="skip the roofline kernel (for a profile of the steps alone)")
     ap.add_argument("--no-winograd", action="store_true", help="keep every plan on the direct convolution kernels (side measurement)")
+    ap.add_argument("--winograd-level", type=int, default=1, choices=[0, 1, 2], help="side measurement: 2 = only the F(2x2,3x3) Winograd kernels, 0 = none")
     ap.add_argument("--cpu-sample-batch", type=int, default=8)
     ap.add_argument("--no-profile", action="store_true", help="dyn and fit decide without the profiling passes")
     ap.add_argument("--winograd-chunk-mib", type=int, default=0, help="side measurement: chunk size of the Winograd workspace (0 = the library's default)")
     ap.add_argument("--no-layer-table", action="store_true", help="skip the per-layer table of the no-offload step")
     args = ap.parse_args()
     global WINOGRAD, PROFILE
-    WINOGRAD = not args.no_winograd
+    WINOGRAD = 0 if args.no_winograd else args.winograd_level
     PROFILE = not args.no_profile
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the vDNN step is a single-GPU method); use --gpus 1", file=sys.stderr)

@@ -73,7 +73,7 @@ typedef enum { VDNN_ALGO_PERF = 0, VDNN_ALGO_MEM = 1, VDNN_ALGO_GREEDY = 2 } vdn
  * budget) takes the first entry under VDNN_ALGO_PERF and fails with VDNN_ERR_OOM_DEVICE where that workspace does not
  * fit, so that plans under different policies and budgets compute the same bits; only VDNN_ALGO_GREEDY moves a layer
  * down its list (first entry whose workspace fits at that point of the step), and results then differ in rounding.
- * vdnn_set_winograd(net, 0) takes the four Winograd kernels off every list of the net. */
+ * vdnn_set_winograd(net, 0) takes the four Winograd kernels off every list of the net, (net, 2) the two F(4x4) ones. */
 typedef enum {
     VDNN_KERNEL_AUTO = -1, VDNN_KERNEL_GATHER = 0, VDNN_KERNEL_PACKED = 1, VDNN_KERNEL_WINOGRAD = 2, VDNN_KERNEL_WINOGRAD_SMALL = 3,
     VDNN_KERNEL_WINOGRAD4 = 4, VDNN_KERNEL_WINOGRAD4_SMALL = 5
@@ -151,8 +151,10 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
  * Re-plans the step.  Returns VDNN_ERR_OOM_DEVICE if the policy cannot fit the budget (the net
  * stays usable with its previous plan). */
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
-/* enabled = 0: no plan of this net uses the Winograd kernel (default: enabled).  Takes effect at the next
- * vdnn_set_policy / vdnn_set_offload_set. */
+/* Which Winograd kernels the CONV layers of this net may run: 1 (default) all of them; 2 only the F(2x2,3x3) forms, whose
+ * rounding error is a tenth of F(4x4,3x3)'s (for callers that want results within a few 1e-6 of the exact ones; VGG-16
+ * at batch 256 then takes 146 instead of 112 ms per step); 0 none (direct kernels only: 186 ms).  Any other value:
+ * VDNN_ERR_INVALID_ARG.  Takes effect at the next vdnn_set_policy / vdnn_set_offload_set. */
 vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
 /* The list described above, as workspace bytes: entry 0 is what VDNN_ALGO_PERF allocates for the layer's forward
  * (bwd = 0) or backward (bwd != 0: the larger of backward-data and backward-filter) computation, the following entries

@@ -178,7 +178,8 @@ class Net:
         self._chk(lib.vdnn_set_policy(self.h, POLICY[policy]))
 
     def set_winograd(self, enabled):
-        self._chk(lib.vdnn_set_winograd(self.h, 1 if enabled else 0))
+        """True / 1: every Winograd kernel; 2: only the F(2x2,3x3) forms; False / 0: none (see vdnn_set_winograd)."""
+        self._chk(lib.vdnn_set_winograd(self.h, int(enabled)))
 
     def workspace_options(self, layer, bwd):
         """Workspace bytes of the ways a layer can run, performance-optimal first (see vdnn_layer_workspace_options)."""

@@ -184,7 +184,7 @@ void build_kernel_options(vdnn_net& n) {
             if (!n.profiled) return (double)kernel_rank(k);
             return pr.conv[pass][k] >= 0 ? (double)pr.conv[pass][k] : 1e9 + (double)kernel_rank(k);
         };
-        auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (!is_winograd(k) || n.winograd); };
+        auto usable = [&](int pass, int k) { return ws_of(pass, k) != kNoKernel && (!is_winograd(k) || n.winograd == 1 || (n.winograd == 2 && winograd_tile(k) == 2)); };
         const bool need_dx = buf_of(n, l.inputs[0]) >= 0;
         if (n.pinned_kernels[i] >= 0) {  // the caller named the kernels: the layer's only way to run
             const int kf = n.pinned_kernels[i] & 15, kd = (n.pinned_kernels[i] >> 4) & 15, kb = (n.pinned_kernels[i] >> 8) & 15;

@@ -516,7 +516,8 @@ vdnn_status_t vdnn_set_conv_algo(vdnn_net_t* n, vdnn_conv_algo_t algo) {
 
 vdnn_status_t vdnn_set_winograd(vdnn_net_t* n, int32_t enabled) {
     if (!n) return VDNN_ERR_INVALID_ARG;
-    n->winograd = enabled != 0;
+    if (enabled < 0 || enabled > 2) return VDNN_ERR_INVALID_ARG;
+    n->winograd = enabled;
     build_kernel_options(*n);
     return VDNN_OK;
 }

@@ -155,7 +155,7 @@ struct vdnn_net {
     size_t part_bytes = (size_t)128 << 20;  // transfer windows move larger blocks in pieces of about this size (0 = whole blocks)
     int policy = VDNN_POLICY_NONE, effective = VDNN_POLICY_NONE;
     int static_algo = VDNN_ALGO_PERF;
-    bool winograd = true;  // the Winograd kernel is among the options of wide 3x3 layers
+    int winograd = 1;      // which Winograd kernels are among the options of 3x3 layers: 0 none, 1 all, 2 only F(2x2, 3x3)
     // Per layer, how it can run, preference order (first = performance-optimal, last of a CONV layer = memory-optimal, no
     // workspace).  Every plan of the net takes its kernels from here, so that plans under different policies and budgets
     // compute the same bits; only the greedy mode (Section 3.3, phase 3) moves a layer down its list.

@@ -659,6 +659,12 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
     none_peak = n.stats()["peak_bytes"]
     assert n.stats()["n_winograd_convs"] == 10
     none_kernels = {i: n.layer_kernels(i) for i, l in enumerate(net["layers"]) if l["type"] == "conv"}
+    n.set_winograd(2)        # only the F(2x2, 3x3) forms: c3_1 (backward only) ... c5_3
+    n.set_policy("none")
+    assert n.stats()["n_winograd_convs"] == 9
+    assert all(not kk.startswith("winograd4") for i in none_kernels for kk in n.layer_kernels(i))
+    assert n.layer_kernels(12) == ("winograd", "winograd", "winograd") and n.layer_kernels(7) == ("packed", "packed", "packed")
+    assert binding.lib.vdnn_set_winograd(n.h, 3) == binding.ERR_INVALID_ARG
     n.set_winograd(False)
     n.set_policy("none")
     assert n.stats()["n_winograd_convs"] == 0 and n.stats()["peak_bytes"] < none_peak
