@@ -33,7 +33,9 @@ FULL_LAYERS = [
     ("vgg c1_1", 256, 3, 224, 224, 64, 3, 1, 1),
     ("vgg c1_2", 256, 64, 224, 224, 64, 3, 1, 1),
     ("vgg c2_1", 256, 64, 112, 112, 128, 3, 1, 1),
+    ("vgg c2_2", 256, 128, 112, 112, 128, 3, 1, 1),    # F(4x4) Winograd on 128 channels, 52 KB planes staged in LDS, 15 chunks
     ("vgg c3_2", 256, 256, 56, 56, 256, 3, 1, 1),
+    ("vgg c4_2", 256, 512, 28, 28, 512, 3, 1, 1),      # backward-filter in three splits of 576 grouped tiles
     ("vgg c5_1", 256, 512, 14, 14, 512, 3, 1, 1),
     ("alexnet c1", 128, 3, 227, 227, 96, 11, 4, 0),
     ("alexnet c2", 128, 96, 27, 27, 256, 5, 1, 2),
