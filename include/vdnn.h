@@ -335,7 +335,7 @@ const char* vdnn_op_last_error(void);
  * agree to rounding (F(2x2): a few 1e-6 of the largest output, F(4x4): about 1e-5); each kernel is deterministic. */
 size_t vdnn_op_conv_workspace(int pass /*vdnn_conv_pass_t*/, int kernel /*vdnn_conv_kernel_t, not AUTO*/, int N, int C, int H, int W, int K,
                               int R, int S, int stride, int pad);
-/* Process-wide chunk size of the Winograd workspaces in bytes (0 restores the default, 512 MiB): a workspace holds the
+/* Process-wide chunk size of the Winograd workspaces in bytes (0 restores the default, 384 MiB): a workspace holds the
  * transformed filter (backward-filter: the products and their partial sums) and the transformed tensors of as many
  * images as fit beside it, at least one.  Workspace sizes and plans derive from it: set it before creating nets, not
  * while one exists. */

@@ -53,7 +53,7 @@ size_t conv_workspace(int pass, int kernel, int N, int C, int H, int W, int K, i
 // (hipErrorInvalidValue where it does not apply or the workspace is too small for it); kKernelAuto runs the fastest
 // one that the workspace they are given has room for.
 // conv_*_packed_workspace: bytes of the packed-weight direct kernel alone (what a Winograd-sized layer falls back to).
-void conv_set_winograd_chunk_bytes(size_t bytes);  // V + Mt bytes per chunk of images (0 = default 512 MiB)
+void conv_set_winograd_chunk_bytes(size_t bytes);  // V + Mt bytes per chunk of images (0 = default 384 MiB)
 size_t conv_fwd_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_bwd_data_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 size_t conv_bwd_filter_packed_workspace(int N, int C, int H, int W, int K, int R, int S, int stride, int pad);

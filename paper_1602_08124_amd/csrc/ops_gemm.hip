@@ -247,9 +247,12 @@ static hipError_t conv_fast(const float* src, const float* w, float* ws, const C
 // traffic costs what the saved multiplications gain (131 against 136).
 // Workspace: U, then V and Mt for `nb` images, nb the largest count that keeps V + Mt within the chunk size.
 // -------------------------------------------------------------------------------------------
-static size_t g_wino_chunk_bytes = (size_t)512 << 20;
+// Default 384 MiB, measured on VGG-16 (256) with 512 / 448 / 384 / 320 / 256 MiB: the step without a budget 112.3 / 113.0 / 113.5 /
+// 116.6 / 119.8 ms, the step under 12 GiB (fit) 210.0 / 198.0 / 187.5 / 192.2 / 195.9 ms: smaller workspaces leave less to offload.
+constexpr size_t kWinoChunkDefaultBytes = (size_t)384 << 20;
+static size_t g_wino_chunk_bytes = kWinoChunkDefaultBytes;
 
-void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? bytes : (size_t)512 << 20; }
+void conv_set_winograd_chunk_bytes(size_t bytes) { g_wino_chunk_bytes = bytes ? bytes : kWinoChunkDefaultBytes; }
 
 // m: the output tile's side, 2 (F(2x2, 3x3), winograd.h) or 4 (F(4x4, 3x3), winograd4.h); (m + 2)^2 grouped products.
 static inline int wino_tiles(int H, int W, int m) { return cdiv(H, m) * cdiv(W, m); }

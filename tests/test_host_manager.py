@@ -531,44 +531,45 @@ def test_every_plan_of_a_net_runs_the_same_kernels():
 def test_workspace_sizes_by_hand():
     """The workspace rules of the kernels evaluated by hand for VGG-16 (256) layers.  Winograd F(2x2, 3x3): transformed filter
     16*C*K floats, then 16*(C + K) floats per 2x2 output tile for a chunk of images: as many as keep the whole workspace
-    within 512 MiB, evened out over the chunks that takes; backward-filter: the 16 products once plus once per reduction
+    within 384 MiB, evened out over the chunks that takes; backward-filter: the 16 products once plus once per reduction
     split, then the same chunk.  F(4x4, 3x3): the same with 36 products per 4x4 output tile.  Packed: one copy of W (rounded
     up to 256 bytes)."""
     MiB = 1 << 20
+    CHUNK = 384 * MiB
     q = binding.op_conv_workspace
     # c4_2: 512 -> 512 at 28 x 28: 196 tiles per image, 16 * 1024 * 196 * 4 = 12 845 056 bytes per image; beside the 16 MiB of
-    # the transformed filter 40 images fit: 7 chunks for 256 images, 37 images each (the last one 34)
+    # the transformed filter 30 images fit: 9 chunks for 256 images, 29 images each (the last one 24)
     x, w = (256, 512, 28, 28), (512, 512, 3, 3)
     U = 16 * 512 * 512 * 4
-    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == U + 37 * 12845056
-    assert U + 40 * 12845056 <= 512 * MiB < U + 41 * 12845056 and 6 * 40 < 256 <= 7 * 37
+    assert q("fwd", "winograd", x, w, 1, 1) == q("bwd_data", "winograd", x, w, 1, 1) == U + 29 * 12845056
+    assert U + 30 * 12845056 <= CHUNK < U + 31 * 12845056 and 8 * 30 < 256 <= 9 * 29
     assert q("fwd", "packed", x, w, 1, 1) == 512 * 512 * 9 * 4
     assert q("fwd", "gather", x, w, 1, 1) == q("bwd_filter", "gather", x, w, 1, 1) == 0
     # backward-filter of c4_2: 4 x 4 tiles of 128 x 128 per product, 16 products: 256 workgroups -> 4 splits; beside the
-    # products and their partial sums (5 U) 35 images fit: 8 chunks of 32
-    assert q("bwd_filter", "winograd", x, w, 1, 1) == U * (1 + 4) + 32 * 12845056
-    assert 5 * U + 35 * 12845056 <= 512 * MiB < 5 * U + 36 * 12845056
-    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 161 images fit: two chunks of 128; a batch smaller than the chunk: all of it
-    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == U + 128 * 3211264
+    # products and their partial sums (5 U) 24 images fit: 11 chunks of 24
+    assert q("bwd_filter", "winograd", x, w, 1, 1) == U * (1 + 4) + 24 * 12845056
+    assert 5 * U + 24 * 12845056 <= CHUNK < 5 * U + 25 * 12845056
+    # c5: 14 x 14, 49 tiles: 3 211 264 bytes per image, 120 images fit: three chunks of 86; a batch smaller than the chunk: all of it
+    assert q("fwd", "winograd", (256, 512, 14, 14), w, 1, 1) == U + 86 * 3211264
     assert q("fwd", "winograd", (8, 512, 14, 14), w, 1, 1) == U + 8 * 3211264
     # 13 x 13 (odd sides): 7 x 7 tiles as well
     assert q("fwd", "winograd", (8, 384, 13, 13), (256, 384, 3, 3), 1, 1) == 16 * 384 * 256 * 4 + 8 * 16 * 640 * 49 * 4
     # c3_2 backward-filter: 256 -> 256 at 56 x 56: 784 tiles, 25 690 112 bytes per image; 2 x 2 tiles x 16 = 64 workgroups -> 16
-    # splits, 17 x 4 MiB; 18 images fit beside them: 15 chunks of 18
-    assert q("bwd_filter", "winograd", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 18 * 25690112
-    # F(4x4, 3x3) on c4_2: 49 tiles per image, 36 * 1024 * 49 * 4 = 7 225 344 bytes per image, 69 fit beside the 36 MiB filter:
-    # 4 chunks of 64; backward-filter: 4 x 4 tiles x 36 products = 576 workgroups: up to 3 splits (2048 workgroups), 53 images fit
-    # beside 4 x 36 MiB: 5 chunks of 52
+    # splits, 17 x 4 MiB; 12 images fit beside them: 22 chunks of 12
+    assert q("bwd_filter", "winograd", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 16 * 256 * 256 * 4 * (1 + 16) + 12 * 25690112
+    # F(4x4, 3x3) on c4_2: 49 tiles per image, 36 * 1024 * 49 * 4 = 7 225 344 bytes per image, 50 fit beside the 36 MiB filter:
+    # 6 chunks of 43; backward-filter: 4 x 4 tiles x 36 products = 576 workgroups: up to 3 splits (2048 workgroups), 34 images fit
+    # beside 4 x 36 MiB: 8 chunks of 32
     U4 = 36 * 512 * 512 * 4
-    assert q("fwd", "winograd4", x, w, 1, 1) == q("bwd_data", "winograd4", x, w, 1, 1) == U4 + 64 * 7225344
-    assert U4 + 69 * 7225344 <= 512 * MiB < U4 + 70 * 7225344 and 3 * 69 < 256 <= 4 * 64
-    assert q("bwd_filter", "winograd4", x, w, 1, 1) == U4 * (1 + 3) + 52 * 7225344
-    assert q("fwd", "winograd4_small", x, w, 1, 1) == U4 + 32 * 7225344
+    assert q("fwd", "winograd4", x, w, 1, 1) == q("bwd_data", "winograd4", x, w, 1, 1) == U4 + 43 * 7225344
+    assert U4 + 50 * 7225344 <= CHUNK < U4 + 51 * 7225344 and 5 * 50 < 256 <= 6 * 43
+    assert q("bwd_filter", "winograd4", x, w, 1, 1) == U4 * (1 + 3) + 32 * 7225344
+    assert q("fwd", "winograd4_small", x, w, 1, 1) == U4 + 22 * 7225344
     # c5: 14 x 14 is covered by 4 x 4 tiles of 4 x 4: 2 359 296 bytes per image, two chunks of 128
     assert q("fwd", "winograd4", (256, 512, 14, 14), w, 1, 1) == U4 + 128 * 36 * 1024 * 16 * 4
-    # c3_2 backward-filter: 196 tiles, 14 450 688 bytes per image; 2 x 2 x 36 = 144 workgroups -> up to 14 splits, 15 x 9 MiB; 27
-    # images fit: 10 chunks of 26, whose 26 * 196 tile positions make 10 splits of at least 512
-    assert q("bwd_filter", "winograd4", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 36 * 256 * 256 * 4 * (1 + 10) + 26 * 14450688
+    # c3_2 backward-filter: 196 tiles, 14 450 688 bytes per image; 2 x 2 x 36 = 144 workgroups -> up to 14 splits, 15 x 9 MiB; 18
+    # images fit: 15 chunks of 18, whose 18 * 196 tile positions make 7 splits of at least 512
+    assert q("bwd_filter", "winograd4", (256, 256, 56, 56), (256, 256, 3, 3), 1, 1) == 36 * 256 * 256 * 4 * (1 + 7) + 18 * 14450688
     # F(4x4) moves 2.25 instead of 4 times the tensor through the workspace and pays from 128 channels on (c2_2, c3_1 forward)
     assert q("fwd", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None and q("fwd", "winograd", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is None
     assert q("bwd_filter", "winograd4", (256, 128, 112, 112), (128, 128, 3, 3), 1, 1) is not None
@@ -577,7 +578,7 @@ def test_workspace_sizes_by_hand():
     for kernel in ("winograd", "winograd4"):
         for xs, ws_ in ((x, w), ((256, 256, 56, 56), (256, 256, 3, 3)), ((128, 1024, 12, 12), (1024, 1024, 3, 3)), ((256, 512, 14, 14), w)):
             for pass_ in ("fwd", "bwd_data", "bwd_filter"):
-                assert q(pass_, kernel, xs, ws_, 1, 1) <= 512 * MiB, (kernel, xs, pass_)
+                assert q(pass_, kernel, xs, ws_, 1, 1) <= CHUNK, (kernel, xs, pass_)
     # not wide enough, not 3x3, strided, unpadded, channels not a multiple of 16: no Winograd
     for xs, ws_, st, pd in (((256, 128, 28, 28), (512, 128, 3, 3), 1, 1), ((256, 512, 28, 28), (64, 512, 3, 3), 1, 1),
                             ((256, 512, 28, 28), (512, 512, 5, 5), 1, 2), ((256, 512, 28, 28), (512, 512, 3, 3), 2, 1),
@@ -669,7 +670,7 @@ def test_winograd_can_be_switched_off_and_its_workspace_must_fit():
     n.set_policy("none")
     assert n.stats()["n_winograd_convs"] == 0 and n.stats()["peak_bytes"] < none_peak
     n.close()
-    tight = none_peak - (256 << 20)
+    tight = none_peak - (192 << 20)
     n = binding.Net(net, tight)
     assert n.try_policy("none") == binding.ERR_OOM_DEVICE
     n.set_conv_algo("greedy")
