@@ -153,7 +153,7 @@ vdnn_status_t vdnn_create(const vdnn_net_desc_t* desc /*host*/, size_t gpu_mem_b
 vdnn_status_t vdnn_set_policy(vdnn_net_t*, vdnn_policy_t);
 /* Which Winograd kernels the CONV layers of this net may run: 1 (default) all of them; 2 only the F(2x2,3x3) forms, whose
  * rounding error is a tenth of F(4x4,3x3)'s (for callers that want results within a few 1e-6 of the exact ones; VGG-16
- * at batch 256 then takes 146 instead of 112 ms per step); 0 none (direct kernels only: 186 ms).  Any other value:
+ * at batch 256 then takes 146 instead of 114 ms per step); 0 none (direct kernels only: 186 ms).  Any other value:
  * VDNN_ERR_INVALID_ARG.  Takes effect at the next vdnn_set_policy / vdnn_set_offload_set. */
 vdnn_status_t vdnn_set_winograd(vdnn_net_t*, int32_t enabled);
 /* The list described above, as workspace bytes: entry 0 is what VDNN_ALGO_PERF allocates for the layer's forward
